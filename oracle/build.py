@@ -1,0 +1,19 @@
+"""Compile the CPU oracle (test infrastructure) into oracle/libgcn_oracle.so."""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+SRC = os.path.join(HERE, "gcn_oracle.cpp")
+LIB = os.path.join(HERE, "libgcn_oracle.so")
+
+
+def build(force: bool = True) -> str:
+    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
+        return LIB
+    cmd = ["g++", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra", "-o", LIB, SRC]
+    subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build())

@@ -1,0 +1,378 @@
+// CPU oracle for partition-based full-graph GCN training.
+//
+// TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what
+// the hot path computes.  It is called by the tests, by the smoke check and by
+// the benchmark's CPU-baseline leg; the product library never links, loads or
+// calls it, and it shares no code with the HIP path.
+//
+// What it follows (paper sections, not listings):
+//   * GCN layer, Eq. 2:  h'_v = sigma( W (x) sum_{u in N(v)} d_uv h_u ), with
+//     the aggregate taken first and the linear + ReLU update after it.
+//   * Backward of UPDATE, Sec. 2.3:  grad W = a^T (ReLU'(aW) * grad h'), with
+//     ReLU' = 1 for positive input and 0 otherwise (so 0 at 0).
+//   * Backward of AGGREGATE, Sec. 4.1: a source sums gradient along its
+//     out-edges; replicas in different chunks sum.
+//   * Chunks, Sec. 4.1 / 4.3: a chunk is a set of destinations with all their
+//     in-edges; N_j is its in-neighbour set.
+//   * Dedup sets and volumes, Sec. 5.1 / 5.3: reuse set N_j ^ N_{j-1}, load set
+//     N_j \ N_{j-1}, V_ori and V_+ru (one GPU, so the inter-GPU term is void).
+//   * Epoch, Alg. 1: forward over layers, loss, backward, parameter update.
+//
+// Readings where the paper is silent (normalisation degree, loss, optimiser,
+// boundary rule, canonical orders) are the ones listed in the design notes of
+// this repository; every one is restated at the function that uses it.
+//
+// Arithmetic is fp64 throughout.  Parallel loops run over independent output
+// rows only, so results do not depend on the thread count.
+//
+// Pins (see tests, "not gpu"): dense brute force on tiny graphs, finite
+// differences of the loss, all-ones features on regular graphs, ln C loss at
+// zero weights, partitioned == unpartitioned, the paper's printed transfer
+// counts and buffer example, brute-force set arithmetic.
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <iterator>
+#include <vector>
+
+extern "C" {
+
+// ---------------------------------------------------------------------------
+// Integer part
+// ---------------------------------------------------------------------------
+
+// Edge list (u -> v) to CSC by destination.  One self-loop per vertex is added
+// when add_self_loops != 0.  Duplicate edges are kept.  Inside a destination
+// the sources ascend (equal sources adjacent).  Returns E' = number of stored
+// entries; indptr has V+1 entries, col must hold E (+V) entries.
+int64_t orc_csc_build(int64_t V, int64_t E, const int32_t* src, const int32_t* dst,
+                      int add_self_loops, int64_t* indptr, int32_t* col) {
+  std::vector<std::pair<int32_t, int32_t>> e;  // (dst, src)
+  e.reserve((size_t)E + (add_self_loops ? (size_t)V : 0));
+  for (int64_t i = 0; i < E; ++i) e.emplace_back(dst[i], src[i]);
+  if (add_self_loops)
+    for (int64_t v = 0; v < V; ++v) e.emplace_back((int32_t)v, (int32_t)v);
+  std::sort(e.begin(), e.end());
+  for (int64_t v = 0; v <= V; ++v) indptr[v] = 0;
+  for (auto& p : e) indptr[p.first + 1]++;
+  for (int64_t v = 0; v < V; ++v) indptr[v + 1] += indptr[v];
+  for (size_t i = 0; i < e.size(); ++i) col[i] = e[i].second;
+  return (int64_t)e.size();
+}
+
+// Chunk boundaries over contiguous destination IDs, b[0]=0, b[n]=V.
+// mode 0 ("computation-balanced", the range rule of Sec. 4.1 read as balancing
+// stored in-edges): b[j] = min{ v : indptr[v] >= ceil(j*E'/n) }.
+// mode 1 (equal vertices): b[j] = floor(j*V/n).  Empty chunks are legal.
+void orc_chunk_bounds(int64_t V, const int64_t* indptr, int n, int mode, int64_t* b) {
+  const int64_t Ep = indptr[V];
+  b[0] = 0;
+  b[n] = V;
+  for (int j = 1; j < n; ++j) {
+    if (mode == 1) {
+      b[j] = (int64_t)(((__int128)j * V) / n);
+    } else {
+      __int128 num = (__int128)j * Ep;
+      int64_t target = (int64_t)((num + n - 1) / n);
+      int64_t v = 0;
+      while (v < V && indptr[v] < target) ++v;
+      b[j] = v;
+    }
+  }
+}
+
+// |N_j| for the chunk of destinations [b0, b1).
+int64_t orc_chunk_nsrc(const int64_t* indptr, const int32_t* col, int64_t b0, int64_t b1) {
+  std::vector<int32_t> s(col + indptr[b0], col + indptr[b1]);
+  std::sort(s.begin(), s.end());
+  return (int64_t)(std::unique(s.begin(), s.end()) - s.begin());
+}
+
+// Dedup remap of one chunk.
+//   N         ascending unique sources of the chunk's edges           [|N_j|]
+//   col_local position of each edge's source in N, edges in CSC order [E'_j]
+//   sptr/sdst the same edges by local source: for local source i the
+//             entries sdst[sptr[i] .. sptr[i+1]) are local destinations
+//             (v - b0), ascending, equal ones adjacent                [|N_j|+1],[E'_j]
+void orc_chunk_dedup(const int64_t* indptr, const int32_t* col, int64_t b0, int64_t b1,
+                     int32_t* N, int32_t* col_local, int64_t* sptr, int32_t* sdst) {
+  const int64_t e0 = indptr[b0], e1 = indptr[b1];
+  std::vector<int32_t> s(col + e0, col + e1);
+  std::sort(s.begin(), s.end());
+  s.erase(std::unique(s.begin(), s.end()), s.end());
+  const int64_t ns = (int64_t)s.size();
+  for (int64_t i = 0; i < ns; ++i) N[i] = s[i];
+  for (int64_t e = e0; e < e1; ++e)
+    col_local[e - e0] = (int32_t)(std::lower_bound(s.begin(), s.end(), col[e]) - s.begin());
+  std::vector<std::pair<int32_t, int32_t>> t;  // (local source, local destination)
+  t.reserve((size_t)(e1 - e0));
+  for (int64_t v = b0; v < b1; ++v)
+    for (int64_t e = indptr[v]; e < indptr[v + 1]; ++e)
+      t.emplace_back(col_local[e - e0], (int32_t)(v - b0));
+  std::sort(t.begin(), t.end());
+  for (int64_t i = 0; i <= ns; ++i) sptr[i] = 0;
+  for (auto& p : t) sptr[p.first + 1]++;
+  for (int64_t i = 0; i < ns; ++i) sptr[i + 1] += sptr[i];
+  for (size_t i = 0; i < t.size(); ++i) sdst[i] = t[i].second;
+}
+
+// Reuse / load split between adjacently scheduled chunks (Sec. 5.1, step 2):
+// R = cur ^ prev, Ld = cur \ prev, both ascending.  Inputs ascending unique.
+void orc_reuse_split(const int32_t* prev, int64_t n_prev, const int32_t* cur, int64_t n_cur,
+                     int32_t* R, int32_t* Ld, int64_t* nR, int64_t* nLd) {
+  int32_t* r_end = std::set_intersection(cur, cur + n_cur, prev, prev + n_prev, R);
+  int32_t* l_end = std::set_difference(cur, cur + n_cur, prev, prev + n_prev, Ld);
+  *nR = r_end - R;
+  *nLd = l_end - Ld;
+}
+
+// Host-GPU transfer volumes in rows for one GPU (Sec. 5.3 with m = 1):
+// V_ori = sum_j |N_j|;  V_+ru = |N_0| + sum_{j>=1} |N_j \ N_{j-1}|.
+void orc_volumes(int64_t V, const int64_t* indptr, const int32_t* col, int n, const int64_t* b,
+                 int64_t* v_ori, int64_t* v_ru) {
+  (void)V;
+  std::vector<int32_t> prev, cur, tmp;
+  int64_t ori = 0, ru = 0;
+  for (int j = 0; j < n; ++j) {
+    cur.assign(col + indptr[b[j]], col + indptr[b[j + 1]]);
+    std::sort(cur.begin(), cur.end());
+    cur.erase(std::unique(cur.begin(), cur.end()), cur.end());
+    ori += (int64_t)cur.size();
+    tmp.clear();
+    std::set_difference(cur.begin(), cur.end(), prev.begin(), prev.end(), std::back_inserter(tmp));
+    ru += (int64_t)tmp.size();
+    prev.swap(cur);
+  }
+  *v_ori = ori;
+  *v_ru = ru;
+}
+
+// ---------------------------------------------------------------------------
+// Float part (fp64)
+// ---------------------------------------------------------------------------
+
+// s_v = 1/sqrt(D_v), D_v = number of stored in-edges of v (self-loop and
+// multiplicity included).  One D on both sides of the symmetric normalisation.
+void orc_norm(int64_t V, const int64_t* indptr, double* s) {
+  for (int64_t v = 0; v < V; ++v) {
+    int64_t D = indptr[v + 1] - indptr[v];
+    s[v] = D > 0 ? 1.0 / std::sqrt((double)D) : 0.0;
+  }
+}
+
+// AGGREGATE of Eq. 2:  a[v] = s_v * sum_{e in in(v)} s_{u_e} h[u_e],  rows v in [v0, v1).
+void orc_aggregate(const int64_t* indptr, const int32_t* col, const double* s, int64_t v0,
+                   int64_t v1, int64_t d, const double* h, double* a) {
+#pragma omp parallel for schedule(dynamic, 64)
+  for (int64_t v = v0; v < v1; ++v) {
+    double* av = a + v * d;
+    for (int64_t k = 0; k < d; ++k) av[k] = 0.0;
+    for (int64_t e = indptr[v]; e < indptr[v + 1]; ++e) {
+      const int64_t u = col[e];
+      const double w = s[u];
+      const double* hu = h + u * d;
+      for (int64_t k = 0; k < d; ++k) av[k] += w * hu[k];
+    }
+    for (int64_t k = 0; k < d; ++k) av[k] *= s[v];
+  }
+}
+
+// Backward of AGGREGATE:  g[u] = s_u * sum_{(u->v)} s_v x[v]  over all stored edges.
+// Written as a loop over destinations scattering into sources (serial, plain).
+void orc_aggregate_T(int64_t V, const int64_t* indptr, const int32_t* col, const double* s,
+                     int64_t d, const double* x, double* g) {
+  for (int64_t i = 0; i < V * d; ++i) g[i] = 0.0;
+  for (int64_t v = 0; v < V; ++v)
+    for (int64_t e = indptr[v]; e < indptr[v + 1]; ++e) {
+      const int64_t u = col[e];
+      const double w = s[v];
+      for (int64_t k = 0; k < d; ++k) g[u * d + k] += w * x[v * d + k];
+    }
+  for (int64_t u = 0; u < V; ++u)
+    for (int64_t k = 0; k < d; ++k) g[u * d + k] *= s[u];
+}
+
+// C[M x N] = A[M x K] * B[K x N]
+void orc_matmul(int64_t M, int64_t K, int64_t N, const double* A, const double* B, double* C) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < M; ++i) {
+    for (int64_t j = 0; j < N; ++j) C[i * N + j] = 0.0;
+    for (int64_t k = 0; k < K; ++k) {
+      const double aik = A[i * K + k];
+      for (int64_t j = 0; j < N; ++j) C[i * N + j] += aik * B[k * N + j];
+    }
+  }
+}
+
+// C[K x N] = A[M x K]^T * B[M x N]   (parallel over the K output rows)
+void orc_matmul_tn(int64_t M, int64_t K, int64_t N, const double* A, const double* B, double* C) {
+#pragma omp parallel for schedule(static)
+  for (int64_t k = 0; k < K; ++k) {
+    for (int64_t j = 0; j < N; ++j) C[k * N + j] = 0.0;
+    for (int64_t i = 0; i < M; ++i) {
+      const double aik = A[i * K + k];
+      for (int64_t j = 0; j < N; ++j) C[k * N + j] += aik * B[i * N + j];
+    }
+  }
+}
+
+// C[M x K] = A[M x N] * B[K x N]^T
+void orc_matmul_nt(int64_t M, int64_t N, int64_t K, const double* A, const double* B, double* C) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < M; ++i)
+    for (int64_t k = 0; k < K; ++k) {
+      double acc = 0.0;
+      for (int64_t j = 0; j < N; ++j) acc += A[i * N + j] * B[k * N + j];
+      C[i * K + k] = acc;
+    }
+}
+
+// Softmax cross-entropy, mean over labelled vertices (label >= 0).
+// grad[v] = (softmax(logits_v) - onehot(y_v)) / |T| for labelled v, else 0.
+double orc_softmax_ce(int64_t V, int64_t C, const double* logits, const int32_t* labels,
+                      double* grad) {
+  int64_t T = 0;
+  for (int64_t v = 0; v < V; ++v) T += labels[v] >= 0;
+  double loss = 0.0;
+  for (int64_t v = 0; v < V; ++v) {
+    double* gv = grad ? grad + v * C : nullptr;
+    if (labels[v] < 0) {
+      if (gv) for (int64_t c = 0; c < C; ++c) gv[c] = 0.0;
+      continue;
+    }
+    const double* x = logits + v * C;
+    double m = x[0];
+    for (int64_t c = 1; c < C; ++c) m = std::max(m, x[c]);
+    double z = 0.0;
+    for (int64_t c = 0; c < C; ++c) z += std::exp(x[c] - m);
+    const double lse = m + std::log(z);
+    loss += lse - x[labels[v]];
+    if (gv)
+      for (int64_t c = 0; c < C; ++c)
+        gv[c] = (std::exp(x[c] - lse) - (c == labels[v] ? 1.0 : 0.0)) / (double)T;
+  }
+  return T > 0 ? loss / (double)T : 0.0;
+}
+
+// One training epoch of an L-layer GCN (Alg. 1 without the partitioning, which
+// does not change the result): forward, loss, backward, SGD step.
+//   dims[L+1]; X fp32 [V x dims[0]]; W fp32, the L matrices [dims[l] x dims[l+1]]
+//   back to back; labels int32 (-1 = unlabelled).
+// Outputs (each array may be null to skip it), per layer l = 0..L-1:
+//   a[l]  [V x dims[l]]    aggregate output a^l
+//   z[l]  [V x dims[l+1]]  pre-activation a^l W^l
+//   h[l]  [V x dims[l+1]]  h^{l+1} = ReLU(z^l), identity on the last layer
+//   gh[l] [V x dims[l+1]]  gradient of the loss w.r.t. h^{l+1}
+//   ga[l] [V x dims[l]]    gradient w.r.t. a^l
+//   gW    concatenated like W;  W_new = W - lr * gW;  *loss.
+// ReLU'(z) = [z > relu_thresh]; the method's value is relu_thresh = 0.  The
+// forward ReLU is always max(z, 0).
+int orc_gcn_epoch(int64_t V, const int64_t* indptr, const int32_t* col, int L,
+                  const int32_t* dims, const float* X, const float* W, const int32_t* labels,
+                  double lr, double relu_thresh, double** a_out, double** z_out, double** h_out,
+                  double** gh_out, double** ga_out, double* gW_out, double* W_new,
+                  double* loss_out) {
+  std::vector<double> s(V);
+  orc_norm(V, indptr, s.data());
+  std::vector<std::vector<double>> h(L + 1), a(L), z(L), Wd(L);
+  std::vector<int64_t> woff(L + 1, 0);
+  for (int l = 0; l < L; ++l) woff[l + 1] = woff[l] + (int64_t)dims[l] * dims[l + 1];
+  h[0].assign(X, X + V * (int64_t)dims[0]);
+  for (int l = 0; l < L; ++l) Wd[l].assign(W + woff[l], W + woff[l + 1]);
+
+  for (int l = 0; l < L; ++l) {
+    const int64_t di = dims[l], dn = dims[l + 1];
+    a[l].resize(V * di);
+    z[l].resize(V * dn);
+    h[l + 1].resize(V * dn);
+    orc_aggregate(indptr, col, s.data(), 0, V, di, h[l].data(), a[l].data());
+    orc_matmul(V, di, dn, a[l].data(), Wd[l].data(), z[l].data());
+    for (int64_t i = 0; i < V * dn; ++i)
+      h[l + 1][i] = (l < L - 1) ? std::max(z[l][i], 0.0) : z[l][i];
+  }
+  std::vector<double> gh(V * (int64_t)dims[L]);
+  const double loss = orc_softmax_ce(V, dims[L], h[L].data(), labels, gh.data());
+  if (loss_out) *loss_out = loss;
+
+  for (int l = L - 1; l >= 0; --l) {
+    const int64_t di = dims[l], dn = dims[l + 1];
+    if (gh_out && gh_out[l]) std::memcpy(gh_out[l], gh.data(), sizeof(double) * V * dn);
+    std::vector<double> gz(V * dn);
+    for (int64_t i = 0; i < V * dn; ++i)
+      gz[i] = (l < L - 1) ? (z[l][i] > relu_thresh ? gh[i] : 0.0) : gh[i];
+    std::vector<double> gW(di * dn);
+    orc_matmul_tn(V, di, dn, a[l].data(), gz.data(), gW.data());
+    std::vector<double> ga(V * di);
+    orc_matmul_nt(V, dn, di, gz.data(), Wd[l].data(), ga.data());
+    if (ga_out && ga_out[l]) std::memcpy(ga_out[l], ga.data(), sizeof(double) * V * di);
+    if (gW_out) std::memcpy(gW_out + woff[l], gW.data(), sizeof(double) * di * dn);
+    if (W_new)
+      for (int64_t i = 0; i < di * dn; ++i) W_new[woff[l] + i] = Wd[l][i] - lr * gW[i];
+    if (l > 0) {
+      gh.assign(V * di, 0.0);
+      orc_aggregate_T(V, indptr, col, s.data(), di, ga.data(), gh.data());
+    }
+  }
+  for (int l = 0; l < L; ++l) {
+    if (a_out && a_out[l]) std::memcpy(a_out[l], a[l].data(), sizeof(double) * a[l].size());
+    if (z_out && z_out[l]) std::memcpy(z_out[l], z[l].data(), sizeof(double) * z[l].size());
+    if (h_out && h_out[l]) std::memcpy(h_out[l], h[l + 1].data(), sizeof(double) * h[l + 1].size());
+  }
+  return 0;
+}
+
+// The same layer step done chunk by chunk through the dedup structures
+// (Sec. 4.1, 5.1): forward reads the rows of N_j by local index; backward
+// sums each chunk's source gradients into the full gradient buffer.  Used to
+// pin "partitioned == unpartitioned" and to tie the integer part to the float
+// part.  b[n+1] are chunk boundaries.
+void orc_layer_fwd_chunked(int64_t V, const int64_t* indptr, const int32_t* col, int n,
+                           const int64_t* b, int64_t d, const double* h, double* a) {
+  std::vector<double> s(V);
+  orc_norm(V, indptr, s.data());
+  for (int j = 0; j < n; ++j) {
+    const int64_t b0 = b[j], b1 = b[j + 1], e0 = indptr[b0], ne = indptr[b1] - e0;
+    const int64_t ns = orc_chunk_nsrc(indptr, col, b0, b1);
+    std::vector<int32_t> N(ns), cl(ne), sdst(ne);
+    std::vector<int64_t> sptr(ns + 1);
+    orc_chunk_dedup(indptr, col, b0, b1, N.data(), cl.data(), sptr.data(), sdst.data());
+    std::vector<double> buf(ns * d);  // the chunk's neighbour rows, one per unique source
+    for (int64_t i = 0; i < ns; ++i)
+      for (int64_t k = 0; k < d; ++k) buf[i * d + k] = s[N[i]] * h[(int64_t)N[i] * d + k];
+    for (int64_t v = b0; v < b1; ++v) {
+      for (int64_t k = 0; k < d; ++k) a[v * d + k] = 0.0;
+      for (int64_t e = indptr[v]; e < indptr[v + 1]; ++e)
+        for (int64_t k = 0; k < d; ++k) a[v * d + k] += buf[(int64_t)cl[e - e0] * d + k];
+      for (int64_t k = 0; k < d; ++k) a[v * d + k] *= s[v];
+    }
+  }
+}
+
+void orc_layer_bwd_chunked(int64_t V, const int64_t* indptr, const int32_t* col, int n,
+                           const int64_t* b, int64_t d, const double* ga, double* gh) {
+  std::vector<double> s(V);
+  orc_norm(V, indptr, s.data());
+  for (int64_t i = 0; i < V * d; ++i) gh[i] = 0.0;
+  for (int j = 0; j < n; ++j) {
+    const int64_t b0 = b[j], b1 = b[j + 1], ne = indptr[b1] - indptr[b0];
+    const int64_t ns = orc_chunk_nsrc(indptr, col, b0, b1);
+    std::vector<int32_t> N(ns), cl(ne), sdst(ne);
+    std::vector<int64_t> sptr(ns + 1);
+    orc_chunk_dedup(indptr, col, b0, b1, N.data(), cl.data(), sptr.data(), sdst.data());
+    for (int64_t i = 0; i < ns; ++i) {
+      const int64_t u = N[i];
+      for (int64_t k = 0; k < d; ++k) {
+        double acc = 0.0;
+        for (int64_t t = sptr[i]; t < sptr[i + 1]; ++t) {
+          const int64_t v = b0 + sdst[t];
+          acc += s[v] * ga[v * d + k];
+        }
+        gh[u * d + k] += s[u] * acc;
+      }
+    }
+  }
+}
+
+}  // extern "C"

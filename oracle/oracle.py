@@ -1,0 +1,216 @@
+"""numpy front end of the CPU oracle (oracle/gcn_oracle.cpp).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's CPU-baseline leg.  Nothing in the product package imports it, and
+it imports nothing from the product package.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        _lib = C.CDLL(path)
+        _lib.orc_csc_build.restype = C.c_int64
+        _lib.orc_chunk_nsrc.restype = C.c_int64
+        _lib.orc_softmax_ce.restype = C.c_double
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _i32(x) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(x), dtype=np.int32)
+
+
+def _i64(x) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(x), dtype=np.int64)
+
+
+def _f64(x) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(x), dtype=np.float64)
+
+
+def csc_build(V: int, src, dst, add_self_loops: bool = True) -> Tuple[np.ndarray, np.ndarray]:
+    src, dst = _i32(src), _i32(dst)
+    E = src.shape[0]
+    indptr = np.zeros(V + 1, dtype=np.int64)
+    col = np.zeros(E + (V if add_self_loops else 0), dtype=np.int32)
+    Ep = lib().orc_csc_build(C.c_int64(V), C.c_int64(E), _p(src), _p(dst), C.c_int(int(add_self_loops)),
+                             _p(indptr), _p(col))
+    assert Ep == col.shape[0]
+    return indptr, col
+
+
+def chunk_bounds(indptr: np.ndarray, n: int, mode: int = 0) -> np.ndarray:
+    V = indptr.shape[0] - 1
+    b = np.zeros(n + 1, dtype=np.int64)
+    lib().orc_chunk_bounds(C.c_int64(V), _p(indptr), C.c_int(n), C.c_int(mode), _p(b))
+    return b
+
+
+def chunk_dedup(indptr: np.ndarray, col: np.ndarray, b0: int, b1: int) -> Dict[str, np.ndarray]:
+    ns = lib().orc_chunk_nsrc(_p(indptr), _p(col), C.c_int64(b0), C.c_int64(b1))
+    ne = int(indptr[b1] - indptr[b0])
+    N = np.zeros(ns, dtype=np.int32)
+    cl = np.zeros(ne, dtype=np.int32)
+    sptr = np.zeros(ns + 1, dtype=np.int64)
+    sdst = np.zeros(ne, dtype=np.int32)
+    lib().orc_chunk_dedup(_p(indptr), _p(col), C.c_int64(b0), C.c_int64(b1), _p(N), _p(cl), _p(sptr), _p(sdst))
+    return {"N": N, "col_local": cl, "sptr": sptr, "sdst": sdst}
+
+
+def reuse_split(prev, cur) -> Tuple[np.ndarray, np.ndarray]:
+    prev, cur = _i32(prev), _i32(cur)
+    R = np.zeros(cur.shape[0], dtype=np.int32)
+    Ld = np.zeros(cur.shape[0], dtype=np.int32)
+    nR, nLd = C.c_int64(0), C.c_int64(0)
+    lib().orc_reuse_split(_p(prev), C.c_int64(prev.shape[0]), _p(cur), C.c_int64(cur.shape[0]), _p(R), _p(Ld),
+                          C.byref(nR), C.byref(nLd))
+    return R[: nR.value].copy(), Ld[: nLd.value].copy()
+
+
+def volumes(indptr: np.ndarray, col: np.ndarray, b: np.ndarray) -> Tuple[int, int]:
+    V = indptr.shape[0] - 1
+    b = _i64(b)
+    vo, vr = C.c_int64(0), C.c_int64(0)
+    lib().orc_volumes(C.c_int64(V), _p(indptr), _p(col), C.c_int(b.shape[0] - 1), _p(b), C.byref(vo), C.byref(vr))
+    return vo.value, vr.value
+
+
+def norm(indptr: np.ndarray) -> np.ndarray:
+    V = indptr.shape[0] - 1
+    s = np.zeros(V, dtype=np.float64)
+    lib().orc_norm(C.c_int64(V), _p(indptr), _p(s))
+    return s
+
+
+def aggregate(indptr, col, h, rows: Optional[Tuple[int, int]] = None) -> np.ndarray:
+    """a = diag(s) A~ diag(s) h; with rows=(v0, v1) only those rows are filled."""
+    h = _f64(h)
+    V, d = h.shape
+    s = norm(indptr)
+    a = np.zeros((V, d), dtype=np.float64)
+    v0, v1 = rows if rows is not None else (0, V)
+    lib().orc_aggregate(_p(indptr), _p(col), _p(s), C.c_int64(v0), C.c_int64(v1), C.c_int64(d), _p(h), _p(a))
+    return a
+
+
+def aggregate_T(indptr, col, x) -> np.ndarray:
+    x = _f64(x)
+    V, d = x.shape
+    s = norm(indptr)
+    g = np.zeros((V, d), dtype=np.float64)
+    lib().orc_aggregate_T(C.c_int64(V), _p(indptr), _p(col), _p(s), C.c_int64(d), _p(x), _p(g))
+    return g
+
+
+def matmul(A, B) -> np.ndarray:
+    A, B = _f64(A), _f64(B)
+    M, K = A.shape
+    K2, N = B.shape
+    assert K == K2
+    Cm = np.zeros((M, N), dtype=np.float64)
+    lib().orc_matmul(C.c_int64(M), C.c_int64(K), C.c_int64(N), _p(A), _p(B), _p(Cm))
+    return Cm
+
+
+def matmul_tn(A, B) -> np.ndarray:
+    A, B = _f64(A), _f64(B)
+    M, K = A.shape
+    M2, N = B.shape
+    assert M == M2
+    Cm = np.zeros((K, N), dtype=np.float64)
+    lib().orc_matmul_tn(C.c_int64(M), C.c_int64(K), C.c_int64(N), _p(A), _p(B), _p(Cm))
+    return Cm
+
+
+def matmul_nt(A, B) -> np.ndarray:
+    A, B = _f64(A), _f64(B)
+    M, N = A.shape
+    K, N2 = B.shape
+    assert N == N2
+    Cm = np.zeros((M, K), dtype=np.float64)
+    lib().orc_matmul_nt(C.c_int64(M), C.c_int64(N), C.c_int64(K), _p(A), _p(B), _p(Cm))
+    return Cm
+
+
+def softmax_ce(logits, labels) -> Tuple[float, np.ndarray]:
+    logits = _f64(logits)
+    labels = _i32(labels)
+    V, Cc = logits.shape
+    g = np.zeros((V, Cc), dtype=np.float64)
+    loss = lib().orc_softmax_ce(C.c_int64(V), C.c_int64(Cc), _p(logits), _p(labels), _p(g))
+    return float(loss), g
+
+
+def gcn_epoch(indptr, col, dims: Sequence[int], X, Ws: Sequence[np.ndarray], labels, lr: float = 0.01,
+              relu_thresh: float = 0.0, want: Sequence[str] = ("a", "z", "h", "gh", "ga")) -> Dict[str, object]:
+    """One epoch on the whole graph.  Returns loss, gW (list), W_new (list) and the
+    per-layer arrays named in `want` (lists indexed by layer l)."""
+    L = len(dims) - 1
+    V = indptr.shape[0] - 1
+    X = np.ascontiguousarray(np.asarray(X), dtype=np.float32)
+    assert X.shape == (V, dims[0])
+    Wcat = np.concatenate([np.ascontiguousarray(np.asarray(w), dtype=np.float32).reshape(-1) for w in Ws])
+    labels = _i32(labels)
+    dims_a = _i32(dims)
+    out: Dict[str, object] = {}
+    ptr_arrays = {}
+    shapes = {"a": lambda l: dims[l], "z": lambda l: dims[l + 1], "h": lambda l: dims[l + 1],
+              "gh": lambda l: dims[l + 1], "ga": lambda l: dims[l]}
+    for key in ("a", "z", "h", "gh", "ga"):
+        arrs = [np.zeros((V, shapes[key](l)), dtype=np.float64) if key in want else None for l in range(L)]
+        out[key] = arrs
+        PA = (C.c_void_p * L)(*[None if a is None else a.ctypes.data for a in arrs])
+        ptr_arrays[key] = PA
+    gW = np.zeros(Wcat.shape[0], dtype=np.float64)
+    Wn = np.zeros(Wcat.shape[0], dtype=np.float64)
+    loss = C.c_double(0.0)
+    rc = lib().orc_gcn_epoch(C.c_int64(V), _p(indptr), _p(col), C.c_int(L), _p(dims_a), _p(X), _p(Wcat),
+                             _p(labels), C.c_double(lr), C.c_double(relu_thresh), ptr_arrays["a"],
+                             ptr_arrays["z"], ptr_arrays["h"], ptr_arrays["gh"], ptr_arrays["ga"], _p(gW),
+                             _p(Wn), C.byref(loss))
+    assert rc == 0
+    out["loss"] = loss.value
+    off = 0
+    out["gW"], out["W_new"] = [], []
+    for l in range(L):
+        n = dims[l] * dims[l + 1]
+        out["gW"].append(gW[off:off + n].reshape(dims[l], dims[l + 1]).copy())
+        out["W_new"].append(Wn[off:off + n].reshape(dims[l], dims[l + 1]).copy())
+        off += n
+    return out
+
+
+def layer_fwd_chunked(indptr, col, b, h) -> np.ndarray:
+    h = _f64(h)
+    V, d = h.shape
+    b = _i64(b)
+    a = np.zeros((V, d), dtype=np.float64)
+    lib().orc_layer_fwd_chunked(C.c_int64(V), _p(indptr), _p(col), C.c_int(b.shape[0] - 1), _p(b), C.c_int64(d),
+                                _p(h), _p(a))
+    return a
+
+
+def layer_bwd_chunked(indptr, col, b, ga) -> np.ndarray:
+    ga = _f64(ga)
+    V, d = ga.shape
+    b = _i64(b)
+    gh = np.zeros((V, d), dtype=np.float64)
+    lib().orc_layer_bwd_chunked(C.c_int64(V), _p(indptr), _p(col), C.c_int(b.shape[0] - 1), _p(b), C.c_int64(d),
+                                _p(ga), _p(gh))
+    return gh
