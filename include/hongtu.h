@@ -1,0 +1,283 @@
+/*
+ * hongtu.h -- C ABI of the MI355X-native hot path of partition-based
+ * full-graph GCN training (one GPU).
+ *
+ * The calls follow the paper's statement of the problem (Alg. 1: graph,
+ * features and parameterised layers in, updated layers out):
+ *
+ *   ht_partition   Sec. 4.1 (range chunks of destinations with all their
+ *                  in-edges), Sec. 5.1 step 2 (reuse / load split between
+ *                  adjacently scheduled chunks), Sec. 6 (in-place buffer
+ *                  positions, topology rewritten to index the buffer).
+ *   ht_layer_fwd   Alg. 2 lines 1-4 (reuse + sparse load of neighbour rows),
+ *                  Alg. 1 lines 8-9 (forward of one layer, output to its home),
+ *                  Eq. 2 (aggregate, then linear + ReLU).
+ *   ht_layer_bwd   Alg. 1 lines 14-18 (checkpoint reload, re-forward of the
+ *                  update stage, backward), Alg. 3 lines 5-8 (neighbour
+ *                  gradients back to the gradient buffer), Sec. 2.3 (backward
+ *                  of the update), Sec. 4.1 (backward of the aggregate).
+ *   ht_epoch       Alg. 1 end to end with the recomputation-caching hybrid of
+ *                  Sec. 4.2, a softmax cross-entropy downstream task and an SGD
+ *                  parameter update.
+ *
+ * Conventions
+ *   - Every function returns an int status: HT_OK (0) or a negative HT_E* code.
+ *     Nothing throws across this boundary.  ht_strerror() names a code;
+ *     ht_last_error() gives the detail of the last failure on a context.
+ *   - Vertex tensors are fp32, row-major, [rows x cols] with a row pitch `ld`
+ *     in floats; ld >= cols and ld % 4 == 0 (rows are read as 16-byte vectors).
+ *     Columns cols..ld-1 are padding: never read as data, may be overwritten.
+ *   - `loc` says where a tensor lives: HT_LOC_DEVICE (HBM of the context's GPU)
+ *     or HT_LOC_HOST_PINNED (page-locked host memory the GPU can address, e.g.
+ *     hipHostMalloc or torch pin_memory).  Plain pageable memory is not accepted.
+ *   - The caller owns every tensor and weight buffer it passes and keeps it
+ *     alive until ht_sync() returns.  The library owns ht_ctx, ht_graph and
+ *     its workspaces.  Inputs are never modified except where marked in/out.
+ *   - Work is enqueued on the context's stream (and side streams the library
+ *     owns); results are complete after ht_sync(), or on return when a
+ *     non-null ht_stats is passed (filling it needs a sync).
+ *   - Without the GPU or the built library there is no fallback: calls fail.
+ */
+#ifndef HONGTU_H
+#define HONGTU_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ht_ctx ht_ctx;
+typedef struct ht_graph ht_graph;
+
+enum {
+  HT_OK = 0,
+  HT_EINVAL = -1, /* bad argument (null pointer, negative size, id out of range) */
+  HT_ENOMEM = -2, /* device or pinned allocation failed, or byte budget exceeded */
+  HT_EHIP = -3,   /* a HIP runtime call failed; see ht_last_error()              */
+  HT_ESHAPE = -4, /* tensor shape / pitch / location does not fit the call       */
+  HT_ESTATE = -5  /* call not valid in the object's current state                */
+};
+
+enum { HT_LOC_DEVICE = 0, HT_LOC_HOST_PINNED = 1 };
+
+/* fp32 matrix view, see "Conventions". */
+typedef struct {
+  float *ptr;
+  int64_t rows;
+  int32_t cols;
+  int64_t ld;
+  int32_t loc;
+} ht_tensor;
+
+/* ------------------------------------------------------------------ context */
+
+/* Create a context on GPU `device`.  `hip_stream` is a hipStream_t the caller
+ * owns (e.g. torch's current stream) or NULL for a library-owned stream. */
+int ht_ctx_create(ht_ctx **out, int device, void *hip_stream);
+int ht_ctx_destroy(ht_ctx *ctx);
+/* Block until all work enqueued through ctx has finished. */
+int ht_sync(ht_ctx *ctx);
+/* Cap on bytes the library may allocate in HBM through this context
+ * (0 = no cap).  Exceeding it makes the allocating call return HT_ENOMEM. */
+int ht_ctx_set_hbm_budget(ht_ctx *ctx, int64_t bytes);
+const char *ht_strerror(int code);
+const char *ht_last_error(const ht_ctx *ctx);
+
+/* ---------------------------------------------------------------- partition */
+
+enum { HT_BALANCE_EDGES = 0, HT_BALANCE_VERTICES = 1 };
+enum { HT_PTR_DEVICE = 0, HT_PTR_HOST = 1 };
+
+typedef struct {
+  int32_t add_self_loops; /* 1: add one (v,v) entry per vertex                          */
+  int32_t balance_mode;   /* HT_BALANCE_EDGES: b_j = min{v: indptr[v] >= ceil(j E'/n)};
+                             HT_BALANCE_VERTICES: b_j = floor(j V / n)                  */
+  int32_t ptr_loc;        /* where src/dst live: HT_PTR_DEVICE or HT_PTR_HOST (any host memory) */
+  int32_t reserved;
+  int64_t cache_rows;     /* rows of the in-place neighbour buffer; 0 = max_j |N_j|     */
+} ht_part_opts;
+
+/* Edge list (src[i] -> dst[i]), 0 <= id < V < 2^31, E >= 0, duplicates kept.
+ * Builds, on the GPU: the CSC by destination with ascending sources inside a
+ * destination; n_chunks contiguous destination ranges; per chunk j the
+ * ascending unique source list N_j, every edge's position in N_j, the same
+ * edges grouped by source for the backward pass, the reuse set N_j ^ N_{j-1},
+ * the load set N_j \ N_{j-1} and a buffer position for every member of N_j
+ * such that reused vertices keep theirs; and the row volumes V_ori, V_+ru.
+ * src/dst stay the caller's and are not modified.  *out is library-owned. */
+int ht_partition(ht_ctx *ctx, int64_t V, int64_t E, const int32_t *src, const int32_t *dst,
+                 int32_t n_chunks, const ht_part_opts *opts, ht_graph **out);
+int ht_graph_destroy(ht_graph *g);
+
+typedef struct {
+  int64_t V;
+  int64_t E_stored; /* edges incl. added self-loops                    */
+  int32_t n_chunks;
+  int32_t reserved;
+  int64_t v_ori;    /* sum_j |N_j|                       (Sec. 5.3)    */
+  int64_t v_ru;     /* |N_0| + sum_{j>=1} |N_j \ N_{j-1}| (Sec. 5.3)    */
+  double alpha;     /* replication factor v_ori / V       (Sec. 2.4)   */
+  int64_t max_nsrc; /* max_j |N_j|                                      */
+  int64_t max_ndst; /* max_j |V_j|                                      */
+  int64_t max_nnz;  /* max_j E'_j                                       */
+  int64_t cache_rows;
+  int64_t hbm_bytes;    /* device bytes held by the graph object        */
+  double partition_ms;  /* wall time of ht_partition                    */
+} ht_graph_info;
+
+typedef struct {
+  int64_t dst_begin, dst_end; /* V_j = [dst_begin, dst_end)  */
+  int64_t nnz;                /* E'_j                        */
+  int64_t n_src;              /* |N_j|                       */
+  int64_t n_reuse, n_load;    /* |N_j ^ N_{j-1}|, |N_j \ N_{j-1}| */
+} ht_chunk_info;
+
+/* Caller-allocated host arrays to receive chunk j; any pointer may be NULL to
+ * skip that array.  Sizes follow ht_chunk_info. */
+typedef struct {
+  int64_t *indptr;    /* [|V_j|+1] CSC offsets rebased to 0                       */
+  int32_t *col;       /* [E'_j]    global source of each edge, CSC order           */
+  int32_t *nbr;       /* [|N_j|]   N_j ascending                                   */
+  int32_t *col_local; /* [E'_j]    position of each edge's source in N_j           */
+  int64_t *sptr;      /* [|N_j|+1] offsets of the by-source grouping               */
+  int32_t *sdst;      /* [E'_j]    local destination (v - dst_begin) of each entry */
+  int32_t *reuse;     /* [n_reuse] N_j ^ N_{j-1} ascending                         */
+  int32_t *load;      /* [n_load]  N_j \ N_{j-1} ascending                         */
+  int32_t *slot;      /* [|N_j|]   buffer position of N_j[i]                       */
+} ht_chunk_host;
+
+int ht_graph_info_get(const ht_graph *g, ht_graph_info *out);
+int ht_graph_chunk_info(const ht_graph *g, int32_t j, ht_chunk_info *out);
+int ht_graph_export_chunk(const ht_graph *g, int32_t j, ht_chunk_host *out);
+/* Global CSC and the normalisation s_v = D_v^{-1/2} (D_v = stored in-degree),
+ * copied to caller-allocated host arrays (any may be NULL). */
+int ht_graph_export_csc(const ht_graph *g, int64_t *indptr /*V+1*/, int32_t *col /*E_stored*/,
+                        float *s /*V*/, int64_t *bounds /*n_chunks+1*/);
+
+/* -------------------------------------------------------------------- layer */
+
+enum { HT_ACT_NONE = 0, HT_ACT_RELU = 1 };
+/* How neighbour rows reach the aggregation (Alg. 2 lines 1-4):
+ *   HT_GATHER_AUTO    direct when H_in is in HBM, buffer otherwise
+ *   HT_GATHER_DIRECT  read rows of H_in in place (H_in must be in HBM)
+ *   HT_GATHER_BUFFER  keep N_j's rows in the in-place neighbour buffer: rows of
+ *                     N_j ^ N_{j-1} stay, rows of N_j \ N_{j-1} are fetched from
+ *                     H_in (HBM or pinned host) into freed positions */
+enum { HT_GATHER_AUTO = 0, HT_GATHER_DIRECT = 1, HT_GATHER_BUFFER = 2 };
+/* What the backward pass starts from (Sec. 4.2):
+ *   HT_CKPT_AGG    the cached aggregate output a^l: AGGREGATE is skipped, only
+ *                  the update stage is recomputed (the hybrid)
+ *   HT_CKPT_INPUT  the layer input h^l: the aggregate is recomputed as well */
+enum { HT_CKPT_AGG = 0, HT_CKPT_INPUT = 1 };
+
+typedef struct {
+  int32_t d_in, d_out;
+  int32_t act;         /* HT_ACT_* applied after the linear transform */
+  int32_t gather_mode; /* HT_GATHER_*                                  */
+  int32_t ckpt_kind;   /* HT_CKPT_* (backward only)                    */
+  int32_t reserved;
+} ht_layer_desc;
+
+/* Timings are HIP-event times on the stream that ran the work, summed over
+ * the call; byte and row counters are exact. */
+typedef struct {
+  double t_total_ms;
+  double t_gather_ms;     /* neighbour-row gather into the buffer            */
+  double t_spmm_fwd_ms;   /* aggregation kernels, forward                    */
+  double t_spmm_bwd_ms;   /* aggregation kernels, backward                   */
+  double t_gemm_ms;       /* dense transform and its gradient GEMMs          */
+  double t_loss_ms;
+  double t_copy_ms;       /* contiguous H2D / D2H copies of chunk rows       */
+  double t_cpu_accum_ms;  /* host-side gradient accumulation                 */
+  double t_update_ms;
+  int64_t n_spmm_fwd, n_spmm_bwd, n_gemm; /* kernel launches behind the times */
+  int64_t edges;             /* stored edges aggregated (forward + backward)     */
+  int64_t rows_loaded;       /* neighbour rows fetched into the buffer           */
+  int64_t rows_reused;       /* neighbour rows reused in place                   */
+  int64_t bytes_h2d;         /* host -> HBM bytes actually moved                 */
+  int64_t bytes_d2h;         /* HBM -> host bytes actually moved                 */
+  int64_t bytes_h2d_nodedup; /* what the neighbour loads would move per chunk without reuse */
+  double spmm_fwd_alg_bytes; /* compulsory bytes of the forward aggregation launches */
+  double spmm_bwd_alg_bytes;
+  double gemm_flops;
+} ht_stats;
+
+/* Forward of one layer over all chunks in schedule order:
+ *   a[V_j] = s_v * sum_{e in in(v)} s_{u_e} H_in[u_e]      (aggregate, Eq. 2)
+ *   H_out[V_j] = act(a[V_j] W)                              (update,   Eq. 2)
+ * H_in [V x d_in], H_out [V x d_out]: device or pinned host.  W: device,
+ * row-major [d_in x d_out], dense.  A_ckpt [V x d_in] (nullable): receives the
+ * aggregate output as the recomputation checkpoint. */
+int ht_layer_fwd(ht_ctx *ctx, const ht_graph *g, const ht_layer_desc *desc, const ht_tensor *H_in,
+                 const float *W, ht_tensor *H_out, ht_tensor *A_ckpt, ht_stats *stats);
+
+/* Backward of one layer over all chunks:
+ *   z = a W (recomputed) ; dz = dH_out * [z > 0] (no mask when act = none)
+ *   dW = a^T dz (overwritten) ; da = dz W^T ; dH_in[N_j] += s_u * sum s_v da[v]
+ * ckpt: a^l (HT_CKPT_AGG) or h^l (HT_CKPT_INPUT).  H_out (nullable): when
+ * given, the ReLU derivative is taken from [H_out > 0] and z is not recomputed.
+ * dH_in (nullable: no input gradient wanted) is in/out: ACCUMULATED into, the
+ * caller zeroes it.  All vertex tensors: device or pinned host. */
+int ht_layer_bwd(ht_ctx *ctx, const ht_graph *g, const ht_layer_desc *desc, const ht_tensor *ckpt,
+                 const float *W, const ht_tensor *dH_out, const ht_tensor *H_out, ht_tensor *dH_in,
+                 float *dW, ht_stats *stats);
+
+/* -------------------------------------------------------------------- epoch */
+
+enum { HT_RES_AUTO = 0, HT_RES_HBM = 1, HT_RES_HOST = 2 };
+/* HT_INTER_AUTO picks per the byte budget; MASK keeps h^{l+1} in HBM and reads
+ * ReLU' from it; HYBRID caches a^l and recomputes z = a W in the backward pass
+ * (Sec. 4.2, Fig. 5(c)). */
+enum { HT_INTER_AUTO = 0, HT_INTER_MASK = 1, HT_INTER_HYBRID = 2 };
+
+typedef struct {
+  int32_t n_layers;
+  int32_t reserved;
+  const int32_t *dims; /* host, n_layers + 1 widths                        */
+  float *const *W;     /* host array of n_layers device pointers, in/out   */
+  float lr;
+  int32_t reserved2;
+} ht_model;
+
+typedef struct {
+  int32_t res_h;  /* residency of h^l (l >= 1) : HT_RES_*                  */
+  int32_t res_a;  /* residency of the checkpoints a^l                      */
+  int32_t res_g;  /* residency of the gradients grad h^l                   */
+  int32_t inter;  /* HT_INTER_*                                            */
+  int32_t gather_mode;
+  int32_t reserved;
+  int64_t hbm_budget_bytes; /* 0 = what the device reports free, minus a margin */
+} ht_plan_opts;
+
+/* One training epoch (Alg. 1): forward over layers and chunks, softmax
+ * cross-entropy averaged over labelled vertices (labels[v] >= 0; device int32
+ * [V]), backward, W^l -= lr * dW^l.  X = h^0 [V x dims[0]].  *loss_out is
+ * written on the host before return (the call synchronises). */
+int ht_epoch(ht_ctx *ctx, const ht_graph *g, const ht_model *model, const ht_tensor *X,
+             const int32_t *labels, const ht_plan_opts *plan, float *loss_out, ht_stats *stats);
+
+/* Views of the buffers the last ht_epoch on ctx left behind (valid until the
+ * next ht_epoch with another shape, or ht_ctx_destroy):
+ *   kind 0: h^l (l = 1..L)   1: a^l (l = 0..L-1)   2: grad h^l (l = 1..L)
+ *   kind 3: dW^l as a [dims[l] x dims[l+1]] device matrix (l = 0..L-1) */
+enum { HT_BUF_H = 0, HT_BUF_A = 1, HT_BUF_GH = 2, HT_BUF_DW = 3 };
+int ht_epoch_buffer(ht_ctx *ctx, int32_t kind, int32_t layer, ht_tensor *out);
+/* Copy the data columns of t (device or pinned host) into the dense host array
+ * dst [rows x cols]; waits for the context's work first. */
+int ht_tensor_to_host(ht_ctx *ctx, const ht_tensor *t, float *dst);
+
+/* Byte accounting of the residency planner for a model on V vertices, as
+ * counted in Table 1 of the paper (fp32): vertex data = h^l and grad h^l for
+ * l = 0..L; intermediate data = two d_l-wide tensors per hidden layer output
+ * (l = 1..L-1: pre-activation and activation) and three d_L-wide ones at the
+ * output layer (logits, class probabilities, their gradient). */
+int ht_memory_model(int64_t V, int32_t n_layers, const int32_t *dims, double *vertex_bytes,
+                    double *intermediate_bytes);
+/* Vertex rows one chunk needs resident: (1 + alpha) * V / n   (Sec. 4.3). */
+double ht_chunk_rows_model(int64_t V, int32_t n_chunks, double alpha);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HONGTU_H */

@@ -1,0 +1,210 @@
+// Context, error reporting, allocation accounting, event timers.
+#include <cstdarg>
+
+#include "ht_internal.h"
+
+int ht_set_err(ht_ctx* ctx, int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof(buf), fmt, ap);
+  va_end(ap);
+  if (ctx) ctx->err = buf;
+  return code;
+}
+
+int ht_dev_alloc(ht_ctx* ctx, void** out, size_t bytes) {
+  *out = nullptr;
+  if (bytes == 0) return HT_OK;
+  if (ctx->hbm_budget > 0 && ctx->hbm_used + (int64_t)bytes > ctx->hbm_budget)
+    return ht_set_err(ctx, HT_ENOMEM, "HBM budget exceeded: %lld in use + %zu requested > %lld",
+                      (long long)ctx->hbm_used, bytes, (long long)ctx->hbm_budget);
+  hipError_t e = hipMalloc(out, bytes);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    *out = nullptr;
+    return ht_set_err(ctx, HT_ENOMEM, "hipMalloc(%zu): %s", bytes, hipGetErrorString(e));
+  }
+  ctx->hbm_used += (int64_t)bytes;
+  return HT_OK;
+}
+
+void ht_dev_free(ht_ctx* ctx, void* p, size_t bytes) {
+  if (!p) return;
+  (void)hipFree(p);
+  if (ctx) ctx->hbm_used -= (int64_t)bytes;
+}
+
+int ht_scratch(ht_ctx* ctx, int slot, size_t bytes, void** out) {
+  if (ctx->scratch_bytes[slot] < bytes) {
+    if (ctx->scratch[slot]) {
+      HT_HIP(ctx, hipStreamSynchronize(ctx->stream));
+      ht_dev_free(ctx, ctx->scratch[slot], ctx->scratch_bytes[slot]);
+      ctx->scratch[slot] = nullptr;
+      ctx->scratch_bytes[slot] = 0;
+    }
+    size_t want = bytes + bytes / 8 + 256;
+    int rc = ht_dev_alloc(ctx, &ctx->scratch[slot], want);
+    if (rc != HT_OK) return rc;
+    ctx->scratch_bytes[slot] = want;
+  }
+  *out = ctx->scratch[slot];
+  return HT_OK;
+}
+
+int ht_host_scratch(ht_ctx* ctx, int slot, size_t bytes, void** out) {
+  if (ctx->hscratch_bytes[slot] < bytes) {
+    if (ctx->hscratch[slot]) {
+      HT_HIP(ctx, hipDeviceSynchronize());
+      (void)hipHostFree(ctx->hscratch[slot]);
+      ctx->hscratch[slot] = nullptr;
+      ctx->hscratch_bytes[slot] = 0;
+    }
+    size_t want = bytes + bytes / 8 + 256;
+    hipError_t e = hipHostMalloc(&ctx->hscratch[slot], want, hipHostMallocDefault);
+    if (e != hipSuccess) {
+      (void)hipGetLastError();
+      ctx->hscratch[slot] = nullptr;
+      return ht_set_err(ctx, HT_ENOMEM, "hipHostMalloc(%zu): %s", want, hipGetErrorString(e));
+    }
+    ctx->hscratch_bytes[slot] = want;
+  }
+  *out = ctx->hscratch[slot];
+  return HT_OK;
+}
+
+hipEvent_t ht_event(ht_ctx* ctx) {
+  if (ctx->ev_next == ctx->ev_pool.size()) {
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    ctx->ev_pool.push_back(e);
+  }
+  return ctx->ev_pool[ctx->ev_next++];
+}
+
+void Timer::begin(double* acc) {
+  if (!on) return;
+  hipEvent_t a = ht_event(ctx), b = ht_event(ctx);
+  if (!a || !b) {
+    on = false;
+    return;
+  }
+  (void)hipEventRecord(a, st);
+  ev.emplace_back(a, b);
+  dst.push_back(acc);
+}
+
+void Timer::end() {
+  if (!on || ev.empty()) return;
+  (void)hipEventRecord(ev.back().second, st);
+}
+
+int Timer::resolve() {
+  for (size_t i = 0; i < ev.size(); ++i) {
+    float ms = 0.f;
+    hipError_t e = hipEventElapsedTime(&ms, ev[i].first, ev[i].second);
+    if (e != hipSuccess) return ht_set_err(ctx, HT_EHIP, "hipEventElapsedTime: %s", hipGetErrorString(e));
+    *dst[i] += (double)ms;
+  }
+  ev.clear();
+  dst.clear();
+  return HT_OK;
+}
+
+void ht_epoch_ws_free(ht_ctx* ctx);
+
+extern "C" {
+
+int ht_ctx_create(ht_ctx** out, int device, void* hip_stream) {
+  if (!out) return HT_EINVAL;
+  *out = nullptr;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return HT_EHIP;
+  if (hipSetDevice(device) != hipSuccess) return HT_EHIP;
+  ht_ctx* c = new (std::nothrow) ht_ctx();
+  if (!c) return HT_ENOMEM;
+  c->device = device;
+  if (hip_stream) {
+    c->stream = (hipStream_t)hip_stream;
+  } else {
+    if (hipStreamCreate(&c->stream) != hipSuccess) {
+      delete c;
+      return HT_EHIP;
+    }
+    c->own_stream = true;
+  }
+  for (int i = 0; i < 2; ++i)
+    if (hipStreamCreate(&c->side[i]) != hipSuccess) {
+      delete c;
+      return HT_EHIP;
+    }
+  *out = c;
+  return HT_OK;
+}
+
+int ht_ctx_destroy(ht_ctx* ctx) {
+  if (!ctx) return HT_EINVAL;
+  (void)hipSetDevice(ctx->device);
+  (void)hipStreamSynchronize(ctx->stream);
+  for (int i = 0; i < 2; ++i)
+    if (ctx->side[i]) {
+      (void)hipStreamSynchronize(ctx->side[i]);
+      (void)hipStreamDestroy(ctx->side[i]);
+    }
+  ht_epoch_ws_free(ctx);
+  for (int i = 0; i < HT_N_SCRATCH; ++i)
+    if (ctx->scratch[i]) ht_dev_free(ctx, ctx->scratch[i], ctx->scratch_bytes[i]);
+  for (int i = 0; i < 2; ++i)
+    if (ctx->hscratch[i]) (void)hipHostFree(ctx->hscratch[i]);
+  for (hipEvent_t e : ctx->ev_pool) (void)hipEventDestroy(e);
+  if (ctx->own_stream) (void)hipStreamDestroy(ctx->stream);
+  delete ctx;
+  return HT_OK;
+}
+
+int ht_sync(ht_ctx* ctx) {
+  if (!ctx) return HT_EINVAL;
+  HT_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  for (int i = 0; i < 2; ++i) HT_HIP(ctx, hipStreamSynchronize(ctx->side[i]));
+  return HT_OK;
+}
+
+int ht_ctx_set_hbm_budget(ht_ctx* ctx, int64_t bytes) {
+  if (!ctx || bytes < 0) return HT_EINVAL;
+  ctx->hbm_budget = bytes;
+  return HT_OK;
+}
+
+const char* ht_strerror(int code) {
+  switch (code) {
+    case HT_OK: return "ok";
+    case HT_EINVAL: return "invalid argument";
+    case HT_ENOMEM: return "out of memory or over the byte budget";
+    case HT_EHIP: return "HIP runtime error";
+    case HT_ESHAPE: return "tensor shape, pitch or location does not fit";
+    case HT_ESTATE: return "call not valid in this state";
+    default: return "unknown error code";
+  }
+}
+
+const char* ht_last_error(const ht_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+int ht_memory_model(int64_t V, int32_t n_layers, const int32_t* dims, double* vertex_bytes,
+                    double* intermediate_bytes) {
+  if (V < 0 || n_layers < 1 || !dims) return HT_EINVAL;
+  double sum = 0.0;
+  for (int l = 0; l <= n_layers; ++l) sum += dims[l];
+  if (vertex_bytes) *vertex_bytes = (double)V * sum * 4.0 * 2.0;
+  double mid = 0.0;
+  for (int l = 1; l < n_layers; ++l) mid += 2.0 * dims[l];
+  mid += 3.0 * dims[n_layers];
+  if (intermediate_bytes) *intermediate_bytes = (double)V * mid * 4.0;
+  return HT_OK;
+}
+
+double ht_chunk_rows_model(int64_t V, int32_t n_chunks, double alpha) {
+  if (n_chunks <= 0) return 0.0;
+  return (1.0 + alpha) * (double)V / (double)n_chunks;
+}
+
+}  // extern "C"

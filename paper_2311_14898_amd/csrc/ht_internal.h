@@ -1,0 +1,248 @@
+// Internal declarations shared by the translation units of libhongtu.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <chrono>
+#include <cstdio>
+#include <string>
+#include <vector>
+
+#include "../../include/hongtu.h"
+
+// Edges one aggregation work item covers at most.  Rows longer than this are
+// cut into several items whose partial sums are added in item order.
+constexpr int HT_SEG = 512;
+
+struct EpochWs;
+
+enum {
+  HT_S_PACKW = 0, HT_S_TNPART, HT_S_LOSS, HT_S_ACHUNK, HT_S_OCHUNK, HT_S_ZCHUNK, HT_S_DZCHUNK, HT_S_DACHUNK,
+  HT_S_NBUF, HT_S_SPART, HT_S_LEAVE, HT_S_MISC, HT_N_SCRATCH
+};
+
+struct ht_ctx {
+  int device = 0;
+  hipStream_t stream = nullptr;
+  bool own_stream = false;
+  hipStream_t side[2] = {nullptr, nullptr};  // copy / gather streams
+  std::string err;
+  int64_t hbm_budget = 0;  // 0 = unlimited
+  int64_t hbm_used = 0;
+  std::vector<hipEvent_t> ev_pool;
+  size_t ev_next = 0;
+  EpochWs* ws = nullptr;  // buffers of the last ht_epoch
+  // device scratch that calls keep between invocations (grow-only)
+  void* scratch[HT_N_SCRATCH] = {};
+  size_t scratch_bytes[HT_N_SCRATCH] = {};
+  // pinned host scratch (D2H staging of gradient rows)
+  void* hscratch[2] = {nullptr, nullptr};
+  size_t hscratch_bytes[2] = {0, 0};
+  int n_threads = 0;  // host threads for CPU-side accumulation (0 = decide on first use)
+};
+
+int ht_set_err(ht_ctx* ctx, int code, const char* fmt, ...);
+
+#define HT_HIP(ctx, call)                                                                  \
+  do {                                                                                     \
+    hipError_t e_ = (call);                                                                \
+    if (e_ != hipSuccess)                                                                  \
+      return ht_set_err((ctx), e_ == hipErrorOutOfMemory ? HT_ENOMEM : HT_EHIP, "%s: %s",  \
+                        #call, hipGetErrorString(e_));                                     \
+  } while (0)
+
+#define HT_TRY(expr)            \
+  do {                          \
+    int rc_ = (expr);           \
+    if (rc_ != HT_OK) return rc_; \
+  } while (0)
+
+#define HT_LAUNCH_CHECK(ctx) HT_HIP(ctx, hipGetLastError())
+
+// Device allocation with budget accounting.
+int ht_dev_alloc(ht_ctx* ctx, void** out, size_t bytes);
+void ht_dev_free(ht_ctx* ctx, void* p, size_t bytes);
+// Grow-only scratch slot (kept on the context).
+int ht_scratch(ht_ctx* ctx, int slot, size_t bytes, void** out);
+// Grow-only pinned host scratch.
+int ht_host_scratch(ht_ctx* ctx, int slot, size_t bytes, void** out);
+
+template <typename T>
+struct DevArr {
+  T* p = nullptr;
+  size_t n = 0;
+  ht_ctx* ctx = nullptr;
+  DevArr() = default;
+  DevArr(const DevArr&) = delete;
+  DevArr& operator=(const DevArr&) = delete;
+  DevArr(DevArr&& o) noexcept : p(o.p), n(o.n), ctx(o.ctx) { o.p = nullptr; o.n = 0; }
+  DevArr& operator=(DevArr&& o) noexcept {
+    if (this != &o) {
+      release();
+      p = o.p; n = o.n; ctx = o.ctx;
+      o.p = nullptr; o.n = 0;
+    }
+    return *this;
+  }
+  ~DevArr() { release(); }
+  int alloc(ht_ctx* c, size_t count) {
+    release();
+    ctx = c;
+    n = count;
+    if (count == 0) return HT_OK;
+    return ht_dev_alloc(c, (void**)&p, count * sizeof(T));
+  }
+  void release() {
+    if (p) ht_dev_free(ctx, p, n * sizeof(T));
+    p = nullptr;
+    n = 0;
+  }
+  size_t bytes() const { return n * sizeof(T); }
+};
+
+static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// ---- primitives (ht_prims.hip) -------------------------------------------------------
+// Exclusive prefix sum of n values into out[0..n); out[n] = total when want_total.
+int ht_scan_i32(ht_ctx* ctx, const int32_t* in, int64_t* out, int64_t n, bool want_total);
+int ht_scan_i64(ht_ctx* ctx, const int64_t* in, int64_t* out, int64_t n, bool want_total);
+// Stable LSD radix sort of 64-bit keys on bits [bit_lo, bit_hi).  keys and tmp
+// have n entries; returns in *sorted which of the two holds the result.
+int ht_radix_sort_u64(ht_ctx* ctx, uint64_t* keys, uint64_t* tmp, int64_t n, int bit_lo, int bit_hi,
+                      uint64_t** sorted);
+// Bitmap helpers: words are uint64, bit b of word w is element 64*w + b.
+// pref[w] = number of set bits before word w; pref[nw] = total.
+int ht_bitmap_prefix(ht_ctx* ctx, const uint64_t* bm, int64_t nw, int32_t* cnt_tmp, int64_t* pref);
+// Writes the indices of set bits, ascending, to out (size pref[nw]).
+int ht_bitmap_expand(ht_ctx* ctx, const uint64_t* bm, int64_t nw, const int64_t* pref, int32_t* out);
+
+// ---- graph -------------------------------------------------------------------------------
+// Work items of one aggregation direction of one chunk: a row with at most
+// HT_SEG edges is one item; a longer row is cut into items of HT_SEG edges whose
+// partial sums are added in item order by a second kernel.
+struct ItemSet {
+  DevArr<char> blob;          // one allocation behind the arrays below
+  int32_t* row = nullptr;     // [n_items] row of the item (local to the chunk)
+  int64_t* e0 = nullptr;      // [n_items] first edge, relative to the chunk's first edge
+  int32_t* len = nullptr;     // [n_items] edges in the item (<= HT_SEG)
+  int32_t* part = nullptr;    // [n_items] -1: the row's only item; else index of its partial sum
+  int32_t* fx_row = nullptr;  // [n_fix] rows with several items
+  int32_t* fx_part0 = nullptr;
+  int32_t* fx_nseg = nullptr;
+  int64_t n_items = 0, n_part = 0, n_fix = 0;
+};
+
+struct ChunkMeta {
+  int64_t dst0 = 0, dst1 = 0;  // destination range
+  int64_t e0 = 0, nnz = 0;     // edge range in the global CSC arrays
+  int64_t nsrc = 0;            // |N_j|
+  int64_t nbr_off = 0;         // offset of N_j in the nbr / slot arenas
+  int64_t sptr_off = 0;        // offset of sptr_j in the sptr arena (nbr_off + j)
+  int64_t n_reuse = 0, n_load = 0, n_leave = 0;
+  int64_t reuse_off = 0, load_off = 0, leave_off = 0;
+  ItemSet fwd, bwd;            // rows = destinations / rows = local sources
+};
+
+struct ht_graph {
+  ht_ctx* ctx = nullptr;
+  int64_t V = 0, Ep = 0;
+  int32_t n = 0;
+  int32_t add_self_loops = 1;
+  DevArr<int64_t> indptr;      // [V+1]
+  DevArr<int32_t> col;         // [E'] global source ids
+  DevArr<float> s;             // [V] D^-1/2
+  std::vector<int64_t> bounds; // [n+1] host
+  std::vector<ChunkMeta> chunks;
+  DevArr<int32_t> nbr;         // [v_ori] N_j lists
+  DevArr<int32_t> col_local;   // [E']
+  DevArr<int32_t> col_slot;    // [E'] buffer position of each edge's source
+  DevArr<int64_t> sptr;        // [v_ori + n] per-chunk offsets, rebased to 0
+  DevArr<int32_t> sdst;        // [E'] local destinations grouped by local source
+  DevArr<int32_t> slot;        // [v_ori] buffer position of N_j[i]
+  DevArr<int32_t> gslot;       // [v_ori] slot | (1<<31 when N_j[i] is newly loaded)
+  DevArr<int32_t> reuse;       // [v_ori - v_ru]
+  DevArr<int32_t> load;        // [v_ru]
+  DevArr<int32_t> load_slot;   // [v_ru]
+  DevArr<int32_t> leave;       // [v_ru] N_j \ N_{j+1} (all of N_{n-1} for the last chunk)
+  DevArr<int32_t> leave_slot;  // [v_ru]
+  int64_t v_ori = 0, v_ru = 0;
+  int64_t max_nsrc = 0, max_ndst = 0, max_nnz = 0, max_fpart = 0, max_bpart = 0;
+  int64_t cache_rows = 0;
+  double partition_ms = 0.0;
+  int64_t hbm_bytes() const;
+};
+
+// ---- compute kernels' host launchers -----------------------------------------------------
+// Aggregation over work items (ht_spmm.hip).  One wave (or a lane group of it)
+// owns an item; sums are taken in edge order, partial sums in item order.
+struct SpmmArgs {
+  // items
+  const int32_t* it_row;
+  const int64_t* it_e0;
+  const int32_t* it_len;
+  const int32_t* it_part;
+  int64_t n_items;
+  const int32_t* fx_row;
+  const int32_t* fx_part0;
+  const int32_t* fx_nseg;
+  int64_t n_fix;
+  // edges
+  const int32_t* idx;     // per edge: row of `src` to read (chunk-relative pointer)
+  const float* ew;        // per-edge weight table indexed by idx (nullable: weight 1)
+  const float* src;       // source matrix
+  int64_t src_ld;
+  int32_t d;              // valid columns
+  // output
+  float* out;             // output matrix
+  int64_t out_ld;
+  const int32_t* out_idx; // row r -> output row (nullable: r); bit 31 set => overwrite even when accumulating
+  const float* post;      // per-row factor
+  const int32_t* post_idx;// row r -> index into post (nullable: r)
+  int32_t accumulate;     // 1: out += value
+  float* partial;         // [n_part x out_ld] workspace
+};
+int ht_spmm_launch(ht_ctx* ctx, hipStream_t st, const SpmmArgs& a);
+
+// Row gather / scatter (ht_spmm.hip)
+// dst[dst_idx[k]] = scale[src_idx[k]] * src[src_idx[k]]   (scale nullable)
+int ht_gather_rows(ht_ctx* ctx, hipStream_t st, const float* src, int64_t src_ld, const int32_t* src_idx,
+                   float* dst, int64_t dst_ld, const int32_t* dst_idx, int64_t n_rows, int32_t d,
+                   const float* scale);
+// dst[dst_idx[k]] += src[src_idx[k]]  (dst_idx unique inside one call)
+int ht_add_rows(ht_ctx* ctx, hipStream_t st, const float* src, int64_t src_ld, const int32_t* src_idx,
+                float* dst, int64_t dst_ld, const int32_t* dst_idx, int64_t n_rows, int32_t d);
+
+// Dense transform (ht_gemm.hip)
+// C[M x N] = A[M x K] B[K x N], optional ReLU, C rows pitch ldc.  B is row-major dense [K x N].
+int ht_gemm_nn(ht_ctx* ctx, hipStream_t st, const float* A, int64_t lda, const float* B, float* C, int64_t ldc,
+               int64_t M, int32_t K, int32_t N, int relu);
+// C[M x K] = A[M x N] B[K x N]^T
+int ht_gemm_nt(ht_ctx* ctx, hipStream_t st, const float* A, int64_t lda, const float* B, float* C, int64_t ldc,
+               int64_t M, int32_t N, int32_t K);
+// C[K x N] (+)= A[M x K]^T B[M x N]; fixed-order reduction over M slices.
+int ht_gemm_tn(ht_ctx* ctx, hipStream_t st, const float* A, int64_t lda, const float* B, int64_t ldb, float* C,
+               int64_t M, int32_t K, int32_t N, int accumulate);
+
+// Elementwise / loss (ht_elem.hip)
+// dz = dh * [ref > 0]
+int ht_relu_mask(ht_ctx* ctx, hipStream_t st, const float* dh, int64_t ld_dh, const float* ref, int64_t ld_ref,
+                 float* dz, int64_t ld_dz, int64_t rows, int32_t cols);
+int ht_softmax_ce(ht_ctx* ctx, hipStream_t st, const float* logits, int64_t ld, const int32_t* labels, int64_t V,
+                  int32_t C, float* grad, int64_t ld_g, float* loss_dev /*1 float*/);
+int ht_sgd(ht_ctx* ctx, hipStream_t st, float* W, const float* dW, int64_t n, float lr);
+int ht_fill_zero(ht_ctx* ctx, hipStream_t st, void* p, size_t bytes);
+
+// stats helpers
+struct Timer {
+  ht_ctx* ctx;
+  hipStream_t st;
+  bool on;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> ev;
+  std::vector<double*> dst;
+  Timer(ht_ctx* c, hipStream_t s, bool enabled) : ctx(c), st(s), on(enabled) {}
+  void begin(double* acc);
+  void end();
+  int resolve();  // after the stream is synchronised
+};
+hipEvent_t ht_event(ht_ctx* ctx);

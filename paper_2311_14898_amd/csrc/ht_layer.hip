@@ -1,0 +1,665 @@
+// Per-chunk layer step, forward and backward, and the epoch built from it.
+//
+//   forward  (Alg. 1 lines 6-9, Alg. 2 lines 1-4, Eq. 2): neighbour rows reach
+//            the aggregation either in place (tensor in HBM) or through the
+//            in-place neighbour buffer (reused rows stay, new rows are fetched
+//            from HBM or pinned host memory); aggregate; linear + ReLU; rows
+//            of a^l and h^{l+1} go to their homes.
+//   backward (Alg. 1 lines 14-19, Alg. 3 lines 5-8, Sec. 2.3, Sec. 4.2): reload
+//            the checkpoint, recompute the update stage, grad W, grad a,
+//            aggregate backward by source; neighbour gradients accumulate in HBM
+//            while their vertex stays buffered and leave to the gradient home
+//            (CPU-side add when that home is host memory).
+#include <algorithm>
+#include <cstring>
+#include <thread>
+
+#include "ht_internal.h"
+
+struct EpochWs {
+  int64_t V = 0;
+  std::vector<int32_t> dims;
+  int res_h = 0, res_a = 0, res_g = 0;
+  std::vector<ht_tensor> h, a, gh;  // h[l] = h^l (l >= 1; h[0] unused), a[l], gh[l] = grad h^l (l >= 1)
+  std::vector<float*> dW;
+  std::vector<size_t> dev_bytes_of;  // for freeing
+  std::vector<void*> dev_ptrs;
+  std::vector<void*> host_ptrs;
+  float* loss_dev = nullptr;
+};
+
+namespace {
+
+int check_tensor(ht_ctx* ctx, const ht_tensor* t, int64_t rows, int32_t cols, const char* name) {
+  if (!t || !t->ptr) return ht_set_err(ctx, HT_EINVAL, "%s: null tensor", name);
+  if (t->rows != rows || t->cols != cols)
+    return ht_set_err(ctx, HT_ESHAPE, "%s: shape [%lld x %d], expected [%lld x %d]", name, (long long)t->rows, t->cols,
+                      (long long)rows, cols);
+  if (t->ld < t->cols || (t->ld & 3))
+    return ht_set_err(ctx, HT_ESHAPE, "%s: row pitch %lld must be >= cols and a multiple of 4", name, (long long)t->ld);
+  if (t->loc != HT_LOC_DEVICE && t->loc != HT_LOC_HOST_PINNED)
+    return ht_set_err(ctx, HT_ESHAPE, "%s: unknown location %d", name, t->loc);
+  if ((uintptr_t)t->ptr & 15) return ht_set_err(ctx, HT_ESHAPE, "%s: base pointer must be 16-byte aligned", name);
+  return HT_OK;
+}
+
+// Pointer the GPU can dereference.
+int gpu_ptr(ht_ctx* ctx, const ht_tensor* t, float** out) {
+  if (t->loc == HT_LOC_DEVICE) {
+    *out = t->ptr;
+    return HT_OK;
+  }
+  void* d = nullptr;
+  hipError_t e = hipHostGetDevicePointer(&d, t->ptr, 0);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return ht_set_err(ctx, HT_ESHAPE, "host tensor is not page-locked / GPU-addressable: %s", hipGetErrorString(e));
+  }
+  *out = (float*)d;
+  return HT_OK;
+}
+
+int host_threads(ht_ctx* ctx) {
+  if (ctx->n_threads <= 0) {
+    unsigned hc = std::thread::hardware_concurrency();
+    ctx->n_threads = (int)std::min<unsigned>(hc ? hc : 4u, 16u);
+  }
+  return ctx->n_threads;
+}
+
+// grad[ids[k]] += rows[k] on the host cores (Alg. 3 line 7); ids are unique.
+void cpu_accumulate(ht_ctx* ctx, float* grad, int64_t ld, const int32_t* ids, const float* rows, int64_t rows_ld,
+                    int64_t n, int d) {
+  const int nt = (int)std::min<int64_t>(host_threads(ctx), std::max<int64_t>(1, n / 256));
+  auto work = [&](int64_t k0, int64_t k1) {
+    for (int64_t k = k0; k < k1; ++k) {
+      float* g = grad + (int64_t)ids[k] * ld;
+      const float* r = rows + k * rows_ld;
+      for (int c = 0; c < d; ++c) g[c] += r[c];
+    }
+  };
+  if (nt <= 1) {
+    work(0, n);
+    return;
+  }
+  std::vector<std::thread> th;
+  const int64_t per = (n + nt - 1) / nt;
+  for (int t = 0; t < nt; ++t) {
+    const int64_t k0 = t * per, k1 = std::min<int64_t>(n, k0 + per);
+    if (k0 < k1) th.emplace_back(work, k0, k1);
+  }
+  for (auto& t : th) t.join();
+}
+
+struct Run {
+  ht_ctx* ctx;
+  const ht_graph* g;
+  Timer tm;
+  ht_stats* st;  // never null inside (a local one is used when the caller passes none)
+  Run(ht_ctx* c, const ht_graph* gr, ht_stats* s, bool timed) : ctx(c), g(gr), tm(c, c->stream, timed), st(s) {}
+};
+
+double spmm_alg_bytes(const ChunkMeta& c, int d) {
+  const double nd = (double)(c.dst1 - c.dst0);
+  return 4.0 * c.nnz + 8.0 * nd + 4.0 * d * (double)c.nsrc + 4.0 * d * nd + 4.0 * ((double)c.nsrc + nd);
+}
+
+// Aggregate of chunk j into out rows [0, ndst) (pitch out_ld).  `Hin` is the
+// GPU-usable pointer of H_in.  buffer mode keeps N_j's rows (pre-scaled by s_u)
+// in ctx scratch HT_S_NBUF.
+int aggregate_chunk(Run& R, int j, bool buffer, const ht_tensor* H_in, const float* Hin, int d, float* out,
+                    int64_t out_ld) {
+  ht_ctx* ctx = R.ctx;
+  const ht_graph* g = R.g;
+  const ChunkMeta& c = g->chunks[j];
+  hipStream_t st = ctx->stream;
+  const int64_t ndst = c.dst1 - c.dst0;
+  if (ndst == 0) return HT_OK;
+  float* nbuf = nullptr;
+  if (buffer) {
+    HT_TRY(ht_scratch(ctx, HT_S_NBUF, (size_t)g->cache_rows * H_in->ld * 4, (void**)&nbuf));
+    R.tm.begin(&R.st->t_gather_ms);
+    HT_TRY(ht_gather_rows(ctx, st, Hin, H_in->ld, g->load.p + c.load_off, nbuf, H_in->ld, g->load_slot.p + c.load_off,
+                          c.n_load, d, g->s.p));
+    R.tm.end();
+    R.st->rows_loaded += c.n_load;
+    R.st->rows_reused += c.n_reuse;
+    if (H_in->loc == HT_LOC_HOST_PINNED) R.st->bytes_h2d += (int64_t)c.n_load * d * 4;
+    R.st->bytes_h2d_nodedup += (int64_t)c.nsrc * d * 4;
+  }
+  float* partial = nullptr;
+  if (c.fwd.n_part > 0) HT_TRY(ht_scratch(ctx, HT_S_SPART, (size_t)g->max_fpart * out_ld * 4, (void**)&partial));
+  SpmmArgs a{};
+  a.it_row = c.fwd.row; a.it_e0 = c.fwd.e0; a.it_len = c.fwd.len; a.it_part = c.fwd.part; a.n_items = c.fwd.n_items;
+  a.fx_row = c.fwd.fx_row; a.fx_part0 = c.fwd.fx_part0; a.fx_nseg = c.fwd.fx_nseg; a.n_fix = c.fwd.n_fix;
+  a.idx = (buffer ? g->col_slot.p : g->col.p) + c.e0;
+  a.ew = buffer ? nullptr : g->s.p;
+  a.src = buffer ? nbuf : Hin;
+  a.src_ld = H_in->ld;
+  a.d = d;
+  a.out = out; a.out_ld = out_ld; a.out_idx = nullptr;
+  a.post = g->s.p + c.dst0; a.post_idx = nullptr;
+  a.accumulate = 0;
+  a.partial = partial;
+  R.tm.begin(&R.st->t_spmm_fwd_ms);
+  HT_TRY(ht_spmm_launch(ctx, st, a));
+  R.tm.end();
+  R.st->n_spmm_fwd += 1;
+  R.st->edges += c.nnz;
+  R.st->spmm_fwd_alg_bytes += spmm_alg_bytes(c, d);
+  return HT_OK;
+}
+
+int resolve_gather(ht_ctx* ctx, int mode, const ht_tensor* t, bool* buffer) {
+  if (mode == HT_GATHER_AUTO) *buffer = t->loc != HT_LOC_DEVICE;
+  else if (mode == HT_GATHER_DIRECT) {
+    if (t->loc != HT_LOC_DEVICE) return ht_set_err(ctx, HT_ESHAPE, "direct gather needs the tensor in HBM");
+    *buffer = false;
+  } else if (mode == HT_GATHER_BUFFER) *buffer = true;
+  else return ht_set_err(ctx, HT_EINVAL, "unknown gather mode %d", mode);
+  return HT_OK;
+}
+
+int layer_fwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* H_in, const float* W, ht_tensor* H_out,
+                   ht_tensor* A_ckpt) {
+  ht_ctx* ctx = R.ctx;
+  const ht_graph* g = R.g;
+  hipStream_t st = ctx->stream;
+  const int di = desc->d_in, dn = desc->d_out;
+  HT_TRY(check_tensor(ctx, H_in, g->V, di, "H_in"));
+  HT_TRY(check_tensor(ctx, H_out, g->V, dn, "H_out"));
+  if (A_ckpt) HT_TRY(check_tensor(ctx, A_ckpt, g->V, di, "A_ckpt"));
+  if (!W) return ht_set_err(ctx, HT_EINVAL, "W is null");
+  bool buffer = false;
+  HT_TRY(resolve_gather(ctx, desc->gather_mode, H_in, &buffer));
+  float* Hin = nullptr;
+  HT_TRY(gpu_ptr(ctx, H_in, &Hin));
+
+  const bool a_dev = A_ckpt && A_ckpt->loc == HT_LOC_DEVICE;
+  const bool h_dev = H_out->loc == HT_LOC_DEVICE;
+  const int64_t a_ld = A_ckpt ? A_ckpt->ld : ((di + 3) & ~3);
+  float* a_chunk = nullptr;
+  float* h_chunk = nullptr;
+  if (!a_dev) HT_TRY(ht_scratch(ctx, HT_S_ACHUNK, (size_t)std::max<int64_t>(g->max_ndst, 1) * a_ld * 4, (void**)&a_chunk));
+  if (!h_dev) HT_TRY(ht_scratch(ctx, HT_S_OCHUNK, (size_t)std::max<int64_t>(g->max_ndst, 1) * H_out->ld * 4, (void**)&h_chunk));
+
+  for (int j = 0; j < g->n; ++j) {
+    const ChunkMeta& c = g->chunks[j];
+    const int64_t ndst = c.dst1 - c.dst0;
+    if (ndst == 0) continue;
+    float* a_dst = a_dev ? A_ckpt->ptr + c.dst0 * a_ld : a_chunk;
+    HT_TRY(aggregate_chunk(R, j, buffer, H_in, Hin, di, a_dst, a_ld));
+    if (A_ckpt && !a_dev) {
+      R.tm.begin(&R.st->t_copy_ms);
+      HT_HIP(ctx, hipMemcpyAsync(A_ckpt->ptr + c.dst0 * a_ld, a_chunk, (size_t)ndst * a_ld * 4, hipMemcpyDeviceToHost, st));
+      R.tm.end();
+      R.st->bytes_d2h += ndst * a_ld * 4;
+    }
+    float* h_dst = h_dev ? H_out->ptr + c.dst0 * H_out->ld : h_chunk;
+    R.tm.begin(&R.st->t_gemm_ms);
+    HT_TRY(ht_gemm_nn(ctx, st, a_dst, a_ld, W, h_dst, H_out->ld, ndst, di, dn, desc->act == HT_ACT_RELU));
+    R.tm.end();
+    R.st->n_gemm += 1;
+    R.st->gemm_flops += 2.0 * ndst * di * dn;
+    if (!h_dev) {
+      R.tm.begin(&R.st->t_copy_ms);
+      HT_HIP(ctx, hipMemcpyAsync(H_out->ptr + c.dst0 * H_out->ld, h_chunk, (size_t)ndst * H_out->ld * 4,
+                                 hipMemcpyDeviceToHost, st));
+      R.tm.end();
+      R.st->bytes_d2h += ndst * H_out->ld * 4;
+    }
+  }
+  return HT_OK;
+}
+
+// Rows [r0, r0+n) of t on the device: in place when t is in HBM, else copied into `staging`.
+int rows_on_device(Run& R, const ht_tensor* t, int64_t r0, int64_t n, float* staging, const float** out) {
+  if (t->loc == HT_LOC_DEVICE) {
+    *out = t->ptr + r0 * t->ld;
+    return HT_OK;
+  }
+  R.tm.begin(&R.st->t_copy_ms);
+  HT_HIP(R.ctx, hipMemcpyAsync(staging, t->ptr + r0 * t->ld, (size_t)n * t->ld * 4, hipMemcpyHostToDevice, R.ctx->stream));
+  R.tm.end();
+  R.st->bytes_h2d += n * t->ld * 4;
+  *out = staging;
+  return HT_OK;
+}
+
+int layer_bwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* ckpt, const float* W, const ht_tensor* dH_out,
+                   const ht_tensor* H_out, ht_tensor* dH_in, float* dW) {
+  ht_ctx* ctx = R.ctx;
+  const ht_graph* g = R.g;
+  hipStream_t st = ctx->stream;
+  const int di = desc->d_in, dn = desc->d_out;
+  HT_TRY(check_tensor(ctx, ckpt, g->V, di, "ckpt"));
+  HT_TRY(check_tensor(ctx, dH_out, g->V, dn, "dH_out"));
+  if (H_out) HT_TRY(check_tensor(ctx, H_out, g->V, dn, "H_out"));
+  if (dH_in) HT_TRY(check_tensor(ctx, dH_in, g->V, di, "dH_in"));
+  if (!W || !dW) return ht_set_err(ctx, HT_EINVAL, "W or dW is null");
+  if (desc->ckpt_kind != HT_CKPT_AGG && desc->ckpt_kind != HT_CKPT_INPUT)
+    return ht_set_err(ctx, HT_EINVAL, "unknown checkpoint kind %d", desc->ckpt_kind);
+  const bool relu = desc->act == HT_ACT_RELU;
+  const int64_t mx = std::max<int64_t>(g->max_ndst, 1);
+  const int64_t ld_i = (di + 3) & ~3, ld_o = (dn + 3) & ~3;
+
+  // forward-side inputs
+  bool agg_buffer = false;
+  float* Hin = nullptr;
+  if (desc->ckpt_kind == HT_CKPT_INPUT) {
+    HT_TRY(resolve_gather(ctx, desc->gather_mode, ckpt, &agg_buffer));
+    HT_TRY(gpu_ptr(ctx, ckpt, &Hin));
+  }
+  // gradient side: direct accumulation into dH_in (HBM) or through the in-place gradient buffer
+  bool gbuffer = false;
+  if (dH_in) HT_TRY(resolve_gather(ctx, desc->gather_mode, dH_in, &gbuffer));
+
+  float *a_chunk = nullptr, *dh_chunk = nullptr, *z_chunk = nullptr, *dz_chunk = nullptr, *da_chunk = nullptr;
+  float* gbuf = nullptr;
+  const int64_t a_ld = desc->ckpt_kind == HT_CKPT_AGG ? ckpt->ld : ld_i;
+  if (desc->ckpt_kind == HT_CKPT_INPUT || ckpt->loc != HT_LOC_DEVICE)
+    HT_TRY(ht_scratch(ctx, HT_S_ACHUNK, (size_t)mx * a_ld * 4, (void**)&a_chunk));
+  if (dH_out->loc != HT_LOC_DEVICE) HT_TRY(ht_scratch(ctx, HT_S_OCHUNK, (size_t)mx * dH_out->ld * 4, (void**)&dh_chunk));
+  if (relu) {
+    const int64_t zl = H_out ? H_out->ld : ld_o;
+    if (!H_out || H_out->loc != HT_LOC_DEVICE) HT_TRY(ht_scratch(ctx, HT_S_ZCHUNK, (size_t)mx * zl * 4, (void**)&z_chunk));
+    HT_TRY(ht_scratch(ctx, HT_S_DZCHUNK, (size_t)mx * ld_o * 4, (void**)&dz_chunk));
+  }
+  if (dH_in) {
+    HT_TRY(ht_scratch(ctx, HT_S_DACHUNK, (size_t)mx * ld_i * 4, (void**)&da_chunk));
+    if (gbuffer) HT_TRY(ht_scratch(ctx, HT_S_MISC, (size_t)g->cache_rows * ld_i * 4, (void**)&gbuf));
+  }
+  // host copy of the leave lists for the CPU-side accumulation
+  std::vector<int32_t> leave_host;
+  const bool cpu_accum = dH_in && gbuffer && dH_in->loc == HT_LOC_HOST_PINNED;
+  float* leave_dev = nullptr;
+  float* leave_pin = nullptr;
+  if (cpu_accum) {
+    int64_t mxl = 1;
+    for (const ChunkMeta& c : g->chunks) mxl = std::max(mxl, c.n_leave);
+    leave_host.resize((size_t)std::max<int64_t>(g->v_ru, 1));
+    HT_HIP(ctx, hipMemcpy(leave_host.data(), g->leave.p, (size_t)g->v_ru * 4, hipMemcpyDeviceToHost));
+    HT_TRY(ht_scratch(ctx, HT_S_LEAVE, (size_t)mxl * ld_i * 4, (void**)&leave_dev));
+    HT_TRY(ht_host_scratch(ctx, 0, (size_t)mxl * ld_i * 4, (void**)&leave_pin));
+  }
+
+  bool first = true;
+  for (int j = 0; j < g->n; ++j) {
+    const ChunkMeta& c = g->chunks[j];
+    const int64_t ndst = c.dst1 - c.dst0;
+    if (ndst > 0) {
+      // a^l rows of the chunk
+      const float* a_rows = nullptr;
+      if (desc->ckpt_kind == HT_CKPT_AGG) {
+        HT_TRY(rows_on_device(R, ckpt, c.dst0, ndst, a_chunk, &a_rows));
+      } else {
+        HT_TRY(aggregate_chunk(R, j, agg_buffer, ckpt, Hin, di, a_chunk, a_ld));
+        a_rows = a_chunk;
+      }
+      const float* dh_rows = nullptr;
+      HT_TRY(rows_on_device(R, dH_out, c.dst0, ndst, dh_chunk, &dh_rows));
+      // dz = dh * ReLU'(z)
+      const float* dz_rows = dh_rows;
+      int64_t dz_ld = dH_out->ld;
+      if (relu) {
+        const float* ref = nullptr;
+        int64_t ref_ld = 0;
+        if (H_out) {
+          HT_TRY(rows_on_device(R, H_out, c.dst0, ndst, z_chunk, &ref));
+          ref_ld = H_out->ld;
+        } else {  // re-forward of the update stage (Alg. 1 line 17)
+          R.tm.begin(&R.st->t_gemm_ms);
+          HT_TRY(ht_gemm_nn(ctx, st, a_rows, a_ld, W, z_chunk, ld_o, ndst, di, dn, 0));
+          R.tm.end();
+          R.st->n_gemm += 1;
+          R.st->gemm_flops += 2.0 * ndst * di * dn;
+          ref = z_chunk;
+          ref_ld = ld_o;
+        }
+        HT_TRY(ht_relu_mask(ctx, st, dh_rows, dH_out->ld, ref, ref_ld, dz_chunk, ld_o, ndst, dn));
+        dz_rows = dz_chunk;
+        dz_ld = ld_o;
+      }
+      R.tm.begin(&R.st->t_gemm_ms);
+      HT_TRY(ht_gemm_tn(ctx, st, a_rows, a_ld, dz_rows, dz_ld, dW, ndst, di, dn, first ? 0 : 1));
+      R.tm.end();
+      R.st->n_gemm += 1;
+      R.st->gemm_flops += 2.0 * ndst * di * dn;
+      first = false;
+      if (dH_in) {
+        R.tm.begin(&R.st->t_gemm_ms);
+        HT_TRY(ht_gemm_nt(ctx, st, dz_rows, dz_ld, W, da_chunk, ld_i, ndst, dn, di));
+        R.tm.end();
+        R.st->n_gemm += 1;
+        R.st->gemm_flops += 2.0 * ndst * di * dn;
+        float* partial = nullptr;
+        const int64_t out_ld = gbuffer ? ld_i : dH_in->ld;
+        if (c.bwd.n_part > 0) HT_TRY(ht_scratch(ctx, HT_S_SPART, (size_t)g->max_bpart * out_ld * 4, (void**)&partial));
+        SpmmArgs a{};
+        a.it_row = c.bwd.row; a.it_e0 = c.bwd.e0; a.it_len = c.bwd.len; a.it_part = c.bwd.part; a.n_items = c.bwd.n_items;
+        a.fx_row = c.bwd.fx_row; a.fx_part0 = c.bwd.fx_part0; a.fx_nseg = c.bwd.fx_nseg; a.n_fix = c.bwd.n_fix;
+        a.idx = g->sdst.p + c.e0;
+        a.ew = g->s.p + c.dst0;
+        a.src = da_chunk;
+        a.src_ld = ld_i;
+        a.d = di;
+        a.out = gbuffer ? gbuf : dH_in->ptr;
+        a.out_ld = out_ld;
+        a.out_idx = gbuffer ? g->gslot.p + c.nbr_off : g->nbr.p + c.nbr_off;
+        a.post = g->s.p;
+        a.post_idx = g->nbr.p + c.nbr_off;
+        a.accumulate = 1;
+        a.partial = partial;
+        R.tm.begin(&R.st->t_spmm_bwd_ms);
+        HT_TRY(ht_spmm_launch(ctx, st, a));
+        R.tm.end();
+        R.st->n_spmm_bwd += 1;
+        R.st->edges += c.nnz;
+        R.st->spmm_bwd_alg_bytes += spmm_alg_bytes(c, di);
+      }
+    }
+    // rows that are not neighbours of the next chunk leave the gradient buffer (Alg. 3 lines 6-7)
+    if (dH_in && gbuffer && c.n_leave > 0) {
+      if (!cpu_accum) {
+        HT_TRY(ht_add_rows(ctx, st, gbuf, ld_i, g->leave_slot.p + c.leave_off, dH_in->ptr, dH_in->ld,
+                           g->leave.p + c.leave_off, c.n_leave, di));
+      } else {
+        R.tm.begin(&R.st->t_copy_ms);
+        HT_TRY(ht_gather_rows(ctx, st, gbuf, ld_i, g->leave_slot.p + c.leave_off, leave_dev, ld_i, nullptr, c.n_leave, di,
+                              nullptr));
+        HT_HIP(ctx, hipMemcpyAsync(leave_pin, leave_dev, (size_t)c.n_leave * ld_i * 4, hipMemcpyDeviceToHost, st));
+        R.tm.end();
+        HT_HIP(ctx, hipStreamSynchronize(st));
+        R.st->bytes_d2h += c.n_leave * (int64_t)di * 4;
+        auto t0 = std::chrono::steady_clock::now();
+        cpu_accumulate(ctx, dH_in->ptr, dH_in->ld, leave_host.data() + c.leave_off, leave_pin, ld_i, c.n_leave, di);
+        R.st->t_cpu_accum_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+      }
+    }
+  }
+  if (first) HT_TRY(ht_fill_zero(ctx, st, dW, (size_t)di * dn * 4));
+  return HT_OK;
+}
+
+int finish(Run& R, ht_stats* user, const std::chrono::steady_clock::time_point& t0, bool sync) {
+  ht_ctx* ctx = R.ctx;
+  if (sync || user) {
+    HT_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    HT_TRY(R.tm.resolve());
+  }
+  ctx->ev_next = 0;
+  if (user) {
+    R.st->t_total_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+    *user = *R.st;
+  }
+  return HT_OK;
+}
+
+}  // namespace
+
+void ht_epoch_ws_free(ht_ctx* ctx) {
+  EpochWs* ws = ctx->ws;
+  if (!ws) return;
+  (void)hipStreamSynchronize(ctx->stream);
+  for (size_t i = 0; i < ws->dev_ptrs.size(); ++i) ht_dev_free(ctx, ws->dev_ptrs[i], ws->dev_bytes_of[i]);
+  for (void* p : ws->host_ptrs) (void)hipHostFree(p);
+  delete ws;
+  ctx->ws = nullptr;
+}
+
+namespace {
+
+int ws_tensor(ht_ctx* ctx, EpochWs* ws, int64_t V, int32_t d, int res, ht_tensor* t) {
+  t->rows = V;
+  t->cols = d;
+  t->ld = (d + 3) & ~3;
+  const size_t bytes = (size_t)V * t->ld * 4;
+  if (res == HT_RES_HOST) {
+    void* p = nullptr;
+    hipError_t e = hipHostMalloc(&p, bytes, hipHostMallocDefault);
+    if (e != hipSuccess) {
+      (void)hipGetLastError();
+      return ht_set_err(ctx, HT_ENOMEM, "hipHostMalloc(%zu): %s", bytes, hipGetErrorString(e));
+    }
+    ws->host_ptrs.push_back(p);
+    t->ptr = (float*)p;
+    t->loc = HT_LOC_HOST_PINNED;
+  } else {
+    void* p = nullptr;
+    HT_TRY(ht_dev_alloc(ctx, &p, bytes));
+    ws->dev_ptrs.push_back(p);
+    ws->dev_bytes_of.push_back(bytes);
+    t->ptr = (float*)p;
+    t->loc = HT_LOC_DEVICE;
+  }
+  return HT_OK;
+}
+
+int zero_tensor(ht_ctx* ctx, ht_tensor* t) {
+  const size_t bytes = (size_t)t->rows * t->ld * 4;
+  if (t->loc == HT_LOC_DEVICE) return ht_fill_zero(ctx, ctx->stream, t->ptr, bytes);
+  HT_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  std::memset(t->ptr, 0, bytes);
+  return HT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ht_layer_fwd(ht_ctx* ctx, const ht_graph* g, const ht_layer_desc* desc, const ht_tensor* H_in, const float* W,
+                 ht_tensor* H_out, ht_tensor* A_ckpt, ht_stats* stats) {
+  if (!ctx) return HT_EINVAL;
+  if (!g || !desc || !H_in || !H_out) return ht_set_err(ctx, HT_EINVAL, "ht_layer_fwd: null argument");
+  if (g->ctx != ctx) return ht_set_err(ctx, HT_ESTATE, "graph belongs to another context");
+  if (desc->d_in <= 0 || desc->d_out <= 0) return ht_set_err(ctx, HT_ESHAPE, "layer widths must be positive");
+  HT_HIP(ctx, hipSetDevice(ctx->device));
+  auto t0 = std::chrono::steady_clock::now();
+  ht_stats local{};
+  Run R(ctx, g, &local, stats != nullptr);
+  int rc = layer_fwd_impl(R, desc, H_in, W, H_out, A_ckpt);
+  if (rc != HT_OK) {
+    (void)hipStreamSynchronize(ctx->stream);
+    ctx->ev_next = 0;
+    return rc;
+  }
+  return finish(R, stats, t0, false);
+}
+
+int ht_layer_bwd(ht_ctx* ctx, const ht_graph* g, const ht_layer_desc* desc, const ht_tensor* ckpt, const float* W,
+                 const ht_tensor* dH_out, const ht_tensor* H_out, ht_tensor* dH_in, float* dW, ht_stats* stats) {
+  if (!ctx) return HT_EINVAL;
+  if (!g || !desc || !ckpt || !dH_out) return ht_set_err(ctx, HT_EINVAL, "ht_layer_bwd: null argument");
+  if (g->ctx != ctx) return ht_set_err(ctx, HT_ESTATE, "graph belongs to another context");
+  if (desc->d_in <= 0 || desc->d_out <= 0) return ht_set_err(ctx, HT_ESHAPE, "layer widths must be positive");
+  HT_HIP(ctx, hipSetDevice(ctx->device));
+  auto t0 = std::chrono::steady_clock::now();
+  ht_stats local{};
+  Run R(ctx, g, &local, stats != nullptr);
+  int rc = layer_bwd_impl(R, desc, ckpt, W, dH_out, H_out, dH_in, dW);
+  if (rc != HT_OK) {
+    (void)hipStreamSynchronize(ctx->stream);
+    ctx->ev_next = 0;
+    return rc;
+  }
+  return finish(R, stats, t0, false);
+}
+
+int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_tensor* X, const int32_t* labels,
+             const ht_plan_opts* plan, float* loss_out, ht_stats* stats) {
+  if (!ctx) return HT_EINVAL;
+  if (!g || !model || !X || !labels || !loss_out) return ht_set_err(ctx, HT_EINVAL, "ht_epoch: null argument");
+  if (g->ctx != ctx) return ht_set_err(ctx, HT_ESTATE, "graph belongs to another context");
+  const int L = model->n_layers;
+  if (L < 1 || !model->dims || !model->W) return ht_set_err(ctx, HT_EINVAL, "ht_epoch: bad model");
+  for (int l = 0; l <= L; ++l)
+    if (model->dims[l] <= 0) return ht_set_err(ctx, HT_ESHAPE, "ht_epoch: layer widths must be positive");
+  for (int l = 0; l < L; ++l)
+    if (!model->W[l]) return ht_set_err(ctx, HT_EINVAL, "ht_epoch: W[%d] is null", l);
+  HT_HIP(ctx, hipSetDevice(ctx->device));
+  HT_TRY(check_tensor(ctx, X, g->V, model->dims[0], "X"));
+  auto t0 = std::chrono::steady_clock::now();
+  const int64_t V = g->V;
+
+  // ---- residency plan (Sec. 4.2 sized to this GPU)
+  int res_h = plan ? plan->res_h : HT_RES_AUTO, res_a = plan ? plan->res_a : HT_RES_AUTO,
+      res_g = plan ? plan->res_g : HT_RES_AUTO;
+  int inter = plan ? plan->inter : HT_INTER_AUTO;
+  const int gather_mode = plan ? plan->gather_mode : HT_GATHER_AUTO;
+  int64_t budget = plan ? plan->hbm_budget_bytes : 0;
+  if (budget == 0) {
+    size_t fr = 0, tot = 0;
+    HT_HIP(ctx, hipMemGetInfo(&fr, &tot));
+    budget = (int64_t)fr - ((int64_t)2 << 30);
+    // buffers of a previous epoch with the same shape are reused, so count them as free
+    if (ctx->ws)
+      for (size_t b : ctx->ws->dev_bytes_of) budget += (int64_t)b;
+  }
+  auto bytes_of = [&](int l0, int l1) {
+    int64_t b = 0;
+    for (int l = l0; l <= l1; ++l) b += V * (int64_t)((model->dims[l] + 3) & ~3) * 4;
+    return b;
+  };
+  int64_t left = budget;
+  // the output layer's logits and their gradient stay in HBM (the loss runs on them in place)
+  left -= 2 * bytes_of(L, L);
+  if (res_g == HT_RES_AUTO) { if (L > 1 && bytes_of(1, L - 1) <= left) { res_g = HT_RES_HBM; left -= bytes_of(1, L - 1); } else res_g = L > 1 ? HT_RES_HOST : HT_RES_HBM; }
+  if (res_a == HT_RES_AUTO) { if (bytes_of(0, L - 1) <= left) { res_a = HT_RES_HBM; left -= bytes_of(0, L - 1); } else res_a = HT_RES_HOST; }
+  if (res_h == HT_RES_AUTO) { if (L > 1 && bytes_of(1, L - 1) <= left) { res_h = HT_RES_HBM; left -= bytes_of(1, L - 1); } else res_h = L > 1 ? HT_RES_HOST : HT_RES_HBM; }
+  if (inter == HT_INTER_AUTO) inter = res_h == HT_RES_HBM ? HT_INTER_MASK : HT_INTER_HYBRID;
+
+  // ---- workspace
+  EpochWs* ws = ctx->ws;
+  bool reuse = ws && ws->V == V && (int)ws->dims.size() == L + 1 && ws->res_h == res_h && ws->res_a == res_a &&
+               ws->res_g == res_g;
+  if (reuse)
+    for (int l = 0; l <= L; ++l) reuse = reuse && ws->dims[l] == model->dims[l];
+  if (!reuse) {
+    ht_epoch_ws_free(ctx);
+    ws = new (std::nothrow) EpochWs();
+    if (!ws) return ht_set_err(ctx, HT_ENOMEM, "ht_epoch: host allocation failed");
+    ctx->ws = ws;
+    ws->V = V;
+    ws->dims.assign(model->dims, model->dims + L + 1);
+    ws->res_h = res_h; ws->res_a = res_a; ws->res_g = res_g;
+    ws->h.assign(L + 1, ht_tensor{});
+    ws->a.assign(L, ht_tensor{});
+    ws->gh.assign(L + 1, ht_tensor{});
+    ws->dW.assign(L, nullptr);
+    int rc = HT_OK;
+    for (int l = 1; l <= L && rc == HT_OK; ++l) rc = ws_tensor(ctx, ws, V, model->dims[l], l == L ? HT_RES_HBM : res_h, &ws->h[l]);
+    for (int l = 0; l < L && rc == HT_OK; ++l) rc = ws_tensor(ctx, ws, V, model->dims[l], res_a, &ws->a[l]);
+    for (int l = 1; l <= L && rc == HT_OK; ++l) rc = ws_tensor(ctx, ws, V, model->dims[l], l == L ? HT_RES_HBM : res_g, &ws->gh[l]);
+    for (int l = 0; l < L && rc == HT_OK; ++l) {
+      void* p = nullptr;
+      const size_t b = (size_t)model->dims[l] * model->dims[l + 1] * 4;
+      rc = ht_dev_alloc(ctx, &p, b);
+      if (rc == HT_OK) { ws->dW[l] = (float*)p; ws->dev_ptrs.push_back(p); ws->dev_bytes_of.push_back(b); }
+    }
+    if (rc == HT_OK) {
+      void* p = nullptr;
+      rc = ht_dev_alloc(ctx, &p, 16);
+      if (rc == HT_OK) { ws->loss_dev = (float*)p; ws->dev_ptrs.push_back(p); ws->dev_bytes_of.push_back(16); }
+    }
+    if (rc != HT_OK) {
+      ht_epoch_ws_free(ctx);
+      return rc;
+    }
+  }
+
+  ht_stats local{};
+  Run R(ctx, g, &local, stats != nullptr);
+  auto fail = [&](int rc) {
+    (void)hipStreamSynchronize(ctx->stream);
+    ctx->ev_next = 0;
+    return rc;
+  };
+  // ---- forward (Alg. 1 lines 4-9)
+  for (int l = 0; l < L; ++l) {
+    ht_layer_desc d{};
+    d.d_in = model->dims[l]; d.d_out = model->dims[l + 1];
+    d.act = l < L - 1 ? HT_ACT_RELU : HT_ACT_NONE;
+    d.gather_mode = gather_mode;
+    int rc = layer_fwd_impl(R, &d, l == 0 ? X : &ws->h[l], model->W[l], &ws->h[l + 1], &ws->a[l]);
+    if (rc != HT_OK) return fail(rc);
+  }
+  // ---- downstream task and its gradient (Alg. 1 lines 10-11)
+  {
+    R.tm.begin(&R.st->t_loss_ms);
+    int rc = ht_softmax_ce(ctx, ctx->stream, ws->h[L].ptr, ws->h[L].ld, labels, V, model->dims[L], ws->gh[L].ptr,
+                           ws->gh[L].ld, ws->loss_dev);
+    R.tm.end();
+    if (rc != HT_OK) return fail(rc);
+  }
+  // ---- backward (Alg. 1 lines 12-19)
+  for (int l = L - 1; l >= 0; --l) {
+    ht_layer_desc d{};
+    d.d_in = model->dims[l]; d.d_out = model->dims[l + 1];
+    d.act = l < L - 1 ? HT_ACT_RELU : HT_ACT_NONE;
+    d.gather_mode = gather_mode;
+    d.ckpt_kind = HT_CKPT_AGG;
+    if (l > 0) {
+      int rc = zero_tensor(ctx, &ws->gh[l]);
+      if (rc != HT_OK) return fail(rc);
+    }
+    const ht_tensor* mask_from = (inter == HT_INTER_MASK && l < L - 1) ? &ws->h[l + 1] : nullptr;
+    int rc = layer_bwd_impl(R, &d, &ws->a[l], model->W[l], &ws->gh[l + 1], mask_from, l > 0 ? &ws->gh[l] : nullptr,
+                            ws->dW[l]);
+    if (rc != HT_OK) return fail(rc);
+  }
+  // ---- parameter update (Alg. 1 lines 20-21)
+  R.tm.begin(&R.st->t_update_ms);
+  for (int l = 0; l < L; ++l) {
+    int rc = ht_sgd(ctx, ctx->stream, model->W[l], ws->dW[l], (int64_t)model->dims[l] * model->dims[l + 1], model->lr);
+    if (rc != HT_OK) return fail(rc);
+  }
+  R.tm.end();
+  {
+    hipError_t e = hipMemcpyAsync(loss_out, ws->loss_dev, 4, hipMemcpyDeviceToHost, ctx->stream);
+    if (e != hipSuccess) return fail(ht_set_err(ctx, HT_EHIP, "loss copy: %s", hipGetErrorString(e)));
+  }
+  return finish(R, stats, t0, true);
+}
+
+int ht_epoch_buffer(ht_ctx* ctx, int32_t kind, int32_t layer, ht_tensor* out) {
+  if (!ctx || !out) return HT_EINVAL;
+  EpochWs* ws = ctx->ws;
+  if (!ws) return ht_set_err(ctx, HT_ESTATE, "no epoch has run on this context");
+  const int L = (int)ws->dims.size() - 1;
+  switch (kind) {
+    case HT_BUF_H:
+      if (layer < 1 || layer > L) return ht_set_err(ctx, HT_EINVAL, "layer out of range");
+      *out = ws->h[layer];
+      return HT_OK;
+    case HT_BUF_A:
+      if (layer < 0 || layer >= L) return ht_set_err(ctx, HT_EINVAL, "layer out of range");
+      *out = ws->a[layer];
+      return HT_OK;
+    case HT_BUF_GH:
+      if (layer < 1 || layer > L) return ht_set_err(ctx, HT_EINVAL, "layer out of range");
+      *out = ws->gh[layer];
+      return HT_OK;
+    case HT_BUF_DW:
+      if (layer < 0 || layer >= L) return ht_set_err(ctx, HT_EINVAL, "layer out of range");
+      out->ptr = ws->dW[layer];
+      out->rows = ws->dims[layer];
+      out->cols = ws->dims[layer + 1];
+      out->ld = ws->dims[layer + 1];
+      out->loc = HT_LOC_DEVICE;
+      return HT_OK;
+    default:
+      return ht_set_err(ctx, HT_EINVAL, "unknown buffer kind %d", kind);
+  }
+}
+
+int ht_tensor_to_host(ht_ctx* ctx, const ht_tensor* t, float* dst) {
+  if (!ctx || !t || !dst) return HT_EINVAL;
+  if (!t->ptr || t->rows < 0 || t->cols <= 0 || t->ld < t->cols) return ht_set_err(ctx, HT_ESHAPE, "bad tensor");
+  HT_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  if (t->rows == 0) return HT_OK;
+  HT_HIP(ctx, hipMemcpy2D(dst, (size_t)t->cols * 4, t->ptr, (size_t)t->ld * 4, (size_t)t->cols * 4, (size_t)t->rows,
+                          t->loc == HT_LOC_DEVICE ? hipMemcpyDeviceToHost : hipMemcpyHostToHost));
+  return HT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,669 @@
+// ht_partition: edge list -> CSC by destination -> contiguous chunks -> per
+// chunk dedup remap (unique sorted sources, local indices), by-source grouping
+// for the backward pass, reuse / load split between adjacent chunks, in-place
+// buffer positions, aggregation work items.  All on the GPU.
+//
+// Sec. 4.1 (chunks = destination ranges with all in-edges), Sec. 5.1 step 2
+// (N_j ^ N_{j-1} reused, N_j \ N_{j-1} loaded), Sec. 5.3 (V_ori, V_+ru),
+// Sec. 6 (same buffer position for duplicated vertices of adjacent chunks;
+// loaded rows take freed positions; topology rewritten to buffer positions).
+#include <algorithm>
+
+#include "ht_internal.h"
+
+namespace {
+
+constexpr int TB = 256;
+inline unsigned nblk(int64_t n, int tb = TB) { return (unsigned)((n + tb - 1) / tb); }
+
+__global__ void k_check_ids(const int32_t* __restrict__ src, const int32_t* __restrict__ dst, int64_t E, int64_t V,
+                            int32_t* __restrict__ flag) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= E) return;
+  int32_t u = src[i], v = dst[i];
+  if (u < 0 || v < 0 || u >= V || v >= V) *flag = 1;
+}
+
+__global__ void k_pack_keys(const int32_t* __restrict__ src, const int32_t* __restrict__ dst, int64_t E, int64_t V,
+                            int bitsV, int self_loops, uint64_t* __restrict__ keys) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t n = E + (self_loops ? V : 0);
+  if (i >= n) return;
+  uint64_t u, v;
+  if (i < E) {
+    u = (uint64_t)(uint32_t)src[i];
+    v = (uint64_t)(uint32_t)dst[i];
+  } else {
+    u = v = (uint64_t)(i - E);
+  }
+  keys[i] = (v << bitsV) | u;
+}
+
+__global__ void k_low_bits(const uint64_t* __restrict__ keys, int64_t n, uint64_t mask, int32_t* __restrict__ out) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = (int32_t)(keys[i] & mask);
+}
+
+// keys sorted by row = key >> shift; ptr[q] = first index whose row >= q, ptr[nrows] = n.
+__global__ void k_boundaries(const uint64_t* __restrict__ keys, int64_t n, int shift, int64_t nrows,
+                             int64_t* __restrict__ ptr) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const int64_t r = (int64_t)(keys[i] >> shift);
+  const int64_t rp = i > 0 ? (int64_t)(keys[i - 1] >> shift) : -1;
+  for (int64_t q = rp + 1; q <= r; ++q) ptr[q] = i;
+  if (i == n - 1)
+    for (int64_t q = r + 1; q <= nrows; ++q) ptr[q] = n;
+}
+
+__global__ void k_norm(const int64_t* __restrict__ indptr, int64_t V, float* __restrict__ s) {
+  int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (v >= V) return;
+  const int64_t D = indptr[v + 1] - indptr[v];
+  s[v] = D > 0 ? (float)(1.0 / sqrt((double)D)) : 0.f;
+}
+
+// b[j] = min{ v in [0, V] : indptr[v] >= target[j] }
+__global__ void k_bounds(const int64_t* __restrict__ indptr, int64_t V, const int64_t* __restrict__ target, int n,
+                         int64_t* __restrict__ b) {
+  int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= n) return;
+  const int64_t t = target[j];
+  int64_t lo = 0, hi = V;  // indptr[V] >= t always
+  while (lo < hi) {
+    int64_t mid = (lo + hi) >> 1;
+    if (indptr[mid] >= t) hi = mid; else lo = mid + 1;
+  }
+  b[j] = lo;
+}
+
+__global__ void k_mark(const int32_t* __restrict__ col, int64_t nnz, uint32_t* bm32) {
+  int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= nnz) return;
+  const uint32_t u = (uint32_t)col[t];
+  const uint32_t bit = 1u << (u & 31);
+  if (!(bm32[u >> 5] & bit)) atomicOr(&bm32[u >> 5], bit);
+}
+
+// totals[0] += popc(cur), totals[1] += popc(cur & prev)
+__global__ void k_popc2(const uint64_t* __restrict__ cur, const uint64_t* __restrict__ prev, int64_t nw,
+                        unsigned long long* __restrict__ totals) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  unsigned long long a = 0, b = 0;
+  if (i < nw) {
+    a = __popcll(cur[i]);
+    b = __popcll(cur[i] & prev[i]);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    a += __shfl_down(a, o, 64);
+    b += __shfl_down(b, o, 64);
+  }
+  if ((threadIdx.x & 63) == 0) {
+    if (a) atomicAdd(&totals[0], a);
+    if (b) atomicAdd(&totals[1], b);
+  }
+}
+
+// op 0: a & b   1: a & ~b
+__global__ void k_bm_op(const uint64_t* __restrict__ a, const uint64_t* __restrict__ b, int64_t nw, int op,
+                        uint64_t* __restrict__ out) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < nw) out[i] = op == 0 ? (a[i] & b[i]) : (a[i] & ~b[i]);
+}
+
+// rank of each edge's source among the set bits = its position in N_j
+__global__ void k_remap(const int32_t* __restrict__ col, int64_t nnz, const uint64_t* __restrict__ bm,
+                        const int64_t* __restrict__ pref, int32_t* __restrict__ col_local) {
+  int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= nnz) return;
+  const uint32_t u = (uint32_t)col[t];
+  const uint64_t w = bm[u >> 6];
+  const uint64_t below = (u & 63) ? (w & (~0ull >> (64 - (u & 63)))) : 0ull;
+  col_local[t] = (int32_t)(pref[u >> 6] + __popcll(below));
+}
+
+// key = (local source << 32) | local destination, one thread per edge
+__global__ void k_csr_keys(const int64_t* __restrict__ indptr, int64_t dst0, int64_t dst1, int64_t e0, int64_t nnz,
+                           const int32_t* __restrict__ col_local, uint64_t* __restrict__ keys) {
+  int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= nnz) return;
+  const int64_t e = e0 + t;
+  int64_t lo = dst0, hi = dst1;  // find the last v with indptr[v] <= e
+  while (hi - lo > 1) {
+    int64_t mid = (lo + hi) >> 1;
+    if (indptr[mid] <= e) lo = mid; else hi = mid;
+  }
+  keys[t] = ((uint64_t)(uint32_t)col_local[t] << 32) | (uint64_t)(uint32_t)(lo - dst0);
+}
+
+// leave list of the previous chunk: remember the position, free it
+__global__ void k_evict(const int32_t* __restrict__ leave, int64_t n, int32_t* __restrict__ vslot,
+                        uint32_t* freebm32, int32_t* __restrict__ leave_slot) {
+  int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (k >= n) return;
+  const int32_t u = leave[k];
+  const int32_t sl = vslot[u];
+  leave_slot[k] = sl;
+  vslot[u] = -1;
+  atomicOr(&freebm32[(uint32_t)sl >> 5], 1u << (sl & 31));
+}
+
+__global__ void k_assign(const int32_t* __restrict__ load, int64_t n, const int32_t* __restrict__ freelist,
+                         int32_t* __restrict__ vslot, uint32_t* freebm32, int32_t* __restrict__ load_slot) {
+  int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (k >= n) return;
+  const int32_t sl = freelist[k];
+  vslot[load[k]] = sl;
+  load_slot[k] = sl;
+  atomicAnd(&freebm32[(uint32_t)sl >> 5], ~(1u << (sl & 31)));
+}
+
+__global__ void k_lookup_slots(const int32_t* __restrict__ nbr, int64_t n, const int32_t* __restrict__ vslot,
+                               const uint64_t* __restrict__ prev_bm, int32_t* __restrict__ slot,
+                               int32_t* __restrict__ gslot) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const uint32_t u = (uint32_t)nbr[i];
+  const int32_t sl = vslot[u];
+  slot[i] = sl;
+  const bool was = (prev_bm[u >> 6] >> (u & 63)) & 1ull;
+  gslot[i] = was ? sl : (int32_t)((uint32_t)sl | 0x80000000u);
+}
+
+__global__ void k_map_i32(const int32_t* __restrict__ idx, int64_t n, const int32_t* __restrict__ table,
+                          int32_t* __restrict__ out) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = table[idx[i]];
+}
+
+__global__ void k_items_count(const int64_t* __restrict__ ptr, int64_t nrows, int32_t* __restrict__ nseg,
+                              int32_t* __restrict__ npart, int32_t* __restrict__ isfix) {
+  int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= nrows) return;
+  const int64_t len = ptr[r + 1] - ptr[r];
+  const int32_t k = len <= HT_SEG ? 1 : (int32_t)((len + HT_SEG - 1) / HT_SEG);
+  nseg[r] = k;
+  npart[r] = k > 1 ? k : 0;
+  isfix[r] = k > 1 ? 1 : 0;
+}
+
+__global__ void k_items_fill(const int64_t* __restrict__ ptr, int64_t ptr0, int64_t nrows,
+                             const int64_t* __restrict__ it_base, const int64_t* __restrict__ part_base,
+                             const int64_t* __restrict__ fix_base, int32_t* __restrict__ it_row,
+                             int64_t* __restrict__ it_e0, int32_t* __restrict__ it_len, int32_t* __restrict__ it_part,
+                             int32_t* __restrict__ fx_row, int32_t* __restrict__ fx_part0,
+                             int32_t* __restrict__ fx_nseg) {
+  int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= nrows) return;
+  const int64_t b = ptr[r] - ptr0, len = ptr[r + 1] - ptr[r];
+  const int64_t t0 = it_base[r];
+  const int32_t k = (int32_t)(it_base[r + 1] - t0);
+  const int64_t p0 = part_base[r];
+  for (int32_t q = 0; q < k; ++q) {
+    it_row[t0 + q] = (int32_t)r;
+    it_e0[t0 + q] = b + (int64_t)q * HT_SEG;
+    const int64_t rem = len - (int64_t)q * HT_SEG;
+    it_len[t0 + q] = (int32_t)(rem < HT_SEG ? rem : HT_SEG);
+    it_part[t0 + q] = k > 1 ? (int32_t)(p0 + q) : -1;
+  }
+  if (k > 1) {
+    const int64_t f = fix_base[r];
+    fx_row[f] = (int32_t)r;
+    fx_part0[f] = (int32_t)p0;
+    fx_nseg[f] = k;
+  }
+}
+
+int bits_for(int64_t n) {  // bits needed for values 0..n-1 (at least 1)
+  int b = 1;
+  while (((int64_t)1 << b) < n) ++b;
+  return b;
+}
+
+struct ItemTmp {
+  DevArr<int32_t> nseg, npart, isfix;
+  DevArr<int64_t> it_base, part_base, fix_base;
+  int alloc(ht_ctx* ctx, int64_t maxrows) {
+    HT_TRY(nseg.alloc(ctx, maxrows));
+    HT_TRY(npart.alloc(ctx, maxrows));
+    HT_TRY(isfix.alloc(ctx, maxrows));
+    HT_TRY(it_base.alloc(ctx, maxrows + 1));
+    HT_TRY(part_base.alloc(ctx, maxrows + 1));
+    HT_TRY(fix_base.alloc(ctx, maxrows + 1));
+    return HT_OK;
+  }
+};
+
+// ptr: device offsets of nrows+1 entries; ptr0: value to subtract so item edges are chunk-relative.
+int build_items(ht_ctx* ctx, ItemTmp& t, const int64_t* ptr, int64_t ptr0, int64_t nrows, ItemSet* out) {
+  out->n_items = out->n_part = out->n_fix = 0;
+  if (nrows == 0) return HT_OK;
+  hipStream_t st = ctx->stream;
+  k_items_count<<<nblk(nrows), TB, 0, st>>>(ptr, nrows, t.nseg.p, t.npart.p, t.isfix.p);
+  HT_LAUNCH_CHECK(ctx);
+  HT_TRY(ht_scan_i32(ctx, t.nseg.p, t.it_base.p, nrows, true));
+  HT_TRY(ht_scan_i32(ctx, t.npart.p, t.part_base.p, nrows, true));
+  HT_TRY(ht_scan_i32(ctx, t.isfix.p, t.fix_base.p, nrows, true));
+  int64_t tot[3];
+  HT_HIP(ctx, hipMemcpyAsync(&tot[0], t.it_base.p + nrows, 8, hipMemcpyDeviceToHost, st));
+  HT_HIP(ctx, hipMemcpyAsync(&tot[1], t.part_base.p + nrows, 8, hipMemcpyDeviceToHost, st));
+  HT_HIP(ctx, hipMemcpyAsync(&tot[2], t.fix_base.p + nrows, 8, hipMemcpyDeviceToHost, st));
+  HT_HIP(ctx, hipStreamSynchronize(st));
+  out->n_items = tot[0];
+  out->n_part = tot[1];
+  out->n_fix = tot[2];
+  // one allocation: e0 (8 B) first, then the 4-byte arrays
+  const size_t ni = (size_t)tot[0], nf = (size_t)tot[2];
+  const size_t bytes = ni * 8 + ni * 4 * 3 + nf * 4 * 3;
+  HT_TRY(out->blob.alloc(ctx, bytes));
+  char* p = out->blob.p;
+  out->e0 = (int64_t*)p; p += ni * 8;
+  out->row = (int32_t*)p; p += ni * 4;
+  out->len = (int32_t*)p; p += ni * 4;
+  out->part = (int32_t*)p; p += ni * 4;
+  out->fx_row = (int32_t*)p; p += nf * 4;
+  out->fx_part0 = (int32_t*)p; p += nf * 4;
+  out->fx_nseg = (int32_t*)p;
+  k_items_fill<<<nblk(nrows), TB, 0, st>>>(ptr, ptr0, nrows, t.it_base.p, t.part_base.p, t.fix_base.p, out->row,
+                                          out->e0, out->len, out->part, out->fx_row, out->fx_part0, out->fx_nseg);
+  HT_LAUNCH_CHECK(ctx);
+  return HT_OK;
+}
+
+int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, const int32_t* dst_in, int32_t n,
+                   const ht_part_opts* opts, ht_graph* g) {
+  hipStream_t st = ctx->stream;
+  const int self_loops = opts ? (opts->add_self_loops != 0) : 1;
+  const int mode = opts ? opts->balance_mode : HT_BALANCE_EDGES;
+  const int ptr_loc = opts ? opts->ptr_loc : HT_PTR_DEVICE;
+  const int64_t Ep = E + (self_loops ? V : 0);
+  g->ctx = ctx;
+  g->V = V;
+  g->Ep = Ep;
+  g->n = n;
+  g->add_self_loops = self_loops;
+
+  // ---- edge list on the device
+  DevArr<int32_t> src_copy, dst_copy;
+  const int32_t* src = src_in;
+  const int32_t* dst = dst_in;
+  if (ptr_loc == HT_PTR_HOST && E > 0) {
+    HT_TRY(src_copy.alloc(ctx, E));
+    HT_TRY(dst_copy.alloc(ctx, E));
+    HT_HIP(ctx, hipMemcpyAsync(src_copy.p, src_in, E * 4, hipMemcpyHostToDevice, st));
+    HT_HIP(ctx, hipMemcpyAsync(dst_copy.p, dst_in, E * 4, hipMemcpyHostToDevice, st));
+    src = src_copy.p;
+    dst = dst_copy.p;
+  }
+  if (E > 0) {
+    DevArr<int32_t> flag;
+    HT_TRY(flag.alloc(ctx, 1));
+    HT_HIP(ctx, hipMemsetAsync(flag.p, 0, 4, st));
+    k_check_ids<<<nblk(E), TB, 0, st>>>(src, dst, E, V, flag.p);
+    HT_LAUNCH_CHECK(ctx);
+    int32_t bad = 0;
+    HT_HIP(ctx, hipMemcpyAsync(&bad, flag.p, 4, hipMemcpyDeviceToHost, st));
+    HT_HIP(ctx, hipStreamSynchronize(st));
+    if (bad) return ht_set_err(ctx, HT_EINVAL, "ht_partition: a vertex id is outside [0, V)");
+  }
+
+  // ---- CSC by (destination, source)
+  const int bitsV = bits_for(V);
+  DevArr<uint64_t> keysA, keysB;
+  HT_TRY(keysA.alloc(ctx, (size_t)(Ep > 0 ? Ep : 1)));
+  HT_TRY(keysB.alloc(ctx, (size_t)(Ep > 0 ? Ep : 1)));
+  HT_TRY(g->indptr.alloc(ctx, (size_t)V + 1));
+  HT_TRY(g->col.alloc(ctx, (size_t)(Ep > 0 ? Ep : 1)));
+  HT_TRY(g->s.alloc(ctx, (size_t)V));
+  HT_HIP(ctx, hipMemsetAsync(g->indptr.p, 0, (V + 1) * 8, st));
+  if (Ep > 0) {
+    k_pack_keys<<<nblk(Ep), TB, 0, st>>>(src, dst, E, V, bitsV, self_loops, keysA.p);
+    HT_LAUNCH_CHECK(ctx);
+    uint64_t* sorted = nullptr;
+    HT_TRY(ht_radix_sort_u64(ctx, keysA.p, keysB.p, Ep, 0, 2 * bitsV, &sorted));
+    k_low_bits<<<nblk(Ep), TB, 0, st>>>(sorted, Ep, ((uint64_t)1 << bitsV) - 1, g->col.p);
+    HT_LAUNCH_CHECK(ctx);
+    k_boundaries<<<nblk(Ep), TB, 0, st>>>(sorted, Ep, bitsV, V, g->indptr.p);
+    HT_LAUNCH_CHECK(ctx);
+  }
+  k_norm<<<nblk(V), TB, 0, st>>>(g->indptr.p, V, g->s.p);
+  HT_LAUNCH_CHECK(ctx);
+  src_copy.release();
+  dst_copy.release();
+
+  // ---- chunk boundaries
+  g->bounds.assign(n + 1, 0);
+  g->bounds[n] = V;
+  if (mode == HT_BALANCE_VERTICES) {
+    for (int j = 1; j < n; ++j) g->bounds[j] = (int64_t)(((__int128)j * V) / n);
+  } else if (n > 1) {
+    std::vector<int64_t> target(n - 1);
+    for (int j = 1; j < n; ++j) target[j - 1] = (int64_t)((((__int128)j * Ep) + n - 1) / n);
+    DevArr<int64_t> dt, db;
+    HT_TRY(dt.alloc(ctx, n - 1));
+    HT_TRY(db.alloc(ctx, n - 1));
+    HT_HIP(ctx, hipMemcpyAsync(dt.p, target.data(), (n - 1) * 8, hipMemcpyHostToDevice, st));
+    k_bounds<<<nblk(n - 1), TB, 0, st>>>(g->indptr.p, V, dt.p, n - 1, db.p);
+    HT_LAUNCH_CHECK(ctx);
+    HT_HIP(ctx, hipMemcpyAsync(&g->bounds[1], db.p, (n - 1) * 8, hipMemcpyDeviceToHost, st));
+    HT_HIP(ctx, hipStreamSynchronize(st));
+  }
+  std::vector<int64_t> eoff(n + 1);
+  for (int j = 0; j <= n; ++j)  // n is small: one 8-byte copy per boundary
+    HT_HIP(ctx, hipMemcpyAsync(&eoff[j], g->indptr.p + g->bounds[j], 8, hipMemcpyDeviceToHost, st));
+  HT_HIP(ctx, hipStreamSynchronize(st));
+  g->chunks.clear();
+  g->chunks.resize(n);
+  for (int j = 0; j < n; ++j) {
+    ChunkMeta& c = g->chunks[j];
+    c.dst0 = g->bounds[j];
+    c.dst1 = g->bounds[j + 1];
+    c.e0 = eoff[j];
+    c.nnz = eoff[j + 1] - eoff[j];
+    g->max_ndst = std::max(g->max_ndst, c.dst1 - c.dst0);
+    g->max_nnz = std::max(g->max_nnz, c.nnz);
+  }
+
+  // ---- pass 1: |N_j| and |N_j ^ N_{j-1}| for every chunk
+  const int64_t nw = ceil_div64(V, 64);
+  DevArr<uint64_t> bmA, bmB, bmT;
+  HT_TRY(bmA.alloc(ctx, nw));
+  HT_TRY(bmB.alloc(ctx, nw));
+  HT_TRY(bmT.alloc(ctx, nw));
+  DevArr<unsigned long long> totals;
+  HT_TRY(totals.alloc(ctx, (size_t)2 * n));
+  HT_HIP(ctx, hipMemsetAsync(totals.p, 0, (size_t)2 * n * 8, st));
+  uint64_t* cur = bmA.p;
+  uint64_t* prev = bmB.p;
+  HT_HIP(ctx, hipMemsetAsync(prev, 0, nw * 8, st));
+  for (int j = 0; j < n; ++j) {
+    const ChunkMeta& c = g->chunks[j];
+    HT_HIP(ctx, hipMemsetAsync(cur, 0, nw * 8, st));
+    if (c.nnz > 0) {
+      k_mark<<<nblk(c.nnz), TB, 0, st>>>(g->col.p + c.e0, c.nnz, (uint32_t*)cur);
+      HT_LAUNCH_CHECK(ctx);
+    }
+    k_popc2<<<nblk(nw), TB, 0, st>>>(cur, prev, nw, totals.p + 2 * j);
+    HT_LAUNCH_CHECK(ctx);
+    std::swap(cur, prev);
+  }
+  std::vector<unsigned long long> htot(2 * n);
+  HT_HIP(ctx, hipMemcpyAsync(htot.data(), totals.p, (size_t)2 * n * 8, hipMemcpyDeviceToHost, st));
+  HT_HIP(ctx, hipStreamSynchronize(st));
+  g->v_ori = g->v_ru = 0;
+  for (int j = 0; j < n; ++j) {
+    ChunkMeta& c = g->chunks[j];
+    c.nsrc = (int64_t)htot[2 * j];
+    c.n_reuse = (int64_t)htot[2 * j + 1];
+    c.n_load = c.nsrc - c.n_reuse;
+    c.nbr_off = g->v_ori;
+    c.sptr_off = g->v_ori + j;
+    c.reuse_off = g->v_ori - g->v_ru;
+    c.load_off = g->v_ru;
+    g->v_ori += c.nsrc;
+    g->v_ru += c.n_load;
+    g->max_nsrc = std::max(g->max_nsrc, c.nsrc);
+  }
+  {
+    int64_t off = 0;
+    for (int j = 0; j < n; ++j) {
+      ChunkMeta& c = g->chunks[j];
+      c.n_leave = (j + 1 < n) ? c.nsrc - g->chunks[j + 1].n_reuse : c.nsrc;
+      c.leave_off = off;
+      off += c.n_leave;
+    }
+  }
+  int64_t C = opts ? opts->cache_rows : 0;
+  if (C == 0) C = g->max_nsrc;
+  if (C < g->max_nsrc)
+    return ht_set_err(ctx, HT_EINVAL, "ht_partition: cache_rows %lld < max_j |N_j| = %lld", (long long)C,
+                      (long long)g->max_nsrc);
+  if (C < 1) C = 1;
+  g->cache_rows = C;
+
+  // ---- arenas
+  const size_t vo = (size_t)std::max<int64_t>(g->v_ori, 1), vr = (size_t)std::max<int64_t>(g->v_ru, 1);
+  HT_TRY(g->nbr.alloc(ctx, vo));
+  HT_TRY(g->slot.alloc(ctx, vo));
+  HT_TRY(g->gslot.alloc(ctx, vo));
+  HT_TRY(g->sptr.alloc(ctx, vo + n));
+  HT_TRY(g->reuse.alloc(ctx, (size_t)std::max<int64_t>(g->v_ori - g->v_ru, 1)));
+  HT_TRY(g->load.alloc(ctx, vr));
+  HT_TRY(g->load_slot.alloc(ctx, vr));
+  HT_TRY(g->leave.alloc(ctx, vr));
+  HT_TRY(g->leave_slot.alloc(ctx, vr));
+  const size_t ep = (size_t)std::max<int64_t>(Ep, 1);
+  HT_TRY(g->col_local.alloc(ctx, ep));
+  HT_TRY(g->col_slot.alloc(ctx, ep));
+  HT_TRY(g->sdst.alloc(ctx, ep));
+
+  // ---- pass 2 temporaries
+  const int64_t nwC = ceil_div64(C, 64);
+  const int64_t nwmax = std::max(nw, nwC);
+  DevArr<int32_t> cnt_tmp, vslot, freelist;
+  DevArr<int64_t> pref;
+  DevArr<uint64_t> freebm;
+  HT_TRY(cnt_tmp.alloc(ctx, nwmax));
+  HT_TRY(pref.alloc(ctx, nwmax + 1));
+  HT_TRY(vslot.alloc(ctx, (size_t)V));
+  HT_TRY(freelist.alloc(ctx, (size_t)C));
+  HT_TRY(freebm.alloc(ctx, nwC));
+  HT_HIP(ctx, hipMemsetAsync(vslot.p, 0xFF, (size_t)V * 4, st));
+  {
+    std::vector<uint64_t> fb(nwC, ~0ull);
+    if (C % 64) fb[nwC - 1] = (~0ull) >> (64 - (C % 64));
+    HT_HIP(ctx, hipMemcpyAsync(freebm.p, fb.data(), nwC * 8, hipMemcpyHostToDevice, st));
+    HT_HIP(ctx, hipStreamSynchronize(st));
+  }
+  ItemTmp itmp;
+  HT_TRY(itmp.alloc(ctx, std::max<int64_t>(std::max(g->max_ndst, g->max_nsrc), 1)));
+
+  cur = bmA.p;
+  prev = bmB.p;
+  HT_HIP(ctx, hipMemsetAsync(prev, 0, nw * 8, st));
+  for (int j = 0; j < n; ++j) {
+    ChunkMeta& c = g->chunks[j];
+    int32_t* nbr_j = g->nbr.p + c.nbr_off;
+    int32_t* slot_j = g->slot.p + c.nbr_off;
+    int32_t* gslot_j = g->gslot.p + c.nbr_off;
+    int64_t* sptr_j = g->sptr.p + c.sptr_off;
+    // unique sorted sources and local indices
+    HT_HIP(ctx, hipMemsetAsync(cur, 0, nw * 8, st));
+    if (c.nnz > 0) {
+      k_mark<<<nblk(c.nnz), TB, 0, st>>>(g->col.p + c.e0, c.nnz, (uint32_t*)cur);
+      HT_LAUNCH_CHECK(ctx);
+    }
+    HT_TRY(ht_bitmap_prefix(ctx, cur, nw, cnt_tmp.p, pref.p));
+    HT_TRY(ht_bitmap_expand(ctx, cur, nw, pref.p, nbr_j));
+    if (c.nnz > 0) {
+      k_remap<<<nblk(c.nnz), TB, 0, st>>>(g->col.p + c.e0, c.nnz, cur, pref.p, g->col_local.p + c.e0);
+      HT_LAUNCH_CHECK(ctx);
+    }
+    // reuse / load / leave(previous chunk)
+    k_bm_op<<<nblk(nw), TB, 0, st>>>(cur, prev, nw, 0, bmT.p);
+    HT_LAUNCH_CHECK(ctx);
+    HT_TRY(ht_bitmap_prefix(ctx, bmT.p, nw, cnt_tmp.p, pref.p));
+    HT_TRY(ht_bitmap_expand(ctx, bmT.p, nw, pref.p, g->reuse.p + c.reuse_off));
+    k_bm_op<<<nblk(nw), TB, 0, st>>>(cur, prev, nw, 1, bmT.p);
+    HT_LAUNCH_CHECK(ctx);
+    HT_TRY(ht_bitmap_prefix(ctx, bmT.p, nw, cnt_tmp.p, pref.p));
+    HT_TRY(ht_bitmap_expand(ctx, bmT.p, nw, pref.p, g->load.p + c.load_off));
+    if (j > 0) {
+      ChunkMeta& pc = g->chunks[j - 1];
+      k_bm_op<<<nblk(nw), TB, 0, st>>>(prev, cur, nw, 1, bmT.p);
+      HT_LAUNCH_CHECK(ctx);
+      HT_TRY(ht_bitmap_prefix(ctx, bmT.p, nw, cnt_tmp.p, pref.p));
+      HT_TRY(ht_bitmap_expand(ctx, bmT.p, nw, pref.p, g->leave.p + pc.leave_off));
+      if (pc.n_leave > 0) {
+        k_evict<<<nblk(pc.n_leave), TB, 0, st>>>(g->leave.p + pc.leave_off, pc.n_leave, vslot.p,
+                                                 (uint32_t*)freebm.p, g->leave_slot.p + pc.leave_off);
+        HT_LAUNCH_CHECK(ctx);
+      }
+    }
+    // positions: loaded rows take the lowest free positions
+    if (c.n_load > 0) {
+      HT_TRY(ht_bitmap_prefix(ctx, freebm.p, nwC, cnt_tmp.p, pref.p));
+      HT_TRY(ht_bitmap_expand(ctx, freebm.p, nwC, pref.p, freelist.p));
+      k_assign<<<nblk(c.n_load), TB, 0, st>>>(g->load.p + c.load_off, c.n_load, freelist.p, vslot.p,
+                                              (uint32_t*)freebm.p, g->load_slot.p + c.load_off);
+      HT_LAUNCH_CHECK(ctx);
+    }
+    if (c.nsrc > 0) {
+      k_lookup_slots<<<nblk(c.nsrc), TB, 0, st>>>(nbr_j, c.nsrc, vslot.p, prev, slot_j, gslot_j);
+      HT_LAUNCH_CHECK(ctx);
+    }
+    if (c.nnz > 0) {
+      k_map_i32<<<nblk(c.nnz), TB, 0, st>>>(g->col_local.p + c.e0, c.nnz, slot_j, g->col_slot.p + c.e0);
+      HT_LAUNCH_CHECK(ctx);
+    }
+    // the same edges grouped by local source, destinations ascending inside a source
+    HT_HIP(ctx, hipMemsetAsync(sptr_j, 0, (c.nsrc + 1) * 8, st));
+    if (c.nnz > 0) {
+      k_csr_keys<<<nblk(c.nnz), TB, 0, st>>>(g->indptr.p, c.dst0, c.dst1, c.e0, c.nnz, g->col_local.p + c.e0,
+                                             keysA.p);
+      HT_LAUNCH_CHECK(ctx);
+      uint64_t* sorted = nullptr;
+      HT_TRY(ht_radix_sort_u64(ctx, keysA.p, keysB.p, c.nnz, 32, 32 + bits_for(c.nsrc), &sorted));
+      k_low_bits<<<nblk(c.nnz), TB, 0, st>>>(sorted, c.nnz, 0xFFFFFFFFull, g->sdst.p + c.e0);
+      HT_LAUNCH_CHECK(ctx);
+      k_boundaries<<<nblk(c.nnz), TB, 0, st>>>(sorted, c.nnz, 32, c.nsrc, sptr_j);
+      HT_LAUNCH_CHECK(ctx);
+    }
+    // work items of both directions
+    HT_TRY(build_items(ctx, itmp, g->indptr.p + c.dst0, c.e0, c.dst1 - c.dst0, &c.fwd));
+    HT_TRY(build_items(ctx, itmp, sptr_j, 0, c.nsrc, &c.bwd));
+    g->max_fpart = std::max(g->max_fpart, c.fwd.n_part);
+    g->max_bpart = std::max(g->max_bpart, c.bwd.n_part);
+    std::swap(cur, prev);
+  }
+  // the last chunk's rows all leave at the end of a pass
+  if (n > 0) {
+    ChunkMeta& lc = g->chunks[n - 1];
+    if (lc.nsrc > 0) {
+      HT_HIP(ctx, hipMemcpyAsync(g->leave.p + lc.leave_off, g->nbr.p + lc.nbr_off, lc.nsrc * 4,
+                                 hipMemcpyDeviceToDevice, st));
+      HT_HIP(ctx, hipMemcpyAsync(g->leave_slot.p + lc.leave_off, g->slot.p + lc.nbr_off, lc.nsrc * 4,
+                                 hipMemcpyDeviceToDevice, st));
+    }
+  }
+  HT_HIP(ctx, hipStreamSynchronize(st));
+  return HT_OK;
+}
+
+template <typename T>
+int d2h(ht_ctx* ctx, T* dst, const T* src, int64_t n) {
+  if (!dst || n <= 0) return HT_OK;
+  HT_HIP(ctx, hipMemcpy(dst, src, (size_t)n * sizeof(T), hipMemcpyDeviceToHost));
+  return HT_OK;
+}
+
+}  // namespace
+
+int64_t ht_graph::hbm_bytes() const {
+  int64_t b = indptr.bytes() + col.bytes() + s.bytes() + nbr.bytes() + col_local.bytes() + col_slot.bytes() +
+              sptr.bytes() + sdst.bytes() + slot.bytes() + gslot.bytes() + reuse.bytes() + load.bytes() +
+              load_slot.bytes() + leave.bytes() + leave_slot.bytes();
+  for (const ChunkMeta& c : chunks) b += c.fwd.blob.bytes() + c.bwd.blob.bytes();
+  return b;
+}
+
+extern "C" {
+
+int ht_partition(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src, const int32_t* dst, int32_t n_chunks,
+                 const ht_part_opts* opts, ht_graph** out) {
+  if (!ctx) return HT_EINVAL;
+  if (!out) return ht_set_err(ctx, HT_EINVAL, "ht_partition: out is null");
+  *out = nullptr;
+  if (V <= 0 || V >= ((int64_t)1 << 31)) return ht_set_err(ctx, HT_EINVAL, "ht_partition: V must be in [1, 2^31)");
+  if (E < 0 || (E > 0 && (!src || !dst))) return ht_set_err(ctx, HT_EINVAL, "ht_partition: bad edge list");
+  if (n_chunks < 1) return ht_set_err(ctx, HT_EINVAL, "ht_partition: n_chunks must be >= 1");
+  if (opts && (opts->balance_mode < 0 || opts->balance_mode > 1 || opts->ptr_loc < 0 || opts->ptr_loc > 1 ||
+               opts->cache_rows < 0))
+    return ht_set_err(ctx, HT_EINVAL, "ht_partition: bad options");
+  HT_HIP(ctx, hipSetDevice(ctx->device));
+  auto t0 = std::chrono::steady_clock::now();
+  ht_graph* g = new (std::nothrow) ht_graph();
+  if (!g) return ht_set_err(ctx, HT_ENOMEM, "ht_partition: host allocation failed");
+  int rc = partition_impl(ctx, V, E, src, dst, n_chunks, opts, g);
+  if (rc != HT_OK) {
+    (void)hipStreamSynchronize(ctx->stream);
+    delete g;
+    return rc;
+  }
+  g->partition_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+  *out = g;
+  return HT_OK;
+}
+
+int ht_graph_destroy(ht_graph* g) {
+  if (!g) return HT_EINVAL;
+  if (g->ctx) (void)hipStreamSynchronize(g->ctx->stream);
+  delete g;
+  return HT_OK;
+}
+
+int ht_graph_info_get(const ht_graph* g, ht_graph_info* out) {
+  if (!g || !out) return HT_EINVAL;
+  out->V = g->V;
+  out->E_stored = g->Ep;
+  out->n_chunks = g->n;
+  out->reserved = 0;
+  out->v_ori = g->v_ori;
+  out->v_ru = g->v_ru;
+  out->alpha = g->V > 0 ? (double)g->v_ori / (double)g->V : 0.0;
+  out->max_nsrc = g->max_nsrc;
+  out->max_ndst = g->max_ndst;
+  out->max_nnz = g->max_nnz;
+  out->cache_rows = g->cache_rows;
+  out->hbm_bytes = g->hbm_bytes();
+  out->partition_ms = g->partition_ms;
+  return HT_OK;
+}
+
+int ht_graph_chunk_info(const ht_graph* g, int32_t j, ht_chunk_info* out) {
+  if (!g || !out || j < 0 || j >= g->n) return HT_EINVAL;
+  const ChunkMeta& c = g->chunks[j];
+  out->dst_begin = c.dst0;
+  out->dst_end = c.dst1;
+  out->nnz = c.nnz;
+  out->n_src = c.nsrc;
+  out->n_reuse = c.n_reuse;
+  out->n_load = c.n_load;
+  return HT_OK;
+}
+
+int ht_graph_export_chunk(const ht_graph* g, int32_t j, ht_chunk_host* out) {
+  if (!g || !out || j < 0 || j >= g->n) return HT_EINVAL;
+  ht_ctx* ctx = g->ctx;
+  const ChunkMeta& c = g->chunks[j];
+  HT_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  const int64_t nd = c.dst1 - c.dst0;
+  if (out->indptr) {
+    HT_TRY(d2h(ctx, out->indptr, g->indptr.p + c.dst0, nd + 1));
+    for (int64_t i = 0; i <= nd; ++i) out->indptr[i] -= c.e0;
+  }
+  HT_TRY(d2h(ctx, out->col, g->col.p + c.e0, c.nnz));
+  HT_TRY(d2h(ctx, out->nbr, g->nbr.p + c.nbr_off, c.nsrc));
+  HT_TRY(d2h(ctx, out->col_local, g->col_local.p + c.e0, c.nnz));
+  HT_TRY(d2h(ctx, out->sptr, g->sptr.p + c.sptr_off, c.nsrc + 1));
+  HT_TRY(d2h(ctx, out->sdst, g->sdst.p + c.e0, c.nnz));
+  HT_TRY(d2h(ctx, out->reuse, g->reuse.p + c.reuse_off, c.n_reuse));
+  HT_TRY(d2h(ctx, out->load, g->load.p + c.load_off, c.n_load));
+  HT_TRY(d2h(ctx, out->slot, g->slot.p + c.nbr_off, c.nsrc));
+  return HT_OK;
+}
+
+int ht_graph_export_csc(const ht_graph* g, int64_t* indptr, int32_t* col, float* s, int64_t* bounds) {
+  if (!g) return HT_EINVAL;
+  ht_ctx* ctx = g->ctx;
+  HT_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  HT_TRY(d2h(ctx, indptr, g->indptr.p, g->V + 1));
+  HT_TRY(d2h(ctx, col, g->col.p, g->Ep));
+  HT_TRY(d2h(ctx, s, g->s.p, g->V));
+  if (bounds)
+    for (int j = 0; j <= g->n; ++j) bounds[j] = g->bounds[j];
+  return HT_OK;
+}
+
+}  // extern "C"

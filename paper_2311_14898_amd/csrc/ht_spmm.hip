@@ -1,0 +1,207 @@
+// Aggregation (Eq. 2's AGGREGATE and its backward, Sec. 4.1) and the row
+// gather / scatter kernels of the in-place neighbour buffer (Alg. 2 lines 2-3,
+// Alg. 3 line 6).
+//
+// Aggregation: a wave owns one work item (at most HT_SEG edges of one row).
+// Features run across lanes as float4; for narrow rows a wave splits into
+// lane groups that take interleaved edges and are summed in a fixed order.
+// No atomics: a row cut into several items is finished by a second kernel
+// that adds the partial sums in item order, so results are bit-reproducible.
+#include "ht_internal.h"
+
+namespace {
+
+__device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ void st4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
+__device__ __forceinline__ float4 fma4(float w, float4 v, float4 a) {
+  a.x = fmaf(w, v.x, a.x);
+  a.y = fmaf(w, v.y, a.y);
+  a.z = fmaf(w, v.z, a.z);
+  a.w = fmaf(w, v.w, a.w);
+  return a;
+}
+__device__ __forceinline__ float4 add4(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
+__device__ __forceinline__ float4 mul4(float s, float4 a) { return make_float4(s * a.x, s * a.y, s * a.z, s * a.w); }
+__device__ __forceinline__ float4 shfl_xor4(float4 v, int o) {
+  return make_float4(__shfl_xor(v.x, o, 64), __shfl_xor(v.y, o, 64), __shfl_xor(v.z, o, 64), __shfl_xor(v.w, o, 64));
+}
+
+// Final write of one output row's float4 column `c4` (in floats).
+__device__ __forceinline__ void write_out(const SpmmArgs& a, int32_t r, int c4, float4 v) {
+  const float post = a.post ? a.post[a.post_idx ? a.post_idx[r] : r] : 1.f;
+  uint32_t orow = a.out_idx ? (uint32_t)a.out_idx[r] : (uint32_t)r;
+  const bool fresh = (orow & 0x80000000u) != 0u;
+  orow &= 0x7FFFFFFFu;
+  float* p = a.out + (int64_t)orow * a.out_ld + c4;
+  v = mul4(post, v);
+  if (a.accumulate && !fresh) v = add4(ld4(p), v);
+  st4(p, v);
+}
+
+template <int LPR, int VPL>
+__global__ void __launch_bounds__(256) k_spmm_items(SpmmArgs a) {
+  constexpr int G = 64 / LPR;
+  const int lane = threadIdx.x & 63;
+  const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= a.n_items) return;
+  const int32_t r = a.it_row[t];
+  const int64_t e0 = a.it_e0[t];
+  const int32_t len = a.it_len[t];
+  const int32_t part = a.it_part[t];
+  const int sub = lane / LPR, ll = lane % LPR;
+  const int d4 = (a.d + 3) & ~3;
+
+  float4 acc[VPL];
+  bool colok[VPL];
+#pragma unroll
+  for (int j = 0; j < VPL; ++j) {
+    acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    colok[j] = (j * LPR + ll) * 4 < d4;
+  }
+  for (int32_t base = 0; base < len; base += 64) {
+    const int32_t n_here = (len - base) < 64 ? (len - base) : 64;
+    int32_t my_idx = 0;
+    float my_w = 0.f;
+    if (lane < n_here) {
+      my_idx = a.idx[e0 + base + lane];
+      my_w = a.ew ? a.ew[my_idx] : 1.f;
+    }
+    for (int32_t k = 0; k < n_here; k += G) {
+      int32_t c;
+      float w;
+      if (G == 1) {
+        c = __builtin_amdgcn_readlane(my_idx, k);
+        w = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_w), k));
+      } else {
+        const int kk = k + sub;           // lanes past the end carry weight 0 and row 0
+        c = __shfl(my_idx, kk & 63, 64);
+        w = __shfl(my_w, kk & 63, 64);
+        if (kk >= n_here) { c = 0; w = 0.f; }
+      }
+      const float* row = a.src + (int64_t)c * a.src_ld;
+#pragma unroll
+      for (int j = 0; j < VPL; ++j)
+        if (colok[j]) acc[j] = fma4(w, ld4(row + (j * LPR + ll) * 4), acc[j]);
+    }
+  }
+  if (G > 1) {
+#pragma unroll
+    for (int o = LPR; o < 64; o <<= 1)
+#pragma unroll
+      for (int j = 0; j < VPL; ++j) acc[j] = add4(acc[j], shfl_xor4(acc[j], o));
+    if (sub != 0) return;
+  }
+#pragma unroll
+  for (int j = 0; j < VPL; ++j) {
+    if (!colok[j]) continue;
+    const int c4 = (j * LPR + ll) * 4;
+    if (part >= 0)
+      st4(a.partial + (int64_t)part * a.out_ld + c4, acc[j]);
+    else
+      write_out(a, r, c4, acc[j]);
+  }
+}
+
+// Rows cut into several items: add their partial sums in item order.
+__global__ void __launch_bounds__(256) k_spmm_fix(SpmmArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int64_t f = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (f >= a.n_fix) return;
+  const int32_t r = a.fx_row[f];
+  const int32_t p0 = a.fx_part0[f];
+  const int32_t ns = a.fx_nseg[f];
+  const int d4 = (a.d + 3) & ~3;
+  for (int c4 = lane * 4; c4 < d4; c4 += 256) {
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int32_t k = 0; k < ns; ++k) acc = add4(acc, ld4(a.partial + (int64_t)(p0 + k) * a.out_ld + c4));
+    write_out(a, r, c4, acc);
+  }
+}
+
+template <int LPR, int VPL>
+int launch_items(ht_ctx* ctx, hipStream_t st, const SpmmArgs& a) {
+  const unsigned blocks = (unsigned)((a.n_items + 3) / 4);
+  k_spmm_items<LPR, VPL><<<blocks, 256, 0, st>>>(a);
+  HT_LAUNCH_CHECK(ctx);
+  return HT_OK;
+}
+
+// dst[dst_idx[k]] = scale[src_idx[k]] * src[src_idx[k]]; a lane group per row.
+template <int ADD>
+__global__ void __launch_bounds__(256) k_rows(const float* __restrict__ src, int64_t src_ld,
+                                              const int32_t* __restrict__ src_idx, float* __restrict__ dst,
+                                              int64_t dst_ld, const int32_t* __restrict__ dst_idx, int64_t n_rows,
+                                              int d4, int lpr, const float* __restrict__ scale) {
+  const int tid = threadIdx.x;
+  const int rows_per_block = 256 / lpr;
+  const int64_t k = (int64_t)blockIdx.x * rows_per_block + tid / lpr;
+  if (k >= n_rows) return;
+  const int ll = tid % lpr;
+  const int64_t si = src_idx ? (int64_t)src_idx[k] : k;
+  const int64_t di = dst_idx ? (int64_t)(dst_idx[k] & 0x7FFFFFFF) : k;
+  const float sc = scale ? scale[si] : 1.f;
+  const float* sp = src + si * src_ld;
+  float* dp = dst + di * dst_ld;
+  for (int c4 = ll * 4; c4 < d4; c4 += lpr * 4) {
+    float4 v = ld4(sp + c4);
+    if (scale) v = mul4(sc, v);
+    if (ADD) v = add4(ld4(dp + c4), v);
+    st4(dp + c4, v);
+  }
+}
+
+int lanes_for(int nvec) { return nvec <= 8 ? 8 : nvec <= 16 ? 16 : nvec <= 32 ? 32 : 64; }
+
+}  // namespace
+
+int ht_spmm_launch(ht_ctx* ctx, hipStream_t st, const SpmmArgs& a0) {
+  if (a0.n_items <= 0) return HT_OK;
+  if ((a0.src_ld & 3) || (a0.out_ld & 3)) return ht_set_err(ctx, HT_ESHAPE, "aggregation: row pitch must be a multiple of 4");
+  // wide rows go in column blocks of 1024 floats
+  for (int c0 = 0; c0 < a0.d; c0 += 1024) {
+    SpmmArgs a = a0;
+    a.src = a0.src + c0;
+    a.out = a0.out + c0;
+    a.partial = a0.partial ? a0.partial + c0 : nullptr;
+    a.d = (a0.d - c0) < 1024 ? (a0.d - c0) : 1024;
+    const int nvec = (a.d + 3) / 4;
+    int rc;
+    if (nvec <= 8) rc = launch_items<8, 1>(ctx, st, a);
+    else if (nvec <= 16) rc = launch_items<16, 1>(ctx, st, a);
+    else if (nvec <= 32) rc = launch_items<32, 1>(ctx, st, a);
+    else if (nvec <= 64) rc = launch_items<64, 1>(ctx, st, a);
+    else if (nvec <= 128) rc = launch_items<64, 2>(ctx, st, a);
+    else if (nvec <= 192) rc = launch_items<64, 3>(ctx, st, a);
+    else rc = launch_items<64, 4>(ctx, st, a);
+    if (rc != HT_OK) return rc;
+    if (a.n_fix > 0) {
+      k_spmm_fix<<<(unsigned)((a.n_fix + 3) / 4), 256, 0, st>>>(a);
+      HT_LAUNCH_CHECK(ctx);
+    }
+  }
+  return HT_OK;
+}
+
+int ht_gather_rows(ht_ctx* ctx, hipStream_t st, const float* src, int64_t src_ld, const int32_t* src_idx, float* dst,
+                   int64_t dst_ld, const int32_t* dst_idx, int64_t n_rows, int32_t d, const float* scale) {
+  if (n_rows <= 0) return HT_OK;
+  const int d4 = (d + 3) & ~3;
+  const int lpr = lanes_for(d4 / 4);
+  const int rpb = 256 / lpr;
+  k_rows<0><<<(unsigned)((n_rows + rpb - 1) / rpb), 256, 0, st>>>(src, src_ld, src_idx, dst, dst_ld, dst_idx, n_rows,
+                                                                d4, lpr, scale);
+  HT_LAUNCH_CHECK(ctx);
+  return HT_OK;
+}
+
+int ht_add_rows(ht_ctx* ctx, hipStream_t st, const float* src, int64_t src_ld, const int32_t* src_idx, float* dst,
+                int64_t dst_ld, const int32_t* dst_idx, int64_t n_rows, int32_t d) {
+  if (n_rows <= 0) return HT_OK;
+  const int d4 = (d + 3) & ~3;
+  const int lpr = lanes_for(d4 / 4);
+  const int rpb = 256 / lpr;
+  k_rows<1><<<(unsigned)((n_rows + rpb - 1) / rpb), 256, 0, st>>>(src, src_ld, src_idx, dst, dst_ld, dst_idx, n_rows,
+                                                                d4, lpr, nullptr);
+  HT_LAUNCH_CHECK(ctx);
+  return HT_OK;
+}

@@ -1,0 +1,136 @@
+"""ht_epoch against the CPU oracle: loss, every activation and gradient, updated weights."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_2311_14898_amd import binding as B
+from paper_2311_14898_amd import inputs
+from tests.util import assert_close
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = B.ht_ctx_create(0)
+    yield c
+    B.ht_ctx_destroy(c)
+
+
+def run_epoch(ctx, w, src, dst, X, y, Ws, n_chunks=None, x_loc=B.HT_LOC_DEVICE, **plan):
+    g = B.ht_partition(ctx, w.V, src.cuda(), dst.cuda(), n_chunks or w.n_chunks)
+    try:
+        Xd = B.to_matrix(X, x_loc)
+        Wd = [x.clone().cuda() for x in Ws]
+        loss, st = B.ht_epoch(ctx, g, w.dims, Wd, w.lr, Xd, y.cuda(), want_stats=True, **plan)
+        L = w.n_layers
+        out = {"loss": loss, "stats": st, "W_new": [x.cpu().numpy() for x in Wd],
+               "a": [B.ht_epoch_buffer(ctx, B.HT_BUF_A, l).numpy() for l in range(L)],
+               "h": [B.ht_epoch_buffer(ctx, B.HT_BUF_H, l + 1).numpy() for l in range(L)],
+               "gh": [B.ht_epoch_buffer(ctx, B.HT_BUF_GH, l + 1).numpy() for l in range(L)],
+               "gW": [B.ht_epoch_buffer(ctx, B.HT_BUF_DW, l).numpy() for l in range(L)]}
+        return out
+    finally:
+        B.ht_graph_destroy(g)
+
+
+def oracle_epoch(w, src, dst, X, y, Ws):
+    indptr, col = orc.csc_build(w.V, src.numpy(), dst.numpy())
+    return orc.gcn_epoch(indptr, col, w.dims, X.numpy(), [x.numpy() for x in Ws], y.numpy(), lr=w.lr)
+
+
+def compare(out, ref, L):
+    assert abs(out["loss"] - ref["loss"]) <= 1e-4 * abs(ref["loss"]), (out["loss"], ref["loss"])
+    for l in range(L):
+        assert_close(out["a"][l], ref["a"][l], f"a^{l}")
+        assert_close(out["h"][l], ref["h"][l], f"h^{l + 1}")
+        assert_close(out["gh"][l], ref["gh"][l], f"grad h^{l + 1}")
+        assert_close(out["gW"][l], ref["gW"][l], f"grad W^{l}")
+        assert_close(out["W_new"][l], ref["W_new"][l], f"W^{l} after the step")
+
+
+@pytest.fixture(scope="module")
+def cfg1():
+    w = inputs.WORKLOADS["cfg1"]
+    src, dst, X, y, Ws = inputs.make_inputs(w)
+    ref = oracle_epoch(w, src, dst, X, y, Ws)
+    # the fp32 path and the fp64 oracle must take the same ReLU decisions
+    for l in range(w.n_layers - 1):
+        assert np.abs(ref["z"][l]).min() > 1e-6
+    return w, src, dst, X, y, Ws, ref
+
+
+def test_cfg1_all_in_hbm(ctx, cfg1):
+    w, src, dst, X, y, Ws, ref = cfg1
+    out = run_epoch(ctx, w, src, dst, X, y, Ws)
+    compare(out, ref, w.n_layers)
+    st = out["stats"]
+    assert st.edges == (w.E + w.V) * (2 * w.n_layers - 1)      # L forward + (L-1) backward aggregations
+    assert st.bytes_h2d == 0 and st.bytes_d2h == 0
+
+
+def test_cfg1_hybrid_equals_mask_bitwise(ctx, cfg1):
+    # Sec. 4.2: recomputing the update stage regenerates identical intermediates
+    w, src, dst, X, y, Ws, ref = cfg1
+    a = run_epoch(ctx, w, src, dst, X, y, Ws, inter=B.HT_INTER_MASK)
+    b = run_epoch(ctx, w, src, dst, X, y, Ws, inter=B.HT_INTER_HYBRID)
+    assert a["loss"] == b["loss"]
+    for l in range(w.n_layers):
+        assert np.array_equal(a["gW"][l], b["gW"][l]) and np.array_equal(a["W_new"][l], b["W_new"][l])
+        assert np.array_equal(a["gh"][l], b["gh"][l])
+
+
+def test_cfg1_host_resident_with_buffer(ctx, cfg1):
+    # vertex data, checkpoints and gradients in pinned host memory: dedup gather through the
+    # in-place buffer, D2H compaction and CPU-side accumulation
+    w, src, dst, X, y, Ws, ref = cfg1
+    out = run_epoch(ctx, w, src, dst, X, y, Ws, x_loc=B.HT_LOC_HOST_PINNED, res_h=B.HT_RES_HOST,
+                    res_a=B.HT_RES_HOST, res_g=B.HT_RES_HOST)
+    compare(out, ref, w.n_layers)
+    st = out["stats"]
+    assert st.rows_loaded + st.rows_reused > 0 and st.bytes_h2d > 0 and st.bytes_d2h > 0
+    assert st.bytes_h2d_nodedup >= 4 * w.dims[0] * st.rows_loaded // w.n_layers
+
+
+def test_cfg1_buffer_mode_in_hbm_and_chunk_count_invariance(ctx, cfg1):
+    w, src, dst, X, y, Ws, ref = cfg1
+    out = run_epoch(ctx, w, src, dst, X, y, Ws, gather_mode=B.HT_GATHER_BUFFER)
+    compare(out, ref, w.n_layers)
+    for n in (1, 9):
+        compare(run_epoch(ctx, w, src, dst, X, y, Ws, n_chunks=n), ref, w.n_layers)
+
+
+def test_three_layers_partial_labels(ctx):
+    w = inputs.Workload("t3", 6000, 70_000, [24, 40, 20, 12], 5, labelled_one_in=3)
+    src, dst, X, y, Ws = inputs.make_inputs(w)
+    ref = oracle_epoch(w, src, dst, X, y, Ws)
+    for l in range(w.n_layers - 1):
+        assert np.abs(ref["z"][l]).min() > 1e-7 * np.abs(ref["z"][l]).max()
+    compare(run_epoch(ctx, w, src, dst, X, y, Ws), ref, 3)
+    compare(run_epoch(ctx, w, src, dst, X, y, Ws, x_loc=B.HT_LOC_HOST_PINNED, res_h=B.HT_RES_HOST,
+                      res_a=B.HT_RES_HOST, res_g=B.HT_RES_HOST), ref, 3)
+
+
+def test_uniform_logits_loss_is_ln_C(ctx):
+    w = inputs.WORKLOADS["cfg1"]
+    src, dst, X, y, _ = inputs.make_inputs(w)
+    Ws = [torch.zeros(w.dims[l], w.dims[l + 1]) for l in range(w.n_layers)]
+    out = run_epoch(ctx, w, src, dst, X, y, Ws)
+    assert abs(out["loss"] - np.log(8.0)) < 1e-6
+
+
+def test_two_epochs_reuse_workspace_and_loss_decreases(ctx, cfg1):
+    w, src, dst, X, y, Ws, ref = cfg1
+    g = B.ht_partition(ctx, w.V, src.cuda(), dst.cuda(), w.n_chunks)
+    try:
+        Xd = B.to_matrix(X)
+        Wd = [x.clone().cuda() for x in Ws]
+        yd = y.cuda()
+        l0, _ = B.ht_epoch(ctx, g, w.dims, Wd, 0.5, Xd, yd)
+        l1, _ = B.ht_epoch(ctx, g, w.dims, Wd, 0.5, Xd, yd)
+        l2, _ = B.ht_epoch(ctx, g, w.dims, Wd, 0.5, Xd, yd)
+        assert abs(l0 - ref["loss"]) <= 1e-4 * ref["loss"]
+        assert l2 < l1 < l0
+    finally:
+        B.ht_graph_destroy(g)

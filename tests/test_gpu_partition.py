@@ -1,0 +1,149 @@
+"""ht_partition against the CPU oracle: every integer output bit for bit."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_2311_14898_amd import binding as B
+from paper_2311_14898_amd import inputs
+from tests.util import hub_graph
+
+pytestmark = pytest.mark.gpu
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = B.ht_ctx_create(0)
+    yield c
+    B.ht_ctx_destroy(c)
+
+
+def check_graph(ctx, V, src, dst, n, self_loops=True, mode=B.HT_BALANCE_EDGES, on_device=True, cache_rows=0):
+    s_t = src.cuda() if on_device else src
+    d_t = dst.cuda() if on_device else dst
+    g = B.ht_partition(ctx, V, s_t, d_t, n, add_self_loops=self_loops, balance_mode=mode, cache_rows=cache_rows)
+    try:
+        indptr, col, s, b = B.ht_graph_export_csc(g)
+        o_indptr, o_col = orc.csc_build(V, src.numpy(), dst.numpy(), self_loops)
+        assert np.array_equal(indptr, o_indptr), "indptr"
+        assert np.array_equal(col, o_col), "col"
+        np.testing.assert_allclose(s, orc.norm(o_indptr).astype(np.float32), rtol=1.2e-7, atol=0)
+        o_b = orc.chunk_bounds(o_indptr, n, mode)
+        assert np.array_equal(b, o_b), f"bounds {b} vs {o_b}"
+        info = B.ht_graph_info_get(g)
+        vo, vr = orc.volumes(o_indptr, o_col, o_b)
+        assert (info.v_ori, info.v_ru) == (vo, vr)
+        assert info.E_stored == o_indptr[-1] and info.V == V and info.n_chunks == n
+        assert abs(info.alpha - vo / V) < 1e-12
+        prev_N = np.zeros(0, np.int32)
+        prev_slot = {}
+        max_nsrc = 0
+        for j in range(n):
+            ch = B.ht_graph_export_chunk(g, j)
+            ci = ch["info"]
+            b0, b1 = int(o_b[j]), int(o_b[j + 1])
+            assert (ci.dst_begin, ci.dst_end) == (b0, b1)
+            o = orc.chunk_dedup(o_indptr, o_col, b0, b1)
+            assert np.array_equal(ch["indptr"], o_indptr[b0:b1 + 1] - o_indptr[b0])
+            assert np.array_equal(ch["col"], o_col[o_indptr[b0]:o_indptr[b1]])
+            for k in ("nbr", "col_local", "sptr", "sdst"):
+                ok = {"nbr": "N"}.get(k, k)
+                assert np.array_equal(ch[k], o[ok]), f"chunk {j}: {k}"
+            R, Ld = orc.reuse_split(prev_N, o["N"])
+            assert np.array_equal(ch["reuse"], R), f"chunk {j}: reuse"
+            assert np.array_equal(ch["load"], Ld), f"chunk {j}: load"
+            # buffer positions: a bijection into [0, cache_rows); reused vertices keep theirs
+            slot = ch["slot"]
+            assert len(set(slot.tolist())) == len(slot), f"chunk {j}: positions collide"
+            if len(slot):
+                assert slot.min() >= 0 and slot.max() < info.cache_rows
+            cur = dict(zip(o["N"].tolist(), slot.tolist()))
+            for u in R.tolist():
+                assert cur[u] == prev_slot[u], f"chunk {j}: reused vertex {u} moved"
+            prev_slot, prev_N = cur, o["N"]
+            max_nsrc = max(max_nsrc, len(slot))
+        assert info.max_nsrc == max_nsrc
+        assert info.cache_rows == (cache_rows or max(max_nsrc, 1))
+    finally:
+        B.ht_graph_destroy(g)
+
+
+def test_tiny_random(ctx):
+    rng = np.random.default_rng(0)
+    V = 45
+    src = torch.from_numpy(rng.integers(0, V, 260).astype(np.int32))
+    dst = torch.from_numpy(rng.integers(0, V, 260).astype(np.int32))
+    for n in (1, 4, 7):
+        check_graph(ctx, V, src, dst, n)
+    check_graph(ctx, V, src, dst, 3, mode=B.HT_BALANCE_VERTICES, on_device=False)
+
+
+def test_more_chunks_than_vertices_and_no_edges(ctx):
+    src = torch.tensor([0, 1, 2, 2], dtype=torch.int32)
+    dst = torch.tensor([1, 2, 0, 1], dtype=torch.int32)
+    check_graph(ctx, 3, src, dst, 8)                       # empty chunks
+    e = torch.zeros(0, dtype=torch.int32)
+    check_graph(ctx, 5, e, e, 2)                            # only self loops
+    check_graph(ctx, 70, src, dst, 3, self_loops=False)     # isolated vertices, empty rows, empty chunks
+
+
+def test_cfg1(ctx):
+    w = inputs.WORKLOADS["cfg1"]
+    src, dst = inputs.rmat_edges(w.V, w.E, w.graph_seed)
+    check_graph(ctx, w.V, src, dst, w.n_chunks)
+    check_graph(ctx, w.V, src, dst, 5, cache_rows=w.V)
+
+
+def test_several_sort_tiles_ragged_and_hubs(ctx):
+    # 1.2 M edges: hundreds of radix-sort tiles with a ragged last one; a hub row and a hub source
+    # that are cut into several aggregation work items
+    V = 150_001
+    src, dst = hub_graph(V, 1_200_003, hub_in=5000, hub_out=7000, seed=3)
+    check_graph(ctx, V, src, dst, 7)
+
+
+def test_rmat_skew_medium(ctx):
+    V, E = 60_000, 1_500_000
+    src, dst = inputs.rmat_edges(V, E, seed=9)
+    check_graph(ctx, V, src, dst, 16)
+
+
+def test_paper_inplace_buffer_example(ctx):
+    # Sec. 6: {2,6,7} keep their positions, {3,5,8} go to the positions of {1,4,9}
+    def ints(key):
+        with open(os.path.join(GOLDEN, "inplace_buffer_example.txt")) as f:
+            for line in f:
+                if line.startswith(key + ":"):
+                    return [int(x) for x in line.split(":")[1].split()]
+    prev, nxt = ints("prev"), ints("next")
+    src = torch.tensor(prev + nxt, dtype=torch.int32)
+    dst = torch.tensor([10] * len(prev) + [11] * len(nxt), dtype=torch.int32)
+    g = B.ht_partition(ctx, 12, src, dst, 2, add_self_loops=False)
+    try:
+        c0, c1 = B.ht_graph_export_chunk(g, 0), B.ht_graph_export_chunk(g, 1)
+        assert c0["nbr"].tolist() == prev and c1["nbr"].tolist() == nxt
+        assert c1["reuse"].tolist() == ints("reused") and c1["load"].tolist() == ints("loaded")
+        p0 = dict(zip(c0["nbr"].tolist(), c0["slot"].tolist()))
+        p1 = dict(zip(c1["nbr"].tolist(), c1["slot"].tolist()))
+        for u in ints("reused"):
+            assert p0[u] == p1[u]
+        assert sorted(p1[u] for u in ints("loaded")) == sorted(p0[u] for u in ints("discarded"))
+        info = B.ht_graph_info_get(g)
+        assert (info.v_ori, info.v_ru) == (12, 9)
+    finally:
+        B.ht_graph_destroy(g)
+
+
+def test_bad_arguments(ctx):
+    src = torch.tensor([0, 5], dtype=torch.int32).cuda()
+    dst = torch.tensor([1, 2], dtype=torch.int32).cuda()
+    with pytest.raises(B.HongtuError) as e:
+        B.ht_partition(ctx, 3, src, dst, 2)             # id 5 >= V
+    assert e.value.code == B.HT_EINVAL
+    with pytest.raises(B.HongtuError):
+        B.ht_partition(ctx, 3, src[:1], dst[:1], 0)     # n_chunks < 1
+    with pytest.raises(B.HongtuError):
+        B.ht_partition(ctx, 10, src, dst, 2, cache_rows=1)   # buffer smaller than a chunk's neighbour set
