@@ -102,10 +102,10 @@ def test_cfg1_buffer_mode_in_hbm_and_chunk_count_invariance(ctx, cfg1):
 
 
 def test_three_layers_partial_labels(ctx):
-    w = inputs.Workload("t3", 6000, 70_000, [24, 40, 20, 12], 5, labelled_one_in=3)
+    w = inputs.Workload("t3", 6000, 70_000, [24, 40, 20, 12], 5, labelled_one_in=3, graph_seed=6)
     src, dst, X, y, Ws = inputs.make_inputs(w)
     ref = oracle_epoch(w, src, dst, X, y, Ws)
-    for l in range(w.n_layers - 1):
+    for l in range(w.n_layers - 1):     # same ReLU decisions on both sides (this graph seed was picked for it)
         assert np.abs(ref["z"][l]).min() > 1e-7 * np.abs(ref["z"][l]).max()
     compare(run_epoch(ctx, w, src, dst, X, y, Ws), ref, 3)
     compare(run_epoch(ctx, w, src, dst, X, y, Ws, x_loc=B.HT_LOC_HOST_PINNED, res_h=B.HT_RES_HOST,
