@@ -60,6 +60,7 @@ enum {
 };
 
 enum { HT_LOC_DEVICE = 0, HT_LOC_HOST_PINNED = 1 };
+#define HT_MAX_LAYERS 8
 
 /* fp32 matrix view, see "Conventions". */
 typedef struct {
@@ -201,6 +202,13 @@ typedef struct {
   double spmm_fwd_alg_bytes; /* compulsory bytes of the forward aggregation launches */
   double spmm_bwd_alg_bytes;
   double gemm_flops;
+  /* Forward aggregation per layer (index = layer in ht_epoch, 0 in ht_layer_*):
+   * time of the main aggregation kernel alone (the partial-sum pass of cut
+   * rows is in t_agg_fix_ms), its launches and compulsory bytes. */
+  double t_agg_fwd_layer_ms[HT_MAX_LAYERS];
+  double agg_fwd_layer_alg_bytes[HT_MAX_LAYERS];
+  int64_t n_agg_fwd_layer[HT_MAX_LAYERS];
+  double t_agg_fix_ms;
 } ht_stats;
 
 /* Forward of one layer over all chunks in schedule order:

@@ -98,11 +98,12 @@ def norm(indptr: np.ndarray) -> np.ndarray:
     return s
 
 
-def aggregate(indptr, col, h, rows: Optional[Tuple[int, int]] = None) -> np.ndarray:
-    """a = diag(s) A~ diag(s) h; with rows=(v0, v1) only those rows are filled."""
+def aggregate(indptr, col, h, rows: Optional[Tuple[int, int]] = None, s: Optional[np.ndarray] = None) -> np.ndarray:
+    """a = diag(s) A~ diag(s) h; with rows=(v0, v1) only those rows are filled.
+    s defaults to norm(indptr); a caller that holds only part of the edges passes the full graph's s."""
     h = _f64(h)
     V, d = h.shape
-    s = norm(indptr)
+    s = norm(indptr) if s is None else _f64(s)
     a = np.zeros((V, d), dtype=np.float64)
     v0, v1 = rows if rows is not None else (0, V)
     lib().orc_aggregate(_p(indptr), _p(col), _p(s), C.c_int64(v0), C.c_int64(v1), C.c_int64(d), _p(h), _p(a))

@@ -27,6 +27,7 @@ HT_CKPT_AGG, HT_CKPT_INPUT = 0, 1
 HT_RES_AUTO, HT_RES_HBM, HT_RES_HOST = 0, 1, 2
 HT_INTER_AUTO, HT_INTER_MASK, HT_INTER_HYBRID = 0, 1, 2
 HT_BUF_H, HT_BUF_A, HT_BUF_GH, HT_BUF_DW = 0, 1, 2, 3
+HT_MAX_LAYERS = 8
 
 
 class ht_tensor(C.Structure):
@@ -67,10 +68,17 @@ class ht_stats(C.Structure):
                 ("n_spmm_fwd", C.c_int64), ("n_spmm_bwd", C.c_int64), ("n_gemm", C.c_int64), ("edges", C.c_int64),
                 ("rows_loaded", C.c_int64), ("rows_reused", C.c_int64), ("bytes_h2d", C.c_int64),
                 ("bytes_d2h", C.c_int64), ("bytes_h2d_nodedup", C.c_int64), ("spmm_fwd_alg_bytes", C.c_double),
-                ("spmm_bwd_alg_bytes", C.c_double), ("gemm_flops", C.c_double)]
+                ("spmm_bwd_alg_bytes", C.c_double), ("gemm_flops", C.c_double),
+                ("t_agg_fwd_layer_ms", C.c_double * HT_MAX_LAYERS),
+                ("agg_fwd_layer_alg_bytes", C.c_double * HT_MAX_LAYERS),
+                ("n_agg_fwd_layer", C.c_int64 * HT_MAX_LAYERS), ("t_agg_fix_ms", C.c_double)]
 
     def as_dict(self):
-        return {k: getattr(self, k) for k, _ in self._fields_}
+        out = {}
+        for k, _ in self._fields_:
+            v = getattr(self, k)
+            out[k] = list(v) if hasattr(v, "__len__") else v
+        return out
 
 
 class ht_model(C.Structure):

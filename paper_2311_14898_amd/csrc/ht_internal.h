@@ -201,6 +201,10 @@ struct SpmmArgs {
   const int32_t* post_idx;// row r -> index into post (nullable: r)
   int32_t accumulate;     // 1: out += value
   float* partial;         // [n_part x out_ld] workspace
+  // optional timing of the two kernels (null: not timed)
+  struct Timer* tm = nullptr;
+  double* t_items = nullptr;
+  double* t_fix = nullptr;
 };
 int ht_spmm_launch(ht_ctx* ctx, hipStream_t st, const SpmmArgs& a);
 

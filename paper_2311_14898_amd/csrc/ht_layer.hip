@@ -96,6 +96,7 @@ struct Run {
   const ht_graph* g;
   Timer tm;
   ht_stats* st;  // never null inside (a local one is used when the caller passes none)
+  int layer = 0; // index into the per-layer statistics
   Run(ht_ctx* c, const ht_graph* gr, ht_stats* s, bool timed) : ctx(c), g(gr), tm(c, c->stream, timed), st(s) {}
 };
 
@@ -141,12 +142,16 @@ int aggregate_chunk(Run& R, int j, bool buffer, const ht_tensor* H_in, const flo
   a.post = g->s.p + c.dst0; a.post_idx = nullptr;
   a.accumulate = 0;
   a.partial = partial;
-  R.tm.begin(&R.st->t_spmm_fwd_ms);
+  const int li = R.layer < HT_MAX_LAYERS ? R.layer : HT_MAX_LAYERS - 1;
+  a.tm = &R.tm;
+  a.t_items = &R.st->t_agg_fwd_layer_ms[li];
+  a.t_fix = &R.st->t_agg_fix_ms;
   HT_TRY(ht_spmm_launch(ctx, st, a));
-  R.tm.end();
   R.st->n_spmm_fwd += 1;
+  R.st->n_agg_fwd_layer[li] += 1;
   R.st->edges += c.nnz;
   R.st->spmm_fwd_alg_bytes += spmm_alg_bytes(c, d);
+  R.st->agg_fwd_layer_alg_bytes[li] += spmm_alg_bytes(c, d);
   return HT_OK;
 }
 
@@ -389,6 +394,8 @@ int finish(Run& R, ht_stats* user, const std::chrono::steady_clock::time_point& 
   }
   ctx->ev_next = 0;
   if (user) {
+    for (int l = 0; l < HT_MAX_LAYERS; ++l) R.st->t_spmm_fwd_ms += R.st->t_agg_fwd_layer_ms[l];
+    R.st->t_spmm_fwd_ms += R.st->t_agg_fix_ms;
     R.st->t_total_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
     *user = *R.st;
   }
@@ -580,6 +587,7 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
     d.d_in = model->dims[l]; d.d_out = model->dims[l + 1];
     d.act = l < L - 1 ? HT_ACT_RELU : HT_ACT_NONE;
     d.gather_mode = gather_mode;
+    R.layer = l;
     int rc = layer_fwd_impl(R, &d, l == 0 ? X : &ws->h[l], model->W[l], &ws->h[l + 1], &ws->a[l]);
     if (rc != HT_OK) return fail(rc);
   }
@@ -602,6 +610,7 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
       int rc = zero_tensor(ctx, &ws->gh[l]);
       if (rc != HT_OK) return fail(rc);
     }
+    R.layer = l;
     const ht_tensor* mask_from = (inter == HT_INTER_MASK && l < L - 1) ? &ws->h[l + 1] : nullptr;
     int rc = layer_bwd_impl(R, &d, &ws->a[l], model->W[l], &ws->gh[l + 1], mask_from, l > 0 ? &ws->gh[l] : nullptr,
                             ws->dW[l]);

@@ -166,6 +166,7 @@ int ht_spmm_launch(ht_ctx* ctx, hipStream_t st, const SpmmArgs& a0) {
     a.d = (a0.d - c0) < 1024 ? (a0.d - c0) : 1024;
     const int nvec = (a.d + 3) / 4;
     int rc;
+    if (a.tm && a.t_items) a.tm->begin(a.t_items);
     if (nvec <= 8) rc = launch_items<8, 1>(ctx, st, a);
     else if (nvec <= 16) rc = launch_items<16, 1>(ctx, st, a);
     else if (nvec <= 32) rc = launch_items<32, 1>(ctx, st, a);
@@ -173,9 +174,12 @@ int ht_spmm_launch(ht_ctx* ctx, hipStream_t st, const SpmmArgs& a0) {
     else if (nvec <= 128) rc = launch_items<64, 2>(ctx, st, a);
     else if (nvec <= 192) rc = launch_items<64, 3>(ctx, st, a);
     else rc = launch_items<64, 4>(ctx, st, a);
+    if (a.tm && a.t_items) a.tm->end();
     if (rc != HT_OK) return rc;
     if (a.n_fix > 0) {
+      if (a.tm && a.t_fix) a.tm->begin(a.t_fix);
       k_spmm_fix<<<(unsigned)((a.n_fix + 3) / 4), 256, 0, st>>>(a);
+      if (a.tm && a.t_fix) a.tm->end();
       HT_LAUNCH_CHECK(ctx);
     }
   }
