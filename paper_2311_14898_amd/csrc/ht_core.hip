@@ -1,5 +1,6 @@
 // Context, error reporting, allocation accounting, event timers.
 #include <cstdarg>
+#include <cstdlib>
 
 #include "ht_internal.h"
 
@@ -124,6 +125,7 @@ int ht_ctx_create(ht_ctx** out, int device, void* hip_stream) {
   ht_ctx* c = new (std::nothrow) ht_ctx();
   if (!c) return HT_ENOMEM;
   c->device = device;
+  if (const char* v = getenv("HT_AGG_VARIANT")) c->agg_variant = atoi(v);
   if (hip_stream) {
     c->stream = (hipStream_t)hip_stream;
   } else {

@@ -39,6 +39,7 @@ struct ht_ctx {
   // pinned host scratch (D2H staging of gradient rows)
   void* hscratch[2] = {nullptr, nullptr};
   size_t hscratch_bytes[2] = {0, 0};
+  int agg_variant = 0;  // 0: feature slabs per XCD; 1: full-width rows per wave (HT_AGG_VARIANT, for A/B runs)
   int n_threads = 0;  // host threads for CPU-side accumulation (0 = decide on first use)
 };
 

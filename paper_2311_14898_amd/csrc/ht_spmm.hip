@@ -102,20 +102,110 @@ __global__ void __launch_bounds__(256) k_spmm_items(SpmmArgs a) {
   }
 }
 
-// Rows cut into several items: add their partial sums in item order.
+// Rows cut into several items: add their partial sums in item order.  One
+// block per row; each wave adds a contiguous quarter of the partial sums, the
+// four results are added in wave order.
 __global__ void __launch_bounds__(256) k_spmm_fix(SpmmArgs a) {
-  const int lane = threadIdx.x & 63;
-  const int64_t f = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (f >= a.n_fix) return;
+  __shared__ float4 sh[4][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t f = blockIdx.x;
   const int32_t r = a.fx_row[f];
   const int32_t p0 = a.fx_part0[f];
   const int32_t ns = a.fx_nseg[f];
   const int d4 = (a.d + 3) & ~3;
-  for (int c4 = lane * 4; c4 < d4; c4 += 256) {
+  const int32_t per = (ns + 3) >> 2;
+  const int32_t k0 = wave * per, k1 = (k0 + per) < ns ? (k0 + per) : ns;
+  for (int cb = 0; cb < d4; cb += 256) {
+    const int c4 = cb + lane * 4;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int32_t k = 0; k < ns; ++k) acc = add4(acc, ld4(a.partial + (int64_t)(p0 + k) * a.out_ld + c4));
-    write_out(a, r, c4, acc);
+    if (c4 < d4) {
+      const float* p = a.partial + (int64_t)p0 * a.out_ld + c4;
+      int32_t k = k0;
+      for (; k + 4 <= k1; k += 4) {
+        const float4 v0 = ld4(p + (int64_t)(k + 0) * a.out_ld);
+        const float4 v1 = ld4(p + (int64_t)(k + 1) * a.out_ld);
+        const float4 v2 = ld4(p + (int64_t)(k + 2) * a.out_ld);
+        const float4 v3 = ld4(p + (int64_t)(k + 3) * a.out_ld);
+        acc = add4(add4(add4(add4(acc, v0), v1), v2), v3);
+      }
+      for (; k < k1; ++k) acc = add4(acc, ld4(p + (int64_t)k * a.out_ld));
+    }
+    sh[wave][lane] = acc;
+    __syncthreads();
+    if (wave == 0 && c4 < d4) {
+      float4 t = add4(add4(add4(sh[0][lane], sh[1][lane]), sh[2][lane]), sh[3][lane]);
+      write_out(a, r, c4, t);
+    }
+    __syncthreads();
   }
+}
+
+// Feature-slab variant.  The 8 XCDs each have their own L2; workgroups go to
+// XCDs round-robin by id, so workgroup b runs on XCD b % 8.  Giving every XCD a
+// fixed slab of the feature columns makes its L2 hold 8x more distinct source
+// rows than full-width rows would.  A wave owns one item and one slab; lanes
+// are (edge slot, float4 of the slab); `eps` edges are read per step.
+__global__ void __launch_bounds__(256) k_spmm_slab(SpmmArgs a, int S, int nvs, int eps) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int xcd = blockIdx.x & 7;
+  const int slab = xcd % S;
+  const int64_t grp = (int64_t)(blockIdx.x >> 3) * (8 / S) + xcd / S;
+  const int64_t t = grp * 4 + wave;
+  if (t >= a.n_items) return;
+  const int nvec = (a.d + 3) >> 2;
+  const int v0 = slab * nvs;
+  const int nv_here = (nvec - v0) < nvs ? (nvec - v0) : nvs;
+  if (nv_here <= 0) return;
+  const int32_t r = a.it_row[t];
+  const int64_t e0 = a.it_e0[t];
+  const int32_t len = a.it_len[t];
+  const int32_t part = a.it_part[t];
+  const int es = lane / nvs, vec = lane - es * nvs;
+  const bool active = es < eps && vec < nv_here;
+  const int coff = (v0 + vec) * 4;
+  const float* srcc = a.src + coff;
+
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int32_t base = 0; base < len; base += 64) {
+    const int32_t n_here = (len - base) < 64 ? (len - base) : 64;
+    int32_t my_idx = 0;
+    float my_w = 0.f;
+    if (lane < n_here) {
+      my_idx = a.idx[e0 + base + lane];
+      my_w = a.ew ? a.ew[my_idx] : 1.f;
+    }
+    for (int32_t k = 0; k < n_here; k += 4 * eps) {
+      int32_t c[4];
+      float w[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int kk = k + u * eps + es;
+        const int kc = kk < n_here ? kk : (n_here - 1);   // past the end: re-read the last edge with weight 0
+        c[u] = __shfl(my_idx, kc, 64);
+        w[u] = __shfl(my_w, kc, 64);
+        if (kk >= n_here) w[u] = 0.f;
+      }
+      if (active) {
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = ld4(srcc + (int64_t)c[u] * a.src_ld);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc = fma4(w[u], v[u], acc);
+      }
+    }
+  }
+  // add the edge slots in slot order; slot 0 holds the result
+  float4 tot = acc;
+  for (int q = 1; q < eps; ++q) {
+    const int from = (lane + q * nvs) & 63;
+    float4 o = make_float4(__shfl(acc.x, from, 64), __shfl(acc.y, from, 64), __shfl(acc.z, from, 64), __shfl(acc.w, from, 64));
+    tot = add4(tot, o);
+  }
+  if (es != 0 || vec >= nv_here) return;
+  if (part >= 0)
+    st4(a.partial + (int64_t)part * a.out_ld + coff, tot);
+  else
+    write_out(a, r, coff, tot);
 }
 
 template <int LPR, int VPL>
@@ -165,9 +255,17 @@ int ht_spmm_launch(ht_ctx* ctx, hipStream_t st, const SpmmArgs& a0) {
     a.partial = a0.partial ? a0.partial + c0 : nullptr;
     a.d = (a0.d - c0) < 1024 ? (a0.d - c0) : 1024;
     const int nvec = (a.d + 3) / 4;
-    int rc;
+    int rc = HT_OK;
     if (a.tm && a.t_items) a.tm->begin(a.t_items);
-    if (nvec <= 8) rc = launch_items<8, 1>(ctx, st, a);
+    if (ctx->agg_variant == 0) {
+      const int S = nvec >= 64 ? 8 : nvec >= 32 ? 4 : nvec >= 16 ? 2 : 1;
+      const int nvs = (nvec + S - 1) / S;
+      const int eps = 64 / nvs;
+      const int64_t groups = (a.n_items + 3) / 4;
+      const int64_t rows8 = (groups + (8 / S) - 1) / (8 / S);
+      k_spmm_slab<<<(unsigned)(rows8 * 8), 256, 0, st>>>(a, S, nvs, eps);
+      HT_LAUNCH_CHECK(ctx);
+    } else if (nvec <= 8) rc = launch_items<8, 1>(ctx, st, a);
     else if (nvec <= 16) rc = launch_items<16, 1>(ctx, st, a);
     else if (nvec <= 32) rc = launch_items<32, 1>(ctx, st, a);
     else if (nvec <= 64) rc = launch_items<64, 1>(ctx, st, a);
@@ -178,7 +276,7 @@ int ht_spmm_launch(ht_ctx* ctx, hipStream_t st, const SpmmArgs& a0) {
     if (rc != HT_OK) return rc;
     if (a.n_fix > 0) {
       if (a.tm && a.t_fix) a.tm->begin(a.t_fix);
-      k_spmm_fix<<<(unsigned)((a.n_fix + 3) / 4), 256, 0, st>>>(a);
+      k_spmm_fix<<<(unsigned)a.n_fix, 256, 0, st>>>(a);
       if (a.tm && a.t_fix) a.tm->end();
       HT_LAUNCH_CHECK(ctx);
     }
