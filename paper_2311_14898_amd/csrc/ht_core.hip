@@ -126,6 +126,8 @@ int ht_ctx_create(ht_ctx** out, int device, void* hip_stream) {
   if (!c) return HT_ENOMEM;
   c->device = device;
   if (const char* v = getenv("HT_AGG_VARIANT")) c->agg_variant = atoi(v);
+  if (const char* v = getenv("HT_SLABS_FWD")) c->slabs_fwd = atoi(v);
+  if (const char* v = getenv("HT_SLABS_BWD")) c->slabs_bwd = atoi(v);
   if (hip_stream) {
     c->stream = (hipStream_t)hip_stream;
   } else {

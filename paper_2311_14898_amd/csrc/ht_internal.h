@@ -39,6 +39,7 @@ struct ht_ctx {
   // pinned host scratch (D2H staging of gradient rows)
   void* hscratch[2] = {nullptr, nullptr};
   size_t hscratch_bytes[2] = {0, 0};
+  int slabs_fwd = 0, slabs_bwd = 0;  // caps on feature slabs (HT_SLABS_FWD / HT_SLABS_BWD), 0 = by width
   int agg_variant = 0;  // 0: feature slabs per XCD; 1: full-width rows per wave (HT_AGG_VARIANT, for A/B runs)
   int n_threads = 0;  // host threads for CPU-side accumulation (0 = decide on first use)
 };
@@ -184,6 +185,7 @@ struct SpmmArgs {
   const int32_t* it_len;
   const int32_t* it_part;
   int64_t n_items;
+  int64_t n_edges;        // edges covered by the items (for launch heuristics)
   const int32_t* fx_row;
   const int32_t* fx_part0;
   const int32_t* fx_nseg;
@@ -202,6 +204,7 @@ struct SpmmArgs {
   const int32_t* post_idx;// row r -> index into post (nullable: r)
   int32_t accumulate;     // 1: out += value
   float* partial;         // [n_part x out_ld] workspace
+  int max_slabs = 0;      // cap on the number of feature slabs (0 = by width)
   // optional timing of the two kernels (null: not timed)
   struct Timer* tm = nullptr;
   double* t_items = nullptr;

@@ -131,7 +131,7 @@ int aggregate_chunk(Run& R, int j, bool buffer, const ht_tensor* H_in, const flo
   float* partial = nullptr;
   if (c.fwd.n_part > 0) HT_TRY(ht_scratch(ctx, HT_S_SPART, (size_t)g->max_fpart * out_ld * 4, (void**)&partial));
   SpmmArgs a{};
-  a.it_row = c.fwd.row; a.it_e0 = c.fwd.e0; a.it_len = c.fwd.len; a.it_part = c.fwd.part; a.n_items = c.fwd.n_items;
+  a.it_row = c.fwd.row; a.it_e0 = c.fwd.e0; a.it_len = c.fwd.len; a.it_part = c.fwd.part; a.n_items = c.fwd.n_items; a.n_edges = c.nnz;
   a.fx_row = c.fwd.fx_row; a.fx_part0 = c.fwd.fx_part0; a.fx_nseg = c.fwd.fx_nseg; a.n_fix = c.fwd.n_fix;
   a.idx = (buffer ? g->col_slot.p : g->col.p) + c.e0;
   a.ew = buffer ? nullptr : g->s.p;
@@ -142,6 +142,7 @@ int aggregate_chunk(Run& R, int j, bool buffer, const ht_tensor* H_in, const flo
   a.post = g->s.p + c.dst0; a.post_idx = nullptr;
   a.accumulate = 0;
   a.partial = partial;
+  a.max_slabs = ctx->slabs_fwd;
   const int li = R.layer < HT_MAX_LAYERS ? R.layer : HT_MAX_LAYERS - 1;
   a.tm = &R.tm;
   a.t_items = &R.st->t_agg_fwd_layer_ms[li];
@@ -341,7 +342,7 @@ int layer_bwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* ckpt, con
         const int64_t out_ld = gbuffer ? ld_i : dH_in->ld;
         if (c.bwd.n_part > 0) HT_TRY(ht_scratch(ctx, HT_S_SPART, (size_t)g->max_bpart * out_ld * 4, (void**)&partial));
         SpmmArgs a{};
-        a.it_row = c.bwd.row; a.it_e0 = c.bwd.e0; a.it_len = c.bwd.len; a.it_part = c.bwd.part; a.n_items = c.bwd.n_items;
+        a.it_row = c.bwd.row; a.it_e0 = c.bwd.e0; a.it_len = c.bwd.len; a.it_part = c.bwd.part; a.n_items = c.bwd.n_items; a.n_edges = c.nnz;
         a.fx_row = c.bwd.fx_row; a.fx_part0 = c.bwd.fx_part0; a.fx_nseg = c.bwd.fx_nseg; a.n_fix = c.bwd.n_fix;
         a.idx = g->sdst.p + c.e0;
         a.ew = g->s.p + c.dst0;
@@ -355,6 +356,7 @@ int layer_bwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* ckpt, con
         a.post_idx = g->nbr.p + c.nbr_off;
         a.accumulate = 1;
         a.partial = partial;
+        a.max_slabs = ctx->slabs_bwd;
         R.tm.begin(&R.st->t_spmm_bwd_ms);
         HT_TRY(ht_spmm_launch(ctx, st, a));
         R.tm.end();

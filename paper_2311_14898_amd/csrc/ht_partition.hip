@@ -8,6 +8,7 @@
 // Sec. 6 (same buffer position for duplicated vertices of adjacent chunks;
 // loaded rows take freed positions; topology rewritten to buffer positions).
 #include <algorithm>
+#include <cstdlib>
 
 #include "ht_internal.h"
 
@@ -177,7 +178,7 @@ __global__ void k_map_i32(const int32_t* __restrict__ idx, int64_t n, const int3
   if (i < n) out[i] = table[idx[i]];
 }
 
-__global__ void k_items_count(const int64_t* __restrict__ ptr, int64_t nrows, int32_t* __restrict__ nseg,
+__global__ void k_items_count(const int64_t* __restrict__ ptr, int64_t nrows, int HT_SEG, int32_t* __restrict__ nseg,
                               int32_t* __restrict__ npart, int32_t* __restrict__ isfix) {
   int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (r >= nrows) return;
@@ -188,7 +189,7 @@ __global__ void k_items_count(const int64_t* __restrict__ ptr, int64_t nrows, in
   isfix[r] = k > 1 ? 1 : 0;
 }
 
-__global__ void k_items_fill(const int64_t* __restrict__ ptr, int64_t ptr0, int64_t nrows,
+__global__ void k_items_fill(const int64_t* __restrict__ ptr, int64_t ptr0, int64_t nrows, int HT_SEG,
                              const int64_t* __restrict__ it_base, const int64_t* __restrict__ part_base,
                              const int64_t* __restrict__ fix_base, int32_t* __restrict__ it_row,
                              int64_t* __restrict__ it_e0, int32_t* __restrict__ it_len, int32_t* __restrict__ it_part,
@@ -215,6 +216,29 @@ __global__ void k_items_fill(const int64_t* __restrict__ ptr, int64_t ptr0, int6
   }
 }
 
+// Dispatch order of work items: by the first row they read (edges of a row are
+// sorted by that index), so items in flight together read neighbouring rows.
+__global__ void k_item_keys(const int64_t* __restrict__ it_e0, const int32_t* __restrict__ it_len, int64_t n,
+                            const int32_t* __restrict__ idx, uint64_t* __restrict__ keys) {
+  int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n) return;
+  const uint32_t first = it_len[t] > 0 ? (uint32_t)idx[it_e0[t]] : 0u;
+  keys[t] = ((uint64_t)first << 32) | (uint64_t)(uint32_t)t;
+}
+
+__global__ void k_item_permute(const uint64_t* __restrict__ keys, int64_t n, const int32_t* __restrict__ row,
+                               const int64_t* __restrict__ e0, const int32_t* __restrict__ len,
+                               const int32_t* __restrict__ part, int32_t* __restrict__ row_o,
+                               int64_t* __restrict__ e0_o, int32_t* __restrict__ len_o, int32_t* __restrict__ part_o) {
+  int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n) return;
+  const uint32_t from = (uint32_t)(keys[t] & 0xFFFFFFFFull);
+  row_o[t] = row[from];
+  e0_o[t] = e0[from];
+  len_o[t] = len[from];
+  part_o[t] = part[from];
+}
+
 int bits_for(int64_t n) {  // bits needed for values 0..n-1 (at least 1)
   int b = 1;
   while (((int64_t)1 << b) < n) ++b;
@@ -236,11 +260,14 @@ struct ItemTmp {
 };
 
 // ptr: device offsets of nrows+1 entries; ptr0: value to subtract so item edges are chunk-relative.
-int build_items(ht_ctx* ctx, ItemTmp& t, const int64_t* ptr, int64_t ptr0, int64_t nrows, ItemSet* out) {
+// idx: the chunk's per-edge row index array (what the aggregation reads), idx_range: its value range.
+// keysA/keysB: scratch of at least n_items entries each.
+int build_items(ht_ctx* ctx, ItemTmp& t, const int64_t* ptr, int64_t ptr0, int64_t nrows, const int32_t* idx,
+                int64_t idx_range, uint64_t* keysA, uint64_t* keysB, bool order, int seg, ItemSet* out) {
   out->n_items = out->n_part = out->n_fix = 0;
   if (nrows == 0) return HT_OK;
   hipStream_t st = ctx->stream;
-  k_items_count<<<nblk(nrows), TB, 0, st>>>(ptr, nrows, t.nseg.p, t.npart.p, t.isfix.p);
+  k_items_count<<<nblk(nrows), TB, 0, st>>>(ptr, nrows, seg, t.nseg.p, t.npart.p, t.isfix.p);
   HT_LAUNCH_CHECK(ctx);
   HT_TRY(ht_scan_i32(ctx, t.nseg.p, t.it_base.p, nrows, true));
   HT_TRY(ht_scan_i32(ctx, t.npart.p, t.part_base.p, nrows, true));
@@ -265,9 +292,33 @@ int build_items(ht_ctx* ctx, ItemTmp& t, const int64_t* ptr, int64_t ptr0, int64
   out->fx_row = (int32_t*)p; p += nf * 4;
   out->fx_part0 = (int32_t*)p; p += nf * 4;
   out->fx_nseg = (int32_t*)p;
-  k_items_fill<<<nblk(nrows), TB, 0, st>>>(ptr, ptr0, nrows, t.it_base.p, t.part_base.p, t.fix_base.p, out->row,
+  k_items_fill<<<nblk(nrows), TB, 0, st>>>(ptr, ptr0, nrows, seg, t.it_base.p, t.part_base.p, t.fix_base.p, out->row,
                                           out->e0, out->len, out->part, out->fx_row, out->fx_part0, out->fx_nseg);
   HT_LAUNCH_CHECK(ctx);
+  if (order && ni > 1) {
+    k_item_keys<<<nblk((int64_t)ni), TB, 0, st>>>(out->e0, out->len, (int64_t)ni, idx, keysA);
+    HT_LAUNCH_CHECK(ctx);
+    uint64_t* sorted = nullptr;
+    HT_TRY(ht_radix_sort_u64(ctx, keysA, keysB, (int64_t)ni, 32, 32 + bits_for(idx_range), &sorted));
+    DevArr<char> blob2;
+    HT_TRY(blob2.alloc(ctx, bytes));
+    char* q = blob2.p;
+    int64_t* e0_o = (int64_t*)q; q += ni * 8;
+    int32_t* row_o = (int32_t*)q; q += ni * 4;
+    int32_t* len_o = (int32_t*)q; q += ni * 4;
+    int32_t* part_o = (int32_t*)q; q += ni * 4;
+    k_item_permute<<<nblk((int64_t)ni), TB, 0, st>>>(sorted, (int64_t)ni, out->row, out->e0, out->len, out->part, row_o,
+                                                    e0_o, len_o, part_o);
+    HT_LAUNCH_CHECK(ctx);
+    if (nf > 0)
+      HT_HIP(ctx, hipMemcpyAsync(q, out->fx_row, nf * 4 * 3, hipMemcpyDeviceToDevice, st));
+    out->fx_row = (int32_t*)q; q += nf * 4;
+    out->fx_part0 = (int32_t*)q; q += nf * 4;
+    out->fx_nseg = (int32_t*)q;
+    out->e0 = e0_o; out->row = row_o; out->len = len_o; out->part = part_o;
+    HT_HIP(ctx, hipStreamSynchronize(st));
+    out->blob = std::move(blob2);
+  }
   return HT_OK;
 }
 
@@ -311,8 +362,9 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
   // ---- CSC by (destination, source)
   const int bitsV = bits_for(V);
   DevArr<uint64_t> keysA, keysB;
-  HT_TRY(keysA.alloc(ctx, (size_t)(Ep > 0 ? Ep : 1)));
-  HT_TRY(keysB.alloc(ctx, (size_t)(Ep > 0 ? Ep : 1)));
+  const size_t nkeys = (size_t)std::max<int64_t>(std::max(Ep, V), 1) + 64;  // also holds one key per work item
+  HT_TRY(keysA.alloc(ctx, nkeys));
+  HT_TRY(keysB.alloc(ctx, nkeys));
   HT_TRY(g->indptr.alloc(ctx, (size_t)V + 1));
   HT_TRY(g->col.alloc(ctx, (size_t)(Ep > 0 ? Ep : 1)));
   HT_TRY(g->s.alloc(ctx, (size_t)V));
@@ -459,6 +511,11 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
   ItemTmp itmp;
   HT_TRY(itmp.alloc(ctx, std::max<int64_t>(std::max(g->max_ndst, g->max_nsrc), 1)));
 
+  const char* ord_env = getenv("HT_ITEM_ORDER");
+  const bool order_items = !(ord_env && atoi(ord_env) == 0);
+  int seg_fwd = HT_SEG, seg_bwd = HT_SEG;   // tunable for experiments only
+  if (const char* v = getenv("HT_SEG_FWD")) seg_fwd = std::max(64, atoi(v));
+  if (const char* v = getenv("HT_SEG_BWD")) seg_bwd = std::max(64, atoi(v));
   cur = bmA.p;
   prev = bmB.p;
   HT_HIP(ctx, hipMemsetAsync(prev, 0, nw * 8, st));
@@ -531,8 +588,11 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
       HT_LAUNCH_CHECK(ctx);
     }
     // work items of both directions
-    HT_TRY(build_items(ctx, itmp, g->indptr.p + c.dst0, c.e0, c.dst1 - c.dst0, &c.fwd));
-    HT_TRY(build_items(ctx, itmp, sptr_j, 0, c.nsrc, &c.bwd));
+    // forward items are ordered by buffer-independent source id; backward ones by local destination
+    HT_TRY(build_items(ctx, itmp, g->indptr.p + c.dst0, c.e0, c.dst1 - c.dst0, g->col.p + c.e0, V, keysA.p, keysB.p,
+                       order_items, seg_fwd, &c.fwd));
+    HT_TRY(build_items(ctx, itmp, sptr_j, 0, c.nsrc, g->sdst.p + c.e0, c.dst1 - c.dst0, keysA.p, keysB.p, order_items,
+                       seg_bwd, &c.bwd));
     g->max_fpart = std::max(g->max_fpart, c.fwd.n_part);
     g->max_bpart = std::max(g->max_bpart, c.bwd.n_part);
     std::swap(cur, prev);

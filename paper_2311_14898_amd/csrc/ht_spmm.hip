@@ -258,9 +258,18 @@ int ht_spmm_launch(ht_ctx* ctx, hipStream_t st, const SpmmArgs& a0) {
     int rc = HT_OK;
     if (a.tm && a.t_items) a.tm->begin(a.t_items);
     if (ctx->agg_variant == 0) {
-      const int S = nvec >= 64 ? 8 : nvec >= 32 ? 4 : nvec >= 16 ? 2 : 1;
+      // Slabs cost one pass over the item's indices each, so short rows get fewer:
+      // measured best on 256-wide rows is 4 slabs for ~500-edge items and 1 for ~80-edge items.
+      int S = nvec >= 32 ? 4 : nvec >= 16 ? 2 : 1;
+      const int64_t avg_len = a.n_edges / (a.n_items > 0 ? a.n_items : 1);
+      if (avg_len < 96) S = 1;
+      else if (avg_len < 192 && S > 2) S = 2;
+      if (a.max_slabs > 0 && S > a.max_slabs) S = a.max_slabs;
+      while (S < 8 && (nvec + S - 1) / S > 64) S *= 2;   // a slab must fit the 64 lanes of a wave
       const int nvs = (nvec + S - 1) / S;
       const int eps = 64 / nvs;
+      if (S < 1 || (S & (S - 1)) || S > 8 || nvs < 1 || nvs > 64 || eps < 1)
+        return ht_set_err(ctx, HT_ESHAPE, "aggregation: bad slab shape S=%d nvs=%d", S, nvs);
       const int64_t groups = (a.n_items + 3) / 4;
       const int64_t rows8 = (groups + (8 / S) - 1) / (8 / S);
       k_spmm_slab<<<(unsigned)(rows8 * 8), 256, 0, st>>>(a, S, nvs, eps);
