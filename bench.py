@@ -96,6 +96,8 @@ def main():
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--scale", type=float, default=1.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cache", choices=["adjacent", "all"], default="adjacent",
+                    help="neighbour-row buffer: reuse between adjacent chunks only, or keep every row once loaded")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a 1 GiB device copy kernel (known traffic) to scale rocprofv3 byte counters")
     args = ap.parse_args()
@@ -111,7 +113,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     w = inputs.WORKLOADS[args.workload].scaled(args.scale)
-    host = w.residency == "host"
+    host = w.residency in ("host", "host_all")
     t_gen = time.perf_counter()
     src, dst = inputs.rmat_edges(w.V, w.E, w.graph_seed, device="cuda")
     X = inputs.features(w.V, w.dims[0])
@@ -121,13 +123,14 @@ def main():
     t_gen = time.perf_counter() - t_gen
 
     ctx = B.ht_ctx_create(0)
-    g = B.ht_partition(ctx, w.V, src, dst, w.n_chunks)
+    g = B.ht_partition(ctx, w.V, src, dst, w.n_chunks, cache_rows=-1 if args.cache == "all" else 0)
     info = B.ht_graph_info_get(g)
     Xd = B.to_matrix(X, B.HT_LOC_HOST_PINNED if host else B.HT_LOC_DEVICE)
     yd = y.cuda()
     Wd = [x.clone().cuda() for x in Ws]
     res = B.HT_RES_HOST if host else B.HT_RES_AUTO
-    plan = dict(res_h=res, res_a=res, res_g=res)
+    # "host": vertex data (h^l, grad h^l) in pinned host memory; "host_all": the checkpoints a^l too
+    plan = dict(res_h=res, res_g=res, res_a=B.HT_RES_HOST if w.residency == "host_all" else B.HT_RES_AUTO)
 
     if args.calib_copy:
         a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
@@ -180,7 +183,8 @@ def main():
                       "scale": args.scale},
            "gteps": gteps, "hbm_gbps_dominant_kernel": achieved, "loss": loss,
            "partition_ms": info.partition_ms, "alpha": info.alpha, "v_ori": info.v_ori, "v_ru": info.v_ru,
-           "dedup_row_savings": 1.0 - info.v_ru / max(info.v_ori, 1),
+           "dedup_row_savings": 1.0 - info.v_ru / max(info.v_ori, 1), "v_load": info.v_load, "cache": args.cache,
+           "cache_rows": info.cache_rows,
            "phase_ms_per_step": {k: tot[k] / args.steps for k in
                                  ("t_gather_ms", "t_spmm_fwd_ms", "t_spmm_bwd_ms", "t_gemm_ms", "t_loss_ms", "t_copy_ms",
                                   "t_cpu_accum_ms", "t_update_ms", "t_agg_fix_ms")},

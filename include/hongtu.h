@@ -96,7 +96,10 @@ typedef struct {
                              HT_BALANCE_VERTICES: b_j = floor(j V / n)                  */
   int32_t ptr_loc;        /* where src/dst live: HT_PTR_DEVICE or HT_PTR_HOST (any host memory) */
   int32_t reserved;
-  int64_t cache_rows;     /* rows of the in-place neighbour buffer; 0 = max_j |N_j|     */
+  int64_t cache_rows;     /* rows of the in-place neighbour buffer: 0 = max_j |N_j| (rows of
+                             N_j ^ N_{j-1} are reused, the rest evicted, as in Sec. 5.1);
+                             > 0 = that many rows, same policy; -1 = as many rows as there are
+                             distinct sources: a row once loaded stays for the whole pass    */
 } ht_part_opts;
 
 /* Edge list (src[i] -> dst[i]), 0 <= id < V < 2^31, E >= 0, duplicates kept.
@@ -124,6 +127,8 @@ typedef struct {
   int64_t max_nnz;  /* max_j E'_j                                       */
   int64_t cache_rows;
   int64_t hbm_bytes;    /* device bytes held by the graph object        */
+  int64_t v_load;       /* rows loaded per pass with this buffer (= v_ru
+                           unless cache_rows = -1)                      */
   double partition_ms;  /* wall time of ht_partition                    */
 } ht_graph_info;
 

@@ -43,7 +43,7 @@ class ht_graph_info(C.Structure):
     _fields_ = [("V", C.c_int64), ("E_stored", C.c_int64), ("n_chunks", C.c_int32), ("reserved", C.c_int32),
                 ("v_ori", C.c_int64), ("v_ru", C.c_int64), ("alpha", C.c_double), ("max_nsrc", C.c_int64),
                 ("max_ndst", C.c_int64), ("max_nnz", C.c_int64), ("cache_rows", C.c_int64), ("hbm_bytes", C.c_int64),
-                ("partition_ms", C.c_double)]
+                ("v_load", C.c_int64), ("partition_ms", C.c_double)]
 
 
 class ht_chunk_info(C.Structure):

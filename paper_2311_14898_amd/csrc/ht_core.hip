@@ -83,32 +83,31 @@ hipEvent_t ht_event(ht_ctx* ctx) {
   return ctx->ev_pool[ctx->ev_next++];
 }
 
-void Timer::begin(double* acc) {
-  if (!on) return;
+int Timer::begin_on(double* acc, hipStream_t s) {
+  if (!on) return -1;
   hipEvent_t a = ht_event(ctx), b = ht_event(ctx);
   if (!a || !b) {
     on = false;
-    return;
+    return -1;
   }
-  (void)hipEventRecord(a, st);
-  ev.emplace_back(a, b);
-  dst.push_back(acc);
+  (void)hipEventRecord(a, s);
+  ev.push_back(Ent{a, b, s, acc});
+  return (int)ev.size() - 1;
 }
 
-void Timer::end() {
-  if (!on || ev.empty()) return;
-  (void)hipEventRecord(ev.back().second, st);
+void Timer::end_id(int id) {
+  if (!on || id < 0 || id >= (int)ev.size()) return;
+  (void)hipEventRecord(ev[id].b, ev[id].s);
 }
 
 int Timer::resolve() {
   for (size_t i = 0; i < ev.size(); ++i) {
     float ms = 0.f;
-    hipError_t e = hipEventElapsedTime(&ms, ev[i].first, ev[i].second);
+    hipError_t e = hipEventElapsedTime(&ms, ev[i].a, ev[i].b);
     if (e != hipSuccess) return ht_set_err(ctx, HT_EHIP, "hipEventElapsedTime: %s", hipGetErrorString(e));
-    *dst[i] += (double)ms;
+    *ev[i].dst += (double)ms;
   }
   ev.clear();
-  dst.clear();
   return HT_OK;
 }
 
@@ -126,6 +125,9 @@ int ht_ctx_create(ht_ctx** out, int device, void* hip_stream) {
   if (!c) return HT_ENOMEM;
   c->device = device;
   if (const char* v = getenv("HT_AGG_VARIANT")) c->agg_variant = atoi(v);
+  if (const char* v = getenv("HT_LINK_BLOCKS")) c->link_blocks = atoi(v) > 0 ? atoi(v) : 64;
+  if (const char* v = getenv("HT_NO_LINK_FENCE")) c->no_link_fence = atoi(v);
+  if (const char* v = getenv("HT_LINK_MEMCPY")) c->link_memcpy = atoi(v);
   if (const char* v = getenv("HT_SLABS_FWD")) c->slabs_fwd = atoi(v);
   if (const char* v = getenv("HT_SLABS_BWD")) c->slabs_bwd = atoi(v);
   if (hip_stream) {
@@ -137,7 +139,7 @@ int ht_ctx_create(ht_ctx** out, int device, void* hip_stream) {
     }
     c->own_stream = true;
   }
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < 3; ++i)
     if (hipStreamCreate(&c->side[i]) != hipSuccess) {
       delete c;
       return HT_EHIP;
@@ -150,7 +152,7 @@ int ht_ctx_destroy(ht_ctx* ctx) {
   if (!ctx) return HT_EINVAL;
   (void)hipSetDevice(ctx->device);
   (void)hipStreamSynchronize(ctx->stream);
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < 3; ++i)
     if (ctx->side[i]) {
       (void)hipStreamSynchronize(ctx->side[i]);
       (void)hipStreamDestroy(ctx->side[i]);
@@ -169,7 +171,7 @@ int ht_ctx_destroy(ht_ctx* ctx) {
 int ht_sync(ht_ctx* ctx) {
   if (!ctx) return HT_EINVAL;
   HT_HIP(ctx, hipStreamSynchronize(ctx->stream));
-  for (int i = 0; i < 2; ++i) HT_HIP(ctx, hipStreamSynchronize(ctx->side[i]));
+  for (int i = 0; i < 3; ++i) HT_HIP(ctx, hipStreamSynchronize(ctx->side[i]));
   return HT_OK;
 }
 

@@ -26,7 +26,7 @@ struct ht_ctx {
   int device = 0;
   hipStream_t stream = nullptr;
   bool own_stream = false;
-  hipStream_t side[2] = {nullptr, nullptr};  // copy / gather streams
+  hipStream_t side[3] = {nullptr, nullptr, nullptr};  // input (gather / H2D), output (D2H), host-function streams
   std::string err;
   int64_t hbm_budget = 0;  // 0 = unlimited
   int64_t hbm_used = 0;
@@ -39,6 +39,9 @@ struct ht_ctx {
   // pinned host scratch (D2H staging of gradient rows)
   void* hscratch[2] = {nullptr, nullptr};
   size_t hscratch_bytes[2] = {0, 0};
+  int no_link_fence = 0;  // 1: let aggregation kernels overlap link traffic (HT_NO_LINK_FENCE, for A/B runs)
+  int link_blocks = 64;   // workgroups of a kernel that moves rows over the host link (HT_LINK_BLOCKS)
+  int link_memcpy = 0;    // 1: use hipMemcpyAsync for contiguous host<->device row ranges (HT_LINK_MEMCPY)
   int slabs_fwd = 0, slabs_bwd = 0;  // caps on feature slabs (HT_SLABS_FWD / HT_SLABS_BWD), 0 = by width
   int agg_variant = 0;  // 0: feature slabs per XCD; 1: full-width rows per wave (HT_AGG_VARIANT, for A/B runs)
   int n_threads = 0;  // host threads for CPU-side accumulation (0 = decide on first use)
@@ -163,15 +166,16 @@ struct ht_graph {
   DevArr<int32_t> sdst;        // [E'] local destinations grouped by local source
   DevArr<int32_t> slot;        // [v_ori] buffer position of N_j[i]
   DevArr<int32_t> gslot;       // [v_ori] slot | (1<<31 when N_j[i] is newly loaded)
-  DevArr<int32_t> reuse;       // [v_ori - v_ru]
-  DevArr<int32_t> load;        // [v_ru]
-  DevArr<int32_t> load_slot;   // [v_ru]
-  DevArr<int32_t> leave;       // [v_ru] N_j \ N_{j+1} (all of N_{n-1} for the last chunk)
-  DevArr<int32_t> leave_slot;  // [v_ru]
-  int64_t v_ori = 0, v_ru = 0;
+  DevArr<int32_t> reuse;       // [v_ori - v_load]
+  DevArr<int32_t> load;        // [v_load]
+  DevArr<int32_t> load_slot;   // [v_load]
+  DevArr<int32_t> leave;       // [v_load] rows leaving after each chunk (everything still buffered after the last)
+  DevArr<int32_t> leave_slot;  // [v_load]
+  int64_t v_ori = 0, v_ru = 0, v_load = 0;  // v_load: rows actually loaded per pass with this buffer
   int64_t max_nsrc = 0, max_ndst = 0, max_nnz = 0, max_fpart = 0, max_bpart = 0;
   int64_t cache_rows = 0;
   double partition_ms = 0.0;
+  mutable std::vector<int32_t> leave_host;  // host copy of `leave`, made on first use by the CPU-side adds
   int64_t hbm_bytes() const;
 };
 
@@ -216,7 +220,9 @@ int ht_spmm_launch(ht_ctx* ctx, hipStream_t st, const SpmmArgs& a);
 // dst[dst_idx[k]] = scale[src_idx[k]] * src[src_idx[k]]   (scale nullable)
 int ht_gather_rows(ht_ctx* ctx, hipStream_t st, const float* src, int64_t src_ld, const int32_t* src_idx,
                    float* dst, int64_t dst_ld, const int32_t* dst_idx, int64_t n_rows, int32_t d,
-                   const float* scale);
+                   const float* scale, int max_blocks = 0);
+// Contiguous copy by a kernel with a small grid; src/dst may be device or GPU-addressable host memory.
+int ht_copy_link(ht_ctx* ctx, hipStream_t st, void* dst, const void* src, size_t bytes, int blocks);
 // dst[dst_idx[k]] += src[src_idx[k]]  (dst_idx unique inside one call)
 int ht_add_rows(ht_ctx* ctx, hipStream_t st, const float* src, int64_t src_ld, const int32_t* src_idx,
                 float* dst, int64_t dst_ld, const int32_t* dst_idx, int64_t n_rows, int32_t d);
@@ -241,16 +247,22 @@ int ht_softmax_ce(ht_ctx* ctx, hipStream_t st, const float* logits, int64_t ld, 
 int ht_sgd(ht_ctx* ctx, hipStream_t st, float* W, const float* dW, int64_t n, float lr);
 int ht_fill_zero(ht_ctx* ctx, hipStream_t st, void* p, size_t bytes);
 
-// stats helpers
+// stats helpers: HIP-event pairs around phases, each on the stream that runs the phase
 struct Timer {
   ht_ctx* ctx;
-  hipStream_t st;
+  hipStream_t st;  // default stream for begin()/end()
   bool on;
-  std::vector<std::pair<hipEvent_t, hipEvent_t>> ev;
-  std::vector<double*> dst;
+  struct Ent {
+    hipEvent_t a, b;
+    hipStream_t s;
+    double* dst;
+  };
+  std::vector<Ent> ev;
   Timer(ht_ctx* c, hipStream_t s, bool enabled) : ctx(c), st(s), on(enabled) {}
-  void begin(double* acc);
-  void end();
-  int resolve();  // after the stream is synchronised
+  void begin(double* acc) { begin_on(acc, st); }
+  void end() { end_id((int)ev.size() - 1); }
+  int begin_on(double* acc, hipStream_t s);  // returns an id for end_id (-1 when timing is off)
+  void end_id(int id);
+  int resolve();  // after the streams are synchronised
 };
 hipEvent_t ht_event(ht_ctx* ctx);

@@ -12,6 +12,8 @@
 //            (CPU-side add when that home is host memory).
 #include <algorithm>
 #include <cstring>
+#include <condition_variable>
+#include <mutex>
 #include <thread>
 
 #include "ht_internal.h"
@@ -105,38 +107,85 @@ double spmm_alg_bytes(const ChunkMeta& c, int d) {
   return 4.0 * c.nnz + 8.0 * nd + 4.0 * d * (double)c.nsrc + 4.0 * d * nd + 4.0 * ((double)c.nsrc + nd);
 }
 
-// Aggregate of chunk j into out rows [0, ndst) (pitch out_ld).  `Hin` is the
-// GPU-usable pointer of H_in.  buffer mode keeps N_j's rows (pre-scaled by s_u)
-// in ctx scratch HT_S_NBUF.
-int aggregate_chunk(Run& R, int j, bool buffer, const ht_tensor* H_in, const float* Hin, int d, float* out,
-                    int64_t out_ld) {
+// Streams of the per-chunk pipeline: compute on the context's stream, neighbour
+// gather / H2D row copies on side[0], D2H row copies on side[1], host functions
+// (CPU-side gradient accumulation) on side[2].  Stages are ordered by events.
+struct Pipe {
+  ht_ctx* ctx;
+  hipStream_t s_c, s_in, s_out, s_host;
+  bool used_in = false, used_out = false, used_host = false;
+  explicit Pipe(ht_ctx* c) : ctx(c), s_c(c->stream), s_in(c->side[0]), s_out(c->side[1]), s_host(c->side[2]) {}
+  // A failed call must not leave side-stream work that refers to the caller's locals.
+  ~Pipe() {
+    if (used_in) (void)hipStreamSynchronize(s_in);
+    if (used_out) (void)hipStreamSynchronize(s_out);
+    if (used_host) (void)hipStreamSynchronize(s_host);
+  }
+  int rec(hipStream_t s, hipEvent_t* out) {
+    hipEvent_t e = ht_event(ctx);
+    if (!e) return ht_set_err(ctx, HT_EHIP, "hipEventCreate failed");
+    HT_HIP(ctx, hipEventRecord(e, s));
+    *out = e;
+    return HT_OK;
+  }
+  int wait(hipStream_t s, hipEvent_t e) {
+    if (!e) return HT_OK;
+    HT_HIP(ctx, hipStreamWaitEvent(s, e, 0));
+    return HT_OK;
+  }
+  // Link traffic and the aggregation kernels are kept apart in time: run together both slow
+  // down several-fold on this GPU (measured), while the dense transforms and the host-side
+  // adds overlap with link traffic at no cost.
+  hipEvent_t last_in = nullptr, last_out = nullptr, quiet = nullptr;
+  bool fence = false;
+  int link_begin(hipStream_t s) { return fence ? wait(s, quiet) : HT_OK; }
+  int link_end(hipStream_t s) {
+    if (!fence) return HT_OK;
+    return rec(s, s == s_in ? &last_in : &last_out);
+  }
+  int agg_begin() {
+    if (!fence) return HT_OK;
+    HT_TRY(wait(s_c, last_in));
+    return wait(s_c, last_out);
+  }
+  int agg_end() { return fence ? rec(s_c, &quiet) : HT_OK; }
+};
+
+// Rows of N_j \ N_{j-1} from H_in (HBM or pinned host, read in place by the
+// kernel) into their positions of the in-place neighbour buffer, scaled by s_u
+// on the way (Alg. 2 lines 2-3).
+int gather_chunk(Run& R, int j, const ht_tensor* H_in, const float* Hin, int d, float* nbuf, hipStream_t st) {
+  const ht_graph* g = R.g;
+  const ChunkMeta& c = g->chunks[j];
+  const int id = R.tm.begin_on(&R.st->t_gather_ms, st);
+  HT_TRY(ht_gather_rows(R.ctx, st, Hin, H_in->ld, g->load.p + c.load_off, nbuf, H_in->ld, g->load_slot.p + c.load_off,
+                        c.n_load, d, g->s.p, H_in->loc == HT_LOC_HOST_PINNED ? R.ctx->link_blocks : 0));
+  R.tm.end_id(id);
+  R.st->rows_loaded += c.n_load;
+  R.st->rows_reused += c.n_reuse;
+  if (H_in->loc == HT_LOC_HOST_PINNED) R.st->bytes_h2d += (int64_t)c.n_load * d * 4;
+  R.st->bytes_h2d_nodedup += (int64_t)c.nsrc * d * 4;
+  return HT_OK;
+}
+
+// Aggregate of chunk j into out rows [0, ndst) (pitch out_ld) on the compute
+// stream.  src/src_ld: H_in read in place, or the neighbour buffer (rows already
+// scaled by s_u, indexed by buffer position).
+int spmm_chunk(Run& R, int j, bool buffer, const float* src, int64_t src_ld, int d, float* out, int64_t out_ld) {
   ht_ctx* ctx = R.ctx;
   const ht_graph* g = R.g;
   const ChunkMeta& c = g->chunks[j];
   hipStream_t st = ctx->stream;
-  const int64_t ndst = c.dst1 - c.dst0;
-  if (ndst == 0) return HT_OK;
-  float* nbuf = nullptr;
-  if (buffer) {
-    HT_TRY(ht_scratch(ctx, HT_S_NBUF, (size_t)g->cache_rows * H_in->ld * 4, (void**)&nbuf));
-    R.tm.begin(&R.st->t_gather_ms);
-    HT_TRY(ht_gather_rows(ctx, st, Hin, H_in->ld, g->load.p + c.load_off, nbuf, H_in->ld, g->load_slot.p + c.load_off,
-                          c.n_load, d, g->s.p));
-    R.tm.end();
-    R.st->rows_loaded += c.n_load;
-    R.st->rows_reused += c.n_reuse;
-    if (H_in->loc == HT_LOC_HOST_PINNED) R.st->bytes_h2d += (int64_t)c.n_load * d * 4;
-    R.st->bytes_h2d_nodedup += (int64_t)c.nsrc * d * 4;
-  }
   float* partial = nullptr;
   if (c.fwd.n_part > 0) HT_TRY(ht_scratch(ctx, HT_S_SPART, (size_t)g->max_fpart * out_ld * 4, (void**)&partial));
   SpmmArgs a{};
-  a.it_row = c.fwd.row; a.it_e0 = c.fwd.e0; a.it_len = c.fwd.len; a.it_part = c.fwd.part; a.n_items = c.fwd.n_items; a.n_edges = c.nnz;
+  a.it_row = c.fwd.row; a.it_e0 = c.fwd.e0; a.it_len = c.fwd.len; a.it_part = c.fwd.part; a.n_items = c.fwd.n_items;
+  a.n_edges = c.nnz;
   a.fx_row = c.fwd.fx_row; a.fx_part0 = c.fwd.fx_part0; a.fx_nseg = c.fwd.fx_nseg; a.n_fix = c.fwd.n_fix;
   a.idx = (buffer ? g->col_slot.p : g->col.p) + c.e0;
   a.ew = buffer ? nullptr : g->s.p;
-  a.src = buffer ? nbuf : Hin;
-  a.src_ld = H_in->ld;
+  a.src = src;
+  a.src_ld = src_ld;
   a.d = d;
   a.out = out; a.out_ld = out_ld; a.out_idx = nullptr;
   a.post = g->s.p + c.dst0; a.post_idx = nullptr;
@@ -166,11 +215,37 @@ int resolve_gather(ht_ctx* ctx, int mode, const ht_tensor* t, bool* buffer) {
   return HT_OK;
 }
 
+// Contiguous row range between HBM and pinned host memory.  host_gpu is the
+// GPU-usable alias of the host side (dst for D2H, src for H2D).
+int copy_rows(Run& R, hipStream_t st, void* dst, const void* src, size_t bytes, hipMemcpyKind kind) {
+  if (bytes == 0) return HT_OK;
+  ht_ctx* ctx = R.ctx;
+  const int id = R.tm.begin_on(&R.st->t_copy_ms, st);
+  if (ctx->link_memcpy) {
+    HT_HIP(ctx, hipMemcpyAsync(dst, src, bytes, kind, st));
+  } else {
+    void* d = dst;
+    const void* s = src;
+    void* mapped = nullptr;
+    if (kind == hipMemcpyDeviceToHost) {
+      HT_HIP(ctx, hipHostGetDevicePointer(&mapped, dst, 0));
+      d = mapped;
+    } else if (kind == hipMemcpyHostToDevice) {
+      HT_HIP(ctx, hipHostGetDevicePointer(&mapped, const_cast<void*>(src), 0));
+      s = mapped;
+    }
+    HT_TRY(ht_copy_link(ctx, st, d, s, bytes, ctx->link_blocks));
+  }
+  R.tm.end_id(id);
+  if (kind == hipMemcpyHostToDevice) R.st->bytes_h2d += (int64_t)bytes;
+  if (kind == hipMemcpyDeviceToHost) R.st->bytes_d2h += (int64_t)bytes;
+  return HT_OK;
+}
+
 int layer_fwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* H_in, const float* W, ht_tensor* H_out,
                    ht_tensor* A_ckpt) {
   ht_ctx* ctx = R.ctx;
   const ht_graph* g = R.g;
-  hipStream_t st = ctx->stream;
   const int di = desc->d_in, dn = desc->d_out;
   HT_TRY(check_tensor(ctx, H_in, g->V, di, "H_in"));
   HT_TRY(check_tensor(ctx, H_out, g->V, dn, "H_out"));
@@ -182,55 +257,173 @@ int layer_fwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* H_in, con
   HT_TRY(gpu_ptr(ctx, H_in, &Hin));
 
   const bool a_dev = A_ckpt && A_ckpt->loc == HT_LOC_DEVICE;
+  const bool a_host = A_ckpt && !a_dev;
   const bool h_dev = H_out->loc == HT_LOC_DEVICE;
+  const bool staged = a_host || !h_dev;                              // some rows leave through the output stream
+  const bool side_in = buffer && H_in->loc == HT_LOC_HOST_PINNED;    // gather runs beside the compute
   const int64_t a_ld = A_ckpt ? A_ckpt->ld : ((di + 3) & ~3);
-  float* a_chunk = nullptr;
-  float* h_chunk = nullptr;
-  if (!a_dev) HT_TRY(ht_scratch(ctx, HT_S_ACHUNK, (size_t)std::max<int64_t>(g->max_ndst, 1) * a_ld * 4, (void**)&a_chunk));
-  if (!h_dev) HT_TRY(ht_scratch(ctx, HT_S_OCHUNK, (size_t)std::max<int64_t>(g->max_ndst, 1) * H_out->ld * 4, (void**)&h_chunk));
+  const int64_t mx = std::max<int64_t>(g->max_ndst, 1);
+  float* a_stage[2] = {nullptr, nullptr};
+  float* h_stage[2] = {nullptr, nullptr};
+  float* nbuf = nullptr;
+  if (!a_dev) {
+    HT_TRY(ht_scratch(ctx, HT_S_ACHUNK, (size_t)mx * a_ld * 4 * 2, (void**)&a_stage[0]));
+    a_stage[1] = a_stage[0] + mx * a_ld;
+  }
+  if (!h_dev) {
+    HT_TRY(ht_scratch(ctx, HT_S_OCHUNK, (size_t)mx * H_out->ld * 4 * 2, (void**)&h_stage[0]));
+    h_stage[1] = h_stage[0] + mx * H_out->ld;
+  }
+  if (buffer) HT_TRY(ht_scratch(ctx, HT_S_NBUF, (size_t)g->cache_rows * H_in->ld * 4, (void**)&nbuf));
 
+  Pipe P(ctx);
+  P.fence = (side_in || staged) && !ctx->no_link_fence;
+  if (side_in) {
+    hipEvent_t ev_start = nullptr;
+    HT_TRY(P.rec(P.s_c, &ev_start));
+    HT_TRY(P.wait(P.s_in, ev_start));
+    P.used_in = true;
+  }
+  hipEvent_t ev_out[2] = {nullptr, nullptr};   // D2H of the staging pair b has finished
+  hipEvent_t ev_agg_prev = nullptr;            // the previous chunk's aggregation has read the buffer
+  int q = 0;
   for (int j = 0; j < g->n; ++j) {
     const ChunkMeta& c = g->chunks[j];
     const int64_t ndst = c.dst1 - c.dst0;
     if (ndst == 0) continue;
-    float* a_dst = a_dev ? A_ckpt->ptr + c.dst0 * a_ld : a_chunk;
-    HT_TRY(aggregate_chunk(R, j, buffer, H_in, Hin, di, a_dst, a_ld));
-    if (A_ckpt && !a_dev) {
-      R.tm.begin(&R.st->t_copy_ms);
-      HT_HIP(ctx, hipMemcpyAsync(A_ckpt->ptr + c.dst0 * a_ld, a_chunk, (size_t)ndst * a_ld * 4, hipMemcpyDeviceToHost, st));
-      R.tm.end();
-      R.st->bytes_d2h += ndst * a_ld * 4;
+    const int b = q & 1;
+    ++q;
+    if (buffer) {
+      if (side_in) {
+        HT_TRY(P.wait(P.s_in, ev_agg_prev));   // the buffer is updated in place
+        HT_TRY(P.link_begin(P.s_in));
+        HT_TRY(gather_chunk(R, j, H_in, Hin, di, nbuf, P.s_in));
+        HT_TRY(P.link_end(P.s_in));
+        hipEvent_t ev_g = nullptr;
+        HT_TRY(P.rec(P.s_in, &ev_g));
+        HT_TRY(P.wait(P.s_c, ev_g));
+      } else {
+        HT_TRY(gather_chunk(R, j, H_in, Hin, di, nbuf, P.s_c));
+      }
     }
-    float* h_dst = h_dev ? H_out->ptr + c.dst0 * H_out->ld : h_chunk;
+    if (staged) HT_TRY(P.wait(P.s_c, ev_out[b]));
+    float* a_dst = a_dev ? A_ckpt->ptr + c.dst0 * a_ld : a_stage[b];
+    HT_TRY(P.agg_begin());
+    HT_TRY(spmm_chunk(R, j, buffer, buffer ? nbuf : Hin, H_in->ld, di, a_dst, a_ld));
+    HT_TRY(P.agg_end());
+    if (side_in) HT_TRY(P.rec(P.s_c, &ev_agg_prev));
+    float* h_dst = h_dev ? H_out->ptr + c.dst0 * H_out->ld : h_stage[b];
     R.tm.begin(&R.st->t_gemm_ms);
-    HT_TRY(ht_gemm_nn(ctx, st, a_dst, a_ld, W, h_dst, H_out->ld, ndst, di, dn, desc->act == HT_ACT_RELU));
+    HT_TRY(ht_gemm_nn(ctx, P.s_c, a_dst, a_ld, W, h_dst, H_out->ld, ndst, di, dn, desc->act == HT_ACT_RELU));
     R.tm.end();
     R.st->n_gemm += 1;
     R.st->gemm_flops += 2.0 * ndst * di * dn;
-    if (!h_dev) {
-      R.tm.begin(&R.st->t_copy_ms);
-      HT_HIP(ctx, hipMemcpyAsync(H_out->ptr + c.dst0 * H_out->ld, h_chunk, (size_t)ndst * H_out->ld * 4,
-                                 hipMemcpyDeviceToHost, st));
-      R.tm.end();
-      R.st->bytes_d2h += ndst * H_out->ld * 4;
+    if (staged) {
+      hipEvent_t ev_c = nullptr;
+      HT_TRY(P.rec(P.s_c, &ev_c));
+      HT_TRY(P.wait(P.s_out, ev_c));
+      HT_TRY(P.link_begin(P.s_out));
+      P.used_out = true;
+      if (a_host)
+        HT_TRY(copy_rows(R, P.s_out, A_ckpt->ptr + c.dst0 * a_ld, a_stage[b], (size_t)ndst * a_ld * 4, hipMemcpyDeviceToHost));
+      if (!h_dev)
+        HT_TRY(copy_rows(R, P.s_out, H_out->ptr + c.dst0 * H_out->ld, h_stage[b], (size_t)ndst * H_out->ld * 4,
+                         hipMemcpyDeviceToHost));
+      HT_TRY(P.link_end(P.s_out));
+      HT_TRY(P.rec(P.s_out, &ev_out[b]));
     }
   }
+  // later work on the compute stream sees every row at its home
+  HT_TRY(P.wait(P.s_c, ev_out[0]));
+  HT_TRY(P.wait(P.s_c, ev_out[1]));
+  P.used_in = P.used_out = false;   // everything is ordered behind the compute stream now
   return HT_OK;
 }
 
-// Rows [r0, r0+n) of t on the device: in place when t is in HBM, else copied into `staging`.
-int rows_on_device(Run& R, const ht_tensor* t, int64_t r0, int64_t n, float* staging, const float** out) {
-  if (t->loc == HT_LOC_DEVICE) {
-    *out = t->ptr + r0 * t->ld;
-    return HT_OK;
+struct AccTask {
+  hipEvent_t ready;   // the D2H of `rows` has finished
+  float* grad;
+  int64_t ld;
+  const int32_t* ids;
+  const float* rows;
+  int64_t rows_ld;
+  int64_t n;
+  int d;
+};
+
+// Host-side gradient accumulation beside the GPU work (Alg. 3 line 7).  A worker
+// thread waits for each task's D2H event on the host and adds the rows; the
+// enqueueing thread only blocks when it is about to reuse a staging buffer whose
+// task has not finished.  (A host function enqueued in a HIP stream would do the
+// same, but it occupies a hardware queue other streams share while it runs.)
+class AccWorker {
+ public:
+  AccWorker(ht_ctx* ctx) : ctx_(ctx) {}
+  ~AccWorker() { finish(); }
+  void start() {
+    if (!th_.joinable()) th_ = std::thread([this] { run(); });
   }
-  R.tm.begin(&R.st->t_copy_ms);
-  HT_HIP(R.ctx, hipMemcpyAsync(staging, t->ptr + r0 * t->ld, (size_t)n * t->ld * 4, hipMemcpyHostToDevice, R.ctx->stream));
-  R.tm.end();
-  R.st->bytes_h2d += n * t->ld * 4;
-  *out = staging;
-  return HT_OK;
-}
+  void push(const AccTask& t) {
+    std::lock_guard<std::mutex> lk(mu_);
+    q_.push_back(t);
+    cv_.notify_all();
+  }
+  // block until at least `count` tasks have completed
+  void wait_done(int64_t count) {
+    std::unique_lock<std::mutex> lk(mu_);
+    cv_.wait(lk, [&] { return done_ >= count || failed_; });
+  }
+  void finish() {
+    if (!th_.joinable()) return;
+    {
+      std::lock_guard<std::mutex> lk(mu_);
+      stop_ = true;
+      cv_.notify_all();
+    }
+    th_.join();
+  }
+  bool failed() const { return failed_; }
+  double ms() const { return ms_; }
+
+ private:
+  void run() {
+    (void)hipSetDevice(ctx_->device);
+    int64_t next = 0;
+    for (;;) {
+      AccTask t;
+      {
+        std::unique_lock<std::mutex> lk(mu_);
+        cv_.wait(lk, [&] { return stop_ || next < (int64_t)q_.size(); });
+        if (next >= (int64_t)q_.size()) return;   // stop requested and queue drained
+        t = q_[next];
+      }
+      if (hipEventSynchronize(t.ready) != hipSuccess) {
+        std::lock_guard<std::mutex> lk(mu_);
+        failed_ = true;
+        cv_.notify_all();
+        return;
+      }
+      auto t0 = std::chrono::steady_clock::now();
+      cpu_accumulate(ctx_, t.grad, t.ld, t.ids, t.rows, t.rows_ld, t.n, t.d);
+      const double ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+      {
+        std::lock_guard<std::mutex> lk(mu_);
+        ms_ += ms;
+        ++next;
+        done_ = next;
+        cv_.notify_all();
+      }
+    }
+  }
+  ht_ctx* ctx_;
+  std::thread th_;
+  std::mutex mu_;
+  std::condition_variable cv_;
+  std::vector<AccTask> q_;
+  int64_t done_ = 0;
+  bool stop_ = false, failed_ = false;
+  double ms_ = 0.0;
+};
 
 int layer_bwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* ckpt, const float* W, const ht_tensor* dH_out,
                    const ht_tensor* H_out, ht_tensor* dH_in, float* dW) {
@@ -246,145 +439,242 @@ int layer_bwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* ckpt, con
   if (desc->ckpt_kind != HT_CKPT_AGG && desc->ckpt_kind != HT_CKPT_INPUT)
     return ht_set_err(ctx, HT_EINVAL, "unknown checkpoint kind %d", desc->ckpt_kind);
   const bool relu = desc->act == HT_ACT_RELU;
+  const bool agg_ckpt = desc->ckpt_kind == HT_CKPT_AGG;
   const int64_t mx = std::max<int64_t>(g->max_ndst, 1);
   const int64_t ld_i = (di + 3) & ~3, ld_o = (dn + 3) & ~3;
 
   // forward-side inputs
   bool agg_buffer = false;
   float* Hin = nullptr;
-  if (desc->ckpt_kind == HT_CKPT_INPUT) {
+  float* nbuf = nullptr;
+  if (!agg_ckpt) {
     HT_TRY(resolve_gather(ctx, desc->gather_mode, ckpt, &agg_buffer));
     HT_TRY(gpu_ptr(ctx, ckpt, &Hin));
+    if (agg_buffer) HT_TRY(ht_scratch(ctx, HT_S_NBUF, (size_t)g->cache_rows * ckpt->ld * 4, (void**)&nbuf));
   }
   // gradient side: direct accumulation into dH_in (HBM) or through the in-place gradient buffer
   bool gbuffer = false;
   if (dH_in) HT_TRY(resolve_gather(ctx, desc->gather_mode, dH_in, &gbuffer));
 
-  float *a_chunk = nullptr, *dh_chunk = nullptr, *z_chunk = nullptr, *dz_chunk = nullptr, *da_chunk = nullptr;
-  float* gbuf = nullptr;
-  const int64_t a_ld = desc->ckpt_kind == HT_CKPT_AGG ? ckpt->ld : ld_i;
-  if (desc->ckpt_kind == HT_CKPT_INPUT || ckpt->loc != HT_LOC_DEVICE)
-    HT_TRY(ht_scratch(ctx, HT_S_ACHUNK, (size_t)mx * a_ld * 4, (void**)&a_chunk));
-  if (dH_out->loc != HT_LOC_DEVICE) HT_TRY(ht_scratch(ctx, HT_S_OCHUNK, (size_t)mx * dH_out->ld * 4, (void**)&dh_chunk));
+  const bool a_host = agg_ckpt && ckpt->loc != HT_LOC_DEVICE;
+  const bool dh_host = dH_out->loc != HT_LOC_DEVICE;
+  const bool ho_host = relu && H_out && H_out->loc != HT_LOC_DEVICE;
+  const bool in_host = a_host || dh_host || ho_host;   // some rows arrive through the input stream
+  float* a_stage[2] = {nullptr, nullptr};
+  float* dh_stage[2] = {nullptr, nullptr};
+  float* z_stage[2] = {nullptr, nullptr};
+  float *dz_chunk = nullptr, *da_chunk = nullptr, *gbuf = nullptr;
+  const int64_t a_ld = agg_ckpt ? ckpt->ld : ld_i;
+  if (!agg_ckpt || a_host) {
+    HT_TRY(ht_scratch(ctx, HT_S_ACHUNK, (size_t)mx * a_ld * 4 * 2, (void**)&a_stage[0]));
+    a_stage[1] = a_stage[0] + mx * a_ld;
+  }
+  if (dh_host) {
+    HT_TRY(ht_scratch(ctx, HT_S_OCHUNK, (size_t)mx * dH_out->ld * 4 * 2, (void**)&dh_stage[0]));
+    dh_stage[1] = dh_stage[0] + mx * dH_out->ld;
+  }
   if (relu) {
     const int64_t zl = H_out ? H_out->ld : ld_o;
-    if (!H_out || H_out->loc != HT_LOC_DEVICE) HT_TRY(ht_scratch(ctx, HT_S_ZCHUNK, (size_t)mx * zl * 4, (void**)&z_chunk));
+    if (!H_out || ho_host) {
+      HT_TRY(ht_scratch(ctx, HT_S_ZCHUNK, (size_t)mx * zl * 4 * 2, (void**)&z_stage[0]));
+      z_stage[1] = z_stage[0] + mx * zl;
+    }
     HT_TRY(ht_scratch(ctx, HT_S_DZCHUNK, (size_t)mx * ld_o * 4, (void**)&dz_chunk));
   }
   if (dH_in) {
     HT_TRY(ht_scratch(ctx, HT_S_DACHUNK, (size_t)mx * ld_i * 4, (void**)&da_chunk));
     if (gbuffer) HT_TRY(ht_scratch(ctx, HT_S_MISC, (size_t)g->cache_rows * ld_i * 4, (void**)&gbuf));
   }
-  // host copy of the leave lists for the CPU-side accumulation
-  std::vector<int32_t> leave_host;
+  // CPU-side accumulation (Alg. 3 line 7): host copy of the leave lists, device and pinned staging pairs
   const bool cpu_accum = dH_in && gbuffer && dH_in->loc == HT_LOC_HOST_PINNED;
-  float* leave_dev = nullptr;
-  float* leave_pin = nullptr;
+  constexpr int NLV = 4;   // depth of the leave staging rings: D2H runs ahead of the host-side adds
+  constexpr int64_t LEAVE_BATCH = 262144;   // rows per compaction / D2H / host-add task
+  float* leave_dev[NLV] = {};
+  float* leave_pin[NLV] = {};
   if (cpu_accum) {
     int64_t mxl = 1;
     for (const ChunkMeta& c : g->chunks) mxl = std::max(mxl, c.n_leave);
-    leave_host.resize((size_t)std::max<int64_t>(g->v_ru, 1));
-    HT_HIP(ctx, hipMemcpy(leave_host.data(), g->leave.p, (size_t)g->v_ru * 4, hipMemcpyDeviceToHost));
-    HT_TRY(ht_scratch(ctx, HT_S_LEAVE, (size_t)mxl * ld_i * 4, (void**)&leave_dev));
-    HT_TRY(ht_host_scratch(ctx, 0, (size_t)mxl * ld_i * 4, (void**)&leave_pin));
+    mxl = std::min(mxl, LEAVE_BATCH);
+    if (g->leave_host.empty()) {
+      g->leave_host.resize((size_t)std::max<int64_t>(g->v_load, 1));
+      HT_HIP(ctx, hipMemcpy(g->leave_host.data(), g->leave.p, (size_t)g->v_load * 4, hipMemcpyDeviceToHost));
+    }
+    HT_TRY(ht_scratch(ctx, HT_S_LEAVE, (size_t)mxl * ld_i * 4 * NLV, (void**)&leave_dev[0]));
+    HT_TRY(ht_host_scratch(ctx, 0, (size_t)mxl * ld_i * 4 * NLV, (void**)&leave_pin[0]));
+    for (int k = 1; k < NLV; ++k) {
+      leave_dev[k] = leave_dev[0] + (int64_t)k * mxl * ld_i;
+      leave_pin[k] = leave_pin[0] + (int64_t)k * mxl * ld_i;
+    }
+    (void)host_threads(ctx);
   }
 
+  Pipe P(ctx);
+  AccWorker worker(ctx);   // declared after P: joined before P's destructor waits for the streams
+  if (cpu_accum) worker.start();
+  P.fence = (in_host || cpu_accum) && !ctx->no_link_fence;
+  if (in_host) {
+    hipEvent_t ev_start = nullptr;
+    HT_TRY(P.rec(P.s_c, &ev_start));
+    HT_TRY(P.wait(P.s_in, ev_start));
+    P.used_in = true;
+  }
+  hipEvent_t ev_cdone[2] = {nullptr, nullptr};     // compute that read the input staging pair b has finished
+  hipEvent_t ev_leave_free[NLV] = {};              // D2H out of leave_dev[r] has finished
+  int n_left = 0;
   bool first = true;
+  int q = 0;
   for (int j = 0; j < g->n; ++j) {
     const ChunkMeta& c = g->chunks[j];
     const int64_t ndst = c.dst1 - c.dst0;
-    if (ndst > 0) {
-      // a^l rows of the chunk
-      const float* a_rows = nullptr;
-      if (desc->ckpt_kind == HT_CKPT_AGG) {
-        HT_TRY(rows_on_device(R, ckpt, c.dst0, ndst, a_chunk, &a_rows));
+    if (ndst == 0) continue;   // no destinations: no edges, no neighbours, nothing leaves
+    const int b = q & 1;
+    ++q;
+    // ---- inputs (Alg. 1 lines 14-16)
+    const float* a_rows = nullptr;
+    const float* dh_rows = nullptr;
+    const float* ref = nullptr;
+    int64_t ref_ld = 0;
+    if (in_host) {
+      HT_TRY(P.wait(P.s_in, ev_cdone[b]));
+      HT_TRY(P.link_begin(P.s_in));
+    }
+    if (agg_ckpt) {
+      if (a_host) {
+        HT_TRY(copy_rows(R, P.s_in, a_stage[b], ckpt->ptr + c.dst0 * a_ld, (size_t)ndst * a_ld * 4, hipMemcpyHostToDevice));
+        a_rows = a_stage[b];
       } else {
-        HT_TRY(aggregate_chunk(R, j, agg_buffer, ckpt, Hin, di, a_chunk, a_ld));
-        a_rows = a_chunk;
+        a_rows = ckpt->ptr + c.dst0 * a_ld;
       }
-      const float* dh_rows = nullptr;
-      HT_TRY(rows_on_device(R, dH_out, c.dst0, ndst, dh_chunk, &dh_rows));
-      // dz = dh * ReLU'(z)
-      const float* dz_rows = dh_rows;
-      int64_t dz_ld = dH_out->ld;
-      if (relu) {
-        const float* ref = nullptr;
-        int64_t ref_ld = 0;
-        if (H_out) {
-          HT_TRY(rows_on_device(R, H_out, c.dst0, ndst, z_chunk, &ref));
-          ref_ld = H_out->ld;
-        } else {  // re-forward of the update stage (Alg. 1 line 17)
-          R.tm.begin(&R.st->t_gemm_ms);
-          HT_TRY(ht_gemm_nn(ctx, st, a_rows, a_ld, W, z_chunk, ld_o, ndst, di, dn, 0));
-          R.tm.end();
-          R.st->n_gemm += 1;
-          R.st->gemm_flops += 2.0 * ndst * di * dn;
-          ref = z_chunk;
-          ref_ld = ld_o;
-        }
-        HT_TRY(ht_relu_mask(ctx, st, dh_rows, dH_out->ld, ref, ref_ld, dz_chunk, ld_o, ndst, dn));
-        dz_rows = dz_chunk;
-        dz_ld = ld_o;
+    }
+    if (dh_host) {
+      HT_TRY(copy_rows(R, P.s_in, dh_stage[b], dH_out->ptr + c.dst0 * dH_out->ld, (size_t)ndst * dH_out->ld * 4,
+                       hipMemcpyHostToDevice));
+      dh_rows = dh_stage[b];
+    } else {
+      dh_rows = dH_out->ptr + c.dst0 * dH_out->ld;
+    }
+    if (relu && H_out) {
+      ref_ld = H_out->ld;
+      if (ho_host) {
+        HT_TRY(copy_rows(R, P.s_in, z_stage[b], H_out->ptr + c.dst0 * H_out->ld, (size_t)ndst * H_out->ld * 4,
+                         hipMemcpyHostToDevice));
+        ref = z_stage[b];
+      } else {
+        ref = H_out->ptr + c.dst0 * H_out->ld;
       }
-      R.tm.begin(&R.st->t_gemm_ms);
-      HT_TRY(ht_gemm_tn(ctx, st, a_rows, a_ld, dz_rows, dz_ld, dW, ndst, di, dn, first ? 0 : 1));
-      R.tm.end();
-      R.st->n_gemm += 1;
-      R.st->gemm_flops += 2.0 * ndst * di * dn;
-      first = false;
-      if (dH_in) {
+    }
+    if (in_host) {
+      HT_TRY(P.link_end(P.s_in));
+      hipEvent_t ev_in = nullptr;
+      HT_TRY(P.rec(P.s_in, &ev_in));
+      HT_TRY(P.wait(P.s_c, ev_in));
+    }
+    // ---- compute
+    if (!agg_ckpt) {   // pure recomputation: aggregate again from h^l
+      if (agg_buffer) HT_TRY(gather_chunk(R, j, ckpt, Hin, di, nbuf, st));
+      HT_TRY(P.agg_begin());
+      HT_TRY(spmm_chunk(R, j, agg_buffer, agg_buffer ? nbuf : Hin, ckpt->ld, di, a_stage[b], a_ld));
+      HT_TRY(P.agg_end());
+      a_rows = a_stage[b];
+    }
+    const float* dz_rows = dh_rows;
+    int64_t dz_ld = dH_out->ld;
+    if (relu) {
+      if (!H_out) {  // re-forward of the update stage (Alg. 1 line 17)
         R.tm.begin(&R.st->t_gemm_ms);
-        HT_TRY(ht_gemm_nt(ctx, st, dz_rows, dz_ld, W, da_chunk, ld_i, ndst, dn, di));
+        HT_TRY(ht_gemm_nn(ctx, st, a_rows, a_ld, W, z_stage[0], ld_o, ndst, di, dn, 0));
         R.tm.end();
         R.st->n_gemm += 1;
         R.st->gemm_flops += 2.0 * ndst * di * dn;
-        float* partial = nullptr;
-        const int64_t out_ld = gbuffer ? ld_i : dH_in->ld;
-        if (c.bwd.n_part > 0) HT_TRY(ht_scratch(ctx, HT_S_SPART, (size_t)g->max_bpart * out_ld * 4, (void**)&partial));
-        SpmmArgs a{};
-        a.it_row = c.bwd.row; a.it_e0 = c.bwd.e0; a.it_len = c.bwd.len; a.it_part = c.bwd.part; a.n_items = c.bwd.n_items; a.n_edges = c.nnz;
-        a.fx_row = c.bwd.fx_row; a.fx_part0 = c.bwd.fx_part0; a.fx_nseg = c.bwd.fx_nseg; a.n_fix = c.bwd.n_fix;
-        a.idx = g->sdst.p + c.e0;
-        a.ew = g->s.p + c.dst0;
-        a.src = da_chunk;
-        a.src_ld = ld_i;
-        a.d = di;
-        a.out = gbuffer ? gbuf : dH_in->ptr;
-        a.out_ld = out_ld;
-        a.out_idx = gbuffer ? g->gslot.p + c.nbr_off : g->nbr.p + c.nbr_off;
-        a.post = g->s.p;
-        a.post_idx = g->nbr.p + c.nbr_off;
-        a.accumulate = 1;
-        a.partial = partial;
-        a.max_slabs = ctx->slabs_bwd;
-        R.tm.begin(&R.st->t_spmm_bwd_ms);
-        HT_TRY(ht_spmm_launch(ctx, st, a));
-        R.tm.end();
-        R.st->n_spmm_bwd += 1;
-        R.st->edges += c.nnz;
-        R.st->spmm_bwd_alg_bytes += spmm_alg_bytes(c, di);
+        ref = z_stage[0];
+        ref_ld = ld_o;
       }
+      HT_TRY(ht_relu_mask(ctx, st, dh_rows, dH_out->ld, ref, ref_ld, dz_chunk, ld_o, ndst, dn));
+      dz_rows = dz_chunk;
+      dz_ld = ld_o;
     }
-    // rows that are not neighbours of the next chunk leave the gradient buffer (Alg. 3 lines 6-7)
+    R.tm.begin(&R.st->t_gemm_ms);
+    HT_TRY(ht_gemm_tn(ctx, st, a_rows, a_ld, dz_rows, dz_ld, dW, ndst, di, dn, first ? 0 : 1));
+    R.tm.end();
+    R.st->n_gemm += 1;
+    R.st->gemm_flops += 2.0 * ndst * di * dn;
+    first = false;
+    if (dH_in) {
+      R.tm.begin(&R.st->t_gemm_ms);
+      HT_TRY(ht_gemm_nt(ctx, st, dz_rows, dz_ld, W, da_chunk, ld_i, ndst, dn, di));
+      R.tm.end();
+      R.st->n_gemm += 1;
+      R.st->gemm_flops += 2.0 * ndst * di * dn;
+    }
+    if (in_host) HT_TRY(P.rec(P.s_c, &ev_cdone[b]));   // the staged inputs have been consumed
+    if (dH_in) {
+      float* partial = nullptr;
+      const int64_t out_ld = gbuffer ? ld_i : dH_in->ld;
+      if (c.bwd.n_part > 0) HT_TRY(ht_scratch(ctx, HT_S_SPART, (size_t)g->max_bpart * out_ld * 4, (void**)&partial));
+      SpmmArgs a{};
+      a.it_row = c.bwd.row; a.it_e0 = c.bwd.e0; a.it_len = c.bwd.len; a.it_part = c.bwd.part; a.n_items = c.bwd.n_items;
+      a.n_edges = c.nnz;
+      a.fx_row = c.bwd.fx_row; a.fx_part0 = c.bwd.fx_part0; a.fx_nseg = c.bwd.fx_nseg; a.n_fix = c.bwd.n_fix;
+      a.idx = g->sdst.p + c.e0;
+      a.ew = g->s.p + c.dst0;
+      a.src = da_chunk;
+      a.src_ld = ld_i;
+      a.d = di;
+      a.out = gbuffer ? gbuf : dH_in->ptr;
+      a.out_ld = out_ld;
+      a.out_idx = gbuffer ? g->gslot.p + c.nbr_off : g->nbr.p + c.nbr_off;
+      a.post = g->s.p;
+      a.post_idx = g->nbr.p + c.nbr_off;
+      a.accumulate = 1;
+      a.partial = partial;
+      a.max_slabs = ctx->slabs_bwd;
+      HT_TRY(P.agg_begin());
+      R.tm.begin(&R.st->t_spmm_bwd_ms);
+      HT_TRY(ht_spmm_launch(ctx, st, a));
+      R.tm.end();
+      HT_TRY(P.agg_end());
+      R.st->n_spmm_bwd += 1;
+      R.st->edges += c.nnz;
+      R.st->spmm_bwd_alg_bytes += spmm_alg_bytes(c, di);
+    }
+    // ---- rows that are not neighbours of the next chunk leave the gradient buffer (Alg. 3 lines 6-7)
     if (dH_in && gbuffer && c.n_leave > 0) {
       if (!cpu_accum) {
         HT_TRY(ht_add_rows(ctx, st, gbuf, ld_i, g->leave_slot.p + c.leave_off, dH_in->ptr, dH_in->ld,
                            g->leave.p + c.leave_off, c.n_leave, di));
       } else {
-        R.tm.begin(&R.st->t_copy_ms);
-        HT_TRY(ht_gather_rows(ctx, st, gbuf, ld_i, g->leave_slot.p + c.leave_off, leave_dev, ld_i, nullptr, c.n_leave, di,
-                              nullptr));
-        HT_HIP(ctx, hipMemcpyAsync(leave_pin, leave_dev, (size_t)c.n_leave * ld_i * 4, hipMemcpyDeviceToHost, st));
-        R.tm.end();
-        HT_HIP(ctx, hipStreamSynchronize(st));
-        R.st->bytes_d2h += c.n_leave * (int64_t)di * 4;
-        auto t0 = std::chrono::steady_clock::now();
-        cpu_accumulate(ctx, dH_in->ptr, dH_in->ld, leave_host.data() + c.leave_off, leave_pin, ld_i, c.n_leave, di);
-        R.st->t_cpu_accum_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+        // compaction on the compute stream (the next chunk overwrites freed positions), D2H on the
+        // output stream, the add on the host beside the next chunks' GPU work
+        for (int64_t k0 = 0; k0 < c.n_leave; k0 += LEAVE_BATCH) {
+          const int64_t nk = std::min(LEAVE_BATCH, c.n_leave - k0);
+          const int64_t off = c.leave_off + k0;
+          const int r = n_left++ % NLV;
+          HT_TRY(P.wait(P.s_c, ev_leave_free[r]));
+          HT_TRY(ht_gather_rows(ctx, st, gbuf, ld_i, g->leave_slot.p + off, leave_dev[r], ld_i, nullptr, nk, di, nullptr));
+          hipEvent_t ev_comp = nullptr;
+          HT_TRY(P.rec(P.s_c, &ev_comp));
+          HT_TRY(P.wait(P.s_out, ev_comp));
+          if (n_left > NLV) worker.wait_done(n_left - NLV);   // the host has consumed leave_pin[r]
+          if (worker.failed()) return ht_set_err(ctx, HT_EHIP, "host-side accumulation: waiting for a copy failed");
+          HT_TRY(P.link_begin(P.s_out));
+          P.used_out = true;
+          HT_TRY(copy_rows(R, P.s_out, leave_pin[r], leave_dev[r], (size_t)nk * ld_i * 4, hipMemcpyDeviceToHost));
+          HT_TRY(P.link_end(P.s_out));
+          HT_TRY(P.rec(P.s_out, &ev_leave_free[r]));
+          worker.push(AccTask{ev_leave_free[r], dH_in->ptr, dH_in->ld, g->leave_host.data() + off, leave_pin[r], ld_i, nk, di});
+        }
       }
     }
   }
   if (first) HT_TRY(ht_fill_zero(ctx, st, dW, (size_t)di * dn * 4));
+  if (cpu_accum) {
+    // the gradient tensor is complete once every host-side add has run
+    worker.finish();
+    if (worker.failed()) return ht_set_err(ctx, HT_EHIP, "host-side accumulation: waiting for a copy failed");
+    R.st->t_cpu_accum_ms += worker.ms();
+    P.used_out = false;
+  }
+  P.used_in = false;   // every input copy was waited for by the compute stream
   return HT_OK;
 }
 

@@ -86,24 +86,32 @@ __global__ void k_mark(const int32_t* __restrict__ col, int64_t nnz, uint32_t* b
   if (!(bm32[u >> 5] & bit)) atomicOr(&bm32[u >> 5], bit);
 }
 
-// totals[0] += popc(cur), totals[1] += popc(cur & prev)
-__global__ void k_popc2(const uint64_t* __restrict__ cur, const uint64_t* __restrict__ prev, int64_t nw,
-                        unsigned long long* __restrict__ totals) {
+// totals[0] += popc(cur), totals[1] += popc(cur & prev), totals[2] += popc(cur & res)
+__global__ void k_popc3(const uint64_t* __restrict__ cur, const uint64_t* __restrict__ prev,
+                        const uint64_t* __restrict__ res, int64_t nw, unsigned long long* __restrict__ totals) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  unsigned long long a = 0, b = 0;
+  unsigned long long a = 0, b = 0, c = 0;
   if (i < nw) {
     a = __popcll(cur[i]);
     b = __popcll(cur[i] & prev[i]);
+    c = __popcll(cur[i] & res[i]);
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
     a += __shfl_down(a, o, 64);
     b += __shfl_down(b, o, 64);
+    c += __shfl_down(c, o, 64);
   }
   if ((threadIdx.x & 63) == 0) {
     if (a) atomicAdd(&totals[0], a);
     if (b) atomicAdd(&totals[1], b);
+    if (c) atomicAdd(&totals[2], c);
   }
+}
+
+__global__ void k_bm_or(uint64_t* __restrict__ acc, const uint64_t* __restrict__ x, int64_t nw) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < nw) acc[i] |= x[i];
 }
 
 // op 0: a & b   1: a & ~b
@@ -417,18 +425,21 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
     g->max_nnz = std::max(g->max_nnz, c.nnz);
   }
 
-  // ---- pass 1: |N_j| and |N_j ^ N_{j-1}| for every chunk
+  // ---- pass 1: |N_j|, |N_j ^ N_{j-1}| and |N_j ^ (N_0 u ... u N_{j-1})| for every chunk
+  const bool keep_all = opts && opts->cache_rows == -1;   // a buffer that never evicts
   const int64_t nw = ceil_div64(V, 64);
-  DevArr<uint64_t> bmA, bmB, bmT;
+  DevArr<uint64_t> bmA, bmB, bmT, bmR;
   HT_TRY(bmA.alloc(ctx, nw));
   HT_TRY(bmB.alloc(ctx, nw));
   HT_TRY(bmT.alloc(ctx, nw));
+  HT_TRY(bmR.alloc(ctx, nw));
   DevArr<unsigned long long> totals;
-  HT_TRY(totals.alloc(ctx, (size_t)2 * n));
-  HT_HIP(ctx, hipMemsetAsync(totals.p, 0, (size_t)2 * n * 8, st));
+  HT_TRY(totals.alloc(ctx, (size_t)3 * n));
+  HT_HIP(ctx, hipMemsetAsync(totals.p, 0, (size_t)3 * n * 8, st));
   uint64_t* cur = bmA.p;
-  uint64_t* prev = bmB.p;
+  uint64_t* prev = bmB.p;   // the previous chunk's set
   HT_HIP(ctx, hipMemsetAsync(prev, 0, nw * 8, st));
+  HT_HIP(ctx, hipMemsetAsync(bmR.p, 0, nw * 8, st));
   for (int j = 0; j < n; ++j) {
     const ChunkMeta& c = g->chunks[j];
     HT_HIP(ctx, hipMemsetAsync(cur, 0, nw * 8, st));
@@ -436,37 +447,42 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
       k_mark<<<nblk(c.nnz), TB, 0, st>>>(g->col.p + c.e0, c.nnz, (uint32_t*)cur);
       HT_LAUNCH_CHECK(ctx);
     }
-    k_popc2<<<nblk(nw), TB, 0, st>>>(cur, prev, nw, totals.p + 2 * j);
+    k_popc3<<<nblk(nw), TB, 0, st>>>(cur, prev, bmR.p, nw, totals.p + 3 * j);
+    HT_LAUNCH_CHECK(ctx);
+    k_bm_or<<<nblk(nw), TB, 0, st>>>(bmR.p, cur, nw);
     HT_LAUNCH_CHECK(ctx);
     std::swap(cur, prev);
   }
-  std::vector<unsigned long long> htot(2 * n);
-  HT_HIP(ctx, hipMemcpyAsync(htot.data(), totals.p, (size_t)2 * n * 8, hipMemcpyDeviceToHost, st));
+  std::vector<unsigned long long> htot(3 * n);
+  HT_HIP(ctx, hipMemcpyAsync(htot.data(), totals.p, (size_t)3 * n * 8, hipMemcpyDeviceToHost, st));
   HT_HIP(ctx, hipStreamSynchronize(st));
-  g->v_ori = g->v_ru = 0;
+  g->v_ori = g->v_ru = g->v_load = 0;
   for (int j = 0; j < n; ++j) {
     ChunkMeta& c = g->chunks[j];
-    c.nsrc = (int64_t)htot[2 * j];
-    c.n_reuse = (int64_t)htot[2 * j + 1];
+    c.nsrc = (int64_t)htot[3 * j];
+    c.n_reuse = (int64_t)htot[3 * j + (keep_all ? 2 : 1)];
     c.n_load = c.nsrc - c.n_reuse;
     c.nbr_off = g->v_ori;
     c.sptr_off = g->v_ori + j;
-    c.reuse_off = g->v_ori - g->v_ru;
-    c.load_off = g->v_ru;
+    c.reuse_off = g->v_ori - g->v_load;
+    c.load_off = g->v_load;
     g->v_ori += c.nsrc;
-    g->v_ru += c.n_load;
+    g->v_load += c.n_load;
+    g->v_ru += c.nsrc - (int64_t)htot[3 * j + 1];   // adjacent-chunk reuse only, as in Sec. 5.3
     g->max_nsrc = std::max(g->max_nsrc, c.nsrc);
   }
   {
     int64_t off = 0;
     for (int j = 0; j < n; ++j) {
       ChunkMeta& c = g->chunks[j];
-      c.n_leave = (j + 1 < n) ? c.nsrc - g->chunks[j + 1].n_reuse : c.nsrc;
+      if (keep_all) c.n_leave = (j + 1 < n) ? 0 : g->v_load;
+      else c.n_leave = (j + 1 < n) ? c.nsrc - g->chunks[j + 1].n_reuse : c.nsrc;
       c.leave_off = off;
       off += c.n_leave;
     }
   }
   int64_t C = opts ? opts->cache_rows : 0;
+  if (keep_all) C = g->v_load;
   if (C == 0) C = g->max_nsrc;
   if (C < g->max_nsrc)
     return ht_set_err(ctx, HT_EINVAL, "ht_partition: cache_rows %lld < max_j |N_j| = %lld", (long long)C,
@@ -475,12 +491,12 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
   g->cache_rows = C;
 
   // ---- arenas
-  const size_t vo = (size_t)std::max<int64_t>(g->v_ori, 1), vr = (size_t)std::max<int64_t>(g->v_ru, 1);
+  const size_t vo = (size_t)std::max<int64_t>(g->v_ori, 1), vr = (size_t)std::max<int64_t>(g->v_load, 1);
   HT_TRY(g->nbr.alloc(ctx, vo));
   HT_TRY(g->slot.alloc(ctx, vo));
   HT_TRY(g->gslot.alloc(ctx, vo));
   HT_TRY(g->sptr.alloc(ctx, vo + n));
-  HT_TRY(g->reuse.alloc(ctx, (size_t)std::max<int64_t>(g->v_ori - g->v_ru, 1)));
+  HT_TRY(g->reuse.alloc(ctx, (size_t)std::max<int64_t>(g->v_ori - g->v_load, 1)));
   HT_TRY(g->load.alloc(ctx, vr));
   HT_TRY(g->load_slot.alloc(ctx, vr));
   HT_TRY(g->leave.alloc(ctx, vr));
@@ -546,7 +562,7 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
     HT_LAUNCH_CHECK(ctx);
     HT_TRY(ht_bitmap_prefix(ctx, bmT.p, nw, cnt_tmp.p, pref.p));
     HT_TRY(ht_bitmap_expand(ctx, bmT.p, nw, pref.p, g->load.p + c.load_off));
-    if (j > 0) {
+    if (j > 0 && !keep_all) {
       ChunkMeta& pc = g->chunks[j - 1];
       k_bm_op<<<nblk(nw), TB, 0, st>>>(prev, cur, nw, 1, bmT.p);
       HT_LAUNCH_CHECK(ctx);
@@ -595,12 +611,25 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
                        seg_bwd, &c.bwd));
     g->max_fpart = std::max(g->max_fpart, c.fwd.n_part);
     g->max_bpart = std::max(g->max_bpart, c.bwd.n_part);
-    std::swap(cur, prev);
+    if (keep_all) {   // prev = every vertex seen so far
+      k_bm_or<<<nblk(nw), TB, 0, st>>>(prev, cur, nw);
+      HT_LAUNCH_CHECK(ctx);
+    } else {
+      std::swap(cur, prev);
+    }
   }
-  // the last chunk's rows all leave at the end of a pass
+  // what is still buffered leaves at the end of a pass
   if (n > 0) {
     ChunkMeta& lc = g->chunks[n - 1];
-    if (lc.nsrc > 0) {
+    if (keep_all) {
+      if (lc.n_leave > 0) {
+        HT_TRY(ht_bitmap_prefix(ctx, prev, nw, cnt_tmp.p, pref.p));
+        HT_TRY(ht_bitmap_expand(ctx, prev, nw, pref.p, g->leave.p + lc.leave_off));
+        k_map_i32<<<nblk(lc.n_leave), TB, 0, st>>>(g->leave.p + lc.leave_off, lc.n_leave, vslot.p,
+                                                   g->leave_slot.p + lc.leave_off);
+        HT_LAUNCH_CHECK(ctx);
+      }
+    } else if (lc.nsrc > 0) {
       HT_HIP(ctx, hipMemcpyAsync(g->leave.p + lc.leave_off, g->nbr.p + lc.nbr_off, lc.nsrc * 4,
                                  hipMemcpyDeviceToDevice, st));
       HT_HIP(ctx, hipMemcpyAsync(g->leave_slot.p + lc.leave_off, g->slot.p + lc.nbr_off, lc.nsrc * 4,
@@ -639,7 +668,7 @@ int ht_partition(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src, const in
   if (E < 0 || (E > 0 && (!src || !dst))) return ht_set_err(ctx, HT_EINVAL, "ht_partition: bad edge list");
   if (n_chunks < 1) return ht_set_err(ctx, HT_EINVAL, "ht_partition: n_chunks must be >= 1");
   if (opts && (opts->balance_mode < 0 || opts->balance_mode > 1 || opts->ptr_loc < 0 || opts->ptr_loc > 1 ||
-               opts->cache_rows < 0))
+               opts->cache_rows < -1))
     return ht_set_err(ctx, HT_EINVAL, "ht_partition: bad options");
   HT_HIP(ctx, hipSetDevice(ctx->device));
   auto t0 = std::chrono::steady_clock::now();
@@ -671,6 +700,7 @@ int ht_graph_info_get(const ht_graph* g, ht_graph_info* out) {
   out->reserved = 0;
   out->v_ori = g->v_ori;
   out->v_ru = g->v_ru;
+  out->v_load = g->v_load;
   out->alpha = g->V > 0 ? (double)g->v_ori / (double)g->V : 0.0;
   out->max_nsrc = g->max_nsrc;
   out->max_ndst = g->max_ndst;

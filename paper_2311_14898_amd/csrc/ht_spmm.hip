@@ -216,7 +216,8 @@ int launch_items(ht_ctx* ctx, hipStream_t st, const SpmmArgs& a) {
   return HT_OK;
 }
 
-// dst[dst_idx[k]] = scale[src_idx[k]] * src[src_idx[k]]; a lane group per row.
+// dst[dst_idx[k]] = scale[src_idx[k]] * src[src_idx[k]]; a lane group per row,
+// grid-stride over rows so the launch can be kept small (see ht_gather_rows).
 template <int ADD>
 __global__ void __launch_bounds__(256) k_rows(const float* __restrict__ src, int64_t src_ld,
                                               const int32_t* __restrict__ src_idx, float* __restrict__ dst,
@@ -224,20 +225,38 @@ __global__ void __launch_bounds__(256) k_rows(const float* __restrict__ src, int
                                               int d4, int lpr, const float* __restrict__ scale) {
   const int tid = threadIdx.x;
   const int rows_per_block = 256 / lpr;
-  const int64_t k = (int64_t)blockIdx.x * rows_per_block + tid / lpr;
-  if (k >= n_rows) return;
   const int ll = tid % lpr;
-  const int64_t si = src_idx ? (int64_t)src_idx[k] : k;
-  const int64_t di = dst_idx ? (int64_t)(dst_idx[k] & 0x7FFFFFFF) : k;
-  const float sc = scale ? scale[si] : 1.f;
-  const float* sp = src + si * src_ld;
-  float* dp = dst + di * dst_ld;
-  for (int c4 = ll * 4; c4 < d4; c4 += lpr * 4) {
-    float4 v = ld4(sp + c4);
-    if (scale) v = mul4(sc, v);
-    if (ADD) v = add4(ld4(dp + c4), v);
-    st4(dp + c4, v);
+  for (int64_t k = (int64_t)blockIdx.x * rows_per_block + tid / lpr; k < n_rows;
+       k += (int64_t)gridDim.x * rows_per_block) {
+    const int64_t si = src_idx ? (int64_t)src_idx[k] : k;
+    const int64_t di = dst_idx ? (int64_t)(dst_idx[k] & 0x7FFFFFFF) : k;
+    const float sc = scale ? scale[si] : 1.f;
+    const float* sp = src + si * src_ld;
+    float* dp = dst + di * dst_ld;
+    for (int c4 = ll * 4; c4 < d4; c4 += lpr * 4) {
+      float4 v = ld4(sp + c4);
+      if (scale) v = mul4(sc, v);
+      if (ADD) v = add4(ld4(dp + c4), v);
+      st4(dp + c4, v);
+    }
   }
+}
+
+// Contiguous copy of n16 16-byte words with a small fixed grid: four loads in
+// flight per lane, grid-stride.  Used for rows that cross the host link, where a
+// few dozen waves saturate the link and a device-filling launch would only
+// crowd out the compute kernels running beside it.
+__global__ void __launch_bounds__(256) k_copy16(const float4* __restrict__ src, float4* __restrict__ dst, int64_t n16) {
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    const float4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    dst[i] = a;
+    dst[i + stride] = b;
+    dst[i + 2 * stride] = c;
+    dst[i + 3 * stride] = d;
+  }
+  for (; i < n16; i += stride) dst[i] = src[i];
 }
 
 int lanes_for(int nvec) { return nvec <= 8 ? 8 : nvec <= 16 ? 16 : nvec <= 32 ? 32 : 64; }
@@ -294,13 +313,15 @@ int ht_spmm_launch(ht_ctx* ctx, hipStream_t st, const SpmmArgs& a0) {
 }
 
 int ht_gather_rows(ht_ctx* ctx, hipStream_t st, const float* src, int64_t src_ld, const int32_t* src_idx, float* dst,
-                   int64_t dst_ld, const int32_t* dst_idx, int64_t n_rows, int32_t d, const float* scale) {
+                   int64_t dst_ld, const int32_t* dst_idx, int64_t n_rows, int32_t d, const float* scale,
+                   int max_blocks) {
   if (n_rows <= 0) return HT_OK;
   const int d4 = (d + 3) & ~3;
   const int lpr = lanes_for(d4 / 4);
   const int rpb = 256 / lpr;
-  k_rows<0><<<(unsigned)((n_rows + rpb - 1) / rpb), 256, 0, st>>>(src, src_ld, src_idx, dst, dst_ld, dst_idx, n_rows,
-                                                                d4, lpr, scale);
+  int64_t blocks = (n_rows + rpb - 1) / rpb;
+  if (max_blocks > 0 && blocks > max_blocks) blocks = max_blocks;
+  k_rows<0><<<(unsigned)blocks, 256, 0, st>>>(src, src_ld, src_idx, dst, dst_ld, dst_idx, n_rows, d4, lpr, scale);
   HT_LAUNCH_CHECK(ctx);
   return HT_OK;
 }
@@ -313,6 +334,18 @@ int ht_add_rows(ht_ctx* ctx, hipStream_t st, const float* src, int64_t src_ld, c
   const int rpb = 256 / lpr;
   k_rows<1><<<(unsigned)((n_rows + rpb - 1) / rpb), 256, 0, st>>>(src, src_ld, src_idx, dst, dst_ld, dst_idx, n_rows,
                                                                 d4, lpr, nullptr);
+  HT_LAUNCH_CHECK(ctx);
+  return HT_OK;
+}
+
+int ht_copy_link(ht_ctx* ctx, hipStream_t st, void* dst, const void* src, size_t bytes, int blocks) {
+  if (bytes == 0) return HT_OK;
+  if ((bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15))
+    return ht_set_err(ctx, HT_ESHAPE, "link copy: pointers and size must be multiples of 16 bytes");
+  const int64_t n16 = (int64_t)(bytes >> 4);
+  int64_t nb = (n16 + 255) / 256;
+  if (nb > blocks) nb = blocks;
+  k_copy16<<<(unsigned)nb, 256, 0, st>>>((const float4*)src, (float4*)dst, n16);
   HT_LAUNCH_CHECK(ctx);
   return HT_OK;
 }

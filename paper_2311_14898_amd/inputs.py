@@ -169,7 +169,7 @@ class Workload:
     E: int
     dims: List[int]
     n_chunks: int
-    residency: str = "hbm"          # "hbm" | "host": where h^l, a^l and grad h^l live
+    residency: str = "hbm"          # "hbm" | "host" (h^l, grad h^l in pinned host memory) | "host_all" (a^l too)
     labelled_one_in: int = 1
     graph_seed: int = 1
     lr: float = 0.01
@@ -192,8 +192,8 @@ WORKLOADS = {
     "cfg1": Workload("cfg1", 10_000, 100_000, [64, 32, 8], 4, "hbm"),
     "cfg2": Workload("cfg2", 232_965, 114_600_000, [602, 256, 41], 8, "hbm"),
     "cfg3": Workload("cfg3", 2_450_000, 61_900_000, [100, 256, 256, 47], 16, "host"),
-    "cfg4": Workload("cfg4", 111_000_000, 1_600_000_000, [128, 256, 256, 172], 64, "host", labelled_one_in=100),
-    "cfg5": Workload("cfg5", 65_600_000, 3_600_000_000, [256, 256, 256, 64], 128, "host"),
+    "cfg4": Workload("cfg4", 111_000_000, 1_600_000_000, [128, 256, 256, 172], 64, "host_all", labelled_one_in=100),
+    "cfg5": Workload("cfg5", 65_600_000, 3_600_000_000, [256, 256, 256, 64], 128, "host_all"),
 }
 
 

@@ -18,8 +18,8 @@ def ctx():
     B.ht_ctx_destroy(c)
 
 
-def run_epoch(ctx, w, src, dst, X, y, Ws, n_chunks=None, x_loc=B.HT_LOC_DEVICE, **plan):
-    g = B.ht_partition(ctx, w.V, src.cuda(), dst.cuda(), n_chunks or w.n_chunks)
+def run_epoch(ctx, w, src, dst, X, y, Ws, n_chunks=None, x_loc=B.HT_LOC_DEVICE, cache_rows=0, **plan):
+    g = B.ht_partition(ctx, w.V, src.cuda(), dst.cuda(), n_chunks or w.n_chunks, cache_rows=cache_rows)
     try:
         Xd = B.to_matrix(X, x_loc)
         Wd = [x.clone().cuda() for x in Ws]
@@ -91,6 +91,18 @@ def test_cfg1_host_resident_with_buffer(ctx, cfg1):
     st = out["stats"]
     assert st.rows_loaded + st.rows_reused > 0 and st.bytes_h2d > 0 and st.bytes_d2h > 0
     assert st.bytes_h2d_nodedup >= 4 * w.dims[0] * st.rows_loaded // w.n_layers
+
+
+def test_cfg1_host_resident_keep_all_buffer(ctx, cfg1):
+    # a buffer as large as the source set: every row crosses the link once per pass
+    w, src, dst, X, y, Ws, ref = cfg1
+    out = run_epoch(ctx, w, src, dst, X, y, Ws, x_loc=B.HT_LOC_HOST_PINNED, cache_rows=-1, res_h=B.HT_RES_HOST,
+                    res_a=B.HT_RES_HOST, res_g=B.HT_RES_HOST)
+    compare(out, ref, w.n_layers)
+    st = out["stats"]
+    assert st.rows_loaded == w.V * w.n_layers          # V rows per forward pass, not V_+ru
+    out = run_epoch(ctx, w, src, dst, X, y, Ws, cache_rows=-1, gather_mode=B.HT_GATHER_BUFFER)
+    compare(out, ref, w.n_layers)
 
 
 def test_cfg1_buffer_mode_in_hbm_and_chunk_count_invariance(ctx, cfg1):

@@ -41,6 +41,8 @@ def check_graph(ctx, V, src, dst, n, self_loops=True, mode=B.HT_BALANCE_EDGES, o
         prev_N = np.zeros(0, np.int32)
         prev_slot = {}
         max_nsrc = 0
+        keep_all = cache_rows == -1
+        n_loaded = 0
         for j in range(n):
             ch = B.ht_graph_export_chunk(g, j)
             ci = ch["info"]
@@ -63,10 +65,19 @@ def check_graph(ctx, V, src, dst, n, self_loops=True, mode=B.HT_BALANCE_EDGES, o
             cur = dict(zip(o["N"].tolist(), slot.tolist()))
             for u in R.tolist():
                 assert cur[u] == prev_slot[u], f"chunk {j}: reused vertex {u} moved"
-            prev_slot, prev_N = cur, o["N"]
+            n_loaded += len(Ld)
+            if keep_all:      # nothing is evicted: reuse is against everything seen so far
+                prev_slot.update(cur)
+                prev_N = np.union1d(prev_N, o["N"]).astype(np.int32)
+            else:
+                prev_slot, prev_N = cur, o["N"]
             max_nsrc = max(max_nsrc, len(slot))
         assert info.max_nsrc == max_nsrc
-        assert info.cache_rows == (cache_rows or max(max_nsrc, 1))
+        assert info.v_load == n_loaded
+        if keep_all:
+            assert len(set(prev_slot.values())) == len(prev_slot) == info.cache_rows == len(prev_N)
+        else:
+            assert info.cache_rows == (cache_rows or max(max_nsrc, 1)) and info.v_load == info.v_ru
     finally:
         B.ht_graph_destroy(g)
 
@@ -88,6 +99,7 @@ def test_more_chunks_than_vertices_and_no_edges(ctx):
     e = torch.zeros(0, dtype=torch.int32)
     check_graph(ctx, 5, e, e, 2)                            # only self loops
     check_graph(ctx, 70, src, dst, 3, self_loops=False)     # isolated vertices, empty rows, empty chunks
+    check_graph(ctx, 70, src, dst, 3, self_loops=False, cache_rows=-1)
 
 
 def test_cfg1(ctx):
@@ -95,6 +107,7 @@ def test_cfg1(ctx):
     src, dst = inputs.rmat_edges(w.V, w.E, w.graph_seed)
     check_graph(ctx, w.V, src, dst, w.n_chunks)
     check_graph(ctx, w.V, src, dst, 5, cache_rows=w.V)
+    check_graph(ctx, w.V, src, dst, w.n_chunks, cache_rows=-1)
 
 
 def test_several_sort_tiles_ragged_and_hubs(ctx):
@@ -109,6 +122,7 @@ def test_rmat_skew_medium(ctx):
     V, E = 60_000, 1_500_000
     src, dst = inputs.rmat_edges(V, E, seed=9)
     check_graph(ctx, V, src, dst, 16)
+    check_graph(ctx, V, src, dst, 16, cache_rows=-1)
 
 
 def test_paper_inplace_buffer_example(ctx):
