@@ -99,6 +99,7 @@ struct Run {
   Timer tm;
   ht_stats* st;  // never null inside (a local one is used when the caller passes none)
   int layer = 0; // index into the per-layer statistics
+  bool dhin_is_zero = false;  // the caller guarantees dH_in holds zeros (lets leaving rows be stored, not added)
   Run(ht_ctx* c, const ht_graph* gr, ht_stats* s, bool timed) : ctx(c), g(gr), tm(c, c->stream, timed), st(s) {}
 };
 
@@ -486,7 +487,12 @@ int layer_bwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* ckpt, con
     if (gbuffer) HT_TRY(ht_scratch(ctx, HT_S_MISC, (size_t)g->cache_rows * ld_i * 4, (void**)&gbuf));
   }
   // CPU-side accumulation (Alg. 3 line 7): host copy of the leave lists, device and pinned staging pairs
-  const bool cpu_accum = dH_in && gbuffer && dH_in->loc == HT_LOC_HOST_PINNED;
+  // Each vertex leaves a never-evicting buffer exactly once, at the end of the pass: if dH_in is known
+  // to hold zeros the rows are stored straight to their home by a link kernel, no host-side add.
+  const bool store_home = dH_in && gbuffer && dH_in->loc == HT_LOC_HOST_PINNED && g->keep_all && R.dhin_is_zero;
+  const bool cpu_accum = dH_in && gbuffer && dH_in->loc == HT_LOC_HOST_PINNED && !store_home;
+  float* dhin_gpu = nullptr;
+  if (store_home) HT_TRY(gpu_ptr(ctx, dH_in, &dhin_gpu));
   constexpr int NLV = 4;   // depth of the leave staging rings: D2H runs ahead of the host-side adds
   constexpr int64_t LEAVE_BATCH = 262144;   // rows per compaction / D2H / host-add task
   float* leave_dev[NLV] = {};
@@ -511,7 +517,7 @@ int layer_bwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* ckpt, con
   Pipe P(ctx);
   AccWorker worker(ctx);   // declared after P: joined before P's destructor waits for the streams
   if (cpu_accum) worker.start();
-  P.fence = (in_host || cpu_accum) && !ctx->no_link_fence;
+  P.fence = (in_host || cpu_accum || store_home) && !ctx->no_link_fence;
   if (in_host) {
     hipEvent_t ev_start = nullptr;
     HT_TRY(P.rec(P.s_c, &ev_start));
@@ -639,7 +645,22 @@ int layer_bwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* ckpt, con
     }
     // ---- rows that are not neighbours of the next chunk leave the gradient buffer (Alg. 3 lines 6-7)
     if (dH_in && gbuffer && c.n_leave > 0) {
-      if (!cpu_accum) {
+      if (store_home) {
+        hipEvent_t ev_done = nullptr, ev_st = nullptr;
+        HT_TRY(P.rec(P.s_c, &ev_done));
+        HT_TRY(P.wait(P.s_out, ev_done));
+        HT_TRY(P.link_begin(P.s_out));
+        P.used_out = true;
+        const int id = R.tm.begin_on(&R.st->t_copy_ms, P.s_out);
+        HT_TRY(ht_gather_rows(ctx, P.s_out, gbuf, ld_i, g->leave_slot.p + c.leave_off, dhin_gpu, dH_in->ld,
+                              g->leave.p + c.leave_off, c.n_leave, di, nullptr, ctx->link_blocks));
+        R.tm.end_id(id);
+        R.st->bytes_d2h += c.n_leave * (int64_t)di * 4;
+        HT_TRY(P.link_end(P.s_out));
+        HT_TRY(P.rec(P.s_out, &ev_st));
+        HT_TRY(P.wait(P.s_c, ev_st));   // the buffer is free again and dH_in complete for later work on the stream
+        P.used_out = false;
+      } else if (!cpu_accum) {
         HT_TRY(ht_add_rows(ctx, st, gbuf, ld_i, g->leave_slot.p + c.leave_off, dH_in->ptr, dH_in->ld,
                            g->leave.p + c.leave_off, c.n_leave, di));
       } else {
@@ -898,9 +919,16 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
     d.act = l < L - 1 ? HT_ACT_RELU : HT_ACT_NONE;
     d.gather_mode = gather_mode;
     d.ckpt_kind = HT_CKPT_AGG;
+    R.dhin_is_zero = false;
     if (l > 0) {
-      int rc = zero_tensor(ctx, &ws->gh[l]);
-      if (rc != HT_OK) return fail(rc);
+      // a never-evicting gradient buffer stores every row of a host-resident grad h^l exactly once
+      const bool stored_once = g->keep_all && g->v_load == V && ws->gh[l].loc == HT_LOC_HOST_PINNED &&
+                               gather_mode != HT_GATHER_DIRECT;
+      if (!stored_once) {
+        int rc = zero_tensor(ctx, &ws->gh[l]);
+        if (rc != HT_OK) return fail(rc);
+      }
+      R.dhin_is_zero = true;
     }
     R.layer = l;
     const ht_tensor* mask_from = (inter == HT_INTER_MASK && l < L - 1) ? &ws->h[l + 1] : nullptr;

@@ -427,6 +427,7 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
 
   // ---- pass 1: |N_j|, |N_j ^ N_{j-1}| and |N_j ^ (N_0 u ... u N_{j-1})| for every chunk
   const bool keep_all = opts && opts->cache_rows == -1;   // a buffer that never evicts
+  g->keep_all = keep_all;
   const int64_t nw = ceil_div64(V, 64);
   DevArr<uint64_t> bmA, bmB, bmT, bmR;
   HT_TRY(bmA.alloc(ctx, nw));
