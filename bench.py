@@ -96,6 +96,7 @@ def main():
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--scale", type=float, default=1.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--verbose", action="store_true", help="progress lines on stderr")
     ap.add_argument("--cache", choices=["adjacent", "all"], default="adjacent",
                     help="neighbour-row buffer: reuse between adjacent chunks only, or keep every row once loaded")
     ap.add_argument("--calib-copy", action="store_true",
@@ -112,6 +113,12 @@ def main():
     from paper_2311_14898_amd import inputs
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    t_origin = time.perf_counter()
+
+    def note(msg):
+        if args.verbose:
+            print(f"[bench {time.perf_counter() - t_origin:7.1f}s] {msg}", file=sys.stderr, flush=True)
+
     w = inputs.WORKLOADS[args.workload].scaled(args.scale)
     host = w.residency in ("host", "host_all")
     t_gen = time.perf_counter()
@@ -121,10 +128,12 @@ def main():
     Ws = inputs.glorot_weights(w.dims)
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
+    note(f"inputs generated: V={w.V} E={w.E}")
 
     ctx = B.ht_ctx_create(0)
     g = B.ht_partition(ctx, w.V, src, dst, w.n_chunks, cache_rows=-1 if args.cache == "all" else 0)
     info = B.ht_graph_info_get(g)
+    note(f"partitioned in {info.partition_ms:.0f} ms: alpha={info.alpha:.2f} v_ru/V={info.v_ru / w.V:.2f} graph HBM {info.hbm_bytes / 1e9:.1f} GB")
     Xd = B.to_matrix(X, B.HT_LOC_HOST_PINNED if host else B.HT_LOC_DEVICE)
     yd = y.cuda()
     Wd = [x.clone().cuda() for x in Ws]
@@ -139,8 +148,10 @@ def main():
             b.copy_(a)          # reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
         del a, b
+    note("inputs resident")
     for _ in range(args.warmup):
         B.ht_epoch(ctx, g, w.dims, Wd, w.lr, Xd, yd, **plan)
+        note("warm-up epoch done")
     torch.cuda.synchronize()
     agg = {"t": 0.0, "n": 0, "bytes": 0.0}
     tot = None
@@ -148,6 +159,7 @@ def main():
     for _ in range(args.steps):
         loss, st = B.ht_epoch(ctx, g, w.dims, Wd, w.lr, Xd, yd, want_stats=True, **plan)
         d = st.as_dict()
+        note(f"epoch done: {d['t_total_ms']:.1f} ms, loss {loss:.5f}")
         agg["t"] += d["t_agg_fwd_layer_ms"][0]
         agg["n"] += d["n_agg_fwd_layer"][0]
         agg["bytes"] += d["agg_fwd_layer_alg_bytes"][0]
