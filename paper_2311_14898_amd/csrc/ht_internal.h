@@ -11,9 +11,10 @@
 
 #include "../../include/hongtu.h"
 
-// Edges one aggregation work item covers at most.  Rows longer than this are
-// cut into several items whose partial sums are added in item order.
-constexpr int HT_SEG = 512;
+// Edges one forward aggregation work item covers at most (backward items take half).  Rows
+// longer than this are cut into several items whose partial sums are added in item order.
+// Shorter items read a narrower range of source rows, which is what keeps them in L2.
+constexpr int HT_SEG = 256;
 
 struct EpochWs;
 
@@ -141,6 +142,7 @@ struct ItemSet {
 struct ChunkMeta {
   int64_t dst0 = 0, dst1 = 0;  // destination range
   int64_t e0 = 0, nnz = 0;     // edge range in the global CSC arrays
+  int64_t ue0 = 0, nu = 0;     // range of distinct (destination, source) pairs in the merged arrays (= e0, nnz when not merged)
   int64_t nsrc = 0;            // |N_j|
   int64_t nbr_off = 0;         // offset of N_j in the nbr / slot arenas
   int64_t sptr_off = 0;        // offset of sptr_j in the sptr arena (nbr_off + j)
@@ -172,6 +174,19 @@ struct ht_graph {
   DevArr<int32_t> load_slot;   // [v_load]
   DevArr<int32_t> leave;       // [v_load] rows leaving after each chunk (everything still buffered after the last)
   DevArr<int32_t> leave_slot;  // [v_load]
+  // Duplicate edges merged for the aggregation kernels (built when at least 5 % of the edges repeat
+  // a pair): one entry per distinct pair, its multiplicity folded into the weight.  The arrays above
+  // stay the canonical ones (export, parity).
+  bool merged = false;
+  int64_t n_unique = 0;
+  DevArr<int64_t> uindptr;     // [V+1] row offsets in distinct-pair space
+  DevArr<int32_t> ucol;        // [n_unique] source of each distinct pair, CSC order
+  DevArr<int32_t> ucol_slot;   // [n_unique] its buffer position
+  DevArr<float> uw_fwd;        // [n_unique] multiplicity * s[source]
+  DevArr<float> umult;         // [n_unique] multiplicity (for rows already scaled in the buffer)
+  DevArr<int64_t> usptr;       // [v_ori + n] per-chunk by-source offsets in distinct-pair space
+  DevArr<int32_t> usdst;       // [n_unique] local destination of each distinct pair, by-source order
+  DevArr<float> uw_bwd;        // [n_unique] multiplicity * s[destination]
   int64_t v_ori = 0, v_ru = 0, v_load = 0;  // v_load: rows actually loaded per pass with this buffer
   int64_t max_nsrc = 0, max_ndst = 0, max_nnz = 0, max_fpart = 0, max_bpart = 0;
   int64_t cache_rows = 0;
@@ -198,6 +213,7 @@ struct SpmmArgs {
   // edges
   const int32_t* idx;     // per edge: row of `src` to read (chunk-relative pointer)
   const float* ew;        // per-edge weight table indexed by idx (nullable: weight 1)
+  const float* w_edge = nullptr;  // per-edge weights in edge order (takes precedence over ew)
   const float* src;       // source matrix
   int64_t src_ld;
   int32_t d;              // valid columns

@@ -183,8 +183,14 @@ int spmm_chunk(Run& R, int j, bool buffer, const float* src, int64_t src_ld, int
   a.it_row = c.fwd.row; a.it_e0 = c.fwd.e0; a.it_len = c.fwd.len; a.it_part = c.fwd.part; a.n_items = c.fwd.n_items;
   a.n_edges = c.nnz;
   a.fx_row = c.fwd.fx_row; a.fx_part0 = c.fwd.fx_part0; a.fx_nseg = c.fwd.fx_nseg; a.n_fix = c.fwd.n_fix;
-  a.idx = (buffer ? g->col_slot.p : g->col.p) + c.e0;
-  a.ew = buffer ? nullptr : g->s.p;
+  if (g->merged) {
+    a.idx = (buffer ? g->ucol_slot.p : g->ucol.p) + c.ue0;
+    a.w_edge = (buffer ? g->umult.p : g->uw_fwd.p) + c.ue0;
+    a.n_edges = c.nu;
+  } else {
+    a.idx = (buffer ? g->col_slot.p : g->col.p) + c.e0;
+    a.ew = buffer ? nullptr : g->s.p;
+  }
   a.src = src;
   a.src_ld = src_ld;
   a.d = d;
@@ -621,8 +627,14 @@ int layer_bwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* ckpt, con
       a.it_row = c.bwd.row; a.it_e0 = c.bwd.e0; a.it_len = c.bwd.len; a.it_part = c.bwd.part; a.n_items = c.bwd.n_items;
       a.n_edges = c.nnz;
       a.fx_row = c.bwd.fx_row; a.fx_part0 = c.bwd.fx_part0; a.fx_nseg = c.bwd.fx_nseg; a.n_fix = c.bwd.n_fix;
-      a.idx = g->sdst.p + c.e0;
-      a.ew = g->s.p + c.dst0;
+      if (g->merged) {
+        a.idx = g->usdst.p + c.ue0;
+        a.w_edge = g->uw_bwd.p + c.ue0;
+        a.n_edges = c.nu;
+      } else {
+        a.idx = g->sdst.p + c.e0;
+        a.ew = g->s.p + c.dst0;
+      }
       a.src = da_chunk;
       a.src_ld = ld_i;
       a.d = di;

@@ -224,6 +224,66 @@ __global__ void k_items_fill(const int64_t* __restrict__ ptr, int64_t ptr0, int6
   }
 }
 
+// ---- merging of duplicate edges (a multigraph's repeated (u -> v) entries are adjacent in both
+// sorted orders): one entry per distinct pair with weight multiplicity * s.
+__global__ void k_dup_flags_u32(const int32_t* __restrict__ col, int64_t n, int32_t* __restrict__ flag) {
+  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e < n) flag[e] = (e == 0 || col[e] != col[e - 1]) ? 1 : 0;
+}
+__global__ void k_row_start_flags(const int64_t* __restrict__ indptr, int64_t V, int64_t n, int32_t* __restrict__ flag) {
+  int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (v < V && indptr[v] < n) flag[indptr[v]] = 1;
+}
+__global__ void k_dup_flags_u64(const uint64_t* __restrict__ keys, int64_t n, int32_t* __restrict__ flag) {
+  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e < n) flag[e] = (e == 0 || keys[e] != keys[e - 1]) ? 1 : 0;
+}
+// upos[u] = position of the u-th flagged entry; upos[nU] = n is written by the host
+__global__ void k_flag_positions(const int32_t* __restrict__ flag, const int64_t* __restrict__ rank, int64_t n,
+                                 int64_t* __restrict__ upos) {
+  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e < n && flag[e]) upos[rank[e]] = e;
+}
+// forward: ucol, weights mult*s[src] (rows read in place) and mult (rows pre-scaled in the buffer)
+__global__ void k_merge_fwd(const int64_t* __restrict__ upos, int64_t nU, const int32_t* __restrict__ col,
+                            const float* __restrict__ s, int32_t* __restrict__ ucol, float* __restrict__ uw,
+                            float* __restrict__ umult) {
+  int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (u >= nU) return;
+  const int64_t e = upos[u];
+  const float m = (float)(upos[u + 1] - e);
+  const int32_t c = col[e];
+  ucol[u] = c;
+  uw[u] = m * s[c];
+  umult[u] = m;
+}
+__global__ void k_uindptr(const int64_t* __restrict__ indptr, const int64_t* __restrict__ rank, int64_t V, int64_t n,
+                          int64_t nU, int64_t* __restrict__ uindptr) {
+  int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (v > V) return;
+  const int64_t e = indptr[v];
+  uindptr[v] = e < n ? rank[e] : nU;
+}
+__global__ void k_gather_i32_at(const int64_t* __restrict__ pos, int64_t pos_off, int64_t n, const int32_t* __restrict__ table,
+                                int32_t* __restrict__ out) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = table[pos[i] - pos_off];
+}
+// backward: per distinct (local source, local destination): usdst, weight mult*s[dst], compacted keys
+__global__ void k_merge_bwd(const int64_t* __restrict__ upos, int64_t nU, const uint64_t* __restrict__ keys,
+                            const float* __restrict__ s_chunk, int32_t* __restrict__ usdst, float* __restrict__ uw,
+                            uint64_t* __restrict__ ukeys) {
+  int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (u >= nU) return;
+  const int64_t t = upos[u];
+  const float m = (float)(upos[u + 1] - t);
+  const uint64_t k = keys[t];
+  const int32_t d = (int32_t)(k & 0xFFFFFFFFull);
+  usdst[u] = d;
+  uw[u] = m * s_chunk[d];
+  ukeys[u] = k;
+}
+
 // Dispatch order of work items: by the first row they read (edges of a row are
 // sorted by that index), so items in flight together read neighbouring rows.
 __global__ void k_item_keys(const int64_t* __restrict__ it_e0, const int32_t* __restrict__ it_len, int64_t n,
@@ -392,6 +452,48 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
   src_copy.release();
   dst_copy.release();
 
+  // ---- duplicate edges: count the distinct (destination, source) pairs; merge when it pays
+  const char* mg_env = getenv("HT_MERGE_DUPS");
+  const bool merge_allowed = !(mg_env && atoi(mg_env) == 0);
+  DevArr<int32_t> dflag;
+  DevArr<int64_t> drank, upos;
+  int64_t nU = Ep;
+  g->merged = false;
+  if (merge_allowed && Ep > 0) {
+    HT_TRY(dflag.alloc(ctx, (size_t)Ep));
+    HT_TRY(drank.alloc(ctx, (size_t)Ep + 1));
+    k_dup_flags_u32<<<nblk(Ep), TB, 0, st>>>(g->col.p, Ep, dflag.p);
+    HT_LAUNCH_CHECK(ctx);
+    k_row_start_flags<<<nblk(V), TB, 0, st>>>(g->indptr.p, V, Ep, dflag.p);
+    HT_LAUNCH_CHECK(ctx);
+    HT_TRY(ht_scan_i32(ctx, dflag.p, drank.p, Ep, true));
+    HT_HIP(ctx, hipMemcpyAsync(&nU, drank.p + Ep, 8, hipMemcpyDeviceToHost, st));
+    HT_HIP(ctx, hipStreamSynchronize(st));
+    // merged arrays cost 16 B per distinct pair: worth it from about 5 % duplicates
+    if ((double)nU <= 0.95 * (double)Ep) {
+      g->merged = true;
+      g->n_unique = nU;
+      HT_TRY(upos.alloc(ctx, (size_t)nU + 1));
+      HT_TRY(g->uindptr.alloc(ctx, (size_t)V + 1));
+      HT_TRY(g->ucol.alloc(ctx, (size_t)nU));
+      HT_TRY(g->ucol_slot.alloc(ctx, (size_t)nU));
+      HT_TRY(g->uw_fwd.alloc(ctx, (size_t)nU));
+      HT_TRY(g->umult.alloc(ctx, (size_t)nU));
+      HT_TRY(g->usdst.alloc(ctx, (size_t)nU));
+      HT_TRY(g->uw_bwd.alloc(ctx, (size_t)nU));
+      k_flag_positions<<<nblk(Ep), TB, 0, st>>>(dflag.p, drank.p, Ep, upos.p);
+      HT_LAUNCH_CHECK(ctx);
+      HT_HIP(ctx, hipMemcpyAsync(upos.p + nU, &Ep, 8, hipMemcpyHostToDevice, st));
+      k_merge_fwd<<<nblk(nU), TB, 0, st>>>(upos.p, nU, g->col.p, g->s.p, g->ucol.p, g->uw_fwd.p, g->umult.p);
+      HT_LAUNCH_CHECK(ctx);
+      k_uindptr<<<nblk(V + 1), TB, 0, st>>>(g->indptr.p, drank.p, V, Ep, nU, g->uindptr.p);
+      HT_LAUNCH_CHECK(ctx);
+      HT_HIP(ctx, hipStreamSynchronize(st));
+    }
+    dflag.release();
+    drank.release();
+  }
+
   // ---- chunk boundaries
   g->bounds.assign(n + 1, 0);
   g->bounds[n] = V;
@@ -413,6 +515,12 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
   for (int j = 0; j <= n; ++j)  // n is small: one 8-byte copy per boundary
     HT_HIP(ctx, hipMemcpyAsync(&eoff[j], g->indptr.p + g->bounds[j], 8, hipMemcpyDeviceToHost, st));
   HT_HIP(ctx, hipStreamSynchronize(st));
+  std::vector<int64_t> ueoff(n + 1, 0);
+  if (g->merged) {
+    for (int j = 0; j <= n; ++j)
+      HT_HIP(ctx, hipMemcpyAsync(&ueoff[j], g->uindptr.p + g->bounds[j], 8, hipMemcpyDeviceToHost, st));
+    HT_HIP(ctx, hipStreamSynchronize(st));
+  }
   g->chunks.clear();
   g->chunks.resize(n);
   for (int j = 0; j < n; ++j) {
@@ -421,6 +529,8 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
     c.dst1 = g->bounds[j + 1];
     c.e0 = eoff[j];
     c.nnz = eoff[j + 1] - eoff[j];
+    c.ue0 = g->merged ? ueoff[j] : c.e0;
+    c.nu = g->merged ? ueoff[j + 1] - ueoff[j] : c.nnz;
     g->max_ndst = std::max(g->max_ndst, c.dst1 - c.dst0);
     g->max_nnz = std::max(g->max_nnz, c.nnz);
   }
@@ -527,10 +637,18 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
   }
   ItemTmp itmp;
   HT_TRY(itmp.alloc(ctx, std::max<int64_t>(std::max(g->max_ndst, g->max_nsrc), 1)));
+  DevArr<int32_t> mflag;
+  DevArr<int64_t> mrank, mpos;
+  if (g->merged) {
+    HT_TRY(g->usptr.alloc(ctx, vo + n));
+    HT_TRY(mflag.alloc(ctx, (size_t)std::max<int64_t>(g->max_nnz, 1)));
+    HT_TRY(mrank.alloc(ctx, (size_t)std::max<int64_t>(g->max_nnz, 1) + 1));
+    HT_TRY(mpos.alloc(ctx, (size_t)std::max<int64_t>(g->max_nnz, 1) + 1));
+  }
 
   const char* ord_env = getenv("HT_ITEM_ORDER");
   const bool order_items = !(ord_env && atoi(ord_env) == 0);
-  int seg_fwd = HT_SEG, seg_bwd = HT_SEG;   // tunable for experiments only
+  int seg_fwd = HT_SEG, seg_bwd = HT_SEG / 2;   // measured best at cfg2; the variables are for experiments
   if (const char* v = getenv("HT_SEG_FWD")) seg_fwd = std::max(64, atoi(v));
   if (const char* v = getenv("HT_SEG_BWD")) seg_bwd = std::max(64, atoi(v));
   cur = bmA.p;
@@ -592,6 +710,7 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
       HT_LAUNCH_CHECK(ctx);
     }
     // the same edges grouped by local source, destinations ascending inside a source
+    uint64_t* csr_sorted = nullptr;
     HT_HIP(ctx, hipMemsetAsync(sptr_j, 0, (c.nsrc + 1) * 8, st));
     if (c.nnz > 0) {
       k_csr_keys<<<nblk(c.nnz), TB, 0, st>>>(g->indptr.p, c.dst0, c.dst1, c.e0, c.nnz, g->col_local.p + c.e0,
@@ -603,13 +722,42 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
       HT_LAUNCH_CHECK(ctx);
       k_boundaries<<<nblk(c.nnz), TB, 0, st>>>(sorted, c.nnz, 32, c.nsrc, sptr_j);
       HT_LAUNCH_CHECK(ctx);
+      csr_sorted = sorted;
     }
     // work items of both directions
     // forward items are ordered by buffer-independent source id; backward ones by local destination
-    HT_TRY(build_items(ctx, itmp, g->indptr.p + c.dst0, c.e0, c.dst1 - c.dst0, g->col.p + c.e0, V, keysA.p, keysB.p,
-                       order_items, seg_fwd, &c.fwd));
-    HT_TRY(build_items(ctx, itmp, sptr_j, 0, c.nsrc, g->sdst.p + c.e0, c.dst1 - c.dst0, keysA.p, keysB.p, order_items,
-                       seg_bwd, &c.bwd));
+    if (!g->merged) {
+      HT_TRY(build_items(ctx, itmp, g->indptr.p + c.dst0, c.e0, c.dst1 - c.dst0, g->col.p + c.e0, V, keysA.p, keysB.p,
+                         order_items, seg_fwd, &c.fwd));
+      HT_TRY(build_items(ctx, itmp, sptr_j, 0, c.nsrc, g->sdst.p + c.e0, c.dst1 - c.dst0, keysA.p, keysB.p, order_items,
+                         seg_bwd, &c.bwd));
+    } else {
+      int64_t* usptr_j = g->usptr.p + c.sptr_off;
+      HT_HIP(ctx, hipMemsetAsync(usptr_j, 0, (c.nsrc + 1) * 8, st));
+      if (c.nu > 0) {
+        // buffer positions of the distinct forward pairs
+        k_gather_i32_at<<<nblk(c.nu), TB, 0, st>>>(upos.p + c.ue0, c.e0, c.nu, g->col_slot.p + c.e0, g->ucol_slot.p + c.ue0);
+        HT_LAUNCH_CHECK(ctx);
+        // distinct (source, destination) pairs of the by-source order; csr_sorted holds the sorted keys
+        uint64_t* other = csr_sorted == keysA.p ? keysB.p : keysA.p;
+        k_dup_flags_u64<<<nblk(c.nnz), TB, 0, st>>>(csr_sorted, c.nnz, mflag.p);
+        HT_LAUNCH_CHECK(ctx);
+        HT_TRY(ht_scan_i32(ctx, mflag.p, mrank.p, c.nnz, false));
+        k_flag_positions<<<nblk(c.nnz), TB, 0, st>>>(mflag.p, mrank.p, c.nnz, mpos.p);
+        HT_LAUNCH_CHECK(ctx);
+        HT_HIP(ctx, hipMemcpyAsync(mpos.p + c.nu, &c.nnz, 8, hipMemcpyHostToDevice, st));
+        k_merge_bwd<<<nblk(c.nu), TB, 0, st>>>(mpos.p, c.nu, csr_sorted, g->s.p + c.dst0, g->usdst.p + c.ue0,
+                                               g->uw_bwd.p + c.ue0, other);
+        HT_LAUNCH_CHECK(ctx);
+        k_boundaries<<<nblk(c.nu), TB, 0, st>>>(other, c.nu, 32, c.nsrc, usptr_j);
+        HT_LAUNCH_CHECK(ctx);
+        HT_HIP(ctx, hipStreamSynchronize(st));   // c.nnz was read by the async copy above
+      }
+      HT_TRY(build_items(ctx, itmp, g->uindptr.p + c.dst0, c.ue0, c.dst1 - c.dst0, g->ucol.p + c.ue0, V, keysA.p, keysB.p,
+                         order_items, seg_fwd, &c.fwd));
+      HT_TRY(build_items(ctx, itmp, usptr_j, 0, c.nsrc, g->usdst.p + c.ue0, c.dst1 - c.dst0, keysA.p, keysB.p,
+                         order_items, seg_bwd, &c.bwd));
+    }
     g->max_fpart = std::max(g->max_fpart, c.fwd.n_part);
     g->max_bpart = std::max(g->max_bpart, c.bwd.n_part);
     if (keep_all) {   // prev = every vertex seen so far
@@ -653,7 +801,8 @@ int d2h(ht_ctx* ctx, T* dst, const T* src, int64_t n) {
 int64_t ht_graph::hbm_bytes() const {
   int64_t b = indptr.bytes() + col.bytes() + s.bytes() + nbr.bytes() + col_local.bytes() + col_slot.bytes() +
               sptr.bytes() + sdst.bytes() + slot.bytes() + gslot.bytes() + reuse.bytes() + load.bytes() +
-              load_slot.bytes() + leave.bytes() + leave_slot.bytes();
+              load_slot.bytes() + leave.bytes() + leave_slot.bytes() + uindptr.bytes() + ucol.bytes() +
+              ucol_slot.bytes() + uw_fwd.bytes() + umult.bytes() + usdst.bytes() + uw_bwd.bytes() + usptr.bytes();
   for (const ChunkMeta& c : chunks) b += c.fwd.blob.bytes() + c.bwd.blob.bytes();
   return b;
 }

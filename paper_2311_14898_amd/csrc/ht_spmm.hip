@@ -64,7 +64,7 @@ __global__ void __launch_bounds__(256) k_spmm_items(SpmmArgs a) {
     float my_w = 0.f;
     if (lane < n_here) {
       my_idx = a.idx[e0 + base + lane];
-      my_w = a.ew ? a.ew[my_idx] : 1.f;
+      my_w = a.w_edge ? a.w_edge[e0 + base + lane] : (a.ew ? a.ew[my_idx] : 1.f);
     }
     for (int32_t k = 0; k < n_here; k += G) {
       int32_t c;
@@ -172,7 +172,7 @@ __global__ void __launch_bounds__(256) k_spmm_slab(SpmmArgs a, int S, int nvs, i
     float my_w = 0.f;
     if (lane < n_here) {
       my_idx = a.idx[e0 + base + lane];
-      my_w = a.ew ? a.ew[my_idx] : 1.f;
+      my_w = a.w_edge ? a.w_edge[e0 + base + lane] : (a.ew ? a.ew[my_idx] : 1.f);
     }
     for (int32_t k = 0; k < n_here; k += 4 * eps) {
       int32_t c[4];
