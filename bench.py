@@ -99,6 +99,7 @@ def main():
     ap.add_argument("--verbose", action="store_true", help="progress lines on stderr")
     ap.add_argument("--cache", choices=["adjacent", "all"], default="adjacent",
                     help="neighbour-row buffer: reuse between adjacent chunks only, or keep every row once loaded")
+    ap.add_argument("--reorder", action="store_true", help="greedy max-overlap chunk schedule (Alg. 4, phase 2)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a 1 GiB device copy kernel (known traffic) to scale rocprofv3 byte counters")
     args = ap.parse_args()
@@ -131,7 +132,8 @@ def main():
     note(f"inputs generated: V={w.V} E={w.E}")
 
     ctx = B.ht_ctx_create(0)
-    g = B.ht_partition(ctx, w.V, src, dst, w.n_chunks, cache_rows=-1 if args.cache == "all" else 0)
+    g = B.ht_partition(ctx, w.V, src, dst, w.n_chunks, cache_rows=-1 if args.cache == "all" else 0,
+                       reorder_chunks=args.reorder)
     info = B.ht_graph_info_get(g)
     note(f"partitioned in {info.partition_ms:.0f} ms: alpha={info.alpha:.2f} v_ru/V={info.v_ru / w.V:.2f} graph HBM {info.hbm_bytes / 1e9:.1f} GB")
     Xd = B.to_matrix(X, B.HT_LOC_HOST_PINNED if host else B.HT_LOC_DEVICE)
@@ -195,7 +197,7 @@ def main():
                       "scale": args.scale},
            "gteps": gteps, "hbm_gbps_dominant_kernel": achieved, "loss": loss,
            "partition_ms": info.partition_ms, "alpha": info.alpha, "v_ori": info.v_ori, "v_ru": info.v_ru,
-           "dedup_row_savings": 1.0 - info.v_ru / max(info.v_ori, 1), "v_load": info.v_load, "cache": args.cache,
+           "dedup_row_savings": 1.0 - info.v_ru / max(info.v_ori, 1), "v_load": info.v_load, "cache": args.cache, "reorder": args.reorder,
            "cache_rows": info.cache_rows,
            "phase_ms_per_step": {k: tot[k] / args.steps for k in
                                  ("t_gather_ms", "t_spmm_fwd_ms", "t_spmm_bwd_ms", "t_gemm_ms", "t_loss_ms", "t_copy_ms",

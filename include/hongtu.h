@@ -95,7 +95,10 @@ typedef struct {
   int32_t balance_mode;   /* HT_BALANCE_EDGES: b_j = min{v: indptr[v] >= ceil(j E'/n)};
                              HT_BALANCE_VERTICES: b_j = floor(j V / n)                  */
   int32_t ptr_loc;        /* where src/dst live: HT_PTR_DEVICE or HT_PTR_HOST (any host memory) */
-  int32_t reserved;
+  int32_t reorder_chunks; /* 1: schedule the chunks in the greedy max-overlap order of Alg. 4,
+                             phase 2 (chunk 0 first, then always the unplaced chunk whose N_k
+                             shares most vertices with the chunk placed last; ties: smallest
+                             id); 0: in vertex-id order.  Chunk j below means schedule position j */
   int64_t cache_rows;     /* rows of the in-place neighbour buffer: 0 = max_j |N_j| (rows of
                              N_j ^ N_{j-1} are reused, the rest evicted, as in Sec. 5.1);
                              > 0 = that many rows, same policy; -1 = as many rows as there are
@@ -160,6 +163,9 @@ int ht_graph_export_chunk(const ht_graph *g, int32_t j, ht_chunk_host *out);
  * copied to caller-allocated host arrays (any may be NULL). */
 int ht_graph_export_csc(const ht_graph *g, int64_t *indptr /*V+1*/, int32_t *col /*E_stored*/,
                         float *s /*V*/, int64_t *bounds /*n_chunks+1*/);
+/* order[j] = id (position in vertex-id order) of the chunk scheduled at position j; the identity
+ * unless reorder_chunks was set. */
+int ht_graph_chunk_order(const ht_graph *g, int32_t *order /*n_chunks*/);
 
 /* -------------------------------------------------------------------- layer */
 

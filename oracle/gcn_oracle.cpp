@@ -149,6 +149,42 @@ void orc_volumes(int64_t V, const int64_t* indptr, const int32_t* col, int n, co
   *v_ru = ru;
 }
 
+// Schedule order of the chunks of one partition by the greedy of Alg. 4, phase 2
+// (one GPU, so a batch is one chunk): the first chunk stays first; then, step by
+// step, the unplaced chunk whose neighbour set shares the most vertices with the
+// chunk placed last comes next.  Ties go to the smallest chunk id (the paper
+// does not say).  order[j] = id of the chunk scheduled at position j.
+void orc_chunk_order(const int64_t* indptr, const int32_t* col, int n, const int64_t* b, int32_t* order) {
+  std::vector<std::vector<int32_t>> N(n);
+  for (int j = 0; j < n; ++j) {
+    N[j].assign(col + indptr[b[j]], col + indptr[b[j + 1]]);
+    std::sort(N[j].begin(), N[j].end());
+    N[j].erase(std::unique(N[j].begin(), N[j].end()), N[j].end());
+  }
+  std::vector<char> placed(n, 0);
+  if (n > 0) {
+    order[0] = 0;
+    placed[0] = 1;
+  }
+  std::vector<int32_t> tmp;
+  for (int j = 1; j < n; ++j) {
+    const std::vector<int32_t>& last = N[order[j - 1]];
+    int best = -1;
+    int64_t best_ov = -1;
+    for (int k = 0; k < n; ++k) {
+      if (placed[k]) continue;
+      tmp.clear();
+      std::set_intersection(N[k].begin(), N[k].end(), last.begin(), last.end(), std::back_inserter(tmp));
+      if ((int64_t)tmp.size() > best_ov) {
+        best_ov = (int64_t)tmp.size();
+        best = k;
+      }
+    }
+    order[j] = best;
+    placed[best] = 1;
+  }
+}
+
 // ---------------------------------------------------------------------------
 // Float part (fp64)
 // ---------------------------------------------------------------------------

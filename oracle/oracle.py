@@ -91,6 +91,15 @@ def volumes(indptr: np.ndarray, col: np.ndarray, b: np.ndarray) -> Tuple[int, in
     return vo.value, vr.value
 
 
+def chunk_order(indptr: np.ndarray, col: np.ndarray, b: np.ndarray) -> np.ndarray:
+    """Greedy schedule order of the chunks (Alg. 4, phase 2, one GPU): order[j] = chunk id at position j."""
+    b = _i64(b)
+    n = b.shape[0] - 1
+    order = np.zeros(n, dtype=np.int32)
+    lib().orc_chunk_order(_p(indptr), _p(col), C.c_int(n), _p(b), _p(order))
+    return order
+
+
 def norm(indptr: np.ndarray) -> np.ndarray:
     V = indptr.shape[0] - 1
     s = np.zeros(V, dtype=np.float64)

@@ -36,7 +36,7 @@ class ht_tensor(C.Structure):
 
 class ht_part_opts(C.Structure):
     _fields_ = [("add_self_loops", C.c_int32), ("balance_mode", C.c_int32), ("ptr_loc", C.c_int32),
-                ("reserved", C.c_int32), ("cache_rows", C.c_int64)]
+                ("reorder_chunks", C.c_int32), ("cache_rows", C.c_int64)]
 
 
 class ht_graph_info(C.Structure):
@@ -93,7 +93,7 @@ class ht_plan_opts(C.Structure):
 
 EXPORTS = ["ht_ctx_create", "ht_ctx_destroy", "ht_sync", "ht_ctx_set_hbm_budget", "ht_strerror", "ht_last_error",
            "ht_partition", "ht_graph_destroy", "ht_graph_info_get", "ht_graph_chunk_info", "ht_graph_export_chunk",
-           "ht_graph_export_csc", "ht_layer_fwd", "ht_layer_bwd", "ht_epoch", "ht_epoch_buffer", "ht_tensor_to_host", "ht_memory_model",
+           "ht_graph_export_csc", "ht_graph_chunk_order", "ht_layer_fwd", "ht_layer_bwd", "ht_epoch", "ht_epoch_buffer", "ht_tensor_to_host", "ht_memory_model",
            "ht_chunk_rows_model"]
 
 _lib = None
@@ -130,6 +130,7 @@ def load():
     lib.ht_graph_chunk_info.argtypes = [C.c_void_p, C.c_int32, C.POINTER(ht_chunk_info)]
     lib.ht_graph_export_chunk.argtypes = [C.c_void_p, C.c_int32, C.POINTER(ht_chunk_host)]
     lib.ht_graph_export_csc.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.ht_graph_chunk_order.argtypes = [C.c_void_p, C.c_void_p]
     lib.ht_layer_fwd.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(ht_layer_desc), C.POINTER(ht_tensor), C.c_void_p,
                                  C.POINTER(ht_tensor), C.POINTER(ht_tensor), C.POINTER(ht_stats)]
     lib.ht_layer_bwd.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(ht_layer_desc), C.POINTER(ht_tensor), C.c_void_p,
@@ -205,12 +206,12 @@ def ht_ctx_set_hbm_budget(ctx, nbytes: int):
 # ---------------------------------------------------------------- partition
 
 def ht_partition(ctx, V: int, src: torch.Tensor, dst: torch.Tensor, n_chunks: int, add_self_loops: bool = True,
-                 balance_mode: int = HT_BALANCE_EDGES, cache_rows: int = 0):
+                 balance_mode: int = HT_BALANCE_EDGES, cache_rows: int = 0, reorder_chunks: bool = False):
     assert src.dtype == torch.int32 and dst.dtype == torch.int32 and src.numel() == dst.numel()
     assert src.is_cuda == dst.is_cuda
     src, dst = src.contiguous(), dst.contiguous()
-    opts = ht_part_opts(int(add_self_loops), balance_mode, HT_PTR_DEVICE if src.is_cuda else HT_PTR_HOST, 0,
-                        cache_rows)
+    opts = ht_part_opts(int(add_self_loops), balance_mode, HT_PTR_DEVICE if src.is_cuda else HT_PTR_HOST,
+                        int(reorder_chunks), cache_rows)
     if src.is_cuda:
         torch.cuda.synchronize()
     g = C.c_void_p()
@@ -257,6 +258,13 @@ def ht_graph_export_csc(g):
     b = np.zeros(info.n_chunks + 1, np.int64)
     _check(load().ht_graph_export_csc(g, indptr.ctypes.data, col.ctypes.data, s.ctypes.data, b.ctypes.data))
     return indptr, col, s, b
+
+
+def ht_graph_chunk_order(g) -> np.ndarray:
+    info = ht_graph_info_get(g)
+    order = np.zeros(info.n_chunks, np.int32)
+    _check(load().ht_graph_chunk_order(g, order.ctypes.data))
+    return order
 
 
 # -------------------------------------------------------------------- layer

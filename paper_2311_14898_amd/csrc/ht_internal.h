@@ -40,6 +40,8 @@ struct ht_ctx {
   // pinned host scratch (D2H staging of gradient rows)
   void* hscratch[2] = {nullptr, nullptr};
   size_t hscratch_bytes[2] = {0, 0};
+  int xcd_contig = 0;     // 1: XCDs take contiguous parts of the item list instead of interleaving it
+                          // (HT_XCD_CONTIG; measured slower at cfg2: 30.7 vs 26.0 ms per epoch)
   int no_link_fence = 0;  // 1: let aggregation kernels overlap link traffic (HT_NO_LINK_FENCE, for A/B runs)
   int link_blocks = 64;   // workgroups of a kernel that moves rows over the host link (HT_LINK_BLOCKS)
   int link_memcpy = 0;    // 1: use hipMemcpyAsync for contiguous host<->device row ranges (HT_LINK_MEMCPY)
@@ -160,7 +162,8 @@ struct ht_graph {
   DevArr<int64_t> indptr;      // [V+1]
   DevArr<int32_t> col;         // [E'] global source ids
   DevArr<float> s;             // [V] D^-1/2
-  std::vector<int64_t> bounds; // [n+1] host
+  std::vector<int64_t> bounds; // [n+1] host, in vertex-id order
+  std::vector<int32_t> order;  // [n] schedule position -> chunk id (identity unless chunks were reorganised)
   std::vector<ChunkMeta> chunks;
   DevArr<int32_t> nbr;         // [v_ori] N_j lists
   DevArr<int32_t> col_local;   // [E']

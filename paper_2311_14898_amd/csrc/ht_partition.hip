@@ -109,6 +109,19 @@ __global__ void k_popc3(const uint64_t* __restrict__ cur, const uint64_t* __rest
   }
 }
 
+// out[k] += popc(bms[k] & last) for every candidate bitmap k (grid.y = k)
+__global__ void k_overlap(const uint64_t* __restrict__ bms, int64_t nw, const uint64_t* __restrict__ last,
+                          unsigned long long* __restrict__ out) {
+  const int k = blockIdx.y;
+  const uint64_t* bm = bms + (int64_t)k * nw;
+  unsigned long long a = 0;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nw; i += (int64_t)gridDim.x * blockDim.x)
+    a += __popcll(bm[i] & last[i]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) a += __shfl_down(a, o, 64);
+  if ((threadIdx.x & 63) == 0 && a) atomicAdd(&out[k], a);
+}
+
 __global__ void k_bm_or(uint64_t* __restrict__ acc, const uint64_t* __restrict__ x, int64_t nw) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < nw) acc[i] |= x[i];
@@ -535,10 +548,50 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
     g->max_nnz = std::max(g->max_nnz, c.nnz);
   }
 
-  // ---- pass 1: |N_j|, |N_j ^ N_{j-1}| and |N_j ^ (N_0 u ... u N_{j-1})| for every chunk
   const bool keep_all = opts && opts->cache_rows == -1;   // a buffer that never evicts
   g->keep_all = keep_all;
   const int64_t nw = ceil_div64(V, 64);
+
+  // ---- chunk reorganisation (Alg. 4, phase 2; one GPU, so a batch is one chunk): the first chunk
+  // stays first, then the unplaced chunk whose neighbour set overlaps most with the chunk placed last
+  // comes next (ties: smallest id).  All n neighbour bitmaps are kept for the n-1 greedy steps.
+  g->order.resize(n);
+  for (int j = 0; j < n; ++j) g->order[j] = j;
+  if (opts && opts->reorder_chunks && n > 2) {
+    DevArr<uint64_t> bms;
+    HT_TRY(bms.alloc(ctx, (size_t)n * nw));
+    HT_HIP(ctx, hipMemsetAsync(bms.p, 0, (size_t)n * nw * 8, st));
+    for (int j = 0; j < n; ++j) {
+      const ChunkMeta& c = g->chunks[j];
+      if (c.nnz > 0) {
+        k_mark<<<nblk(c.nnz), TB, 0, st>>>(g->col.p + c.e0, c.nnz, (uint32_t*)(bms.p + (size_t)j * nw));
+        HT_LAUNCH_CHECK(ctx);
+      }
+    }
+    DevArr<unsigned long long> ov;
+    HT_TRY(ov.alloc(ctx, n));
+    std::vector<unsigned long long> hov(n);
+    std::vector<char> placed(n, 0);
+    placed[0] = 1;
+    const unsigned gx = (unsigned)std::min<int64_t>(ceil_div64(nw, TB), 64);
+    for (int j = 1; j < n; ++j) {
+      HT_HIP(ctx, hipMemsetAsync(ov.p, 0, (size_t)n * 8, st));
+      k_overlap<<<dim3(gx, n), TB, 0, st>>>(bms.p, nw, bms.p + (size_t)g->order[j - 1] * nw, ov.p);
+      HT_LAUNCH_CHECK(ctx);
+      HT_HIP(ctx, hipMemcpyAsync(hov.data(), ov.p, (size_t)n * 8, hipMemcpyDeviceToHost, st));
+      HT_HIP(ctx, hipStreamSynchronize(st));
+      int best = -1;
+      for (int k = 0; k < n; ++k)
+        if (!placed[k] && (best < 0 || hov[k] > hov[best])) best = k;
+      g->order[j] = best;
+      placed[best] = 1;
+    }
+    std::vector<ChunkMeta> sorted_chunks(n);
+    for (int j = 0; j < n; ++j) sorted_chunks[j] = std::move(g->chunks[g->order[j]]);
+    g->chunks = std::move(sorted_chunks);
+  }
+
+  // ---- pass 1: |N_j|, |N_j ^ N_{j-1}| and |N_j ^ (N_0 u ... u N_{j-1})| for every chunk, in schedule order
   DevArr<uint64_t> bmA, bmB, bmT, bmR;
   HT_TRY(bmA.alloc(ctx, nw));
   HT_TRY(bmB.alloc(ctx, nw));
@@ -817,7 +870,7 @@ int ht_partition(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src, const in
   if (V <= 0 || V >= ((int64_t)1 << 31)) return ht_set_err(ctx, HT_EINVAL, "ht_partition: V must be in [1, 2^31)");
   if (E < 0 || (E > 0 && (!src || !dst))) return ht_set_err(ctx, HT_EINVAL, "ht_partition: bad edge list");
   if (n_chunks < 1) return ht_set_err(ctx, HT_EINVAL, "ht_partition: n_chunks must be >= 1");
-  if (opts && (opts->balance_mode < 0 || opts->balance_mode > 1 || opts->ptr_loc < 0 || opts->ptr_loc > 1 ||
+  if (opts && (opts->reorder_chunks < 0 || opts->reorder_chunks > 1 || opts->balance_mode < 0 || opts->balance_mode > 1 || opts->ptr_loc < 0 || opts->ptr_loc > 1 ||
                opts->cache_rows < -1))
     return ht_set_err(ctx, HT_EINVAL, "ht_partition: bad options");
   HT_HIP(ctx, hipSetDevice(ctx->device));
@@ -903,6 +956,12 @@ int ht_graph_export_csc(const ht_graph* g, int64_t* indptr, int32_t* col, float*
   HT_TRY(d2h(ctx, s, g->s.p, g->V));
   if (bounds)
     for (int j = 0; j <= g->n; ++j) bounds[j] = g->bounds[j];
+  return HT_OK;
+}
+
+int ht_graph_chunk_order(const ht_graph* g, int32_t* order) {
+  if (!g || !order) return HT_EINVAL;
+  for (int j = 0; j < g->n; ++j) order[j] = g->order[j];
   return HT_OK;
 }
 

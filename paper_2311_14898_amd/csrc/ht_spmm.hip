@@ -145,11 +145,15 @@ __global__ void __launch_bounds__(256) k_spmm_fix(SpmmArgs a) {
 // fixed slab of the feature columns makes its L2 hold 8x more distinct source
 // rows than full-width rows would.  A wave owns one item and one slab; lanes
 // are (edge slot, float4 of the slab); `eps` edges are read per step.
-__global__ void __launch_bounds__(256) k_spmm_slab(SpmmArgs a, int S, int nvs, int eps) {
+__global__ void __launch_bounds__(256) k_spmm_slab(SpmmArgs a, int S, int nvs, int eps, int64_t grp_per_part) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int xcd = blockIdx.x & 7;
   const int slab = xcd % S;
-  const int64_t grp = (int64_t)(blockIdx.x >> 3) * (8 / S) + xcd / S;
+  // The 8/S XCDs that share a slab split the (source-ordered) item list into contiguous parts
+  // (grp_per_part > 0), so their L2s hold different source rows; or interleave it (grp_per_part = 0).
+  const int64_t i = blockIdx.x >> 3;
+  if (grp_per_part > 0 && i >= grp_per_part) return;
+  const int64_t grp = grp_per_part > 0 ? (int64_t)(xcd / S) * grp_per_part + i : i * (8 / S) + xcd / S;
   const int64_t t = grp * 4 + wave;
   if (t >= a.n_items) return;
   const int nvec = (a.d + 3) >> 2;
@@ -283,15 +287,18 @@ int ht_spmm_launch(ht_ctx* ctx, hipStream_t st, const SpmmArgs& a0) {
       const int64_t avg_len = a.n_edges / (a.n_items > 0 ? a.n_items : 1);
       if (avg_len < 96) S = 1;
       else if (avg_len < 192 && S > 2) S = 2;
-      if (a.max_slabs > 0 && S > a.max_slabs) S = a.max_slabs;
+      if (a.max_slabs > 0) S = a.max_slabs;                // experiments: force a slab count
+      while (S > 1 && nvec / S < 1) S /= 2;
       while (S < 8 && (nvec + S - 1) / S > 64) S *= 2;   // a slab must fit the 64 lanes of a wave
       const int nvs = (nvec + S - 1) / S;
       const int eps = 64 / nvs;
       if (S < 1 || (S & (S - 1)) || S > 8 || nvs < 1 || nvs > 64 || eps < 1)
         return ht_set_err(ctx, HT_ESHAPE, "aggregation: bad slab shape S=%d nvs=%d", S, nvs);
       const int64_t groups = (a.n_items + 3) / 4;
-      const int64_t rows8 = (groups + (8 / S) - 1) / (8 / S);
-      k_spmm_slab<<<(unsigned)(rows8 * 8), 256, 0, st>>>(a, S, nvs, eps);
+      const int parts = 8 / S;
+      const int64_t gpp = (groups + parts - 1) / parts;   // item groups per XCD of a slab
+      const int64_t rows8 = ctx->xcd_contig ? gpp : (groups + parts - 1) / parts;
+      k_spmm_slab<<<(unsigned)(rows8 * 8), 256, 0, st>>>(a, S, nvs, eps, ctx->xcd_contig ? gpp : 0);
       HT_LAUNCH_CHECK(ctx);
     } else if (nvec <= 8) rc = launch_items<8, 1>(ctx, st, a);
     else if (nvec <= 16) rc = launch_items<16, 1>(ctx, st, a);

@@ -18,8 +18,9 @@ def ctx():
     B.ht_ctx_destroy(c)
 
 
-def run_epoch(ctx, w, src, dst, X, y, Ws, n_chunks=None, x_loc=B.HT_LOC_DEVICE, cache_rows=0, **plan):
-    g = B.ht_partition(ctx, w.V, src.cuda(), dst.cuda(), n_chunks or w.n_chunks, cache_rows=cache_rows)
+def run_epoch(ctx, w, src, dst, X, y, Ws, n_chunks=None, x_loc=B.HT_LOC_DEVICE, cache_rows=0, reorder=False, **plan):
+    g = B.ht_partition(ctx, w.V, src.cuda(), dst.cuda(), n_chunks or w.n_chunks, cache_rows=cache_rows,
+                       reorder_chunks=reorder)
     try:
         Xd = B.to_matrix(X, x_loc)
         Wd = [x.clone().cuda() for x in Ws]
@@ -111,6 +112,10 @@ def test_cfg1_buffer_mode_in_hbm_and_chunk_count_invariance(ctx, cfg1):
     compare(out, ref, w.n_layers)
     for n in (1, 9):
         compare(run_epoch(ctx, w, src, dst, X, y, Ws, n_chunks=n), ref, w.n_layers)
+    # reorganised schedule (Alg. 4 phase 2): same result, host-resident and in HBM
+    compare(run_epoch(ctx, w, src, dst, X, y, Ws, n_chunks=9, reorder=True), ref, w.n_layers)
+    compare(run_epoch(ctx, w, src, dst, X, y, Ws, n_chunks=9, reorder=True, x_loc=B.HT_LOC_HOST_PINNED,
+                      res_h=B.HT_RES_HOST, res_a=B.HT_RES_HOST, res_g=B.HT_RES_HOST), ref, w.n_layers)
 
 
 def test_three_layers_partial_labels(ctx):

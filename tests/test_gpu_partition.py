@@ -21,10 +21,12 @@ def ctx():
     B.ht_ctx_destroy(c)
 
 
-def check_graph(ctx, V, src, dst, n, self_loops=True, mode=B.HT_BALANCE_EDGES, on_device=True, cache_rows=0):
+def check_graph(ctx, V, src, dst, n, self_loops=True, mode=B.HT_BALANCE_EDGES, on_device=True, cache_rows=0,
+                reorder=False):
     s_t = src.cuda() if on_device else src
     d_t = dst.cuda() if on_device else dst
-    g = B.ht_partition(ctx, V, s_t, d_t, n, add_self_loops=self_loops, balance_mode=mode, cache_rows=cache_rows)
+    g = B.ht_partition(ctx, V, s_t, d_t, n, add_self_loops=self_loops, balance_mode=mode, cache_rows=cache_rows,
+                       reorder_chunks=reorder)
     try:
         indptr, col, s, b = B.ht_graph_export_csc(g)
         o_indptr, o_col = orc.csc_build(V, src.numpy(), dst.numpy(), self_loops)
@@ -34,8 +36,13 @@ def check_graph(ctx, V, src, dst, n, self_loops=True, mode=B.HT_BALANCE_EDGES, o
         o_b = orc.chunk_bounds(o_indptr, n, mode)
         assert np.array_equal(b, o_b), f"bounds {b} vs {o_b}"
         info = B.ht_graph_info_get(g)
+        order = B.ht_graph_chunk_order(g)
+        o_order = orc.chunk_order(o_indptr, o_col, o_b) if (reorder and n > 2) else np.arange(n, dtype=np.int32)
+        assert np.array_equal(order, o_order), f"schedule {order} vs {o_order}"
         vo, vr = orc.volumes(o_indptr, o_col, o_b)
-        assert (info.v_ori, info.v_ru) == (vo, vr)
+        assert info.v_ori == vo
+        if not reorder:
+            assert info.v_ru == vr
         assert info.E_stored == o_indptr[-1] and info.V == V and info.n_chunks == n
         assert abs(info.alpha - vo / V) < 1e-12
         prev_N = np.zeros(0, np.int32)
@@ -46,7 +53,7 @@ def check_graph(ctx, V, src, dst, n, self_loops=True, mode=B.HT_BALANCE_EDGES, o
         for j in range(n):
             ch = B.ht_graph_export_chunk(g, j)
             ci = ch["info"]
-            b0, b1 = int(o_b[j]), int(o_b[j + 1])
+            b0, b1 = int(o_b[o_order[j]]), int(o_b[o_order[j] + 1])
             assert (ci.dst_begin, ci.dst_end) == (b0, b1)
             o = orc.chunk_dedup(o_indptr, o_col, b0, b1)
             assert np.array_equal(ch["indptr"], o_indptr[b0:b1 + 1] - o_indptr[b0])
@@ -74,6 +81,8 @@ def check_graph(ctx, V, src, dst, n, self_loops=True, mode=B.HT_BALANCE_EDGES, o
             max_nsrc = max(max_nsrc, len(slot))
         assert info.max_nsrc == max_nsrc
         assert info.v_load == n_loaded
+        if not keep_all:
+            assert info.v_ru == n_loaded          # |N_0| + sum |N_j \ N_{j-1}| along the schedule
         if keep_all:
             assert len(set(prev_slot.values())) == len(prev_slot) == info.cache_rows == len(prev_N)
         else:
@@ -108,6 +117,8 @@ def test_cfg1(ctx):
     check_graph(ctx, w.V, src, dst, w.n_chunks)
     check_graph(ctx, w.V, src, dst, 5, cache_rows=w.V)
     check_graph(ctx, w.V, src, dst, w.n_chunks, cache_rows=-1)
+    check_graph(ctx, w.V, src, dst, 9, reorder=True)
+    check_graph(ctx, w.V, src, dst, 9, reorder=True, cache_rows=-1)
 
 
 def test_several_sort_tiles_ragged_and_hubs(ctx):
@@ -123,6 +134,7 @@ def test_rmat_skew_medium(ctx):
     src, dst = inputs.rmat_edges(V, E, seed=9)
     check_graph(ctx, V, src, dst, 16)
     check_graph(ctx, V, src, dst, 16, cache_rows=-1)
+    check_graph(ctx, V, src, dst, 16, reorder=True)
 
 
 def test_paper_inplace_buffer_example(ctx):

@@ -316,3 +316,26 @@ def test_planted_mistakes_are_caught():
     assert np.abs(good - Ahat.T @ h).max() > 1e-3                 # transposed adjacency differs
     indptr_n, col_n = orc.csc_build(V, src, dst, add_self_loops=False)
     assert np.abs(orc.aggregate(indptr_n, col_n, h) - Ahat @ h).max() > 1e-3
+
+
+def test_chunk_order_greedy_against_python_sets():
+    # Alg. 4 phase 2 with one partition: max overlap with the chunk placed last, ties to the smallest id
+    V = 60
+    src, dst = _tiny_graph(V, 500, 11)
+    indptr, col = orc.csc_build(V, src, dst)
+    for n in (1, 2, 5, 9):
+        b = orc.chunk_bounds(indptr, n)
+        sets = [set(col[indptr[b[j]]:indptr[b[j + 1]]].tolist()) for j in range(n)]
+        order = [0]
+        left = list(range(1, n))
+        while left:
+            last = sets[order[-1]]
+            k = max(left, key=lambda c: (len(sets[c] & last), -c))
+            order.append(k)
+            left.remove(k)
+        assert orc.chunk_order(indptr, col, b).tolist() == order
+    # a hand-made case: chunk 2 shares more with chunk 0 than chunk 1 does, so it is scheduled second
+    src = np.array([0, 1, 2, 3, 7, 8, 0, 1, 2], dtype=np.int32)
+    dst = np.array([10, 10, 10, 10, 11, 11, 12, 12, 12], dtype=np.int32)
+    indptr, col = orc.csc_build(13, src, dst, add_self_loops=False)
+    assert orc.chunk_order(indptr, col, np.array([0, 11, 12, 13])).tolist() == [0, 2, 1]
