@@ -131,6 +131,10 @@ int ht_ctx_create(ht_ctx** out, int device, void* hip_stream) {
   if (const char* v = getenv("HT_LINK_MEMCPY")) c->link_memcpy = atoi(v);
   if (const char* v = getenv("HT_SLABS_FWD")) c->slabs_fwd = atoi(v);
   if (const char* v = getenv("HT_SLABS_BWD")) c->slabs_bwd = atoi(v);
+  if (const char* v = getenv("HT_AGG_UNROLL")) c->agg_unroll = atoi(v) == 8 ? 8 : 4;
+  if (const char* v = getenv("HT_AGG_UNIFORM")) c->agg_uniform = atoi(v);
+  if (const char* v = getenv("HT_SLAB_ALIGN")) c->slab_align = atoi(v);
+  if (const char* v = getenv("HT_AGG_PHASES")) c->agg_phases = atoi(v) > 1 ? atoi(v) : 1;
   if (hip_stream) {
     c->stream = (hipStream_t)hip_stream;
   } else {

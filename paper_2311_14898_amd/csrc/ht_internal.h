@@ -46,6 +46,10 @@ struct ht_ctx {
   int link_blocks = 64;   // workgroups of a kernel that moves rows over the host link (HT_LINK_BLOCKS)
   int link_memcpy = 0;    // 1: use hipMemcpyAsync for contiguous host<->device row ranges (HT_LINK_MEMCPY)
   int slabs_fwd = 0, slabs_bwd = 0;  // caps on feature slabs (HT_SLABS_FWD / HT_SLABS_BWD), 0 = by width
+  int agg_unroll = 4;     // HT_AGG_UNROLL: row reads in flight per lane (4 or 8)
+  int agg_uniform = 1;    // HT_AGG_UNIFORM=0: no wave-uniform fast path for one-edge-per-step shapes
+  int slab_align = 1;     // HT_SLAB_ALIGN=0: do not round slabs to whole cache lines
+  int agg_phases = 1;     // HT_AGG_PHASES: slabs are spread over this many consecutive launches
   int agg_variant = 0;  // 0: feature slabs per XCD; 1: full-width rows per wave (HT_AGG_VARIANT, for A/B runs)
   int n_threads = 0;  // host threads for CPU-side accumulation (0 = decide on first use)
 };
@@ -113,6 +117,14 @@ static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b;
 
 // ---- primitives (ht_prims.hip) -------------------------------------------------------
 // Exclusive prefix sum of n values into out[0..n); out[n] = total when want_total.
+// Row pitch (in floats) of a library-allocated [rows x d] matrix: a multiple of 4 (16-byte
+// vectors); in HBM, rows start on 128-byte cache lines when that costs at most 3 % more memory,
+// so a feature slab never shares a line with the slab of another XCD.
+inline int64_t ht_row_pitch(int32_t d, bool device) {
+  const int64_t p4 = ((int64_t)d + 3) & ~(int64_t)3, p32 = ((int64_t)d + 31) & ~(int64_t)31;
+  return (device && p32 * 100 <= p4 * 103) ? p32 : p4;
+}
+
 int ht_scan_i32(ht_ctx* ctx, const int32_t* in, int64_t* out, int64_t n, bool want_total);
 int ht_scan_i64(ht_ctx* ctx, const int64_t* in, int64_t* out, int64_t n, bool want_total);
 // Stable LSD radix sort of 64-bit keys on bits [bit_lo, bit_hi).  keys and tmp

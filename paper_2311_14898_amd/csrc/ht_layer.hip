@@ -268,7 +268,7 @@ int layer_fwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* H_in, con
   const bool h_dev = H_out->loc == HT_LOC_DEVICE;
   const bool staged = a_host || !h_dev;                              // some rows leave through the output stream
   const bool side_in = buffer && H_in->loc == HT_LOC_HOST_PINNED;    // gather runs beside the compute
-  const int64_t a_ld = A_ckpt ? A_ckpt->ld : ((di + 3) & ~3);
+  const int64_t a_ld = A_ckpt ? A_ckpt->ld : ht_row_pitch(di, true);
   const int64_t mx = std::max<int64_t>(g->max_ndst, 1);
   float* a_stage[2] = {nullptr, nullptr};
   float* h_stage[2] = {nullptr, nullptr};
@@ -744,7 +744,7 @@ namespace {
 int ws_tensor(ht_ctx* ctx, EpochWs* ws, int64_t V, int32_t d, int res, ht_tensor* t) {
   t->rows = V;
   t->cols = d;
-  t->ld = (d + 3) & ~3;
+  t->ld = ht_row_pitch(d, res != HT_RES_HOST);
   const size_t bytes = (size_t)V * t->ld * 4;
   if (res == HT_RES_HOST) {
     void* p = nullptr;

@@ -145,10 +145,11 @@ __global__ void __launch_bounds__(256) k_spmm_fix(SpmmArgs a) {
 // fixed slab of the feature columns makes its L2 hold 8x more distinct source
 // rows than full-width rows would.  A wave owns one item and one slab; lanes
 // are (edge slot, float4 of the slab); `eps` edges are read per step.
-__global__ void __launch_bounds__(256) k_spmm_slab(SpmmArgs a, int S, int nvs, int eps, int64_t grp_per_part) {
+template <int U, bool UNI>
+__global__ void __launch_bounds__(256) k_spmm_slab(SpmmArgs a, int S, int nvs, int eps, int64_t grp_per_part, int slab0) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int xcd = blockIdx.x & 7;
-  const int slab = xcd % S;
+  const int slab = slab0 + xcd % S;
   // The 8/S XCDs that share a slab split the (source-ordered) item list into contiguous parts
   // (grp_per_part > 0), so their L2s hold different source rows; or interleave it (grp_per_part = 0).
   const int64_t i = blockIdx.x >> 3;
@@ -178,23 +179,46 @@ __global__ void __launch_bounds__(256) k_spmm_slab(SpmmArgs a, int S, int nvs, i
       my_idx = a.idx[e0 + base + lane];
       my_w = a.w_edge ? a.w_edge[e0 + base + lane] : (a.ew ? a.ew[my_idx] : 1.f);
     }
-    for (int32_t k = 0; k < n_here; k += 4 * eps) {
-      int32_t c[4];
-      float w[4];
+    if (UNI) {
+      // one edge per step for the whole wave: the index and weight are wave-uniform
+      for (int32_t k = 0; k < n_here; k += U) {
+        int32_t c[U];
+        float w[U];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int kk = k + u * eps + es;
-        const int kc = kk < n_here ? kk : (n_here - 1);   // past the end: re-read the last edge with weight 0
-        c[u] = __shfl(my_idx, kc, 64);
-        w[u] = __shfl(my_w, kc, 64);
-        if (kk >= n_here) w[u] = 0.f;
+        for (int u = 0; u < U; ++u) {
+          const int kk = k + u;
+          const int kc = kk < n_here ? kk : (n_here - 1);
+          c[u] = __builtin_amdgcn_readlane(my_idx, kc);
+          w[u] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_w), kc));
+          if (kk >= n_here) w[u] = 0.f;
+        }
+        if (active) {
+          float4 v[U];
+#pragma unroll
+          for (int u = 0; u < U; ++u) v[u] = ld4(srcc + (int64_t)c[u] * a.src_ld);
+#pragma unroll
+          for (int u = 0; u < U; ++u) acc = fma4(w[u], v[u], acc);
+        }
       }
-      if (active) {
-        float4 v[4];
+    } else {
+      for (int32_t k = 0; k < n_here; k += U * eps) {
+        int32_t c[U];
+        float w[U];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = ld4(srcc + (int64_t)c[u] * a.src_ld);
+        for (int u = 0; u < U; ++u) {
+          const int kk = k + u * eps + es;
+          const int kc = kk < n_here ? kk : (n_here - 1);   // past the end: re-read the last edge with weight 0
+          c[u] = __shfl(my_idx, kc, 64);
+          w[u] = __shfl(my_w, kc, 64);
+          if (kk >= n_here) w[u] = 0.f;
+        }
+        if (active) {
+          float4 v[U];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) acc = fma4(w[u], v[u], acc);
+          for (int u = 0; u < U; ++u) v[u] = ld4(srcc + (int64_t)c[u] * a.src_ld);
+#pragma unroll
+          for (int u = 0; u < U; ++u) acc = fma4(w[u], v[u], acc);
+        }
       }
     }
   }
@@ -289,8 +313,12 @@ int ht_spmm_launch(ht_ctx* ctx, hipStream_t st, const SpmmArgs& a0) {
       else if (avg_len < 192 && S > 2) S = 2;
       if (a.max_slabs > 0) S = a.max_slabs;                // experiments: force a slab count
       while (S > 1 && nvec / S < 1) S /= 2;
-      while (S < 8 && (nvec + S - 1) / S > 64) S *= 2;   // a slab must fit the 64 lanes of a wave
-      const int nvs = (nvec + S - 1) / S;
+      int P = ctx->agg_phases;
+      while (P > 1 && nvec / (S * P) < 1) P /= 2;
+      while (S < 8 && (nvec + S * P - 1) / (S * P) > 64) S *= 2;   // a slab must fit the 64 lanes of a wave
+      int nvs = (nvec + S * P - 1) / (S * P);
+      // rows that start on 128-byte lines: slabs in whole lines, so no line is fetched by two XCDs
+      if (ctx->slab_align && (a.src_ld & 31) == 0 && ((uintptr_t)a.src & 127) == 0 && nvs > 8 && ((nvs + 7) & ~7) <= 64) nvs = (nvs + 7) & ~7;
       const int eps = 64 / nvs;
       if (S < 1 || (S & (S - 1)) || S > 8 || nvs < 1 || nvs > 64 || eps < 1)
         return ht_set_err(ctx, HT_ESHAPE, "aggregation: bad slab shape S=%d nvs=%d", S, nvs);
@@ -298,8 +326,19 @@ int ht_spmm_launch(ht_ctx* ctx, hipStream_t st, const SpmmArgs& a0) {
       const int parts = 8 / S;
       const int64_t gpp = (groups + parts - 1) / parts;   // item groups per XCD of a slab
       const int64_t rows8 = ctx->xcd_contig ? gpp : (groups + parts - 1) / parts;
-      k_spmm_slab<<<(unsigned)(rows8 * 8), 256, 0, st>>>(a, S, nvs, eps, ctx->xcd_contig ? gpp : 0);
-      HT_LAUNCH_CHECK(ctx);
+      for (int p = 0; p < P; ++p) {
+        const unsigned nb = (unsigned)(rows8 * 8);
+        const int64_t gp = ctx->xcd_contig ? gpp : 0;
+        const bool uni = eps == 1 && ctx->agg_uniform;
+        if (ctx->agg_unroll == 8) {
+          if (uni) k_spmm_slab<8, true><<<nb, 256, 0, st>>>(a, S, nvs, eps, gp, p * S);
+          else k_spmm_slab<8, false><<<nb, 256, 0, st>>>(a, S, nvs, eps, gp, p * S);
+        } else {
+          if (uni) k_spmm_slab<4, true><<<nb, 256, 0, st>>>(a, S, nvs, eps, gp, p * S);
+          else k_spmm_slab<4, false><<<nb, 256, 0, st>>>(a, S, nvs, eps, gp, p * S);
+        }
+        HT_LAUNCH_CHECK(ctx);
+      }
     } else if (nvec <= 8) rc = launch_items<8, 1>(ctx, st, a);
     else if (nvec <= 16) rc = launch_items<16, 1>(ctx, st, a);
     else if (nvec <= 32) rc = launch_items<32, 1>(ctx, st, a);
