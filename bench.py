@@ -100,6 +100,9 @@ def main():
     ap.add_argument("--cache", choices=["adjacent", "all"], default="adjacent",
                     help="neighbour-row buffer: reuse between adjacent chunks only, or keep every row once loaded")
     ap.add_argument("--reorder", action="store_true", help="greedy max-overlap chunk schedule (Alg. 4, phase 2)")
+    ap.add_argument("--order", choices=["paper", "auto"], default="paper",
+                    help="stage order of a layer: aggregate then transform as Eq. 2 prints it (the timed default), or "
+                         "transform first in the layers that get narrower (same function, fewer bytes aggregated)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a 1 GiB device copy kernel (known traffic) to scale rocprofv3 byte counters")
     args = ap.parse_args()
@@ -151,38 +154,48 @@ def main():
         torch.cuda.synchronize()
         del a, b
     note("inputs resident")
-    for _ in range(args.warmup):
-        B.ht_epoch(ctx, g, w.dims, Wd, w.lr, Xd, yd, **plan)
-        note("warm-up epoch done")
-    torch.cuda.synchronize()
-    agg = {"t": 0.0, "n": 0, "bytes": 0.0}
-    tot = None
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        loss, st = B.ht_epoch(ctx, g, w.dims, Wd, w.lr, Xd, yd, want_stats=True, **plan)
-        d = st.as_dict()
-        note(f"epoch done: {d['t_total_ms']:.1f} ms, loss {loss:.5f}")
-        agg["t"] += d["t_agg_fwd_layer_ms"][0]
-        agg["n"] += d["n_agg_fwd_layer"][0]
-        agg["bytes"] += d["agg_fwd_layer_alg_bytes"][0]
-        if tot is None:
-            tot = d
-        else:
-            for k, v in d.items():
-                tot[k] = [a + b for a, b in zip(tot[k], v)] if isinstance(v, list) else tot[k] + v
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+
+    def timed_epochs(order):
+        """W warm-up epochs, then K timed ones; returns (seconds, summed stats, last loss)."""
+        for _ in range(args.warmup):
+            B.ht_epoch(ctx, g, w.dims, Wd, w.lr, Xd, yd, order=order, **plan)
+            note("warm-up epoch done")
+        torch.cuda.synchronize()
+        tot = None
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            loss, st = B.ht_epoch(ctx, g, w.dims, Wd, w.lr, Xd, yd, want_stats=True, order=order, **plan)
+            d = st.as_dict()
+            note(f"epoch done: {d['t_total_ms']:.1f} ms, loss {loss:.5f}")
+            if tot is None:
+                tot = d
+            else:
+                for k, v in d.items():
+                    tot[k] = [a + b for a, b in zip(tot[k], v)] if isinstance(v, list) else tot[k] + v
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0, tot, loss
+
+    main_order = B.HT_ORDER_AUTO if args.order == "auto" else B.HT_ORDER_AGG_FIRST
+    elapsed, tot, loss = timed_epochs(main_order)
+    agg = {"t": tot["t_agg_fwd_layer_ms"][0], "n": tot["n_agg_fwd_layer"][0], "bytes": tot["agg_fwd_layer_alg_bytes"][0]}
+    other = None
+    if not host and args.scale == 1.0:
+        # the other stage order on the same graph and weights (which keep training: the loss differs)
+        o_el, o_tot, _ = timed_epochs(B.HT_ORDER_AGG_FIRST if args.order == "auto" else B.HT_ORDER_AUTO)
+        other = {"order": "paper" if args.order == "auto" else "auto", "ms_per_step": 1e3 * o_el / args.steps,
+                 "agg_fwd_layer_ms_per_step": [x / args.steps for x in o_tot["t_agg_fwd_layer_ms"][:w.n_layers]],
+                 "t_spmm_bwd_ms": o_tot["t_spmm_bwd_ms"] / args.steps, "t_gemm_ms": o_tot["t_gemm_ms"] / args.steps}
     ms_per_step = 1e3 * elapsed / args.steps
     Ep = info.E_stored
     L = w.n_layers
-    gteps = Ep * (2 * L - 1) / (elapsed / args.steps) / 1e9
+    gteps = tot["edges"] / elapsed / 1e9      # stored edges aggregated per second (L forward + L-1 backward passes)
 
     # roofline of the dominant kernel: the layer-0 forward aggregation (widest rows, every chunk)
     avg_ms = agg["t"] / max(agg["n"], 1)
     bytes_per_launch = agg["bytes"] / max(agg["n"], 1)
     achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
     traffic = read_traffic(f"agg_fwd_{args.workload}_traffic.txt") if args.scale == 1.0 else None
-    roofline = {"bound": "hbm", "kernel": "forward aggregation, layer 0 (k_spmm_items)", "achieved": achieved,
+    roofline = {"bound": "hbm", "kernel": "forward aggregation, layer 0 (k_spmm_slab)", "achieved": achieved,
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                 "avg_launch_ms": avg_ms, "launches": agg["n"], "algorithmic_bytes_per_launch": bytes_per_launch,
                 "gathered_GBs_cacheless": 4.0 * w.dims[0] * Ep / max(agg["t"] / args.steps * 1e-3, 1e-12) / 1e9}
@@ -208,6 +221,7 @@ def main():
            "bytes_h2d_nodedup_per_step": tot["bytes_h2d_nodedup"] / args.steps,
            "input_generation_s": t_gen,
            "paper_context": "HongTu-IM 2-layer GCN on reddit (same shape), 1xA100: 0.20 s/epoch (Table 4); other hardware, real dataset",
+           "order": args.order, "other_order": other,
            "roofline": roofline}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, src.cpu().numpy(), dst.cpu().numpy(), X, y, Ws)

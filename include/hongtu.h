@@ -182,13 +182,21 @@ enum { HT_GATHER_AUTO = 0, HT_GATHER_DIRECT = 1, HT_GATHER_BUFFER = 2 };
  *                  the update stage is recomputed (the hybrid)
  *   HT_CKPT_INPUT  the layer input h^l: the aggregate is recomputed as well */
 enum { HT_CKPT_AGG = 0, HT_CKPT_INPUT = 1 };
+/* Order of the two stages of a layer.  Eq. 2 aggregates first and transforms the
+ * aggregate, which is what Sec. 4.2's hybrid caches.  Because both stages are
+ * linear, H' = act(A_hat (H W)) is the same function; it aggregates rows of
+ * width d_out instead of d_in, which moves fewer bytes when d_out < d_in.
+ *   HT_ORDER_AGG_FIRST     a = A_hat H ; H' = act(a W)            (Eq. 2 as printed)
+ *   HT_ORDER_UPDATE_FIRST  t = H W     ; H' = act(A_hat t)
+ * UPDATE_FIRST needs every vertex tensor of the call in HBM. */
+enum { HT_ORDER_AGG_FIRST = 0, HT_ORDER_UPDATE_FIRST = 1, HT_ORDER_AUTO = 2 };
 
 typedef struct {
   int32_t d_in, d_out;
   int32_t act;         /* HT_ACT_* applied after the linear transform */
   int32_t gather_mode; /* HT_GATHER_*                                  */
   int32_t ckpt_kind;   /* HT_CKPT_* (backward only)                    */
-  int32_t reserved;
+  int32_t order;       /* HT_ORDER_AGG_FIRST or HT_ORDER_UPDATE_FIRST  */
 } ht_layer_desc;
 
 /* Timings are HIP-event times on the stream that ran the work, summed over
@@ -227,7 +235,10 @@ typedef struct {
  *   H_out[V_j] = act(a[V_j] W)                              (update,   Eq. 2)
  * H_in [V x d_in], H_out [V x d_out]: device or pinned host.  W: device,
  * row-major [d_in x d_out], dense.  A_ckpt [V x d_in] (nullable): receives the
- * aggregate output as the recomputation checkpoint. */
+ * aggregate output as the recomputation checkpoint.
+ * With desc->order = HT_ORDER_UPDATE_FIRST: t = H_in W for every vertex, then
+ * H_out[V_j] = act(s_v * sum s_{u_e} t[u_e]); A_ckpt is not written (there is
+ * no aggregate of width d_in); H_in and H_out must be in HBM, else HT_ESHAPE. */
 int ht_layer_fwd(ht_ctx *ctx, const ht_graph *g, const ht_layer_desc *desc, const ht_tensor *H_in,
                  const float *W, ht_tensor *H_out, ht_tensor *A_ckpt, ht_stats *stats);
 
@@ -237,7 +248,10 @@ int ht_layer_fwd(ht_ctx *ctx, const ht_graph *g, const ht_layer_desc *desc, cons
  * ckpt: a^l (HT_CKPT_AGG) or h^l (HT_CKPT_INPUT).  H_out (nullable): when
  * given, the ReLU derivative is taken from [H_out > 0] and z is not recomputed.
  * dH_in (nullable: no input gradient wanted) is in/out: ACCUMULATED into, the
- * caller zeroes it.  All vertex tensors: device or pinned host. */
+ * caller zeroes it.  All vertex tensors: device or pinned host.
+ * With desc->order = HT_ORDER_UPDATE_FIRST (all tensors in HBM): ckpt is the
+ * layer input h^l; dz as above (H_out is required when act = relu);
+ * dt[N_j] += s_u * sum s_v dz[v] ; dW = h^T dt (overwritten) ; dH_in += dt W^T. */
 int ht_layer_bwd(ht_ctx *ctx, const ht_graph *g, const ht_layer_desc *desc, const ht_tensor *ckpt,
                  const float *W, const ht_tensor *dH_out, const ht_tensor *H_out, ht_tensor *dH_in,
                  float *dW, ht_stats *stats);
@@ -265,7 +279,9 @@ typedef struct {
   int32_t res_g;  /* residency of the gradients grad h^l                   */
   int32_t inter;  /* HT_INTER_*                                            */
   int32_t gather_mode;
-  int32_t reserved;
+  int32_t order;  /* HT_ORDER_*: AGG_FIRST (0, Eq. 2 as printed) for every layer;
+                   * UPDATE_FIRST / AUTO: update first in the layers whose tensors
+                   * are all in HBM (AUTO: only where d_out < d_in)         */
   int64_t hbm_budget_bytes; /* 0 = what the device reports free, minus a margin */
 } ht_plan_opts;
 

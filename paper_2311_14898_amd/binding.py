@@ -24,6 +24,7 @@ HT_PTR_DEVICE, HT_PTR_HOST = 0, 1
 HT_ACT_NONE, HT_ACT_RELU = 0, 1
 HT_GATHER_AUTO, HT_GATHER_DIRECT, HT_GATHER_BUFFER = 0, 1, 2
 HT_CKPT_AGG, HT_CKPT_INPUT = 0, 1
+HT_ORDER_AGG_FIRST, HT_ORDER_UPDATE_FIRST, HT_ORDER_AUTO = 0, 1, 2
 HT_RES_AUTO, HT_RES_HBM, HT_RES_HOST = 0, 1, 2
 HT_INTER_AUTO, HT_INTER_MASK, HT_INTER_HYBRID = 0, 1, 2
 HT_BUF_H, HT_BUF_A, HT_BUF_GH, HT_BUF_DW = 0, 1, 2, 3
@@ -58,7 +59,7 @@ class ht_chunk_host(C.Structure):
 
 class ht_layer_desc(C.Structure):
     _fields_ = [("d_in", C.c_int32), ("d_out", C.c_int32), ("act", C.c_int32), ("gather_mode", C.c_int32),
-                ("ckpt_kind", C.c_int32), ("reserved", C.c_int32)]
+                ("ckpt_kind", C.c_int32), ("order", C.c_int32)]
 
 
 class ht_stats(C.Structure):
@@ -88,7 +89,7 @@ class ht_model(C.Structure):
 
 class ht_plan_opts(C.Structure):
     _fields_ = [("res_h", C.c_int32), ("res_a", C.c_int32), ("res_g", C.c_int32), ("inter", C.c_int32),
-                ("gather_mode", C.c_int32), ("reserved", C.c_int32), ("hbm_budget_bytes", C.c_int64)]
+                ("gather_mode", C.c_int32), ("order", C.c_int32), ("hbm_budget_bytes", C.c_int64)]
 
 
 EXPORTS = ["ht_ctx_create", "ht_ctx_destroy", "ht_sync", "ht_ctx_set_hbm_budget", "ht_strerror", "ht_last_error",
@@ -272,9 +273,10 @@ def ht_graph_chunk_order(g) -> np.ndarray:
 # -------------------------------------------------------------------- layer
 
 def ht_layer_fwd(ctx, g, d_in: int, d_out: int, act: int, H_in: torch.Tensor, W: torch.Tensor, H_out: torch.Tensor,
-                 A_ckpt: Optional[torch.Tensor] = None, gather_mode: int = HT_GATHER_AUTO, want_stats: bool = False):
+                 A_ckpt: Optional[torch.Tensor] = None, gather_mode: int = HT_GATHER_AUTO, want_stats: bool = False,
+                 order: int = HT_ORDER_AGG_FIRST):
     assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous() and tuple(W.shape) == (d_in, d_out)
-    desc = ht_layer_desc(d_in, d_out, act, gather_mode, 0, 0)
+    desc = ht_layer_desc(d_in, d_out, act, gather_mode, 0, order)
     hin, hout = tensor_view(H_in, d_in), tensor_view(H_out, d_out)
     ack = tensor_view(A_ckpt, d_in) if A_ckpt is not None else None
     st = ht_stats() if want_stats else None
@@ -287,10 +289,11 @@ def ht_layer_fwd(ctx, g, d_in: int, d_out: int, act: int, H_in: torch.Tensor, W:
 
 def ht_layer_bwd(ctx, g, d_in: int, d_out: int, act: int, ckpt: torch.Tensor, W: torch.Tensor, dH_out: torch.Tensor,
                  dW: torch.Tensor, dH_in: Optional[torch.Tensor] = None, H_out: Optional[torch.Tensor] = None,
-                 ckpt_kind: int = HT_CKPT_AGG, gather_mode: int = HT_GATHER_AUTO, want_stats: bool = False):
+                 ckpt_kind: int = HT_CKPT_AGG, gather_mode: int = HT_GATHER_AUTO, want_stats: bool = False,
+                 order: int = HT_ORDER_AGG_FIRST):
     assert W.is_cuda and W.is_contiguous() and tuple(W.shape) == (d_in, d_out)
     assert dW.is_cuda and dW.is_contiguous() and tuple(dW.shape) == (d_in, d_out) and dW.dtype == torch.float32
-    desc = ht_layer_desc(d_in, d_out, act, gather_mode, ckpt_kind, 0)
+    desc = ht_layer_desc(d_in, d_out, act, gather_mode, ckpt_kind, order)
     ck, dho = tensor_view(ckpt, d_in), tensor_view(dH_out, d_out)
     ho = tensor_view(H_out, d_out) if H_out is not None else None
     dhi = tensor_view(dH_in, d_in) if dH_in is not None else None
@@ -306,7 +309,8 @@ def ht_layer_bwd(ctx, g, d_in: int, d_out: int, act: int, ckpt: torch.Tensor, W:
 
 def ht_epoch(ctx, g, dims: Sequence[int], Ws: List[torch.Tensor], lr: float, X: torch.Tensor, labels: torch.Tensor,
              res_h: int = HT_RES_AUTO, res_a: int = HT_RES_AUTO, res_g: int = HT_RES_AUTO, inter: int = HT_INTER_AUTO,
-             gather_mode: int = HT_GATHER_AUTO, hbm_budget_bytes: int = 0, want_stats: bool = False, sync: bool = True):
+             gather_mode: int = HT_GATHER_AUTO, hbm_budget_bytes: int = 0, want_stats: bool = False, sync: bool = True,
+             order: int = HT_ORDER_AGG_FIRST):
     """One epoch; Ws (device tensors) are updated in place.  Returns (loss, stats or None)."""
     L = len(dims) - 1
     assert len(Ws) == L and labels.is_cuda and labels.dtype == torch.int32
@@ -315,7 +319,7 @@ def ht_epoch(ctx, g, dims: Sequence[int], Ws: List[torch.Tensor], lr: float, X: 
     dims_a = (C.c_int32 * (L + 1))(*dims)
     Wp = (C.c_void_p * L)(*[w.data_ptr() for w in Ws])
     model = ht_model(L, 0, dims_a, Wp, lr, 0)
-    plan = ht_plan_opts(res_h, res_a, res_g, inter, gather_mode, 0, hbm_budget_bytes)
+    plan = ht_plan_opts(res_h, res_a, res_g, inter, gather_mode, order, hbm_budget_bytes)
     x = tensor_view(X, dims[0])
     loss = C.c_float(0.0)
     st = ht_stats() if want_stats else None

@@ -107,7 +107,8 @@ __global__ void __launch_bounds__(256) k_gemm_nn(const float* __restrict__ A, in
         const int64_t gr = m0 + wm * TI * 32 + i * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
         if (gr < M) {
           float v = acc[i][j][e];
-          if (relu) v = v > 0.f ? v : 0.f;
+          if (relu & 1) v = v > 0.f ? v : 0.f;
+          if (relu & 2) v += C[gr * ldc + gc];
           C[gr * ldc + gc] = v;
         }
       }
@@ -240,7 +241,7 @@ int ht_gemm_nn(ht_ctx* ctx, hipStream_t st, const float* A, int64_t lda, const f
 }
 
 int ht_gemm_nt(ht_ctx* ctx, hipStream_t st, const float* A, int64_t lda, const float* B, float* C, int64_t ldc,
-               int64_t M, int32_t N, int32_t K) {
+               int64_t M, int32_t N, int32_t K, int accumulate) {
   // C[M x K] = A[M x N] (B[K x N])^T : reduction over N, output width K
   if (lda & 3) return ht_set_err(ctx, HT_ESHAPE, "gemm: row pitch must be a multiple of 4");
   const int Rp = round_up(N, BK), Cp = round_up(K, 128);
@@ -249,7 +250,7 @@ int ht_gemm_nt(ht_ctx* ctx, hipStream_t st, const float* A, int64_t lda, const f
   // Bp[n][k] = B[k][n]
   k_pack_b<<<(unsigned)(((int64_t)Rp * Cp + 255) / 256), 256, 0, st>>>(B, K, N, 1, Bp, Rp, Cp);
   HT_LAUNCH_CHECK(ctx);
-  return gemm_nn_packed(ctx, st, A, lda, Bp, Cp, C, ldc, M, N, K, 0);
+  return gemm_nn_packed(ctx, st, A, lda, Bp, Cp, C, ldc, M, N, K, accumulate ? 2 : 0);
 }
 
 int ht_gemm_tn(ht_ctx* ctx, hipStream_t st, const float* A, int64_t lda, const float* B, int64_t ldb, float* C,

@@ -20,7 +20,7 @@ struct EpochWs;
 
 enum {
   HT_S_PACKW = 0, HT_S_TNPART, HT_S_LOSS, HT_S_ACHUNK, HT_S_OCHUNK, HT_S_ZCHUNK, HT_S_DZCHUNK, HT_S_DACHUNK,
-  HT_S_NBUF, HT_S_SPART, HT_S_LEAVE, HT_S_MISC, HT_N_SCRATCH
+  HT_S_NBUF, HT_S_SPART, HT_S_LEAVE, HT_S_MISC, HT_S_TFULL, HT_N_SCRATCH
 };
 
 struct ht_ctx {
@@ -240,6 +240,7 @@ struct SpmmArgs {
   const int32_t* post_idx;// row r -> index into post (nullable: r)
   int32_t accumulate;     // 1: out += value
   float* partial;         // [n_part x out_ld] workspace
+  int relu = 0;           // clamp the finished row at 0 (only without accumulate)
   int max_slabs = 0;      // cap on the number of feature slabs (0 = by width)
   // optional timing of the two kernels (null: not timed)
   struct Timer* tm = nullptr;
@@ -265,7 +266,7 @@ int ht_gemm_nn(ht_ctx* ctx, hipStream_t st, const float* A, int64_t lda, const f
                int64_t M, int32_t K, int32_t N, int relu);
 // C[M x K] = A[M x N] B[K x N]^T
 int ht_gemm_nt(ht_ctx* ctx, hipStream_t st, const float* A, int64_t lda, const float* B, float* C, int64_t ldc,
-               int64_t M, int32_t N, int32_t K);
+               int64_t M, int32_t N, int32_t K, int accumulate);
 // C[K x N] (+)= A[M x K]^T B[M x N]; fixed-order reduction over M slices.
 int ht_gemm_tn(ht_ctx* ctx, hipStream_t st, const float* A, int64_t lda, const float* B, int64_t ldb, float* C,
                int64_t M, int32_t K, int32_t N, int accumulate);

@@ -22,6 +22,7 @@ struct EpochWs {
   int64_t V = 0;
   std::vector<int32_t> dims;
   int res_h = 0, res_a = 0, res_g = 0;
+  uint32_t upd_mask = 0;             // bit l: layer l runs update-first (no a^l is kept for it)
   std::vector<ht_tensor> h, a, gh;  // h[l] = h^l (l >= 1; h[0] unused), a[l], gh[l] = grad h^l (l >= 1)
   std::vector<float*> dW;
   std::vector<size_t> dev_bytes_of;  // for freeing
@@ -448,7 +449,7 @@ int layer_bwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* ckpt, con
   const bool relu = desc->act == HT_ACT_RELU;
   const bool agg_ckpt = desc->ckpt_kind == HT_CKPT_AGG;
   const int64_t mx = std::max<int64_t>(g->max_ndst, 1);
-  const int64_t ld_i = (di + 3) & ~3, ld_o = (dn + 3) & ~3;
+  const int64_t ld_i = ht_row_pitch(di, true), ld_o = ht_row_pitch(dn, true);
 
   // forward-side inputs
   bool agg_buffer = false;
@@ -613,7 +614,7 @@ int layer_bwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* ckpt, con
     first = false;
     if (dH_in) {
       R.tm.begin(&R.st->t_gemm_ms);
-      HT_TRY(ht_gemm_nt(ctx, st, dz_rows, dz_ld, W, da_chunk, ld_i, ndst, dn, di));
+      HT_TRY(ht_gemm_nt(ctx, st, dz_rows, dz_ld, W, da_chunk, ld_i, ndst, dn, di, 0));
       R.tm.end();
       R.st->n_gemm += 1;
       R.st->gemm_flops += 2.0 * ndst * di * dn;
@@ -711,6 +712,163 @@ int layer_bwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* ckpt, con
   return HT_OK;
 }
 
+// ---- update-first order: H' = act(A_hat (H W)).  Same function as Eq. 2 (both stages are
+// linear), aggregating rows of width d_out.  Everything lives in HBM here.
+
+int need_hbm(ht_ctx* ctx, const ht_tensor* t, const char* name) {
+  if (t->loc != HT_LOC_DEVICE)
+    return ht_set_err(ctx, HT_ESHAPE, "update-first order: %s must be in HBM", name);
+  return HT_OK;
+}
+
+// Aggregation arguments of chunk j at width d: forward (rows = destinations, reading rows of
+// `src` by global id) or backward (rows = sources N_j, reading the chunk's destination rows).
+void agg_args_direct(const ht_graph* g, const ChunkMeta& c, bool fwd, SpmmArgs* a) {
+  const ItemSet& it = fwd ? c.fwd : c.bwd;
+  a->it_row = it.row; a->it_e0 = it.e0; a->it_len = it.len; a->it_part = it.part; a->n_items = it.n_items;
+  a->fx_row = it.fx_row; a->fx_part0 = it.fx_part0; a->fx_nseg = it.fx_nseg; a->n_fix = it.n_fix;
+  a->n_edges = c.nnz;
+  if (g->merged) {
+    a->idx = (fwd ? g->ucol.p : g->usdst.p) + c.ue0;
+    a->w_edge = (fwd ? g->uw_fwd.p : g->uw_bwd.p) + c.ue0;
+    a->n_edges = c.nu;
+  } else {
+    a->idx = fwd ? g->col.p + c.e0 : g->sdst.p + c.e0;
+    a->ew = fwd ? g->s.p : g->s.p + c.dst0;
+  }
+}
+
+int layer_fwd_update_first(Run& R, const ht_layer_desc* desc, const ht_tensor* H_in, const float* W, ht_tensor* H_out) {
+  ht_ctx* ctx = R.ctx;
+  const ht_graph* g = R.g;
+  hipStream_t st = ctx->stream;
+  const int di = desc->d_in, dn = desc->d_out;
+  HT_TRY(check_tensor(ctx, H_in, g->V, di, "H_in"));
+  HT_TRY(check_tensor(ctx, H_out, g->V, dn, "H_out"));
+  HT_TRY(need_hbm(ctx, H_in, "H_in"));
+  HT_TRY(need_hbm(ctx, H_out, "H_out"));
+  if (!W) return ht_set_err(ctx, HT_EINVAL, "W is null");
+  const int64_t ld_t = ht_row_pitch(dn, true);
+  float* T = nullptr;
+  HT_TRY(ht_scratch(ctx, HT_S_TFULL, (size_t)std::max<int64_t>(g->V, 1) * ld_t * 4, (void**)&T));
+  // t = H_in W for every vertex (row ranges keep the launches within the grid limits)
+  const int64_t step = (int64_t)1 << 22;
+  for (int64_t r0 = 0; r0 < g->V; r0 += step) {
+    const int64_t nr = std::min(step, g->V - r0);
+    R.tm.begin(&R.st->t_gemm_ms);
+    HT_TRY(ht_gemm_nn(ctx, st, H_in->ptr + r0 * H_in->ld, H_in->ld, W, T + r0 * ld_t, ld_t, nr, di, dn, 0));
+    R.tm.end();
+    R.st->n_gemm += 1;
+    R.st->gemm_flops += 2.0 * nr * di * dn;
+  }
+  const int li = R.layer < HT_MAX_LAYERS ? R.layer : HT_MAX_LAYERS - 1;
+  for (int j = 0; j < g->n; ++j) {
+    const ChunkMeta& c = g->chunks[j];
+    if (c.dst1 == c.dst0) continue;
+    float* partial = nullptr;
+    if (c.fwd.n_part > 0) HT_TRY(ht_scratch(ctx, HT_S_SPART, (size_t)g->max_fpart * H_out->ld * 4, (void**)&partial));
+    SpmmArgs a{};
+    agg_args_direct(g, c, true, &a);
+    a.src = T; a.src_ld = ld_t; a.d = dn;
+    a.out = H_out->ptr + c.dst0 * H_out->ld; a.out_ld = H_out->ld; a.out_idx = nullptr;
+    a.post = g->s.p + c.dst0; a.post_idx = nullptr;
+    a.accumulate = 0;
+    a.relu = desc->act == HT_ACT_RELU;
+    a.partial = partial;
+    a.max_slabs = ctx->slabs_fwd;
+    a.tm = &R.tm;
+    a.t_items = &R.st->t_agg_fwd_layer_ms[li];
+    a.t_fix = &R.st->t_agg_fix_ms;
+    HT_TRY(ht_spmm_launch(ctx, st, a));
+    R.st->n_spmm_fwd += 1;
+    R.st->n_agg_fwd_layer[li] += 1;
+    R.st->edges += c.nnz;
+    R.st->spmm_fwd_alg_bytes += spmm_alg_bytes(c, dn);
+    R.st->agg_fwd_layer_alg_bytes[li] += spmm_alg_bytes(c, dn);
+  }
+  return HT_OK;
+}
+
+int layer_bwd_update_first(Run& R, const ht_layer_desc* desc, const ht_tensor* H_in, const float* W,
+                           const ht_tensor* dH_out, const ht_tensor* H_out, ht_tensor* dH_in, float* dW) {
+  ht_ctx* ctx = R.ctx;
+  const ht_graph* g = R.g;
+  hipStream_t st = ctx->stream;
+  const int di = desc->d_in, dn = desc->d_out;
+  const bool relu = desc->act == HT_ACT_RELU;
+  HT_TRY(check_tensor(ctx, H_in, g->V, di, "ckpt"));
+  HT_TRY(check_tensor(ctx, dH_out, g->V, dn, "dH_out"));
+  HT_TRY(need_hbm(ctx, H_in, "ckpt"));
+  HT_TRY(need_hbm(ctx, dH_out, "dH_out"));
+  if (relu && !H_out) return ht_set_err(ctx, HT_EINVAL, "update-first backward with ReLU needs H_out");
+  if (H_out) {
+    HT_TRY(check_tensor(ctx, H_out, g->V, dn, "H_out"));
+    HT_TRY(need_hbm(ctx, H_out, "H_out"));
+  }
+  if (dH_in) {
+    HT_TRY(check_tensor(ctx, dH_in, g->V, di, "dH_in"));
+    HT_TRY(need_hbm(ctx, dH_in, "dH_in"));
+  }
+  if (!W || !dW) return ht_set_err(ctx, HT_EINVAL, "W or dW is null");
+  const int64_t ld_t = ht_row_pitch(dn, true);
+  const int64_t mx = std::max<int64_t>(g->max_ndst, 1);
+  float *dT = nullptr, *dz_chunk = nullptr;
+  HT_TRY(ht_scratch(ctx, HT_S_TFULL, (size_t)std::max<int64_t>(g->V, 1) * ld_t * 4, (void**)&dT));
+  if (relu) HT_TRY(ht_scratch(ctx, HT_S_DZCHUNK, (size_t)mx * ld_t * 4, (void**)&dz_chunk));
+  HT_TRY(ht_fill_zero(ctx, st, dT, (size_t)g->V * ld_t * 4));
+  // dt[N_j] += s_u * sum_v s_v dz[v], chunk by chunk
+  for (int j = 0; j < g->n; ++j) {
+    const ChunkMeta& c = g->chunks[j];
+    const int64_t ndst = c.dst1 - c.dst0;
+    if (ndst == 0) continue;
+    const float* dz_rows = dH_out->ptr + c.dst0 * dH_out->ld;
+    int64_t dz_ld = dH_out->ld;
+    if (relu) {
+      HT_TRY(ht_relu_mask(ctx, st, dz_rows, dz_ld, H_out->ptr + c.dst0 * H_out->ld, H_out->ld, dz_chunk, ld_t, ndst, dn));
+      dz_rows = dz_chunk;
+      dz_ld = ld_t;
+    }
+    float* partial = nullptr;
+    if (c.bwd.n_part > 0) HT_TRY(ht_scratch(ctx, HT_S_SPART, (size_t)g->max_bpart * ld_t * 4, (void**)&partial));
+    SpmmArgs a{};
+    agg_args_direct(g, c, false, &a);
+    a.src = dz_rows; a.src_ld = dz_ld; a.d = dn;
+    a.out = dT; a.out_ld = ld_t;
+    a.out_idx = g->nbr.p + c.nbr_off;
+    a.post = g->s.p; a.post_idx = g->nbr.p + c.nbr_off;
+    a.accumulate = 1;
+    a.partial = partial;
+    a.max_slabs = ctx->slabs_bwd;
+    R.tm.begin(&R.st->t_spmm_bwd_ms);
+    HT_TRY(ht_spmm_launch(ctx, st, a));
+    R.tm.end();
+    R.st->n_spmm_bwd += 1;
+    R.st->edges += c.nnz;
+    R.st->spmm_bwd_alg_bytes += spmm_alg_bytes(c, dn);
+  }
+  // dW = h^T dt, dH_in += dt W^T over row ranges
+  const int64_t step = (int64_t)1 << 22;
+  bool first = true;
+  for (int64_t r0 = 0; r0 < g->V; r0 += step) {
+    const int64_t nr = std::min(step, g->V - r0);
+    R.tm.begin(&R.st->t_gemm_ms);
+    HT_TRY(ht_gemm_tn(ctx, st, H_in->ptr + r0 * H_in->ld, H_in->ld, dT + r0 * ld_t, ld_t, dW, nr, di, dn, first ? 0 : 1));
+    R.tm.end();
+    R.st->n_gemm += 1;
+    R.st->gemm_flops += 2.0 * nr * di * dn;
+    first = false;
+    if (dH_in) {
+      R.tm.begin(&R.st->t_gemm_ms);
+      HT_TRY(ht_gemm_nt(ctx, st, dT + r0 * ld_t, ld_t, W, dH_in->ptr + r0 * dH_in->ld, dH_in->ld, nr, dn, di, 1));
+      R.tm.end();
+      R.st->n_gemm += 1;
+      R.st->gemm_flops += 2.0 * nr * di * dn;
+    }
+  }
+  if (first) HT_TRY(ht_fill_zero(ctx, st, dW, (size_t)di * dn * 4));
+  return HT_OK;
+}
+
 int finish(Run& R, ht_stats* user, const std::chrono::steady_clock::time_point& t0, bool sync) {
   ht_ctx* ctx = R.ctx;
   if (sync || user) {
@@ -789,7 +947,10 @@ int ht_layer_fwd(ht_ctx* ctx, const ht_graph* g, const ht_layer_desc* desc, cons
   auto t0 = std::chrono::steady_clock::now();
   ht_stats local{};
   Run R(ctx, g, &local, stats != nullptr);
-  int rc = layer_fwd_impl(R, desc, H_in, W, H_out, A_ckpt);
+  if (desc->order != HT_ORDER_AGG_FIRST && desc->order != HT_ORDER_UPDATE_FIRST)
+    return ht_set_err(ctx, HT_EINVAL, "unknown stage order %d", desc->order);
+  int rc = desc->order == HT_ORDER_UPDATE_FIRST ? layer_fwd_update_first(R, desc, H_in, W, H_out)
+                                                : layer_fwd_impl(R, desc, H_in, W, H_out, A_ckpt);
   if (rc != HT_OK) {
     (void)hipStreamSynchronize(ctx->stream);
     ctx->ev_next = 0;
@@ -808,7 +969,10 @@ int ht_layer_bwd(ht_ctx* ctx, const ht_graph* g, const ht_layer_desc* desc, cons
   auto t0 = std::chrono::steady_clock::now();
   ht_stats local{};
   Run R(ctx, g, &local, stats != nullptr);
-  int rc = layer_bwd_impl(R, desc, ckpt, W, dH_out, H_out, dH_in, dW);
+  if (desc->order != HT_ORDER_AGG_FIRST && desc->order != HT_ORDER_UPDATE_FIRST)
+    return ht_set_err(ctx, HT_EINVAL, "unknown stage order %d", desc->order);
+  int rc = desc->order == HT_ORDER_UPDATE_FIRST ? layer_bwd_update_first(R, desc, ckpt, W, dH_out, H_out, dH_in, dW)
+                                                : layer_bwd_impl(R, desc, ckpt, W, dH_out, H_out, dH_in, dW);
   if (rc != HT_OK) {
     (void)hipStreamSynchronize(ctx->stream);
     ctx->ev_next = 0;
@@ -849,7 +1013,7 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
   }
   auto bytes_of = [&](int l0, int l1) {
     int64_t b = 0;
-    for (int l = l0; l <= l1; ++l) b += V * (int64_t)((model->dims[l] + 3) & ~3) * 4;
+    for (int l = l0; l <= l1; ++l) b += V * ht_row_pitch(model->dims[l], true) * 4;
     return b;
   };
   int64_t left = budget;
@@ -859,11 +1023,26 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
   if (res_a == HT_RES_AUTO) { if (bytes_of(0, L - 1) <= left) { res_a = HT_RES_HBM; left -= bytes_of(0, L - 1); } else res_a = HT_RES_HOST; }
   if (res_h == HT_RES_AUTO) { if (L > 1 && bytes_of(1, L - 1) <= left) { res_h = HT_RES_HBM; left -= bytes_of(1, L - 1); } else res_h = L > 1 ? HT_RES_HOST : HT_RES_HBM; }
   if (inter == HT_INTER_AUTO) inter = res_h == HT_RES_HBM ? HT_INTER_MASK : HT_INTER_HYBRID;
+  // ---- stage order per layer: update-first only where every tensor of the layer is in HBM
+  const int order = plan ? plan->order : HT_ORDER_AGG_FIRST;
+  if (order != HT_ORDER_AGG_FIRST && order != HT_ORDER_UPDATE_FIRST && order != HT_ORDER_AUTO)
+    return ht_set_err(ctx, HT_EINVAL, "ht_epoch: unknown stage order %d", order);
+  uint32_t upd_mask = 0;
+  if (order != HT_ORDER_AGG_FIRST && L <= 32 && gather_mode != HT_GATHER_BUFFER) {
+    for (int l = 0; l < L; ++l) {
+      const bool in_hbm = l == 0 ? X->loc == HT_LOC_DEVICE : res_h == HT_RES_HBM;
+      const bool out_hbm = l == L - 1 || res_h == HT_RES_HBM;
+      const bool gout_hbm = l == L - 1 || res_g == HT_RES_HBM;
+      const bool gin_hbm = l == 0 || res_g == HT_RES_HBM;
+      const bool narrower = model->dims[l + 1] < model->dims[l];
+      if (in_hbm && out_hbm && gout_hbm && gin_hbm && (order == HT_ORDER_UPDATE_FIRST || narrower)) upd_mask |= 1u << l;
+    }
+  }
 
   // ---- workspace
   EpochWs* ws = ctx->ws;
   bool reuse = ws && ws->V == V && (int)ws->dims.size() == L + 1 && ws->res_h == res_h && ws->res_a == res_a &&
-               ws->res_g == res_g;
+               ws->res_g == res_g && ws->upd_mask == upd_mask;
   if (reuse)
     for (int l = 0; l <= L; ++l) reuse = reuse && ws->dims[l] == model->dims[l];
   if (!reuse) {
@@ -874,13 +1053,15 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
     ws->V = V;
     ws->dims.assign(model->dims, model->dims + L + 1);
     ws->res_h = res_h; ws->res_a = res_a; ws->res_g = res_g;
+    ws->upd_mask = upd_mask;
     ws->h.assign(L + 1, ht_tensor{});
     ws->a.assign(L, ht_tensor{});
     ws->gh.assign(L + 1, ht_tensor{});
     ws->dW.assign(L, nullptr);
     int rc = HT_OK;
     for (int l = 1; l <= L && rc == HT_OK; ++l) rc = ws_tensor(ctx, ws, V, model->dims[l], l == L ? HT_RES_HBM : res_h, &ws->h[l]);
-    for (int l = 0; l < L && rc == HT_OK; ++l) rc = ws_tensor(ctx, ws, V, model->dims[l], res_a, &ws->a[l]);
+    for (int l = 0; l < L && rc == HT_OK; ++l)
+      if (!((upd_mask >> l) & 1)) rc = ws_tensor(ctx, ws, V, model->dims[l], res_a, &ws->a[l]);
     for (int l = 1; l <= L && rc == HT_OK; ++l) rc = ws_tensor(ctx, ws, V, model->dims[l], l == L ? HT_RES_HBM : res_g, &ws->gh[l]);
     for (int l = 0; l < L && rc == HT_OK; ++l) {
       void* p = nullptr;
@@ -913,7 +1094,10 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
     d.act = l < L - 1 ? HT_ACT_RELU : HT_ACT_NONE;
     d.gather_mode = gather_mode;
     R.layer = l;
-    int rc = layer_fwd_impl(R, &d, l == 0 ? X : &ws->h[l], model->W[l], &ws->h[l + 1], &ws->a[l]);
+    const bool upd = (upd_mask >> l) & 1;
+    d.order = upd ? HT_ORDER_UPDATE_FIRST : HT_ORDER_AGG_FIRST;
+    int rc = upd ? layer_fwd_update_first(R, &d, l == 0 ? X : &ws->h[l], model->W[l], &ws->h[l + 1])
+                 : layer_fwd_impl(R, &d, l == 0 ? X : &ws->h[l], model->W[l], &ws->h[l + 1], &ws->a[l]);
     if (rc != HT_OK) return fail(rc);
   }
   // ---- downstream task and its gradient (Alg. 1 lines 10-11)
@@ -944,8 +1128,12 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
     }
     R.layer = l;
     const ht_tensor* mask_from = (inter == HT_INTER_MASK && l < L - 1) ? &ws->h[l + 1] : nullptr;
-    int rc = layer_bwd_impl(R, &d, &ws->a[l], model->W[l], &ws->gh[l + 1], mask_from, l > 0 ? &ws->gh[l] : nullptr,
-                            ws->dW[l]);
+    const bool upd = (upd_mask >> l) & 1;
+    d.order = upd ? HT_ORDER_UPDATE_FIRST : HT_ORDER_AGG_FIRST;
+    int rc = upd ? layer_bwd_update_first(R, &d, l == 0 ? X : &ws->h[l], model->W[l], &ws->gh[l + 1],
+                                          l < L - 1 ? &ws->h[l + 1] : nullptr, l > 0 ? &ws->gh[l] : nullptr, ws->dW[l])
+                 : layer_bwd_impl(R, &d, &ws->a[l], model->W[l], &ws->gh[l + 1], mask_from,
+                                  l > 0 ? &ws->gh[l] : nullptr, ws->dW[l]);
     if (rc != HT_OK) return fail(rc);
   }
   // ---- parameter update (Alg. 1 lines 20-21)
@@ -974,6 +1162,7 @@ int ht_epoch_buffer(ht_ctx* ctx, int32_t kind, int32_t layer, ht_tensor* out) {
       return HT_OK;
     case HT_BUF_A:
       if (layer < 0 || layer >= L) return ht_set_err(ctx, HT_EINVAL, "layer out of range");
+      if (!ws->a[layer].ptr) return ht_set_err(ctx, HT_ESTATE, "layer %d ran update-first: no aggregate checkpoint", layer);
       *out = ws->a[layer];
       return HT_OK;
     case HT_BUF_GH:

@@ -35,6 +35,7 @@ __device__ __forceinline__ void write_out(const SpmmArgs& a, int32_t r, int c4, 
   float* p = a.out + (int64_t)orow * a.out_ld + c4;
   v = mul4(post, v);
   if (a.accumulate && !fresh) v = add4(ld4(p), v);
+  if (a.relu) v = make_float4(v.x > 0.f ? v.x : 0.f, v.y > 0.f ? v.y : 0.f, v.z > 0.f ? v.z : 0.f, v.w > 0.f ? v.w : 0.f);
   st4(p, v);
 }
 

@@ -18,7 +18,9 @@ def ctx():
     B.ht_ctx_destroy(c)
 
 
-def run_epoch(ctx, w, src, dst, X, y, Ws, n_chunks=None, x_loc=B.HT_LOC_DEVICE, cache_rows=0, reorder=False, **plan):
+def run_epoch(ctx, w, src, dst, X, y, Ws, n_chunks=None, x_loc=B.HT_LOC_DEVICE, cache_rows=0, reorder=False,
+              update_first=(), **plan):
+    """update_first: the layers expected to run update-first (they keep no aggregate checkpoint)."""
     g = B.ht_partition(ctx, w.V, src.cuda(), dst.cuda(), n_chunks or w.n_chunks, cache_rows=cache_rows,
                        reorder_chunks=reorder)
     try:
@@ -27,7 +29,8 @@ def run_epoch(ctx, w, src, dst, X, y, Ws, n_chunks=None, x_loc=B.HT_LOC_DEVICE, 
         loss, st = B.ht_epoch(ctx, g, w.dims, Wd, w.lr, Xd, y.cuda(), want_stats=True, **plan)
         L = w.n_layers
         out = {"loss": loss, "stats": st, "W_new": [x.cpu().numpy() for x in Wd],
-               "a": [B.ht_epoch_buffer(ctx, B.HT_BUF_A, l).numpy() for l in range(L)],
+               "a": [B.ht_epoch_buffer(ctx, B.HT_BUF_A, l).numpy() if l not in update_first else None
+                     for l in range(L)],
                "h": [B.ht_epoch_buffer(ctx, B.HT_BUF_H, l + 1).numpy() for l in range(L)],
                "gh": [B.ht_epoch_buffer(ctx, B.HT_BUF_GH, l + 1).numpy() for l in range(L)],
                "gW": [B.ht_epoch_buffer(ctx, B.HT_BUF_DW, l).numpy() for l in range(L)]}
@@ -44,7 +47,8 @@ def oracle_epoch(w, src, dst, X, y, Ws):
 def compare(out, ref, L):
     assert abs(out["loss"] - ref["loss"]) <= 1e-4 * abs(ref["loss"]), (out["loss"], ref["loss"])
     for l in range(L):
-        assert_close(out["a"][l], ref["a"][l], f"a^{l}")
+        if out["a"][l] is not None:
+            assert_close(out["a"][l], ref["a"][l], f"a^{l}")
         assert_close(out["h"][l], ref["h"][l], f"h^{l + 1}")
         assert_close(out["gh"][l], ref["gh"][l], f"grad h^{l + 1}")
         assert_close(out["gW"][l], ref["gW"][l], f"grad W^{l}")
@@ -116,6 +120,32 @@ def test_cfg1_buffer_mode_in_hbm_and_chunk_count_invariance(ctx, cfg1):
     compare(run_epoch(ctx, w, src, dst, X, y, Ws, n_chunks=9, reorder=True), ref, w.n_layers)
     compare(run_epoch(ctx, w, src, dst, X, y, Ws, n_chunks=9, reorder=True, x_loc=B.HT_LOC_HOST_PINNED,
                       res_h=B.HT_RES_HOST, res_a=B.HT_RES_HOST, res_g=B.HT_RES_HOST), ref, w.n_layers)
+
+
+def test_cfg1_update_first_order(ctx, cfg1):
+    # H' = act(A_hat (H W)): the same function as Eq. 2 with the two linear stages swapped
+    w, src, dst, X, y, Ws, ref = cfg1
+    L = w.n_layers
+    out = run_epoch(ctx, w, src, dst, X, y, Ws, order=B.HT_ORDER_UPDATE_FIRST, update_first=range(L))
+    compare(out, ref, L)
+    assert out["stats"].edges == (w.E + w.V) * 2 * L            # one aggregation per layer and direction
+    # AUTO: only layers that get narrower (64 -> 32 -> 8: both)
+    compare(run_epoch(ctx, w, src, dst, X, y, Ws, order=B.HT_ORDER_AUTO, update_first=range(L), n_chunks=7), ref, L)
+    # host-resident tensors keep the printed order whatever is asked for
+    out = run_epoch(ctx, w, src, dst, X, y, Ws, order=B.HT_ORDER_AUTO, x_loc=B.HT_LOC_HOST_PINNED,
+                    res_h=B.HT_RES_HOST, res_a=B.HT_RES_HOST, res_g=B.HT_RES_HOST)
+    compare(out, ref, L)
+    with pytest.raises(B.HongtuError):
+        run_epoch(ctx, w, src, dst, X, y, Ws, order=7)
+
+
+def test_update_first_only_where_narrower(ctx):
+    w = inputs.Workload("t3w", 6000, 70_000, [24, 40, 20, 12], 5, labelled_one_in=3, graph_seed=6)
+    src, dst, X, y, Ws = inputs.make_inputs(w)
+    ref = oracle_epoch(w, src, dst, X, y, Ws)
+    for l in range(w.n_layers - 1):
+        assert np.abs(ref["z"][l]).min() > 1e-7 * np.abs(ref["z"][l]).max()
+    compare(run_epoch(ctx, w, src, dst, X, y, Ws, order=B.HT_ORDER_AUTO, update_first=(1, 2)), ref, 3)
 
 
 def test_three_layers_partial_labels(ctx):

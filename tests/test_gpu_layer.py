@@ -89,6 +89,32 @@ def test_fwd_residency_and_gather_modes(ctx, hub_case, loc_in, loc_out, loc_a, g
     _fwd(ctx, hub_case, 72, 41, B.HT_ACT_NONE, loc_in, loc_out, loc_a, gather, seed=5)
 
 
+@pytest.mark.parametrize("d_in,d_out,act", [(64, 32, B.HT_ACT_RELU), (602, 256, B.HT_ACT_RELU), (256, 41, B.HT_ACT_NONE),
+                                            (20, 130, B.HT_ACT_RELU)])
+def test_fwd_update_first(ctx, rmat_case, hub_case, d_in, d_out, act):
+    # t = H W first, then the aggregation at width d_out with the activation fused into its last write
+    for case in (rmat_case, hub_case):
+        rng = np.random.default_rng(d_in + d_out)
+        H = rng.standard_normal((case.V, d_in)).astype(np.float32)
+        W = (rng.standard_normal((d_in, d_out)) / np.sqrt(d_in)).astype(np.float32)
+        H_out = B.alloc_matrix(case.V, d_out, DEV, zero=False)
+        B.ht_layer_fwd(ctx, case.g, d_in, d_out, act, _mat(H, DEV), torch.from_numpy(W).cuda(), H_out,
+                       order=B.HT_ORDER_UPDATE_FIRST)
+        B.ht_sync(ctx)
+        z_ref = orc.matmul(orc.aggregate(case.indptr, case.col, H), W)
+        assert_close(H_out.cpu().numpy()[:, :d_out], np.maximum(z_ref, 0.0) if act == B.HT_ACT_RELU else z_ref, "h_out")
+
+
+def test_update_first_needs_hbm(ctx, rmat_case):
+    c = rmat_case
+    H = B.alloc_matrix(c.V, 16, HOST)
+    W = torch.zeros(16, 8, device="cuda")
+    with pytest.raises(B.HongtuError):
+        B.ht_layer_fwd(ctx, c.g, 16, 8, B.HT_ACT_NONE, H, W, B.alloc_matrix(c.V, 8, DEV), order=B.HT_ORDER_UPDATE_FIRST)
+    with pytest.raises(B.HongtuError):
+        B.ht_layer_fwd(ctx, c.g, 16, 8, B.HT_ACT_NONE, B.alloc_matrix(c.V, 16, DEV), W, B.alloc_matrix(c.V, 8, DEV), order=5)
+
+
 def test_fwd_hub_rows_wide(ctx, hub_case):
     _fwd(ctx, hub_case, 256, 256, B.HT_ACT_RELU, DEV, DEV, DEV, B.HT_GATHER_DIRECT, seed=6)
     _fwd(ctx, hub_case, 602, 64, B.HT_ACT_RELU, DEV, DEV, DEV, B.HT_GATHER_BUFFER, seed=7)
@@ -150,7 +176,7 @@ def _bwd_inputs(case, d_in, d_out, ckpt_input, structured, seed):
 
 
 def _bwd(ctx, case, d_in, d_out, relu, loc, gather, mask_from_h, ckpt_input=False, want_dhin=True, seed=0,
-         structured=True):
+         structured=True, order=B.HT_ORDER_AGG_FIRST):
     ck_np, W, dh = _bwd_inputs(case, d_in, d_out, ckpt_input, structured and relu, seed)
     a = orc.aggregate(case.indptr, case.col, ck_np) if ckpt_input else ck_np
     ck = _mat(ck_np, loc)
@@ -165,7 +191,7 @@ def _bwd(ctx, case, d_in, d_out, relu, loc, gather, mask_from_h, ckpt_input=Fals
     dH_in = B.alloc_matrix(case.V, d_in, loc) if want_dhin else None
     B.ht_layer_bwd(ctx, case.g, d_in, d_out, B.HT_ACT_RELU if relu else B.HT_ACT_NONE, ck, Wd, dH_out, dW,
                    dH_in=dH_in, H_out=H_out, ckpt_kind=B.HT_CKPT_INPUT if ckpt_input else B.HT_CKPT_AGG,
-                   gather_mode=gather)
+                   gather_mode=gather, order=order)
     B.ht_sync(ctx)
     assert_close(dW.cpu().numpy(), dW_ref, "dW")
     if want_dhin:
@@ -192,6 +218,15 @@ def test_bwd_gaussian_inputs(ctx, rmat_case, d_in, d_out, seed):
 ])
 def test_bwd_residency_modes(ctx, hub_case, loc, gather, mask_from_h, ckpt_input):
     _bwd(ctx, hub_case, 72, 40, True, loc, gather, mask_from_h, ckpt_input, seed=21)
+
+
+@pytest.mark.parametrize("d_in,d_out,relu,want_dhin", [(64, 32, True, True), (256, 41, False, True), (602, 256, True, False),
+                                                       (72, 130, True, True)])
+def test_bwd_update_first(ctx, rmat_case, hub_case, d_in, d_out, relu, want_dhin):
+    # the checkpoint is the layer input h^l; dt = A_hat^T dz at width d_out, dW = h^T dt, dH_in = dt W^T
+    for case in (rmat_case, hub_case):
+        _bwd(ctx, case, d_in, d_out, relu, DEV, B.HT_GATHER_AUTO, mask_from_h=True, ckpt_input=True,
+             want_dhin=want_dhin, seed=40 + d_in, order=B.HT_ORDER_UPDATE_FIRST)
 
 
 def test_bwd_no_activation_no_input_gradient(ctx, rmat_case):
