@@ -261,8 +261,10 @@ int ht_layer_bwd(ht_ctx *ctx, const ht_graph *g, const ht_layer_desc *desc, cons
 enum { HT_RES_AUTO = 0, HT_RES_HBM = 1, HT_RES_HOST = 2 };
 /* HT_INTER_AUTO picks per the byte budget; MASK keeps h^{l+1} in HBM and reads
  * ReLU' from it; HYBRID caches a^l and recomputes z = a W in the backward pass
- * (Sec. 4.2, Fig. 5(c)). */
-enum { HT_INTER_AUTO = 0, HT_INTER_MASK = 1, HT_INTER_HYBRID = 2 };
+ * (Sec. 4.2, Fig. 5(c)); RECOMPUTE keeps no a^l at all: the backward pass
+ * gathers and aggregates again from h^l (Fig. 5(b)), then recomputes z unless
+ * h^{l+1} is in HBM to read ReLU' from.  AUTO never picks RECOMPUTE. */
+enum { HT_INTER_AUTO = 0, HT_INTER_MASK = 1, HT_INTER_HYBRID = 2, HT_INTER_RECOMPUTE = 3 };
 
 typedef struct {
   int32_t n_layers;

@@ -26,7 +26,7 @@ HT_GATHER_AUTO, HT_GATHER_DIRECT, HT_GATHER_BUFFER = 0, 1, 2
 HT_CKPT_AGG, HT_CKPT_INPUT = 0, 1
 HT_ORDER_AGG_FIRST, HT_ORDER_UPDATE_FIRST, HT_ORDER_AUTO = 0, 1, 2
 HT_RES_AUTO, HT_RES_HBM, HT_RES_HOST = 0, 1, 2
-HT_INTER_AUTO, HT_INTER_MASK, HT_INTER_HYBRID = 0, 1, 2
+HT_INTER_AUTO, HT_INTER_MASK, HT_INTER_HYBRID, HT_INTER_RECOMPUTE = 0, 1, 2, 3
 HT_BUF_H, HT_BUF_A, HT_BUF_GH, HT_BUF_DW = 0, 1, 2, 3
 HT_MAX_LAYERS = 8
 

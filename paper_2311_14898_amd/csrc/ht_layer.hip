@@ -22,6 +22,7 @@ struct EpochWs {
   int64_t V = 0;
   std::vector<int32_t> dims;
   int res_h = 0, res_a = 0, res_g = 0;
+  bool no_ckpt = false;              // pure recomputation: no a^l for any layer
   uint32_t upd_mask = 0;             // bit l: layer l runs update-first (no a^l is kept for it)
   std::vector<ht_tensor> h, a, gh;  // h[l] = h^l (l >= 1; h[0] unused), a[l], gh[l] = grad h^l (l >= 1)
   std::vector<float*> dW;
@@ -1020,9 +1021,13 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
   // the output layer's logits and their gradient stay in HBM (the loss runs on them in place)
   left -= 2 * bytes_of(L, L);
   if (res_g == HT_RES_AUTO) { if (L > 1 && bytes_of(1, L - 1) <= left) { res_g = HT_RES_HBM; left -= bytes_of(1, L - 1); } else res_g = L > 1 ? HT_RES_HOST : HT_RES_HBM; }
-  if (res_a == HT_RES_AUTO) { if (bytes_of(0, L - 1) <= left) { res_a = HT_RES_HBM; left -= bytes_of(0, L - 1); } else res_a = HT_RES_HOST; }
+  if (inter == HT_INTER_RECOMPUTE) res_a = HT_RES_HBM;   // no checkpoint tensors exist: nothing to place
+  else if (res_a == HT_RES_AUTO) { if (bytes_of(0, L - 1) <= left) { res_a = HT_RES_HBM; left -= bytes_of(0, L - 1); } else res_a = HT_RES_HOST; }
   if (res_h == HT_RES_AUTO) { if (L > 1 && bytes_of(1, L - 1) <= left) { res_h = HT_RES_HBM; left -= bytes_of(1, L - 1); } else res_h = L > 1 ? HT_RES_HOST : HT_RES_HBM; }
   if (inter == HT_INTER_AUTO) inter = res_h == HT_RES_HBM ? HT_INTER_MASK : HT_INTER_HYBRID;
+  if (inter != HT_INTER_MASK && inter != HT_INTER_HYBRID && inter != HT_INTER_RECOMPUTE)
+    return ht_set_err(ctx, HT_EINVAL, "ht_epoch: unknown intermediate-data mode %d", inter);
+  const bool recompute = inter == HT_INTER_RECOMPUTE;
   // ---- stage order per layer: update-first only where every tensor of the layer is in HBM
   const int order = plan ? plan->order : HT_ORDER_AGG_FIRST;
   if (order != HT_ORDER_AGG_FIRST && order != HT_ORDER_UPDATE_FIRST && order != HT_ORDER_AUTO)
@@ -1042,7 +1047,7 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
   // ---- workspace
   EpochWs* ws = ctx->ws;
   bool reuse = ws && ws->V == V && (int)ws->dims.size() == L + 1 && ws->res_h == res_h && ws->res_a == res_a &&
-               ws->res_g == res_g && ws->upd_mask == upd_mask;
+               ws->res_g == res_g && ws->upd_mask == upd_mask && ws->no_ckpt == recompute;
   if (reuse)
     for (int l = 0; l <= L; ++l) reuse = reuse && ws->dims[l] == model->dims[l];
   if (!reuse) {
@@ -1054,6 +1059,7 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
     ws->dims.assign(model->dims, model->dims + L + 1);
     ws->res_h = res_h; ws->res_a = res_a; ws->res_g = res_g;
     ws->upd_mask = upd_mask;
+    ws->no_ckpt = recompute;
     ws->h.assign(L + 1, ht_tensor{});
     ws->a.assign(L, ht_tensor{});
     ws->gh.assign(L + 1, ht_tensor{});
@@ -1061,7 +1067,7 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
     int rc = HT_OK;
     for (int l = 1; l <= L && rc == HT_OK; ++l) rc = ws_tensor(ctx, ws, V, model->dims[l], l == L ? HT_RES_HBM : res_h, &ws->h[l]);
     for (int l = 0; l < L && rc == HT_OK; ++l)
-      if (!((upd_mask >> l) & 1)) rc = ws_tensor(ctx, ws, V, model->dims[l], res_a, &ws->a[l]);
+      if (!((upd_mask >> l) & 1) && !recompute) rc = ws_tensor(ctx, ws, V, model->dims[l], res_a, &ws->a[l]);
     for (int l = 1; l <= L && rc == HT_OK; ++l) rc = ws_tensor(ctx, ws, V, model->dims[l], l == L ? HT_RES_HBM : res_g, &ws->gh[l]);
     for (int l = 0; l < L && rc == HT_OK; ++l) {
       void* p = nullptr;
@@ -1097,7 +1103,8 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
     const bool upd = (upd_mask >> l) & 1;
     d.order = upd ? HT_ORDER_UPDATE_FIRST : HT_ORDER_AGG_FIRST;
     int rc = upd ? layer_fwd_update_first(R, &d, l == 0 ? X : &ws->h[l], model->W[l], &ws->h[l + 1])
-                 : layer_fwd_impl(R, &d, l == 0 ? X : &ws->h[l], model->W[l], &ws->h[l + 1], &ws->a[l]);
+                 : layer_fwd_impl(R, &d, l == 0 ? X : &ws->h[l], model->W[l], &ws->h[l + 1],
+                                  recompute ? nullptr : &ws->a[l]);
     if (rc != HT_OK) return fail(rc);
   }
   // ---- downstream task and its gradient (Alg. 1 lines 10-11)
@@ -1114,7 +1121,7 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
     d.d_in = model->dims[l]; d.d_out = model->dims[l + 1];
     d.act = l < L - 1 ? HT_ACT_RELU : HT_ACT_NONE;
     d.gather_mode = gather_mode;
-    d.ckpt_kind = HT_CKPT_AGG;
+    d.ckpt_kind = recompute ? HT_CKPT_INPUT : HT_CKPT_AGG;
     R.dhin_is_zero = false;
     if (l > 0) {
       // a never-evicting gradient buffer stores every row of a host-resident grad h^l exactly once
@@ -1127,12 +1134,14 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
       R.dhin_is_zero = true;
     }
     R.layer = l;
-    const ht_tensor* mask_from = (inter == HT_INTER_MASK && l < L - 1) ? &ws->h[l + 1] : nullptr;
+    const bool mask_ok = inter == HT_INTER_MASK || (recompute && ws->h[l + 1].loc == HT_LOC_DEVICE);
+    const ht_tensor* mask_from = (mask_ok && l < L - 1) ? &ws->h[l + 1] : nullptr;
+    const ht_tensor* ckpt = recompute ? (l == 0 ? X : &ws->h[l]) : &ws->a[l];
     const bool upd = (upd_mask >> l) & 1;
     d.order = upd ? HT_ORDER_UPDATE_FIRST : HT_ORDER_AGG_FIRST;
     int rc = upd ? layer_bwd_update_first(R, &d, l == 0 ? X : &ws->h[l], model->W[l], &ws->gh[l + 1],
                                           l < L - 1 ? &ws->h[l + 1] : nullptr, l > 0 ? &ws->gh[l] : nullptr, ws->dW[l])
-                 : layer_bwd_impl(R, &d, &ws->a[l], model->W[l], &ws->gh[l + 1], mask_from,
+                 : layer_bwd_impl(R, &d, ckpt, model->W[l], &ws->gh[l + 1], mask_from,
                                   l > 0 ? &ws->gh[l] : nullptr, ws->dW[l]);
     if (rc != HT_OK) return fail(rc);
   }
@@ -1162,7 +1171,7 @@ int ht_epoch_buffer(ht_ctx* ctx, int32_t kind, int32_t layer, ht_tensor* out) {
       return HT_OK;
     case HT_BUF_A:
       if (layer < 0 || layer >= L) return ht_set_err(ctx, HT_EINVAL, "layer out of range");
-      if (!ws->a[layer].ptr) return ht_set_err(ctx, HT_ESTATE, "layer %d ran update-first: no aggregate checkpoint", layer);
+      if (!ws->a[layer].ptr) return ht_set_err(ctx, HT_ESTATE, "layer %d keeps no aggregate checkpoint", layer);
       *out = ws->a[layer];
       return HT_OK;
     case HT_BUF_GH:

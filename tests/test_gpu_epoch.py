@@ -122,6 +122,23 @@ def test_cfg1_buffer_mode_in_hbm_and_chunk_count_invariance(ctx, cfg1):
                       res_h=B.HT_RES_HOST, res_a=B.HT_RES_HOST, res_g=B.HT_RES_HOST), ref, w.n_layers)
 
 
+def test_cfg1_pure_recomputation(ctx, cfg1):
+    # Fig. 5(b): no aggregate checkpoints; the backward pass gathers and aggregates again from h^l
+    w, src, dst, X, y, Ws, ref = cfg1
+    L = w.n_layers
+    out = run_epoch(ctx, w, src, dst, X, y, Ws, inter=B.HT_INTER_RECOMPUTE, update_first=range(L))
+    compare(out, ref, L)
+    assert out["stats"].edges == (w.E + w.V) * (3 * L - 1)       # L forward, L recomputed, L-1 backward
+    out = run_epoch(ctx, w, src, dst, X, y, Ws, inter=B.HT_INTER_RECOMPUTE, update_first=range(L),
+                    x_loc=B.HT_LOC_HOST_PINNED, res_h=B.HT_RES_HOST, res_g=B.HT_RES_HOST)
+    compare(out, ref, L)
+    # the regenerated intermediates are the ones the hybrid caches: same bits
+    a = run_epoch(ctx, w, src, dst, X, y, Ws, inter=B.HT_INTER_HYBRID)
+    b = run_epoch(ctx, w, src, dst, X, y, Ws, inter=B.HT_INTER_RECOMPUTE, update_first=range(L))
+    for l in range(L):
+        assert np.array_equal(a["gW"][l], b["gW"][l]) and np.array_equal(a["gh"][l], b["gh"][l])
+
+
 def test_cfg1_update_first_order(ctx, cfg1):
     # H' = act(A_hat (H W)): the same function as Eq. 2 with the two linear stages swapped
     w, src, dst, X, y, Ws, ref = cfg1
