@@ -148,7 +148,8 @@ __global__ void __launch_bounds__(256) k_spmm_fix(SpmmArgs a) {
 // are (edge slot, float4 of the slab); `eps` edges are read per step.
 template <int U, bool UNI>
 __global__ void __launch_bounds__(256) k_spmm_slab(SpmmArgs a, int S, int nvs, int eps, int64_t grp_per_part, int slab0) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // the wave index is the same in all 64 lanes: saying so keeps the item's fields and the loop control in scalar registers
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int xcd = blockIdx.x & 7;
   const int slab = slab0 + xcd % S;
   // The 8/S XCDs that share a slab split the (source-ordered) item list into contiguous parts

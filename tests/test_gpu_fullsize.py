@@ -171,3 +171,45 @@ def test_stats_and_traffic_counters(run):
     assert st.edges == Ep * (2 * w.n_layers - 1)
     assert st.n_spmm_fwd == w.n_chunks * w.n_layers and st.n_spmm_bwd == w.n_chunks * (w.n_layers - 1)
     assert st.bytes_h2d == 0 and st.bytes_d2h == 0
+
+
+def test_update_first_order_full_size(run):
+    """The same epoch with the planner free to transform first (both layers of this model get
+    narrower): sampled forward rows, loss, and every gradient, each step recomputed by the oracle in
+    the printed order (aggregate, then transform) from the step's actual inputs.  ReLU decisions
+    are read from the device's own h^{l+1}, as the update-first backward pass does."""
+    w, ctx, g = run["w"], run["ctx"], run["g"]
+    V, dims, L = w.V, w.dims, w.n_layers
+    src, dst = run["src"], run["dst"]
+    Wd = [torch.from_numpy(x).clone().cuda() for x in run["Ws"]]
+    loss, st = B.ht_epoch(ctx, g, dims, Wd, w.lr, B.to_matrix(torch.from_numpy(run["X"])), torch.from_numpy(run["y"]).cuda(),
+                          want_stats=True, order=B.HT_ORDER_AUTO)
+    assert st.edges == (w.E + w.V) * 2 * L and st.n_spmm_bwd == w.n_chunks * L
+    h_dev = [run["X"]] + [B.ht_epoch_buffer(ctx, B.HT_BUF_H, l + 1).numpy() for l in range(L)]
+    gh_dev = [None] + [B.ht_epoch_buffer(ctx, B.HT_BUF_GH, l + 1).numpy() for l in range(L)]
+    gW_dev = [B.ht_epoch_buffer(ctx, B.HT_BUF_DW, l).numpy() for l in range(L)]
+    with pytest.raises(B.HongtuError):
+        B.ht_epoch_buffer(ctx, B.HT_BUF_A, 0)          # no aggregate checkpoint in this order
+    rng = np.random.default_rng(2)
+    deg = np.bincount(dst, minlength=V)
+    hubs = np.argsort(deg)[-4:]
+    rows = np.unique(np.concatenate([rng.integers(0, V, N_SAMPLE), hubs, [0, V - 1]]))
+    indptr, col = orc.csc_build(V, src, dst, add_self_loops=True)
+    s = orc.norm(indptr)
+    keep = np.isin(dst, rows)
+    indptr_s, col_s = orc.csc_build(V, src[keep], dst[keep], add_self_loops=True)
+    for l in range(L):
+        z_ref = orc.matmul(orc.aggregate(indptr_s, col_s, h_dev[l], s=s)[rows], run["Ws"][l])
+        assert_close(h_dev[l + 1][rows], np.maximum(z_ref, 0.0) if l < L - 1 else z_ref, f"h^{l + 1} rows")
+    loss_ref, g_ref = orc.softmax_ce(h_dev[L], run["y"])
+    assert abs(loss - loss_ref) <= 1e-4 * abs(loss_ref)
+    assert_close(gh_dev[L][rows], g_ref[rows], "grad h^L rows")
+    for l in range(L - 1, -1, -1):
+        gh = gh_dev[l + 1].astype(np.float64)
+        dz = np.where(h_dev[l + 1] > 0.0, gh, 0.0) if l < L - 1 else gh
+        dt = orc.aggregate_T(indptr, col, dz)                                   # width d_out
+        assert_close(gW_dev[l], orc.matmul_tn(h_dev[l], dt), f"grad W^{l}")
+        assert_close(Wd[l].cpu().numpy(), run["Ws"][l].astype(np.float64) - w.lr * gW_dev[l].astype(np.float64), f"W^{l} step")
+        if l > 0:
+            ref = orc.matmul_nt(dt[rows], run["Ws"][l])
+            assert (np.abs(gh_dev[l][rows] - ref) <= 1e-4 * np.abs(gh_dev[l]).max()).all(), f"grad h^{l} rows"
