@@ -103,6 +103,7 @@ def main():
     ap.add_argument("--order", choices=["paper", "auto"], default="paper",
                     help="stage order of a layer: aggregate then transform as Eq. 2 prints it (the timed default), or "
                          "transform first in the layers that get narrower (same function, fewer bytes aggregated)")
+    ap.add_argument("--no-other-order", action="store_true", help="do not time the second stage order as well")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a 1 GiB device copy kernel (known traffic) to scale rocprofv3 byte counters")
     args = ap.parse_args()
@@ -179,7 +180,7 @@ def main():
     elapsed, tot, loss = timed_epochs(main_order)
     agg = {"t": tot["t_agg_fwd_layer_ms"][0], "n": tot["n_agg_fwd_layer"][0], "bytes": tot["agg_fwd_layer_alg_bytes"][0]}
     other = None
-    if not host and args.scale == 1.0:
+    if not host and args.scale == 1.0 and not args.no_other_order:
         # the other stage order on the same graph and weights (which keep training: the loss differs)
         o_el, o_tot, _ = timed_epochs(B.HT_ORDER_AGG_FIRST if args.order == "auto" else B.HT_ORDER_AUTO)
         other = {"order": "paper" if args.order == "auto" else "auto", "ms_per_step": 1e3 * o_el / args.steps,
