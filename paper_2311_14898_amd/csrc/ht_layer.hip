@@ -1196,8 +1196,36 @@ int ht_tensor_to_host(ht_ctx* ctx, const ht_tensor* t, float* dst) {
   if (!t->ptr || t->rows < 0 || t->cols <= 0 || t->ld < t->cols) return ht_set_err(ctx, HT_ESHAPE, "bad tensor");
   HT_HIP(ctx, hipStreamSynchronize(ctx->stream));
   if (t->rows == 0) return HT_OK;
-  HT_HIP(ctx, hipMemcpy2D(dst, (size_t)t->cols * 4, t->ptr, (size_t)t->ld * 4, (size_t)t->cols * 4, (size_t)t->rows,
-                          t->loc == HT_LOC_DEVICE ? hipMemcpyDeviceToHost : hipMemcpyHostToHost));
+  // rows [r0, r1) of `from` (pitch ld) into the dense destination, on the host cores
+  auto pack = [&](const float* from, int64_t r0, int64_t r1) {
+    const int nt = (int)std::min<int64_t>(host_threads(ctx), std::max<int64_t>(1, (r1 - r0) / 4096));
+    auto work = [&](int64_t a, int64_t b) {
+      for (int64_t r = a; r < b; ++r)
+        std::memcpy(dst + r * t->cols, from + (r - r0) * t->ld, (size_t)t->cols * 4);
+    };
+    if (nt <= 1) return work(r0, r1);
+    std::vector<std::thread> th;
+    const int64_t per = (r1 - r0 + nt - 1) / nt;
+    for (int k = 0; k < nt; ++k) {
+      const int64_t a = r0 + k * per, b = std::min(r1, a + per);
+      if (a < b) th.emplace_back(work, a, b);
+    }
+    for (auto& x : th) x.join();
+  };
+  if (t->loc != HT_LOC_DEVICE) {
+    pack(t->ptr, 0, t->rows);
+    return HT_OK;
+  }
+  // HBM: whole padded rows through a page-locked bounce buffer (a pitched copy into pageable
+  // memory runs at a fraction of the link rate), then packed on the host
+  const int64_t rows_per = std::max<int64_t>(1, ((int64_t)64 << 20) / (t->ld * 4));
+  float* bounce = nullptr;
+  HT_TRY(ht_host_scratch(ctx, 1, (size_t)rows_per * t->ld * 4, (void**)&bounce));
+  for (int64_t r0 = 0; r0 < t->rows; r0 += rows_per) {
+    const int64_t r1 = std::min(t->rows, r0 + rows_per);
+    HT_HIP(ctx, hipMemcpy(bounce, t->ptr + r0 * t->ld, (size_t)(r1 - r0) * t->ld * 4, hipMemcpyDeviceToHost));
+    pack(bounce, r0, r1);
+  }
   return HT_OK;
 }
 
