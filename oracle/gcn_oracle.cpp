@@ -17,6 +17,8 @@
 //   * Dedup sets and volumes, Sec. 5.1 / 5.3: reuse set N_j ^ N_{j-1}, load set
 //     N_j \ N_{j-1}, V_ori and V_+ru (one GPU, so the inter-GPU term is void).
 //   * Epoch, Alg. 1: forward over layers, loss, backward, parameter update.
+//   * GAT layer, Eq. 3: attention coefficients from a^l [W h_v || W h_u], LeakyReLU,
+//     neighbour-oriented softmax, weighted sum; its backward by the chain rule.
 //
 // Readings where the paper is silent (normalisation degree, loss, optimiser,
 // boundary rule, canonical orders) are the ones listed in the design notes of
@@ -28,7 +30,9 @@
 // Pins (see tests, "not gpu"): dense brute force on tiny graphs, finite
 // differences of the loss, all-ones features on regular graphs, ln C loss at
 // zero weights, partitioned == unpartitioned, the paper's printed transfer
-// counts and buffer example, brute-force set arithmetic.
+// counts and buffer example, brute-force set arithmetic; for the GAT layer a
+// dense statement of Eq. 3 on tiny multigraphs, autograd through it, finite
+// differences, the neighbour mean at zero attention parameters.
 
 #include <algorithm>
 #include <cmath>
@@ -409,6 +413,120 @@ void orc_layer_bwd_chunked(int64_t V, const int64_t* indptr, const int32_t* col,
       }
     }
   }
+}
+
+// ---------------------------------------------------------------------------
+// GAT layer (Eq. 3), one attention head
+// ---------------------------------------------------------------------------
+// For every stored edge e = (u -> v) of the CSC (multi-edges each count, the
+// self-loop is an edge like any other):
+//   t = H W                                   parameterised representations
+//   y_e = a_dst . t_v + a_src . t_u           a^l applied to [W h_v || W h_u]
+//   x_e = LeakyReLU(y_e)                      slope for y_e <= 0, 1 for y_e > 0
+//   alpha_e = exp(x_e) / sum_{e' in in(v)} exp(x_e')    neighbour-oriented softmax
+//   z_v = sum_{e in in(v)} alpha_e t_u ;  h'_v = ReLU(z_v) (or z_v)
+// Readings: the rows that are summed are the parameterised ones (W h_u), as
+// in the attention model the equation cites (the printed sum shows h_u); the
+// first half of a^l multiplies the destination's half of the concatenation; the
+// softmax subtracts the row maximum (same value, no overflow).
+// A vertex with no in-edge (only possible without self-loops) gets z_v = 0.
+void orc_gat_fwd(int64_t V, const int64_t* indptr, const int32_t* col, int64_t d_in, int64_t d_out, const double* H,
+                 const double* W, const double* a_dst, const double* a_src, double slope, int relu, double* T,
+                 double* alpha, double* Z, double* out) {
+  orc_matmul(V, d_in, d_out, H, W, T);
+  std::vector<double> p(V), q(V);
+  for (int64_t v = 0; v < V; ++v) {
+    double sp = 0.0, sq = 0.0;
+    for (int64_t k = 0; k < d_out; ++k) {
+      sp += a_dst[k] * T[v * d_out + k];
+      sq += a_src[k] * T[v * d_out + k];
+    }
+    p[v] = sp;
+    q[v] = sq;
+  }
+#pragma omp parallel for schedule(dynamic, 64)
+  for (int64_t v = 0; v < V; ++v) {
+    const int64_t e0 = indptr[v], e1 = indptr[v + 1];
+    double m = -1e300;
+    for (int64_t e = e0; e < e1; ++e) {
+      const double y = p[v] + q[col[e]];
+      const double x = y > 0.0 ? y : slope * y;
+      alpha[e] = x;
+      if (x > m) m = x;
+    }
+    double sum = 0.0;
+    for (int64_t e = e0; e < e1; ++e) {
+      alpha[e] = std::exp(alpha[e] - m);
+      sum += alpha[e];
+    }
+    for (int64_t k = 0; k < d_out; ++k) Z[v * d_out + k] = 0.0;
+    for (int64_t e = e0; e < e1; ++e) {
+      alpha[e] /= sum;
+      const double* tu = T + (int64_t)col[e] * d_out;
+      for (int64_t k = 0; k < d_out; ++k) Z[v * d_out + k] += alpha[e] * tu[k];
+    }
+    for (int64_t k = 0; k < d_out; ++k) {
+      const double z = Z[v * d_out + k];
+      out[v * d_out + k] = (relu && !(z > 0.0)) ? 0.0 : z;
+    }
+  }
+}
+
+// Chain rule through the layer above, edge by edge.  dOut = grad h'.
+//   dz = dOut * [z > 0]
+//   d alpha_e = dz_v . t_u ;  dt_u += alpha_e dz_v
+//   softmax:   dx_e = alpha_e (d alpha_e - sum_{e'} alpha_e' d alpha_e')
+//   LeakyReLU: dy_e = dx_e * (1 if y_e > 0 else slope)
+//   dp_v += dy_e ; dq_u += dy_e ;  dt_v += dp_v a_dst ; dt_u += dq_u a_src
+//   da_dst = sum_v dp_v t_v ; da_src = sum_u dq_u t_u ; dW = H^T dt ; dH = dt W^T
+void orc_gat_bwd(int64_t V, const int64_t* indptr, const int32_t* col, int64_t d_in, int64_t d_out, const double* H,
+                 const double* W, const double* a_dst, const double* a_src, double slope, int relu, const double* T,
+                 const double* alpha, const double* Z, const double* dOut, double* dH, double* dW, double* da_dst,
+                 double* da_src) {
+  std::vector<double> p(V), q(V), dp(V, 0.0), dq(V, 0.0), dT((size_t)V * d_out, 0.0), dz(d_out);
+  for (int64_t v = 0; v < V; ++v) {
+    double sp = 0.0, sq = 0.0;
+    for (int64_t k = 0; k < d_out; ++k) {
+      sp += a_dst[k] * T[v * d_out + k];
+      sq += a_src[k] * T[v * d_out + k];
+    }
+    p[v] = sp;
+    q[v] = sq;
+  }
+  for (int64_t v = 0; v < V; ++v) {
+    const int64_t e0 = indptr[v], e1 = indptr[v + 1];
+    for (int64_t k = 0; k < d_out; ++k)
+      dz[k] = (relu && !(Z[v * d_out + k] > 0.0)) ? 0.0 : dOut[v * d_out + k];
+    std::vector<double> dal(e1 - e0);
+    double S = 0.0;
+    for (int64_t e = e0; e < e1; ++e) {
+      const int64_t u = col[e];
+      double dot = 0.0;
+      for (int64_t k = 0; k < d_out; ++k) {
+        dot += dz[k] * T[u * d_out + k];
+        dT[u * d_out + k] += alpha[e] * dz[k];
+      }
+      dal[e - e0] = dot;
+      S += alpha[e] * dot;
+    }
+    for (int64_t e = e0; e < e1; ++e) {
+      const int64_t u = col[e];
+      const double dx = alpha[e] * (dal[e - e0] - S);
+      const double y = p[v] + q[u];
+      const double dy = dx * (y > 0.0 ? 1.0 : slope);
+      dp[v] += dy;
+      dq[u] += dy;
+    }
+  }
+  for (int64_t k = 0; k < d_out; ++k) da_dst[k] = da_src[k] = 0.0;
+  for (int64_t v = 0; v < V; ++v)
+    for (int64_t k = 0; k < d_out; ++k) {
+      dT[v * d_out + k] += dp[v] * a_dst[k] + dq[v] * a_src[k];
+      da_dst[k] += dp[v] * T[v * d_out + k];
+      da_src[k] += dq[v] * T[v * d_out + k];
+    }
+  orc_matmul_tn(V, d_in, d_out, H, dT.data(), dW);
+  if (dH) orc_matmul_nt(V, d_out, d_in, dT.data(), W, dH);
 }
 
 }  // extern "C"

@@ -224,3 +224,36 @@ def layer_bwd_chunked(indptr, col, b, ga) -> np.ndarray:
     lib().orc_layer_bwd_chunked(C.c_int64(V), _p(indptr), _p(col), C.c_int(b.shape[0] - 1), _p(b), C.c_int64(d),
                                 _p(ga), _p(gh))
     return gh
+
+
+# ---------------------------------------------------------------- GAT layer (Eq. 3)
+
+def gat_layer_fwd(indptr, col, H, W, a_dst, a_src, slope: float = 0.2, relu: bool = True) -> Dict[str, np.ndarray]:
+    """One attention head over the stored edges: t = H W, alpha = neighbour softmax of
+    LeakyReLU(a_dst.t_v + a_src.t_u), z_v = sum alpha_e t_u, h = ReLU(z) (or z)."""
+    H, W, a_dst, a_src = _f64(H), _f64(W), _f64(a_dst), _f64(a_src)
+    V, d_in = H.shape
+    d_out = W.shape[1]
+    assert W.shape[0] == d_in and a_dst.shape == (d_out,) and a_src.shape == (d_out,)
+    indptr, col = _i64(indptr), _i32(col)
+    out = {"t": np.zeros((V, d_out)), "alpha": np.zeros(int(indptr[-1])), "z": np.zeros((V, d_out)),
+           "h": np.zeros((V, d_out))}
+    lib().orc_gat_fwd(C.c_int64(V), _p(indptr), _p(col), C.c_int64(d_in), C.c_int64(d_out), _p(H), _p(W), _p(a_dst),
+                      _p(a_src), C.c_double(slope), C.c_int(int(relu)), _p(out["t"]), _p(out["alpha"]), _p(out["z"]),
+                      _p(out["h"]))
+    return out
+
+
+def gat_layer_bwd(indptr, col, H, W, a_dst, a_src, fwd: Dict[str, np.ndarray], dh, slope: float = 0.2,
+                  relu: bool = True, want_dH: bool = True) -> Dict[str, np.ndarray]:
+    """Gradients of the layer above given dh = grad h; `fwd` is gat_layer_fwd's result."""
+    H, W, a_dst, a_src, dh = _f64(H), _f64(W), _f64(a_dst), _f64(a_src), _f64(dh)
+    V, d_in = H.shape
+    d_out = W.shape[1]
+    indptr, col = _i64(indptr), _i32(col)
+    out = {"dH": np.zeros((V, d_in)) if want_dH else None, "dW": np.zeros((d_in, d_out)), "da_dst": np.zeros(d_out),
+           "da_src": np.zeros(d_out)}
+    lib().orc_gat_bwd(C.c_int64(V), _p(indptr), _p(col), C.c_int64(d_in), C.c_int64(d_out), _p(H), _p(W), _p(a_dst),
+                      _p(a_src), C.c_double(slope), C.c_int(int(relu)), _p(fwd["t"]), _p(fwd["alpha"]), _p(fwd["z"]),
+                      _p(dh), _p(out["dH"]), _p(out["dW"]), _p(out["da_dst"]), _p(out["da_src"]))
+    return out
