@@ -256,6 +256,40 @@ int ht_layer_bwd(ht_ctx *ctx, const ht_graph *g, const ht_layer_desc *desc, cons
                  const float *W, const ht_tensor *dH_out, const ht_tensor *H_out, ht_tensor *dH_in,
                  float *dW, ht_stats *stats);
 
+/* ---------------------------------------------------------------- GAT layer */
+
+/* One attention head of Eq. 3 over the stored edges (multi-edges count once
+ * each, the self-loop is an edge like any other):
+ *   t = H W ;  y_e = a_dst . t_v + a_src . t_u  for e = (u -> v)
+ *   alpha_e = exp(LeakyReLU(y_e)) / sum over v's in-edges ;  H'_v = act(sum alpha_e t_u)
+ * a_dst / a_src are the halves of a^l that meet the destination's / the
+ * source's half of the concatenation [W h_v || W h_u]; the D^-1/2 weights of
+ * the GCN path are not used. */
+typedef struct {
+  int32_t d_in, d_out; /* d_out <= 1024 */
+  int32_t act;         /* HT_ACT_*                                  */
+  float slope;         /* LeakyReLU slope for y <= 0, in [0, 1]     */
+} ht_gat_desc;
+
+/* Forward over all chunks.  H_in [V x d_in], H_out [V x d_out]: HBM (HT_ESHAPE
+ * otherwise).  W [d_in x d_out] row-major dense, a_dst, a_src [d_out]: device.
+ * Nothing of size O(E) and no parameterised row outlives the call. */
+int ht_gat_layer_fwd(ht_ctx *ctx, const ht_graph *g, const ht_gat_desc *desc, const ht_tensor *H_in,
+                     const float *W, const float *a_dst, const float *a_src, ht_tensor *H_out,
+                     ht_stats *stats);
+
+/* Backward by recomputation from the layer input (Sec. 4.2: models with
+ * computation on edges recompute instead of caching O(|E|) data): t, the
+ * scores and the coefficients are computed again, then
+ *   dz = dH_out * [H_out > 0] (no mask when act = none)
+ *   dW, da_dst, da_src: overwritten;  dH_in (nullable): ACCUMULATED into.
+ * H_out is the forward result (also read for the softmax's backward); all
+ * vertex tensors in HBM; dW [d_in x d_out], da_dst, da_src [d_out]: device. */
+int ht_gat_layer_bwd(ht_ctx *ctx, const ht_graph *g, const ht_gat_desc *desc, const ht_tensor *H_in,
+                     const float *W, const float *a_dst, const float *a_src, const ht_tensor *H_out,
+                     const ht_tensor *dH_out, ht_tensor *dH_in, float *dW, float *da_dst, float *da_src,
+                     ht_stats *stats);
+
 /* -------------------------------------------------------------------- epoch */
 
 enum { HT_RES_AUTO = 0, HT_RES_HBM = 1, HT_RES_HOST = 2 };

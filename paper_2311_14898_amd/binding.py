@@ -87,6 +87,10 @@ class ht_model(C.Structure):
                 ("W", C.POINTER(C.c_void_p)), ("lr", C.c_float), ("reserved2", C.c_int32)]
 
 
+class ht_gat_desc(C.Structure):
+    _fields_ = [("d_in", C.c_int32), ("d_out", C.c_int32), ("act", C.c_int32), ("slope", C.c_float)]
+
+
 class ht_plan_opts(C.Structure):
     _fields_ = [("res_h", C.c_int32), ("res_a", C.c_int32), ("res_g", C.c_int32), ("inter", C.c_int32),
                 ("gather_mode", C.c_int32), ("order", C.c_int32), ("hbm_budget_bytes", C.c_int64)]
@@ -95,7 +99,7 @@ class ht_plan_opts(C.Structure):
 EXPORTS = ["ht_ctx_create", "ht_ctx_destroy", "ht_sync", "ht_ctx_set_hbm_budget", "ht_strerror", "ht_last_error",
            "ht_partition", "ht_graph_destroy", "ht_graph_info_get", "ht_graph_chunk_info", "ht_graph_export_chunk",
            "ht_graph_export_csc", "ht_graph_chunk_order", "ht_layer_fwd", "ht_layer_bwd", "ht_epoch", "ht_epoch_buffer", "ht_tensor_to_host", "ht_memory_model",
-           "ht_chunk_rows_model"]
+           "ht_chunk_rows_model", "ht_gat_layer_fwd", "ht_gat_layer_bwd"]
 
 _lib = None
 
@@ -143,6 +147,11 @@ def load():
     lib.ht_tensor_to_host.argtypes = [C.c_void_p, C.POINTER(ht_tensor), C.c_void_p]
     lib.ht_memory_model.argtypes = [C.c_int64, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_double),
                                     C.POINTER(C.c_double)]
+    lib.ht_gat_layer_fwd.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(ht_gat_desc), C.POINTER(ht_tensor), C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.POINTER(ht_tensor), C.POINTER(ht_stats)]
+    lib.ht_gat_layer_bwd.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(ht_gat_desc), C.POINTER(ht_tensor), C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.POINTER(ht_tensor), C.POINTER(ht_tensor),
+                                     C.POINTER(ht_tensor), C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(ht_stats)]
     _lib = lib
     return lib
 
@@ -302,6 +311,43 @@ def ht_layer_bwd(ctx, g, d_in: int, d_out: int, act: int, ckpt: torch.Tensor, W:
     _check(load().ht_layer_bwd(ctx, g, C.byref(desc), C.byref(ck), C.c_void_p(W.data_ptr()), C.byref(dho),
                                C.byref(ho) if ho is not None else None, C.byref(dhi) if dhi is not None else None,
                                C.c_void_p(dW.data_ptr()), C.byref(st) if st is not None else None), ctx)
+    return st
+
+
+# ---------------------------------------------------------------- GAT layer
+
+def _vec(t: torch.Tensor, n: int):
+    assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() == n
+    return C.c_void_p(t.data_ptr())
+
+
+def ht_gat_layer_fwd(ctx, g, d_in: int, d_out: int, act: int, H_in: torch.Tensor, W: torch.Tensor, a_dst: torch.Tensor,
+                     a_src: torch.Tensor, H_out: torch.Tensor, slope: float = 0.2, want_stats: bool = False):
+    assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous() and tuple(W.shape) == (d_in, d_out)
+    desc = ht_gat_desc(d_in, d_out, act, slope)
+    hin, hout = tensor_view(H_in, d_in), tensor_view(H_out, d_out)
+    st = ht_stats() if want_stats else None
+    torch.cuda.synchronize()
+    _check(load().ht_gat_layer_fwd(ctx, g, C.byref(desc), C.byref(hin), C.c_void_p(W.data_ptr()), _vec(a_dst, d_out),
+                                   _vec(a_src, d_out), C.byref(hout), C.byref(st) if st is not None else None), ctx)
+    return st
+
+
+def ht_gat_layer_bwd(ctx, g, d_in: int, d_out: int, act: int, H_in: torch.Tensor, W: torch.Tensor, a_dst: torch.Tensor,
+                     a_src: torch.Tensor, H_out: torch.Tensor, dH_out: torch.Tensor, dW: torch.Tensor,
+                     da_dst: torch.Tensor, da_src: torch.Tensor, dH_in: Optional[torch.Tensor] = None,
+                     slope: float = 0.2, want_stats: bool = False):
+    assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous() and tuple(W.shape) == (d_in, d_out)
+    assert dW.is_cuda and dW.dtype == torch.float32 and dW.is_contiguous() and tuple(dW.shape) == (d_in, d_out)
+    desc = ht_gat_desc(d_in, d_out, act, slope)
+    hin, hout, dho = tensor_view(H_in, d_in), tensor_view(H_out, d_out), tensor_view(dH_out, d_out)
+    dhi = tensor_view(dH_in, d_in) if dH_in is not None else None
+    st = ht_stats() if want_stats else None
+    torch.cuda.synchronize()
+    _check(load().ht_gat_layer_bwd(ctx, g, C.byref(desc), C.byref(hin), C.c_void_p(W.data_ptr()), _vec(a_dst, d_out),
+                                   _vec(a_src, d_out), C.byref(hout), C.byref(dho),
+                                   C.byref(dhi) if dhi is not None else None, C.c_void_p(dW.data_ptr()),
+                                   _vec(da_dst, d_out), _vec(da_src, d_out), C.byref(st) if st is not None else None), ctx)
     return st
 
 

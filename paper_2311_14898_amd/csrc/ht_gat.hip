@@ -1,0 +1,559 @@
+// GAT layer (Eq. 3), one attention head, forward and backward over the chunks
+// of a partitioned graph, all vertex tensors in HBM.
+//
+//   t = H W ;  p_v = a_dst . t_v ;  q_u = a_src . t_u
+//   edge (u -> v):  y = p_v + q_u ;  x = LeakyReLU(y) ;  alpha = softmax over in(v)
+//   z_v = sum alpha_e t_u ;  h'_v = act(z_v)
+//
+// A chunk holds every in-edge of its destinations (Sec. 4.1), so the neighbour
+// softmax is complete inside a chunk.  Nothing of size O(E) survives a call: the
+// backward pass recomputes t, p, q and the coefficients (Sec. 4.2: for models
+// with edge computation recomputation is cheaper than caching O(|E|) data).
+// Per chunk, edge coefficients live in a scratch array of the chunk's size.
+//
+// Backward.  With dz = dh' * act'(z) and S_v = dz_v . z_v  (= sum_e alpha_e dalpha_e):
+//   dalpha_e = dz_v . t_u ;  dy_e = alpha_e (dalpha_e - S_v) LeakyReLU'(y_e)
+//   dp_v = sum_{e in in(v)} dy_e      (pass over destinations, reads rows of t)
+//   dq_u = sum_{e in out(u)} dy_e ;  dt_u = sum_{e in out(u)} alpha_e dz_v
+//                                     (pass over sources, reads rows of dz)
+//   dt_v += dp_v a_dst + dq_v a_src ;  da_dst = sum_v dp_v t_v ;  da_src = sum_v dq_v t_v
+//   dW = H^T dt ;  dH = dt W^T
+// Both passes are pulls over the work items built at partition time; rows cut
+// into several items are finished in item order, so results are bit-reproducible.
+// Merged duplicate edges: an entry of multiplicity k stands for k equal edges,
+// its coefficient is k times the single edge's.
+#include <algorithm>
+#include <chrono>
+
+#include "ht_internal.h"
+
+namespace {
+
+__device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ void st4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+  return x;
+}
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
+  return x;
+}
+__device__ __forceinline__ float lrelu(float y, float slope) { return y > 0.f ? y : slope * y; }
+// coefficient of one entry; the same expression in every kernel, so the forward, the
+// destination pass and the source pass of a chunk see identical values
+__device__ __forceinline__ float coef(float y, float slope, float m, float zinv, float mult) {
+  return mult * expf(lrelu(y, slope) - m) * zinv;
+}
+
+// p[v] = a_dst . T[v], q[v] = a_src . T[v]; a wave per vertex
+__global__ void __launch_bounds__(256) k_gat_pq(const float* __restrict__ T, int64_t ld, int d, const float* __restrict__ a_dst,
+                                                const float* __restrict__ a_src, int64_t V, float* __restrict__ p,
+                                                float* __restrict__ q) {
+  const int lane = threadIdx.x & 63;
+  const int64_t v = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (v >= V) return;
+  float sp = 0.f, sq = 0.f;
+  for (int c = lane; c < d; c += 64) {
+    const float t = T[v * ld + c];
+    sp = fmaf(a_dst[c], t, sp);
+    sq = fmaf(a_src[c], t, sq);
+  }
+  sp = wave_sum(sp);
+  sq = wave_sum(sq);
+  if (lane == 0) {
+    p[v] = sp;
+    q[v] = sq;
+  }
+}
+
+// Neighbour softmax of the rows of one chunk: row maximum m, 1 / sum, and the
+// coefficient of every entry (in destination order).  A wave per row.
+__global__ void __launch_bounds__(256) k_gat_softmax(const int64_t* __restrict__ rowptr, int64_t e_base, int64_t ndst,
+                                                     const int32_t* __restrict__ col, const float* __restrict__ mult,
+                                                     const float* __restrict__ p_chunk, const float* __restrict__ q,
+                                                     float slope, float* __restrict__ w, float* __restrict__ m_chunk,
+                                                     float* __restrict__ zinv_chunk) {
+  const int lane = threadIdx.x & 63;
+  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= ndst) return;
+  const int64_t e0 = rowptr[r] - e_base, e1 = rowptr[r + 1] - e_base;
+  const float pv = p_chunk[r];
+  float m = -3.0e38f;
+  for (int64_t e = e0 + lane; e < e1; e += 64) m = fmaxf(m, lrelu(pv + q[col[e]], slope));
+  m = wave_max(m);
+  float s = 0.f;
+  for (int64_t e = e0 + lane; e < e1; e += 64) s += (mult ? mult[e] : 1.f) * expf(lrelu(pv + q[col[e]], slope) - m);
+  s = wave_sum(s);
+  const float zinv = s > 0.f ? 1.f / s : 0.f;
+  for (int64_t e = e0 + lane; e < e1; e += 64) w[e] = coef(pv + q[col[e]], slope, m, zinv, mult ? mult[e] : 1.f);
+  if (lane == 0) {
+    m_chunk[r] = m;
+    zinv_chunk[r] = zinv;
+  }
+}
+
+// dz = dh * [h > 0] (or dh), pad columns zero, and S_v = dz_v . h_v; a wave per row of the chunk
+__global__ void __launch_bounds__(256) k_gat_dz(const float* __restrict__ dh, int64_t ld_dh, const float* __restrict__ h,
+                                                int64_t ld_h, int relu, int64_t rows, int d, float* __restrict__ dz,
+                                                int64_t ld_dz, float* __restrict__ S) {
+  const int lane = threadIdx.x & 63;
+  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  float s = 0.f;
+  for (int c = lane; c < (int)ld_dz; c += 64) {
+    float g = 0.f;
+    if (c < d) {
+      const float hv = h[r * ld_h + c];
+      g = dh[r * ld_dh + c];
+      if (relu && !(hv > 0.f)) g = 0.f;
+      s = fmaf(g, hv, s);
+    }
+    dz[r * ld_dz + c] = g;
+  }
+  s = wave_sum(s);
+  if (lane == 0) S[r] = s;
+}
+
+struct GatPass {
+  // items of the pass (rows = destinations of the chunk, or local sources)
+  const int32_t* it_row; const int64_t* it_e0; const int32_t* it_len; const int32_t* it_part; int64_t n_items;
+  const int32_t* idx;        // per entry: row of `mat` to read (global source id / local destination)
+  const float* w;            // destination pass: coefficient per entry (destination order)
+  const float* mult;         // source pass: multiplicity per entry (nullable: 1)
+  const float* mat;          // rows gathered per entry: t (destination pass) or dz of the chunk (source pass)
+  int64_t mat_ld;
+  const float* own;          // the item's own row: dz of the chunk (destination pass) or t (source pass)
+  int64_t own_ld;
+  const int32_t* own_idx;    // row r -> row of `own` (nullable: r)
+  int d;
+  const float* p; const float* q;        // per vertex
+  const float* m; const float* zinv;     // per vertex (source pass recomputes coefficients from them)
+  const float* S;            // per row of the chunk
+  int64_t dst0;              // first destination of the chunk
+  float slope;
+  // outputs
+  float* dp_chunk;           // destination pass: dp of rows without a partial
+  float* spart;              // scalar partial per cut item
+  float* out; int64_t out_ld; const int32_t* out_idx;   // source pass: dt rows (accumulated), scalar in column sc_col
+  float* partial;            // source pass: [n_part x out_ld] partial rows of cut items
+  int sc_col;
+};
+
+// Destination pass: dp_v = sum over v's entries of  w_e (dz_v . t_u - S_v) LeakyReLU'(y_e).
+// A wave per item; lanes hold float4 slices of dz_v; four rows of t are in flight.
+template <int VPL>
+__global__ void __launch_bounds__(256) k_gat_dst(GatPass a) {
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t t = (int64_t)blockIdx.x * 4 + wave;
+  if (t >= a.n_items) return;
+  const int32_t r = a.it_row[t];
+  const int64_t e0 = a.it_e0[t];
+  const int32_t len = a.it_len[t], part = a.it_part[t];
+  float4 mine[VPL];
+#pragma unroll
+  for (int j = 0; j < VPL; ++j) {
+    const int c = (j * 64 + lane) * 4;
+    mine[j] = c < a.d ? ld4(a.own + (int64_t)r * a.own_ld + c) : make_float4(0.f, 0.f, 0.f, 0.f);   // pads of dz are zero
+  }
+  const float pv = a.p[a.dst0 + r], Sv = a.S[r];
+  float acc = 0.f;
+  for (int32_t base = 0; base < len; base += 64) {
+    const int32_t nh = (len - base) < 64 ? (len - base) : 64;
+    int32_t my_u = 0;
+    float my_w = 0.f, my_q = 0.f;
+    if (lane < nh) {
+      my_u = a.idx[e0 + base + lane];
+      my_w = a.w[e0 + base + lane];
+      my_q = a.q[my_u];
+    }
+    for (int32_t k = 0; k < nh; k += 4) {
+      float dot[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int kc = (k + u) < nh ? (k + u) : (nh - 1);
+        const int32_t c = __builtin_amdgcn_readlane(my_u, kc);
+        float s = 0.f;
+#pragma unroll
+        for (int j = 0; j < VPL; ++j) {
+          const int cc = (j * 64 + lane) * 4;
+          if (cc < a.d) {
+            const float4 x = ld4(a.mat + (int64_t)c * a.mat_ld + cc);
+            s = fmaf(mine[j].x, x.x, fmaf(mine[j].y, x.y, fmaf(mine[j].z, x.z, fmaf(mine[j].w, x.w, s))));
+          }
+        }
+        dot[u] = s;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float da = wave_sum(dot[u]);
+        if (k + u < nh) {
+          const float w = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_w), k + u));
+          const float y = pv + __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_q), k + u));
+          acc += w * (da - Sv) * (y > 0.f ? 1.f : a.slope);
+        }
+      }
+    }
+  }
+  if (lane == 0) {
+    if (part >= 0) a.spart[part] = acc;
+    else a.dp_chunk[r] = acc;
+  }
+}
+
+// dp of the rows cut into several items: their partial sums in item order
+__global__ void k_gat_fix_scalar(const int32_t* __restrict__ fx_row, const int32_t* __restrict__ fx_part0,
+                                 const int32_t* __restrict__ fx_nseg, int64_t n_fix, const float* __restrict__ spart,
+                                 float* __restrict__ dp_chunk) {
+  const int64_t f = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (f >= n_fix) return;
+  float s = 0.f;
+  const int32_t p0 = fx_part0[f], ns = fx_nseg[f];
+  for (int32_t k = 0; k < ns; ++k) s += spart[p0 + k];
+  dp_chunk[fx_row[f]] = s;
+}
+
+// Source pass: for local source i (vertex u) over its entries (u -> v) of the chunk:
+//   dt_u += sum w_e dz_v ;  dq_u += sum w_e (dz_v . t_u - S_v) LeakyReLU'(y_e),  w_e recomputed.
+template <int VPL>
+__global__ void __launch_bounds__(256) k_gat_src(GatPass a) {
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t t = (int64_t)blockIdx.x * 4 + wave;
+  if (t >= a.n_items) return;
+  const int32_t r = a.it_row[t];
+  const int64_t e0 = a.it_e0[t];
+  const int32_t len = a.it_len[t], part = a.it_part[t];
+  const int32_t u_id = a.own_idx[r];
+  float4 mine[VPL], acc[VPL];
+#pragma unroll
+  for (int j = 0; j < VPL; ++j) {
+    const int c = (j * 64 + lane) * 4;
+    mine[j] = c < a.d ? ld4(a.own + (int64_t)u_id * a.own_ld + c) : make_float4(0.f, 0.f, 0.f, 0.f);   // pads of t are zero
+    acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  const float qu = a.q[u_id];
+  float accq = 0.f;
+  for (int32_t base = 0; base < len; base += 64) {
+    const int32_t nh = (len - base) < 64 ? (len - base) : 64;
+    int32_t my_v = 0;
+    float my_c = 0.f, my_f = 0.f, my_S = 0.f;   // coefficient, LeakyReLU', S_v of the lane's entry
+    if (lane < nh) {
+      my_v = a.idx[e0 + base + lane];
+      const int64_t v = a.dst0 + my_v;
+      const float y = a.p[v] + qu;
+      my_c = coef(y, a.slope, a.m[v], a.zinv[v], a.mult ? a.mult[e0 + base + lane] : 1.f);
+      my_f = y > 0.f ? 1.f : a.slope;
+      my_S = a.S[my_v];
+    }
+    for (int32_t k = 0; k < nh; k += 4) {
+      float4 x[4][VPL];
+      float dot[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int kc = (k + u) < nh ? (k + u) : (nh - 1);
+        const int32_t c = __builtin_amdgcn_readlane(my_v, kc);
+        float s = 0.f;
+#pragma unroll
+        for (int j = 0; j < VPL; ++j) {
+          const int cc = (j * 64 + lane) * 4;
+          x[u][j] = cc < a.d ? ld4(a.mat + (int64_t)c * a.mat_ld + cc) : make_float4(0.f, 0.f, 0.f, 0.f);
+          s = fmaf(mine[j].x, x[u][j].x, fmaf(mine[j].y, x[u][j].y, fmaf(mine[j].z, x[u][j].z, fmaf(mine[j].w, x[u][j].w, s))));
+        }
+        dot[u] = s;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float da = wave_sum(dot[u]);
+        if (k + u < nh) {
+          const float w = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_c), k + u));
+          const float f = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_f), k + u));
+          const float Sv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_S), k + u));
+          accq += w * (da - Sv) * f;
+#pragma unroll
+          for (int j = 0; j < VPL; ++j) {
+            acc[j].x = fmaf(w, x[u][j].x, acc[j].x);
+            acc[j].y = fmaf(w, x[u][j].y, acc[j].y);
+            acc[j].z = fmaf(w, x[u][j].z, acc[j].z);
+            acc[j].w = fmaf(w, x[u][j].w, acc[j].w);
+          }
+        }
+      }
+    }
+  }
+  float* row = part >= 0 ? a.partial + (int64_t)part * a.out_ld : a.out + (int64_t)a.out_idx[r] * a.out_ld;
+#pragma unroll
+  for (int j = 0; j < VPL; ++j) {
+    const int c = (j * 64 + lane) * 4;
+    if (c >= a.d) continue;
+    float4 v = acc[j];
+    if (part < 0) {
+      const float4 o = ld4(row + c);
+      v = make_float4(o.x + v.x, o.y + v.y, o.z + v.z, o.w + v.w);
+    }
+    st4(row + c, v);
+  }
+  if (lane == 0) {
+    // the scalar travels in its own float4 column block behind the data columns
+    float4 sc = make_float4(accq, 0.f, 0.f, 0.f);
+    if (part < 0) sc.x += row[a.sc_col];
+    st4(row + a.sc_col, sc);
+  }
+}
+
+// dt_v += dp_v a_dst + dq_v a_src; the pair (dp_v, dq_v) also goes to a [V x 4] matrix for da = T^T [dp dq]
+__global__ void __launch_bounds__(256) k_gat_finish(float* __restrict__ dT, int64_t ld, int d, int sc_col,
+                                                    const float* __restrict__ dp, const float* __restrict__ a_dst,
+                                                    const float* __restrict__ a_src, int64_t V, float* __restrict__ pq4) {
+  const int lane = threadIdx.x & 63;
+  const int64_t v = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (v >= V) return;
+  const float dpv = dp[v], dqv = dT[v * ld + sc_col];
+  for (int c = lane; c < d; c += 64) dT[v * ld + c] += dpv * a_dst[c] + dqv * a_src[c];
+  if (lane == 0) st4(pq4 + v * 4, make_float4(dpv, dqv, 0.f, 0.f));
+}
+
+__global__ void k_gat_split(const float* __restrict__ da4, int d, float* __restrict__ da_dst, float* __restrict__ da_src) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c < d) {
+    da_dst[c] = da4[c * 4 + 0];
+    da_src[c] = da4[c * 4 + 1];
+  }
+}
+
+struct GatWs {
+  float *T, *p, *q, *m, *zinv, *S, *dp, *pq4, *w;
+  int64_t ld_t;
+};
+
+int check(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const ht_tensor* t, int32_t cols, const char* name) {
+  if (!t || !t->ptr) return ht_set_err(ctx, HT_EINVAL, "%s: null tensor", name);
+  if (t->rows != g->V || t->cols != cols) return ht_set_err(ctx, HT_ESHAPE, "%s: expected [%lld x %d]", name, (long long)g->V, cols);
+  if (t->ld < cols || (t->ld & 3) || ((uintptr_t)t->ptr & 15)) return ht_set_err(ctx, HT_ESHAPE, "%s: bad pitch or alignment", name);
+  if (t->loc != HT_LOC_DEVICE) return ht_set_err(ctx, HT_ESHAPE, "GAT layer: %s must be in HBM", name);
+  (void)desc;
+  return HT_OK;
+}
+
+int check_desc(ht_ctx* ctx, const ht_gat_desc* d) {
+  if (d->d_in <= 0 || d->d_out <= 0) return ht_set_err(ctx, HT_ESHAPE, "layer widths must be positive");
+  if (d->d_out > 1024) return ht_set_err(ctx, HT_ESHAPE, "GAT layer: d_out %d > 1024", d->d_out);
+  if (d->act != HT_ACT_NONE && d->act != HT_ACT_RELU) return ht_set_err(ctx, HT_EINVAL, "unknown activation %d", d->act);
+  if (!(d->slope >= 0.f && d->slope <= 1.f)) return ht_set_err(ctx, HT_EINVAL, "LeakyReLU slope must lie in [0, 1]");
+  return HT_OK;
+}
+
+// t = H W (pad columns zero), p, q
+int prepare(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const ht_tensor* H, const float* W, const float* a_dst,
+            const float* a_src, bool backward, GatWs* ws, ht_stats* st) {
+  hipStream_t s = ctx->stream;
+  const int64_t V = std::max<int64_t>(g->V, 1);
+  ws->ld_t = ht_row_pitch(desc->d_out, true);
+  HT_TRY(ht_scratch(ctx, HT_S_TFULL, (size_t)V * ws->ld_t * 4, (void**)&ws->T));
+  float* vec = nullptr;
+  HT_TRY(ht_scratch(ctx, HT_S_GATV, (size_t)V * 10 * 4, (void**)&vec));
+  ws->p = vec; ws->q = vec + V; ws->m = vec + 2 * V; ws->zinv = vec + 3 * V; ws->S = vec + 4 * V; ws->dp = vec + 5 * V;
+  ws->pq4 = vec + 6 * V;
+  HT_TRY(ht_scratch(ctx, HT_S_GATE, (size_t)std::max<int64_t>(g->max_nnz, 1) * 4, (void**)&ws->w));
+  if (ws->ld_t != desc->d_out) HT_TRY(ht_fill_zero(ctx, s, ws->T, (size_t)g->V * ws->ld_t * 4));
+  const int64_t step = (int64_t)1 << 22;
+  for (int64_t r0 = 0; r0 < g->V; r0 += step) {
+    const int64_t nr = std::min(step, g->V - r0);
+    HT_TRY(ht_gemm_nn(ctx, s, H->ptr + r0 * H->ld, H->ld, W, ws->T + r0 * ws->ld_t, ws->ld_t, nr, desc->d_in, desc->d_out, 0));
+    st->n_gemm += 1;
+    st->gemm_flops += 2.0 * nr * desc->d_in * desc->d_out;
+  }
+  if (g->V > 0) {
+    k_gat_pq<<<(unsigned)((g->V + 3) / 4), 256, 0, s>>>(ws->T, ws->ld_t, desc->d_out, a_dst, a_src, g->V, ws->p, ws->q);
+    HT_LAUNCH_CHECK(ctx);
+  }
+  (void)backward;
+  return HT_OK;
+}
+
+int softmax_chunk(ht_ctx* ctx, const ht_graph* g, const ChunkMeta& c, const ht_gat_desc* desc, const GatWs& ws) {
+  const int64_t ndst = c.dst1 - c.dst0;
+  const int64_t* rowptr = (g->merged ? g->uindptr.p : g->indptr.p) + c.dst0;
+  const int64_t e_base = g->merged ? c.ue0 : c.e0;
+  const int32_t* col = g->merged ? g->ucol.p + c.ue0 : g->col.p + c.e0;
+  const float* mult = g->merged ? g->umult.p + c.ue0 : nullptr;
+  k_gat_softmax<<<(unsigned)((ndst + 3) / 4), 256, 0, ctx->stream>>>(rowptr, e_base, ndst, col, mult, ws.p + c.dst0, ws.q,
+                                                                      desc->slope, ws.w, ws.m + c.dst0, ws.zinv + c.dst0);
+  HT_LAUNCH_CHECK(ctx);
+  return HT_OK;
+}
+
+int launch_dst(ht_ctx* ctx, const GatPass& a, int nvec) {
+  const unsigned nb = (unsigned)((a.n_items + 3) / 4);
+  if (nvec <= 64) k_gat_dst<1><<<nb, 256, 0, ctx->stream>>>(a);
+  else if (nvec <= 128) k_gat_dst<2><<<nb, 256, 0, ctx->stream>>>(a);
+  else k_gat_dst<4><<<nb, 256, 0, ctx->stream>>>(a);
+  HT_LAUNCH_CHECK(ctx);
+  return HT_OK;
+}
+int launch_src(ht_ctx* ctx, const GatPass& a, int nvec) {
+  const unsigned nb = (unsigned)((a.n_items + 3) / 4);
+  if (nvec <= 64) k_gat_src<1><<<nb, 256, 0, ctx->stream>>>(a);
+  else if (nvec <= 128) k_gat_src<2><<<nb, 256, 0, ctx->stream>>>(a);
+  else k_gat_src<4><<<nb, 256, 0, ctx->stream>>>(a);
+  HT_LAUNCH_CHECK(ctx);
+  return HT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ht_gat_layer_fwd(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const ht_tensor* H_in, const float* W,
+                     const float* a_dst, const float* a_src, ht_tensor* H_out, ht_stats* stats) {
+  if (!ctx) return HT_EINVAL;
+  if (!g || !desc || !H_in || !H_out || !W || !a_dst || !a_src) return ht_set_err(ctx, HT_EINVAL, "ht_gat_layer_fwd: null argument");
+  if (g->ctx != ctx) return ht_set_err(ctx, HT_ESTATE, "graph belongs to another context");
+  HT_TRY(check_desc(ctx, desc));
+  HT_TRY(check(ctx, g, desc, H_in, desc->d_in, "H_in"));
+  HT_TRY(check(ctx, g, desc, H_out, desc->d_out, "H_out"));
+  HT_HIP(ctx, hipSetDevice(ctx->device));
+  auto t0 = std::chrono::steady_clock::now();
+  hipStream_t st = ctx->stream;
+  ht_stats local{};
+  GatWs ws{};
+  HT_TRY(prepare(ctx, g, desc, H_in, W, a_dst, a_src, false, &ws, &local));
+  for (int j = 0; j < g->n; ++j) {
+    const ChunkMeta& c = g->chunks[j];
+    if (c.dst1 == c.dst0) continue;
+    HT_TRY(softmax_chunk(ctx, g, c, desc, ws));
+    float* partial = nullptr;
+    if (c.fwd.n_part > 0) HT_TRY(ht_scratch(ctx, HT_S_SPART, (size_t)g->max_fpart * H_out->ld * 4, (void**)&partial));
+    SpmmArgs a{};
+    a.it_row = c.fwd.row; a.it_e0 = c.fwd.e0; a.it_len = c.fwd.len; a.it_part = c.fwd.part; a.n_items = c.fwd.n_items;
+    a.fx_row = c.fwd.fx_row; a.fx_part0 = c.fwd.fx_part0; a.fx_nseg = c.fwd.fx_nseg; a.n_fix = c.fwd.n_fix;
+    a.n_edges = g->merged ? c.nu : c.nnz;
+    a.idx = g->merged ? g->ucol.p + c.ue0 : g->col.p + c.e0;
+    a.w_edge = ws.w;
+    a.src = ws.T; a.src_ld = ws.ld_t; a.d = desc->d_out;
+    a.out = H_out->ptr + c.dst0 * H_out->ld; a.out_ld = H_out->ld;
+    a.accumulate = 0;
+    a.relu = desc->act == HT_ACT_RELU;
+    a.partial = partial;
+    HT_TRY(ht_spmm_launch(ctx, st, a));
+    local.n_spmm_fwd += 1;
+    local.edges += c.nnz;
+  }
+  HT_HIP(ctx, hipStreamSynchronize(st));
+  if (stats) {
+    local.t_total_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+    *stats = local;
+  }
+  return HT_OK;
+}
+
+int ht_gat_layer_bwd(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const ht_tensor* H_in, const float* W,
+                     const float* a_dst, const float* a_src, const ht_tensor* H_out, const ht_tensor* dH_out,
+                     ht_tensor* dH_in, float* dW, float* da_dst, float* da_src, ht_stats* stats) {
+  if (!ctx) return HT_EINVAL;
+  if (!g || !desc || !H_in || !H_out || !dH_out || !W || !a_dst || !a_src || !dW || !da_dst || !da_src)
+    return ht_set_err(ctx, HT_EINVAL, "ht_gat_layer_bwd: null argument");
+  if (g->ctx != ctx) return ht_set_err(ctx, HT_ESTATE, "graph belongs to another context");
+  HT_TRY(check_desc(ctx, desc));
+  HT_TRY(check(ctx, g, desc, H_in, desc->d_in, "H_in"));
+  HT_TRY(check(ctx, g, desc, H_out, desc->d_out, "H_out"));
+  HT_TRY(check(ctx, g, desc, dH_out, desc->d_out, "dH_out"));
+  if (dH_in) HT_TRY(check(ctx, g, desc, dH_in, desc->d_in, "dH_in"));
+  HT_HIP(ctx, hipSetDevice(ctx->device));
+  auto t0 = std::chrono::steady_clock::now();
+  hipStream_t st = ctx->stream;
+  ht_stats local{};
+  GatWs ws{};
+  HT_TRY(prepare(ctx, g, desc, H_in, W, a_dst, a_src, true, &ws, &local));
+  const int d = desc->d_out;
+  const int nvec = (d + 3) / 4;
+  const int sc_col = (int)ws.ld_t;              // the scalar column block sits behind the padded data columns
+  const int64_t ld_dt = ws.ld_t + 4;
+  const int64_t mx = std::max<int64_t>(g->max_ndst, 1);
+  float *dT = nullptr, *dz = nullptr, *spart = nullptr, *da4 = nullptr;
+  HT_TRY(ht_scratch(ctx, HT_S_TFULL2, (size_t)std::max<int64_t>(g->V, 1) * ld_dt * 4, (void**)&dT));
+  HT_TRY(ht_scratch(ctx, HT_S_DZCHUNK, (size_t)mx * ws.ld_t * 4, (void**)&dz));
+  HT_TRY(ht_scratch(ctx, HT_S_MISC, (size_t)(std::max<int64_t>(g->max_fpart, 1) + (int64_t)d * 4) * 4, (void**)&spart));
+  da4 = spart + std::max<int64_t>(g->max_fpart, 1);
+  HT_TRY(ht_fill_zero(ctx, st, dT, (size_t)g->V * ld_dt * 4));
+  for (int j = 0; j < g->n; ++j) {
+    const ChunkMeta& c = g->chunks[j];
+    const int64_t ndst = c.dst1 - c.dst0;
+    if (ndst == 0) continue;
+    HT_TRY(softmax_chunk(ctx, g, c, desc, ws));
+    k_gat_dz<<<(unsigned)((ndst + 3) / 4), 256, 0, st>>>(dH_out->ptr + c.dst0 * dH_out->ld, dH_out->ld,
+                                                          H_out->ptr + c.dst0 * H_out->ld, H_out->ld,
+                                                          desc->act == HT_ACT_RELU, ndst, d, dz, ws.ld_t, ws.S);
+    HT_LAUNCH_CHECK(ctx);
+    GatPass a{};
+    a.d = d; a.p = ws.p; a.q = ws.q; a.m = ws.m; a.zinv = ws.zinv; a.S = ws.S; a.dst0 = c.dst0; a.slope = desc->slope;
+    // destination pass
+    a.it_row = c.fwd.row; a.it_e0 = c.fwd.e0; a.it_len = c.fwd.len; a.it_part = c.fwd.part; a.n_items = c.fwd.n_items;
+    a.idx = g->merged ? g->ucol.p + c.ue0 : g->col.p + c.e0;
+    a.w = ws.w;
+    a.mat = ws.T; a.mat_ld = ws.ld_t;
+    a.own = dz; a.own_ld = ws.ld_t; a.own_idx = nullptr;
+    a.dp_chunk = ws.dp + c.dst0; a.spart = spart;
+    if (a.n_items > 0) HT_TRY(launch_dst(ctx, a, nvec));
+    if (c.fwd.n_fix > 0) {
+      k_gat_fix_scalar<<<(unsigned)((c.fwd.n_fix + 255) / 256), 256, 0, st>>>(c.fwd.fx_row, c.fwd.fx_part0, c.fwd.fx_nseg,
+                                                                               c.fwd.n_fix, spart, ws.dp + c.dst0);
+      HT_LAUNCH_CHECK(ctx);
+    }
+    // source pass
+    float* partial = nullptr;
+    if (c.bwd.n_part > 0) HT_TRY(ht_scratch(ctx, HT_S_SPART, (size_t)g->max_bpart * ld_dt * 4, (void**)&partial));
+    a.it_row = c.bwd.row; a.it_e0 = c.bwd.e0; a.it_len = c.bwd.len; a.it_part = c.bwd.part; a.n_items = c.bwd.n_items;
+    a.idx = g->merged ? g->usdst.p + c.ue0 : g->sdst.p + c.e0;
+    a.w = nullptr;
+    a.mult = g->merged ? g->umult_bwd.p + c.ue0 : nullptr;
+    a.mat = dz; a.mat_ld = ws.ld_t;
+    a.own = ws.T; a.own_ld = ws.ld_t; a.own_idx = g->nbr.p + c.nbr_off;
+    a.out = dT; a.out_ld = ld_dt; a.out_idx = g->nbr.p + c.nbr_off;
+    a.partial = partial; a.sc_col = sc_col;
+    if (a.n_items > 0) HT_TRY(launch_src(ctx, a, nvec));
+    if (c.bwd.n_fix > 0) {
+      SpmmArgs f{};
+      f.fx_row = c.bwd.fx_row; f.fx_part0 = c.bwd.fx_part0; f.fx_nseg = c.bwd.fx_nseg; f.n_fix = c.bwd.n_fix;
+      f.d = sc_col + 4;
+      f.out = dT; f.out_ld = ld_dt; f.out_idx = g->nbr.p + c.nbr_off;
+      f.accumulate = 1;
+      f.partial = partial;
+      HT_TRY(ht_spmm_fix_launch(ctx, st, f));
+    }
+    local.n_spmm_bwd += 2;
+    local.edges += 2 * c.nnz;
+  }
+  if (g->V > 0) {
+    k_gat_finish<<<(unsigned)((g->V + 3) / 4), 256, 0, st>>>(dT, ld_dt, d, sc_col, ws.dp, a_dst, a_src, g->V, ws.pq4);
+    HT_LAUNCH_CHECK(ctx);
+  }
+  // da = T^T [dp dq 0 0]; dW = H^T dt; dH += dt W^T
+  const int64_t step = (int64_t)1 << 22;
+  bool first = true;
+  for (int64_t r0 = 0; r0 < g->V; r0 += step) {
+    const int64_t nr = std::min(step, g->V - r0);
+    HT_TRY(ht_gemm_tn(ctx, st, ws.T + r0 * ws.ld_t, ws.ld_t, ws.pq4 + r0 * 4, 4, da4, nr, d, 4, first ? 0 : 1));
+    HT_TRY(ht_gemm_tn(ctx, st, H_in->ptr + r0 * H_in->ld, H_in->ld, dT + r0 * ld_dt, ld_dt, dW, nr, desc->d_in, d, first ? 0 : 1));
+    if (dH_in)
+      HT_TRY(ht_gemm_nt(ctx, st, dT + r0 * ld_dt, ld_dt, W, dH_in->ptr + r0 * dH_in->ld, dH_in->ld, nr, d, desc->d_in, 1));
+    local.n_gemm += 3;
+    local.gemm_flops += 4.0 * nr * desc->d_in * d;
+    first = false;
+  }
+  if (first) {
+    HT_TRY(ht_fill_zero(ctx, st, dW, (size_t)desc->d_in * d * 4));
+    HT_TRY(ht_fill_zero(ctx, st, da4, (size_t)d * 16));
+  }
+  k_gat_split<<<(unsigned)((d + 255) / 256), 256, 0, st>>>(da4, d, da_dst, da_src);
+  HT_LAUNCH_CHECK(ctx);
+  HT_HIP(ctx, hipStreamSynchronize(st));
+  if (stats) {
+    local.t_total_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+    *stats = local;
+  }
+  return HT_OK;
+}
+
+}  // extern "C"

@@ -20,7 +20,7 @@ struct EpochWs;
 
 enum {
   HT_S_PACKW = 0, HT_S_TNPART, HT_S_LOSS, HT_S_ACHUNK, HT_S_OCHUNK, HT_S_ZCHUNK, HT_S_DZCHUNK, HT_S_DACHUNK,
-  HT_S_NBUF, HT_S_SPART, HT_S_LEAVE, HT_S_MISC, HT_S_TFULL, HT_N_SCRATCH
+  HT_S_NBUF, HT_S_SPART, HT_S_LEAVE, HT_S_MISC, HT_S_TFULL, HT_S_TFULL2, HT_S_GATV, HT_S_GATE, HT_N_SCRATCH
 };
 
 struct ht_ctx {
@@ -202,6 +202,7 @@ struct ht_graph {
   DevArr<int64_t> usptr;       // [v_ori + n] per-chunk by-source offsets in distinct-pair space
   DevArr<int32_t> usdst;       // [n_unique] local destination of each distinct pair, by-source order
   DevArr<float> uw_bwd;        // [n_unique] multiplicity * s[destination]
+  DevArr<float> umult_bwd;     // [n_unique] multiplicity, by-source order
   int64_t v_ori = 0, v_ru = 0, v_load = 0;  // v_load: rows actually loaded per pass with this buffer
   int64_t max_nsrc = 0, max_ndst = 0, max_nnz = 0, max_fpart = 0, max_bpart = 0;
   int64_t cache_rows = 0;
@@ -248,6 +249,8 @@ struct SpmmArgs {
   double* t_fix = nullptr;
 };
 int ht_spmm_launch(ht_ctx* ctx, hipStream_t st, const SpmmArgs& a);
+// Only the second kernel: rows fx_row[] = their partial rows added in item order (d, out*, partial, fx_* are read).
+int ht_spmm_fix_launch(ht_ctx* ctx, hipStream_t st, const SpmmArgs& a);
 
 // Row gather / scatter (ht_spmm.hip)
 // dst[dst_idx[k]] = scale[src_idx[k]] * src[src_idx[k]]   (scale nullable)

@@ -285,7 +285,7 @@ __global__ void k_gather_i32_at(const int64_t* __restrict__ pos, int64_t pos_off
 // backward: per distinct (local source, local destination): usdst, weight mult*s[dst], compacted keys
 __global__ void k_merge_bwd(const int64_t* __restrict__ upos, int64_t nU, const uint64_t* __restrict__ keys,
                             const float* __restrict__ s_chunk, int32_t* __restrict__ usdst, float* __restrict__ uw,
-                            uint64_t* __restrict__ ukeys) {
+                            float* __restrict__ umult, uint64_t* __restrict__ ukeys) {
   int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (u >= nU) return;
   const int64_t t = upos[u];
@@ -294,6 +294,7 @@ __global__ void k_merge_bwd(const int64_t* __restrict__ upos, int64_t nU, const 
   const int32_t d = (int32_t)(k & 0xFFFFFFFFull);
   usdst[u] = d;
   uw[u] = m * s_chunk[d];
+  umult[u] = m;
   ukeys[u] = k;
 }
 
@@ -494,6 +495,7 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
       HT_TRY(g->umult.alloc(ctx, (size_t)nU));
       HT_TRY(g->usdst.alloc(ctx, (size_t)nU));
       HT_TRY(g->uw_bwd.alloc(ctx, (size_t)nU));
+      HT_TRY(g->umult_bwd.alloc(ctx, (size_t)nU));
       k_flag_positions<<<nblk(Ep), TB, 0, st>>>(dflag.p, drank.p, Ep, upos.p);
       HT_LAUNCH_CHECK(ctx);
       HT_HIP(ctx, hipMemcpyAsync(upos.p + nU, &Ep, 8, hipMemcpyHostToDevice, st));
@@ -800,7 +802,7 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
         HT_LAUNCH_CHECK(ctx);
         HT_HIP(ctx, hipMemcpyAsync(mpos.p + c.nu, &c.nnz, 8, hipMemcpyHostToDevice, st));
         k_merge_bwd<<<nblk(c.nu), TB, 0, st>>>(mpos.p, c.nu, csr_sorted, g->s.p + c.dst0, g->usdst.p + c.ue0,
-                                               g->uw_bwd.p + c.ue0, other);
+                                               g->uw_bwd.p + c.ue0, g->umult_bwd.p + c.ue0, other);
         HT_LAUNCH_CHECK(ctx);
         k_boundaries<<<nblk(c.nu), TB, 0, st>>>(other, c.nu, 32, c.nsrc, usptr_j);
         HT_LAUNCH_CHECK(ctx);
@@ -855,7 +857,7 @@ int64_t ht_graph::hbm_bytes() const {
   int64_t b = indptr.bytes() + col.bytes() + s.bytes() + nbr.bytes() + col_local.bytes() + col_slot.bytes() +
               sptr.bytes() + sdst.bytes() + slot.bytes() + gslot.bytes() + reuse.bytes() + load.bytes() +
               load_slot.bytes() + leave.bytes() + leave_slot.bytes() + uindptr.bytes() + ucol.bytes() +
-              ucol_slot.bytes() + uw_fwd.bytes() + umult.bytes() + usdst.bytes() + uw_bwd.bytes() + usptr.bytes();
+              ucol_slot.bytes() + uw_fwd.bytes() + umult.bytes() + usdst.bytes() + uw_bwd.bytes() + umult_bwd.bytes() + usptr.bytes();
   for (const ChunkMeta& c : chunks) b += c.fwd.blob.bytes() + c.bwd.blob.bytes();
   return b;
 }

@@ -360,6 +360,14 @@ int ht_spmm_launch(ht_ctx* ctx, hipStream_t st, const SpmmArgs& a0) {
   return HT_OK;
 }
 
+int ht_spmm_fix_launch(ht_ctx* ctx, hipStream_t st, const SpmmArgs& a) {
+  if (a.n_fix <= 0) return HT_OK;
+  if (a.out_ld & 3) return ht_set_err(ctx, HT_ESHAPE, "aggregation: row pitch must be a multiple of 4");
+  k_spmm_fix<<<(unsigned)a.n_fix, 256, 0, st>>>(a);
+  HT_LAUNCH_CHECK(ctx);
+  return HT_OK;
+}
+
 int ht_gather_rows(ht_ctx* ctx, hipStream_t st, const float* src, int64_t src_ld, const int32_t* src_idx, float* dst,
                    int64_t dst_ld, const int32_t* dst_idx, int64_t n_rows, int32_t d, const float* scale,
                    int max_blocks) {

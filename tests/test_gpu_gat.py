@@ -1,0 +1,125 @@
+"""ht_gat_layer_fwd / ht_gat_layer_bwd (Eq. 3, one head) against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_2311_14898_amd import binding as B
+from paper_2311_14898_amd import inputs
+from tests.util import assert_close, hub_graph
+
+pytestmark = pytest.mark.gpu
+DEV = B.HT_LOC_DEVICE
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = B.ht_ctx_create(0)
+    yield c
+    B.ht_ctx_destroy(c)
+
+
+class Case:
+    def __init__(self, ctx, V, src, dst, n):
+        self.V = V
+        self.g = B.ht_partition(ctx, V, src.cuda(), dst.cuda(), n)
+        self.indptr, self.col = orc.csc_build(V, src.numpy(), dst.numpy(), True)
+
+
+@pytest.fixture(scope="module")
+def cases(ctx):
+    out = {}
+    V = 9_000
+    src, dst = inputs.rmat_edges(V, 150_000, seed=4)
+    out["rmat"] = Case(ctx, V, src, dst, 5)                      # few repeated pairs: canonical arrays
+    k = torch.arange(0, src.numel(), 3)
+    out["multi"] = Case(ctx, V, torch.cat([src, src[k], src[k]]), torch.cat([dst, dst[k], dst[k]]), 4)   # merged entries
+    Vh = 15_013
+    s, d = hub_graph(Vh, 120_000, hub_in=2500, hub_out=2000, seed=2)
+    out["hub"] = Case(ctx, Vh, s, d, 3)                          # rows and sources cut into several items
+    yield out
+    for c in out.values():
+        B.ht_graph_destroy(c.g)
+
+
+def _mat(x):
+    return B.to_matrix(torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)), DEV)
+
+
+def _run(ctx, case, d_in, d_out, relu, seed, want_dhin=True, slope=0.2):
+    rng = np.random.default_rng(seed)
+    V = case.V
+    H = rng.standard_normal((V, d_in)).astype(np.float32)
+    W = (rng.standard_normal((d_in, d_out)) / np.sqrt(d_in)).astype(np.float32)
+    a_dst = (rng.standard_normal(d_out) / np.sqrt(d_out)).astype(np.float32)
+    a_src = (rng.standard_normal(d_out) / np.sqrt(d_out)).astype(np.float32)
+    dh = rng.standard_normal((V, d_out)).astype(np.float32)
+    act = B.HT_ACT_RELU if relu else B.HT_ACT_NONE
+    f = orc.gat_layer_fwd(case.indptr, case.col, H, W, a_dst, a_src, slope=slope, relu=relu)
+    Hd, Wd = _mat(H), torch.from_numpy(W).cuda()
+    ad, as_ = torch.from_numpy(a_dst).cuda(), torch.from_numpy(a_src).cuda()
+    H_out = B.alloc_matrix(V, d_out, DEV, zero=False)
+    B.ht_gat_layer_fwd(ctx, case.g, d_in, d_out, act, Hd, Wd, ad, as_, H_out, slope=slope)
+    assert_close(H_out.cpu().numpy()[:, :d_out], f["h"], "h_out")
+    # backward from the oracle's own forward result, so both sides mask the same elements
+    b = orc.gat_layer_bwd(case.indptr, case.col, H, W, a_dst, a_src, f, dh, slope=slope, relu=relu, want_dH=want_dhin)
+    dW = torch.empty(d_in, d_out, device="cuda")
+    dad, das = torch.empty(d_out, device="cuda"), torch.empty(d_out, device="cuda")
+    dH_in = B.alloc_matrix(V, d_in, DEV) if want_dhin else None
+    B.ht_gat_layer_bwd(ctx, case.g, d_in, d_out, act, Hd, Wd, ad, as_, _mat(f["h"]), _mat(dh), dW, dad, das, dH_in=dH_in,
+                       slope=slope)
+    assert_close(dW.cpu().numpy(), b["dW"], "dW")
+    assert_close(dad.cpu().numpy(), b["da_dst"], "da_dst")
+    assert_close(das.cpu().numpy(), b["da_src"], "da_src")
+    if want_dhin:
+        assert_close(dH_in.cpu().numpy()[:, :d_in], b["dH"], "dH_in")
+    return H_out, dW
+
+
+@pytest.mark.parametrize("d_in,d_out", [(16, 8), (64, 32), (100, 41), (130, 256), (48, 300), (24, 520)])
+def test_gat_widths(ctx, cases, d_in, d_out):
+    _run(ctx, cases["rmat"], d_in, d_out, True, seed=d_in + d_out)
+
+
+@pytest.mark.parametrize("name", ["multi", "hub"])
+@pytest.mark.parametrize("relu", [True, False])
+def test_gat_multigraph_and_hubs(ctx, cases, name, relu):
+    _run(ctx, cases[name], 72, 40, relu, seed=7)
+
+
+def test_gat_no_input_gradient_and_other_slope(ctx, cases):
+    _run(ctx, cases["multi"], 32, 64, True, seed=9, want_dhin=False, slope=0.05)
+
+
+def test_gat_zero_attention_is_the_neighbour_mean(ctx, cases):
+    c = cases["rmat"]
+    rng = np.random.default_rng(3)
+    H = rng.standard_normal((c.V, 24)).astype(np.float32)
+    W = np.eye(24, dtype=np.float32)
+    zero = torch.zeros(24, device="cuda")
+    H_out = B.alloc_matrix(c.V, 24, DEV, zero=False)
+    B.ht_gat_layer_fwd(ctx, c.g, 24, 24, B.HT_ACT_NONE, _mat(H), torch.from_numpy(W).cuda(), zero, zero, H_out)
+    deg = np.diff(c.indptr)
+    ref = np.add.reduceat(H.astype(np.float64)[c.col], c.indptr[:-1], axis=0) / deg[:, None]
+    assert_close(H_out.cpu().numpy()[:, :24], ref, "mean")
+
+
+def test_gat_deterministic(ctx, cases):
+    a = _run(ctx, cases["hub"], 40, 48, True, seed=5)
+    b = _run(ctx, cases["hub"], 40, 48, True, seed=5)
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+def test_gat_errors(ctx, cases):
+    c = cases["rmat"]
+    W = torch.zeros(16, 8, device="cuda")
+    v = torch.zeros(8, device="cuda")
+    with pytest.raises(B.HongtuError):      # host-resident input
+        B.ht_gat_layer_fwd(ctx, c.g, 16, 8, B.HT_ACT_NONE, B.alloc_matrix(c.V, 16, B.HT_LOC_HOST_PINNED), W, v, v,
+                           B.alloc_matrix(c.V, 8, DEV))
+    with pytest.raises(B.HongtuError):      # slope out of range
+        B.ht_gat_layer_fwd(ctx, c.g, 16, 8, B.HT_ACT_NONE, B.alloc_matrix(c.V, 16, DEV), W, v, v,
+                           B.alloc_matrix(c.V, 8, DEV), slope=2.0)
+    with pytest.raises(B.HongtuError):      # wrong row count
+        B.ht_gat_layer_fwd(ctx, c.g, 16, 8, B.HT_ACT_NONE, B.alloc_matrix(c.V - 1, 16, DEV), W, v, v,
+                           B.alloc_matrix(c.V, 8, DEV))
