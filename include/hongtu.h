@@ -290,6 +290,25 @@ int ht_gat_layer_bwd(ht_ctx *ctx, const ht_graph *g, const ht_gat_desc *desc, co
                      const ht_tensor *dH_out, ht_tensor *dH_in, float *dW, float *da_dst, float *da_src,
                      ht_stats *stats);
 
+typedef struct {
+  int32_t n_layers;    /* <= HT_MAX_LAYERS                                  */
+  int32_t reserved;
+  const int32_t *dims; /* host, n_layers + 1 widths                         */
+  float *const *W;     /* host arrays of n_layers device pointers, in/out   */
+  float *const *a_dst; /* [dims[l+1]] each                                  */
+  float *const *a_src;
+  float lr;
+  float slope;
+} ht_gat_model;
+
+/* Alg. 1 with GAT layers, every tensor in HBM: forward (ReLU between layers,
+ * none after the last), softmax cross-entropy over labelled vertices
+ * (labels[v] >= 0, device int32 [V]), backward with each layer's intermediates
+ * recomputed from its input, W -= lr dW and a -= lr da.  X [V x dims[0]] HBM.
+ * loss_out: host float, valid on return (the call synchronises). */
+int ht_gat_epoch(ht_ctx *ctx, const ht_graph *g, const ht_gat_model *model, const ht_tensor *X,
+                 const int32_t *labels, float *loss_out, ht_stats *stats);
+
 /* -------------------------------------------------------------------- epoch */
 
 enum { HT_RES_AUTO = 0, HT_RES_HBM = 1, HT_RES_HOST = 2 };

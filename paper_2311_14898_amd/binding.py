@@ -91,6 +91,12 @@ class ht_gat_desc(C.Structure):
     _fields_ = [("d_in", C.c_int32), ("d_out", C.c_int32), ("act", C.c_int32), ("slope", C.c_float)]
 
 
+class ht_gat_model(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("reserved", C.c_int32), ("dims", C.POINTER(C.c_int32)),
+                ("W", C.POINTER(C.c_void_p)), ("a_dst", C.POINTER(C.c_void_p)), ("a_src", C.POINTER(C.c_void_p)),
+                ("lr", C.c_float), ("slope", C.c_float)]
+
+
 class ht_plan_opts(C.Structure):
     _fields_ = [("res_h", C.c_int32), ("res_a", C.c_int32), ("res_g", C.c_int32), ("inter", C.c_int32),
                 ("gather_mode", C.c_int32), ("order", C.c_int32), ("hbm_budget_bytes", C.c_int64)]
@@ -99,7 +105,7 @@ class ht_plan_opts(C.Structure):
 EXPORTS = ["ht_ctx_create", "ht_ctx_destroy", "ht_sync", "ht_ctx_set_hbm_budget", "ht_strerror", "ht_last_error",
            "ht_partition", "ht_graph_destroy", "ht_graph_info_get", "ht_graph_chunk_info", "ht_graph_export_chunk",
            "ht_graph_export_csc", "ht_graph_chunk_order", "ht_layer_fwd", "ht_layer_bwd", "ht_epoch", "ht_epoch_buffer", "ht_tensor_to_host", "ht_memory_model",
-           "ht_chunk_rows_model", "ht_gat_layer_fwd", "ht_gat_layer_bwd"]
+           "ht_chunk_rows_model", "ht_gat_layer_fwd", "ht_gat_layer_bwd", "ht_gat_epoch"]
 
 _lib = None
 
@@ -152,6 +158,8 @@ def load():
     lib.ht_gat_layer_bwd.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(ht_gat_desc), C.POINTER(ht_tensor), C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.POINTER(ht_tensor), C.POINTER(ht_tensor),
                                      C.POINTER(ht_tensor), C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(ht_stats)]
+    lib.ht_gat_epoch.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(ht_gat_model), C.POINTER(ht_tensor), C.c_void_p,
+                                 C.POINTER(C.c_float), C.POINTER(ht_stats)]
     _lib = lib
     return lib
 
@@ -349,6 +357,28 @@ def ht_gat_layer_bwd(ctx, g, d_in: int, d_out: int, act: int, H_in: torch.Tensor
                                    C.byref(dhi) if dhi is not None else None, C.c_void_p(dW.data_ptr()),
                                    _vec(da_dst, d_out), _vec(da_src, d_out), C.byref(st) if st is not None else None), ctx)
     return st
+
+
+def ht_gat_epoch(ctx, g, dims: Sequence[int], Ws: List[torch.Tensor], a_dst: List[torch.Tensor], a_src: List[torch.Tensor],
+                 lr: float, X: torch.Tensor, labels: torch.Tensor, slope: float = 0.2, want_stats: bool = False):
+    """One GAT epoch in HBM; Ws, a_dst, a_src (device tensors) are updated in place.  Returns (loss, stats or None)."""
+    L = len(dims) - 1
+    assert len(Ws) == L and len(a_dst) == L and len(a_src) == L and labels.is_cuda and labels.dtype == torch.int32
+    for l in range(L):
+        assert Ws[l].is_cuda and Ws[l].is_contiguous() and tuple(Ws[l].shape) == (dims[l], dims[l + 1])
+        _vec(a_dst[l], dims[l + 1]), _vec(a_src[l], dims[l + 1])
+    dims_a = (C.c_int32 * (L + 1))(*dims)
+    Wp = (C.c_void_p * L)(*[w.data_ptr() for w in Ws])
+    Ap = (C.c_void_p * L)(*[a.data_ptr() for a in a_dst])
+    Sp = (C.c_void_p * L)(*[a.data_ptr() for a in a_src])
+    model = ht_gat_model(L, 0, dims_a, Wp, Ap, Sp, lr, slope)
+    x = tensor_view(X, dims[0])
+    loss = C.c_float(0.0)
+    st = ht_stats() if want_stats else None
+    torch.cuda.synchronize()
+    _check(load().ht_gat_epoch(ctx, g, C.byref(model), C.byref(x), C.c_void_p(labels.data_ptr()), C.byref(loss),
+                               C.byref(st) if st is not None else None), ctx)
+    return loss.value, st
 
 
 # -------------------------------------------------------------------- epoch

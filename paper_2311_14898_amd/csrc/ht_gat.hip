@@ -24,6 +24,7 @@
 // its coefficient is k times the single edge's.
 #include <algorithm>
 #include <chrono>
+#include <vector>
 
 #include "ht_internal.h"
 
@@ -401,24 +402,14 @@ int launch_src(ht_ctx* ctx, const GatPass& a, int nvec) {
   return HT_OK;
 }
 
-}  // namespace
-
-extern "C" {
-
-int ht_gat_layer_fwd(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const ht_tensor* H_in, const float* W,
-                     const float* a_dst, const float* a_src, ht_tensor* H_out, ht_stats* stats) {
-  if (!ctx) return HT_EINVAL;
-  if (!g || !desc || !H_in || !H_out || !W || !a_dst || !a_src) return ht_set_err(ctx, HT_EINVAL, "ht_gat_layer_fwd: null argument");
-  if (g->ctx != ctx) return ht_set_err(ctx, HT_ESTATE, "graph belongs to another context");
+int gat_fwd_impl(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const ht_tensor* H_in, const float* W,
+                 const float* a_dst, const float* a_src, ht_tensor* H_out, ht_stats* local) {
   HT_TRY(check_desc(ctx, desc));
   HT_TRY(check(ctx, g, desc, H_in, desc->d_in, "H_in"));
   HT_TRY(check(ctx, g, desc, H_out, desc->d_out, "H_out"));
-  HT_HIP(ctx, hipSetDevice(ctx->device));
-  auto t0 = std::chrono::steady_clock::now();
   hipStream_t st = ctx->stream;
-  ht_stats local{};
   GatWs ws{};
-  HT_TRY(prepare(ctx, g, desc, H_in, W, a_dst, a_src, false, &ws, &local));
+  HT_TRY(prepare(ctx, g, desc, H_in, W, a_dst, a_src, false, &ws, local));
   for (int j = 0; j < g->n; ++j) {
     const ChunkMeta& c = g->chunks[j];
     if (c.dst1 == c.dst0) continue;
@@ -437,35 +428,23 @@ int ht_gat_layer_fwd(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, co
     a.relu = desc->act == HT_ACT_RELU;
     a.partial = partial;
     HT_TRY(ht_spmm_launch(ctx, st, a));
-    local.n_spmm_fwd += 1;
-    local.edges += c.nnz;
-  }
-  HT_HIP(ctx, hipStreamSynchronize(st));
-  if (stats) {
-    local.t_total_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
-    *stats = local;
+    local->n_spmm_fwd += 1;
+    local->edges += c.nnz;
   }
   return HT_OK;
 }
 
-int ht_gat_layer_bwd(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const ht_tensor* H_in, const float* W,
-                     const float* a_dst, const float* a_src, const ht_tensor* H_out, const ht_tensor* dH_out,
-                     ht_tensor* dH_in, float* dW, float* da_dst, float* da_src, ht_stats* stats) {
-  if (!ctx) return HT_EINVAL;
-  if (!g || !desc || !H_in || !H_out || !dH_out || !W || !a_dst || !a_src || !dW || !da_dst || !da_src)
-    return ht_set_err(ctx, HT_EINVAL, "ht_gat_layer_bwd: null argument");
-  if (g->ctx != ctx) return ht_set_err(ctx, HT_ESTATE, "graph belongs to another context");
+int gat_bwd_impl(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const ht_tensor* H_in, const float* W,
+                 const float* a_dst, const float* a_src, const ht_tensor* H_out, const ht_tensor* dH_out,
+                 ht_tensor* dH_in, float* dW, float* da_dst, float* da_src, ht_stats* local) {
   HT_TRY(check_desc(ctx, desc));
   HT_TRY(check(ctx, g, desc, H_in, desc->d_in, "H_in"));
   HT_TRY(check(ctx, g, desc, H_out, desc->d_out, "H_out"));
   HT_TRY(check(ctx, g, desc, dH_out, desc->d_out, "dH_out"));
   if (dH_in) HT_TRY(check(ctx, g, desc, dH_in, desc->d_in, "dH_in"));
-  HT_HIP(ctx, hipSetDevice(ctx->device));
-  auto t0 = std::chrono::steady_clock::now();
   hipStream_t st = ctx->stream;
-  ht_stats local{};
   GatWs ws{};
-  HT_TRY(prepare(ctx, g, desc, H_in, W, a_dst, a_src, true, &ws, &local));
+  HT_TRY(prepare(ctx, g, desc, H_in, W, a_dst, a_src, true, &ws, local));
   const int d = desc->d_out;
   const int nvec = (d + 3) / 4;
   const int sc_col = (int)ws.ld_t;              // the scalar column block sits behind the padded data columns
@@ -522,8 +501,8 @@ int ht_gat_layer_bwd(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, co
       f.partial = partial;
       HT_TRY(ht_spmm_fix_launch(ctx, st, f));
     }
-    local.n_spmm_bwd += 2;
-    local.edges += 2 * c.nnz;
+    local->n_spmm_bwd += 2;
+    local->edges += 2 * c.nnz;
   }
   if (g->V > 0) {
     k_gat_finish<<<(unsigned)((g->V + 3) / 4), 256, 0, st>>>(dT, ld_dt, d, sc_col, ws.dp, a_dst, a_src, g->V, ws.pq4);
@@ -538,8 +517,8 @@ int ht_gat_layer_bwd(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, co
     HT_TRY(ht_gemm_tn(ctx, st, H_in->ptr + r0 * H_in->ld, H_in->ld, dT + r0 * ld_dt, ld_dt, dW, nr, desc->d_in, d, first ? 0 : 1));
     if (dH_in)
       HT_TRY(ht_gemm_nt(ctx, st, dT + r0 * ld_dt, ld_dt, W, dH_in->ptr + r0 * dH_in->ld, dH_in->ld, nr, d, desc->d_in, 1));
-    local.n_gemm += 3;
-    local.gemm_flops += 4.0 * nr * desc->d_in * d;
+    local->n_gemm += 3;
+    local->gemm_flops += 4.0 * nr * desc->d_in * d;
     first = false;
   }
   if (first) {
@@ -548,6 +527,127 @@ int ht_gat_layer_bwd(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, co
   }
   k_gat_split<<<(unsigned)((d + 255) / 256), 256, 0, st>>>(da4, d, da_dst, da_src);
   HT_LAUNCH_CHECK(ctx);
+  return HT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ht_gat_layer_fwd(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const ht_tensor* H_in, const float* W,
+                     const float* a_dst, const float* a_src, ht_tensor* H_out, ht_stats* stats) {
+  if (!ctx) return HT_EINVAL;
+  if (!g || !desc || !H_in || !H_out || !W || !a_dst || !a_src) return ht_set_err(ctx, HT_EINVAL, "ht_gat_layer_fwd: null argument");
+  if (g->ctx != ctx) return ht_set_err(ctx, HT_ESTATE, "graph belongs to another context");
+  HT_HIP(ctx, hipSetDevice(ctx->device));
+  auto t0 = std::chrono::steady_clock::now();
+  ht_stats local{};
+  int rc = gat_fwd_impl(ctx, g, desc, H_in, W, a_dst, a_src, H_out, &local);
+  hipError_t e = hipStreamSynchronize(ctx->stream);
+  if (rc != HT_OK) return rc;
+  HT_HIP(ctx, e);
+  if (stats) {
+    local.t_total_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+    *stats = local;
+  }
+  return HT_OK;
+}
+
+int ht_gat_layer_bwd(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const ht_tensor* H_in, const float* W,
+                     const float* a_dst, const float* a_src, const ht_tensor* H_out, const ht_tensor* dH_out,
+                     ht_tensor* dH_in, float* dW, float* da_dst, float* da_src, ht_stats* stats) {
+  if (!ctx) return HT_EINVAL;
+  if (!g || !desc || !H_in || !H_out || !dH_out || !W || !a_dst || !a_src || !dW || !da_dst || !da_src)
+    return ht_set_err(ctx, HT_EINVAL, "ht_gat_layer_bwd: null argument");
+  if (g->ctx != ctx) return ht_set_err(ctx, HT_ESTATE, "graph belongs to another context");
+  HT_HIP(ctx, hipSetDevice(ctx->device));
+  auto t0 = std::chrono::steady_clock::now();
+  ht_stats local{};
+  int rc = gat_bwd_impl(ctx, g, desc, H_in, W, a_dst, a_src, H_out, dH_out, dH_in, dW, da_dst, da_src, &local);
+  hipError_t e = hipStreamSynchronize(ctx->stream);
+  if (rc != HT_OK) return rc;
+  HT_HIP(ctx, e);
+  if (stats) {
+    local.t_total_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+    *stats = local;
+  }
+  return HT_OK;
+}
+
+// Alg. 1 with GAT layers, everything in HBM: forward over the layers (only the layer outputs
+// are kept), softmax cross-entropy on the labelled vertices, backward layer by layer with
+// every layer's intermediates recomputed from its input, SGD step on W^l and a^l.
+int ht_gat_epoch(ht_ctx* ctx, const ht_graph* g, const ht_gat_model* model, const ht_tensor* X, const int32_t* labels,
+                 float* loss_out, ht_stats* stats) {
+  if (!ctx) return HT_EINVAL;
+  if (!g || !model || !X || !labels || !loss_out) return ht_set_err(ctx, HT_EINVAL, "ht_gat_epoch: null argument");
+  if (g->ctx != ctx) return ht_set_err(ctx, HT_ESTATE, "graph belongs to another context");
+  const int L = model->n_layers;
+  if (L < 1 || L > HT_MAX_LAYERS || !model->dims || !model->W || !model->a_dst || !model->a_src)
+    return ht_set_err(ctx, HT_EINVAL, "ht_gat_epoch: bad model");
+  for (int l = 0; l <= L; ++l)
+    if (model->dims[l] <= 0) return ht_set_err(ctx, HT_ESHAPE, "ht_gat_epoch: layer widths must be positive");
+  for (int l = 0; l < L; ++l)
+    if (!model->W[l] || !model->a_dst[l] || !model->a_src[l]) return ht_set_err(ctx, HT_EINVAL, "ht_gat_epoch: null parameter of layer %d", l);
+  HT_HIP(ctx, hipSetDevice(ctx->device));
+  auto t0 = std::chrono::steady_clock::now();
+  hipStream_t st = ctx->stream;
+  const int64_t V = g->V;
+  // workspace: h^1..h^L, grad h^1..grad h^L, then dW^l, da_dst^l, da_src^l, loss
+  size_t floats = 64 + 64 * (size_t)L;
+  for (int l = 1; l <= L; ++l) floats += 2 * (size_t)std::max<int64_t>(V, 1) * ht_row_pitch(model->dims[l], true);
+  for (int l = 0; l < L; ++l) floats += (size_t)model->dims[l] * model->dims[l + 1] + 2 * (size_t)model->dims[l + 1] + 96;
+  float* base = nullptr;
+  HT_TRY(ht_scratch(ctx, HT_S_GATWS, floats * 4, (void**)&base));
+  std::vector<ht_tensor> h(L + 1), gh(L + 1);
+  std::vector<float*> dW(L), dad(L), das(L);
+  float* cur = base;
+  auto take = [&](size_t n) { float* p = cur; cur += (n + 31) & ~(size_t)31; return p; };
+  for (int l = 1; l <= L; ++l) {
+    const int64_t ld = ht_row_pitch(model->dims[l], true);
+    h[l] = ht_tensor{take((size_t)std::max<int64_t>(V, 1) * ld), V, model->dims[l], ld, HT_LOC_DEVICE};
+    gh[l] = ht_tensor{take((size_t)std::max<int64_t>(V, 1) * ld), V, model->dims[l], ld, HT_LOC_DEVICE};
+  }
+  for (int l = 0; l < L; ++l) {
+    dW[l] = take((size_t)model->dims[l] * model->dims[l + 1]);
+    dad[l] = take(model->dims[l + 1]);
+    das[l] = take(model->dims[l + 1]);
+  }
+  float* loss_dev = take(4);
+  ht_stats local{};
+  auto fail = [&](int rc) {
+    (void)hipStreamSynchronize(st);
+    return rc;
+  };
+  for (int l = 0; l < L; ++l) {
+    ht_gat_desc d{model->dims[l], model->dims[l + 1], l < L - 1 ? HT_ACT_RELU : HT_ACT_NONE, model->slope};
+    int rc = gat_fwd_impl(ctx, g, &d, l == 0 ? X : &h[l], model->W[l], model->a_dst[l], model->a_src[l], &h[l + 1], &local);
+    if (rc != HT_OK) return fail(rc);
+  }
+  {
+    int rc = ht_softmax_ce(ctx, st, h[L].ptr, h[L].ld, labels, V, model->dims[L], gh[L].ptr, gh[L].ld, loss_dev);
+    if (rc != HT_OK) return fail(rc);
+  }
+  for (int l = L - 1; l >= 0; --l) {
+    ht_gat_desc d{model->dims[l], model->dims[l + 1], l < L - 1 ? HT_ACT_RELU : HT_ACT_NONE, model->slope};
+    if (l > 0) {
+      int rc = ht_fill_zero(ctx, st, gh[l].ptr, (size_t)V * gh[l].ld * 4);
+      if (rc != HT_OK) return fail(rc);
+    }
+    int rc = gat_bwd_impl(ctx, g, &d, l == 0 ? X : &h[l], model->W[l], model->a_dst[l], model->a_src[l], &h[l + 1], &gh[l + 1],
+                          l > 0 ? &gh[l] : nullptr, dW[l], dad[l], das[l], &local);
+    if (rc != HT_OK) return fail(rc);
+  }
+  for (int l = 0; l < L; ++l) {
+    int rc = ht_sgd(ctx, st, model->W[l], dW[l], (int64_t)model->dims[l] * model->dims[l + 1], model->lr);
+    if (rc == HT_OK) rc = ht_sgd(ctx, st, model->a_dst[l], dad[l], model->dims[l + 1], model->lr);
+    if (rc == HT_OK) rc = ht_sgd(ctx, st, model->a_src[l], das[l], model->dims[l + 1], model->lr);
+    if (rc != HT_OK) return fail(rc);
+  }
+  {
+    hipError_t e = hipMemcpyAsync(loss_out, loss_dev, 4, hipMemcpyDeviceToHost, st);
+    if (e != hipSuccess) return fail(ht_set_err(ctx, HT_EHIP, "loss copy: %s", hipGetErrorString(e)));
+  }
   HT_HIP(ctx, hipStreamSynchronize(st));
   if (stats) {
     local.t_total_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();

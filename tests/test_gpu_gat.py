@@ -110,6 +110,44 @@ def test_gat_deterministic(ctx, cases):
     assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
 
 
+def test_gat_epoch(ctx, cases):
+    """Alg. 1 with two GAT layers against the oracle's layer functions composed in the same order."""
+    c = cases["multi"]
+    V, dims, lr = c.V, [40, 24, 7], 20.0         # a large step, so that the updated parameters expose the gradients
+    rng = np.random.default_rng(12)
+    X = rng.standard_normal((V, dims[0])).astype(np.float32)
+    y = rng.integers(0, dims[-1], V).astype(np.int32)
+    y[rng.random(V) < 0.3] = -1
+    Ws = [(rng.standard_normal((dims[l], dims[l + 1])) / np.sqrt(dims[l])).astype(np.float32) for l in range(2)]
+    ad = [(rng.standard_normal(dims[l + 1]) / np.sqrt(dims[l + 1])).astype(np.float32) for l in range(2)]
+    as_ = [(rng.standard_normal(dims[l + 1]) / np.sqrt(dims[l + 1])).astype(np.float32) for l in range(2)]
+    # oracle
+    f0 = orc.gat_layer_fwd(c.indptr, c.col, X, Ws[0], ad[0], as_[0], relu=True)
+    f1 = orc.gat_layer_fwd(c.indptr, c.col, f0["h"], Ws[1], ad[1], as_[1], relu=False)
+    assert np.abs(f0["z"]).min() > 1e-7        # same ReLU decisions on both sides
+    loss_ref, g2 = orc.softmax_ce(f1["h"], y)
+    b1 = orc.gat_layer_bwd(c.indptr, c.col, f0["h"], Ws[1], ad[1], as_[1], f1, g2, relu=False)
+    b0 = orc.gat_layer_bwd(c.indptr, c.col, X, Ws[0], ad[0], as_[0], f0, b1["dH"], relu=True, want_dH=False)
+    # device
+    Wd = [torch.from_numpy(w).cuda() for w in Ws]
+    add = [torch.from_numpy(a).cuda() for a in ad]
+    asd = [torch.from_numpy(a).cuda() for a in as_]
+    loss, st = B.ht_gat_epoch(ctx, c.g, dims, Wd, add, asd, lr, _mat(X), torch.from_numpy(y).cuda(), want_stats=True)
+    assert abs(loss - loss_ref) <= 1e-4 * abs(loss_ref)
+    for l, b in ((0, b0), (1, b1)):
+        assert_close(Wd[l].cpu().numpy(), Ws[l].astype(np.float64) - lr * b["dW"], f"W^{l} after the step")
+        assert_close(add[l].cpu().numpy(), ad[l].astype(np.float64) - lr * b["da_dst"], f"a_dst^{l} after the step")
+        assert_close(asd[l].cpu().numpy(), as_[l].astype(np.float64) - lr * b["da_src"], f"a_src^{l} after the step")
+        assert np.abs(lr * b["dW"]).max() > 0.05 * np.abs(Ws[l]).max()      # the step is visible at the tolerance
+    assert st.edges == len(c.col) * (2 + 4)     # 2 forward aggregations, 2 x 2 backward passes
+    # small steps from the same start: the loss goes down
+    Wd = [torch.from_numpy(w).cuda() for w in Ws]
+    add = [torch.from_numpy(a).cuda() for a in ad]
+    asd = [torch.from_numpy(a).cuda() for a in as_]
+    losses = [B.ht_gat_epoch(ctx, c.g, dims, Wd, add, asd, 0.05, _mat(X), torch.from_numpy(y).cuda())[0] for _ in range(3)]
+    assert losses[0] == loss and losses[2] < losses[1] < losses[0]
+
+
 def test_gat_errors(ctx, cases):
     c = cases["rmat"]
     W = torch.zeros(16, 8, device="cuda")
