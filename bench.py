@@ -76,6 +76,70 @@ def cpu_baseline(w, src_cpu, dst_cpu, X, y, Ws):
                       f"epoch by flop count ({ef / sample_flops:.1f}x)", "sample_seconds": t}
 
 
+def gat_epoch_flops(w):
+    V, dims, L, Ep = w.V, w.dims, w.n_layers, w.E + w.V
+    f = 0.0
+    for l in range(L):
+        f += 2.0 * 2.0 * V * dims[l] * dims[l + 1]            # t = H W, forward and recomputed
+        f += 2.0 * dims[l + 1] * Ep * (1 + 2 * 2)             # weighted sum forward; two backward passes (dot + sum each)
+        f += 2.0 * V * dims[l] * dims[l + 1] * (2 if l > 0 else 1)    # dW, dH
+    return f
+
+
+def main_gat(args):
+    """GAT (Eq. 3, one head per layer) on the same workload: epochs of ht_gat_epoch, everything in HBM."""
+    import numpy as np
+    import torch
+    from paper_2311_14898_amd import binding as B
+    from paper_2311_14898_amd import inputs
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    w = inputs.WORKLOADS[args.workload].scaled(args.scale)
+    src, dst = inputs.rmat_edges(w.V, w.E, w.graph_seed, device="cuda")
+    X = inputs.features(w.V, w.dims[0])
+    y = inputs.labels(w.V, w.dims[-1], labelled_one_in=w.labelled_one_in)
+    Ws = inputs.glorot_weights(w.dims)
+    a_dst, a_src = inputs.attention_vectors(w.dims)
+    ctx = B.ht_ctx_create(0)
+    g = B.ht_partition(ctx, w.V, src, dst, w.n_chunks)
+    info = B.ht_graph_info_get(g)
+    Xd, yd = B.to_matrix(X, B.HT_LOC_DEVICE), y.cuda()
+    Wd, ad, asd = [x.clone().cuda() for x in Ws], [x.clone().cuda() for x in a_dst], [x.clone().cuda() for x in a_src]
+    for _ in range(args.warmup):
+        B.ht_gat_epoch(ctx, g, w.dims, Wd, ad, asd, w.lr, Xd, yd)
+    torch.cuda.synchronize()
+    tot = None
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        loss, st = B.ht_gat_epoch(ctx, g, w.dims, Wd, ad, asd, w.lr, Xd, yd, want_stats=True)
+        d = st.as_dict()
+        if tot is None:
+            tot = d
+        else:
+            for k, v in d.items():
+                tot[k] = [a + b for a, b in zip(tot[k], v)] if isinstance(v, list) else tot[k] + v
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    L, Ep, K = w.n_layers, info.E_stored, args.steps
+    # dominant kernel: the source pass of the widest layer output gathers one row of dz per distinct pair
+    src_ms = tot["t_gat_src_ms"] / K
+    out = {"metric": "GAT full-graph epoch time (s), 1xMI355X", "value": elapsed / K, "unit": "s", "n_gpus": 1, "steps": K,
+           "warmup": args.warmup, "ms_per_step": 1e3 * elapsed / K, "higher_is_better": False, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"{w.name}: {L}-layer GAT (one head), R-MAT V={w.V} E={w.E} (+{w.V} self-loops), dims "
+                                  f"{'-'.join(map(str, w.dims))}, {w.n_chunks} chunks, vertex data in HBM", "scale": args.scale},
+           "loss": loss, "gteps": tot["edges"] / elapsed / 1e9,
+           "phase_ms_per_step": {"softmax": tot["t_gat_softmax_ms"] / K, "aggregate_fwd": tot["t_spmm_fwd_ms"] / K,
+                                 "destination_pass": tot["t_gat_dst_ms"] / K, "source_pass": src_ms,
+                                 "gemm": tot["t_gemm_ms"] / K, "loss": tot["t_loss_ms"] / K},
+           "agg_fwd_layer_ms_per_step": [x / K for x in tot["t_agg_fwd_layer_ms"][:L]],
+           "gemm_tflops": tot["gemm_flops"] / max(tot["t_gemm_ms"] * 1e-3, 1e-12) / 1e12,
+           "epoch_gflop": gat_epoch_flops(w) / 1e9,
+           "paper_context": "HongTu-IM 2-layer GAT on reddit (same shape), 1xA100, Table 4; other hardware, real dataset"}
+    B.ht_graph_destroy(g)
+    B.ht_ctx_destroy(ctx)
+    print(json.dumps(out))
+
+
 def read_traffic(name):
     """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter summary."""
     path = os.path.join(ROOT, "profiles", name)
@@ -100,6 +164,8 @@ def main():
     ap.add_argument("--cache", choices=["adjacent", "all"], default="adjacent",
                     help="neighbour-row buffer: reuse between adjacent chunks only, or keep every row once loaded")
     ap.add_argument("--reorder", action="store_true", help="greedy max-overlap chunk schedule (Alg. 4, phase 2)")
+    ap.add_argument("--model", choices=["gcn", "gat"], default="gcn", help="gcn: the benchmark; gat: the attention model "
+                    "on the same workload (its own JSON line, HBM-resident workloads only)")
     ap.add_argument("--order", choices=["paper", "auto"], default="paper",
                     help="stage order of a layer: aggregate then transform as Eq. 2 prints it (the timed default), or "
                          "transform first in the layers that get narrower (same function, fewer bytes aggregated)")
@@ -111,6 +177,9 @@ def main():
         print("bench.py: this build runs on ONE GPU (the data-parallel hot path of one partition); "
               "--gpus N with N > 1 is not supported", file=sys.stderr)
         sys.exit(2)
+
+    if args.model == "gat":
+        return main_gat(args)
 
     import numpy as np
     import torch

@@ -228,6 +228,8 @@ typedef struct {
   double agg_fwd_layer_alg_bytes[HT_MAX_LAYERS];
   int64_t n_agg_fwd_layer[HT_MAX_LAYERS];
   double t_agg_fix_ms;
+  /* GAT layers: neighbour softmax, destination pass, source pass (with its partial-row pass) */
+  double t_gat_softmax_ms, t_gat_dst_ms, t_gat_src_ms;
 } ht_stats;
 
 /* Forward of one layer over all chunks in schedule order:

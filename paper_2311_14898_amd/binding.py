@@ -72,7 +72,8 @@ class ht_stats(C.Structure):
                 ("spmm_bwd_alg_bytes", C.c_double), ("gemm_flops", C.c_double),
                 ("t_agg_fwd_layer_ms", C.c_double * HT_MAX_LAYERS),
                 ("agg_fwd_layer_alg_bytes", C.c_double * HT_MAX_LAYERS),
-                ("n_agg_fwd_layer", C.c_int64 * HT_MAX_LAYERS), ("t_agg_fix_ms", C.c_double)]
+                ("n_agg_fwd_layer", C.c_int64 * HT_MAX_LAYERS), ("t_agg_fix_ms", C.c_double),
+                ("t_gat_softmax_ms", C.c_double), ("t_gat_dst_ms", C.c_double), ("t_gat_src_ms", C.c_double)]
 
     def as_dict(self):
         out = {}

@@ -42,11 +42,27 @@ __device__ __forceinline__ float wave_max(float x) {
   for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
   return x;
 }
+// Sums of four values over the wave at once: the first two exchange steps fold the four inputs
+// into one register (a quarter of the wave per input), four more finish the quarters.
+__device__ __forceinline__ void wave_sum4(const float d[4], float r[4]) {
+  const int lane = threadIdx.x & 63;
+  const bool h32 = (lane & 32) != 0, h16 = (lane & 16) != 0;
+  const float a = (h32 ? d[1] : d[0]) + __shfl_xor(h32 ? d[0] : d[1], 32, 64);
+  const float b = (h32 ? d[3] : d[2]) + __shfl_xor(h32 ? d[2] : d[3], 32, 64);
+  float c = (h16 ? b : a) + __shfl_xor(h16 ? a : b, 16, 64);
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) c += __shfl_xor(c, o, 64);
+  r[0] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(c), 0));
+  r[1] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(c), 32));
+  r[2] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(c), 16));
+  r[3] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(c), 48));
+}
 __device__ __forceinline__ float lrelu(float y, float slope) { return y > 0.f ? y : slope * y; }
 // coefficient of one entry; the same expression in every kernel, so the forward, the
 // destination pass and the source pass of a chunk see identical values
 __device__ __forceinline__ float coef(float y, float slope, float m, float zinv, float mult) {
-  return mult * expf(lrelu(y, slope) - m) * zinv;
+  const float x = lrelu(y, slope);
+  return mult * expf(x - m) * zinv;
 }
 
 // p[v] = a_dst . T[v], q[v] = a_src . T[v]; a wave per vertex
@@ -70,30 +86,70 @@ __global__ void __launch_bounds__(256) k_gat_pq(const float* __restrict__ T, int
   }
 }
 
-// Neighbour softmax of the rows of one chunk: row maximum m, 1 / sum, and the
-// coefficient of every entry (in destination order).  A wave per row.
-__global__ void __launch_bounds__(256) k_gat_softmax(const int64_t* __restrict__ rowptr, int64_t e_base, int64_t ndst,
-                                                     const int32_t* __restrict__ col, const float* __restrict__ mult,
-                                                     const float* __restrict__ p_chunk, const float* __restrict__ q,
-                                                     float slope, float* __restrict__ w, float* __restrict__ m_chunk,
-                                                     float* __restrict__ zinv_chunk) {
-  const int lane = threadIdx.x & 63;
-  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (r >= ndst) return;
-  const int64_t e0 = rowptr[r] - e_base, e1 = rowptr[r + 1] - e_base;
+// Neighbour softmax of the rows of one chunk in three steps over the work items (a wave per
+// item, so a hub row is shared by many waves):
+//   1. per item: the scores x_e (kept in w[]), their maximum m_i and s_i = sum mult_e exp(x_e - m_i);
+//   2. per row cut into several items: m_v = max m_i, Z_v = sum s_i exp(m_i - m_v), in item order;
+//   3. per item: w_e = mult_e exp(x_e - m_v) / Z_v.
+__global__ void __launch_bounds__(256) k_gat_scores(const int32_t* __restrict__ it_row, const int64_t* __restrict__ it_e0,
+                                                    const int32_t* __restrict__ it_len, const int32_t* __restrict__ it_part,
+                                                    int64_t n_items, const int32_t* __restrict__ col,
+                                                    const float* __restrict__ mult, const float* __restrict__ p_chunk,
+                                                    const float* __restrict__ q, float slope, float* __restrict__ w,
+                                                    float* __restrict__ m_chunk, float* __restrict__ zinv_chunk,
+                                                    float* __restrict__ part_m, float* __restrict__ part_s) {
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t t = (int64_t)blockIdx.x * 4 + wave;
+  if (t >= n_items) return;
+  const int32_t r = it_row[t], len = it_len[t], part = it_part[t];
+  const int64_t e0 = it_e0[t];
   const float pv = p_chunk[r];
   float m = -3.0e38f;
-  for (int64_t e = e0 + lane; e < e1; e += 64) m = fmaxf(m, lrelu(pv + q[col[e]], slope));
+  for (int32_t k = lane; k < len; k += 64) {
+    const float x = lrelu(pv + q[col[e0 + k]], slope);
+    w[e0 + k] = x;
+    m = fmaxf(m, x);
+  }
   m = wave_max(m);
   float s = 0.f;
-  for (int64_t e = e0 + lane; e < e1; e += 64) s += (mult ? mult[e] : 1.f) * expf(lrelu(pv + q[col[e]], slope) - m);
+  for (int32_t k = lane; k < len; k += 64) s += (mult ? mult[e0 + k] : 1.f) * expf(w[e0 + k] - m);
   s = wave_sum(s);
-  const float zinv = s > 0.f ? 1.f / s : 0.f;
-  for (int64_t e = e0 + lane; e < e1; e += 64) w[e] = coef(pv + q[col[e]], slope, m, zinv, mult ? mult[e] : 1.f);
   if (lane == 0) {
-    m_chunk[r] = m;
-    zinv_chunk[r] = zinv;
+    if (part >= 0) {
+      part_m[part] = m;
+      part_s[part] = s;
+    } else {
+      m_chunk[r] = m;
+      zinv_chunk[r] = s > 0.f ? 1.f / s : 0.f;
+    }
   }
+}
+
+__global__ void k_gat_rowstats(const int32_t* __restrict__ fx_row, const int32_t* __restrict__ fx_part0,
+                               const int32_t* __restrict__ fx_nseg, int64_t n_fix, const float* __restrict__ part_m,
+                               const float* __restrict__ part_s, float* __restrict__ m_chunk, float* __restrict__ zinv_chunk) {
+  const int64_t f = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (f >= n_fix) return;
+  const int32_t p0 = fx_part0[f], ns = fx_nseg[f];
+  float m = -3.0e38f;
+  for (int32_t k = 0; k < ns; ++k) m = fmaxf(m, part_m[p0 + k]);
+  float s = 0.f;
+  for (int32_t k = 0; k < ns; ++k) s += part_s[p0 + k] * expf(part_m[p0 + k] - m);
+  m_chunk[fx_row[f]] = m;
+  zinv_chunk[fx_row[f]] = s > 0.f ? 1.f / s : 0.f;
+}
+
+__global__ void __launch_bounds__(256) k_gat_coefs(const int32_t* __restrict__ it_row, const int64_t* __restrict__ it_e0,
+                                                   const int32_t* __restrict__ it_len, int64_t n_items,
+                                                   const float* __restrict__ mult, const float* __restrict__ m_chunk,
+                                                   const float* __restrict__ zinv_chunk, float* __restrict__ w) {
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t t = (int64_t)blockIdx.x * 4 + wave;
+  if (t >= n_items) return;
+  const int32_t r = it_row[t], len = it_len[t];
+  const int64_t e0 = it_e0[t];
+  const float m = m_chunk[r], zinv = zinv_chunk[r];
+  for (int32_t k = lane; k < len; k += 64) w[e0 + k] = (mult ? mult[e0 + k] : 1.f) * expf(w[e0 + k] - m) * zinv;
 }
 
 // dz = dh * [h > 0] (or dh), pad columns zero, and S_v = dz_v . h_v; a wave per row of the chunk
@@ -187,17 +243,74 @@ __global__ void __launch_bounds__(256) k_gat_dst(GatPass a) {
         }
         dot[u] = s;
       }
+      float da[4];
+      wave_sum4(dot, da);
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        const float da = wave_sum(dot[u]);
         if (k + u < nh) {
           const float w = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_w), k + u));
           const float y = pv + __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_q), k + u));
-          acc += w * (da - Sv) * (y > 0.f ? 1.f : a.slope);
+          acc += w * (da[u] - Sv) * (y > 0.f ? 1.f : a.slope);
         }
       }
     }
   }
+  if (lane == 0) {
+    if (part >= 0) a.spart[part] = acc;
+    else a.dp_chunk[r] = acc;
+  }
+}
+
+// The same pass for rows of at most G float4: the wave splits into 64 / G lane groups that
+// take interleaved entries; a group's partial results are added in group order at the end.
+template <int G>
+__global__ void __launch_bounds__(256) k_gat_dst_g(GatPass a) {
+  constexpr int NG = 64 / G;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t t = (int64_t)blockIdx.x * 4 + wave;
+  if (t >= a.n_items) return;
+  const int32_t r = a.it_row[t];
+  const int64_t e0 = a.it_e0[t];
+  const int32_t len = a.it_len[t], part = a.it_part[t];
+  const int grp = lane / G, c4 = (lane % G) * 4;
+  const bool has = c4 < a.d;
+  const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+  const float4 mine = has ? ld4(a.own + (int64_t)r * a.own_ld + c4) : zero;
+  const float pv = a.p[a.dst0 + r], Sv = a.S[r];
+  float acc = 0.f;
+  for (int32_t base = 0; base < len; base += 64) {
+    const int32_t nh = (len - base) < 64 ? (len - base) : 64;
+    int32_t my_u = 0;
+    float my_w = 0.f, my_q = 0.f;
+    if (lane < nh) {
+      my_u = a.idx[e0 + base + lane];
+      my_w = a.w[e0 + base + lane];
+      my_q = a.q[my_u];
+    }
+    for (int32_t k = 0; k < nh; k += 4 * NG) {
+      float dot[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int ent = k + u * NG + grp;
+        const int kc = ent < nh ? ent : (nh - 1);
+        const int32_t c = __shfl(my_u, kc, 64);
+        const float4 x = has ? ld4(a.mat + (int64_t)c * a.mat_ld + c4) : zero;
+        dot[u] = fmaf(mine.x, x.x, fmaf(mine.y, x.y, fmaf(mine.z, x.z, mine.w * x.w)));
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+#pragma unroll
+        for (int o = G / 2; o > 0; o >>= 1) dot[u] += __shfl_xor(dot[u], o, 64);
+        const int ent = k + u * NG + grp;
+        const int kc = ent < nh ? ent : (nh - 1);
+        const float w = __shfl(my_w, kc, 64);
+        const float y = pv + __shfl(my_q, kc, 64);
+        if (ent < nh) acc += w * (dot[u] - Sv) * (y > 0.f ? 1.f : a.slope);
+      }
+    }
+  }
+#pragma unroll
+  for (int o = G; o < 64; o <<= 1) acc += __shfl_xor(acc, o, 64);
   if (lane == 0) {
     if (part >= 0) a.spart[part] = acc;
     else a.dp_chunk[r] = acc;
@@ -264,14 +377,15 @@ __global__ void __launch_bounds__(256) k_gat_src(GatPass a) {
         }
         dot[u] = s;
       }
+      float da[4];
+      wave_sum4(dot, da);
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        const float da = wave_sum(dot[u]);
         if (k + u < nh) {
           const float w = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_c), k + u));
           const float f = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_f), k + u));
           const float Sv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_S), k + u));
-          accq += w * (da - Sv) * f;
+          accq += w * (da[u] - Sv) * f;
 #pragma unroll
           for (int j = 0; j < VPL; ++j) {
             acc[j].x = fmaf(w, x[u][j].x, acc[j].x);
@@ -297,6 +411,87 @@ __global__ void __launch_bounds__(256) k_gat_src(GatPass a) {
   }
   if (lane == 0) {
     // the scalar travels in its own float4 column block behind the data columns
+    float4 sc = make_float4(accq, 0.f, 0.f, 0.f);
+    if (part < 0) sc.x += row[a.sc_col];
+    st4(row + a.sc_col, sc);
+  }
+}
+
+template <int G>
+__global__ void __launch_bounds__(256) k_gat_src_g(GatPass a) {
+  constexpr int NG = 64 / G;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t t = (int64_t)blockIdx.x * 4 + wave;
+  if (t >= a.n_items) return;
+  const int32_t r = a.it_row[t];
+  const int64_t e0 = a.it_e0[t];
+  const int32_t len = a.it_len[t], part = a.it_part[t];
+  const int32_t u_id = a.own_idx[r];
+  const int grp = lane / G, c4 = (lane % G) * 4;
+  const bool has = c4 < a.d;
+  const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+  const float4 mine = has ? ld4(a.own + (int64_t)u_id * a.own_ld + c4) : zero;
+  float4 acc = zero;
+  const float qu = a.q[u_id];
+  float accq = 0.f;
+  for (int32_t base = 0; base < len; base += 64) {
+    const int32_t nh = (len - base) < 64 ? (len - base) : 64;
+    int32_t my_v = 0;
+    float my_c = 0.f, my_f = 0.f, my_S = 0.f;
+    if (lane < nh) {
+      my_v = a.idx[e0 + base + lane];
+      const int64_t v = a.dst0 + my_v;
+      const float y = a.p[v] + qu;
+      my_c = coef(y, a.slope, a.m[v], a.zinv[v], a.mult ? a.mult[e0 + base + lane] : 1.f);
+      my_f = y > 0.f ? 1.f : a.slope;
+      my_S = a.S[my_v];
+    }
+    for (int32_t k = 0; k < nh; k += 4 * NG) {
+      float4 x[4];
+      float dot[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int ent = k + u * NG + grp;
+        const int kc = ent < nh ? ent : (nh - 1);
+        const int32_t c = __shfl(my_v, kc, 64);
+        x[u] = has ? ld4(a.mat + (int64_t)c * a.mat_ld + c4) : zero;
+        dot[u] = fmaf(mine.x, x[u].x, fmaf(mine.y, x[u].y, fmaf(mine.z, x[u].z, mine.w * x[u].w)));
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+#pragma unroll
+        for (int o = G / 2; o > 0; o >>= 1) dot[u] += __shfl_xor(dot[u], o, 64);
+        const int ent = k + u * NG + grp;
+        const int kc = ent < nh ? ent : (nh - 1);
+        float w = __shfl(my_c, kc, 64);
+        const float f = __shfl(my_f, kc, 64), Sv = __shfl(my_S, kc, 64);
+        if (ent >= nh) w = 0.f;
+        accq += w * (dot[u] - Sv) * f;
+        acc.x = fmaf(w, x[u].x, acc.x);
+        acc.y = fmaf(w, x[u].y, acc.y);
+        acc.z = fmaf(w, x[u].z, acc.z);
+        acc.w = fmaf(w, x[u].w, acc.w);
+      }
+    }
+  }
+#pragma unroll
+  for (int o = G; o < 64; o <<= 1) {
+    acc.x += __shfl_xor(acc.x, o, 64);
+    acc.y += __shfl_xor(acc.y, o, 64);
+    acc.z += __shfl_xor(acc.z, o, 64);
+    acc.w += __shfl_xor(acc.w, o, 64);
+    accq += __shfl_xor(accq, o, 64);
+  }
+  float* row = part >= 0 ? a.partial + (int64_t)part * a.out_ld : a.out + (int64_t)a.out_idx[r] * a.out_ld;
+  if (grp == 0 && has) {
+    float4 v = acc;
+    if (part < 0) {
+      const float4 o = ld4(row + c4);
+      v = make_float4(o.x + v.x, o.y + v.y, o.z + v.z, o.w + v.w);
+    }
+    st4(row + c4, v);
+  }
+  if (lane == 0) {
     float4 sc = make_float4(accq, 0.f, 0.f, 0.f);
     if (part < 0) sc.x += row[a.sc_col];
     st4(row + a.sc_col, sc);
@@ -347,7 +542,7 @@ int check_desc(ht_ctx* ctx, const ht_gat_desc* d) {
 
 // t = H W (pad columns zero), p, q
 int prepare(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const ht_tensor* H, const float* W, const float* a_dst,
-            const float* a_src, bool backward, GatWs* ws, ht_stats* st) {
+            const float* a_src, bool backward, GatWs* ws, ht_stats* st, Timer* tm) {
   hipStream_t s = ctx->stream;
   const int64_t V = std::max<int64_t>(g->V, 1);
   ws->ld_t = ht_row_pitch(desc->d_out, true);
@@ -361,7 +556,9 @@ int prepare(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const ht_te
   const int64_t step = (int64_t)1 << 22;
   for (int64_t r0 = 0; r0 < g->V; r0 += step) {
     const int64_t nr = std::min(step, g->V - r0);
+    tm->begin(&st->t_gemm_ms);
     HT_TRY(ht_gemm_nn(ctx, s, H->ptr + r0 * H->ld, H->ld, W, ws->T + r0 * ws->ld_t, ws->ld_t, nr, desc->d_in, desc->d_out, 0));
+    tm->end();
     st->n_gemm += 1;
     st->gemm_flops += 2.0 * nr * desc->d_in * desc->d_out;
   }
@@ -373,21 +570,36 @@ int prepare(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const ht_te
   return HT_OK;
 }
 
-int softmax_chunk(ht_ctx* ctx, const ht_graph* g, const ChunkMeta& c, const ht_gat_desc* desc, const GatWs& ws) {
-  const int64_t ndst = c.dst1 - c.dst0;
-  const int64_t* rowptr = (g->merged ? g->uindptr.p : g->indptr.p) + c.dst0;
-  const int64_t e_base = g->merged ? c.ue0 : c.e0;
+int softmax_chunk(ht_ctx* ctx, const ht_graph* g, const ChunkMeta& c, const ht_gat_desc* desc, const GatWs& ws, ht_stats* st,
+                  Timer* tm) {
   const int32_t* col = g->merged ? g->ucol.p + c.ue0 : g->col.p + c.e0;
   const float* mult = g->merged ? g->umult.p + c.ue0 : nullptr;
-  k_gat_softmax<<<(unsigned)((ndst + 3) / 4), 256, 0, ctx->stream>>>(rowptr, e_base, ndst, col, mult, ws.p + c.dst0, ws.q,
-                                                                      desc->slope, ws.w, ws.m + c.dst0, ws.zinv + c.dst0);
+  const ItemSet& it = c.fwd;
+  // rows without an in-edge (possible without self-loops) have no item: coefficient sums of 0
+  HT_TRY(ht_fill_zero(ctx, ctx->stream, ws.zinv + c.dst0, (size_t)(c.dst1 - c.dst0) * 4));
+  if (it.n_items == 0) return HT_OK;
+  float* part = nullptr;
+  HT_TRY(ht_scratch(ctx, HT_S_GATP, (size_t)std::max<int64_t>(g->max_fpart, 1) * 2 * 4, (void**)&part));
+  float* part_s = part + std::max<int64_t>(g->max_fpart, 1);
+  const unsigned nb = (unsigned)((it.n_items + 3) / 4);
+  tm->begin(&st->t_gat_softmax_ms);
+  k_gat_scores<<<nb, 256, 0, ctx->stream>>>(it.row, it.e0, it.len, it.part, it.n_items, col, mult, ws.p + c.dst0, ws.q,
+                                            desc->slope, ws.w, ws.m + c.dst0, ws.zinv + c.dst0, part, part_s);
+  if (it.n_fix > 0)
+    k_gat_rowstats<<<(unsigned)((it.n_fix + 255) / 256), 256, 0, ctx->stream>>>(it.fx_row, it.fx_part0, it.fx_nseg, it.n_fix,
+                                                                               part, part_s, ws.m + c.dst0, ws.zinv + c.dst0);
+  k_gat_coefs<<<nb, 256, 0, ctx->stream>>>(it.row, it.e0, it.len, it.n_items, mult, ws.m + c.dst0, ws.zinv + c.dst0, ws.w);
+  tm->end();
   HT_LAUNCH_CHECK(ctx);
   return HT_OK;
 }
 
 int launch_dst(ht_ctx* ctx, const GatPass& a, int nvec) {
   const unsigned nb = (unsigned)((a.n_items + 3) / 4);
-  if (nvec <= 64) k_gat_dst<1><<<nb, 256, 0, ctx->stream>>>(a);
+  if (nvec <= 8) k_gat_dst_g<8><<<nb, 256, 0, ctx->stream>>>(a);
+  else if (nvec <= 16) k_gat_dst_g<16><<<nb, 256, 0, ctx->stream>>>(a);
+  else if (nvec <= 32) k_gat_dst_g<32><<<nb, 256, 0, ctx->stream>>>(a);
+  else if (nvec <= 64) k_gat_dst<1><<<nb, 256, 0, ctx->stream>>>(a);
   else if (nvec <= 128) k_gat_dst<2><<<nb, 256, 0, ctx->stream>>>(a);
   else k_gat_dst<4><<<nb, 256, 0, ctx->stream>>>(a);
   HT_LAUNCH_CHECK(ctx);
@@ -395,7 +607,10 @@ int launch_dst(ht_ctx* ctx, const GatPass& a, int nvec) {
 }
 int launch_src(ht_ctx* ctx, const GatPass& a, int nvec) {
   const unsigned nb = (unsigned)((a.n_items + 3) / 4);
-  if (nvec <= 64) k_gat_src<1><<<nb, 256, 0, ctx->stream>>>(a);
+  if (nvec <= 8) k_gat_src_g<8><<<nb, 256, 0, ctx->stream>>>(a);
+  else if (nvec <= 16) k_gat_src_g<16><<<nb, 256, 0, ctx->stream>>>(a);
+  else if (nvec <= 32) k_gat_src_g<32><<<nb, 256, 0, ctx->stream>>>(a);
+  else if (nvec <= 64) k_gat_src<1><<<nb, 256, 0, ctx->stream>>>(a);
   else if (nvec <= 128) k_gat_src<2><<<nb, 256, 0, ctx->stream>>>(a);
   else k_gat_src<4><<<nb, 256, 0, ctx->stream>>>(a);
   HT_LAUNCH_CHECK(ctx);
@@ -403,17 +618,17 @@ int launch_src(ht_ctx* ctx, const GatPass& a, int nvec) {
 }
 
 int gat_fwd_impl(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const ht_tensor* H_in, const float* W,
-                 const float* a_dst, const float* a_src, ht_tensor* H_out, ht_stats* local) {
+                 const float* a_dst, const float* a_src, ht_tensor* H_out, ht_stats* local, Timer* tm, int layer) {
   HT_TRY(check_desc(ctx, desc));
   HT_TRY(check(ctx, g, desc, H_in, desc->d_in, "H_in"));
   HT_TRY(check(ctx, g, desc, H_out, desc->d_out, "H_out"));
   hipStream_t st = ctx->stream;
   GatWs ws{};
-  HT_TRY(prepare(ctx, g, desc, H_in, W, a_dst, a_src, false, &ws, local));
+  HT_TRY(prepare(ctx, g, desc, H_in, W, a_dst, a_src, false, &ws, local, tm));
   for (int j = 0; j < g->n; ++j) {
     const ChunkMeta& c = g->chunks[j];
     if (c.dst1 == c.dst0) continue;
-    HT_TRY(softmax_chunk(ctx, g, c, desc, ws));
+    HT_TRY(softmax_chunk(ctx, g, c, desc, ws, local, tm));
     float* partial = nullptr;
     if (c.fwd.n_part > 0) HT_TRY(ht_scratch(ctx, HT_S_SPART, (size_t)g->max_fpart * H_out->ld * 4, (void**)&partial));
     SpmmArgs a{};
@@ -427,8 +642,12 @@ int gat_fwd_impl(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const 
     a.accumulate = 0;
     a.relu = desc->act == HT_ACT_RELU;
     a.partial = partial;
+    a.tm = tm;
+    a.t_items = &local->t_agg_fwd_layer_ms[layer < HT_MAX_LAYERS ? layer : HT_MAX_LAYERS - 1];
+    a.t_fix = &local->t_agg_fix_ms;
     HT_TRY(ht_spmm_launch(ctx, st, a));
     local->n_spmm_fwd += 1;
+    local->n_agg_fwd_layer[layer < HT_MAX_LAYERS ? layer : HT_MAX_LAYERS - 1] += 1;
     local->edges += c.nnz;
   }
   return HT_OK;
@@ -436,7 +655,7 @@ int gat_fwd_impl(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const 
 
 int gat_bwd_impl(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const ht_tensor* H_in, const float* W,
                  const float* a_dst, const float* a_src, const ht_tensor* H_out, const ht_tensor* dH_out,
-                 ht_tensor* dH_in, float* dW, float* da_dst, float* da_src, ht_stats* local) {
+                 ht_tensor* dH_in, float* dW, float* da_dst, float* da_src, ht_stats* local, Timer* tm) {
   HT_TRY(check_desc(ctx, desc));
   HT_TRY(check(ctx, g, desc, H_in, desc->d_in, "H_in"));
   HT_TRY(check(ctx, g, desc, H_out, desc->d_out, "H_out"));
@@ -444,7 +663,7 @@ int gat_bwd_impl(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const 
   if (dH_in) HT_TRY(check(ctx, g, desc, dH_in, desc->d_in, "dH_in"));
   hipStream_t st = ctx->stream;
   GatWs ws{};
-  HT_TRY(prepare(ctx, g, desc, H_in, W, a_dst, a_src, true, &ws, local));
+  HT_TRY(prepare(ctx, g, desc, H_in, W, a_dst, a_src, true, &ws, local, tm));
   const int d = desc->d_out;
   const int nvec = (d + 3) / 4;
   const int sc_col = (int)ws.ld_t;              // the scalar column block sits behind the padded data columns
@@ -460,7 +679,7 @@ int gat_bwd_impl(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const 
     const ChunkMeta& c = g->chunks[j];
     const int64_t ndst = c.dst1 - c.dst0;
     if (ndst == 0) continue;
-    HT_TRY(softmax_chunk(ctx, g, c, desc, ws));
+    HT_TRY(softmax_chunk(ctx, g, c, desc, ws, local, tm));
     k_gat_dz<<<(unsigned)((ndst + 3) / 4), 256, 0, st>>>(dH_out->ptr + c.dst0 * dH_out->ld, dH_out->ld,
                                                           H_out->ptr + c.dst0 * H_out->ld, H_out->ld,
                                                           desc->act == HT_ACT_RELU, ndst, d, dz, ws.ld_t, ws.S);
@@ -474,12 +693,14 @@ int gat_bwd_impl(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const 
     a.mat = ws.T; a.mat_ld = ws.ld_t;
     a.own = dz; a.own_ld = ws.ld_t; a.own_idx = nullptr;
     a.dp_chunk = ws.dp + c.dst0; a.spart = spart;
+    tm->begin(&local->t_gat_dst_ms);
     if (a.n_items > 0) HT_TRY(launch_dst(ctx, a, nvec));
     if (c.fwd.n_fix > 0) {
       k_gat_fix_scalar<<<(unsigned)((c.fwd.n_fix + 255) / 256), 256, 0, st>>>(c.fwd.fx_row, c.fwd.fx_part0, c.fwd.fx_nseg,
                                                                                c.fwd.n_fix, spart, ws.dp + c.dst0);
       HT_LAUNCH_CHECK(ctx);
     }
+    tm->end();
     // source pass
     float* partial = nullptr;
     if (c.bwd.n_part > 0) HT_TRY(ht_scratch(ctx, HT_S_SPART, (size_t)g->max_bpart * ld_dt * 4, (void**)&partial));
@@ -491,6 +712,7 @@ int gat_bwd_impl(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const 
     a.own = ws.T; a.own_ld = ws.ld_t; a.own_idx = g->nbr.p + c.nbr_off;
     a.out = dT; a.out_ld = ld_dt; a.out_idx = g->nbr.p + c.nbr_off;
     a.partial = partial; a.sc_col = sc_col;
+    tm->begin(&local->t_gat_src_ms);
     if (a.n_items > 0) HT_TRY(launch_src(ctx, a, nvec));
     if (c.bwd.n_fix > 0) {
       SpmmArgs f{};
@@ -501,6 +723,7 @@ int gat_bwd_impl(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const 
       f.partial = partial;
       HT_TRY(ht_spmm_fix_launch(ctx, st, f));
     }
+    tm->end();
     local->n_spmm_bwd += 2;
     local->edges += 2 * c.nnz;
   }
@@ -513,10 +736,12 @@ int gat_bwd_impl(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const 
   bool first = true;
   for (int64_t r0 = 0; r0 < g->V; r0 += step) {
     const int64_t nr = std::min(step, g->V - r0);
+    tm->begin(&local->t_gemm_ms);
     HT_TRY(ht_gemm_tn(ctx, st, ws.T + r0 * ws.ld_t, ws.ld_t, ws.pq4 + r0 * 4, 4, da4, nr, d, 4, first ? 0 : 1));
     HT_TRY(ht_gemm_tn(ctx, st, H_in->ptr + r0 * H_in->ld, H_in->ld, dT + r0 * ld_dt, ld_dt, dW, nr, desc->d_in, d, first ? 0 : 1));
     if (dH_in)
       HT_TRY(ht_gemm_nt(ctx, st, dT + r0 * ld_dt, ld_dt, W, dH_in->ptr + r0 * dH_in->ld, dH_in->ld, nr, d, desc->d_in, 1));
+    tm->end();
     local->n_gemm += 3;
     local->gemm_flops += 4.0 * nr * desc->d_in * d;
     first = false;
@@ -542,8 +767,11 @@ int ht_gat_layer_fwd(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, co
   HT_HIP(ctx, hipSetDevice(ctx->device));
   auto t0 = std::chrono::steady_clock::now();
   ht_stats local{};
-  int rc = gat_fwd_impl(ctx, g, desc, H_in, W, a_dst, a_src, H_out, &local);
+  Timer tm(ctx, ctx->stream, stats != nullptr);
+  int rc = gat_fwd_impl(ctx, g, desc, H_in, W, a_dst, a_src, H_out, &local, &tm, 0);
   hipError_t e = hipStreamSynchronize(ctx->stream);
+  if (rc == HT_OK && e == hipSuccess) rc = tm.resolve();
+  ctx->ev_next = 0;
   if (rc != HT_OK) return rc;
   HT_HIP(ctx, e);
   if (stats) {
@@ -563,8 +791,11 @@ int ht_gat_layer_bwd(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, co
   HT_HIP(ctx, hipSetDevice(ctx->device));
   auto t0 = std::chrono::steady_clock::now();
   ht_stats local{};
-  int rc = gat_bwd_impl(ctx, g, desc, H_in, W, a_dst, a_src, H_out, dH_out, dH_in, dW, da_dst, da_src, &local);
+  Timer tm(ctx, ctx->stream, stats != nullptr);
+  int rc = gat_bwd_impl(ctx, g, desc, H_in, W, a_dst, a_src, H_out, dH_out, dH_in, dW, da_dst, da_src, &local, &tm);
   hipError_t e = hipStreamSynchronize(ctx->stream);
+  if (rc == HT_OK && e == hipSuccess) rc = tm.resolve();
+  ctx->ev_next = 0;
   if (rc != HT_OK) return rc;
   HT_HIP(ctx, e);
   if (stats) {
@@ -615,17 +846,21 @@ int ht_gat_epoch(ht_ctx* ctx, const ht_graph* g, const ht_gat_model* model, cons
   }
   float* loss_dev = take(4);
   ht_stats local{};
+  Timer tm(ctx, st, stats != nullptr);
   auto fail = [&](int rc) {
     (void)hipStreamSynchronize(st);
+    ctx->ev_next = 0;
     return rc;
   };
   for (int l = 0; l < L; ++l) {
     ht_gat_desc d{model->dims[l], model->dims[l + 1], l < L - 1 ? HT_ACT_RELU : HT_ACT_NONE, model->slope};
-    int rc = gat_fwd_impl(ctx, g, &d, l == 0 ? X : &h[l], model->W[l], model->a_dst[l], model->a_src[l], &h[l + 1], &local);
+    int rc = gat_fwd_impl(ctx, g, &d, l == 0 ? X : &h[l], model->W[l], model->a_dst[l], model->a_src[l], &h[l + 1], &local, &tm, l);
     if (rc != HT_OK) return fail(rc);
   }
   {
+    tm.begin(&local.t_loss_ms);
     int rc = ht_softmax_ce(ctx, st, h[L].ptr, h[L].ld, labels, V, model->dims[L], gh[L].ptr, gh[L].ld, loss_dev);
+    tm.end();
     if (rc != HT_OK) return fail(rc);
   }
   for (int l = L - 1; l >= 0; --l) {
@@ -635,7 +870,7 @@ int ht_gat_epoch(ht_ctx* ctx, const ht_graph* g, const ht_gat_model* model, cons
       if (rc != HT_OK) return fail(rc);
     }
     int rc = gat_bwd_impl(ctx, g, &d, l == 0 ? X : &h[l], model->W[l], model->a_dst[l], model->a_src[l], &h[l + 1], &gh[l + 1],
-                          l > 0 ? &gh[l] : nullptr, dW[l], dad[l], das[l], &local);
+                          l > 0 ? &gh[l] : nullptr, dW[l], dad[l], das[l], &local, &tm);
     if (rc != HT_OK) return fail(rc);
   }
   for (int l = 0; l < L; ++l) {
@@ -648,8 +883,16 @@ int ht_gat_epoch(ht_ctx* ctx, const ht_graph* g, const ht_gat_model* model, cons
     hipError_t e = hipMemcpyAsync(loss_out, loss_dev, 4, hipMemcpyDeviceToHost, st);
     if (e != hipSuccess) return fail(ht_set_err(ctx, HT_EHIP, "loss copy: %s", hipGetErrorString(e)));
   }
-  HT_HIP(ctx, hipStreamSynchronize(st));
+  {
+    hipError_t e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return fail(ht_set_err(ctx, HT_EHIP, "synchronize: %s", hipGetErrorString(e)));
+    int rc = tm.resolve();
+    ctx->ev_next = 0;
+    if (rc != HT_OK) return rc;
+  }
   if (stats) {
+    for (int l = 0; l < HT_MAX_LAYERS; ++l) local.t_spmm_fwd_ms += local.t_agg_fwd_layer_ms[l];
+    local.t_spmm_fwd_ms += local.t_agg_fix_ms;
     local.t_total_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
     *stats = local;
   }

@@ -161,6 +161,19 @@ def glorot_weights(dims: List[int], seed: int = 4) -> List[torch.Tensor]:
     return out
 
 
+def attention_vectors(dims: List[int], seed: int = 5):
+    """Per layer the two halves of the attention vector (destination half, source half), each
+    [dims[l+1]], uniform in +-sqrt(6 / (2 dims[l+1] + 1)), fp32, on the CPU."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    a_dst, a_src = [], []
+    for l in range(len(dims) - 1):
+        b = math.sqrt(6.0 / (2 * dims[l + 1] + 1))
+        a_dst.append(((torch.rand(dims[l + 1], generator=g, dtype=torch.float32) * 2.0 - 1.0) * b).contiguous())
+        a_src.append(((torch.rand(dims[l + 1], generator=g, dtype=torch.float32) * 2.0 - 1.0) * b).contiguous())
+    return a_dst, a_src
+
+
 @dataclass
 class Workload:
     """One configuration: graph shape, layer widths, chunk count, residency."""

@@ -76,7 +76,7 @@ def _run(ctx, case, d_in, d_out, relu, seed, want_dhin=True, slope=0.2):
     return H_out, dW
 
 
-@pytest.mark.parametrize("d_in,d_out", [(16, 8), (64, 32), (100, 41), (130, 256), (48, 300), (24, 520)])
+@pytest.mark.parametrize("d_in,d_out", [(16, 8), (64, 32), (100, 41), (30, 100), (130, 256), (48, 300), (24, 520)])
 def test_gat_widths(ctx, cases, d_in, d_out):
     _run(ctx, cases["rmat"], d_in, d_out, True, seed=d_in + d_out)
 
