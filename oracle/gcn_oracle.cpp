@@ -479,11 +479,15 @@ void orc_gat_fwd(int64_t V, const int64_t* indptr, const int32_t* col, int64_t d
 //   LeakyReLU: dy_e = dx_e * (1 if y_e > 0 else slope)
 //   dp_v += dy_e ; dq_u += dy_e ;  dt_v += dp_v a_dst ; dt_u += dq_u a_src
 //   da_dst = sum_v dp_v t_v ; da_src = sum_u dq_u t_u ; dW = H^T dt ; dH = dt W^T
+// Two sweeps so that every loop runs over independent rows: destinations first
+// (d alpha, dy_e, dp_v), then sources over their out-edges in edge order
+// (dt_u, dq_u); the out-edge lists come from a counting sort of the edge ids.
 void orc_gat_bwd(int64_t V, const int64_t* indptr, const int32_t* col, int64_t d_in, int64_t d_out, const double* H,
                  const double* W, const double* a_dst, const double* a_src, double slope, int relu, const double* T,
                  const double* alpha, const double* Z, const double* dOut, double* dH, double* dW, double* da_dst,
                  double* da_src) {
-  std::vector<double> p(V), q(V), dp(V, 0.0), dq(V, 0.0), dT((size_t)V * d_out, 0.0), dz(d_out);
+  const int64_t E = indptr[V];
+  std::vector<double> p(V), q(V), dp(V, 0.0), dq(V, 0.0), dT((size_t)V * d_out, 0.0), dy((size_t)E);
   for (int64_t v = 0; v < V; ++v) {
     double sp = 0.0, sq = 0.0;
     for (int64_t k = 0; k < d_out; ++k) {
@@ -493,30 +497,49 @@ void orc_gat_bwd(int64_t V, const int64_t* indptr, const int32_t* col, int64_t d
     p[v] = sp;
     q[v] = sq;
   }
+  auto dz_at = [&](int64_t v, int64_t k) { return (relu && !(Z[v * d_out + k] > 0.0)) ? 0.0 : dOut[v * d_out + k]; };
+#pragma omp parallel for schedule(dynamic, 64)
   for (int64_t v = 0; v < V; ++v) {
     const int64_t e0 = indptr[v], e1 = indptr[v + 1];
-    for (int64_t k = 0; k < d_out; ++k)
-      dz[k] = (relu && !(Z[v * d_out + k] > 0.0)) ? 0.0 : dOut[v * d_out + k];
-    std::vector<double> dal(e1 - e0);
     double S = 0.0;
     for (int64_t e = e0; e < e1; ++e) {
       const int64_t u = col[e];
       double dot = 0.0;
-      for (int64_t k = 0; k < d_out; ++k) {
-        dot += dz[k] * T[u * d_out + k];
-        dT[u * d_out + k] += alpha[e] * dz[k];
-      }
-      dal[e - e0] = dot;
+      for (int64_t k = 0; k < d_out; ++k) dot += dz_at(v, k) * T[u * d_out + k];
+      dy[e] = dot;                       // d alpha_e for now
       S += alpha[e] * dot;
     }
+    double acc = 0.0;
     for (int64_t e = e0; e < e1; ++e) {
-      const int64_t u = col[e];
-      const double dx = alpha[e] * (dal[e - e0] - S);
-      const double y = p[v] + q[u];
-      const double dy = dx * (y > 0.0 ? 1.0 : slope);
-      dp[v] += dy;
-      dq[u] += dy;
+      const double dx = alpha[e] * (dy[e] - S);
+      const double y = p[v] + q[col[e]];
+      dy[e] = dx * (y > 0.0 ? 1.0 : slope);
+      acc += dy[e];
     }
+    dp[v] = acc;
+  }
+  // out-edges of every source, ascending edge id
+  std::vector<int64_t> optr(V + 1, 0), oedge((size_t)E);
+  std::vector<int32_t> dst_of((size_t)E);
+  for (int64_t v = 0; v < V; ++v)
+    for (int64_t e = indptr[v]; e < indptr[v + 1]; ++e) {
+      dst_of[e] = (int32_t)v;
+      optr[col[e] + 1]++;
+    }
+  for (int64_t u = 0; u < V; ++u) optr[u + 1] += optr[u];
+  {
+    std::vector<int64_t> pos(optr.begin(), optr.end() - 1);
+    for (int64_t e = 0; e < E; ++e) oedge[pos[col[e]]++] = e;
+  }
+#pragma omp parallel for schedule(dynamic, 64)
+  for (int64_t u = 0; u < V; ++u) {
+    double acc = 0.0;
+    for (int64_t i = optr[u]; i < optr[u + 1]; ++i) {
+      const int64_t e = oedge[i], v = dst_of[e];
+      for (int64_t k = 0; k < d_out; ++k) dT[u * d_out + k] += alpha[e] * dz_at(v, k);
+      acc += dy[e];
+    }
+    dq[u] = acc;
   }
   for (int64_t k = 0; k < d_out; ++k) da_dst[k] = da_src[k] = 0.0;
   for (int64_t v = 0; v < V; ++v)

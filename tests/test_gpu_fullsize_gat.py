@@ -1,0 +1,60 @@
+"""GAT layer parity at the benchmark's full size (config 2's graph and first layer: 232,965
+vertices, 114.6 M edges, 602 -> 256, 8 chunks, all in HBM), in the launch configuration
+`bench.py --model gat` runs.  The oracle computes the whole layer forward and backward in fp64
+(about half a minute on the machine's host cores), so every output tensor is compared in full."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_2311_14898_amd import binding as B
+from paper_2311_14898_amd import inputs
+from tests.util import assert_close
+
+pytestmark = pytest.mark.gpu
+
+
+def test_gat_layer_full_size():
+    t0 = time.perf_counter()
+    note = lambda m: print(f"[{time.perf_counter() - t0:6.1f}s] {m}", flush=True)
+    w = inputs.WORKLOADS["cfg2"]
+    V, d_in, d_out = w.V, w.dims[0], w.dims[1]
+    src, dst = inputs.rmat_edges(V, w.E, w.graph_seed, device="cuda")
+    X = inputs.features(V, d_in)
+    W = inputs.glorot_weights(w.dims)[0]
+    a_dst, a_src = [x[0] for x in inputs.attention_vectors(w.dims)]
+    dh = torch.randn(V, d_out, generator=torch.Generator().manual_seed(9))
+    ctx = B.ht_ctx_create(0)
+    g = B.ht_partition(ctx, V, src, dst, w.n_chunks)
+    try:
+        Xd, Wd, ad, asd = B.to_matrix(X), W.cuda(), a_dst.cuda(), a_src.cuda()
+        H_out = B.alloc_matrix(V, d_out, zero=False)
+        B.ht_gat_layer_fwd(ctx, g, d_in, d_out, B.HT_ACT_RELU, Xd, Wd, ad, asd, H_out)
+        h_dev = H_out.cpu().numpy()[:, :d_out]
+        note("device forward done")
+        indptr, col = orc.csc_build(V, src.cpu().numpy(), dst.cpu().numpy(), add_self_loops=True)
+        f = orc.gat_layer_fwd(indptr, col, X.numpy(), W.numpy(), a_dst.numpy(), a_src.numpy(), relu=True)
+        note("oracle forward done")
+        assert_close(h_dev, f["h"], "h_out")
+        # the device masks by its own forward result; the oracle by its own pre-activations.  Elements whose
+        # pre-activation is within fp32 rounding of 0 could differ: count them and require none.
+        flips = np.count_nonzero((h_dev > 0) != (f["z"] > 0))
+        assert flips == 0, f"{flips} ReLU decisions differ"
+        dW = torch.empty(d_in, d_out, device="cuda")
+        dad, das = torch.empty(d_out, device="cuda"), torch.empty(d_out, device="cuda")
+        dH_in = B.alloc_matrix(V, d_in)
+        st = B.ht_gat_layer_bwd(ctx, g, d_in, d_out, B.HT_ACT_RELU, Xd, Wd, ad, asd, H_out, B.to_matrix(dh), dW, dad, das,
+                                dH_in=dH_in, want_stats=True)
+        note("device backward done")
+        assert st.n_spmm_bwd == 2 * w.n_chunks and st.edges == 2 * (w.E + V)
+        b = orc.gat_layer_bwd(indptr, col, X.numpy(), W.numpy(), a_dst.numpy(), a_src.numpy(), f, dh.numpy(), relu=True)
+        note("oracle backward done")
+        assert_close(dW.cpu().numpy(), b["dW"], "dW")
+        assert_close(dad.cpu().numpy(), b["da_dst"], "da_dst")
+        assert_close(das.cpu().numpy(), b["da_src"], "da_src")
+        assert_close(dH_in.cpu().numpy()[:, :d_in], b["dH"], "dH_in")
+    finally:
+        B.ht_graph_destroy(g)
+        B.ht_ctx_destroy(ctx)
