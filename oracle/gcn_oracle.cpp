@@ -479,13 +479,14 @@ void orc_gat_fwd(int64_t V, const int64_t* indptr, const int32_t* col, int64_t d
 //   LeakyReLU: dy_e = dx_e * (1 if y_e > 0 else slope)
 //   dp_v += dy_e ; dq_u += dy_e ;  dt_v += dp_v a_dst ; dt_u += dq_u a_src
 //   da_dst = sum_v dp_v t_v ; da_src = sum_u dq_u t_u ; dW = H^T dt ; dH = dt W^T
+// dec_p / dec_q (nullable, [V] fp32): see the LeakyReLU step below.
 // Two sweeps so that every loop runs over independent rows: destinations first
 // (d alpha, dy_e, dp_v), then sources over their out-edges in edge order
 // (dt_u, dq_u); the out-edge lists come from a counting sort of the edge ids.
 void orc_gat_bwd(int64_t V, const int64_t* indptr, const int32_t* col, int64_t d_in, int64_t d_out, const double* H,
                  const double* W, const double* a_dst, const double* a_src, double slope, int relu, const double* T,
-                 const double* alpha, const double* Z, const double* dOut, double* dH, double* dW, double* da_dst,
-                 double* da_src) {
+                 const double* alpha, const double* Z, const double* dOut, const float* dec_p, const float* dec_q,
+                 double* dH, double* dW, double* da_dst, double* da_src) {
   const int64_t E = indptr[V];
   std::vector<double> p(V), q(V), dp(V, 0.0), dq(V, 0.0), dT((size_t)V * d_out, 0.0), dy((size_t)E);
   for (int64_t v = 0; v < V; ++v) {
@@ -513,7 +514,10 @@ void orc_gat_bwd(int64_t V, const int64_t* indptr, const int32_t* col, int64_t d
     for (int64_t e = e0; e < e1; ++e) {
       const double dx = alpha[e] * (dy[e] - S);
       const double y = p[v] + q[col[e]];
-      dy[e] = dx * (y > 0.0 ? 1.0 : slope);
+      // which slope: the sign of y; or, when a checker supplies fp32 halves of the score, the sign of
+      // their fp32 sum (an fp32 implementation's decision for scores within rounding of 0)
+      const bool pos = dec_p ? (float)(dec_p[v] + dec_q[col[e]]) > 0.f : y > 0.0;
+      dy[e] = dx * (pos ? 1.0 : slope);
       acc += dy[e];
     }
     dp[v] = acc;
