@@ -135,6 +135,34 @@ def main_gat(args):
            "gemm_tflops": tot["gemm_flops"] / max(tot["t_gemm_ms"] * 1e-3, 1e-12) / 1e12,
            "epoch_gflop": gat_epoch_flops(w) / 1e9,
            "paper_context": "HongTu-IM 2-layer GAT on reddit (same shape), 1xA100, Table 4; other hardware, real dataset"}
+    # dominant kernels: the two backward passes; each gathers one row of width d_out per distinct (u, v) pair
+    out["roofline"] = {"bound": "hbm", "kernel": "GAT backward passes (k_gat_dst + k_gat_src), all layers",
+                       "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None, "traffic": None,
+                       "ms_per_step": tot["t_gat_dst_ms"] / K + src_ms}
+    alg = 0.0
+    for l in range(L):      # compulsory bytes of one pass at width d_{l+1}: topology + each row of t / dz once + outputs
+        alg += 2 * (4.0 * Ep + 4.0 * w.dims[l + 1] * (info.v_ori + w.V) + 16.0 * w.V)
+    out["roofline"]["achieved"] = alg / ((tot["t_gat_dst_ms"] / K + src_ms) * 1e-3) / 1e9
+    out["roofline"]["frac"] = out["roofline"]["achieved"] / HBM_PEAK_GBS
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+        indptr, col = orc.csc_build(w.V, src.cpu().numpy(), dst.cpu().numpy(), add_self_loops=True)
+        h, fw = X.numpy(), []
+        t_cpu = time.perf_counter()
+        for l in range(L):
+            fw.append(orc.gat_layer_fwd(indptr, col, h, Ws[l].numpy(), a_dst[l].numpy(), a_src[l].numpy(), relu=l < L - 1))
+            h = fw[-1]["h"]
+        loss_ref, gh = orc.softmax_ce(h, y.numpy())
+        for l in range(L - 1, -1, -1):
+            hin = X.numpy() if l == 0 else fw[l - 1]["h"]
+            bw = orc.gat_layer_bwd(indptr, col, hin, Ws[l].numpy(), a_dst[l].numpy(), a_src[l].numpy(), fw[l], gh,
+                                   relu=l < L - 1, want_dH=l > 0)
+            gh = bw["dH"]
+        t_cpu = time.perf_counter() - t_cpu
+        out["cpu_baseline"] = {"value": t_cpu, "unit": "s/epoch", "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count())),
+                               "kind": "oracle", "sample": f"one whole GAT epoch of the fp64 oracle (forward, loss, backward; no "
+                               f"update) on the same graph and inputs, {t_cpu:.1f} s; CSC construction not timed",
+                               "oracle_loss": loss_ref}
     B.ht_graph_destroy(g)
     B.ht_ctx_destroy(ctx)
     print(json.dumps(out))

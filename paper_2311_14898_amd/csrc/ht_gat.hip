@@ -19,7 +19,7 @@
 //   dt_v += dp_v a_dst + dq_v a_src ;  da_dst = sum_v dp_v t_v ;  da_src = sum_v dq_v t_v
 //   dW = H^T dt ;  dH = dt W^T
 // Both passes are pulls over the work items built at partition time; rows cut
-// into several items are finished in item order, so results are bit-reproducible.
+// into several items are finished in a fixed order, so results are bit-reproducible.
 // Merged duplicate edges: an entry of multiplicity k stands for k equal edges,
 // its coefficient is k times the single edge's.
 #include <algorithm>
@@ -89,7 +89,7 @@ __global__ void __launch_bounds__(256) k_gat_pq(const float* __restrict__ T, int
 // Neighbour softmax of the rows of one chunk in three steps over the work items (a wave per
 // item, so a hub row is shared by many waves):
 //   1. per item: the scores x_e (kept in w[]), their maximum m_i and s_i = sum mult_e exp(x_e - m_i);
-//   2. per row cut into several items: m_v = max m_i, Z_v = sum s_i exp(m_i - m_v), in item order;
+//   2. per row cut into several items: m_v = max m_i, Z_v = sum s_i exp(m_i - m_v), in a fixed order;
 //   3. per item: w_e = mult_e exp(x_e - m_v) / Z_v.
 __global__ void __launch_bounds__(256) k_gat_scores(const int32_t* __restrict__ it_row, const int64_t* __restrict__ it_e0,
                                                     const int32_t* __restrict__ it_len, const int32_t* __restrict__ it_part,
@@ -125,18 +125,25 @@ __global__ void __launch_bounds__(256) k_gat_scores(const int32_t* __restrict__ 
   }
 }
 
-__global__ void k_gat_rowstats(const int32_t* __restrict__ fx_row, const int32_t* __restrict__ fx_part0,
-                               const int32_t* __restrict__ fx_nseg, int64_t n_fix, const float* __restrict__ part_m,
-                               const float* __restrict__ part_s, float* __restrict__ m_chunk, float* __restrict__ zinv_chunk) {
-  const int64_t f = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+__global__ void __launch_bounds__(256) k_gat_rowstats(const int32_t* __restrict__ fx_row, const int32_t* __restrict__ fx_part0,
+                                                      const int32_t* __restrict__ fx_nseg, int64_t n_fix,
+                                                      const float* __restrict__ part_m, const float* __restrict__ part_s,
+                                                      float* __restrict__ m_chunk, float* __restrict__ zinv_chunk) {
+  // a wave per cut row; lanes take the row's items 64 apart, lane sums are added in lane order
+  const int lane = threadIdx.x & 63;
+  const int64_t f = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (f >= n_fix) return;
   const int32_t p0 = fx_part0[f], ns = fx_nseg[f];
   float m = -3.0e38f;
-  for (int32_t k = 0; k < ns; ++k) m = fmaxf(m, part_m[p0 + k]);
+  for (int32_t k = lane; k < ns; k += 64) m = fmaxf(m, part_m[p0 + k]);
+  m = wave_max(m);
   float s = 0.f;
-  for (int32_t k = 0; k < ns; ++k) s += part_s[p0 + k] * expf(part_m[p0 + k] - m);
-  m_chunk[fx_row[f]] = m;
-  zinv_chunk[fx_row[f]] = s > 0.f ? 1.f / s : 0.f;
+  for (int32_t k = lane; k < ns; k += 64) s += part_s[p0 + k] * expf(part_m[p0 + k] - m);
+  s = wave_sum(s);
+  if (lane == 0) {
+    m_chunk[fx_row[f]] = m;
+    zinv_chunk[fx_row[f]] = s > 0.f ? 1.f / s : 0.f;
+  }
 }
 
 __global__ void __launch_bounds__(256) k_gat_coefs(const int32_t* __restrict__ it_row, const int64_t* __restrict__ it_e0,
@@ -317,16 +324,18 @@ __global__ void __launch_bounds__(256) k_gat_dst_g(GatPass a) {
   }
 }
 
-// dp of the rows cut into several items: their partial sums in item order
-__global__ void k_gat_fix_scalar(const int32_t* __restrict__ fx_row, const int32_t* __restrict__ fx_part0,
-                                 const int32_t* __restrict__ fx_nseg, int64_t n_fix, const float* __restrict__ spart,
-                                 float* __restrict__ dp_chunk) {
-  const int64_t f = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+// dp of the rows cut into several items: a wave per row adds the item sums (lanes 64 apart, then lane order)
+__global__ void __launch_bounds__(256) k_gat_fix_scalar(const int32_t* __restrict__ fx_row, const int32_t* __restrict__ fx_part0,
+                                                        const int32_t* __restrict__ fx_nseg, int64_t n_fix,
+                                                        const float* __restrict__ spart, float* __restrict__ dp_chunk) {
+  const int lane = threadIdx.x & 63;
+  const int64_t f = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (f >= n_fix) return;
-  float s = 0.f;
   const int32_t p0 = fx_part0[f], ns = fx_nseg[f];
-  for (int32_t k = 0; k < ns; ++k) s += spart[p0 + k];
-  dp_chunk[fx_row[f]] = s;
+  float s = 0.f;
+  for (int32_t k = lane; k < ns; k += 64) s += spart[p0 + k];
+  s = wave_sum(s);
+  if (lane == 0) dp_chunk[fx_row[f]] = s;
 }
 
 // Source pass: for local source i (vertex u) over its entries (u -> v) of the chunk:
@@ -586,7 +595,7 @@ int softmax_chunk(ht_ctx* ctx, const ht_graph* g, const ChunkMeta& c, const ht_g
   k_gat_scores<<<nb, 256, 0, ctx->stream>>>(it.row, it.e0, it.len, it.part, it.n_items, col, mult, ws.p + c.dst0, ws.q,
                                             desc->slope, ws.w, ws.m + c.dst0, ws.zinv + c.dst0, part, part_s);
   if (it.n_fix > 0)
-    k_gat_rowstats<<<(unsigned)((it.n_fix + 255) / 256), 256, 0, ctx->stream>>>(it.fx_row, it.fx_part0, it.fx_nseg, it.n_fix,
+    k_gat_rowstats<<<(unsigned)((it.n_fix + 3) / 4), 256, 0, ctx->stream>>>(it.fx_row, it.fx_part0, it.fx_nseg, it.n_fix,
                                                                                part, part_s, ws.m + c.dst0, ws.zinv + c.dst0);
   k_gat_coefs<<<nb, 256, 0, ctx->stream>>>(it.row, it.e0, it.len, it.n_items, mult, ws.m + c.dst0, ws.zinv + c.dst0, ws.w);
   tm->end();
@@ -696,7 +705,7 @@ int gat_bwd_impl(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const 
     tm->begin(&local->t_gat_dst_ms);
     if (a.n_items > 0) HT_TRY(launch_dst(ctx, a, nvec));
     if (c.fwd.n_fix > 0) {
-      k_gat_fix_scalar<<<(unsigned)((c.fwd.n_fix + 255) / 256), 256, 0, st>>>(c.fwd.fx_row, c.fwd.fx_part0, c.fwd.fx_nseg,
+      k_gat_fix_scalar<<<(unsigned)((c.fwd.n_fix + 3) / 4), 256, 0, st>>>(c.fwd.fx_row, c.fwd.fx_part0, c.fwd.fx_nseg,
                                                                                c.fwd.n_fix, spart, ws.dp + c.dst0);
       HT_LAUNCH_CHECK(ctx);
     }
