@@ -12,10 +12,12 @@
 // Per chunk, edge coefficients live in a scratch array of the chunk's size.
 //
 // Backward.  With dz = dh' * act'(z) and S_v = dz_v . z_v  (= sum_e alpha_e dalpha_e):
-//   dalpha_e = dz_v . t_u ;  dy_e = alpha_e (dalpha_e - S_v) LeakyReLU'(y_e)
-//   dp_v = sum_{e in in(v)} dy_e      (pass over destinations, reads rows of t)
-//   dq_u = sum_{e in out(u)} dy_e ;  dt_u = sum_{e in out(u)} alpha_e dz_v
-//                                     (pass over sources, reads rows of dz)
+//   dalpha_e = dz_v . t_u ;  dy_e = alpha_e (dalpha_e - S_v) f_e ,  f_e = LeakyReLU'(y_e)
+//   dp_v = sum_{e in in(v)} dy_e  = dz_v . (sum_e alpha_e f_e t_u) - S_v sum_e alpha_e f_e
+//                                     (pass over destinations, an aggregation of rows of t)
+//   dq_u = sum_{e in out(u)} dy_e = t_u . (sum_e alpha_e f_e dz_v) - sum_e alpha_e f_e S_v
+//   dt_u = sum_{e in out(u)} alpha_e dz_v
+//                                     (pass over sources, two aggregations of the same rows of dz)
 //   dt_v += dp_v a_dst + dq_v a_src ;  da_dst = sum_v dp_v t_v ;  da_src = sum_v dq_v t_v
 //   dW = H^T dt ;  dH = dt W^T
 // Both passes are pulls over the work items built at partition time; rows cut
@@ -41,21 +43,6 @@ __device__ __forceinline__ float wave_max(float x) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
   return x;
-}
-// Sums of four values over the wave at once: the first two exchange steps fold the four inputs
-// into one register (a quarter of the wave per input), four more finish the quarters.
-__device__ __forceinline__ void wave_sum4(const float d[4], float r[4]) {
-  const int lane = threadIdx.x & 63;
-  const bool h32 = (lane & 32) != 0, h16 = (lane & 16) != 0;
-  const float a = (h32 ? d[1] : d[0]) + __shfl_xor(h32 ? d[0] : d[1], 32, 64);
-  const float b = (h32 ? d[3] : d[2]) + __shfl_xor(h32 ? d[2] : d[3], 32, 64);
-  float c = (h16 ? b : a) + __shfl_xor(h16 ? a : b, 16, 64);
-#pragma unroll
-  for (int o = 8; o > 0; o >>= 1) c += __shfl_xor(c, o, 64);
-  r[0] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(c), 0));
-  r[1] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(c), 32));
-  r[2] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(c), 16));
-  r[3] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(c), 48));
 }
 __device__ __forceinline__ float lrelu(float y, float slope) { return y > 0.f ? y : slope * y; }
 // coefficient of one entry; the same expression in every kernel, so the forward, the
@@ -206,8 +193,10 @@ struct GatPass {
   int sc_col;
 };
 
-// Destination pass: dp_v = sum over v's entries of  w_e (dz_v . t_u - S_v) LeakyReLU'(y_e).
-// A wave per item; lanes hold float4 slices of dz_v; four rows of t are in flight.
+// Destination pass.  dp_v = sum_e w_e f_e (dz_v . t_u - S_v) with f_e = LeakyReLU'(y_e); regrouped as
+//   dp_v = dz_v . (sum_e w_e f_e t_u) - S_v sum_e w_e f_e
+// it is an aggregation of rows of t with the weights w_e f_e and one dot product per item.
+// A wave per item; four rows of t are in flight per lane.
 template <int VPL>
 __global__ void __launch_bounds__(256) k_gat_dst(GatPass a) {
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -216,60 +205,68 @@ __global__ void __launch_bounds__(256) k_gat_dst(GatPass a) {
   const int32_t r = a.it_row[t];
   const int64_t e0 = a.it_e0[t];
   const int32_t len = a.it_len[t], part = a.it_part[t];
-  float4 mine[VPL];
+  float4 Q[VPL];
 #pragma unroll
-  for (int j = 0; j < VPL; ++j) {
-    const int c = (j * 64 + lane) * 4;
-    mine[j] = c < a.d ? ld4(a.own + (int64_t)r * a.own_ld + c) : make_float4(0.f, 0.f, 0.f, 0.f);   // pads of dz are zero
-  }
-  const float pv = a.p[a.dst0 + r], Sv = a.S[r];
-  float acc = 0.f;
+  for (int j = 0; j < VPL; ++j) Q[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+  const float pv = a.p[a.dst0 + r];
+  float rsum = 0.f;
   for (int32_t base = 0; base < len; base += 64) {
     const int32_t nh = (len - base) < 64 ? (len - base) : 64;
     int32_t my_u = 0;
-    float my_w = 0.f, my_q = 0.f;
+    float my_wf = 0.f;
     if (lane < nh) {
       my_u = a.idx[e0 + base + lane];
-      my_w = a.w[e0 + base + lane];
-      my_q = a.q[my_u];
+      my_wf = a.w[e0 + base + lane] * (pv + a.q[my_u] > 0.f ? 1.f : a.slope);
     }
+    rsum += wave_sum(my_wf);
     for (int32_t k = 0; k < nh; k += 4) {
-      float dot[4];
+      int32_t c[4];
+      float w[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int kc = (k + u) < nh ? (k + u) : (nh - 1);
-        const int32_t c = __builtin_amdgcn_readlane(my_u, kc);
-        float s = 0.f;
+        c[u] = __builtin_amdgcn_readlane(my_u, kc);
+        w[u] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_wf), kc));
+        if (k + u >= nh) w[u] = 0.f;
+      }
+      float4 x[4][VPL];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
 #pragma unroll
         for (int j = 0; j < VPL; ++j) {
           const int cc = (j * 64 + lane) * 4;
-          if (cc < a.d) {
-            const float4 x = ld4(a.mat + (int64_t)c * a.mat_ld + cc);
-            s = fmaf(mine[j].x, x.x, fmaf(mine[j].y, x.y, fmaf(mine[j].z, x.z, fmaf(mine[j].w, x.w, s))));
-          }
+          x[u][j] = cc < a.d ? ld4(a.mat + (int64_t)c[u] * a.mat_ld + cc) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
-        dot[u] = s;
-      }
-      float da[4];
-      wave_sum4(dot, da);
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        if (k + u < nh) {
-          const float w = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_w), k + u));
-          const float y = pv + __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_q), k + u));
-          acc += w * (da[u] - Sv) * (y > 0.f ? 1.f : a.slope);
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int j = 0; j < VPL; ++j) {
+          Q[j].x = fmaf(w[u], x[u][j].x, Q[j].x);
+          Q[j].y = fmaf(w[u], x[u][j].y, Q[j].y);
+          Q[j].z = fmaf(w[u], x[u][j].z, Q[j].z);
+          Q[j].w = fmaf(w[u], x[u][j].w, Q[j].w);
         }
-      }
     }
   }
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < VPL; ++j) {
+    const int c = (j * 64 + lane) * 4;
+    if (c < a.d) {
+      const float4 mine = ld4(a.own + (int64_t)r * a.own_ld + c);   // pads of dz are zero
+      s = fmaf(mine.x, Q[j].x, fmaf(mine.y, Q[j].y, fmaf(mine.z, Q[j].z, fmaf(mine.w, Q[j].w, s))));
+    }
+  }
+  s = wave_sum(s);
   if (lane == 0) {
+    const float acc = s - a.S[r] * rsum;
     if (part >= 0) a.spart[part] = acc;
     else a.dp_chunk[r] = acc;
   }
 }
 
 // The same pass for rows of at most G float4: the wave splits into 64 / G lane groups that
-// take interleaved entries; a group's partial results are added in group order at the end.
+// take interleaved entries; the groups' sums meet in the final dot product.
 template <int G>
 __global__ void __launch_bounds__(256) k_gat_dst_g(GatPass a) {
   constexpr int NG = 64 / G;
@@ -282,43 +279,47 @@ __global__ void __launch_bounds__(256) k_gat_dst_g(GatPass a) {
   const int grp = lane / G, c4 = (lane % G) * 4;
   const bool has = c4 < a.d;
   const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
-  const float4 mine = has ? ld4(a.own + (int64_t)r * a.own_ld + c4) : zero;
-  const float pv = a.p[a.dst0 + r], Sv = a.S[r];
-  float acc = 0.f;
+  float4 Q = zero;
+  const float pv = a.p[a.dst0 + r];
+  float rsum = 0.f;
   for (int32_t base = 0; base < len; base += 64) {
     const int32_t nh = (len - base) < 64 ? (len - base) : 64;
     int32_t my_u = 0;
-    float my_w = 0.f, my_q = 0.f;
+    float my_wf = 0.f;
     if (lane < nh) {
       my_u = a.idx[e0 + base + lane];
-      my_w = a.w[e0 + base + lane];
-      my_q = a.q[my_u];
+      my_wf = a.w[e0 + base + lane] * (pv + a.q[my_u] > 0.f ? 1.f : a.slope);
     }
+    rsum += wave_sum(my_wf);
     for (int32_t k = 0; k < nh; k += 4 * NG) {
-      float dot[4];
+      float4 x[4];
+      float w[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int ent = k + u * NG + grp;
         const int kc = ent < nh ? ent : (nh - 1);
         const int32_t c = __shfl(my_u, kc, 64);
-        const float4 x = has ? ld4(a.mat + (int64_t)c * a.mat_ld + c4) : zero;
-        dot[u] = fmaf(mine.x, x.x, fmaf(mine.y, x.y, fmaf(mine.z, x.z, mine.w * x.w)));
+        w[u] = __shfl(my_wf, kc, 64);
+        if (ent >= nh) w[u] = 0.f;
+        x[u] = has ? ld4(a.mat + (int64_t)c * a.mat_ld + c4) : zero;
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-#pragma unroll
-        for (int o = G / 2; o > 0; o >>= 1) dot[u] += __shfl_xor(dot[u], o, 64);
-        const int ent = k + u * NG + grp;
-        const int kc = ent < nh ? ent : (nh - 1);
-        const float w = __shfl(my_w, kc, 64);
-        const float y = pv + __shfl(my_q, kc, 64);
-        if (ent < nh) acc += w * (dot[u] - Sv) * (y > 0.f ? 1.f : a.slope);
+        Q.x = fmaf(w[u], x[u].x, Q.x);
+        Q.y = fmaf(w[u], x[u].y, Q.y);
+        Q.z = fmaf(w[u], x[u].z, Q.z);
+        Q.w = fmaf(w[u], x[u].w, Q.w);
       }
     }
   }
-#pragma unroll
-  for (int o = G; o < 64; o <<= 1) acc += __shfl_xor(acc, o, 64);
+  float s = 0.f;
+  if (has) {
+    const float4 mine = ld4(a.own + (int64_t)r * a.own_ld + c4);
+    s = fmaf(mine.x, Q.x, fmaf(mine.y, Q.y, fmaf(mine.z, Q.z, mine.w * Q.w)));
+  }
+  s = wave_sum(s);
   if (lane == 0) {
+    const float acc = s - a.S[r] * rsum;
     if (part >= 0) a.spart[part] = acc;
     else a.dp_chunk[r] = acc;
   }
@@ -338,8 +339,10 @@ __global__ void __launch_bounds__(256) k_gat_fix_scalar(const int32_t* __restric
   if (lane == 0) dp_chunk[fx_row[f]] = s;
 }
 
-// Source pass: for local source i (vertex u) over its entries (u -> v) of the chunk:
-//   dt_u += sum w_e dz_v ;  dq_u += sum w_e (dz_v . t_u - S_v) LeakyReLU'(y_e),  w_e recomputed.
+// Source pass: for local source i (vertex u) over its entries (u -> v) of the chunk, w_e recomputed:
+//   dt_u += sum_e w_e dz_v
+//   dq_u += sum_e w_e f_e (dz_v . t_u - S_v) = t_u . (sum_e w_e f_e dz_v) - sum_e w_e f_e S_v
+// i.e. two aggregations of the same gathered rows of dz and one dot product per item.
 template <int VPL>
 __global__ void __launch_bounds__(256) k_gat_src(GatPass a) {
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -349,68 +352,66 @@ __global__ void __launch_bounds__(256) k_gat_src(GatPass a) {
   const int64_t e0 = a.it_e0[t];
   const int32_t len = a.it_len[t], part = a.it_part[t];
   const int32_t u_id = a.own_idx[r];
-  float4 mine[VPL], acc[VPL];
+  float4 acc[VPL], G[VPL];
 #pragma unroll
-  for (int j = 0; j < VPL; ++j) {
-    const int c = (j * 64 + lane) * 4;
-    mine[j] = c < a.d ? ld4(a.own + (int64_t)u_id * a.own_ld + c) : make_float4(0.f, 0.f, 0.f, 0.f);   // pads of t are zero
-    acc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-  }
+  for (int j = 0; j < VPL; ++j) acc[j] = G[j] = make_float4(0.f, 0.f, 0.f, 0.f);
   const float qu = a.q[u_id];
-  float accq = 0.f;
+  float csum = 0.f;
   for (int32_t base = 0; base < len; base += 64) {
     const int32_t nh = (len - base) < 64 ? (len - base) : 64;
     int32_t my_v = 0;
-    float my_c = 0.f, my_f = 0.f, my_S = 0.f;   // coefficient, LeakyReLU', S_v of the lane's entry
+    float my_c = 0.f, my_cf = 0.f, my_cs = 0.f;   // w_e, w_e f_e, w_e f_e S_v of the lane's entry
     if (lane < nh) {
       my_v = a.idx[e0 + base + lane];
       const int64_t v = a.dst0 + my_v;
       const float y = a.p[v] + qu;
       my_c = coef(y, a.slope, a.m[v], a.zinv[v], a.mult ? a.mult[e0 + base + lane] : 1.f);
-      my_f = y > 0.f ? 1.f : a.slope;
-      my_S = a.S[my_v];
+      my_cf = my_c * (y > 0.f ? 1.f : a.slope);
+      my_cs = my_cf * a.S[my_v];
     }
+    csum += wave_sum(my_cs);
     for (int32_t k = 0; k < nh; k += 4) {
-      float4 x[4][VPL];
-      float dot[4];
+      int32_t c[4];
+      float w[4], wf[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int kc = (k + u) < nh ? (k + u) : (nh - 1);
-        const int32_t c = __builtin_amdgcn_readlane(my_v, kc);
-        float s = 0.f;
+        c[u] = __builtin_amdgcn_readlane(my_v, kc);
+        w[u] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_c), kc));
+        wf[u] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_cf), kc));
+        if (k + u >= nh) w[u] = wf[u] = 0.f;
+      }
+      float4 x[4][VPL];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
 #pragma unroll
         for (int j = 0; j < VPL; ++j) {
           const int cc = (j * 64 + lane) * 4;
-          x[u][j] = cc < a.d ? ld4(a.mat + (int64_t)c * a.mat_ld + cc) : make_float4(0.f, 0.f, 0.f, 0.f);
-          s = fmaf(mine[j].x, x[u][j].x, fmaf(mine[j].y, x[u][j].y, fmaf(mine[j].z, x[u][j].z, fmaf(mine[j].w, x[u][j].w, s))));
+          x[u][j] = cc < a.d ? ld4(a.mat + (int64_t)c[u] * a.mat_ld + cc) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
-        dot[u] = s;
-      }
-      float da[4];
-      wave_sum4(dot, da);
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        if (k + u < nh) {
-          const float w = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_c), k + u));
-          const float f = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_f), k + u));
-          const float Sv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_S), k + u));
-          accq += w * (da[u] - Sv) * f;
+      for (int u = 0; u < 4; ++u)
 #pragma unroll
-          for (int j = 0; j < VPL; ++j) {
-            acc[j].x = fmaf(w, x[u][j].x, acc[j].x);
-            acc[j].y = fmaf(w, x[u][j].y, acc[j].y);
-            acc[j].z = fmaf(w, x[u][j].z, acc[j].z);
-            acc[j].w = fmaf(w, x[u][j].w, acc[j].w);
-          }
+        for (int j = 0; j < VPL; ++j) {
+          acc[j].x = fmaf(w[u], x[u][j].x, acc[j].x);
+          acc[j].y = fmaf(w[u], x[u][j].y, acc[j].y);
+          acc[j].z = fmaf(w[u], x[u][j].z, acc[j].z);
+          acc[j].w = fmaf(w[u], x[u][j].w, acc[j].w);
+          G[j].x = fmaf(wf[u], x[u][j].x, G[j].x);
+          G[j].y = fmaf(wf[u], x[u][j].y, G[j].y);
+          G[j].z = fmaf(wf[u], x[u][j].z, G[j].z);
+          G[j].w = fmaf(wf[u], x[u][j].w, G[j].w);
         }
-      }
     }
   }
+  float s = 0.f;
   float* row = part >= 0 ? a.partial + (int64_t)part * a.out_ld : a.out + (int64_t)a.out_idx[r] * a.out_ld;
 #pragma unroll
   for (int j = 0; j < VPL; ++j) {
     const int c = (j * 64 + lane) * 4;
     if (c >= a.d) continue;
+    const float4 mine = ld4(a.own + (int64_t)u_id * a.own_ld + c);   // pads of t are zero
+    s = fmaf(mine.x, G[j].x, fmaf(mine.y, G[j].y, fmaf(mine.z, G[j].z, fmaf(mine.w, G[j].w, s))));
     float4 v = acc[j];
     if (part < 0) {
       const float4 o = ld4(row + c);
@@ -418,17 +419,18 @@ __global__ void __launch_bounds__(256) k_gat_src(GatPass a) {
     }
     st4(row + c, v);
   }
+  s = wave_sum(s);
   if (lane == 0) {
     // the scalar travels in its own float4 column block behind the data columns
-    float4 sc = make_float4(accq, 0.f, 0.f, 0.f);
+    float4 sc = make_float4(s - csum, 0.f, 0.f, 0.f);
     if (part < 0) sc.x += row[a.sc_col];
     st4(row + a.sc_col, sc);
   }
 }
 
-template <int G>
+template <int G_>
 __global__ void __launch_bounds__(256) k_gat_src_g(GatPass a) {
-  constexpr int NG = 64 / G;
+  constexpr int NG = 64 / G_;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t t = (int64_t)blockIdx.x * 4 + wave;
   if (t >= a.n_items) return;
@@ -436,72 +438,75 @@ __global__ void __launch_bounds__(256) k_gat_src_g(GatPass a) {
   const int64_t e0 = a.it_e0[t];
   const int32_t len = a.it_len[t], part = a.it_part[t];
   const int32_t u_id = a.own_idx[r];
-  const int grp = lane / G, c4 = (lane % G) * 4;
+  const int grp = lane / G_, c4 = (lane % G_) * 4;
   const bool has = c4 < a.d;
   const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
-  const float4 mine = has ? ld4(a.own + (int64_t)u_id * a.own_ld + c4) : zero;
-  float4 acc = zero;
+  float4 acc = zero, G = zero;
   const float qu = a.q[u_id];
-  float accq = 0.f;
+  float csum = 0.f;
   for (int32_t base = 0; base < len; base += 64) {
     const int32_t nh = (len - base) < 64 ? (len - base) : 64;
     int32_t my_v = 0;
-    float my_c = 0.f, my_f = 0.f, my_S = 0.f;
+    float my_c = 0.f, my_cf = 0.f, my_cs = 0.f;
     if (lane < nh) {
       my_v = a.idx[e0 + base + lane];
       const int64_t v = a.dst0 + my_v;
       const float y = a.p[v] + qu;
       my_c = coef(y, a.slope, a.m[v], a.zinv[v], a.mult ? a.mult[e0 + base + lane] : 1.f);
-      my_f = y > 0.f ? 1.f : a.slope;
-      my_S = a.S[my_v];
+      my_cf = my_c * (y > 0.f ? 1.f : a.slope);
+      my_cs = my_cf * a.S[my_v];
     }
+    csum += wave_sum(my_cs);
     for (int32_t k = 0; k < nh; k += 4 * NG) {
       float4 x[4];
-      float dot[4];
+      float w[4], wf[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int ent = k + u * NG + grp;
         const int kc = ent < nh ? ent : (nh - 1);
         const int32_t c = __shfl(my_v, kc, 64);
+        w[u] = __shfl(my_c, kc, 64);
+        wf[u] = __shfl(my_cf, kc, 64);
+        if (ent >= nh) w[u] = wf[u] = 0.f;
         x[u] = has ? ld4(a.mat + (int64_t)c * a.mat_ld + c4) : zero;
-        dot[u] = fmaf(mine.x, x[u].x, fmaf(mine.y, x[u].y, fmaf(mine.z, x[u].z, mine.w * x[u].w)));
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-#pragma unroll
-        for (int o = G / 2; o > 0; o >>= 1) dot[u] += __shfl_xor(dot[u], o, 64);
-        const int ent = k + u * NG + grp;
-        const int kc = ent < nh ? ent : (nh - 1);
-        float w = __shfl(my_c, kc, 64);
-        const float f = __shfl(my_f, kc, 64), Sv = __shfl(my_S, kc, 64);
-        if (ent >= nh) w = 0.f;
-        accq += w * (dot[u] - Sv) * f;
-        acc.x = fmaf(w, x[u].x, acc.x);
-        acc.y = fmaf(w, x[u].y, acc.y);
-        acc.z = fmaf(w, x[u].z, acc.z);
-        acc.w = fmaf(w, x[u].w, acc.w);
+        acc.x = fmaf(w[u], x[u].x, acc.x);
+        acc.y = fmaf(w[u], x[u].y, acc.y);
+        acc.z = fmaf(w[u], x[u].z, acc.z);
+        acc.w = fmaf(w[u], x[u].w, acc.w);
+        G.x = fmaf(wf[u], x[u].x, G.x);
+        G.y = fmaf(wf[u], x[u].y, G.y);
+        G.z = fmaf(wf[u], x[u].z, G.z);
+        G.w = fmaf(wf[u], x[u].w, G.w);
       }
     }
   }
 #pragma unroll
-  for (int o = G; o < 64; o <<= 1) {
+  for (int o = G_; o < 64; o <<= 1) {
     acc.x += __shfl_xor(acc.x, o, 64);
     acc.y += __shfl_xor(acc.y, o, 64);
     acc.z += __shfl_xor(acc.z, o, 64);
     acc.w += __shfl_xor(acc.w, o, 64);
-    accq += __shfl_xor(accq, o, 64);
   }
+  float s = 0.f;
   float* row = part >= 0 ? a.partial + (int64_t)part * a.out_ld : a.out + (int64_t)a.out_idx[r] * a.out_ld;
-  if (grp == 0 && has) {
-    float4 v = acc;
-    if (part < 0) {
-      const float4 o = ld4(row + c4);
-      v = make_float4(o.x + v.x, o.y + v.y, o.z + v.z, o.w + v.w);
+  if (has) {
+    const float4 mine = ld4(a.own + (int64_t)u_id * a.own_ld + c4);
+    s = fmaf(mine.x, G.x, fmaf(mine.y, G.y, fmaf(mine.z, G.z, mine.w * G.w)));
+    if (grp == 0) {
+      float4 v = acc;
+      if (part < 0) {
+        const float4 o = ld4(row + c4);
+        v = make_float4(o.x + v.x, o.y + v.y, o.z + v.z, o.w + v.w);
+      }
+      st4(row + c4, v);
     }
-    st4(row + c4, v);
   }
+  s = wave_sum(s);
   if (lane == 0) {
-    float4 sc = make_float4(accq, 0.f, 0.f, 0.f);
+    float4 sc = make_float4(s - csum, 0.f, 0.f, 0.f);
     if (part < 0) sc.x += row[a.sc_col];
     st4(row + a.sc_col, sc);
   }
