@@ -1093,6 +1093,25 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
     ctx->ev_next = 0;
     return rc;
   };
+  // Host-resident gradient tensors that the backward pass adds into start as zeros.  They are not
+  // touched before the backward pass, so a helper thread clears them beside the forward pass
+  // instead of the GPU waiting for a memset between two layers.
+  auto stored_once = [&](int l) {   // a never-evicting gradient buffer stores every row of a host-resident grad h^l exactly once
+    return g->keep_all && g->v_load == V && ws->gh[l].loc == HT_LOC_HOST_PINNED && gather_mode != HT_GATHER_DIRECT;
+  };
+  struct Joiner {
+    std::thread th;
+    ~Joiner() { if (th.joinable()) th.join(); }
+  } zeroer;
+  {
+    std::vector<ht_tensor*> todo;
+    for (int l = 1; l < L; ++l)
+      if (ws->gh[l].loc == HT_LOC_HOST_PINNED && !stored_once(l)) todo.push_back(&ws->gh[l]);
+    if (!todo.empty())
+      zeroer.th = std::thread([todo] {
+        for (ht_tensor* t : todo) std::memset(t->ptr, 0, (size_t)t->rows * t->ld * 4);
+      });
+  }
   // ---- forward (Alg. 1 lines 4-9)
   for (int l = 0; l < L; ++l) {
     ht_layer_desc d{};
@@ -1124,10 +1143,9 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
     d.ckpt_kind = recompute ? HT_CKPT_INPUT : HT_CKPT_AGG;
     R.dhin_is_zero = false;
     if (l > 0) {
-      // a never-evicting gradient buffer stores every row of a host-resident grad h^l exactly once
-      const bool stored_once = g->keep_all && g->v_load == V && ws->gh[l].loc == HT_LOC_HOST_PINNED &&
-                               gather_mode != HT_GATHER_DIRECT;
-      if (!stored_once) {
+      if (ws->gh[l].loc == HT_LOC_HOST_PINNED) {
+        if (zeroer.th.joinable()) zeroer.th.join();     // cleared beside the forward pass (or stored exactly once)
+      } else {
         int rc = zero_tensor(ctx, &ws->gh[l]);
         if (rc != HT_OK) return fail(rc);
       }
