@@ -192,6 +192,9 @@ def main():
     ap.add_argument("--cache", choices=["adjacent", "all"], default="adjacent",
                     help="neighbour-row buffer: reuse between adjacent chunks only, or keep every row once loaded")
     ap.add_argument("--reorder", action="store_true", help="greedy max-overlap chunk schedule (Alg. 4, phase 2)")
+    ap.add_argument("--residency", choices=["workload", "auto", "h-host"], default="workload",
+                    help="where the vertex tensors live: as the workload says; wherever the planner's byte budget puts them; "
+                         "or h^l in pinned host memory with a^l and the gradients placed by the planner")
     ap.add_argument("--model", choices=["gcn", "gat"], default="gcn", help="gcn: the benchmark; gat: the attention model "
                     "on the same workload (its own JSON line, HBM-resident workloads only)")
     ap.add_argument("--order", choices=["paper", "auto"], default="paper",
@@ -222,7 +225,7 @@ def main():
             print(f"[bench {time.perf_counter() - t_origin:7.1f}s] {msg}", file=sys.stderr, flush=True)
 
     w = inputs.WORKLOADS[args.workload].scaled(args.scale)
-    host = w.residency in ("host", "host_all")
+    host = w.residency in ("host", "host_all") and args.residency == "workload"
     t_gen = time.perf_counter()
     src, dst = inputs.rmat_edges(w.V, w.E, w.graph_seed, device="cuda")
     X = inputs.features(w.V, w.dims[0])
@@ -242,7 +245,9 @@ def main():
     Wd = [x.clone().cuda() for x in Ws]
     res = B.HT_RES_HOST if host else B.HT_RES_AUTO
     # "host": vertex data (h^l, grad h^l) in pinned host memory; "host_all": the checkpoints a^l too
-    plan = dict(res_h=res, res_g=res, res_a=B.HT_RES_HOST if w.residency == "host_all" else B.HT_RES_AUTO)
+    plan = dict(res_h=res, res_g=res, res_a=B.HT_RES_HOST if (host and w.residency == "host_all") else B.HT_RES_AUTO)
+    if args.residency == "h-host":
+        plan = dict(res_h=B.HT_RES_HOST, res_g=B.HT_RES_AUTO, res_a=B.HT_RES_AUTO)
 
     if args.calib_copy:
         a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
@@ -304,7 +309,7 @@ def main():
            "dtype": "f32", "data": "synthetic",
            "config": {"workload": f"{w.name}: {L}-layer GCN, R-MAT V={w.V} E={w.E} (+{w.V} self-loops), dims "
                                   f"{'-'.join(map(str, w.dims))}, {w.n_chunks} chunks, vertex data in "
-                                  f"{'pinned host memory' if host else 'HBM'}",
+                                  f"{'pinned host memory' if host else 'HBM'}" + (f" (residency: {args.residency})" if args.residency != "workload" else ""),
                       "scale": args.scale},
            "gteps": gteps, "hbm_gbps_dominant_kernel": achieved, "loss": loss,
            "partition_ms": info.partition_ms, "alpha": info.alpha, "v_ori": info.v_ori, "v_ru": info.v_ru,
