@@ -192,6 +192,7 @@ def main():
     ap.add_argument("--cache", choices=["adjacent", "all"], default="adjacent",
                     help="neighbour-row buffer: reuse between adjacent chunks only, or keep every row once loaded")
     ap.add_argument("--reorder", action="store_true", help="greedy max-overlap chunk schedule (Alg. 4, phase 2)")
+    ap.add_argument("--chunks", type=int, default=0, help="number of chunks (default: the workload's)")
     ap.add_argument("--residency", choices=["workload", "auto", "h-host"], default="workload",
                     help="where the vertex tensors live: as the workload says; wherever the planner's byte budget puts them; "
                          "or h^l in pinned host memory with a^l and the gradients placed by the planner")
@@ -225,6 +226,8 @@ def main():
             print(f"[bench {time.perf_counter() - t_origin:7.1f}s] {msg}", file=sys.stderr, flush=True)
 
     w = inputs.WORKLOADS[args.workload].scaled(args.scale)
+    if args.chunks > 0:
+        w.n_chunks = args.chunks
     host = w.residency in ("host", "host_all") and args.residency == "workload"
     t_gen = time.perf_counter()
     src, dst = inputs.rmat_edges(w.V, w.E, w.graph_seed, device="cuda")

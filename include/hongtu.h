@@ -376,6 +376,15 @@ int ht_memory_model(int64_t V, int32_t n_layers, const int32_t *dims, double *ve
                     double *intermediate_bytes);
 /* Vertex rows one chunk needs resident: (1 + alpha) * V / n   (Sec. 4.3). */
 double ht_chunk_rows_model(int64_t V, int32_t n_chunks, double alpha);
+/* Communication cost of one pass over the chunks, Eq. 4 of the paper, in seconds:
+ *   C = V_+ru / T_hd + (V_ori - V_+p2p) / T_dd + (V_+p2p - V_+ru) / T_ru
+ * with the volumes in rows of bytes_per_row bytes and the three throughputs
+ * (host link, GPU-to-GPU, in-place reuse) in bytes per second.  On one GPU
+ * V_+p2p = V_ori and the middle term is void.  Returns -1 for a non-positive
+ * throughput whose term is not void, or volumes that do not satisfy
+ * v_ru <= v_p2p <= v_ori. */
+double ht_comm_cost_model(int64_t v_ori, int64_t v_p2p, int64_t v_ru, int64_t bytes_per_row, double t_hd,
+                          double t_dd, double t_ru);
 
 #ifdef __cplusplus
 }

@@ -106,7 +106,7 @@ class ht_plan_opts(C.Structure):
 EXPORTS = ["ht_ctx_create", "ht_ctx_destroy", "ht_sync", "ht_ctx_set_hbm_budget", "ht_strerror", "ht_last_error",
            "ht_partition", "ht_graph_destroy", "ht_graph_info_get", "ht_graph_chunk_info", "ht_graph_export_chunk",
            "ht_graph_export_csc", "ht_graph_chunk_order", "ht_layer_fwd", "ht_layer_bwd", "ht_epoch", "ht_epoch_buffer", "ht_tensor_to_host", "ht_memory_model",
-           "ht_chunk_rows_model", "ht_gat_layer_fwd", "ht_gat_layer_bwd", "ht_gat_epoch", "ht_gat_scores"]
+           "ht_chunk_rows_model", "ht_gat_layer_fwd", "ht_gat_layer_bwd", "ht_gat_epoch", "ht_gat_scores", "ht_comm_cost_model"]
 
 _lib = None
 
@@ -131,6 +131,8 @@ def load():
     lib.ht_last_error.argtypes = [C.c_void_p]
     lib.ht_chunk_rows_model.restype = C.c_double
     lib.ht_chunk_rows_model.argtypes = [C.c_int64, C.c_int32, C.c_double]
+    lib.ht_comm_cost_model.restype = C.c_double
+    lib.ht_comm_cost_model.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_int64, C.c_double, C.c_double, C.c_double]
     lib.ht_ctx_create.argtypes = [C.POINTER(C.c_void_p), C.c_int, C.c_void_p]
     lib.ht_ctx_destroy.argtypes = [C.c_void_p]
     lib.ht_sync.argtypes = [C.c_void_p]
@@ -360,6 +362,10 @@ def ht_gat_layer_bwd(ctx, g, d_in: int, d_out: int, act: int, H_in: torch.Tensor
                                    C.byref(dhi) if dhi is not None else None, C.c_void_p(dW.data_ptr()),
                                    _vec(da_dst, d_out), _vec(da_src, d_out), C.byref(st) if st is not None else None), ctx)
     return st
+
+
+def ht_comm_cost_model(v_ori: int, v_p2p: int, v_ru: int, bytes_per_row: int, t_hd: float, t_dd: float, t_ru: float) -> float:
+    return float(load().ht_comm_cost_model(v_ori, v_p2p, v_ru, bytes_per_row, t_hd, t_dd, t_ru))
 
 
 def ht_gat_scores(ctx, g, d_in: int, d_out: int, H_in: torch.Tensor, W: torch.Tensor, a_dst: torch.Tensor,

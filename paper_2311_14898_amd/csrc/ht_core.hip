@@ -218,4 +218,19 @@ double ht_chunk_rows_model(int64_t V, int32_t n_chunks, double alpha) {
   return (1.0 + alpha) * (double)V / (double)n_chunks;
 }
 
+double ht_comm_cost_model(int64_t v_ori, int64_t v_p2p, int64_t v_ru, int64_t bytes_per_row, double t_hd, double t_dd,
+                          double t_ru) {
+  if (v_ru < 0 || v_ru > v_p2p || v_p2p > v_ori || bytes_per_row < 0) return -1.0;
+  const double b = (double)bytes_per_row;
+  double c = 0.0;
+  const int64_t parts[3] = {v_ru, v_ori - v_p2p, v_p2p - v_ru};
+  const double thr[3] = {t_hd, t_dd, t_ru};
+  for (int k = 0; k < 3; ++k) {
+    if (parts[k] == 0) continue;
+    if (!(thr[k] > 0.0)) return -1.0;
+    c += (double)parts[k] * b / thr[k];
+  }
+  return c;
+}
+
 }  // extern "C"

@@ -35,3 +35,14 @@ def test_chunk_rows_model():
     # (1 + alpha) |V| / (m n), Sec. 4.3
     assert B.ht_chunk_rows_model(1000, 10, 2.5) == pytest.approx(350.0)
     assert B.ht_strerror_text(B.HT_ESHAPE) != ""
+
+
+def test_comm_cost_model():
+    # Eq. 4 with the Sec. 5.1 example's printed counts (11 rows after sharing between GPUs, 8 after reuse)
+    # and an arbitrary 14 rows without any dedup
+    c = B.ht_comm_cost_model(14, 11, 8, 400, 25e9, 200e9, 1500e9)
+    assert c == pytest.approx(8 * 400 / 25e9 + 3 * 400 / 200e9 + 3 * 400 / 1500e9, rel=1e-12)
+    # one GPU: the inter-GPU term is void, its throughput is not looked at
+    assert B.ht_comm_cost_model(14, 14, 8, 400, 25e9, 0.0, 1500e9) == pytest.approx(8 * 400 / 25e9 + 6 * 400 / 1500e9)
+    assert B.ht_comm_cost_model(14, 11, 12, 400, 25e9, 200e9, 1500e9) == -1.0      # v_ru > v_p2p
+    assert B.ht_comm_cost_model(14, 11, 8, 400, 0.0, 200e9, 1500e9) == -1.0        # a needed throughput is missing
