@@ -133,17 +133,52 @@ __global__ void __launch_bounds__(256) k_gat_rowstats(const int32_t* __restrict_
   }
 }
 
+// wf / r_chunk / part_r (backward pass only, nullable): wf_e = w_e f_e with f_e = LeakyReLU'(y_e), the
+// weights of the destination pass, and their sum per item (per row when the row is one item).
 __global__ void __launch_bounds__(256) k_gat_coefs(const int32_t* __restrict__ it_row, const int64_t* __restrict__ it_e0,
-                                                   const int32_t* __restrict__ it_len, int64_t n_items,
-                                                   const float* __restrict__ mult, const float* __restrict__ m_chunk,
-                                                   const float* __restrict__ zinv_chunk, float* __restrict__ w) {
+                                                   const int32_t* __restrict__ it_len, const int32_t* __restrict__ it_part,
+                                                   int64_t n_items, const float* __restrict__ mult,
+                                                   const float* __restrict__ m_chunk, const float* __restrict__ zinv_chunk,
+                                                   float slope, float* __restrict__ w, float* __restrict__ wf,
+                                                   float* __restrict__ r_chunk, float* __restrict__ part_r) {
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t t = (int64_t)blockIdx.x * 4 + wave;
   if (t >= n_items) return;
   const int32_t r = it_row[t], len = it_len[t];
   const int64_t e0 = it_e0[t];
   const float m = m_chunk[r], zinv = zinv_chunk[r];
-  for (int32_t k = lane; k < len; k += 64) w[e0 + k] = (mult ? mult[e0 + k] : 1.f) * expf(w[e0 + k] - m) * zinv;
+  float rs = 0.f;
+  for (int32_t k = lane; k < len; k += 64) {
+    const float x = w[e0 + k];       // the score LeakyReLU(y_e): same sign as y_e
+    const float c = (mult ? mult[e0 + k] : 1.f) * expf(x - m) * zinv;
+    w[e0 + k] = c;
+    if (wf) {
+      const float cf = c * (x > 0.f ? 1.f : slope);
+      wf[e0 + k] = cf;
+      rs += cf;
+    }
+  }
+  if (wf) {
+    rs = wave_sum(rs);
+    if (lane == 0) {
+      const int32_t part = it_part[t];
+      if (part >= 0) part_r[part] = rs;
+      else r_chunk[r] = rs;
+    }
+  }
+}
+
+// dp_v = dz_v . Q_v - S_v r_v; a wave per row of the chunk
+__global__ void __launch_bounds__(256) k_gat_dp(const float* __restrict__ dz, const float* __restrict__ Q, int64_t ld, int d,
+                                                const float* __restrict__ S, const float* __restrict__ r_chunk, int64_t rows,
+                                                float* __restrict__ dp_chunk) {
+  const int lane = threadIdx.x & 63;
+  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  float s = 0.f;
+  for (int c = lane; c < d; c += 64) s = fmaf(dz[r * ld + c], Q[r * ld + c], s);
+  s = wave_sum(s);
+  if (lane == 0) dp_chunk[r] = s - S[r] * r_chunk[r];
 }
 
 // dz = dh * [h > 0] (or dh), pad columns zero, and S_v = dz_v . h_v; a wave per row of the chunk
@@ -169,166 +204,31 @@ __global__ void __launch_bounds__(256) k_gat_dz(const float* __restrict__ dh, in
 }
 
 struct GatPass {
-  // items of the pass (rows = destinations of the chunk, or local sources)
+  // items of the source pass (rows = local sources of the chunk)
   const int32_t* it_row; const int64_t* it_e0; const int32_t* it_len; const int32_t* it_part; int64_t n_items;
-  const int32_t* idx;        // per entry: row of `mat` to read (global source id / local destination)
-  const float* w;            // destination pass: coefficient per entry (destination order)
-  const float* mult;         // source pass: multiplicity per entry (nullable: 1)
-  const float* mat;          // rows gathered per entry: t (destination pass) or dz of the chunk (source pass)
+  const int32_t* idx;        // per entry: local destination = row of `mat` to read
+  const float* mult;         // multiplicity per entry (nullable: 1)
+  const float* mat;          // rows gathered per entry: dz of the chunk
   int64_t mat_ld;
-  const float* own;          // the item's own row: dz of the chunk (destination pass) or t (source pass)
+  const float* own;          // the item's own row: t
   int64_t own_ld;
-  const int32_t* own_idx;    // row r -> row of `own` (nullable: r)
+  const int32_t* own_idx;    // row r -> row of `own`
   int d;
   const float* p; const float* q;        // per vertex
-  const float* m; const float* zinv;     // per vertex (source pass recomputes coefficients from them)
+  const float* m; const float* zinv;     // per vertex: the coefficients are recomputed from them
   const float* S;            // per row of the chunk
   int64_t dst0;              // first destination of the chunk
   float slope;
   // outputs
-  float* dp_chunk;           // destination pass: dp of rows without a partial
-  float* spart;              // scalar partial per cut item
-  float* out; int64_t out_ld; const int32_t* out_idx;   // source pass: dt rows (accumulated), scalar in column sc_col
-  float* partial;            // source pass: [n_part x out_ld] partial rows of cut items
+  float* out; int64_t out_ld; const int32_t* out_idx;   // dt rows (accumulated), scalar in column sc_col
+  float* partial;            // [n_part x out_ld] partial rows of cut items
   int sc_col;
 };
 
-// Destination pass.  dp_v = sum_e w_e f_e (dz_v . t_u - S_v) with f_e = LeakyReLU'(y_e); regrouped as
-//   dp_v = dz_v . (sum_e w_e f_e t_u) - S_v sum_e w_e f_e
-// it is an aggregation of rows of t with the weights w_e f_e and one dot product per item.
-// A wave per item; four rows of t are in flight per lane.
-template <int VPL>
-__global__ void __launch_bounds__(256) k_gat_dst(GatPass a) {
-  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int64_t t = (int64_t)blockIdx.x * 4 + wave;
-  if (t >= a.n_items) return;
-  const int32_t r = a.it_row[t];
-  const int64_t e0 = a.it_e0[t];
-  const int32_t len = a.it_len[t], part = a.it_part[t];
-  float4 Q[VPL];
-#pragma unroll
-  for (int j = 0; j < VPL; ++j) Q[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-  const float pv = a.p[a.dst0 + r];
-  float rsum = 0.f;
-  for (int32_t base = 0; base < len; base += 64) {
-    const int32_t nh = (len - base) < 64 ? (len - base) : 64;
-    int32_t my_u = 0;
-    float my_wf = 0.f;
-    if (lane < nh) {
-      my_u = a.idx[e0 + base + lane];
-      my_wf = a.w[e0 + base + lane] * (pv + a.q[my_u] > 0.f ? 1.f : a.slope);
-    }
-    rsum += wave_sum(my_wf);
-    for (int32_t k = 0; k < nh; k += 4) {
-      int32_t c[4];
-      float w[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int kc = (k + u) < nh ? (k + u) : (nh - 1);
-        c[u] = __builtin_amdgcn_readlane(my_u, kc);
-        w[u] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_wf), kc));
-        if (k + u >= nh) w[u] = 0.f;
-      }
-      float4 x[4][VPL];
-#pragma unroll
-      for (int u = 0; u < 4; ++u)
-#pragma unroll
-        for (int j = 0; j < VPL; ++j) {
-          const int cc = (j * 64 + lane) * 4;
-          x[u][j] = cc < a.d ? ld4(a.mat + (int64_t)c[u] * a.mat_ld + cc) : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
-#pragma unroll
-      for (int u = 0; u < 4; ++u)
-#pragma unroll
-        for (int j = 0; j < VPL; ++j) {
-          Q[j].x = fmaf(w[u], x[u][j].x, Q[j].x);
-          Q[j].y = fmaf(w[u], x[u][j].y, Q[j].y);
-          Q[j].z = fmaf(w[u], x[u][j].z, Q[j].z);
-          Q[j].w = fmaf(w[u], x[u][j].w, Q[j].w);
-        }
-    }
-  }
-  float s = 0.f;
-#pragma unroll
-  for (int j = 0; j < VPL; ++j) {
-    const int c = (j * 64 + lane) * 4;
-    if (c < a.d) {
-      const float4 mine = ld4(a.own + (int64_t)r * a.own_ld + c);   // pads of dz are zero
-      s = fmaf(mine.x, Q[j].x, fmaf(mine.y, Q[j].y, fmaf(mine.z, Q[j].z, fmaf(mine.w, Q[j].w, s))));
-    }
-  }
-  s = wave_sum(s);
-  if (lane == 0) {
-    const float acc = s - a.S[r] * rsum;
-    if (part >= 0) a.spart[part] = acc;
-    else a.dp_chunk[r] = acc;
-  }
-}
-
-// The same pass for rows of at most G float4: the wave splits into 64 / G lane groups that
-// take interleaved entries; the groups' sums meet in the final dot product.
-template <int G>
-__global__ void __launch_bounds__(256) k_gat_dst_g(GatPass a) {
-  constexpr int NG = 64 / G;
-  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int64_t t = (int64_t)blockIdx.x * 4 + wave;
-  if (t >= a.n_items) return;
-  const int32_t r = a.it_row[t];
-  const int64_t e0 = a.it_e0[t];
-  const int32_t len = a.it_len[t], part = a.it_part[t];
-  const int grp = lane / G, c4 = (lane % G) * 4;
-  const bool has = c4 < a.d;
-  const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
-  float4 Q = zero;
-  const float pv = a.p[a.dst0 + r];
-  float rsum = 0.f;
-  for (int32_t base = 0; base < len; base += 64) {
-    const int32_t nh = (len - base) < 64 ? (len - base) : 64;
-    int32_t my_u = 0;
-    float my_wf = 0.f;
-    if (lane < nh) {
-      my_u = a.idx[e0 + base + lane];
-      my_wf = a.w[e0 + base + lane] * (pv + a.q[my_u] > 0.f ? 1.f : a.slope);
-    }
-    rsum += wave_sum(my_wf);
-    for (int32_t k = 0; k < nh; k += 4 * NG) {
-      float4 x[4];
-      float w[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int ent = k + u * NG + grp;
-        const int kc = ent < nh ? ent : (nh - 1);
-        const int32_t c = __shfl(my_u, kc, 64);
-        w[u] = __shfl(my_wf, kc, 64);
-        if (ent >= nh) w[u] = 0.f;
-        x[u] = has ? ld4(a.mat + (int64_t)c * a.mat_ld + c4) : zero;
-      }
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        Q.x = fmaf(w[u], x[u].x, Q.x);
-        Q.y = fmaf(w[u], x[u].y, Q.y);
-        Q.z = fmaf(w[u], x[u].z, Q.z);
-        Q.w = fmaf(w[u], x[u].w, Q.w);
-      }
-    }
-  }
-  float s = 0.f;
-  if (has) {
-    const float4 mine = ld4(a.own + (int64_t)r * a.own_ld + c4);
-    s = fmaf(mine.x, Q.x, fmaf(mine.y, Q.y, fmaf(mine.z, Q.z, mine.w * Q.w)));
-  }
-  s = wave_sum(s);
-  if (lane == 0) {
-    const float acc = s - a.S[r] * rsum;
-    if (part >= 0) a.spart[part] = acc;
-    else a.dp_chunk[r] = acc;
-  }
-}
-
-// dp of the rows cut into several items: a wave per row adds the item sums (lanes 64 apart, then lane order)
+// per-row sums of rows cut into several items: a wave per row adds the item sums (lanes 64 apart, then lane order)
 __global__ void __launch_bounds__(256) k_gat_fix_scalar(const int32_t* __restrict__ fx_row, const int32_t* __restrict__ fx_part0,
                                                         const int32_t* __restrict__ fx_nseg, int64_t n_fix,
-                                                        const float* __restrict__ spart, float* __restrict__ dp_chunk) {
+                                                        const float* __restrict__ spart, float* __restrict__ row_sum) {
   const int lane = threadIdx.x & 63;
   const int64_t f = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (f >= n_fix) return;
@@ -336,7 +236,7 @@ __global__ void __launch_bounds__(256) k_gat_fix_scalar(const int32_t* __restric
   float s = 0.f;
   for (int32_t k = lane; k < ns; k += 64) s += spart[p0 + k];
   s = wave_sum(s);
-  if (lane == 0) dp_chunk[fx_row[f]] = s;
+  if (lane == 0) row_sum[fx_row[f]] = s;
 }
 
 // Source pass: for local source i (vertex u) over its entries (u -> v) of the chunk, w_e recomputed:
@@ -533,7 +433,7 @@ __global__ void k_gat_split(const float* __restrict__ da4, int d, float* __restr
 }
 
 struct GatWs {
-  float *T, *p, *q, *m, *zinv, *S, *dp, *pq4, *w;
+  float *T, *p, *q, *m, *zinv, *S, *dp, *r, *pq4, *w, *wf;
   int64_t ld_t;
 };
 
@@ -562,10 +462,13 @@ int prepare(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const ht_te
   ws->ld_t = ht_row_pitch(desc->d_out, true);
   HT_TRY(ht_scratch(ctx, HT_S_TFULL, (size_t)V * ws->ld_t * 4, (void**)&ws->T));
   float* vec = nullptr;
-  HT_TRY(ht_scratch(ctx, HT_S_GATV, (size_t)V * 10 * 4, (void**)&vec));
+  HT_TRY(ht_scratch(ctx, HT_S_GATV, (size_t)V * 12 * 4, (void**)&vec));
   ws->p = vec; ws->q = vec + V; ws->m = vec + 2 * V; ws->zinv = vec + 3 * V; ws->S = vec + 4 * V; ws->dp = vec + 5 * V;
-  ws->pq4 = vec + 6 * V;
-  HT_TRY(ht_scratch(ctx, HT_S_GATE, (size_t)std::max<int64_t>(g->max_nnz, 1) * 4, (void**)&ws->w));
+  ws->r = vec + 6 * V;
+  ws->pq4 = vec + 8 * V;      // 16-byte aligned whatever V is
+  const size_t ne = (size_t)std::max<int64_t>(g->max_nnz, 1);
+  HT_TRY(ht_scratch(ctx, HT_S_GATE, ne * 4 * (backward ? 2 : 1), (void**)&ws->w));
+  ws->wf = backward ? ws->w + ne : nullptr;
   if (ws->ld_t != desc->d_out) HT_TRY(ht_fill_zero(ctx, s, ws->T, (size_t)g->V * ws->ld_t * 4));
   const int64_t step = (int64_t)1 << 22;
   for (int64_t r0 = 0; r0 < g->V; r0 += step) {
@@ -580,12 +483,11 @@ int prepare(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const ht_te
     k_gat_pq<<<(unsigned)((g->V + 3) / 4), 256, 0, s>>>(ws->T, ws->ld_t, desc->d_out, a_dst, a_src, g->V, ws->p, ws->q);
     HT_LAUNCH_CHECK(ctx);
   }
-  (void)backward;
   return HT_OK;
 }
 
 int softmax_chunk(ht_ctx* ctx, const ht_graph* g, const ChunkMeta& c, const ht_gat_desc* desc, const GatWs& ws, ht_stats* st,
-                  Timer* tm) {
+                  Timer* tm, bool backward) {
   const int32_t* col = g->merged ? g->ucol.p + c.ue0 : g->col.p + c.e0;
   const float* mult = g->merged ? g->umult.p + c.ue0 : nullptr;
   const ItemSet& it = c.fwd;
@@ -593,8 +495,10 @@ int softmax_chunk(ht_ctx* ctx, const ht_graph* g, const ChunkMeta& c, const ht_g
   HT_TRY(ht_fill_zero(ctx, ctx->stream, ws.zinv + c.dst0, (size_t)(c.dst1 - c.dst0) * 4));
   if (it.n_items == 0) return HT_OK;
   float* part = nullptr;
-  HT_TRY(ht_scratch(ctx, HT_S_GATP, (size_t)std::max<int64_t>(g->max_fpart, 1) * 2 * 4, (void**)&part));
+  HT_TRY(ht_scratch(ctx, HT_S_GATP, (size_t)std::max<int64_t>(g->max_fpart, 1) * 3 * 4, (void**)&part));
   float* part_s = part + std::max<int64_t>(g->max_fpart, 1);
+  float* part_r = part_s + std::max<int64_t>(g->max_fpart, 1);
+  if (backward) HT_TRY(ht_fill_zero(ctx, ctx->stream, ws.r + c.dst0, (size_t)(c.dst1 - c.dst0) * 4));
   const unsigned nb = (unsigned)((it.n_items + 3) / 4);
   tm->begin(&st->t_gat_softmax_ms);
   k_gat_scores<<<nb, 256, 0, ctx->stream>>>(it.row, it.e0, it.len, it.part, it.n_items, col, mult, ws.p + c.dst0, ws.q,
@@ -602,23 +506,16 @@ int softmax_chunk(ht_ctx* ctx, const ht_graph* g, const ChunkMeta& c, const ht_g
   if (it.n_fix > 0)
     k_gat_rowstats<<<(unsigned)((it.n_fix + 3) / 4), 256, 0, ctx->stream>>>(it.fx_row, it.fx_part0, it.fx_nseg, it.n_fix,
                                                                                part, part_s, ws.m + c.dst0, ws.zinv + c.dst0);
-  k_gat_coefs<<<nb, 256, 0, ctx->stream>>>(it.row, it.e0, it.len, it.n_items, mult, ws.m + c.dst0, ws.zinv + c.dst0, ws.w);
+  k_gat_coefs<<<nb, 256, 0, ctx->stream>>>(it.row, it.e0, it.len, it.part, it.n_items, mult, ws.m + c.dst0, ws.zinv + c.dst0,
+                                           desc->slope, ws.w, backward ? ws.wf : nullptr, ws.r + c.dst0, part_r);
+  if (backward && it.n_fix > 0)
+    k_gat_fix_scalar<<<(unsigned)((it.n_fix + 3) / 4), 256, 0, ctx->stream>>>(it.fx_row, it.fx_part0, it.fx_nseg, it.n_fix, part_r,
+                                                                             ws.r + c.dst0);
   tm->end();
   HT_LAUNCH_CHECK(ctx);
   return HT_OK;
 }
 
-int launch_dst(ht_ctx* ctx, const GatPass& a, int nvec) {
-  const unsigned nb = (unsigned)((a.n_items + 3) / 4);
-  if (nvec <= 8) k_gat_dst_g<8><<<nb, 256, 0, ctx->stream>>>(a);
-  else if (nvec <= 16) k_gat_dst_g<16><<<nb, 256, 0, ctx->stream>>>(a);
-  else if (nvec <= 32) k_gat_dst_g<32><<<nb, 256, 0, ctx->stream>>>(a);
-  else if (nvec <= 64) k_gat_dst<1><<<nb, 256, 0, ctx->stream>>>(a);
-  else if (nvec <= 128) k_gat_dst<2><<<nb, 256, 0, ctx->stream>>>(a);
-  else k_gat_dst<4><<<nb, 256, 0, ctx->stream>>>(a);
-  HT_LAUNCH_CHECK(ctx);
-  return HT_OK;
-}
 int launch_src(ht_ctx* ctx, const GatPass& a, int nvec) {
   const unsigned nb = (unsigned)((a.n_items + 3) / 4);
   if (nvec <= 8) k_gat_src_g<8><<<nb, 256, 0, ctx->stream>>>(a);
@@ -642,7 +539,7 @@ int gat_fwd_impl(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const 
   for (int j = 0; j < g->n; ++j) {
     const ChunkMeta& c = g->chunks[j];
     if (c.dst1 == c.dst0) continue;
-    HT_TRY(softmax_chunk(ctx, g, c, desc, ws, local, tm));
+    HT_TRY(softmax_chunk(ctx, g, c, desc, ws, local, tm, false));
     float* partial = nullptr;
     if (c.fwd.n_part > 0) HT_TRY(ht_scratch(ctx, HT_S_SPART, (size_t)g->max_fpart * H_out->ld * 4, (void**)&partial));
     SpmmArgs a{};
@@ -683,35 +580,41 @@ int gat_bwd_impl(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const 
   const int sc_col = (int)ws.ld_t;              // the scalar column block sits behind the padded data columns
   const int64_t ld_dt = ws.ld_t + 4;
   const int64_t mx = std::max<int64_t>(g->max_ndst, 1);
-  float *dT = nullptr, *dz = nullptr, *spart = nullptr, *da4 = nullptr;
+  float *dT = nullptr, *dz = nullptr, *Q = nullptr, *da4 = nullptr;
   HT_TRY(ht_scratch(ctx, HT_S_TFULL2, (size_t)std::max<int64_t>(g->V, 1) * ld_dt * 4, (void**)&dT));
   HT_TRY(ht_scratch(ctx, HT_S_DZCHUNK, (size_t)mx * ws.ld_t * 4, (void**)&dz));
-  HT_TRY(ht_scratch(ctx, HT_S_MISC, (size_t)(std::max<int64_t>(g->max_fpart, 1) + (int64_t)d * 4) * 4, (void**)&spart));
-  da4 = spart + std::max<int64_t>(g->max_fpart, 1);
+  HT_TRY(ht_scratch(ctx, HT_S_ACHUNK, (size_t)mx * ws.ld_t * 4, (void**)&Q));
+  HT_TRY(ht_scratch(ctx, HT_S_MISC, (size_t)d * 16, (void**)&da4));
   HT_TRY(ht_fill_zero(ctx, st, dT, (size_t)g->V * ld_dt * 4));
   for (int j = 0; j < g->n; ++j) {
     const ChunkMeta& c = g->chunks[j];
     const int64_t ndst = c.dst1 - c.dst0;
     if (ndst == 0) continue;
-    HT_TRY(softmax_chunk(ctx, g, c, desc, ws, local, tm));
+    HT_TRY(softmax_chunk(ctx, g, c, desc, ws, local, tm, true));
     k_gat_dz<<<(unsigned)((ndst + 3) / 4), 256, 0, st>>>(dH_out->ptr + c.dst0 * dH_out->ld, dH_out->ld,
                                                           H_out->ptr + c.dst0 * H_out->ld, H_out->ld,
                                                           desc->act == HT_ACT_RELU, ndst, d, dz, ws.ld_t, ws.S);
     HT_LAUNCH_CHECK(ctx);
     GatPass a{};
     a.d = d; a.p = ws.p; a.q = ws.q; a.m = ws.m; a.zinv = ws.zinv; a.S = ws.S; a.dst0 = c.dst0; a.slope = desc->slope;
-    // destination pass
-    a.it_row = c.fwd.row; a.it_e0 = c.fwd.e0; a.it_len = c.fwd.len; a.it_part = c.fwd.part; a.n_items = c.fwd.n_items;
-    a.idx = g->merged ? g->ucol.p + c.ue0 : g->col.p + c.e0;
-    a.w = ws.w;
-    a.mat = ws.T; a.mat_ld = ws.ld_t;
-    a.own = dz; a.own_ld = ws.ld_t; a.own_idx = nullptr;
-    a.dp_chunk = ws.dp + c.dst0; a.spart = spart;
+    // destination pass: Q_v = sum_e w_e f_e t_u through the aggregation kernel, then dp_v = dz_v . Q_v - S_v r_v
     tm->begin(&local->t_gat_dst_ms);
-    if (a.n_items > 0) HT_TRY(launch_dst(ctx, a, nvec));
-    if (c.fwd.n_fix > 0) {
-      k_gat_fix_scalar<<<(unsigned)((c.fwd.n_fix + 3) / 4), 256, 0, st>>>(c.fwd.fx_row, c.fwd.fx_part0, c.fwd.fx_nseg,
-                                                                               c.fwd.n_fix, spart, ws.dp + c.dst0);
+    {
+      float* fpart = nullptr;
+      if (c.fwd.n_part > 0) HT_TRY(ht_scratch(ctx, HT_S_SPART, (size_t)g->max_fpart * ws.ld_t * 4, (void**)&fpart));
+      SpmmArgs q{};
+      q.it_row = c.fwd.row; q.it_e0 = c.fwd.e0; q.it_len = c.fwd.len; q.it_part = c.fwd.part; q.n_items = c.fwd.n_items;
+      q.fx_row = c.fwd.fx_row; q.fx_part0 = c.fwd.fx_part0; q.fx_nseg = c.fwd.fx_nseg; q.n_fix = c.fwd.n_fix;
+      q.n_edges = g->merged ? c.nu : c.nnz;
+      q.idx = g->merged ? g->ucol.p + c.ue0 : g->col.p + c.e0;
+      q.w_edge = ws.wf;
+      q.src = ws.T; q.src_ld = ws.ld_t; q.d = d;
+      q.out = Q; q.out_ld = ws.ld_t;
+      q.accumulate = 0;
+      q.partial = fpart;
+      HT_TRY(ht_fill_zero(ctx, st, Q, (size_t)ndst * ws.ld_t * 4));     // rows without an in-edge have no item
+      HT_TRY(ht_spmm_launch(ctx, st, q));
+      k_gat_dp<<<(unsigned)((ndst + 3) / 4), 256, 0, st>>>(dz, Q, ws.ld_t, d, ws.S, ws.r + c.dst0, ndst, ws.dp + c.dst0);
       HT_LAUNCH_CHECK(ctx);
     }
     tm->end();
@@ -720,7 +623,6 @@ int gat_bwd_impl(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const 
     if (c.bwd.n_part > 0) HT_TRY(ht_scratch(ctx, HT_S_SPART, (size_t)g->max_bpart * ld_dt * 4, (void**)&partial));
     a.it_row = c.bwd.row; a.it_e0 = c.bwd.e0; a.it_len = c.bwd.len; a.it_part = c.bwd.part; a.n_items = c.bwd.n_items;
     a.idx = g->merged ? g->usdst.p + c.ue0 : g->sdst.p + c.e0;
-    a.w = nullptr;
     a.mult = g->merged ? g->umult_bwd.p + c.ue0 : nullptr;
     a.mat = dz; a.mat_ld = ws.ld_t;
     a.own = ws.T; a.own_ld = ws.ld_t; a.own_idx = g->nbr.p + c.nbr_off;
