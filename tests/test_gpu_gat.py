@@ -91,6 +91,21 @@ def test_gat_no_input_gradient_and_other_slope(ctx, cases):
     _run(ctx, cases["multi"], 32, 64, True, seed=9, want_dhin=False, slope=0.05)
 
 
+def test_gat_partition_options(ctx):
+    # the layer does not care how the graph was chunked or scheduled
+    V = 7_001
+    src, dst = inputs.rmat_edges(V, 90_000, seed=11)
+    for kw in (dict(reorder_chunks=True), dict(balance_mode=1, cache_rows=-1), dict(add_self_loops=False)):
+        c = Case.__new__(Case)
+        c.V = V
+        c.g = B.ht_partition(ctx, V, src.cuda(), dst.cuda(), 7, **kw)
+        c.indptr, c.col = orc.csc_build(V, src.numpy(), dst.numpy(), kw.get("add_self_loops", True))
+        try:
+            _run(ctx, c, 24, 36, True, seed=13)
+        finally:
+            B.ht_graph_destroy(c.g)
+
+
 def test_gat_zero_attention_is_the_neighbour_mean(ctx, cases):
     c = cases["rmat"]
     rng = np.random.default_rng(3)
