@@ -9,11 +9,11 @@
  *                  in-edges), Sec. 5.1 step 2 (reuse / load split between
  *                  adjacently scheduled chunks), Sec. 6 (in-place buffer
  *                  positions, topology rewritten to index the buffer).
- *   ht_layer_fwd   Alg. 2 lines 1-4 (reuse + sparse load of neighbour rows),
- *                  Alg. 1 lines 8-9 (forward of one layer, output to its home),
+ *   ht_layer_fwd   Alg. 2 (reuse + sparse load of neighbour rows),
+ *                  Alg. 1 (forward of one layer, output to its home),
  *                  Eq. 2 (aggregate, then linear + ReLU).
- *   ht_layer_bwd   Alg. 1 lines 14-18 (checkpoint reload, re-forward of the
- *                  update stage, backward), Alg. 3 lines 5-8 (neighbour
+ *   ht_layer_bwd   Alg. 1 (checkpoint reload, re-forward of the
+ *                  update stage, backward), Alg. 3 (neighbour
  *                  gradients back to the gradient buffer), Sec. 2.3 (backward
  *                  of the update), Sec. 4.1 (backward of the aggregate).
  *   ht_epoch       Alg. 1 end to end with the recomputation-caching hybrid of
@@ -170,7 +170,7 @@ int ht_graph_chunk_order(const ht_graph *g, int32_t *order /*n_chunks*/);
 /* -------------------------------------------------------------------- layer */
 
 enum { HT_ACT_NONE = 0, HT_ACT_RELU = 1 };
-/* How neighbour rows reach the aggregation (Alg. 2 lines 1-4):
+/* How neighbour rows reach the aggregation (Alg. 2):
  *   HT_GATHER_AUTO    direct when H_in is in HBM, buffer otherwise
  *   HT_GATHER_DIRECT  read rows of H_in in place (H_in must be in HBM)
  *   HT_GATHER_BUFFER  keep N_j's rows in the in-place neighbour buffer: rows of

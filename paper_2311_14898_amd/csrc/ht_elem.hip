@@ -1,6 +1,6 @@
 // Small HBM-bound kernels: ReLU derivative mask (Sec. 2.3), softmax
-// cross-entropy and its gradient (the downstream task of Alg. 1 lines 10-11),
-// SGD step (Alg. 1 lines 20-21), zero fill.
+// cross-entropy and its gradient (the downstream task of Alg. 1),
+// SGD step (Alg. 1), zero fill.
 #include "ht_internal.h"
 
 namespace {

@@ -1,11 +1,11 @@
 // Per-chunk layer step, forward and backward, and the epoch built from it.
 //
-//   forward  (Alg. 1 lines 6-9, Alg. 2 lines 1-4, Eq. 2): neighbour rows reach
+//   forward  (Alg. 1, Alg. 2, Eq. 2): neighbour rows reach
 //            the aggregation either in place (tensor in HBM) or through the
 //            in-place neighbour buffer (reused rows stay, new rows are fetched
 //            from HBM or pinned host memory); aggregate; linear + ReLU; rows
 //            of a^l and h^{l+1} go to their homes.
-//   backward (Alg. 1 lines 14-19, Alg. 3 lines 5-8, Sec. 2.3, Sec. 4.2): reload
+//   backward (Alg. 1, Alg. 3, Sec. 2.3, Sec. 4.2): reload
 //            the checkpoint, recompute the update stage, grad W, grad a,
 //            aggregate backward by source; neighbour gradients accumulate in HBM
 //            while their vertex stays buffered and leave to the gradient home
@@ -71,7 +71,7 @@ int host_threads(ht_ctx* ctx) {
   return ctx->n_threads;
 }
 
-// grad[ids[k]] += rows[k] on the host cores (Alg. 3 line 7); ids are unique.
+// grad[ids[k]] += rows[k] on the host cores (Alg. 3); ids are unique.
 void cpu_accumulate(ht_ctx* ctx, float* grad, int64_t ld, const int32_t* ids, const float* rows, int64_t rows_ld,
                     int64_t n, int d) {
   const int nt = (int)std::min<int64_t>(host_threads(ctx), std::max<int64_t>(1, n / 256));
@@ -156,7 +156,7 @@ struct Pipe {
 
 // Rows of N_j \ N_{j-1} from H_in (HBM or pinned host, read in place by the
 // kernel) into their positions of the in-place neighbour buffer, scaled by s_u
-// on the way (Alg. 2 lines 2-3).
+// on the way (Alg. 2).
 int gather_chunk(Run& R, int j, const ht_tensor* H_in, const float* Hin, int d, float* nbuf, hipStream_t st) {
   const ht_graph* g = R.g;
   const ChunkMeta& c = g->chunks[j];
@@ -360,7 +360,7 @@ struct AccTask {
   int d;
 };
 
-// Host-side gradient accumulation beside the GPU work (Alg. 3 line 7).  A worker
+// Host-side gradient accumulation beside the GPU work (Alg. 3).  A worker
 // thread waits for each task's D2H event on the host and adds the rows; the
 // enqueueing thread only blocks when it is about to reuse a staging buffer whose
 // task has not finished.  (A host function enqueued in a HIP stream would do the
@@ -494,7 +494,7 @@ int layer_bwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* ckpt, con
     HT_TRY(ht_scratch(ctx, HT_S_DACHUNK, (size_t)mx * ld_i * 4, (void**)&da_chunk));
     if (gbuffer) HT_TRY(ht_scratch(ctx, HT_S_MISC, (size_t)g->cache_rows * ld_i * 4, (void**)&gbuf));
   }
-  // CPU-side accumulation (Alg. 3 line 7): host copy of the leave lists, device and pinned staging pairs
+  // CPU-side accumulation (Alg. 3): host copy of the leave lists, device and pinned staging pairs
   // Each vertex leaves a never-evicting buffer exactly once, at the end of the pass: if dH_in is known
   // to hold zeros the rows are stored straight to their home by a link kernel, no host-side add.
   const bool store_home = dH_in && gbuffer && dH_in->loc == HT_LOC_HOST_PINNED && g->keep_all && R.dhin_is_zero;
@@ -543,7 +543,7 @@ int layer_bwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* ckpt, con
     if (ndst == 0) continue;   // no destinations: no edges, no neighbours, nothing leaves
     const int b = q & 1;
     ++q;
-    // ---- inputs (Alg. 1 lines 14-16)
+    // ---- inputs (Alg. 1)
     const float* a_rows = nullptr;
     const float* dh_rows = nullptr;
     const float* ref = nullptr;
@@ -594,7 +594,7 @@ int layer_bwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* ckpt, con
     const float* dz_rows = dh_rows;
     int64_t dz_ld = dH_out->ld;
     if (relu) {
-      if (!H_out) {  // re-forward of the update stage (Alg. 1 line 17)
+      if (!H_out) {  // re-forward of the update stage (Alg. 1)
         R.tm.begin(&R.st->t_gemm_ms);
         HT_TRY(ht_gemm_nn(ctx, st, a_rows, a_ld, W, z_stage[0], ld_o, ndst, di, dn, 0));
         R.tm.end();
@@ -657,7 +657,7 @@ int layer_bwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* ckpt, con
       R.st->edges += c.nnz;
       R.st->spmm_bwd_alg_bytes += spmm_alg_bytes(c, di);
     }
-    // ---- rows that are not neighbours of the next chunk leave the gradient buffer (Alg. 3 lines 6-7)
+    // ---- rows that are not neighbours of the next chunk leave the gradient buffer (Alg. 3)
     if (dH_in && gbuffer && c.n_leave > 0) {
       if (store_home) {
         hipEvent_t ev_done = nullptr, ev_st = nullptr;
@@ -1112,7 +1112,7 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
         for (ht_tensor* t : todo) std::memset(t->ptr, 0, (size_t)t->rows * t->ld * 4);
       });
   }
-  // ---- forward (Alg. 1 lines 4-9)
+  // ---- forward (Alg. 1)
   for (int l = 0; l < L; ++l) {
     ht_layer_desc d{};
     d.d_in = model->dims[l]; d.d_out = model->dims[l + 1];
@@ -1126,7 +1126,7 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
                                   recompute ? nullptr : &ws->a[l]);
     if (rc != HT_OK) return fail(rc);
   }
-  // ---- downstream task and its gradient (Alg. 1 lines 10-11)
+  // ---- downstream task and its gradient (Alg. 1)
   {
     R.tm.begin(&R.st->t_loss_ms);
     int rc = ht_softmax_ce(ctx, ctx->stream, ws->h[L].ptr, ws->h[L].ld, labels, V, model->dims[L], ws->gh[L].ptr,
@@ -1134,7 +1134,7 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
     R.tm.end();
     if (rc != HT_OK) return fail(rc);
   }
-  // ---- backward (Alg. 1 lines 12-19)
+  // ---- backward (Alg. 1)
   for (int l = L - 1; l >= 0; --l) {
     ht_layer_desc d{};
     d.d_in = model->dims[l]; d.d_out = model->dims[l + 1];
@@ -1163,7 +1163,7 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
                                   l > 0 ? &ws->gh[l] : nullptr, ws->dW[l]);
     if (rc != HT_OK) return fail(rc);
   }
-  // ---- parameter update (Alg. 1 lines 20-21)
+  // ---- parameter update (Alg. 1)
   R.tm.begin(&R.st->t_update_ms);
   for (int l = 0; l < L; ++l) {
     int rc = ht_sgd(ctx, ctx->stream, model->W[l], ws->dW[l], (int64_t)model->dims[l] * model->dims[l + 1], model->lr);

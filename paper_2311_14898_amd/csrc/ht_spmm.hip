@@ -1,6 +1,6 @@
 // Aggregation (Eq. 2's AGGREGATE and its backward, Sec. 4.1) and the row
-// gather / scatter kernels of the in-place neighbour buffer (Alg. 2 lines 2-3,
-// Alg. 3 line 6).
+// gather / scatter kernels of the in-place neighbour buffer (Alg. 2,
+// Alg. 3).
 //
 // Aggregation: a wave owns one work item (at most HT_SEG edges of one row).
 // Features run across lanes as float4; for narrow rows a wave splits into
