@@ -39,6 +39,7 @@
 #include <cstdint>
 #include <cstring>
 #include <iterator>
+#include <set>
 #include <vector>
 
 extern "C" {
@@ -186,6 +187,85 @@ void orc_chunk_order(const int64_t* indptr, const int32_t* col, int n, const int
     }
     order[j] = best;
     placed[best] = 1;
+  }
+}
+
+// Row-buffer schedule: which neighbour rows are reused, loaded and released at
+// every chunk, for a buffer of C rows (C >= max_j |N_j|), chunks taken in the
+// given order (order[j] = chunk id at position j).
+//   policy 0  adjacent reuse (Sec. 5.1, step 2): after a chunk every row the
+//             next chunk does not need is released, whatever C is.
+//   policy 1  a row is released only when room is needed, and then the rows
+//             whose next use lies farthest ahead go first (rows never used
+//             again before all others; equal next use: smaller id first).
+//             With the whole schedule known in advance this is the paging
+//             rule that loads the fewest rows (Belady); the paper's Sec. 5.3
+//             formula is policy 0.
+// Per position j: reuse_j = N_j ^ resident, load_j = N_j \ resident (both
+// ascending), leave_j = rows released after chunk j (ascending; after the last
+// chunk everything still resident).  Lists are written back to back into
+// reuse / load / leave (each must hold sum_j |N_j| entries), counts into n_*.
+void orc_cache_schedule(const int64_t* indptr, const int32_t* col, int n, const int64_t* b, const int32_t* order,
+                        int64_t C, int policy, int64_t* n_reuse, int64_t* n_load, int64_t* n_leave, int32_t* reuse,
+                        int32_t* load, int32_t* leave) {
+  std::vector<std::vector<int32_t>> N(n);
+  for (int j = 0; j < n; ++j) {
+    const int id = order[j];
+    N[j].assign(col + indptr[b[id]], col + indptr[b[id + 1]]);
+    std::sort(N[j].begin(), N[j].end());
+    N[j].erase(std::unique(N[j].begin(), N[j].end()), N[j].end());
+  }
+  // next use of u strictly after position j: first k > j with u in N_k, else n
+  auto next_use = [&](int32_t u, int j) {
+    for (int k = j + 1; k < n; ++k)
+      if (std::binary_search(N[k].begin(), N[k].end(), u)) return k;
+    return n;
+  };
+  std::set<int32_t> resident;
+  int64_t ro = 0, lo = 0, vo = 0;
+  for (int j = 0; j < n; ++j) {
+    // room for N_j: release rows that are resident, not needed now, farthest next use first
+    if (j > 0) {
+      std::vector<int32_t> out;
+      if (policy == 0) {
+        for (int32_t u : resident)
+          if (!std::binary_search(N[j].begin(), N[j].end(), u)) out.push_back(u);
+      } else {
+        std::set<int32_t> uni(resident);
+        uni.insert(N[j].begin(), N[j].end());
+        int64_t over = (int64_t)uni.size() - C;
+        if (over > 0) {
+          std::vector<std::pair<int, int32_t>> cand;   // (-next use, id): ascending order = farthest first, then smaller id
+          for (int32_t u : resident)
+            if (!std::binary_search(N[j].begin(), N[j].end(), u)) cand.push_back({-next_use(u, j), u});
+          std::sort(cand.begin(), cand.end());
+          for (int64_t k = 0; k < over; ++k) out.push_back(cand[k].second);
+          std::sort(out.begin(), out.end());
+        }
+      }
+      n_leave[j - 1] = (int64_t)out.size();
+      for (int32_t u : out) {
+        leave[vo++] = u;
+        resident.erase(u);
+      }
+    }
+    int64_t nr = 0, nl = 0;
+    for (int32_t u : N[j]) {
+      if (resident.count(u)) {
+        reuse[ro++] = u;
+        ++nr;
+      } else {
+        load[lo++] = u;
+        ++nl;
+      }
+    }
+    n_reuse[j] = nr;
+    n_load[j] = nl;
+    resident.insert(N[j].begin(), N[j].end());
+  }
+  if (n > 0) {
+    n_leave[n - 1] = (int64_t)resident.size();
+    for (int32_t u : resident) leave[vo++] = u;
   }
 }
 

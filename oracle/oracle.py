@@ -100,6 +100,24 @@ def chunk_order(indptr: np.ndarray, col: np.ndarray, b: np.ndarray) -> np.ndarra
     return order
 
 
+def cache_schedule(indptr, col, b, order, rows: int, policy: int) -> List[Dict[str, np.ndarray]]:
+    """Per schedule position the rows reused, loaded and released (after the chunk) by a buffer of `rows` rows.
+    policy 0: adjacent reuse (Sec. 5.1); policy 1: release only for room, farthest next use first."""
+    b, order = _i64(b), _i32(order)
+    n = b.shape[0] - 1
+    tot = int(sum(len(np.unique(col[indptr[b[k]]:indptr[b[k + 1]]])) for k in range(n)))
+    nr, nl, nv = (np.zeros(n, dtype=np.int64) for _ in range(3))
+    reuse, load, leave = (np.zeros(max(tot, 1), dtype=np.int32) for _ in range(3))
+    lib().orc_cache_schedule(_p(_i64(indptr)), _p(_i32(col)), C.c_int(n), _p(b), _p(order), C.c_int64(rows), C.c_int(policy),
+                             _p(nr), _p(nl), _p(nv), _p(reuse), _p(load), _p(leave))
+    out, ro, lo, vo = [], 0, 0, 0
+    for j in range(n):
+        out.append({"reuse": reuse[ro:ro + nr[j]].copy(), "load": load[lo:lo + nl[j]].copy(),
+                    "leave": leave[vo:vo + nv[j]].copy()})
+        ro, lo, vo = ro + nr[j], lo + nl[j], vo + nv[j]
+    return out
+
+
 def norm(indptr: np.ndarray) -> np.ndarray:
     V = indptr.shape[0] - 1
     s = np.zeros(V, dtype=np.float64)

@@ -339,3 +339,105 @@ def test_chunk_order_greedy_against_python_sets():
     dst = np.array([10, 10, 10, 10, 11, 11, 12, 12, 12], dtype=np.int32)
     indptr, col = orc.csc_build(13, src, dst, add_self_loops=False)
     assert orc.chunk_order(indptr, col, np.array([0, 11, 12, 13])).tolist() == [0, 2, 1]
+
+
+# ------------------------------------------------------------------ row-buffer schedules
+
+def _tiny_chunks(rng, V, n, per):
+    """A graph whose chunk j (destination j) has the given random source set; returns CSC, bounds."""
+    src, dst = [], []
+    for j in range(n):
+        for u in rng.choice(V, size=per, replace=False):
+            src.append(u)
+            dst.append(j)
+    src, dst = np.array(src, np.int32), np.array(dst, np.int32)
+    indptr, col = orc.csc_build(max(V, n), src, dst, add_self_loops=False)
+    b = np.array(list(range(n)) + [max(V, n)], dtype=np.int64)      # chunk j = destination j (the last one takes the rest)
+    return indptr, col, b
+
+
+def test_cache_schedule_adjacent_policy_is_the_reuse_split():
+    rng = np.random.default_rng(0)
+    indptr, col, b = _tiny_chunks(rng, 30, 6, 9)
+    order = np.arange(6, dtype=np.int32)
+    sch = orc.cache_schedule(indptr, col, b, order, 9, 0)
+    N = [np.unique(col[indptr[b[j]]:indptr[b[j + 1]]]) for j in range(6)]
+    prev = np.zeros(0, np.int32)
+    for j in range(6):
+        R, Ld = orc.reuse_split(prev, N[j])
+        assert np.array_equal(sch[j]["reuse"], R) and np.array_equal(sch[j]["load"], Ld)
+        nxt = N[j + 1] if j + 1 < 6 else np.zeros(0, np.int32)
+        assert np.array_equal(sch[j]["leave"], np.setdiff1d(N[j], nxt))
+        prev = N[j]
+
+
+def _min_loads_brute_force(N, C):
+    """Fewest row loads over every way of releasing rows (depth-first over release choices)."""
+    import itertools
+    n = len(N)
+    best = [10 ** 9]
+
+    def go(j, resident, loads):
+        if loads >= best[0]:
+            return
+        if j == n:
+            best[0] = loads
+            return
+        need = set(N[j])
+        loads += len(need - resident)
+        uni = resident | need
+        over = len(uni) - C
+        if over <= 0:
+            go(j + 1, uni, loads)
+            return
+        cand = sorted(resident - need)
+        for out in itertools.combinations(cand, over):
+            go(j + 1, uni - set(out), loads)
+
+    go(0, set(), 0)
+    return best[0]
+
+
+def test_cache_schedule_farthest_next_use_loads_the_fewest_rows():
+    rng = np.random.default_rng(1)
+    for trial in range(12):
+        V, n, per = 9, 6, 4
+        indptr, col, b = _tiny_chunks(rng, V, n, per)
+        N = [sorted(set(col[indptr[b[j]]:indptr[b[j + 1]]].tolist())) for j in range(n)]
+        for C in (4, 5, 6):
+            sch = orc.cache_schedule(indptr, col, b, np.arange(n, dtype=np.int32), C, 1)
+            loads = sum(len(s["load"]) for s in sch)
+            assert loads == _min_loads_brute_force(N, C), (trial, C)
+            # never more rows than the buffer holds; every needed row is there; released rows really leave
+            resident = set()
+            for j, s in enumerate(sch):
+                assert set(s["reuse"]) <= resident and not (set(s["load"]) & resident)
+                assert sorted(set(s["reuse"]) | set(s["load"])) == N[j]
+                resident |= set(s["load"])
+                assert len(resident) <= C
+                assert set(s["leave"]) <= resident
+                if j + 1 < n:
+                    assert not (set(s["leave"]) & set(N[j + 1]))
+                resident -= set(s["leave"])
+            assert not resident
+            # the adjacent policy never loads fewer
+            adj = orc.cache_schedule(indptr, col, b, np.arange(n, dtype=np.int32), C, 0)
+            assert loads <= sum(len(s["load"]) for s in adj)
+
+
+def test_cache_schedule_large_buffer_loads_every_row_once_and_tie_break():
+    rng = np.random.default_rng(2)
+    indptr, col, b = _tiny_chunks(rng, 20, 5, 6)
+    N = [np.unique(col[indptr[b[j]]:indptr[b[j + 1]]]) for j in range(5)]
+    union = np.unique(np.concatenate(N))
+    sch = orc.cache_schedule(indptr, col, b, np.arange(5, dtype=np.int32), len(union), 1)
+    assert sum(len(s["load"]) for s in sch) == len(union)
+    assert all(len(s["leave"]) == 0 for s in sch[:-1]) and np.array_equal(sch[-1]["leave"], union)
+    # hand-made: chunks {0,1,2}, {3,4,5}, {0,1,2}... with C = 4: rows 0,1,2 all have next use 2; one may stay: the
+    # two smallest ids go first among equals
+    src = np.array([0, 1, 2, 3, 4, 5, 0, 1, 2], np.int32)
+    dst = np.array([0, 0, 0, 1, 1, 1, 2, 2, 2], np.int32)
+    indptr, col = orc.csc_build(6, src, dst, add_self_loops=False)
+    b = np.array([0, 1, 2, 6], dtype=np.int64)
+    sch = orc.cache_schedule(indptr, col, b, np.arange(3, dtype=np.int32), 4, 1)
+    assert sch[0]["leave"].tolist() == [0, 1] and sch[1]["leave"].tolist() == [3, 4, 5][:2] and sch[2]["reuse"].tolist() == [2]
