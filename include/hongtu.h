@@ -89,6 +89,15 @@ const char *ht_last_error(const ht_ctx *ctx);
 
 enum { HT_BALANCE_EDGES = 0, HT_BALANCE_VERTICES = 1 };
 enum { HT_PTR_DEVICE = 0, HT_PTR_HOST = 1 };
+/* Which rows the in-place neighbour buffer keeps between chunks:
+ *   HT_CACHE_ADJACENT  Sec. 5.1 step 2: rows of N_j ^ N_{j-1} stay, every other row is released
+ *                      after its chunk, whatever the buffer's size
+ *   HT_CACHE_FARTHEST  a row is released only when the buffer (cache_rows rows) needs the room, and
+ *                      then the rows whose next use lies farthest ahead in the chunk schedule go
+ *                      first (never used again first; equal next use: smaller id first).  The
+ *                      schedule is known when the graph is partitioned, so this is the rule that
+ *                      loads the fewest rows a buffer of that size can. */
+enum { HT_CACHE_ADJACENT = 0, HT_CACHE_FARTHEST = 1 };
 
 typedef struct {
   int32_t add_self_loops; /* 1: add one (v,v) entry per vertex                          */
@@ -101,8 +110,10 @@ typedef struct {
                              id); 0: in vertex-id order.  Chunk j below means schedule position j */
   int64_t cache_rows;     /* rows of the in-place neighbour buffer: 0 = max_j |N_j| (rows of
                              N_j ^ N_{j-1} are reused, the rest evicted, as in Sec. 5.1);
-                             > 0 = that many rows, same policy; -1 = as many rows as there are
-                             distinct sources: a row once loaded stays for the whole pass    */
+                             > 0 = that many rows (at least max_j |N_j|); -1 = as many rows as
+                             there are distinct sources: a row once loaded stays for the whole pass */
+  int32_t cache_policy;   /* HT_CACHE_* (ignored when cache_rows = -1)                     */
+  int32_t reserved;
 } ht_part_opts;
 
 /* Edge list (src[i] -> dst[i]), 0 <= id < V < 2^31, E >= 0, duplicates kept.
@@ -139,7 +150,8 @@ typedef struct {
   int64_t dst_begin, dst_end; /* V_j = [dst_begin, dst_end)  */
   int64_t nnz;                /* E'_j                        */
   int64_t n_src;              /* |N_j|                       */
-  int64_t n_reuse, n_load;    /* |N_j ^ N_{j-1}|, |N_j \ N_{j-1}| */
+  int64_t n_reuse, n_load;    /* rows of N_j already buffered / fetched (|N_j ^ N_{j-1}|, |N_j \ N_{j-1}| with HT_CACHE_ADJACENT) */
+  int64_t n_leave;            /* rows released after this chunk (after the last: all still buffered) */
 } ht_chunk_info;
 
 /* Caller-allocated host arrays to receive chunk j; any pointer may be NULL to
@@ -154,6 +166,7 @@ typedef struct {
   int32_t *reuse;     /* [n_reuse] N_j ^ N_{j-1} ascending                         */
   int32_t *load;      /* [n_load]  N_j \ N_{j-1} ascending                         */
   int32_t *slot;      /* [|N_j|]   buffer position of N_j[i]                       */
+  int32_t *leave;     /* [n_leave] rows released after this chunk, ascending       */
 } ht_chunk_host;
 
 int ht_graph_info_get(const ht_graph *g, ht_graph_info *out);

@@ -21,6 +21,7 @@ HT_EINVAL, HT_ENOMEM, HT_EHIP, HT_ESHAPE, HT_ESTATE = -1, -2, -3, -4, -5
 HT_LOC_DEVICE, HT_LOC_HOST_PINNED = 0, 1
 HT_BALANCE_EDGES, HT_BALANCE_VERTICES = 0, 1
 HT_PTR_DEVICE, HT_PTR_HOST = 0, 1
+HT_CACHE_ADJACENT, HT_CACHE_FARTHEST = 0, 1
 HT_ACT_NONE, HT_ACT_RELU = 0, 1
 HT_GATHER_AUTO, HT_GATHER_DIRECT, HT_GATHER_BUFFER = 0, 1, 2
 HT_CKPT_AGG, HT_CKPT_INPUT = 0, 1
@@ -37,7 +38,8 @@ class ht_tensor(C.Structure):
 
 class ht_part_opts(C.Structure):
     _fields_ = [("add_self_loops", C.c_int32), ("balance_mode", C.c_int32), ("ptr_loc", C.c_int32),
-                ("reorder_chunks", C.c_int32), ("cache_rows", C.c_int64)]
+                ("reorder_chunks", C.c_int32), ("cache_rows", C.c_int64), ("cache_policy", C.c_int32),
+                ("reserved", C.c_int32)]
 
 
 class ht_graph_info(C.Structure):
@@ -49,12 +51,12 @@ class ht_graph_info(C.Structure):
 
 class ht_chunk_info(C.Structure):
     _fields_ = [("dst_begin", C.c_int64), ("dst_end", C.c_int64), ("nnz", C.c_int64), ("n_src", C.c_int64),
-                ("n_reuse", C.c_int64), ("n_load", C.c_int64)]
+                ("n_reuse", C.c_int64), ("n_load", C.c_int64), ("n_leave", C.c_int64)]
 
 
 class ht_chunk_host(C.Structure):
     _fields_ = [(k, C.c_void_p) for k in
-                ("indptr", "col", "nbr", "col_local", "sptr", "sdst", "reuse", "load", "slot")]
+                ("indptr", "col", "nbr", "col_local", "sptr", "sdst", "reuse", "load", "slot", "leave")]
 
 
 class ht_layer_desc(C.Structure):
@@ -231,12 +233,13 @@ def ht_ctx_set_hbm_budget(ctx, nbytes: int):
 # ---------------------------------------------------------------- partition
 
 def ht_partition(ctx, V: int, src: torch.Tensor, dst: torch.Tensor, n_chunks: int, add_self_loops: bool = True,
-                 balance_mode: int = HT_BALANCE_EDGES, cache_rows: int = 0, reorder_chunks: bool = False):
+                 balance_mode: int = HT_BALANCE_EDGES, cache_rows: int = 0, reorder_chunks: bool = False,
+                 cache_policy: int = 0):
     assert src.dtype == torch.int32 and dst.dtype == torch.int32 and src.numel() == dst.numel()
     assert src.is_cuda == dst.is_cuda
     src, dst = src.contiguous(), dst.contiguous()
     opts = ht_part_opts(int(add_self_loops), balance_mode, HT_PTR_DEVICE if src.is_cuda else HT_PTR_HOST,
-                        int(reorder_chunks), cache_rows)
+                        int(reorder_chunks), cache_rows, cache_policy, 0)
     if src.is_cuda:
         torch.cuda.synchronize()
     g = C.c_void_p()
@@ -268,7 +271,7 @@ def ht_graph_export_chunk(g, j: int) -> dict:
             "nbr": np.zeros(ci.n_src, np.int32), "col_local": np.zeros(ci.nnz, np.int32),
             "sptr": np.zeros(ci.n_src + 1, np.int64), "sdst": np.zeros(ci.nnz, np.int32),
             "reuse": np.zeros(ci.n_reuse, np.int32), "load": np.zeros(ci.n_load, np.int32),
-            "slot": np.zeros(ci.n_src, np.int32)}
+            "slot": np.zeros(ci.n_src, np.int32), "leave": np.zeros(ci.n_leave, np.int32)}
     ch = ht_chunk_host(*[arrs[k].ctypes.data for k, _ in ht_chunk_host._fields_])
     _check(load().ht_graph_export_chunk(g, j, C.byref(ch)))
     arrs["info"] = ci

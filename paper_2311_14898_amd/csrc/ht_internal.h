@@ -206,6 +206,7 @@ struct ht_graph {
   int64_t v_ori = 0, v_ru = 0, v_load = 0;  // v_load: rows actually loaded per pass with this buffer
   int64_t max_nsrc = 0, max_ndst = 0, max_nnz = 0, max_fpart = 0, max_bpart = 0;
   int64_t cache_rows = 0;
+  int32_t cache_policy = 0;    // HT_CACHE_*
   double partition_ms = 0.0;
   mutable std::vector<int32_t> leave_host;  // host copy of `leave`, made on first use by the CPU-side adds
   int64_t hbm_bytes() const;

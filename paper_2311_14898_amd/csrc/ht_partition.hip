@@ -109,6 +109,85 @@ __global__ void k_popc3(const uint64_t* __restrict__ cur, const uint64_t* __rest
   }
 }
 
+// ---- row-buffer schedule with a known future (release for room, farthest next use first)
+// nxt[i] = position of the next chunk after j that needs N_j[i] (n: none); chunks are visited last to first
+__global__ void k_next_use(const int32_t* __restrict__ nbr, int64_t n, int32_t* __restrict__ last, int32_t j,
+                           int32_t* __restrict__ nxt) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const int32_t u = nbr[i];
+  nxt[i] = last[u];
+  last[u] = j;
+}
+__global__ void k_set_nu(const int32_t* __restrict__ nbr, int64_t n, const int32_t* __restrict__ nxt,
+                         int32_t* __restrict__ nu) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) nu[nbr[i]] = nxt[i];
+}
+// totals[0] += |R u cur|, totals[1] += |R ^ cur|
+__global__ void k_popc_union(const uint64_t* __restrict__ R, const uint64_t* __restrict__ cur, int64_t nw,
+                             unsigned long long* __restrict__ totals) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  unsigned long long a = 0, b = 0;
+  if (i < nw) {
+    a = __popcll(R[i] | cur[i]);
+    b = __popcll(R[i] & cur[i]);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    a += __shfl_down(a, o, 64);
+    b += __shfl_down(b, o, 64);
+  }
+  if ((threadIdx.x & 63) == 0) {
+    if (a) atomicAdd(&totals[0], a);
+    if (b) atomicAdd(&totals[1], b);
+  }
+}
+// hist[nu[u]] += 1 for every u in the candidate set (integer counts: order does not matter)
+__global__ void k_hist_nu(const uint64_t* __restrict__ cand, int64_t nw, const int32_t* __restrict__ nu,
+                          unsigned int* __restrict__ hist) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= nw) return;
+  uint64_t w = cand[i];
+  while (w) {
+    const int b = __ffsll((long long)w) - 1;
+    w &= w - 1;
+    atomicAdd(&hist[nu[i * 64 + b]], 1u);
+  }
+}
+// gt = candidates whose next use lies beyond t, eq = candidates whose next use is t
+__global__ void k_select_nu(const uint64_t* __restrict__ cand, int64_t nw, const int32_t* __restrict__ nu, int32_t t,
+                            uint64_t* __restrict__ gt, uint64_t* __restrict__ eq) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= nw) return;
+  uint64_t w = cand[i], g = 0, e = 0;
+  while (w) {
+    const int b = __ffsll((long long)w) - 1;
+    w &= w - 1;
+    const int32_t x = nu[i * 64 + b];
+    if (x > t) g |= 1ull << b;
+    else if (x == t) e |= 1ull << b;
+  }
+  gt[i] = g;
+  eq[i] = e;
+}
+// out |= the m members of eq with the smallest ids (pref = exclusive prefix of eq's per-word popcounts)
+__global__ void k_take_first(const uint64_t* __restrict__ eq, const int64_t* __restrict__ pref, int64_t nw, int64_t m,
+                             uint64_t* __restrict__ out) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= nw) return;
+  int64_t room = m - pref[i];
+  if (room <= 0) return;
+  uint64_t w = eq[i], keep = 0;
+  while (w && room > 0) {
+    const uint64_t low = w & (~w + 1);
+    keep |= low;
+    w ^= low;
+    --room;
+  }
+  out[i] |= keep;
+}
+
 // out[k] += popc(bms[k] & last) for every candidate bitmap k (grid.y = k)
 __global__ void k_overlap(const uint64_t* __restrict__ bms, int64_t nw, const uint64_t* __restrict__ last,
                           unsigned long long* __restrict__ out) {
@@ -132,6 +211,12 @@ __global__ void k_bm_op(const uint64_t* __restrict__ a, const uint64_t* __restri
                         uint64_t* __restrict__ out) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < nw) out[i] = op == 0 ? (a[i] & b[i]) : (a[i] & ~b[i]);
+}
+
+// a &= ~b
+__global__ void k_bm_clear(uint64_t* __restrict__ a, const uint64_t* __restrict__ b, int64_t nw) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < nw) a[i] &= ~b[i];
 }
 
 // rank of each edge's source among the set bits = its position in N_j
@@ -552,6 +637,7 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
 
   const bool keep_all = opts && opts->cache_rows == -1;   // a buffer that never evicts
   g->keep_all = keep_all;
+  const bool far_first = opts && opts->cache_policy == HT_CACHE_FARTHEST && !keep_all;   // release for room only
   const int64_t nw = ceil_div64(V, 64);
 
   // ---- chunk reorganisation (Alg. 4, phase 2; one GPU, so a batch is one chunk): the first chunk
@@ -626,39 +712,154 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
   for (int j = 0; j < n; ++j) {
     ChunkMeta& c = g->chunks[j];
     c.nsrc = (int64_t)htot[3 * j];
-    c.n_reuse = (int64_t)htot[3 * j + (keep_all ? 2 : 1)];
-    c.n_load = c.nsrc - c.n_reuse;
     c.nbr_off = g->v_ori;
     c.sptr_off = g->v_ori + j;
-    c.reuse_off = g->v_ori - g->v_load;
-    c.load_off = g->v_load;
     g->v_ori += c.nsrc;
-    g->v_load += c.n_load;
     g->v_ru += c.nsrc - (int64_t)htot[3 * j + 1];   // adjacent-chunk reuse only, as in Sec. 5.3
     g->max_nsrc = std::max(g->max_nsrc, c.nsrc);
+  }
+  int64_t C = opts ? opts->cache_rows : 0;
+  if (C <= 0) C = g->max_nsrc;
+  if (C < g->max_nsrc)
+    return ht_set_err(ctx, HT_EINVAL, "ht_partition: cache_rows %lld < max_j |N_j| = %lld", (long long)C,
+                      (long long)g->max_nsrc);
+  const size_t vo = (size_t)std::max<int64_t>(g->v_ori, 1);
+  HT_TRY(g->nbr.alloc(ctx, vo));
+
+  // ---- schedule of the buffer.  Adjacent reuse and the never-evicting buffer follow from the counts
+  // above; "farthest next use first" is simulated chunk by chunk on bitmaps: the rows released before
+  // chunk j (= leaving after chunk j-1) are kept as one bitmap per chunk for pass 2.
+  std::vector<int64_t> n_reuse(n), n_leave(n, 0);
+  DevArr<uint64_t> Ebm;      // [n x nw], row j: rows released before chunk j
+  if (!far_first) {
+    for (int j = 0; j < n; ++j) n_reuse[j] = (int64_t)htot[3 * j + (keep_all ? 2 : 1)];
+  } else {
+    DevArr<int32_t> nxt, last, nu;
+    DevArr<unsigned int> hist;
+    DevArr<unsigned long long> tot2;
+    DevArr<int32_t> cnt1;
+    DevArr<int64_t> pref1;
+    DevArr<uint64_t> eqbm;
+    HT_TRY(nxt.alloc(ctx, vo));
+    HT_TRY(last.alloc(ctx, (size_t)V));
+    HT_TRY(nu.alloc(ctx, (size_t)V));
+    HT_TRY(hist.alloc(ctx, (size_t)n + 1));
+    HT_TRY(tot2.alloc(ctx, 2));
+    HT_TRY(cnt1.alloc(ctx, nw));
+    HT_TRY(pref1.alloc(ctx, nw + 1));
+    HT_TRY(eqbm.alloc(ctx, nw));
+    HT_TRY(Ebm.alloc(ctx, (size_t)n * nw));
+    HT_HIP(ctx, hipMemsetAsync(Ebm.p, 0, (size_t)n * nw * 8, st));
+    {
+      std::vector<int32_t> init((size_t)V, n);
+      HT_HIP(ctx, hipMemcpyAsync(last.p, init.data(), (size_t)V * 4, hipMemcpyHostToDevice, st));
+      HT_HIP(ctx, hipMemcpyAsync(nu.p, init.data(), (size_t)V * 4, hipMemcpyHostToDevice, st));
+      HT_HIP(ctx, hipStreamSynchronize(st));
+    }
+    // N_j lists and next uses, last chunk first
+    for (int j = n - 1; j >= 0; --j) {
+      const ChunkMeta& c = g->chunks[j];
+      HT_HIP(ctx, hipMemsetAsync(bmA.p, 0, nw * 8, st));
+      if (c.nnz > 0) {
+        k_mark<<<nblk(c.nnz), TB, 0, st>>>(g->col.p + c.e0, c.nnz, (uint32_t*)bmA.p);
+        HT_LAUNCH_CHECK(ctx);
+      }
+      HT_TRY(ht_bitmap_prefix(ctx, bmA.p, nw, cnt1.p, pref1.p));
+      HT_TRY(ht_bitmap_expand(ctx, bmA.p, nw, pref1.p, g->nbr.p + c.nbr_off));
+      if (c.nsrc > 0) {
+        k_next_use<<<nblk(c.nsrc), TB, 0, st>>>(g->nbr.p + c.nbr_off, c.nsrc, last.p, j, nxt.p + c.nbr_off);
+        HT_LAUNCH_CHECK(ctx);
+      }
+    }
+    // forward simulation: bmR = resident rows
+    HT_HIP(ctx, hipMemsetAsync(bmR.p, 0, nw * 8, st));
+    std::vector<unsigned int> hh((size_t)n + 1);
+    for (int j = 0; j < n; ++j) {
+      const ChunkMeta& c = g->chunks[j];
+      HT_HIP(ctx, hipMemsetAsync(bmA.p, 0, nw * 8, st));
+      if (c.nnz > 0) {
+        k_mark<<<nblk(c.nnz), TB, 0, st>>>(g->col.p + c.e0, c.nnz, (uint32_t*)bmA.p);
+        HT_LAUNCH_CHECK(ctx);
+      }
+      HT_HIP(ctx, hipMemsetAsync(tot2.p, 0, 16, st));
+      k_popc_union<<<nblk(nw), TB, 0, st>>>(bmR.p, bmA.p, nw, tot2.p);
+      HT_LAUNCH_CHECK(ctx);
+      unsigned long long t2[2];
+      HT_HIP(ctx, hipMemcpyAsync(t2, tot2.p, 16, hipMemcpyDeviceToHost, st));
+      HT_HIP(ctx, hipStreamSynchronize(st));
+      n_reuse[j] = (int64_t)t2[1];
+      const int64_t over = (int64_t)t2[0] - C;
+      if (over > 0) {
+        uint64_t* E = Ebm.p + (size_t)j * nw;
+        k_bm_op<<<nblk(nw), TB, 0, st>>>(bmR.p, bmA.p, nw, 1, bmT.p);   // candidates: resident, not needed now
+        HT_LAUNCH_CHECK(ctx);
+        HT_HIP(ctx, hipMemsetAsync(hist.p, 0, ((size_t)n + 1) * 4, st));
+        k_hist_nu<<<nblk(nw), TB, 0, st>>>(bmT.p, nw, nu.p, hist.p);
+        HT_LAUNCH_CHECK(ctx);
+        HT_HIP(ctx, hipMemcpyAsync(hh.data(), hist.p, ((size_t)n + 1) * 4, hipMemcpyDeviceToHost, st));
+        HT_HIP(ctx, hipStreamSynchronize(st));
+        int32_t t = n;
+        int64_t cum = 0, m = 0;
+        for (; t >= 0; --t) {
+          if (cum + (int64_t)hh[t] >= over) {
+            m = over - cum;
+            break;
+          }
+          cum += hh[t];
+        }
+        if (t < 0) return ht_set_err(ctx, HT_ESTATE, "ht_partition: buffer schedule ran out of rows to release");
+        k_select_nu<<<nblk(nw), TB, 0, st>>>(bmT.p, nw, nu.p, t, E, eqbm.p);
+        HT_LAUNCH_CHECK(ctx);
+        HT_TRY(ht_bitmap_prefix(ctx, eqbm.p, nw, cnt1.p, pref1.p));
+        k_take_first<<<nblk(nw), TB, 0, st>>>(eqbm.p, pref1.p, nw, m, E);
+        HT_LAUNCH_CHECK(ctx);
+        k_bm_clear<<<nblk(nw), TB, 0, st>>>(bmR.p, E, nw);
+        HT_LAUNCH_CHECK(ctx);
+        n_leave[j - 1] = over;     // j > 0 here: nothing is resident before the first chunk
+      }
+      k_bm_or<<<nblk(nw), TB, 0, st>>>(bmR.p, bmA.p, nw);
+      HT_LAUNCH_CHECK(ctx);
+      if (c.nsrc > 0) {
+        k_set_nu<<<nblk(c.nsrc), TB, 0, st>>>(g->nbr.p + c.nbr_off, c.nsrc, nxt.p + c.nbr_off, nu.p);
+        HT_LAUNCH_CHECK(ctx);
+      }
+    }
+    if (n > 0) {
+      HT_HIP(ctx, hipMemsetAsync(tot2.p, 0, 16, st));
+      k_popc_union<<<nblk(nw), TB, 0, st>>>(bmR.p, bmR.p, nw, tot2.p);
+      HT_LAUNCH_CHECK(ctx);
+      unsigned long long t2[2];
+      HT_HIP(ctx, hipMemcpyAsync(t2, tot2.p, 16, hipMemcpyDeviceToHost, st));
+      HT_HIP(ctx, hipStreamSynchronize(st));
+      n_leave[n - 1] = (int64_t)t2[0];   // what is still resident leaves at the end of a pass
+    }
+  }
+  for (int j = 0; j < n; ++j) {
+    ChunkMeta& c = g->chunks[j];
+    c.n_reuse = n_reuse[j];
+    c.n_load = c.nsrc - c.n_reuse;
+    c.reuse_off = c.nbr_off - g->v_load;
+    c.load_off = g->v_load;
+    g->v_load += c.n_load;
   }
   {
     int64_t off = 0;
     for (int j = 0; j < n; ++j) {
       ChunkMeta& c = g->chunks[j];
-      if (keep_all) c.n_leave = (j + 1 < n) ? 0 : g->v_load;
+      if (far_first) c.n_leave = n_leave[j];
+      else if (keep_all) c.n_leave = (j + 1 < n) ? 0 : g->v_load;
       else c.n_leave = (j + 1 < n) ? c.nsrc - g->chunks[j + 1].n_reuse : c.nsrc;
       c.leave_off = off;
       off += c.n_leave;
     }
   }
-  int64_t C = opts ? opts->cache_rows : 0;
-  if (keep_all) C = g->v_load;
-  if (C == 0) C = g->max_nsrc;
-  if (C < g->max_nsrc)
-    return ht_set_err(ctx, HT_EINVAL, "ht_partition: cache_rows %lld < max_j |N_j| = %lld", (long long)C,
-                      (long long)g->max_nsrc);
+  if (keep_all) C = std::max<int64_t>(g->v_load, 1);
   if (C < 1) C = 1;
   g->cache_rows = C;
+  g->cache_policy = far_first ? HT_CACHE_FARTHEST : HT_CACHE_ADJACENT;
 
   // ---- arenas
-  const size_t vo = (size_t)std::max<int64_t>(g->v_ori, 1), vr = (size_t)std::max<int64_t>(g->v_load, 1);
-  HT_TRY(g->nbr.alloc(ctx, vo));
+  const size_t vr = (size_t)std::max<int64_t>(g->v_load, 1);
   HT_TRY(g->slot.alloc(ctx, vo));
   HT_TRY(g->gslot.alloc(ctx, vo));
   HT_TRY(g->sptr.alloc(ctx, vo + n));
@@ -738,8 +939,12 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
     HT_TRY(ht_bitmap_expand(ctx, bmT.p, nw, pref.p, g->load.p + c.load_off));
     if (j > 0 && !keep_all) {
       ChunkMeta& pc = g->chunks[j - 1];
-      k_bm_op<<<nblk(nw), TB, 0, st>>>(prev, cur, nw, 1, bmT.p);
-      HT_LAUNCH_CHECK(ctx);
+      if (far_first) {
+        HT_HIP(ctx, hipMemcpyAsync(bmT.p, Ebm.p + (size_t)j * nw, nw * 8, hipMemcpyDeviceToDevice, st));
+      } else {
+        k_bm_op<<<nblk(nw), TB, 0, st>>>(prev, cur, nw, 1, bmT.p);
+        HT_LAUNCH_CHECK(ctx);
+      }
       HT_TRY(ht_bitmap_prefix(ctx, bmT.p, nw, cnt_tmp.p, pref.p));
       HT_TRY(ht_bitmap_expand(ctx, bmT.p, nw, pref.p, g->leave.p + pc.leave_off));
       if (pc.n_leave > 0) {
@@ -815,7 +1020,12 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
     }
     g->max_fpart = std::max(g->max_fpart, c.fwd.n_part);
     g->max_bpart = std::max(g->max_bpart, c.bwd.n_part);
-    if (keep_all) {   // prev = every vertex seen so far
+    if (far_first) {   // prev = resident rows: minus what was released before this chunk, plus this chunk's
+      k_bm_clear<<<nblk(nw), TB, 0, st>>>(prev, Ebm.p + (size_t)j * nw, nw);
+      HT_LAUNCH_CHECK(ctx);
+      k_bm_or<<<nblk(nw), TB, 0, st>>>(prev, cur, nw);
+      HT_LAUNCH_CHECK(ctx);
+    } else if (keep_all) {   // prev = every vertex seen so far
       k_bm_or<<<nblk(nw), TB, 0, st>>>(prev, cur, nw);
       HT_LAUNCH_CHECK(ctx);
     } else {
@@ -825,7 +1035,7 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
   // what is still buffered leaves at the end of a pass
   if (n > 0) {
     ChunkMeta& lc = g->chunks[n - 1];
-    if (keep_all) {
+    if (keep_all || far_first) {
       if (lc.n_leave > 0) {
         HT_TRY(ht_bitmap_prefix(ctx, prev, nw, cnt_tmp.p, pref.p));
         HT_TRY(ht_bitmap_expand(ctx, prev, nw, pref.p, g->leave.p + lc.leave_off));
@@ -873,7 +1083,7 @@ int ht_partition(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src, const in
   if (E < 0 || (E > 0 && (!src || !dst))) return ht_set_err(ctx, HT_EINVAL, "ht_partition: bad edge list");
   if (n_chunks < 1) return ht_set_err(ctx, HT_EINVAL, "ht_partition: n_chunks must be >= 1");
   if (opts && (opts->reorder_chunks < 0 || opts->reorder_chunks > 1 || opts->balance_mode < 0 || opts->balance_mode > 1 || opts->ptr_loc < 0 || opts->ptr_loc > 1 ||
-               opts->cache_rows < -1))
+               opts->cache_rows < -1 || opts->cache_policy < 0 || opts->cache_policy > 1))
     return ht_set_err(ctx, HT_EINVAL, "ht_partition: bad options");
   HT_HIP(ctx, hipSetDevice(ctx->device));
   auto t0 = std::chrono::steady_clock::now();
@@ -925,6 +1135,7 @@ int ht_graph_chunk_info(const ht_graph* g, int32_t j, ht_chunk_info* out) {
   out->n_src = c.nsrc;
   out->n_reuse = c.n_reuse;
   out->n_load = c.n_load;
+  out->n_leave = c.n_leave;
   return HT_OK;
 }
 
@@ -946,6 +1157,7 @@ int ht_graph_export_chunk(const ht_graph* g, int32_t j, ht_chunk_host* out) {
   HT_TRY(d2h(ctx, out->reuse, g->reuse.p + c.reuse_off, c.n_reuse));
   HT_TRY(d2h(ctx, out->load, g->load.p + c.load_off, c.n_load));
   HT_TRY(d2h(ctx, out->slot, g->slot.p + c.nbr_off, c.nsrc));
+  HT_TRY(d2h(ctx, out->leave, g->leave.p + c.leave_off, c.n_leave));
   return HT_OK;
 }
 

@@ -19,10 +19,10 @@ def ctx():
 
 
 def run_epoch(ctx, w, src, dst, X, y, Ws, n_chunks=None, x_loc=B.HT_LOC_DEVICE, cache_rows=0, reorder=False,
-              update_first=(), **plan):
+              update_first=(), cache_policy=0, **plan):
     """update_first: the layers expected to run update-first (they keep no aggregate checkpoint)."""
     g = B.ht_partition(ctx, w.V, src.cuda(), dst.cuda(), n_chunks or w.n_chunks, cache_rows=cache_rows,
-                       reorder_chunks=reorder)
+                       reorder_chunks=reorder, cache_policy=cache_policy)
     try:
         Xd = B.to_matrix(X, x_loc)
         Wd = [x.clone().cuda() for x in Ws]
@@ -108,6 +108,23 @@ def test_cfg1_host_resident_keep_all_buffer(ctx, cfg1):
     assert st.rows_loaded == w.V * w.n_layers          # V rows per forward pass, not V_+ru
     out = run_epoch(ctx, w, src, dst, X, y, Ws, cache_rows=-1, gather_mode=B.HT_GATHER_BUFFER)
     compare(out, ref, w.n_layers)
+
+
+def test_cfg1_host_resident_farthest_next_use_buffer(ctx, cfg1):
+    # a buffer between the two extremes that releases rows only for room: same results, fewer rows over the link
+    w, src, dst, X, y, Ws, ref = cfg1
+    host = dict(x_loc=B.HT_LOC_HOST_PINNED, res_h=B.HT_RES_HOST, res_a=B.HT_RES_HOST, res_g=B.HT_RES_HOST)
+    base = run_epoch(ctx, w, src, dst, X, y, Ws, n_chunks=8, **host)["stats"].rows_loaded
+    last = base
+    for rows in (0, 7000, 9000):
+        out = run_epoch(ctx, w, src, dst, X, y, Ws, n_chunks=8, cache_rows=rows, cache_policy=B.HT_CACHE_FARTHEST,
+                        **host)
+        compare(out, ref, w.n_layers)
+        assert out["stats"].rows_loaded <= last
+        last = out["stats"].rows_loaded
+    assert last < base
+    compare(run_epoch(ctx, w, src, dst, X, y, Ws, n_chunks=8, cache_rows=7000, cache_policy=B.HT_CACHE_FARTHEST,
+                      reorder=True, gather_mode=B.HT_GATHER_BUFFER), ref, w.n_layers)
 
 
 def test_cfg1_buffer_mode_in_hbm_and_chunk_count_invariance(ctx, cfg1):

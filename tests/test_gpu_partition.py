@@ -91,6 +91,69 @@ def check_graph(ctx, V, src, dst, n, self_loops=True, mode=B.HT_BALANCE_EDGES, o
         B.ht_graph_destroy(g)
 
 
+def check_schedule(ctx, V, src, dst, n, rows, policy, reorder=False, mode=B.HT_BALANCE_EDGES):
+    """reuse / load / leave lists of every chunk against the oracle's row-buffer schedule, bit for bit, and the
+    buffer positions against the lists: a row keeps its position while it stays, and no two rows share one."""
+    g = B.ht_partition(ctx, V, src.cuda(), dst.cuda(), n, balance_mode=mode, cache_rows=rows, cache_policy=policy,
+                       reorder_chunks=reorder)
+    try:
+        info = B.ht_graph_info_get(g)
+        indptr, col, _, b = B.ht_graph_export_csc(g)
+        order = B.ht_graph_chunk_order(g)
+        distinct = len(np.unique(col))
+        o_rows = rows if rows > 0 else (distinct if rows == -1 else info.max_nsrc)
+        ref = orc.cache_schedule(indptr, col, b, order, max(o_rows, 1), 1 if rows == -1 else policy)
+        where = {}
+        loads = 0
+        for j in range(n):
+            ch = B.ht_graph_export_chunk(g, j)
+            for k in ("reuse", "load", "leave"):
+                assert np.array_equal(ch[k], ref[j][k]), f"chunk {j}: {k} ({len(ch[k])} vs {len(ref[j][k])})"
+            pos = dict(zip(ch["nbr"].tolist(), ch["slot"].tolist()))
+            for u in ch["reuse"].tolist():
+                assert where[u] == pos[u], f"chunk {j}: row {u} moved while it stayed"
+            for u in ch["load"].tolist():
+                assert u not in where
+                where[u] = pos[u]
+            assert len(set(where.values())) == len(where) <= info.cache_rows, f"chunk {j}: positions collide"
+            assert all(0 <= p < info.cache_rows for p in where.values())
+            for u in ch["leave"].tolist():
+                del where[u]
+            loads += len(ch["load"])
+        assert not where and info.v_load == loads
+        return loads
+    finally:
+        B.ht_graph_destroy(g)
+
+
+def test_buffer_schedule_farthest_next_use(ctx):
+    """A buffer larger than one chunk's sources that knows the chunk schedule: lists equal the oracle's, and the
+    loads fall from the adjacent-reuse count to one per distinct source as the buffer grows."""
+    rng = np.random.default_rng(11)
+    V, E = 400, 3000
+    src = torch.from_numpy(rng.integers(0, V, E).astype(np.int32))
+    dst = torch.from_numpy(rng.integers(0, V, E).astype(np.int32))
+    base = check_schedule(ctx, V, src, dst, 7, 0, B.HT_CACHE_ADJACENT)
+    assert check_schedule(ctx, V, src, dst, 7, 0, B.HT_CACHE_FARTHEST) <= base       # same room, better choice
+    prev = base
+    for rows in (300, 330, 360, 400):
+        adj = check_schedule(ctx, V, src, dst, 7, rows, B.HT_CACHE_ADJACENT)
+        assert adj == base                                        # adjacent reuse gains nothing from more room
+        far = check_schedule(ctx, V, src, dst, 7, rows, B.HT_CACHE_FARTHEST)
+        assert far <= prev
+        prev = far
+    assert prev == V                                              # every vertex has a self-loop: V distinct sources
+    assert check_schedule(ctx, V, src, dst, 7, -1, 0) == V
+    # skewed graph, reorganised schedule, ties between rows that are never needed again
+    w = inputs.WORKLOADS["cfg1"]
+    src, dst = inputs.rmat_edges(w.V, w.E, w.graph_seed)
+    for n, rows, reorder in ((8, 0, False), (8, 6000, False), (9, 7000, True), (16, 5000, True), (3, 9000, False)):
+        check_schedule(ctx, w.V, src, dst, n, rows, B.HT_CACHE_FARTHEST, reorder=reorder)
+    src, dst = hub_graph(5000, 20_000, hub_in=900, hub_out=1200, seed=3)
+    check_schedule(ctx, 5000, src, dst, 6, 0, B.HT_CACHE_FARTHEST)
+    check_schedule(ctx, 5000, src, dst, 6, 4000, B.HT_CACHE_FARTHEST, mode=B.HT_BALANCE_VERTICES)
+
+
 def test_tiny_random(ctx):
     rng = np.random.default_rng(0)
     V = 45
@@ -173,3 +236,5 @@ def test_bad_arguments(ctx):
         B.ht_partition(ctx, 3, src[:1], dst[:1], 0)     # n_chunks < 1
     with pytest.raises(B.HongtuError):
         B.ht_partition(ctx, 10, src, dst, 2, cache_rows=1)   # buffer smaller than a chunk's neighbour set
+    with pytest.raises(B.HongtuError):
+        B.ht_partition(ctx, 10, src, dst, 2, cache_policy=2)
