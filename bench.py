@@ -189,8 +189,12 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--verbose", action="store_true", help="progress lines on stderr")
-    ap.add_argument("--cache", choices=["adjacent", "all"], default="adjacent",
-                    help="neighbour-row buffer: reuse between adjacent chunks only, or keep every row once loaded")
+    ap.add_argument("--cache", choices=["adjacent", "all", "farthest"], default="adjacent",
+                    help="neighbour-row buffer: reuse between adjacent chunks only; keep every row once loaded; or "
+                         "--cache-rows rows that are released only for room, farthest next use first")
+    ap.add_argument("--cache-rows", type=float, default=0,
+                    help="rows of the buffer for --cache farthest; a value below 16 is a multiple of max_j |N_j| "
+                         "(default: exactly max_j |N_j|)")
     ap.add_argument("--reorder", action="store_true", help="greedy max-overlap chunk schedule (Alg. 4, phase 2)")
     ap.add_argument("--chunks", type=int, default=0, help="number of chunks (default: the workload's)")
     ap.add_argument("--residency", choices=["workload", "auto", "h-host"], default="workload",
@@ -239,8 +243,15 @@ def main():
     note(f"inputs generated: V={w.V} E={w.E}")
 
     ctx = B.ht_ctx_create(0)
-    g = B.ht_partition(ctx, w.V, src, dst, w.n_chunks, cache_rows=-1 if args.cache == "all" else 0,
-                       reorder_chunks=args.reorder)
+    cache_rows = -1 if args.cache == "all" else 0
+    if args.cache == "farthest" and args.cache_rows > 0:
+        cache_rows = int(args.cache_rows)
+        if args.cache_rows < 16:        # relative to the largest chunk's sources: needs a first partition to learn it
+            g0 = B.ht_partition(ctx, w.V, src, dst, w.n_chunks, reorder_chunks=args.reorder)
+            cache_rows = int(args.cache_rows * B.ht_graph_info_get(g0).max_nsrc)
+            B.ht_graph_destroy(g0)
+    g = B.ht_partition(ctx, w.V, src, dst, w.n_chunks, cache_rows=cache_rows, reorder_chunks=args.reorder,
+                       cache_policy=B.HT_CACHE_FARTHEST if args.cache == "farthest" else B.HT_CACHE_ADJACENT)
     info = B.ht_graph_info_get(g)
     note(f"partitioned in {info.partition_ms:.0f} ms: alpha={info.alpha:.2f} v_ru/V={info.v_ru / w.V:.2f} graph HBM {info.hbm_bytes / 1e9:.1f} GB")
     Xd = B.to_matrix(X, B.HT_LOC_HOST_PINNED if host else B.HT_LOC_DEVICE)
