@@ -1,0 +1,179 @@
+"""Maximum size on one GPU: the largest graph of the paper's dataset table at its full scale
+(65.6 M vertices, 3.6 billion edges, 128 chunks; the stand-in has the same counts), i.e. more than
+2^31 stored edges and about 100 GB of graph arrays in HBM.  The partition is checked on whole
+chunks against the oracle, then one layer of the widest shape (256 -> 64, ReLU) runs forward and
+backward over all 128 chunks with every tensor in HBM and is checked on sampled destination rows,
+sampled sources and sampled weight-gradient entries, each recomputed by the oracle in fp64 from the
+same inputs.
+
+The oracle never sees the whole graph: for the sampled rows the needed in-edges (out-edges) are cut
+from the edge list with torch and relabelled to a small id space; the symmetric normalisation comes
+from the full graph's in-degrees.
+"""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_2311_14898_amd import binding as B
+from paper_2311_14898_amd import inputs
+from tests.util import assert_close
+
+pytestmark = pytest.mark.gpu
+D_IN, D_OUT = 256, 64
+ROWS_PER_FILL = 1 << 22
+
+
+def _randn_rows(V, d, seed):
+    """[V, d] fp32 N(0,1) on the GPU, filled in slabs from a seeded generator."""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    t = torch.empty((V, d), dtype=torch.float32, device="cuda")
+    for r0 in range(0, V, ROWS_PER_FILL):
+        r1 = min(V, r0 + ROWS_PER_FILL)
+        t[r0:r1].normal_(generator=gen)
+    return t
+
+
+def _edges_touching(key, other, ids, V):
+    """(key, other) of the edges whose `key` endpoint is one of ids, as numpy arrays."""
+    table = torch.zeros(V, dtype=torch.bool, device="cuda")
+    table[torch.from_numpy(ids).cuda()] = True
+    k_out, o_out = [], []
+    step = 1 << 29
+    for e0 in range(0, key.numel(), step):
+        k = key[e0:e0 + step]
+        m = table[k.long()]
+        k_out.append(k[m].cpu())
+        o_out.append(other[e0:e0 + step][m].cpu())
+    return torch.cat(k_out).numpy(), torch.cat(o_out).numpy()
+
+
+def test_cfg5_full_scale_partition_and_one_layer():
+    w = inputs.WORKLOADS["cfg5"]
+    V, E, n = w.V, w.E, w.n_chunks
+    if torch.cuda.mem_get_info()[0] < 285e9:
+        pytest.skip("needs a GPU with 285 GB of free memory")
+    t_start = time.perf_counter()
+
+    def note(msg):
+        print(f"[{time.perf_counter() - t_start:6.1f}s] {msg}", flush=True)
+
+    src, dst = inputs.rmat_edges(V, E, w.graph_seed, device="cuda")
+    deg = torch.bincount(dst, minlength=V)                       # in-degrees without the self-loops
+    note(f"{src.numel()} edges generated")
+
+    ctx = B.ht_ctx_create(0)
+    g = B.ht_partition(ctx, V, src, dst, n)
+    try:
+        info = B.ht_graph_info_get(g)
+        note(f"partitioned in {info.partition_ms:.0f} ms, {info.hbm_bytes / 1e9:.0f} GB of graph arrays")
+        assert info.V == V and info.n_chunks == n and info.E_stored == E + V > 2 ** 31
+        cis = [B.ht_graph_chunk_info(g, j) for j in range(n)]
+        assert cis[0].dst_begin == 0 and cis[-1].dst_end == V
+        assert all(cis[j].dst_end == cis[j + 1].dst_begin for j in range(n - 1))
+        assert sum(c.nnz for c in cis) == E + V
+        assert sum(c.n_src for c in cis) == info.v_ori and sum(c.n_load for c in cis) == info.v_load == info.v_ru
+        assert all(c.n_reuse + c.n_load == c.n_src for c in cis) and cis[0].n_reuse == 0
+        assert max(c.n_src for c in cis) == info.max_nsrc == info.cache_rows
+        # edge balance: a boundary can overshoot its target by at most one destination's in-edges
+        max_deg = int(deg.max()) + 1
+        assert all(abs(c.nnz - (E + V) / n) <= 2 * max_deg for c in cis)
+
+        # ---- whole chunks against the oracle's dedup (a late, vertex-rich chunk and the hub-heavy second one)
+        for j in (1, n - 1):
+            ch = B.ht_graph_export_chunk(g, j)
+            ci = ch["info"]
+            nd = ci.dst_end - ci.dst_begin
+            d0 = deg[ci.dst_begin:ci.dst_end].cpu().numpy() + 1
+            assert np.array_equal(np.diff(ch["indptr"]), d0), f"chunk {j}: in-degrees"
+            o = orc.chunk_dedup(ch["indptr"], ch["col"], 0, nd)
+            for k, ok in (("nbr", "N"), ("col_local", "col_local"), ("sptr", "sptr"), ("sdst", "sdst")):
+                assert np.array_equal(ch[k], o[ok]), f"chunk {j}: {k}"
+            prev_N = B.ht_graph_export_chunk(g, j - 1)["nbr"]
+            R, Ld = orc.reuse_split(prev_N, o["N"])
+            assert np.array_equal(ch["reuse"], R) and np.array_equal(ch["load"], Ld), f"chunk {j}: reuse / load"
+            # a few destinations of this chunk against the raw edge list
+            vs = np.unique(np.concatenate([[ci.dst_begin, ci.dst_end - 1],
+                                           np.random.default_rng(j).integers(ci.dst_begin, ci.dst_end, 6)]))
+            kd, ks = _edges_touching(dst, src, vs, V)
+            for v in vs.tolist():
+                want = np.sort(np.concatenate([ks[kd == v], [v]]))
+                got = ch["col"][ch["indptr"][v - ci.dst_begin]:ch["indptr"][v - ci.dst_begin + 1]]
+                assert np.array_equal(got, want), f"in-neighbours of {v}"
+            note(f"chunk {j} checked ({ci.nnz} edges, {ci.n_src} sources)")
+            del ch, o
+
+        # ---- samples for the layer: destination rows with their in-edges, sources with their out-edges
+        rng = np.random.default_rng(9)
+        # (hubs of bounded degree: the few vertices with millions of edges would cost the CPU side minutes)
+        hub_in = int(torch.argmax(torch.where(deg <= 200_000, deg, -1)))
+        rows = np.unique(np.concatenate([rng.integers(1000, V, 40), [hub_in, V - 1]]))
+        e_dst, e_src = _edges_touching(dst, src, rows, V)
+        odeg = torch.bincount(src, minlength=V)
+        hub_out = int(torch.argmax(torch.where(odeg <= 100_000, odeg, -1)))
+        del odeg
+        us = np.unique(np.concatenate([rng.integers(1000, V, 24), [hub_out, V - 1]]))
+        o_src, o_dst = _edges_touching(src, dst, us, V)
+        del src, dst
+        torch.cuda.empty_cache()
+        note(f"samples cut: {len(e_dst)} in-edges of {len(rows)} rows, {len(o_src)} out-edges of {len(us)} sources")
+
+        def s_of(ids):      # symmetric normalisation of the full graph at these vertices, by the oracle's rule
+            d = deg[torch.from_numpy(ids).cuda()].cpu().numpy().astype(np.int64) + 1
+            return orc.norm(np.concatenate([[0], np.cumsum(d)]))
+
+        # ---- forward
+        H = _randn_rows(V, D_IN, 21)
+        Wt = inputs.glorot_weights([D_IN, D_OUT])[0]
+        Wd = Wt.cuda()
+        A = torch.empty((V, D_IN), dtype=torch.float32, device="cuda")
+        Hout = torch.empty((V, D_OUT), dtype=torch.float32, device="cuda")
+        st = B.ht_layer_fwd(ctx, g, D_IN, D_OUT, B.HT_ACT_RELU, H, Wd, Hout, A_ckpt=A, want_stats=True)
+        note(f"layer forward over {n} chunks: {st.t_total_ms:.0f} ms")
+        need = np.unique(np.concatenate([e_src, rows]))
+        c_src = np.searchsorted(need, np.concatenate([e_src, rows])).astype(np.int32)   # self-loops appended
+        c_dst = np.searchsorted(need, np.concatenate([e_dst, rows])).astype(np.int32)
+        indptr_c, col_c = orc.csc_build(len(need), c_src, c_dst, add_self_loops=False)
+        h_c = H[torch.from_numpy(need).cuda()].cpu().numpy()
+        rows_c = np.searchsorted(need, rows)
+        a_ref = orc.aggregate(indptr_c, col_c, h_c, s=s_of(need))[rows_c]
+        a_dev = A[torch.from_numpy(rows).cuda()].cpu().numpy()
+        assert_close(a_dev, a_ref, "a rows")
+        h_out_rows = Hout[torch.from_numpy(rows).cuda()].cpu().numpy()
+        assert_close(h_out_rows, np.maximum(orc.matmul(a_dev, Wt.numpy()), 0.0), "h' rows")
+        note("forward rows checked")
+        del h_c
+
+        # ---- backward from the aggregate checkpoint; grad h takes H's memory (H is not read any more)
+        dHout = _randn_rows(V, D_OUT, 22)
+        dW = torch.zeros((D_IN, D_OUT), dtype=torch.float32, device="cuda")
+        dHin = H.zero_()                              # the input gradient is accumulated into
+        st = B.ht_layer_bwd(ctx, g, D_IN, D_OUT, B.HT_ACT_RELU, A, Wd, dHout, dW, dH_in=dHin, H_out=Hout,
+                            want_stats=True)
+        note(f"layer backward: {st.t_total_ms:.0f} ms")
+        gW = dW.cpu().numpy()
+        scale = np.abs(gW).max()
+        for i, k in ((0, 0), (77, 5), (255, 63), (128, 31)):
+            a_col = A[:, i].contiguous().cpu().numpy().astype(np.float64)
+            dz_col = torch.where(Hout[:, k] > 0, dHout[:, k], torch.zeros((), device="cuda")).cpu().numpy()
+            ref = float(np.dot(a_col, dz_col.astype(np.float64)))
+            assert abs(gW[i, k] - ref) <= 1e-4 * scale, f"grad W[{i},{k}]: {gW[i, k]} vs {ref}"
+        note("weight-gradient entries checked")
+        s_us = s_of(us)
+        lo, hi = torch.aminmax(dHin)                  # (no |x| temporary: the tensor is 67 GB)
+        gscale = max(-float(lo), float(hi))
+        for q, u in enumerate(us.tolist()):
+            vs = np.concatenate([o_dst[o_src == u], [u]])
+            vt = torch.from_numpy(vs).cuda()
+            dz = torch.where(Hout[vt] > 0, dHout[vt], torch.zeros((), device="cuda")).cpu().numpy()
+            da = orc.matmul_nt(dz, Wt.numpy())
+            ref = s_us[q] * (s_of(vs)[:, None] * da).sum(axis=0)
+            got = dHin[u].cpu().numpy()
+            assert (np.abs(got - ref) <= 1e-4 * gscale).all(), f"grad h of source {u}"
+        note("source gradients checked")
+    finally:
+        B.ht_graph_destroy(g)
+        B.ht_ctx_destroy(ctx)
