@@ -143,16 +143,31 @@ __global__ void k_popc_union(const uint64_t* __restrict__ R, const uint64_t* __r
     if (b) atomicAdd(&totals[1], b);
   }
 }
-// hist[nu[u]] += 1 for every u in the candidate set (integer counts: order does not matter)
-__global__ void k_hist_nu(const uint64_t* __restrict__ cand, int64_t nw, const int32_t* __restrict__ nu,
+// hist[nu[u]] += 1 for every u in the candidate set (integer counts: order does not matter).
+// nbins <= HIST_LDS_BINS: counted per block in LDS first, so the few global bins see one add per block.
+constexpr int HIST_LDS_BINS = 4096;
+__global__ void k_hist_nu(const uint64_t* __restrict__ cand, int64_t nw, const int32_t* __restrict__ nu, int nbins,
                           unsigned int* __restrict__ hist) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= nw) return;
-  uint64_t w = cand[i];
-  while (w) {
-    const int b = __ffsll((long long)w) - 1;
-    w &= w - 1;
-    atomicAdd(&hist[nu[i * 64 + b]], 1u);
+  __shared__ unsigned int h[HIST_LDS_BINS];
+  const bool local = nbins <= HIST_LDS_BINS;
+  if (local) {
+    for (int b = threadIdx.x; b < nbins; b += blockDim.x) h[b] = 0;
+    __syncthreads();
+  }
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nw; i += (int64_t)gridDim.x * blockDim.x) {
+    uint64_t w = cand[i];
+    while (w) {
+      const int b = __ffsll((long long)w) - 1;
+      w &= w - 1;
+      const int32_t x = nu[i * 64 + b];
+      if (local) atomicAdd(&h[x], 1u);
+      else atomicAdd(&hist[x], 1u);
+    }
+  }
+  if (local) {
+    __syncthreads();
+    for (int b = threadIdx.x; b < nbins; b += blockDim.x)
+      if (h[b]) atomicAdd(&hist[b], h[b]);
   }
 }
 // gt = candidates whose next use lies beyond t, eq = candidates whose next use is t
@@ -794,7 +809,7 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
         k_bm_op<<<nblk(nw), TB, 0, st>>>(bmR.p, bmA.p, nw, 1, bmT.p);   // candidates: resident, not needed now
         HT_LAUNCH_CHECK(ctx);
         HT_HIP(ctx, hipMemsetAsync(hist.p, 0, ((size_t)n + 1) * 4, st));
-        k_hist_nu<<<nblk(nw), TB, 0, st>>>(bmT.p, nw, nu.p, hist.p);
+        k_hist_nu<<<(unsigned)std::min<int64_t>(nblk(nw), 2048), TB, 0, st>>>(bmT.p, nw, nu.p, n + 1, hist.p);
         HT_LAUNCH_CHECK(ctx);
         HT_HIP(ctx, hipMemcpyAsync(hh.data(), hist.p, ((size_t)n + 1) * 4, hipMemcpyDeviceToHost, st));
         HT_HIP(ctx, hipStreamSynchronize(st));

@@ -2,14 +2,15 @@
 (65.6 M vertices, 3.6 billion edges, 128 chunks; the stand-in has the same counts), i.e. more than
 2^31 stored edges and about 100 GB of graph arrays in HBM.  The partition is checked on whole
 chunks against the oracle, then one layer of the widest shape (256 -> 64, ReLU) runs forward and
-backward over all 128 chunks with every tensor in HBM and is checked on sampled destination rows,
-sampled sources and sampled weight-gradient entries, each recomputed by the oracle in fp64 from the
+backward over all 128 chunks with every tensor in HBM and is checked on about 1000 sampled destination
+rows, 200 sampled sources and sampled weight-gradient entries, each recomputed by the oracle in fp64 from the
 same inputs.
 
 The oracle never sees the whole graph: for the sampled rows the needed in-edges (out-edges) are cut
 from the edge list with torch and relabelled to a small id space; the symmetric normalisation comes
 from the full graph's in-degrees.
 """
+import gc
 import time
 
 import numpy as np
@@ -24,6 +25,16 @@ from tests.util import assert_close
 pytestmark = pytest.mark.gpu
 D_IN, D_OUT = 256, 64
 ROWS_PER_FILL = 1 << 22
+
+
+@pytest.fixture(autouse=True)
+def _give_back_cached_memory():
+    """torch keeps freed blocks; the library allocates with hipMalloc and needs them returned."""
+    gc.collect()
+    torch.cuda.empty_cache()
+    yield
+    gc.collect()
+    torch.cuda.empty_cache()
 
 
 def _randn_rows(V, d, seed):
@@ -110,12 +121,12 @@ def test_cfg5_full_scale_partition_and_one_layer():
         rng = np.random.default_rng(9)
         # (hubs of bounded degree: the few vertices with millions of edges would cost the CPU side minutes)
         hub_in = int(torch.argmax(torch.where(deg <= 200_000, deg, -1)))
-        rows = np.unique(np.concatenate([rng.integers(1000, V, 40), [hub_in, V - 1]]))
+        rows = np.unique(np.concatenate([rng.integers(1000, V, 1000), [hub_in, V - 1]]))
         e_dst, e_src = _edges_touching(dst, src, rows, V)
         odeg = torch.bincount(src, minlength=V)
         hub_out = int(torch.argmax(torch.where(odeg <= 100_000, odeg, -1)))
         del odeg
-        us = np.unique(np.concatenate([rng.integers(1000, V, 24), [hub_out, V - 1]]))
+        us = np.unique(np.concatenate([rng.integers(1000, V, 200), [hub_out, V - 1]]))
         o_src, o_dst = _edges_touching(src, dst, us, V)
         del src, dst
         torch.cuda.empty_cache()
@@ -176,4 +187,56 @@ def test_cfg5_full_scale_partition_and_one_layer():
         note("source gradients checked")
     finally:
         B.ht_graph_destroy(g)
+        B.ht_ctx_destroy(ctx)
+
+
+def test_cfg4_full_scale_partition_with_schedule_aware_buffer():
+    """The dataset shape with the most vertices (111 M, 1.6 billion edges, 64 chunks): partition with the buffer
+    that releases rows only for room, 1.5 x the largest chunk's sources.  One whole chunk against the oracle's
+    dedup; the buffer schedule through its invariants (the oracle's schedule needs the whole graph on the CPU)."""
+    w = inputs.WORKLOADS["cfg4"]
+    V, E, n = w.V, w.E, w.n_chunks
+    if torch.cuda.mem_get_info()[0] < 200e9:
+        pytest.skip("needs a GPU with 200 GB of free memory")
+    src, dst = inputs.rmat_edges(V, E, w.graph_seed, device="cuda")
+    ctx = B.ht_ctx_create(0)
+    g = g2 = None
+    try:
+        g = B.ht_partition(ctx, V, src, dst, n)
+        base = B.ht_graph_info_get(g)
+        cis = [B.ht_graph_chunk_info(g, j) for j in range(n)]
+        assert base.E_stored == E + V == sum(c.nnz for c in cis) and base.v_load == base.v_ru
+        j = n // 2
+        ch = B.ht_graph_export_chunk(g, j)
+        o = orc.chunk_dedup(ch["indptr"], ch["col"], 0, ch["info"].dst_end - ch["info"].dst_begin)
+        for k, ok in (("nbr", "N"), ("col_local", "col_local"), ("sptr", "sptr"), ("sdst", "sdst")):
+            assert np.array_equal(ch[k], o[ok]), f"chunk {j}: {k}"
+        R, Ld = orc.reuse_split(B.ht_graph_export_chunk(g, j - 1)["nbr"], o["N"])
+        assert np.array_equal(ch["reuse"], R) and np.array_equal(ch["load"], Ld)
+        B.ht_graph_destroy(g)
+        g = None
+        rows = int(1.5 * base.max_nsrc)
+        g2 = B.ht_partition(ctx, V, src, dst, n, cache_rows=rows, cache_policy=B.HT_CACHE_FARTHEST)
+        info = B.ht_graph_info_get(g2)
+        cis = [B.ht_graph_chunk_info(g2, j) for j in range(n)]
+        assert info.cache_rows == rows and info.v_ori == base.v_ori and info.v_ru == base.v_ru
+        assert V <= info.v_load < base.v_load                       # every vertex is a source (self-loops)
+        assert sum(c.n_load for c in cis) == info.v_load == sum(c.n_leave for c in cis)
+        resident = 0
+        for c in cis:
+            assert c.n_reuse + c.n_load == c.n_src and c.n_reuse <= resident
+            resident += c.n_load
+            assert resident <= rows
+            resident -= c.n_leave
+        assert resident == 0
+        # the rows the middle chunk finds in the buffer include those of the chunk before it
+        ch2 = B.ht_graph_export_chunk(g2, j)
+        assert np.array_equal(ch2["nbr"], o["N"]) and np.isin(R, ch2["reuse"]).all()
+        assert np.array_equal(np.sort(np.concatenate([ch2["reuse"], ch2["load"]])), o["N"])
+        print(f"rows loaded per pass: {base.v_load} (adjacent reuse) -> {info.v_load} (V = {V}), "
+              f"partition {base.partition_ms:.0f} / {info.partition_ms:.0f} ms", flush=True)
+    finally:
+        for x in (g, g2):
+            if x is not None:
+                B.ht_graph_destroy(x)
         B.ht_ctx_destroy(ctx)
