@@ -195,12 +195,12 @@ void orc_chunk_order(const int64_t* indptr, const int32_t* col, int n, const int
 // given order (order[j] = chunk id at position j).
 //   policy 0  adjacent reuse (Sec. 5.1, step 2): after a chunk every row the
 //             next chunk does not need is released, whatever C is.
-//   policy 1  a row is released only when room is needed, and then the rows
-//             whose next use lies farthest ahead go first (rows never used
-//             again before all others; equal next use: smaller id first).
-//             With the whole schedule known in advance this is the paging
-//             rule that loads the fewest rows (Belady); the paper's Sec. 5.3
-//             formula is policy 0.
+//   policy 1  a row is released right after the last chunk that needs it;
+//             a row with a later use is released only when room is needed,
+//             and then the rows whose next use lies farthest ahead go first
+//             (equal next use: smaller id first).  With the whole schedule
+//             known in advance this is the paging rule that loads the fewest
+//             rows (Belady); the paper's Sec. 5.3 formula is policy 0.
 // Per position j: reuse_j = N_j ^ resident, load_j = N_j \ resident (both
 // ascending), leave_j = rows released after chunk j (ascending; after the last
 // chunk everything still resident).  Lists are written back to back into
@@ -231,6 +231,9 @@ void orc_cache_schedule(const int64_t* indptr, const int32_t* col, int n, const 
         for (int32_t u : resident)
           if (!std::binary_search(N[j].begin(), N[j].end(), u)) out.push_back(u);
       } else {
+        for (int32_t u : resident)
+          if (next_use(u, j - 1) == n) out.push_back(u);      // not needed at position j or later
+        for (int32_t u : out) resident.erase(u);
         std::set<int32_t> uni(resident);
         uni.insert(N[j].begin(), N[j].end());
         int64_t over = (int64_t)uni.size() - C;
@@ -240,8 +243,8 @@ void orc_cache_schedule(const int64_t* indptr, const int32_t* col, int n, const 
             if (!std::binary_search(N[j].begin(), N[j].end(), u)) cand.push_back({-next_use(u, j), u});
           std::sort(cand.begin(), cand.end());
           for (int64_t k = 0; k < over; ++k) out.push_back(cand[k].second);
-          std::sort(out.begin(), out.end());
         }
+        std::sort(out.begin(), out.end());
       }
       n_leave[j - 1] = (int64_t)out.size();
       for (int32_t u : out) {

@@ -419,6 +419,9 @@ def test_cache_schedule_farthest_next_use_loads_the_fewest_rows():
                 if j + 1 < n:
                     assert not (set(s["leave"]) & set(N[j + 1]))
                 resident -= set(s["leave"])
+                # nothing stays beyond its last use
+                later = set().union(*N[j + 1:]) if j + 1 < n else set()
+                assert resident <= later
             assert not resident
             # the adjacent policy never loads fewer
             adj = orc.cache_schedule(indptr, col, b, np.arange(n, dtype=np.int32), C, 0)
@@ -432,12 +435,15 @@ def test_cache_schedule_large_buffer_loads_every_row_once_and_tie_break():
     union = np.unique(np.concatenate(N))
     sch = orc.cache_schedule(indptr, col, b, np.arange(5, dtype=np.int32), len(union), 1)
     assert sum(len(s["load"]) for s in sch) == len(union)
-    assert all(len(s["leave"]) == 0 for s in sch[:-1]) and np.array_equal(sch[-1]["leave"], union)
-    # hand-made: chunks {0,1,2}, {3,4,5}, {0,1,2}... with C = 4: rows 0,1,2 all have next use 2; one may stay: the
-    # two smallest ids go first among equals
+    last = {int(u): max(j for j in range(5) if u in N[j]) for u in union}        # room for all: a row leaves after its last use
+    for j in range(5):
+        assert sch[j]["leave"].tolist() == sorted(u for u, k in last.items() if k == j)
+    # hand-made: chunks {0,1,2}, {3,4,5}, {0,1,2} with C = 4: rows 0,1,2 all have next use 2; one may stay: the
+    # two smallest ids go first among equals; 3,4,5 are never needed again and leave after their chunk
     src = np.array([0, 1, 2, 3, 4, 5, 0, 1, 2], np.int32)
     dst = np.array([0, 0, 0, 1, 1, 1, 2, 2, 2], np.int32)
     indptr, col = orc.csc_build(6, src, dst, add_self_loops=False)
     b = np.array([0, 1, 2, 6], dtype=np.int64)
     sch = orc.cache_schedule(indptr, col, b, np.arange(3, dtype=np.int32), 4, 1)
-    assert sch[0]["leave"].tolist() == [0, 1] and sch[1]["leave"].tolist() == [3, 4, 5][:2] and sch[2]["reuse"].tolist() == [2]
+    assert sch[0]["leave"].tolist() == [0, 1] and sch[1]["leave"].tolist() == [3, 4, 5] and sch[2]["reuse"].tolist() == [2]
+    assert sch[2]["load"].tolist() == [0, 1] and sch[2]["leave"].tolist() == [0, 1, 2]
