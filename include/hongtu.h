@@ -92,11 +92,13 @@ enum { HT_PTR_DEVICE = 0, HT_PTR_HOST = 1 };
 /* Which rows the in-place neighbour buffer keeps between chunks:
  *   HT_CACHE_ADJACENT  Sec. 5.1 step 2: rows of N_j ^ N_{j-1} stay, every other row is released
  *                      after its chunk, whatever the buffer's size
- *   HT_CACHE_FARTHEST  a row is released only when the buffer (cache_rows rows) needs the room, and
- *                      then the rows whose next use lies farthest ahead in the chunk schedule go
- *                      first (never used again first; equal next use: smaller id first).  The
- *                      schedule is known when the graph is partitioned, so this is the rule that
- *                      loads the fewest rows a buffer of that size can. */
+ *   HT_CACHE_FARTHEST  a row is released right after the last chunk that needs it; a row with a
+ *                      later use is released only when the buffer (cache_rows rows) needs the
+ *                      room, and then the rows whose next use lies farthest ahead in the chunk
+ *                      schedule go first (equal next use: smaller id first).  The schedule is
+ *                      known when the graph is partitioned, so this is the rule that loads the
+ *                      fewest rows a buffer of that size can; in the backward pass the rows that
+ *                      leave (Alg. 3) are spread over the pass instead of waiting for its end. */
 enum { HT_CACHE_ADJACENT = 0, HT_CACHE_FARTHEST = 1 };
 
 typedef struct {
@@ -111,8 +113,9 @@ typedef struct {
   int64_t cache_rows;     /* rows of the in-place neighbour buffer: 0 = max_j |N_j| (rows of
                              N_j ^ N_{j-1} are reused, the rest evicted, as in Sec. 5.1);
                              > 0 = that many rows (at least max_j |N_j|); -1 = as many rows as
-                             there are distinct sources: a row once loaded stays for the whole pass */
-  int32_t cache_policy;   /* HT_CACHE_* (ignored when cache_rows = -1)                     */
+                             there are distinct sources, with HT_CACHE_FARTHEST: every row is
+                             loaded once per pass and stays until its last use               */
+  int32_t cache_policy;   /* HT_CACHE_* (cache_rows = -1 implies HT_CACHE_FARTHEST)        */
   int32_t reserved;
 } ht_part_opts;
 

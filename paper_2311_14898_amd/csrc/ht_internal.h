@@ -170,7 +170,7 @@ struct ht_graph {
   int64_t V = 0, Ep = 0;
   int32_t n = 0;
   int32_t add_self_loops = 1;
-  bool keep_all = false;       // the neighbour buffer never evicts (cache_rows = -1)
+  bool single_leave = false;   // schedule-aware buffer that loads (and so releases) every row once per pass
   DevArr<int64_t> indptr;      // [V+1]
   DevArr<int32_t> col;         // [E'] global source ids
   DevArr<float> s;             // [V] D^-1/2

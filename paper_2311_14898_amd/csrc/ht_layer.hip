@@ -495,9 +495,10 @@ int layer_bwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* ckpt, con
     if (gbuffer) HT_TRY(ht_scratch(ctx, HT_S_MISC, (size_t)g->cache_rows * ld_i * 4, (void**)&gbuf));
   }
   // CPU-side accumulation (Alg. 3): host copy of the leave lists, device and pinned staging pairs
-  // Each vertex leaves a never-evicting buffer exactly once, at the end of the pass: if dH_in is known
-  // to hold zeros the rows are stored straight to their home by a link kernel, no host-side add.
-  const bool store_home = dH_in && gbuffer && dH_in->loc == HT_LOC_HOST_PINNED && g->keep_all && R.dhin_is_zero;
+  // When the schedule loads every row once per pass, each row also leaves exactly once, after the last
+  // chunk that adds to it: if dH_in is known to hold zeros the rows are stored straight to their home
+  // by a link kernel, no host-side add.
+  const bool store_home = dH_in && gbuffer && dH_in->loc == HT_LOC_HOST_PINNED && g->single_leave && R.dhin_is_zero;
   const bool cpu_accum = dH_in && gbuffer && dH_in->loc == HT_LOC_HOST_PINNED && !store_home;
   float* dhin_gpu = nullptr;
   if (store_home) HT_TRY(gpu_ptr(ctx, dH_in, &dhin_gpu));
@@ -537,10 +538,58 @@ int layer_bwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* ckpt, con
   int n_left = 0;
   bool first = true;
   int q = 0;
+  // ---- rows that the schedule releases after a chunk leave the gradient buffer (Alg. 3)
+  hipEvent_t ev_stored = nullptr;   // the last store of leaving rows straight to their home
+  auto leave_rows = [&](const ChunkMeta& c) -> int {
+    if (!(dH_in && gbuffer && c.n_leave > 0)) return HT_OK;
+    if (store_home) {
+      hipEvent_t ev_done = nullptr, ev_st = nullptr;
+      HT_TRY(P.rec(P.s_c, &ev_done));
+      HT_TRY(P.wait(P.s_out, ev_done));
+      HT_TRY(P.link_begin(P.s_out));
+      P.used_out = true;
+      const int id = R.tm.begin_on(&R.st->t_copy_ms, P.s_out);
+      HT_TRY(ht_gather_rows(ctx, P.s_out, gbuf, ld_i, g->leave_slot.p + c.leave_off, dhin_gpu, dH_in->ld,
+                            g->leave.p + c.leave_off, c.n_leave, di, nullptr, ctx->link_blocks));
+      R.tm.end_id(id);
+      R.st->bytes_d2h += c.n_leave * (int64_t)di * 4;
+      HT_TRY(P.link_end(P.s_out));
+      HT_TRY(P.rec(P.s_out, &ev_st));
+      ev_stored = ev_st;   // waited for before the next aggregation writes freed positions, and at the end
+    } else if (!cpu_accum) {
+      HT_TRY(ht_add_rows(ctx, st, gbuf, ld_i, g->leave_slot.p + c.leave_off, dH_in->ptr, dH_in->ld,
+                         g->leave.p + c.leave_off, c.n_leave, di));
+    } else {
+      // compaction on the compute stream (the next chunk overwrites freed positions), D2H on the
+      // output stream, the add on the host beside the next chunks' GPU work
+      for (int64_t k0 = 0; k0 < c.n_leave; k0 += LEAVE_BATCH) {
+        const int64_t nk = std::min(LEAVE_BATCH, c.n_leave - k0);
+        const int64_t off = c.leave_off + k0;
+        const int r = n_left++ % NLV;
+        HT_TRY(P.wait(P.s_c, ev_leave_free[r]));
+        HT_TRY(ht_gather_rows(ctx, st, gbuf, ld_i, g->leave_slot.p + off, leave_dev[r], ld_i, nullptr, nk, di, nullptr));
+        hipEvent_t ev_comp = nullptr;
+        HT_TRY(P.rec(P.s_c, &ev_comp));
+        HT_TRY(P.wait(P.s_out, ev_comp));
+        if (n_left > NLV) worker.wait_done(n_left - NLV);   // the host has consumed leave_pin[r]
+        if (worker.failed()) return ht_set_err(ctx, HT_EHIP, "host-side accumulation: waiting for a copy failed");
+        HT_TRY(P.link_begin(P.s_out));
+        P.used_out = true;
+        HT_TRY(copy_rows(R, P.s_out, leave_pin[r], leave_dev[r], (size_t)nk * ld_i * 4, hipMemcpyDeviceToHost));
+        HT_TRY(P.link_end(P.s_out));
+        HT_TRY(P.rec(P.s_out, &ev_leave_free[r]));
+        worker.push(AccTask{ev_leave_free[r], dH_in->ptr, dH_in->ld, g->leave_host.data() + off, leave_pin[r], ld_i, nk, di});
+      }
+    }
+    return HT_OK;
+  };
   for (int j = 0; j < g->n; ++j) {
     const ChunkMeta& c = g->chunks[j];
     const int64_t ndst = c.dst1 - c.dst0;
-    if (ndst == 0) continue;   // no destinations: no edges, no neighbours, nothing leaves
+    if (ndst == 0) {   // no destinations: no edges, no neighbours; the schedule may still release rows here
+      HT_TRY(leave_rows(c));
+      continue;
+    }
     const int b = q & 1;
     ++q;
     // ---- inputs (Alg. 1)
@@ -648,6 +697,7 @@ int layer_bwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* ckpt, con
       a.accumulate = 1;
       a.partial = partial;
       a.max_slabs = ctx->slabs_bwd;
+      HT_TRY(P.wait(P.s_c, ev_stored));   // positions freed by the last store are written from here on
       HT_TRY(P.agg_begin());
       R.tm.begin(&R.st->t_spmm_bwd_ms);
       HT_TRY(ht_spmm_launch(ctx, st, a));
@@ -657,51 +707,13 @@ int layer_bwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* ckpt, con
       R.st->edges += c.nnz;
       R.st->spmm_bwd_alg_bytes += spmm_alg_bytes(c, di);
     }
-    // ---- rows that are not neighbours of the next chunk leave the gradient buffer (Alg. 3)
-    if (dH_in && gbuffer && c.n_leave > 0) {
-      if (store_home) {
-        hipEvent_t ev_done = nullptr, ev_st = nullptr;
-        HT_TRY(P.rec(P.s_c, &ev_done));
-        HT_TRY(P.wait(P.s_out, ev_done));
-        HT_TRY(P.link_begin(P.s_out));
-        P.used_out = true;
-        const int id = R.tm.begin_on(&R.st->t_copy_ms, P.s_out);
-        HT_TRY(ht_gather_rows(ctx, P.s_out, gbuf, ld_i, g->leave_slot.p + c.leave_off, dhin_gpu, dH_in->ld,
-                              g->leave.p + c.leave_off, c.n_leave, di, nullptr, ctx->link_blocks));
-        R.tm.end_id(id);
-        R.st->bytes_d2h += c.n_leave * (int64_t)di * 4;
-        HT_TRY(P.link_end(P.s_out));
-        HT_TRY(P.rec(P.s_out, &ev_st));
-        HT_TRY(P.wait(P.s_c, ev_st));   // the buffer is free again and dH_in complete for later work on the stream
-        P.used_out = false;
-      } else if (!cpu_accum) {
-        HT_TRY(ht_add_rows(ctx, st, gbuf, ld_i, g->leave_slot.p + c.leave_off, dH_in->ptr, dH_in->ld,
-                           g->leave.p + c.leave_off, c.n_leave, di));
-      } else {
-        // compaction on the compute stream (the next chunk overwrites freed positions), D2H on the
-        // output stream, the add on the host beside the next chunks' GPU work
-        for (int64_t k0 = 0; k0 < c.n_leave; k0 += LEAVE_BATCH) {
-          const int64_t nk = std::min(LEAVE_BATCH, c.n_leave - k0);
-          const int64_t off = c.leave_off + k0;
-          const int r = n_left++ % NLV;
-          HT_TRY(P.wait(P.s_c, ev_leave_free[r]));
-          HT_TRY(ht_gather_rows(ctx, st, gbuf, ld_i, g->leave_slot.p + off, leave_dev[r], ld_i, nullptr, nk, di, nullptr));
-          hipEvent_t ev_comp = nullptr;
-          HT_TRY(P.rec(P.s_c, &ev_comp));
-          HT_TRY(P.wait(P.s_out, ev_comp));
-          if (n_left > NLV) worker.wait_done(n_left - NLV);   // the host has consumed leave_pin[r]
-          if (worker.failed()) return ht_set_err(ctx, HT_EHIP, "host-side accumulation: waiting for a copy failed");
-          HT_TRY(P.link_begin(P.s_out));
-          P.used_out = true;
-          HT_TRY(copy_rows(R, P.s_out, leave_pin[r], leave_dev[r], (size_t)nk * ld_i * 4, hipMemcpyDeviceToHost));
-          HT_TRY(P.link_end(P.s_out));
-          HT_TRY(P.rec(P.s_out, &ev_leave_free[r]));
-          worker.push(AccTask{ev_leave_free[r], dH_in->ptr, dH_in->ld, g->leave_host.data() + off, leave_pin[r], ld_i, nk, di});
-        }
-      }
-    }
+    HT_TRY(leave_rows(c));
   }
   if (first) HT_TRY(ht_fill_zero(ctx, st, dW, (size_t)di * dn * 4));
+  if (store_home) {   // dH_in is complete for later work on the stream
+    HT_TRY(P.wait(P.s_c, ev_stored));
+    P.used_out = false;
+  }
   if (cpu_accum) {
     // the gradient tensor is complete once every host-side add has run
     worker.finish();
@@ -1097,7 +1109,7 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
   // touched before the backward pass, so a helper thread clears them beside the forward pass
   // instead of the GPU waiting for a memset between two layers.
   auto stored_once = [&](int l) {   // a never-evicting gradient buffer stores every row of a host-resident grad h^l exactly once
-    return g->keep_all && g->v_load == V && ws->gh[l].loc == HT_LOC_HOST_PINNED && gather_mode != HT_GATHER_DIRECT;
+    return g->single_leave && g->v_load == V && ws->gh[l].loc == HT_LOC_HOST_PINNED && gather_mode != HT_GATHER_DIRECT;
   };
   struct Joiner {
     std::thread th;

@@ -183,8 +183,20 @@ __global__ void k_select_nu(const uint64_t* __restrict__ cand, int64_t nw, const
     if (x > t) g |= 1ull << b;
     else if (x == t) e |= 1ull << b;
   }
-  gt[i] = g;
+  gt[i] |= g;      // the row may already hold the rows that left after their last use
   eq[i] = e;
+}
+// rows of N_j that no later chunk needs: set in bm, counted into *count
+__global__ void k_mark_dead(const int32_t* __restrict__ nbr, int64_t n, const int32_t* __restrict__ nxt, int32_t never,
+                            uint32_t* bm32, unsigned long long* __restrict__ count) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const bool dead = i < n && nxt[i] == never;
+  if (dead) {
+    const uint32_t u = (uint32_t)nbr[i];
+    atomicOr(&bm32[u >> 5], 1u << (u & 31));
+  }
+  const unsigned long long m = __ballot(dead);
+  if ((threadIdx.x & 63) == 0 && m) atomicAdd(count, (unsigned long long)__popcll(m));
 }
 // out |= the m members of eq with the smallest ids (pref = exclusive prefix of eq's per-word popcounts)
 __global__ void k_take_first(const uint64_t* __restrict__ eq, const int64_t* __restrict__ pref, int64_t nw, int64_t m,
@@ -650,9 +662,9 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
     g->max_nnz = std::max(g->max_nnz, c.nnz);
   }
 
-  const bool keep_all = opts && opts->cache_rows == -1;   // a buffer that never evicts
-  g->keep_all = keep_all;
-  const bool far_first = opts && opts->cache_policy == HT_CACHE_FARTHEST && !keep_all;   // release for room only
+  // a buffer with room for every distinct source is the schedule-aware buffer at that size
+  const bool keep_all = opts && opts->cache_rows == -1;
+  const bool far_first = (opts && opts->cache_policy == HT_CACHE_FARTHEST) || keep_all;
   const int64_t nw = ceil_div64(V, 64);
 
   // ---- chunk reorganisation (Alg. 4, phase 2; one GPU, so a batch is one chunk): the first chunk
@@ -733,7 +745,10 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
     g->v_ru += c.nsrc - (int64_t)htot[3 * j + 1];   // adjacent-chunk reuse only, as in Sec. 5.3
     g->max_nsrc = std::max(g->max_nsrc, c.nsrc);
   }
+  int64_t n_distinct = 0;      // |N_0 u ... u N_{n-1}|
+  for (int j = 0; j < n; ++j) n_distinct += g->chunks[j].nsrc - (int64_t)htot[3 * j + 2];
   int64_t C = opts ? opts->cache_rows : 0;
+  if (keep_all) C = n_distinct;
   if (C <= 0) C = g->max_nsrc;
   if (C < g->max_nsrc)
     return ht_set_err(ctx, HT_EINVAL, "ht_partition: cache_rows %lld < max_j |N_j| = %lld", (long long)C,
@@ -741,17 +756,18 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
   const size_t vo = (size_t)std::max<int64_t>(g->v_ori, 1);
   HT_TRY(g->nbr.alloc(ctx, vo));
 
-  // ---- schedule of the buffer.  Adjacent reuse and the never-evicting buffer follow from the counts
-  // above; "farthest next use first" is simulated chunk by chunk on bitmaps: the rows released before
-  // chunk j (= leaving after chunk j-1) are kept as one bitmap per chunk for pass 2.
+  // ---- schedule of the buffer.  Adjacent reuse follows from the counts above; the schedule-aware
+  // buffer (a row leaves after its last use, or for room with the farthest next use first) is
+  // simulated chunk by chunk on bitmaps: the rows released before chunk j (= leaving after chunk
+  // j-1) are kept as one bitmap per chunk for pass 2.
   std::vector<int64_t> n_reuse(n), n_leave(n, 0);
   DevArr<uint64_t> Ebm;      // [n x nw], row j: rows released before chunk j
   if (!far_first) {
-    for (int j = 0; j < n; ++j) n_reuse[j] = (int64_t)htot[3 * j + (keep_all ? 2 : 1)];
+    for (int j = 0; j < n; ++j) n_reuse[j] = (int64_t)htot[3 * j + 1];
   } else {
     DevArr<int32_t> nxt, last, nu;
     DevArr<unsigned int> hist;
-    DevArr<unsigned long long> tot2;
+    DevArr<unsigned long long> tot2, dead_cnt;
     DevArr<int32_t> cnt1;
     DevArr<int64_t> pref1;
     DevArr<uint64_t> eqbm;
@@ -760,6 +776,8 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
     HT_TRY(nu.alloc(ctx, (size_t)V));
     HT_TRY(hist.alloc(ctx, (size_t)n + 1));
     HT_TRY(tot2.alloc(ctx, 2));
+    HT_TRY(dead_cnt.alloc(ctx, (size_t)n));
+    HT_HIP(ctx, hipMemsetAsync(dead_cnt.p, 0, (size_t)n * 8, st));
     HT_TRY(cnt1.alloc(ctx, nw));
     HT_TRY(pref1.alloc(ctx, nw + 1));
     HT_TRY(eqbm.alloc(ctx, nw));
@@ -837,7 +855,21 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
       if (c.nsrc > 0) {
         k_set_nu<<<nblk(c.nsrc), TB, 0, st>>>(g->nbr.p + c.nbr_off, c.nsrc, nxt.p + c.nbr_off, nu.p);
         HT_LAUNCH_CHECK(ctx);
+        if (j + 1 < n) {   // rows that no later chunk needs leave now (after the last chunk everything does)
+          uint64_t* E1 = Ebm.p + (size_t)(j + 1) * nw;
+          k_mark_dead<<<nblk(c.nsrc), TB, 0, st>>>(g->nbr.p + c.nbr_off, c.nsrc, nxt.p + c.nbr_off, n, (uint32_t*)E1,
+                                                   dead_cnt.p + j);
+          HT_LAUNCH_CHECK(ctx);
+          k_bm_clear<<<nblk(nw), TB, 0, st>>>(bmR.p, E1, nw);
+          HT_LAUNCH_CHECK(ctx);
+        }
       }
+    }
+    if (n > 1) {
+      std::vector<unsigned long long> hd((size_t)n);
+      HT_HIP(ctx, hipMemcpyAsync(hd.data(), dead_cnt.p, (size_t)n * 8, hipMemcpyDeviceToHost, st));
+      HT_HIP(ctx, hipStreamSynchronize(st));
+      for (int j = 0; j + 1 < n; ++j) n_leave[j] += (int64_t)hd[j];
     }
     if (n > 0) {
       HT_HIP(ctx, hipMemsetAsync(tot2.p, 0, 16, st));
@@ -862,16 +894,15 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
     for (int j = 0; j < n; ++j) {
       ChunkMeta& c = g->chunks[j];
       if (far_first) c.n_leave = n_leave[j];
-      else if (keep_all) c.n_leave = (j + 1 < n) ? 0 : g->v_load;
       else c.n_leave = (j + 1 < n) ? c.nsrc - g->chunks[j + 1].n_reuse : c.nsrc;
       c.leave_off = off;
       off += c.n_leave;
     }
   }
-  if (keep_all) C = std::max<int64_t>(g->v_load, 1);
   if (C < 1) C = 1;
   g->cache_rows = C;
   g->cache_policy = far_first ? HT_CACHE_FARTHEST : HT_CACHE_ADJACENT;
+  g->single_leave = far_first && g->v_load == n_distinct;
 
   // ---- arenas
   const size_t vr = (size_t)std::max<int64_t>(g->v_load, 1);
@@ -952,7 +983,7 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
     HT_LAUNCH_CHECK(ctx);
     HT_TRY(ht_bitmap_prefix(ctx, bmT.p, nw, cnt_tmp.p, pref.p));
     HT_TRY(ht_bitmap_expand(ctx, bmT.p, nw, pref.p, g->load.p + c.load_off));
-    if (j > 0 && !keep_all) {
+    if (j > 0) {
       ChunkMeta& pc = g->chunks[j - 1];
       if (far_first) {
         HT_HIP(ctx, hipMemcpyAsync(bmT.p, Ebm.p + (size_t)j * nw, nw * 8, hipMemcpyDeviceToDevice, st));
@@ -1040,9 +1071,6 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
       HT_LAUNCH_CHECK(ctx);
       k_bm_or<<<nblk(nw), TB, 0, st>>>(prev, cur, nw);
       HT_LAUNCH_CHECK(ctx);
-    } else if (keep_all) {   // prev = every vertex seen so far
-      k_bm_or<<<nblk(nw), TB, 0, st>>>(prev, cur, nw);
-      HT_LAUNCH_CHECK(ctx);
     } else {
       std::swap(cur, prev);
     }
@@ -1050,7 +1078,7 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
   // what is still buffered leaves at the end of a pass
   if (n > 0) {
     ChunkMeta& lc = g->chunks[n - 1];
-    if (keep_all || far_first) {
+    if (far_first) {
       if (lc.n_leave > 0) {
         HT_TRY(ht_bitmap_prefix(ctx, prev, nw, cnt_tmp.p, pref.p));
         HT_TRY(ht_bitmap_expand(ctx, prev, nw, pref.p, g->leave.p + lc.leave_off));

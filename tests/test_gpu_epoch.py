@@ -193,6 +193,29 @@ def test_three_layers_partial_labels(ctx):
                       res_a=B.HT_RES_HOST, res_g=B.HT_RES_HOST), ref, 3)
 
 
+def test_empty_chunks_with_schedule_aware_buffer(ctx):
+    """Hub destinations swallow several edge targets, so some chunks have no destinations; the schedule may still
+    release rows at such a position (room for the chunk after it), and the backward pass must write them back."""
+    V = 900
+    rng = np.random.default_rng(4)
+    src = np.concatenate([rng.integers(0, V, 4000), rng.integers(0, V, 3000), rng.integers(0, V, 2500)])
+    dst = np.concatenate([rng.integers(0, V, 4000), np.full(3000, 300), np.full(2500, 301)])
+    keep = src != dst
+    src, dst = torch.from_numpy(src[keep].astype(np.int32)), torch.from_numpy(dst[keep].astype(np.int32))
+    w = inputs.Workload("hubs", V, int(src.numel()), [20, 16, 6], 12)
+    X, y, Ws = inputs.features(V, 20), inputs.labels(V, 6), inputs.glorot_weights(w.dims)
+    ref = oracle_epoch(w, src, dst, X, y, Ws)
+    host = dict(x_loc=B.HT_LOC_HOST_PINNED, res_h=B.HT_RES_HOST, res_a=B.HT_RES_HOST, res_g=B.HT_RES_HOST)
+    g = B.ht_partition(ctx, V, src.cuda(), dst.cuda(), w.n_chunks)
+    cis = [B.ht_graph_chunk_info(g, j) for j in range(w.n_chunks)]
+    B.ht_graph_destroy(g)
+    assert any(c.dst_end == c.dst_begin for c in cis[:-1]), "the case needs an empty chunk in the middle"
+    for kw in (dict(), dict(cache_policy=B.HT_CACHE_FARTHEST), dict(cache_rows=-1),
+               dict(cache_rows=int(1.2 * max(c.n_src for c in cis)), cache_policy=B.HT_CACHE_FARTHEST)):
+        compare(run_epoch(ctx, w, src, dst, X, y, Ws, **kw, **host), ref, w.n_layers)
+        compare(run_epoch(ctx, w, src, dst, X, y, Ws, gather_mode=B.HT_GATHER_BUFFER, **kw), ref, w.n_layers)
+
+
 def test_uniform_logits_loss_is_ln_C(ctx):
     w = inputs.WORKLOADS["cfg1"]
     src, dst, X, y, _ = inputs.make_inputs(w)

@@ -73,7 +73,7 @@ def check_graph(ctx, V, src, dst, n, self_loops=True, mode=B.HT_BALANCE_EDGES, o
             for u in R.tolist():
                 assert cur[u] == prev_slot[u], f"chunk {j}: reused vertex {u} moved"
             n_loaded += len(Ld)
-            if keep_all:      # nothing is evicted: reuse is against everything seen so far
+            if keep_all:      # room for every source: reuse is against everything seen so far
                 prev_slot.update(cur)
                 prev_N = np.union1d(prev_N, o["N"]).astype(np.int32)
             else:
@@ -83,8 +83,8 @@ def check_graph(ctx, V, src, dst, n, self_loops=True, mode=B.HT_BALANCE_EDGES, o
         assert info.v_load == n_loaded
         if not keep_all:
             assert info.v_ru == n_loaded          # |N_0| + sum |N_j \ N_{j-1}| along the schedule
-        if keep_all:
-            assert len(set(prev_slot.values())) == len(prev_slot) == info.cache_rows == len(prev_N)
+        if keep_all:      # (positions are reused once a row has left after its last use: check_schedule covers them)
+            assert len(prev_slot) == info.cache_rows == len(prev_N)
         else:
             assert info.cache_rows == (cache_rows or max(max_nsrc, 1)) and info.v_load == info.v_ru
     finally:
