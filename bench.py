@@ -87,7 +87,8 @@ def gat_epoch_flops(w):
 
 
 def main_gat(args):
-    """GAT (Eq. 3, one head per layer) on the same workload: epochs of ht_gat_epoch, everything in HBM."""
+    """GAT (Eq. 3, one head per layer) on the same workload: epochs of ht_gat_epoch; vertex data in HBM, or (the
+    workload says "host", or --residency h-host) X, h^l and grad h^l in pinned host memory."""
     import numpy as np
     import torch
     from paper_2311_14898_amd import binding as B
@@ -102,15 +103,17 @@ def main_gat(args):
     ctx = B.ht_ctx_create(0)
     g = B.ht_partition(ctx, w.V, src, dst, w.n_chunks)
     info = B.ht_graph_info_get(g)
-    Xd, yd = B.to_matrix(X, B.HT_LOC_DEVICE), y.cuda()
+    host = args.residency == "h-host" or (args.residency == "workload" and w.residency != "hbm")
+    res_h = B.HT_RES_HOST if host else B.HT_RES_HBM
+    Xd, yd = B.to_matrix(X, B.HT_LOC_HOST_PINNED if host else B.HT_LOC_DEVICE), y.cuda()
     Wd, ad, asd = [x.clone().cuda() for x in Ws], [x.clone().cuda() for x in a_dst], [x.clone().cuda() for x in a_src]
     for _ in range(args.warmup):
-        B.ht_gat_epoch(ctx, g, w.dims, Wd, ad, asd, w.lr, Xd, yd)
+        B.ht_gat_epoch(ctx, g, w.dims, Wd, ad, asd, w.lr, Xd, yd, res_h=res_h)
     torch.cuda.synchronize()
     tot = None
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        loss, st = B.ht_gat_epoch(ctx, g, w.dims, Wd, ad, asd, w.lr, Xd, yd, want_stats=True)
+        loss, st = B.ht_gat_epoch(ctx, g, w.dims, Wd, ad, asd, w.lr, Xd, yd, want_stats=True, res_h=res_h)
         d = st.as_dict()
         if tot is None:
             tot = d
@@ -126,11 +129,13 @@ def main_gat(args):
            "warmup": args.warmup, "ms_per_step": 1e3 * elapsed / K, "higher_is_better": False, "scaling": "weak",
            "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": f"{w.name}: {L}-layer GAT (one head), R-MAT V={w.V} E={w.E} (+{w.V} self-loops), dims "
-                                  f"{'-'.join(map(str, w.dims))}, {w.n_chunks} chunks, vertex data in HBM", "scale": args.scale},
+                                  f"{'-'.join(map(str, w.dims))}, {w.n_chunks} chunks, vertex data in "
+                                  f"{'pinned host memory (t = HW of a layer in HBM)' if host else 'HBM'}", "scale": args.scale},
            "loss": loss, "gteps": tot["edges"] / elapsed / 1e9,
+           "bytes_h2d_per_step": tot["bytes_h2d"] / K, "bytes_d2h_per_step": tot["bytes_d2h"] / K,
            "phase_ms_per_step": {"softmax": tot["t_gat_softmax_ms"] / K, "aggregate_fwd": tot["t_spmm_fwd_ms"] / K,
                                  "destination_pass": tot["t_gat_dst_ms"] / K, "source_pass": src_ms,
-                                 "gemm": tot["t_gemm_ms"] / K, "loss": tot["t_loss_ms"] / K},
+                                 "gemm": tot["t_gemm_ms"] / K, "loss": tot["t_loss_ms"] / K, "link_copies": tot["t_copy_ms"] / K},
            "agg_fwd_layer_ms_per_step": [x / K for x in tot["t_agg_fwd_layer_ms"][:L]],
            "gemm_tflops": tot["gemm_flops"] / max(tot["t_gemm_ms"] * 1e-3, 1e-12) / 1e12,
            "epoch_gflop": gat_epoch_flops(w) / 1e9,

@@ -289,9 +289,12 @@ typedef struct {
   float slope;         /* LeakyReLU slope for y <= 0, in [0, 1]     */
 } ht_gat_desc;
 
-/* Forward over all chunks.  H_in [V x d_in], H_out [V x d_out]: HBM (HT_ESHAPE
- * otherwise).  W [d_in x d_out] row-major dense, a_dst, a_src [d_out]: device.
- * Nothing of size O(E) and no parameterised row outlives the call. */
+/* Forward over all chunks.  H_in [V x d_in], H_out [V x d_out]: HBM or pinned
+ * host memory.  W [d_in x d_out] row-major dense, a_dst, a_src [d_out]: device.
+ * The parameterised rows t = H W of all vertices are held in HBM during the
+ * call ([V x d_out] of library scratch), so a host-resident tensor is read or
+ * written once, in contiguous row ranges, and no neighbour row crosses the
+ * host link.  Nothing of size O(E) and no parameterised row outlives the call. */
 int ht_gat_layer_fwd(ht_ctx *ctx, const ht_graph *g, const ht_gat_desc *desc, const ht_tensor *H_in,
                      const float *W, const float *a_dst, const float *a_src, ht_tensor *H_out,
                      ht_stats *stats);
@@ -301,8 +304,10 @@ int ht_gat_layer_fwd(ht_ctx *ctx, const ht_graph *g, const ht_gat_desc *desc, co
  * scores and the coefficients are computed again, then
  *   dz = dH_out * [H_out > 0] (no mask when act = none)
  *   dW, da_dst, da_src: overwritten;  dH_in (nullable): ACCUMULATED into.
- * H_out is the forward result (also read for the softmax's backward); all
- * vertex tensors in HBM; dW [d_in x d_out], da_dst, da_src [d_out]: device. */
+ * H_out is the forward result (also read for the softmax's backward); every
+ * vertex tensor in HBM or pinned host memory (host-resident ones are staged in
+ * contiguous row ranges; dt [V x d_out] is library scratch in HBM);
+ * dW [d_in x d_out], da_dst, da_src [d_out]: device. */
 int ht_gat_layer_bwd(ht_ctx *ctx, const ht_graph *g, const ht_gat_desc *desc, const ht_tensor *H_in,
                      const float *W, const float *a_dst, const float *a_src, const ht_tensor *H_out,
                      const ht_tensor *dH_out, ht_tensor *dH_in, float *dW, float *da_dst, float *da_src,
@@ -316,9 +321,13 @@ int ht_gat_layer_bwd(ht_ctx *ctx, const ht_graph *g, const ht_gat_desc *desc, co
 int ht_gat_scores(ht_ctx *ctx, const ht_graph *g, const ht_gat_desc *desc, const ht_tensor *H_in,
                   const float *W, const float *a_dst, const float *a_src, float *p_host, float *q_host);
 
+/* where a class of vertex tensors lives (also used by ht_plan_opts below) */
+enum { HT_RES_AUTO = 0, HT_RES_HBM = 1, HT_RES_HOST = 2 };
 typedef struct {
   int32_t n_layers;    /* <= HT_MAX_LAYERS                                  */
-  int32_t reserved;
+  int32_t res_h;       /* HT_RES_AUTO / HT_RES_HBM: h^l, grad h^l in HBM;
+                          HT_RES_HOST: h^1..h^{L-1} and their gradients in
+                          pinned host memory (library-owned)                */
   const int32_t *dims; /* host, n_layers + 1 widths                         */
   float *const *W;     /* host arrays of n_layers device pointers, in/out   */
   float *const *a_dst; /* [dims[l+1]] each                                  */
@@ -327,17 +336,16 @@ typedef struct {
   float slope;
 } ht_gat_model;
 
-/* Alg. 1 with GAT layers, every tensor in HBM: forward (ReLU between layers,
- * none after the last), softmax cross-entropy over labelled vertices
- * (labels[v] >= 0, device int32 [V]), backward with each layer's intermediates
- * recomputed from its input, W -= lr dW and a -= lr da.  X [V x dims[0]] HBM.
+/* Alg. 1 with GAT layers: forward (ReLU between layers, none after the
+ * last), softmax cross-entropy over labelled vertices (labels[v] >= 0, device
+ * int32 [V]), backward with each layer's intermediates recomputed from its
+ * input, W -= lr dW and a -= lr da.  X [V x dims[0]]: HBM or pinned host.
  * loss_out: host float, valid on return (the call synchronises). */
 int ht_gat_epoch(ht_ctx *ctx, const ht_graph *g, const ht_gat_model *model, const ht_tensor *X,
                  const int32_t *labels, float *loss_out, ht_stats *stats);
 
 /* -------------------------------------------------------------------- epoch */
 
-enum { HT_RES_AUTO = 0, HT_RES_HBM = 1, HT_RES_HOST = 2 };
 /* HT_INTER_AUTO picks per the byte budget; MASK keeps h^{l+1} in HBM and reads
  * ReLU' from it; HYBRID caches a^l and recomputes z = a W in the backward pass
  * (Sec. 4.2, Fig. 5(c)); RECOMPUTE keeps no a^l at all: the backward pass

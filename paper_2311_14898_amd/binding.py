@@ -95,7 +95,7 @@ class ht_gat_desc(C.Structure):
 
 
 class ht_gat_model(C.Structure):
-    _fields_ = [("n_layers", C.c_int32), ("reserved", C.c_int32), ("dims", C.POINTER(C.c_int32)),
+    _fields_ = [("n_layers", C.c_int32), ("res_h", C.c_int32), ("dims", C.POINTER(C.c_int32)),
                 ("W", C.POINTER(C.c_void_p)), ("a_dst", C.POINTER(C.c_void_p)), ("a_src", C.POINTER(C.c_void_p)),
                 ("lr", C.c_float), ("slope", C.c_float)]
 
@@ -386,8 +386,9 @@ def ht_gat_scores(ctx, g, d_in: int, d_out: int, H_in: torch.Tensor, W: torch.Te
 
 
 def ht_gat_epoch(ctx, g, dims: Sequence[int], Ws: List[torch.Tensor], a_dst: List[torch.Tensor], a_src: List[torch.Tensor],
-                 lr: float, X: torch.Tensor, labels: torch.Tensor, slope: float = 0.2, want_stats: bool = False):
-    """One GAT epoch in HBM; Ws, a_dst, a_src (device tensors) are updated in place.  Returns (loss, stats or None)."""
+                 lr: float, X: torch.Tensor, labels: torch.Tensor, slope: float = 0.2, want_stats: bool = False,
+                 res_h: int = 0):
+    """One GAT epoch; Ws, a_dst, a_src (device tensors) are updated in place.  Returns (loss, stats or None)."""
     L = len(dims) - 1
     assert len(Ws) == L and len(a_dst) == L and len(a_src) == L and labels.is_cuda and labels.dtype == torch.int32
     for l in range(L):
@@ -397,7 +398,7 @@ def ht_gat_epoch(ctx, g, dims: Sequence[int], Ws: List[torch.Tensor], a_dst: Lis
     Wp = (C.c_void_p * L)(*[w.data_ptr() for w in Ws])
     Ap = (C.c_void_p * L)(*[a.data_ptr() for a in a_dst])
     Sp = (C.c_void_p * L)(*[a.data_ptr() for a in a_src])
-    model = ht_gat_model(L, 0, dims_a, Wp, Ap, Sp, lr, slope)
+    model = ht_gat_model(L, res_h, dims_a, Wp, Ap, Sp, lr, slope)
     x = tensor_view(X, dims[0])
     loss = C.c_float(0.0)
     st = ht_stats() if want_stats else None

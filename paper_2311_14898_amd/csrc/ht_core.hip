@@ -135,6 +135,7 @@ int ht_ctx_create(ht_ctx** out, int device, void* hip_stream) {
   if (const char* v = getenv("HT_AGG_UNIFORM")) c->agg_uniform = atoi(v);
   if (const char* v = getenv("HT_SLAB_ALIGN")) c->slab_align = atoi(v);
   if (const char* v = getenv("HT_AGG_PHASES")) c->agg_phases = atoi(v) > 1 ? atoi(v) : 1;
+  if (const char* v = getenv("HT_LINK_BLOCK_ROWS")) c->link_block_rows = atoll(v) > 0 ? atoll(v) : c->link_block_rows;
   if (hip_stream) {
     c->stream = (hipStream_t)hip_stream;
   } else {
@@ -165,7 +166,7 @@ int ht_ctx_destroy(ht_ctx* ctx) {
   ht_epoch_ws_free(ctx);
   for (int i = 0; i < HT_N_SCRATCH; ++i)
     if (ctx->scratch[i]) ht_dev_free(ctx, ctx->scratch[i], ctx->scratch_bytes[i]);
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < 3; ++i)
     if (ctx->hscratch[i]) (void)hipHostFree(ctx->hscratch[i]);
   for (hipEvent_t e : ctx->ev_pool) (void)hipEventDestroy(e);
   if (ctx->own_stream) (void)hipStreamDestroy(ctx->stream);

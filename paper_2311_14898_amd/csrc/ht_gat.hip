@@ -1,5 +1,10 @@
 // GAT layer (Eq. 3), one attention head, forward and backward over the chunks
-// of a partitioned graph, all vertex tensors in HBM.
+// of a partitioned graph.  The layer's tensors H_in, H_out, dH_out, dH_in may live
+// in HBM or in pinned host memory; the parameterised rows t = H W of all vertices
+// always stay in HBM for the duration of a call, so neighbour rows never cross the
+// host link: a host-resident tensor is only ever read or written in contiguous row
+// ranges (V rows per pass instead of the sum of |N_j|), through staging pairs on
+// side streams.
 //
 //   t = H W ;  p_v = a_dst . t_v ;  q_u = a_src . t_u
 //   edge (u -> v):  y = p_v + q_u ;  x = LeakyReLU(y) ;  alpha = softmax over in(v)
@@ -437,11 +442,73 @@ struct GatWs {
   int64_t ld_t;
 };
 
+// Contiguous row ranges between pinned host memory and staging pairs in HBM: copies run on the
+// side streams, the compute stream waits for the block it needs and frees the block it has read.
+struct Link {
+  ht_ctx* ctx;
+  ht_stats* st;
+  Timer* tm;
+  hipStream_t s_c, s_in, s_out;
+  hipEvent_t last_out = nullptr;
+  bool used = false;
+  Link(ht_ctx* c, ht_stats* s, Timer* t) : ctx(c), st(s), tm(t), s_c(c->stream), s_in(c->side[0]), s_out(c->side[1]) {}
+  // A failed call must not leave side-stream work that refers to the caller's buffers.
+  ~Link() {
+    if (used) {
+      (void)hipStreamSynchronize(s_in);
+      (void)hipStreamSynchronize(s_out);
+    }
+  }
+  int rec(hipStream_t s, hipEvent_t* out) {
+    hipEvent_t e = ht_event(ctx);
+    if (!e) return ht_set_err(ctx, HT_EHIP, "hipEventCreate failed");
+    HT_HIP(ctx, hipEventRecord(e, s));
+    *out = e;
+    return HT_OK;
+  }
+  int wait(hipStream_t s, hipEvent_t e) {
+    if (e) HT_HIP(ctx, hipStreamWaitEvent(s, e, 0));
+    return HT_OK;
+  }
+  // the side streams start behind everything the compute stream has been given so far
+  int fork() {
+    hipEvent_t e = nullptr;
+    HT_TRY(rec(s_c, &e));
+    HT_TRY(wait(s_in, e));
+    HT_TRY(wait(s_out, e));
+    used = true;
+    return HT_OK;
+  }
+  // the compute stream continues behind every store to the host
+  int join() {
+    HT_TRY(wait(s_c, last_out));
+    hipEvent_t e = nullptr;
+    HT_TRY(rec(s_in, &e));
+    return wait(s_c, e);
+  }
+  int copy(hipStream_t s, void* dst, const void* src, size_t bytes, bool to_host) {
+    if (bytes == 0) return HT_OK;
+    const int id = tm->begin_on(&st->t_copy_ms, s);
+    if (ctx->link_memcpy) {
+      HT_HIP(ctx, hipMemcpyAsync(dst, src, bytes, to_host ? hipMemcpyDeviceToHost : hipMemcpyHostToDevice, s));
+    } else {
+      void* mapped = nullptr;
+      HT_HIP(ctx, hipHostGetDevicePointer(&mapped, to_host ? dst : const_cast<void*>(src), 0));
+      HT_TRY(ht_copy_link(ctx, s, to_host ? mapped : dst, to_host ? src : mapped, bytes, ctx->link_blocks));
+    }
+    tm->end_id(id);
+    (to_host ? st->bytes_d2h : st->bytes_h2d) += (int64_t)bytes;
+    return HT_OK;
+  }
+};
+
+inline bool on_host(const ht_tensor* t) { return t && t->loc == HT_LOC_HOST_PINNED; }
+
 int check(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const ht_tensor* t, int32_t cols, const char* name) {
   if (!t || !t->ptr) return ht_set_err(ctx, HT_EINVAL, "%s: null tensor", name);
   if (t->rows != g->V || t->cols != cols) return ht_set_err(ctx, HT_ESHAPE, "%s: expected [%lld x %d]", name, (long long)g->V, cols);
   if (t->ld < cols || (t->ld & 3) || ((uintptr_t)t->ptr & 15)) return ht_set_err(ctx, HT_ESHAPE, "%s: bad pitch or alignment", name);
-  if (t->loc != HT_LOC_DEVICE) return ht_set_err(ctx, HT_ESHAPE, "GAT layer: %s must be in HBM", name);
+  if (t->loc != HT_LOC_DEVICE && t->loc != HT_LOC_HOST_PINNED) return ht_set_err(ctx, HT_ESHAPE, "%s: unknown location", name);
   (void)desc;
   return HT_OK;
 }
@@ -455,8 +522,10 @@ int check_desc(ht_ctx* ctx, const ht_gat_desc* d) {
 }
 
 // t = H W (pad columns zero), p, q
+constexpr int64_t BLOCK_HBM = (int64_t)1 << 22;    // rows per GEMM call
+
 int prepare(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const ht_tensor* H, const float* W, const float* a_dst,
-            const float* a_src, bool backward, GatWs* ws, ht_stats* st, Timer* tm) {
+            const float* a_src, bool backward, GatWs* ws, ht_stats* st, Timer* tm, Link* lk) {
   hipStream_t s = ctx->stream;
   const int64_t V = std::max<int64_t>(g->V, 1);
   ws->ld_t = ht_row_pitch(desc->d_out, true);
@@ -470,12 +539,32 @@ int prepare(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const ht_te
   HT_TRY(ht_scratch(ctx, HT_S_GATE, ne * 4 * (backward ? 2 : 1), (void**)&ws->w));
   ws->wf = backward ? ws->w + ne : nullptr;
   if (ws->ld_t != desc->d_out) HT_TRY(ht_fill_zero(ctx, s, ws->T, (size_t)g->V * ws->ld_t * 4));
-  const int64_t step = (int64_t)1 << 22;
-  for (int64_t r0 = 0; r0 < g->V; r0 += step) {
+  const bool host = on_host(H);
+  const int64_t step = host ? ctx->link_block_rows : BLOCK_HBM;   // rows per staged block / per GEMM call
+  float* stage[2] = {nullptr, nullptr};
+  hipEvent_t ev_free[2] = {nullptr, nullptr};
+  if (host) {
+    const int64_t rows = std::min<int64_t>(step, V);
+    HT_TRY(ht_scratch(ctx, HT_S_LINK0, (size_t)rows * H->ld * 4 * 2, (void**)&stage[0]));
+    stage[1] = stage[0] + rows * H->ld;
+  }
+  int k = 0;
+  for (int64_t r0 = 0; r0 < g->V; r0 += step, ++k) {
     const int64_t nr = std::min(step, g->V - r0);
+    const float* rows = H->ptr + r0 * H->ld;
+    const int b = k & 1;
+    if (host) {
+      hipEvent_t ev_in = nullptr;
+      HT_TRY(lk->wait(lk->s_in, ev_free[b]));
+      HT_TRY(lk->copy(lk->s_in, stage[b], rows, (size_t)nr * H->ld * 4, false));
+      HT_TRY(lk->rec(lk->s_in, &ev_in));
+      HT_TRY(lk->wait(s, ev_in));
+      rows = stage[b];
+    }
     tm->begin(&st->t_gemm_ms);
-    HT_TRY(ht_gemm_nn(ctx, s, H->ptr + r0 * H->ld, H->ld, W, ws->T + r0 * ws->ld_t, ws->ld_t, nr, desc->d_in, desc->d_out, 0));
+    HT_TRY(ht_gemm_nn(ctx, s, rows, H->ld, W, ws->T + r0 * ws->ld_t, ws->ld_t, nr, desc->d_in, desc->d_out, 0));
     tm->end();
+    if (host) HT_TRY(lk->rec(s, &ev_free[b]));
     st->n_gemm += 1;
     st->gemm_flops += 2.0 * nr * desc->d_in * desc->d_out;
   }
@@ -535,10 +624,22 @@ int gat_fwd_impl(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const 
   HT_TRY(check(ctx, g, desc, H_out, desc->d_out, "H_out"));
   hipStream_t st = ctx->stream;
   GatWs ws{};
-  HT_TRY(prepare(ctx, g, desc, H_in, W, a_dst, a_src, false, &ws, local, tm));
+  Link lk(ctx, local, tm);
+  const bool out_host = on_host(H_out);
+  if (on_host(H_in) || out_host) HT_TRY(lk.fork());
+  HT_TRY(prepare(ctx, g, desc, H_in, W, a_dst, a_src, false, &ws, local, tm, &lk));
+  float* obuf[2] = {nullptr, nullptr};
+  hipEvent_t ev_ofree[2] = {nullptr, nullptr};
+  if (out_host) {
+    const int64_t rows = std::max<int64_t>(g->max_ndst, 1);
+    HT_TRY(ht_scratch(ctx, HT_S_LINK1, (size_t)rows * H_out->ld * 4 * 2, (void**)&obuf[0]));
+    obuf[1] = obuf[0] + rows * H_out->ld;
+  }
+  int q = 0;
   for (int j = 0; j < g->n; ++j) {
     const ChunkMeta& c = g->chunks[j];
     if (c.dst1 == c.dst0) continue;
+    const int b = q++ & 1;
     HT_TRY(softmax_chunk(ctx, g, c, desc, ws, local, tm, false));
     float* partial = nullptr;
     if (c.fwd.n_part > 0) HT_TRY(ht_scratch(ctx, HT_S_SPART, (size_t)g->max_fpart * H_out->ld * 4, (void**)&partial));
@@ -549,24 +650,39 @@ int gat_fwd_impl(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const 
     a.idx = g->merged ? g->ucol.p + c.ue0 : g->col.p + c.e0;
     a.w_edge = ws.w;
     a.src = ws.T; a.src_ld = ws.ld_t; a.d = desc->d_out;
-    a.out = H_out->ptr + c.dst0 * H_out->ld; a.out_ld = H_out->ld;
+    a.out = out_host ? obuf[b] : H_out->ptr + c.dst0 * H_out->ld; a.out_ld = H_out->ld;
     a.accumulate = 0;
     a.relu = desc->act == HT_ACT_RELU;
     a.partial = partial;
     a.tm = tm;
     a.t_items = &local->t_agg_fwd_layer_ms[layer < HT_MAX_LAYERS ? layer : HT_MAX_LAYERS - 1];
     a.t_fix = &local->t_agg_fix_ms;
+    if (out_host) {
+      HT_TRY(lk.wait(st, ev_ofree[b]));
+      // rows without an in-edge have no work item: their output is zero
+      HT_TRY(ht_fill_zero(ctx, st, obuf[b], (size_t)(c.dst1 - c.dst0) * H_out->ld * 4));
+    }
     HT_TRY(ht_spmm_launch(ctx, st, a));
+    if (out_host) {
+      hipEvent_t ev_done = nullptr;
+      HT_TRY(lk.rec(st, &ev_done));
+      HT_TRY(lk.wait(lk.s_out, ev_done));
+      HT_TRY(lk.copy(lk.s_out, H_out->ptr + c.dst0 * H_out->ld, obuf[b], (size_t)(c.dst1 - c.dst0) * H_out->ld * 4, true));
+      HT_TRY(lk.rec(lk.s_out, &ev_ofree[b]));
+      lk.last_out = ev_ofree[b];
+    }
     local->n_spmm_fwd += 1;
     local->n_agg_fwd_layer[layer < HT_MAX_LAYERS ? layer : HT_MAX_LAYERS - 1] += 1;
     local->edges += c.nnz;
   }
+  if (lk.used) HT_TRY(lk.join());
   return HT_OK;
 }
 
 int gat_bwd_impl(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const ht_tensor* H_in, const float* W,
                  const float* a_dst, const float* a_src, const ht_tensor* H_out, const ht_tensor* dH_out,
-                 ht_tensor* dH_in, float* dW, float* da_dst, float* da_src, ht_stats* local, Timer* tm) {
+                 ht_tensor* dH_in, float* dW, float* da_dst, float* da_src, ht_stats* local, Timer* tm,
+                 bool dhin_is_zero) {
   HT_TRY(check_desc(ctx, desc));
   HT_TRY(check(ctx, g, desc, H_in, desc->d_in, "H_in"));
   HT_TRY(check(ctx, g, desc, H_out, desc->d_out, "H_out"));
@@ -574,7 +690,10 @@ int gat_bwd_impl(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const 
   if (dH_in) HT_TRY(check(ctx, g, desc, dH_in, desc->d_in, "dH_in"));
   hipStream_t st = ctx->stream;
   GatWs ws{};
-  HT_TRY(prepare(ctx, g, desc, H_in, W, a_dst, a_src, true, &ws, local, tm));
+  Link lk(ctx, local, tm);
+  const bool hin_host = on_host(H_in), hout_host = on_host(H_out), dho_host = on_host(dH_out), dhi_host = on_host(dH_in);
+  if (hin_host || hout_host || dho_host || dhi_host) HT_TRY(lk.fork());
+  HT_TRY(prepare(ctx, g, desc, H_in, W, a_dst, a_src, true, &ws, local, tm, &lk));
   const int d = desc->d_out;
   const int nvec = (d + 3) / 4;
   const int sc_col = (int)ws.ld_t;              // the scalar column block sits behind the padded data columns
@@ -586,15 +705,44 @@ int gat_bwd_impl(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const 
   HT_TRY(ht_scratch(ctx, HT_S_ACHUNK, (size_t)mx * ws.ld_t * 4, (void**)&Q));
   HT_TRY(ht_scratch(ctx, HT_S_MISC, (size_t)d * 16, (void**)&da4));
   HT_TRY(ht_fill_zero(ctx, st, dT, (size_t)g->V * ld_dt * 4));
-  for (int j = 0; j < g->n; ++j) {
-    const ChunkMeta& c = g->chunks[j];
+  // host-resident H_out / dH_out: the rows of the next chunk are staged while this one computes
+  float* hbuf[2] = {nullptr, nullptr};
+  float* gbuf[2] = {nullptr, nullptr};
+  hipEvent_t ev_in[2] = {nullptr, nullptr}, ev_free[2] = {nullptr, nullptr};
+  if (hout_host) {
+    HT_TRY(ht_scratch(ctx, HT_S_LINK1, (size_t)mx * H_out->ld * 4 * 2, (void**)&hbuf[0]));
+    hbuf[1] = hbuf[0] + mx * H_out->ld;
+  }
+  if (dho_host) {
+    HT_TRY(ht_scratch(ctx, HT_S_LINK2, (size_t)mx * dH_out->ld * 4 * 2, (void**)&gbuf[0]));
+    gbuf[1] = gbuf[0] + mx * dH_out->ld;
+  }
+  std::vector<int> live;
+  for (int j = 0; j < g->n; ++j)
+    if (g->chunks[j].dst1 > g->chunks[j].dst0) live.push_back(j);
+  auto stage_chunk = [&](size_t i) -> int {
+    if (!(hout_host || dho_host) || i >= live.size()) return HT_OK;
+    const ChunkMeta& c = g->chunks[live[i]];
+    const int b = (int)(i & 1);
+    const int64_t nd = c.dst1 - c.dst0;
+    HT_TRY(lk.wait(lk.s_in, ev_free[b]));
+    if (hout_host) HT_TRY(lk.copy(lk.s_in, hbuf[b], H_out->ptr + c.dst0 * H_out->ld, (size_t)nd * H_out->ld * 4, false));
+    if (dho_host) HT_TRY(lk.copy(lk.s_in, gbuf[b], dH_out->ptr + c.dst0 * dH_out->ld, (size_t)nd * dH_out->ld * 4, false));
+    return lk.rec(lk.s_in, &ev_in[b]);
+  };
+  HT_TRY(stage_chunk(0));
+  for (size_t i = 0; i < live.size(); ++i) {
+    const ChunkMeta& c = g->chunks[live[i]];
     const int64_t ndst = c.dst1 - c.dst0;
-    if (ndst == 0) continue;
+    const int b = (int)(i & 1);
+    HT_TRY(stage_chunk(i + 1));
     HT_TRY(softmax_chunk(ctx, g, c, desc, ws, local, tm, true));
-    k_gat_dz<<<(unsigned)((ndst + 3) / 4), 256, 0, st>>>(dH_out->ptr + c.dst0 * dH_out->ld, dH_out->ld,
-                                                          H_out->ptr + c.dst0 * H_out->ld, H_out->ld,
+    if (hout_host || dho_host) HT_TRY(lk.wait(st, ev_in[b]));
+    k_gat_dz<<<(unsigned)((ndst + 3) / 4), 256, 0, st>>>(dho_host ? gbuf[b] : dH_out->ptr + c.dst0 * dH_out->ld, dH_out->ld,
+                                                          hout_host ? hbuf[b] : H_out->ptr + c.dst0 * H_out->ld, H_out->ld,
                                                           desc->act == HT_ACT_RELU, ndst, d, dz, ws.ld_t, ws.S);
     HT_LAUNCH_CHECK(ctx);
+    if (hout_host || dho_host) HT_TRY(lk.rec(st, &ev_free[b]));   // the staged rows have been consumed
     GatPass a{};
     a.d = d; a.p = ws.p; a.q = ws.q; a.m = ws.m; a.zinv = ws.zinv; a.S = ws.S; a.dst0 = c.dst0; a.slope = desc->slope;
     // destination pass: Q_v = sum_e w_e f_e t_u through the aggregation kernel, then dp_v = dz_v . Q_v - S_v r_v
@@ -647,17 +795,61 @@ int gat_bwd_impl(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const 
     k_gat_finish<<<(unsigned)((g->V + 3) / 4), 256, 0, st>>>(dT, ld_dt, d, sc_col, ws.dp, a_dst, a_src, g->V, ws.pq4);
     HT_LAUNCH_CHECK(ctx);
   }
-  // da = T^T [dp dq 0 0]; dW = H^T dt; dH += dt W^T
-  const int64_t step = (int64_t)1 << 22;
+  // da = T^T [dp dq 0 0]; dW = H^T dt; dH += dt W^T, in row blocks; host-resident H_in / dH_in blocks go
+  // through staging pairs (dH_in: in, add, out; straight out when it is known to hold zeros)
+  const int64_t step = (hin_host || dhi_host) ? ctx->link_block_rows : BLOCK_HBM;
+  const int64_t brows = std::min<int64_t>(step, std::max<int64_t>(g->V, 1));
+  float* sH[2] = {nullptr, nullptr};
+  float* sD[2] = {nullptr, nullptr};
+  hipEvent_t ev_bfree[2] = {nullptr, nullptr}, ev_dout[2] = {nullptr, nullptr};
+  if (hin_host) {
+    HT_TRY(ht_scratch(ctx, HT_S_LINK0, (size_t)brows * H_in->ld * 4 * 2, (void**)&sH[0]));
+    sH[1] = sH[0] + brows * H_in->ld;
+  }
+  if (dhi_host) {
+    // (the chunk loop is over: its staging pair is free)
+    HT_TRY(ht_scratch(ctx, HT_S_LINK1, (size_t)brows * dH_in->ld * 4 * 2, (void**)&sD[0]));
+    sD[1] = sD[0] + brows * dH_in->ld;
+  }
+  // the staging memory was used by the earlier phases: copies into it start behind their last reader
+  if (lk.used) HT_TRY(lk.fork());
   bool first = true;
-  for (int64_t r0 = 0; r0 < g->V; r0 += step) {
+  int k = 0;
+  for (int64_t r0 = 0; r0 < g->V; r0 += step, ++k) {
     const int64_t nr = std::min(step, g->V - r0);
+    const int b = k & 1;
+    const float* h_rows = H_in->ptr + r0 * H_in->ld;
+    float* dh_rows = dH_in ? dH_in->ptr + r0 * dH_in->ld : nullptr;
+    const bool dh_add = !(dhi_host && dhin_is_zero);
+    if (hin_host || dhi_host) {
+      hipEvent_t ev_bin = nullptr;
+      HT_TRY(lk.wait(lk.s_in, ev_bfree[b]));
+      HT_TRY(lk.wait(lk.s_in, ev_dout[b]));
+      if (hin_host) {
+        HT_TRY(lk.copy(lk.s_in, sH[b], h_rows, (size_t)nr * H_in->ld * 4, false));
+        h_rows = sH[b];
+      }
+      if (dhi_host) {
+        if (dh_add) HT_TRY(lk.copy(lk.s_in, sD[b], dh_rows, (size_t)nr * dH_in->ld * 4, false));
+        else HT_TRY(lk.wait(st, ev_dout[b]));      // the compute stream overwrites the block
+        dh_rows = sD[b];
+      }
+      HT_TRY(lk.rec(lk.s_in, &ev_bin));
+      HT_TRY(lk.wait(st, ev_bin));
+    }
     tm->begin(&local->t_gemm_ms);
     HT_TRY(ht_gemm_tn(ctx, st, ws.T + r0 * ws.ld_t, ws.ld_t, ws.pq4 + r0 * 4, 4, da4, nr, d, 4, first ? 0 : 1));
-    HT_TRY(ht_gemm_tn(ctx, st, H_in->ptr + r0 * H_in->ld, H_in->ld, dT + r0 * ld_dt, ld_dt, dW, nr, desc->d_in, d, first ? 0 : 1));
+    HT_TRY(ht_gemm_tn(ctx, st, h_rows, H_in->ld, dT + r0 * ld_dt, ld_dt, dW, nr, desc->d_in, d, first ? 0 : 1));
     if (dH_in)
-      HT_TRY(ht_gemm_nt(ctx, st, dT + r0 * ld_dt, ld_dt, W, dH_in->ptr + r0 * dH_in->ld, dH_in->ld, nr, d, desc->d_in, 1));
+      HT_TRY(ht_gemm_nt(ctx, st, dT + r0 * ld_dt, ld_dt, W, dh_rows, dH_in->ld, nr, d, desc->d_in, dh_add ? 1 : 0));
     tm->end();
+    if (hin_host || dhi_host) HT_TRY(lk.rec(st, &ev_bfree[b]));
+    if (dhi_host) {
+      HT_TRY(lk.wait(lk.s_out, ev_bfree[b]));
+      HT_TRY(lk.copy(lk.s_out, dH_in->ptr + r0 * dH_in->ld, sD[b], (size_t)nr * dH_in->ld * 4, true));
+      HT_TRY(lk.rec(lk.s_out, &ev_dout[b]));
+      lk.last_out = ev_dout[b];
+    }
     local->n_gemm += 3;
     local->gemm_flops += 4.0 * nr * desc->d_in * d;
     first = false;
@@ -668,6 +860,7 @@ int gat_bwd_impl(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const 
   }
   k_gat_split<<<(unsigned)((d + 255) / 256), 256, 0, st>>>(da4, d, da_dst, da_src);
   HT_LAUNCH_CHECK(ctx);
+  if (lk.used) HT_TRY(lk.join());
   return HT_OK;
 }
 
@@ -708,7 +901,7 @@ int ht_gat_layer_bwd(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, co
   auto t0 = std::chrono::steady_clock::now();
   ht_stats local{};
   Timer tm(ctx, ctx->stream, stats != nullptr);
-  int rc = gat_bwd_impl(ctx, g, desc, H_in, W, a_dst, a_src, H_out, dH_out, dH_in, dW, da_dst, da_src, &local, &tm);
+  int rc = gat_bwd_impl(ctx, g, desc, H_in, W, a_dst, a_src, H_out, dH_out, dH_in, dW, da_dst, da_src, &local, &tm, false);
   hipError_t e = hipStreamSynchronize(ctx->stream);
   if (rc == HT_OK && e == hipSuccess) rc = tm.resolve();
   ctx->ev_next = 0;
@@ -733,7 +926,9 @@ int ht_gat_scores(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const
   ht_stats local{};
   Timer tm(ctx, ctx->stream, false);
   GatWs ws{};
-  HT_TRY(prepare(ctx, g, desc, H_in, W, a_dst, a_src, false, &ws, &local, &tm));
+  Link lk(ctx, &local, &tm);
+  if (on_host(H_in)) HT_TRY(lk.fork());
+  HT_TRY(prepare(ctx, g, desc, H_in, W, a_dst, a_src, false, &ws, &local, &tm, &lk));
   HT_HIP(ctx, hipStreamSynchronize(ctx->stream));
   if (g->V > 0) {
     HT_HIP(ctx, hipMemcpy(p_host, ws.p, (size_t)g->V * 4, hipMemcpyDeviceToHost));
@@ -742,9 +937,11 @@ int ht_gat_scores(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const
   return HT_OK;
 }
 
-// Alg. 1 with GAT layers, everything in HBM: forward over the layers (only the layer outputs
-// are kept), softmax cross-entropy on the labelled vertices, backward layer by layer with
-// every layer's intermediates recomputed from its input, SGD step on W^l and a^l.
+// Alg. 1 with GAT layers: forward over the layers (only the layer outputs are kept), softmax
+// cross-entropy on the labelled vertices, backward layer by layer with every layer's
+// intermediates recomputed from its input, SGD step on W^l and a^l.  With res_h = HT_RES_HOST
+// the layer outputs h^1..h^{L-1} and their gradients live in pinned host memory (Alg. 1 keeps
+// h^l and grad h^l on the CPU); the logits h^L and their gradient stay in HBM for the loss.
 int ht_gat_epoch(ht_ctx* ctx, const ht_graph* g, const ht_gat_model* model, const ht_tensor* X, const int32_t* labels,
                  float* loss_out, ht_stats* stats) {
   if (!ctx) return HT_EINVAL;
@@ -761,20 +958,32 @@ int ht_gat_epoch(ht_ctx* ctx, const ht_graph* g, const ht_gat_model* model, cons
   auto t0 = std::chrono::steady_clock::now();
   hipStream_t st = ctx->stream;
   const int64_t V = g->V;
-  // workspace: h^1..h^L, grad h^1..grad h^L, then dW^l, da_dst^l, da_src^l, loss
-  size_t floats = 64 + 64 * (size_t)L;
-  for (int l = 1; l <= L; ++l) floats += 2 * (size_t)std::max<int64_t>(V, 1) * ht_row_pitch(model->dims[l], true);
+  if (model->res_h != HT_RES_AUTO && model->res_h != HT_RES_HBM && model->res_h != HT_RES_HOST)
+    return ht_set_err(ctx, HT_EINVAL, "ht_gat_epoch: unknown residency %d", model->res_h);
+  const bool h_host = model->res_h == HT_RES_HOST;
+  auto in_hbm = [&](int l) { return !h_host || l == L; };
+  // workspace: h^1..h^L, grad h^1..grad h^L (HBM or pinned host), then dW^l, da_dst^l, da_src^l, loss
+  size_t floats = 64 + 64 * (size_t)L, hfloats = 64 * (size_t)L;
+  for (int l = 1; l <= L; ++l)
+    (in_hbm(l) ? floats : hfloats) += 2 * ((size_t)std::max<int64_t>(V, 1) * ht_row_pitch(model->dims[l], in_hbm(l)) + 32);
   for (int l = 0; l < L; ++l) floats += (size_t)model->dims[l] * model->dims[l + 1] + 2 * (size_t)model->dims[l + 1] + 96;
   float* base = nullptr;
+  float* hbase = nullptr;
   HT_TRY(ht_scratch(ctx, HT_S_GATWS, floats * 4, (void**)&base));
+  if (h_host && L > 1) HT_TRY(ht_host_scratch(ctx, 2, hfloats * 4, (void**)&hbase));
   std::vector<ht_tensor> h(L + 1), gh(L + 1);
   std::vector<float*> dW(L), dad(L), das(L);
   float* cur = base;
+  float* hcur = hbase;
   auto take = [&](size_t n) { float* p = cur; cur += (n + 31) & ~(size_t)31; return p; };
+  auto take_host = [&](size_t n) { float* p = hcur; hcur += (n + 31) & ~(size_t)31; return p; };
   for (int l = 1; l <= L; ++l) {
-    const int64_t ld = ht_row_pitch(model->dims[l], true);
-    h[l] = ht_tensor{take((size_t)std::max<int64_t>(V, 1) * ld), V, model->dims[l], ld, HT_LOC_DEVICE};
-    gh[l] = ht_tensor{take((size_t)std::max<int64_t>(V, 1) * ld), V, model->dims[l], ld, HT_LOC_DEVICE};
+    const bool dev = in_hbm(l);
+    const int64_t ld = ht_row_pitch(model->dims[l], dev);
+    const size_t n = (size_t)std::max<int64_t>(V, 1) * ld;
+    const int loc = dev ? HT_LOC_DEVICE : HT_LOC_HOST_PINNED;
+    h[l] = ht_tensor{dev ? take(n) : take_host(n), V, model->dims[l], ld, loc};
+    gh[l] = ht_tensor{dev ? take(n) : take_host(n), V, model->dims[l], ld, loc};
   }
   for (int l = 0; l < L; ++l) {
     dW[l] = take((size_t)model->dims[l] * model->dims[l + 1]);
@@ -786,6 +995,8 @@ int ht_gat_epoch(ht_ctx* ctx, const ht_graph* g, const ht_gat_model* model, cons
   Timer tm(ctx, st, stats != nullptr);
   auto fail = [&](int rc) {
     (void)hipStreamSynchronize(st);
+    (void)hipStreamSynchronize(ctx->side[0]);
+    (void)hipStreamSynchronize(ctx->side[1]);
     ctx->ev_next = 0;
     return rc;
   };
@@ -802,12 +1013,12 @@ int ht_gat_epoch(ht_ctx* ctx, const ht_graph* g, const ht_gat_model* model, cons
   }
   for (int l = L - 1; l >= 0; --l) {
     ht_gat_desc d{model->dims[l], model->dims[l + 1], l < L - 1 ? HT_ACT_RELU : HT_ACT_NONE, model->slope};
-    if (l > 0) {
+    if (l > 0 && gh[l].loc == HT_LOC_DEVICE) {   // (a host-resident gradient is written, not added to)
       int rc = ht_fill_zero(ctx, st, gh[l].ptr, (size_t)V * gh[l].ld * 4);
       if (rc != HT_OK) return fail(rc);
     }
     int rc = gat_bwd_impl(ctx, g, &d, l == 0 ? X : &h[l], model->W[l], model->a_dst[l], model->a_src[l], &h[l + 1], &gh[l + 1],
-                          l > 0 ? &gh[l] : nullptr, dW[l], dad[l], das[l], &local, &tm);
+                          l > 0 ? &gh[l] : nullptr, dW[l], dad[l], das[l], &local, &tm, true);
     if (rc != HT_OK) return fail(rc);
   }
   for (int l = 0; l < L; ++l) {

@@ -20,7 +20,8 @@ struct EpochWs;
 
 enum {
   HT_S_PACKW = 0, HT_S_TNPART, HT_S_LOSS, HT_S_ACHUNK, HT_S_OCHUNK, HT_S_ZCHUNK, HT_S_DZCHUNK, HT_S_DACHUNK,
-  HT_S_NBUF, HT_S_SPART, HT_S_LEAVE, HT_S_MISC, HT_S_TFULL, HT_S_TFULL2, HT_S_GATV, HT_S_GATE, HT_S_GATWS, HT_S_GATP, HT_N_SCRATCH
+  HT_S_NBUF, HT_S_SPART, HT_S_LEAVE, HT_S_MISC, HT_S_TFULL, HT_S_TFULL2, HT_S_GATV, HT_S_GATE, HT_S_GATWS, HT_S_GATP,
+  HT_S_LINK0, HT_S_LINK1, HT_S_LINK2, HT_N_SCRATCH
 };
 
 struct ht_ctx {
@@ -38,8 +39,8 @@ struct ht_ctx {
   void* scratch[HT_N_SCRATCH] = {};
   size_t scratch_bytes[HT_N_SCRATCH] = {};
   // pinned host scratch (D2H staging of gradient rows)
-  void* hscratch[2] = {nullptr, nullptr};
-  size_t hscratch_bytes[2] = {0, 0};
+  void* hscratch[3] = {nullptr, nullptr, nullptr};
+  size_t hscratch_bytes[3] = {0, 0, 0};
   int xcd_contig = 0;     // 1: XCDs take contiguous parts of the item list instead of interleaving it
                           // (HT_XCD_CONTIG; measured slower at cfg2: 30.7 vs 26.0 ms per epoch)
   int no_link_fence = 0;  // 1: let aggregation kernels overlap link traffic (HT_NO_LINK_FENCE, for A/B runs)
@@ -50,6 +51,7 @@ struct ht_ctx {
   int agg_uniform = 1;    // HT_AGG_UNIFORM=0: no wave-uniform fast path for one-edge-per-step shapes
   int slab_align = 1;     // HT_SLAB_ALIGN=0: do not round slabs to whole cache lines
   int agg_phases = 1;     // HT_AGG_PHASES: slabs are spread over this many consecutive launches
+  int64_t link_block_rows = (int64_t)1 << 20;   // HT_LINK_BLOCK_ROWS: rows per staged block of a host-resident tensor (GAT path)
   int agg_variant = 0;  // 0: feature slabs per XCD; 1: full-width rows per wave (HT_AGG_VARIANT, for A/B runs)
   int n_threads = 0;  // host threads for CPU-side accumulation (0 = decide on first use)
 };

@@ -21,7 +21,7 @@ def ctx():
 
 class Case:
     def __init__(self, ctx, V, src, dst, n):
-        self.V = V
+        self.V, self.src, self.dst = V, src, dst
         self.g = B.ht_partition(ctx, V, src.cuda(), dst.cuda(), n)
         self.indptr, self.col = orc.csc_build(V, src.numpy(), dst.numpy(), True)
 
@@ -46,7 +46,14 @@ def _mat(x):
     return B.to_matrix(torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)), DEV)
 
 
-def _run(ctx, case, d_in, d_out, relu, seed, want_dhin=True, slope=0.2):
+def _run(ctx, case, d_in, d_out, relu, seed, want_dhin=True, slope=0.2, host=()):
+    """host: which of the layer's tensors live in pinned host memory ("H_in", "H_out", "dH_out", "dH_in")."""
+    def loc(name):
+        return B.HT_LOC_HOST_PINNED if name in host else DEV
+
+    def mat(x, name):
+        return B.to_matrix(torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)), loc(name))
+
     rng = np.random.default_rng(seed)
     V = case.V
     H = rng.standard_normal((V, d_in)).astype(np.float32)
@@ -56,23 +63,28 @@ def _run(ctx, case, d_in, d_out, relu, seed, want_dhin=True, slope=0.2):
     dh = rng.standard_normal((V, d_out)).astype(np.float32)
     act = B.HT_ACT_RELU if relu else B.HT_ACT_NONE
     f = orc.gat_layer_fwd(case.indptr, case.col, H, W, a_dst, a_src, slope=slope, relu=relu)
-    Hd, Wd = _mat(H), torch.from_numpy(W).cuda()
+    Hd, Wd = mat(H, "H_in"), torch.from_numpy(W).cuda()
     ad, as_ = torch.from_numpy(a_dst).cuda(), torch.from_numpy(a_src).cuda()
-    H_out = B.alloc_matrix(V, d_out, DEV, zero=False)
+    H_out = B.alloc_matrix(V, d_out, loc("H_out"), zero=False)
     B.ht_gat_layer_fwd(ctx, case.g, d_in, d_out, act, Hd, Wd, ad, as_, H_out, slope=slope)
     assert_close(H_out.cpu().numpy()[:, :d_out], f["h"], "h_out")
     # backward from the oracle's own forward result, so both sides mask the same elements
     b = orc.gat_layer_bwd(case.indptr, case.col, H, W, a_dst, a_src, f, dh, slope=slope, relu=relu, want_dH=want_dhin)
     dW = torch.empty(d_in, d_out, device="cuda")
     dad, das = torch.empty(d_out, device="cuda"), torch.empty(d_out, device="cuda")
-    dH_in = B.alloc_matrix(V, d_in, DEV) if want_dhin else None
-    B.ht_gat_layer_bwd(ctx, case.g, d_in, d_out, act, Hd, Wd, ad, as_, _mat(f["h"]), _mat(dh), dW, dad, das, dH_in=dH_in,
-                       slope=slope)
+    dH_in = B.alloc_matrix(V, d_in, loc("dH_in")) if want_dhin else None
+    if want_dhin:       # the input gradient is added to what the tensor holds
+        base = np.random.default_rng(seed + 1).standard_normal((V, d_in)).astype(np.float32) if host else None
+        if base is not None:
+            dH_in[:, :d_in] = torch.from_numpy(base)
+    B.ht_gat_layer_bwd(ctx, case.g, d_in, d_out, act, Hd, Wd, ad, as_, mat(f["h"], "H_out"), mat(dh, "dH_out"), dW, dad, das,
+                       dH_in=dH_in, slope=slope)
     assert_close(dW.cpu().numpy(), b["dW"], "dW")
     assert_close(dad.cpu().numpy(), b["da_dst"], "da_dst")
     assert_close(das.cpu().numpy(), b["da_src"], "da_src")
     if want_dhin:
-        assert_close(dH_in.cpu().numpy()[:, :d_in], b["dH"], "dH_in")
+        got = dH_in.cpu().numpy()[:, :d_in].astype(np.float64)
+        assert_close(got - (base if host else 0.0), b["dH"], "dH_in")
     return H_out, dW
 
 
@@ -119,6 +131,36 @@ def test_gat_zero_attention_is_the_neighbour_mean(ctx, cases):
     assert_close(H_out.cpu().numpy()[:, :24], ref, "mean")
 
 
+ALL_HOST = ("H_in", "H_out", "dH_out", "dH_in")
+
+
+@pytest.mark.parametrize("host", [("H_in",), ("H_out", "dH_out"), ("dH_in",), ALL_HOST], ids=lambda h: "+".join(h))
+def test_gat_host_resident_tensors(ctx, cases, host):
+    _run(ctx, cases["rmat"], 100, 41, True, seed=21, host=host)
+    _run(ctx, cases["hub"], 30, 100, False, seed=22, host=host)
+
+
+def test_gat_host_resident_small_blocks(cases):
+    """Staged row blocks much smaller than the tensors: several rounds through both buffers of each staging pair."""
+    import os
+    os.environ["HT_LINK_BLOCK_ROWS"] = "700"
+    try:
+        c2 = B.ht_ctx_create(0)
+    finally:
+        del os.environ["HT_LINK_BLOCK_ROWS"]
+    try:
+        case = cases["multi"]
+        twin = Case(c2, case.V, case.src, case.dst, 5)
+        try:
+            assert case.V > 4 * 700
+            _run(c2, twin, 64, 32, True, seed=23, host=ALL_HOST)
+            _run(c2, twin, 40, 130, True, seed=24, host=("H_in", "dH_in"))
+        finally:
+            B.ht_graph_destroy(twin.g)
+    finally:
+        B.ht_ctx_destroy(c2)
+
+
 def test_gat_deterministic(ctx, cases):
     a = _run(ctx, cases["hub"], 40, 48, True, seed=5)
     b = _run(ctx, cases["hub"], 40, 48, True, seed=5)
@@ -161,15 +203,27 @@ def test_gat_epoch(ctx, cases):
     asd = [torch.from_numpy(a).cuda() for a in as_]
     losses = [B.ht_gat_epoch(ctx, c.g, dims, Wd, add, asd, 0.05, _mat(X), torch.from_numpy(y).cuda())[0] for _ in range(3)]
     assert losses[0] == loss and losses[2] < losses[1] < losses[0]
+    # the same epoch with X, h^1 and its gradient in pinned host memory
+    Wd = [torch.from_numpy(w).cuda() for w in Ws]
+    add = [torch.from_numpy(a).cuda() for a in ad]
+    asd = [torch.from_numpy(a).cuda() for a in as_]
+    Xh = B.to_matrix(torch.from_numpy(X), B.HT_LOC_HOST_PINNED)
+    loss_h, st = B.ht_gat_epoch(ctx, c.g, dims, Wd, add, asd, lr, Xh, torch.from_numpy(y).cuda(), want_stats=True,
+                                res_h=B.HT_RES_HOST)
+    assert abs(loss_h - loss_ref) <= 1e-4 * abs(loss_ref)
+    for l, b in ((0, b0), (1, b1)):
+        assert_close(Wd[l].cpu().numpy(), Ws[l].astype(np.float64) - lr * b["dW"], f"W^{l} after the step (host)")
+        assert_close(add[l].cpu().numpy(), ad[l].astype(np.float64) - lr * b["da_dst"], f"a_dst^{l} after the step (host)")
+    # link traffic, all in contiguous row ranges: X three times (t forward, t again and dW backward); h^1 out once and in
+    # four times (t and dW of layer 1, forward and backward; as H_out of layer 0's backward); grad h^1 out and in once
+    ld0, ld1 = B.pad_ld(dims[0], B.HT_LOC_HOST_PINNED), B.pad_ld(dims[1], B.HT_LOC_HOST_PINNED)
+    assert st.bytes_h2d == 4 * V * (3 * ld0 + 5 * ld1) and st.bytes_d2h == 4 * V * 2 * ld1
 
 
 def test_gat_errors(ctx, cases):
     c = cases["rmat"]
     W = torch.zeros(16, 8, device="cuda")
     v = torch.zeros(8, device="cuda")
-    with pytest.raises(B.HongtuError):      # host-resident input
-        B.ht_gat_layer_fwd(ctx, c.g, 16, 8, B.HT_ACT_NONE, B.alloc_matrix(c.V, 16, B.HT_LOC_HOST_PINNED), W, v, v,
-                           B.alloc_matrix(c.V, 8, DEV))
     with pytest.raises(B.HongtuError):      # slope out of range
         B.ht_gat_layer_fwd(ctx, c.g, 16, 8, B.HT_ACT_NONE, B.alloc_matrix(c.V, 16, DEV), W, v, v,
                            B.alloc_matrix(c.V, 8, DEV), slope=2.0)
