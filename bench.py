@@ -211,6 +211,10 @@ def main():
                     help="stage order of a layer: aggregate then transform as Eq. 2 prints it (the timed default), or "
                          "transform first in the layers that get narrower (same function, fewer bytes aggregated)")
     ap.add_argument("--no-other-order", action="store_true", help="do not time the second stage order as well")
+    ap.add_argument("--hbm-budget-gb", type=float, default=0, help="byte budget the residency planner works with "
+                    "(default: the free HBM)")
+    ap.add_argument("--inter", choices=["auto", "hybrid", "recompute"], default="auto",
+                    help="intermediate data: the planner's choice, a^l cached (Fig. 5(c)), or recomputed (Fig. 5(b))")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a 1 GiB device copy kernel (known traffic) to scale rocprofv3 byte counters")
     args = ap.parse_args()
@@ -267,6 +271,8 @@ def main():
     plan = dict(res_h=res, res_g=res, res_a=B.HT_RES_HOST if (host and w.residency == "host_all") else B.HT_RES_AUTO)
     if args.residency == "h-host":
         plan = dict(res_h=B.HT_RES_HOST, res_g=B.HT_RES_AUTO, res_a=B.HT_RES_AUTO)
+    plan["hbm_budget_bytes"] = int(args.hbm_budget_gb * 1e9)
+    plan["inter"] = {"auto": B.HT_INTER_AUTO, "hybrid": B.HT_INTER_HYBRID, "recompute": B.HT_INTER_RECOMPUTE}[args.inter]
 
     if args.calib_copy:
         a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
@@ -344,6 +350,10 @@ def main():
            "input_generation_s": t_gen,
            "paper_context": "HongTu-IM 2-layer GCN on reddit (same shape), 1xA100: 0.20 s/epoch (Table 4); other hardware, real dataset",
            "order": args.order, "other_order": other,
+           "plan": {"inter": ["auto", "mask", "hybrid", "recompute"][tot["plan_inter"] // args.steps],
+                    "h": ["-", "hbm", "host"][tot["plan_res_h"] // args.steps],
+                    "a": ["-", "hbm", "host"][tot["plan_res_a"] // args.steps],
+                    "grad_h": ["-", "hbm", "host"][tot["plan_res_g"] // args.steps]},
            "roofline": roofline}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, src.cpu().numpy(), dst.cpu().numpy(), X, y, Ws)

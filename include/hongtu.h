@@ -246,6 +246,9 @@ typedef struct {
   double t_agg_fix_ms;
   /* GAT layers: neighbour softmax, destination pass, source pass (with its partial-row pass) */
   double t_gat_softmax_ms, t_gat_dst_ms, t_gat_src_ms;
+  /* what ht_epoch's planner settled on: HT_INTER_*, then HT_RES_* of h^l, a^l and grad h^l
+   * (0 after calls that plan nothing) */
+  int32_t plan_inter, plan_res_h, plan_res_a, plan_res_g;
 } ht_stats;
 
 /* Forward of one layer over all chunks in schedule order:
@@ -350,7 +353,12 @@ int ht_gat_epoch(ht_ctx *ctx, const ht_graph *g, const ht_gat_model *model, cons
  * ReLU' from it; HYBRID caches a^l and recomputes z = a W in the backward pass
  * (Sec. 4.2, Fig. 5(c)); RECOMPUTE keeps no a^l at all: the backward pass
  * gathers and aggregates again from h^l (Fig. 5(b)), then recomputes z unless
- * h^{l+1} is in HBM to read ReLU' from.  AUTO never picks RECOMPUTE. */
+ * h^{l+1} is in HBM to read ReLU' from.  AUTO caches a^l in HBM when the byte
+ * budget allows; when it does not, it compares what the host-side cache costs
+ * (a^l written and read back over the host link, Fig. 5(c)) with what
+ * recomputation costs (neighbour rows of a host-resident h^l fetched once
+ * more, and the aggregation run again, Fig. 5(b)) at this GPU's measured link
+ * and gather rates, and takes the cheaper one. */
 enum { HT_INTER_AUTO = 0, HT_INTER_MASK = 1, HT_INTER_HYBRID = 2, HT_INTER_RECOMPUTE = 3 };
 
 typedef struct {

@@ -75,7 +75,9 @@ class ht_stats(C.Structure):
                 ("t_agg_fwd_layer_ms", C.c_double * HT_MAX_LAYERS),
                 ("agg_fwd_layer_alg_bytes", C.c_double * HT_MAX_LAYERS),
                 ("n_agg_fwd_layer", C.c_int64 * HT_MAX_LAYERS), ("t_agg_fix_ms", C.c_double),
-                ("t_gat_softmax_ms", C.c_double), ("t_gat_dst_ms", C.c_double), ("t_gat_src_ms", C.c_double)]
+                ("t_gat_softmax_ms", C.c_double), ("t_gat_dst_ms", C.c_double), ("t_gat_src_ms", C.c_double),
+                ("plan_inter", C.c_int32), ("plan_res_h", C.c_int32), ("plan_res_a", C.c_int32),
+                ("plan_res_g", C.c_int32)]
 
     def as_dict(self):
         out = {}

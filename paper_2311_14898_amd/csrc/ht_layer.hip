@@ -1033,9 +1033,30 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
   // the output layer's logits and their gradient stay in HBM (the loss runs on them in place)
   left -= 2 * bytes_of(L, L);
   if (res_g == HT_RES_AUTO) { if (L > 1 && bytes_of(1, L - 1) <= left) { res_g = HT_RES_HBM; left -= bytes_of(1, L - 1); } else res_g = L > 1 ? HT_RES_HOST : HT_RES_HBM; }
+  bool a_spills = false;      // the planner, not the caller, put a^l in host memory
   if (inter == HT_INTER_RECOMPUTE) res_a = HT_RES_HBM;   // no checkpoint tensors exist: nothing to place
-  else if (res_a == HT_RES_AUTO) { if (bytes_of(0, L - 1) <= left) { res_a = HT_RES_HBM; left -= bytes_of(0, L - 1); } else res_a = HT_RES_HOST; }
+  else if (res_a == HT_RES_AUTO) {
+    if (bytes_of(0, L - 1) <= left) { res_a = HT_RES_HBM; left -= bytes_of(0, L - 1); }
+    else { res_a = HT_RES_HOST; a_spills = true; }
+  }
   if (res_h == HT_RES_AUTO) { if (L > 1 && bytes_of(1, L - 1) <= left) { res_h = HT_RES_HBM; left -= bytes_of(1, L - 1); } else res_h = L > 1 ? HT_RES_HOST : HT_RES_HBM; }
+  if (inter == HT_INTER_AUTO && a_spills) {
+    // Sec. 4.2's trade-off priced for this GPU.  Host-side cache: a^l crosses the link twice.  Recomputation:
+    // the rows of a host-resident h^l that the buffer schedule loads cross it once more, and every layer
+    // is aggregated a second time.
+    double t_cache = 0.0, t_again = 0.0;
+    const double pairs = (double)(g->merged ? g->n_unique : g->Ep);
+    for (int l = 0; l < L; ++l) {
+      const double row = 4.0 * (double)model->dims[l];
+      const bool in_host = l == 0 ? X->loc == HT_LOC_HOST_PINNED : res_h == HT_RES_HOST;
+      t_cache += 2.0 * (double)V * row / HT_LINK_BYTES_PER_S;
+      t_again += (in_host ? (double)g->v_load * row / HT_LINK_BYTES_PER_S : 0.0) + pairs * row / HT_GATHER_BYTES_PER_S;
+    }
+    if (t_again < t_cache) {
+      inter = HT_INTER_RECOMPUTE;
+      res_a = HT_RES_HBM;
+    }
+  }
   if (inter == HT_INTER_AUTO) inter = res_h == HT_RES_HBM ? HT_INTER_MASK : HT_INTER_HYBRID;
   if (inter != HT_INTER_MASK && inter != HT_INTER_HYBRID && inter != HT_INTER_RECOMPUTE)
     return ht_set_err(ctx, HT_EINVAL, "ht_epoch: unknown intermediate-data mode %d", inter);
@@ -1186,6 +1207,10 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
     hipError_t e = hipMemcpyAsync(loss_out, ws->loss_dev, 4, hipMemcpyDeviceToHost, ctx->stream);
     if (e != hipSuccess) return fail(ht_set_err(ctx, HT_EHIP, "loss copy: %s", hipGetErrorString(e)));
   }
+  local.plan_inter = inter;
+  local.plan_res_h = res_h;
+  local.plan_res_a = recompute ? 0 : res_a;
+  local.plan_res_g = res_g;
   return finish(R, stats, t0, true);
 }
 

@@ -156,6 +156,40 @@ def test_cfg1_pure_recomputation(ctx, cfg1):
         assert np.array_equal(a["gW"][l], b["gW"][l]) and np.array_equal(a["gh"][l], b["gh"][l])
 
 
+def test_planner_prices_recomputation_against_the_host_side_cache(ctx, cfg1):
+    """HT_INTER_AUTO under a byte budget that a^l does not fit (Sec. 4.2's trade-off, priced for this GPU)."""
+    w, src, dst, X, y, Ws, ref = cfg1
+    L = w.n_layers
+    MB = 1 << 20
+    # room for everything: a^l cached in HBM, ReLU' read from h^{l+1}
+    st = run_epoch(ctx, w, src, dst, X, y, Ws, hbm_budget_bytes=64 * MB)["stats"]
+    assert (st.plan_inter, st.plan_res_a, st.plan_res_h, st.plan_res_g) == (B.HT_INTER_MASK, B.HT_RES_HBM, B.HT_RES_HBM, B.HT_RES_HBM)
+    # logits 0.64 MB, grad h 1.28 MB, h 1.28 MB fit, a^l (3.84 MB) does not; h^l in HBM: aggregating again costs no
+    # link traffic at all, the host-side cache would cost 2 x 3.84 MB of it
+    out = run_epoch(ctx, w, src, dst, X, y, Ws, hbm_budget_bytes=int(4.2 * MB), update_first=range(L))
+    compare(out, ref, L)
+    st = out["stats"]
+    assert (st.plan_inter, st.plan_res_h, st.plan_res_g) == (B.HT_INTER_RECOMPUTE, B.HT_RES_HBM, B.HT_RES_HBM)
+    assert st.bytes_h2d == 0 and st.bytes_d2h == 0 and st.edges == (w.E + w.V) * (3 * L - 1)
+    # nothing fits and X is on the host: recomputation fetches the buffer schedule's rows once more (v_load per
+    # layer) where the cache moves 2 V rows: it wins with a schedule that loads every row once, not with the
+    # adjacent-reuse buffer of many small chunks
+    host = dict(x_loc=B.HT_LOC_HOST_PINNED, hbm_budget_bytes=MB // 4)
+    out = run_epoch(ctx, w, src, dst, X, y, Ws, cache_rows=-1, update_first=range(L), **host)
+    compare(out, ref, L)
+    assert out["stats"].plan_inter == B.HT_INTER_RECOMPUTE and out["stats"].plan_res_h == B.HT_RES_HOST
+    g = B.ht_partition(ctx, w.V, src.cuda(), dst.cuda(), 32)
+    v_load = B.ht_graph_info_get(g).v_load
+    B.ht_graph_destroy(g)
+    assert v_load > 2.3 * w.V
+    out = run_epoch(ctx, w, src, dst, X, y, Ws, n_chunks=32, **host)
+    compare(out, ref, L)
+    assert (out["stats"].plan_inter, out["stats"].plan_res_a) == (B.HT_INTER_HYBRID, B.HT_RES_HOST)
+    # a caller who places a^l on the host keeps the hybrid
+    st = run_epoch(ctx, w, src, dst, X, y, Ws, res_a=B.HT_RES_HOST)["stats"]
+    assert st.plan_inter in (B.HT_INTER_MASK, B.HT_INTER_HYBRID) and st.plan_res_a == B.HT_RES_HOST
+
+
 def test_cfg1_update_first_order(ctx, cfg1):
     # H' = act(A_hat (H W)): the same function as Eq. 2 with the two linear stages swapped
     w, src, dst, X, y, Ws, ref = cfg1
