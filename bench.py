@@ -17,6 +17,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+FP32_MFMA_PEAK_TFLOPS = 157.3
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E peak
 
 
@@ -345,6 +346,12 @@ def main():
                                   "t_cpu_accum_ms", "t_update_ms", "t_agg_fix_ms")},
            "agg_fwd_layer_ms_per_step": [x / args.steps for x in tot["t_agg_fwd_layer_ms"][:L]],
            "gemm_tflops": tot["gemm_flops"] / max(tot["t_gemm_ms"] * 1e-3, 1e-12) / 1e12,
+           "gemm_frac_of_fp32_mfma_peak": tot["gemm_flops"] / max(tot["t_gemm_ms"] * 1e-3, 1e-12) / 1e12 / FP32_MFMA_PEAK_TFLOPS,
+           "partition_medges_per_s": Ep / max(info.partition_ms * 1e-3, 1e-12) / 1e6,
+           "link": {"h2d_gbps_over_epoch": tot["bytes_h2d"] / elapsed / 1e9, "d2h_gbps_over_epoch": tot["bytes_d2h"] / elapsed / 1e9,
+                    "measured_one_way_gbps": 57.0, "measured_two_way_gbps_each": 46.0,
+                    "note": "rates over the whole epoch (both directions run beside compute); the measured "
+                            "ceilings are copy-kernel microbenchmarks on this box's host link"} if host or tot["bytes_h2d"] else None,
            "bytes_h2d_per_step": tot["bytes_h2d"] / args.steps, "bytes_d2h_per_step": tot["bytes_d2h"] / args.steps,
            "bytes_h2d_nodedup_per_step": tot["bytes_h2d_nodedup"] / args.steps,
            "input_generation_s": t_gen,
