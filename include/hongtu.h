@@ -380,6 +380,14 @@ typedef struct {
                    * UPDATE_FIRST / AUTO: update first in the layers whose tensors
                    * are all in HBM (AUTO: only where d_out < d_in)         */
   int64_t hbm_budget_bytes; /* 0 = what the device reports free, minus a margin */
+  int32_t reuse_input_aggregate; /* 1: the caller promises that X and the graph are the same as in the
+                   * previous ht_epoch call on this context.  a^0 = A_hat X does not depend on
+                   * the parameters, so the copy the previous epoch cached for its backward pass
+                   * is taken instead of gathering and aggregating layer 0 again (layer 0 then
+                   * keeps the printed stage order whatever `order` says).  Ignored on the
+                   * first epoch, after a change of shape, plan or X pointer, and with
+                   * HT_INTER_RECOMPUTE.  Not part of the paper's method: 0 reproduces it. */
+  int32_t reserved;
 } ht_plan_opts;
 
 /* One training epoch (Alg. 1): forward over layers and chunks, softmax

@@ -30,6 +30,8 @@ struct EpochWs {
   std::vector<void*> dev_ptrs;
   std::vector<void*> host_ptrs;
   float* loss_dev = nullptr;
+  const float* a0_of = nullptr;      // a[0] holds A_hat X for the X at this address (nullptr: not valid)
+  const ht_graph* a0_graph = nullptr;
 };
 
 namespace {
@@ -346,6 +348,76 @@ int layer_fwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* H_in, con
   HT_TRY(P.wait(P.s_c, ev_out[0]));
   HT_TRY(P.wait(P.s_c, ev_out[1]));
   P.used_in = P.used_out = false;   // everything is ordered behind the compute stream now
+  return HT_OK;
+}
+
+// Layer forward from a cached aggregate: h' = act(a W) per chunk, a^l read from A (HBM in place,
+// or pinned host memory through a staging pair).  Used for layer 0 when a^0 = A_hat X of an earlier
+// epoch is still valid.
+int layer_fwd_from_ckpt(Run& R, const ht_layer_desc* desc, const ht_tensor* A, const float* W, ht_tensor* H_out) {
+  ht_ctx* ctx = R.ctx;
+  const ht_graph* g = R.g;
+  const int di = desc->d_in, dn = desc->d_out;
+  HT_TRY(check_tensor(ctx, A, g->V, di, "A_ckpt"));
+  HT_TRY(check_tensor(ctx, H_out, g->V, dn, "H_out"));
+  const bool a_host = A->loc == HT_LOC_HOST_PINNED;
+  const bool h_dev = H_out->loc == HT_LOC_DEVICE;
+  const int64_t mx = std::max<int64_t>(g->max_ndst, 1);
+  float* a_stage[2] = {nullptr, nullptr};
+  float* h_stage[2] = {nullptr, nullptr};
+  if (a_host) {
+    HT_TRY(ht_scratch(ctx, HT_S_ACHUNK, (size_t)mx * A->ld * 4 * 2, (void**)&a_stage[0]));
+    a_stage[1] = a_stage[0] + mx * A->ld;
+  }
+  if (!h_dev) {
+    HT_TRY(ht_scratch(ctx, HT_S_OCHUNK, (size_t)mx * H_out->ld * 4 * 2, (void**)&h_stage[0]));
+    h_stage[1] = h_stage[0] + mx * H_out->ld;
+  }
+  Pipe P(ctx);
+  if (a_host) {
+    hipEvent_t ev_start = nullptr;
+    HT_TRY(P.rec(P.s_c, &ev_start));
+    HT_TRY(P.wait(P.s_in, ev_start));
+    P.used_in = true;
+  }
+  hipEvent_t ev_out[2] = {nullptr, nullptr}, ev_cdone[2] = {nullptr, nullptr};
+  int q = 0;
+  for (int j = 0; j < g->n; ++j) {
+    const ChunkMeta& c = g->chunks[j];
+    const int64_t ndst = c.dst1 - c.dst0;
+    if (ndst == 0) continue;
+    const int b = q & 1;
+    ++q;
+    const float* a_rows = A->ptr + c.dst0 * A->ld;
+    if (a_host) {
+      hipEvent_t ev_in = nullptr;
+      HT_TRY(P.wait(P.s_in, ev_cdone[b]));
+      HT_TRY(copy_rows(R, P.s_in, a_stage[b], a_rows, (size_t)ndst * A->ld * 4, hipMemcpyHostToDevice));
+      HT_TRY(P.rec(P.s_in, &ev_in));
+      HT_TRY(P.wait(P.s_c, ev_in));
+      a_rows = a_stage[b];
+    }
+    if (!h_dev) HT_TRY(P.wait(P.s_c, ev_out[b]));
+    float* h_dst = h_dev ? H_out->ptr + c.dst0 * H_out->ld : h_stage[b];
+    R.tm.begin(&R.st->t_gemm_ms);
+    HT_TRY(ht_gemm_nn(ctx, P.s_c, a_rows, A->ld, W, h_dst, H_out->ld, ndst, di, dn, desc->act == HT_ACT_RELU));
+    R.tm.end();
+    R.st->n_gemm += 1;
+    R.st->gemm_flops += 2.0 * ndst * di * dn;
+    if (a_host) HT_TRY(P.rec(P.s_c, &ev_cdone[b]));
+    if (!h_dev) {
+      hipEvent_t ev_c = nullptr;
+      HT_TRY(P.rec(P.s_c, &ev_c));
+      HT_TRY(P.wait(P.s_out, ev_c));
+      P.used_out = true;
+      HT_TRY(copy_rows(R, P.s_out, H_out->ptr + c.dst0 * H_out->ld, h_stage[b], (size_t)ndst * H_out->ld * 4,
+                       hipMemcpyDeviceToHost));
+      HT_TRY(P.rec(P.s_out, &ev_out[b]));
+    }
+  }
+  HT_TRY(P.wait(P.s_c, ev_out[0]));
+  HT_TRY(P.wait(P.s_c, ev_out[1]));
+  P.used_in = P.used_out = false;
   return HT_OK;
 }
 
@@ -1065,9 +1137,10 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
   const int order = plan ? plan->order : HT_ORDER_AGG_FIRST;
   if (order != HT_ORDER_AGG_FIRST && order != HT_ORDER_UPDATE_FIRST && order != HT_ORDER_AUTO)
     return ht_set_err(ctx, HT_EINVAL, "ht_epoch: unknown stage order %d", order);
+  const bool want_reuse0 = plan && plan->reuse_input_aggregate && !recompute;
   uint32_t upd_mask = 0;
   if (order != HT_ORDER_AGG_FIRST && L <= 32 && gather_mode != HT_GATHER_BUFFER) {
-    for (int l = 0; l < L; ++l) {
+    for (int l = want_reuse0 ? 1 : 0; l < L; ++l) {   // (a^0 is only kept by the printed stage order)
       const bool in_hbm = l == 0 ? X->loc == HT_LOC_DEVICE : res_h == HT_RES_HBM;
       const bool out_hbm = l == L - 1 || res_h == HT_RES_HBM;
       const bool gout_hbm = l == L - 1 || res_g == HT_RES_HBM;
@@ -1083,6 +1156,7 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
                ws->res_g == res_g && ws->upd_mask == upd_mask && ws->no_ckpt == recompute;
   if (reuse)
     for (int l = 0; l <= L; ++l) reuse = reuse && ws->dims[l] == model->dims[l];
+  const bool reuse0 = reuse && want_reuse0 && ws->a0_of == X->ptr && ws->a0_graph == g && ws->a[0].ptr;
   if (!reuse) {
     ht_epoch_ws_free(ctx);
     ws = new (std::nothrow) EpochWs();
@@ -1154,10 +1228,19 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
     R.layer = l;
     const bool upd = (upd_mask >> l) & 1;
     d.order = upd ? HT_ORDER_UPDATE_FIRST : HT_ORDER_AGG_FIRST;
-    int rc = upd ? layer_fwd_update_first(R, &d, l == 0 ? X : &ws->h[l], model->W[l], &ws->h[l + 1])
-                 : layer_fwd_impl(R, &d, l == 0 ? X : &ws->h[l], model->W[l], &ws->h[l + 1],
-                                  recompute ? nullptr : &ws->a[l]);
-    if (rc != HT_OK) return fail(rc);
+    int rc = upd                ? layer_fwd_update_first(R, &d, l == 0 ? X : &ws->h[l], model->W[l], &ws->h[l + 1])
+             : (l == 0 && reuse0) ? layer_fwd_from_ckpt(R, &d, &ws->a[0], model->W[0], &ws->h[1])
+                                  : layer_fwd_impl(R, &d, l == 0 ? X : &ws->h[l], model->W[l], &ws->h[l + 1],
+                                                   recompute ? nullptr : &ws->a[l]);
+    if (rc != HT_OK) {
+      ws->a0_of = nullptr;
+      return fail(rc);
+    }
+    if (l == 0) {   // a^0 = A_hat X is in a[0] from here on (the backward pass only reads it)
+      const bool kept = !upd && !recompute;
+      ws->a0_of = kept ? X->ptr : nullptr;
+      ws->a0_graph = kept ? g : nullptr;
+    }
   }
   // ---- downstream task and its gradient (Alg. 1)
   {
