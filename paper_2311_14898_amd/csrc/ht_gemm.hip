@@ -56,10 +56,14 @@ __global__ void __launch_bounds__(256) k_gemm_nn(const float* __restrict__ A, in
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  for (int k0 = 0; k0 < K; k0 += BK) {
-    // A tile: BM rows x 16 floats = BM*4 float4
+  // The tiles of step k0 + BK are fetched into registers while the matrix cores work on step k0.
+  constexpr int NA = BM * 4 / 256, NB = BK * BN / 4 / 256;
+  static_assert(NA * 256 == BM * 4 && NB * 256 == BK * BN / 4, "tile loads must divide among 256 threads");
+  float4 ra[NA], rb[NB];
+  auto fetch = [&](int k0) {
 #pragma unroll
-    for (int f = tid; f < BM * 4; f += 256) {
+    for (int u = 0; u < NA; ++u) {
+      const int f = tid + u * 256;
       const int row = f >> 2, kv = (f & 3) * 4;
       const int64_t gm = m0 + row;
       const int gk = k0 + kv;
@@ -70,17 +74,35 @@ __global__ void __launch_bounds__(256) k_gemm_nn(const float* __restrict__ A, in
         if (gk + 2 >= K) v.z = 0.f;
         if (gk + 3 >= K) v.w = 0.f;
       }
-      float* d = As + row * LDA_S + kv;
-      d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+      ra[u] = v;
     }
-    // B tile: 16 rows x BN floats
 #pragma unroll
-    for (int f = tid; f < BK * BN / 4; f += 256) {
+    for (int u = 0; u < NB; ++u) {
+      const int f = tid + u * 256;
       const int kr = f / (BN / 4), nv = (f % (BN / 4)) * 4;
-      const float4 v = ld4g(Bp + (int64_t)(k0 + kr) * Np + n0 + nv);
-      *reinterpret_cast<float4*>(Bs + kr * (BN + 4) + nv) = v;
+      rb[u] = ld4g(Bp + (int64_t)(k0 + kr) * Np + n0 + nv);
     }
+  };
+  auto stash = [&]() {
+#pragma unroll
+    for (int u = 0; u < NA; ++u) {
+      const int f = tid + u * 256;
+      const int row = f >> 2, kv = (f & 3) * 4;
+      float* d = As + row * LDA_S + kv;
+      d[0] = ra[u].x; d[1] = ra[u].y; d[2] = ra[u].z; d[3] = ra[u].w;
+    }
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+      const int f = tid + u * 256;
+      const int kr = f / (BN / 4), nv = (f % (BN / 4)) * 4;
+      *reinterpret_cast<float4*>(Bs + kr * (BN + 4) + nv) = rb[u];
+    }
+  };
+  fetch(0);
+  for (int k0 = 0; k0 < K; k0 += BK) {
+    stash();
     __syncthreads();
+    if (k0 + BK < K) fetch(k0 + BK);
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 2) {
       float af[TI], bf[TJ];
@@ -140,9 +162,13 @@ __global__ void __launch_bounds__(256) k_gemm_tn(const float* __restrict__ A, in
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  for (int64_t mm0 = ms; mm0 < me; mm0 += BK) {
+  constexpr int NA = BK * BM / 4 / 256, NB = BK * BN / 4 / 256;
+  static_assert(NA * 256 == BK * BM / 4 && NB * 256 == BK * BN / 4, "tile loads must divide among 256 threads");
+  float4 ra[NA], rb[NB];
+  auto fetch = [&](int64_t mm0) {
 #pragma unroll
-    for (int f = tid; f < BK * BM / 4; f += 256) {
+    for (int u = 0; u < NA; ++u) {
+      const int f = tid + u * 256;
       const int mr = f / (BM / 4), cv = (f % (BM / 4)) * 4;
       const int64_t gm = mm0 + mr;
       const int gk = kc0 + cv;
@@ -153,10 +179,11 @@ __global__ void __launch_bounds__(256) k_gemm_tn(const float* __restrict__ A, in
         if (gk + 2 >= K) v.z = 0.f;
         if (gk + 3 >= K) v.w = 0.f;
       }
-      *reinterpret_cast<float4*>(As + mr * (BM + 4) + cv) = v;
+      ra[u] = v;
     }
 #pragma unroll
-    for (int f = tid; f < BK * BN / 4; f += 256) {
+    for (int u = 0; u < NB; ++u) {
+      const int f = tid + u * 256;
       const int mr = f / (BN / 4), cv = (f % (BN / 4)) * 4;
       const int64_t gm = mm0 + mr;
       const int gn = n0 + cv;
@@ -167,9 +194,28 @@ __global__ void __launch_bounds__(256) k_gemm_tn(const float* __restrict__ A, in
         if (gn + 2 >= N) v.z = 0.f;
         if (gn + 3 >= N) v.w = 0.f;
       }
-      *reinterpret_cast<float4*>(Bs + mr * (BN + 4) + cv) = v;
+      rb[u] = v;
     }
+  };
+  auto stash = [&]() {
+#pragma unroll
+    for (int u = 0; u < NA; ++u) {
+      const int f = tid + u * 256;
+      const int mr = f / (BM / 4), cv = (f % (BM / 4)) * 4;
+      *reinterpret_cast<float4*>(As + mr * (BM + 4) + cv) = ra[u];
+    }
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+      const int f = tid + u * 256;
+      const int mr = f / (BN / 4), cv = (f % (BN / 4)) * 4;
+      *reinterpret_cast<float4*>(Bs + mr * (BN + 4) + cv) = rb[u];
+    }
+  };
+  if (ms < me) fetch(ms);
+  for (int64_t mm0 = ms; mm0 < me; mm0 += BK) {
+    stash();
     __syncthreads();
+    if (mm0 + BK < me) fetch(mm0 + BK);
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 2) {
       float af[TI], bf[TJ];
