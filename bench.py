@@ -325,6 +325,21 @@ def main():
                      "t_spmm_bwd_ms": r_tot["t_spmm_bwd_ms"] / args.steps, "t_gemm_ms": r_tot["t_gemm_ms"] / args.steps,
                      "bytes_h2d_per_step": r_tot["bytes_h2d"] / args.steps,
                      "note": "steady-state epochs that take layer 0's aggregate from an earlier epoch (same X and graph)"}
+    graph_run = None
+    if not host and not args.no_other_order:
+        # the same epochs (printed order) without per-phase events, eagerly and as HIP graph replays
+        def plain(use_graph):
+            for _ in range(3):          # eager epoch, captured epoch, first replay
+                B.ht_epoch(ctx, g, w.dims, Wd, w.lr, Xd, yd, order=main_order, use_graph=use_graph, **plan)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                B.ht_epoch(ctx, g, w.dims, Wd, w.lr, Xd, yd, order=main_order, use_graph=use_graph, **plan)
+            torch.cuda.synchronize()
+            return 1e3 * (time.perf_counter() - t0) / args.steps
+        n0 = B.ht_ctx_graph_launches(ctx)
+        graph_run = {"eager_no_stats_ms_per_step": plain(False), "graph_ms_per_step": plain(True),
+                     "graph_launches": B.ht_ctx_graph_launches(ctx) - n0}
     ms_per_step = 1e3 * elapsed / args.steps
     Ep = info.E_stored
     L = w.n_layers
@@ -367,7 +382,7 @@ def main():
            "bytes_h2d_nodedup_per_step": tot["bytes_h2d_nodedup"] / args.steps,
            "input_generation_s": t_gen,
            "paper_context": "HongTu-IM 2-layer GCN on reddit (same shape), 1xA100: 0.20 s/epoch (Table 4); other hardware, real dataset",
-           "order": args.order, "other_order": other, "input_aggregate_reuse": reuse_run,
+           "order": args.order, "other_order": other, "input_aggregate_reuse": reuse_run, "hip_graph": graph_run,
            "plan": {"inter": ["auto", "mask", "hybrid", "recompute"][tot["plan_inter"] // args.steps],
                     "h": ["-", "hbm", "host"][tot["plan_res_h"] // args.steps],
                     "a": ["-", "hbm", "host"][tot["plan_res_a"] // args.steps],

@@ -82,6 +82,9 @@ int ht_sync(ht_ctx *ctx);
 /* Cap on bytes the library may allocate in HBM through this context
  * (0 = no cap).  Exceeding it makes the allocating call return HT_ENOMEM. */
 int ht_ctx_set_hbm_budget(ht_ctx *ctx, int64_t bytes);
+/* Number of ht_epoch calls on this context that ran as one HIP graph launch
+ * (ht_plan_opts.use_graph); -1 for a null context. */
+int64_t ht_ctx_graph_launches(const ht_ctx *ctx);
 const char *ht_strerror(int code);
 const char *ht_last_error(const ht_ctx *ctx);
 
@@ -387,7 +390,10 @@ typedef struct {
                    * keeps the printed stage order whatever `order` says).  Ignored on the
                    * first epoch, after a change of shape, plan or X pointer, and with
                    * HT_INTER_RECOMPUTE.  Not part of the paper's method: 0 reproduces it. */
-  int32_t reserved;
+  int32_t use_graph; /* 1: when every tensor of the epoch is in HBM and no stats are asked for, the
+                   * epoch's kernels are captured into a HIP graph on the second call with the same
+                   * graph, X, labels, parameter pointers, lr and plan, and replayed from then on
+                   * (same kernels, same order: same bits).  Ignored otherwise. */
 } ht_plan_opts;
 
 /* One training epoch (Alg. 1): forward over layers and chunks, softmax

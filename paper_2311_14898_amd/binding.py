@@ -105,10 +105,10 @@ class ht_gat_model(C.Structure):
 class ht_plan_opts(C.Structure):
     _fields_ = [("res_h", C.c_int32), ("res_a", C.c_int32), ("res_g", C.c_int32), ("inter", C.c_int32),
                 ("gather_mode", C.c_int32), ("order", C.c_int32), ("hbm_budget_bytes", C.c_int64),
-                ("reuse_input_aggregate", C.c_int32), ("reserved", C.c_int32)]
+                ("reuse_input_aggregate", C.c_int32), ("use_graph", C.c_int32)]
 
 
-EXPORTS = ["ht_ctx_create", "ht_ctx_destroy", "ht_sync", "ht_ctx_set_hbm_budget", "ht_strerror", "ht_last_error",
+EXPORTS = ["ht_ctx_create", "ht_ctx_destroy", "ht_sync", "ht_ctx_set_hbm_budget", "ht_ctx_graph_launches", "ht_strerror", "ht_last_error",
            "ht_partition", "ht_graph_destroy", "ht_graph_info_get", "ht_graph_chunk_info", "ht_graph_export_chunk",
            "ht_graph_export_csc", "ht_graph_chunk_order", "ht_layer_fwd", "ht_layer_bwd", "ht_epoch", "ht_epoch_buffer", "ht_tensor_to_host", "ht_memory_model",
            "ht_chunk_rows_model", "ht_gat_layer_fwd", "ht_gat_layer_bwd", "ht_gat_epoch", "ht_gat_scores", "ht_comm_cost_model"]
@@ -142,6 +142,8 @@ def load():
     lib.ht_ctx_destroy.argtypes = [C.c_void_p]
     lib.ht_sync.argtypes = [C.c_void_p]
     lib.ht_ctx_set_hbm_budget.argtypes = [C.c_void_p, C.c_int64]
+    lib.ht_ctx_graph_launches.argtypes = [C.c_void_p]
+    lib.ht_ctx_graph_launches.restype = C.c_int64
     lib.ht_partition.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_int32,
                                  C.POINTER(ht_part_opts), C.POINTER(C.c_void_p)]
     lib.ht_graph_destroy.argtypes = [C.c_void_p]
@@ -227,6 +229,10 @@ def ht_ctx_destroy(ctx):
 
 def ht_sync(ctx):
     _check(load().ht_sync(ctx), ctx)
+
+
+def ht_ctx_graph_launches(ctx) -> int:
+    return int(load().ht_ctx_graph_launches(ctx))
 
 
 def ht_ctx_set_hbm_budget(ctx, nbytes: int):
@@ -416,7 +422,7 @@ def ht_gat_epoch(ctx, g, dims: Sequence[int], Ws: List[torch.Tensor], a_dst: Lis
 def ht_epoch(ctx, g, dims: Sequence[int], Ws: List[torch.Tensor], lr: float, X: torch.Tensor, labels: torch.Tensor,
              res_h: int = HT_RES_AUTO, res_a: int = HT_RES_AUTO, res_g: int = HT_RES_AUTO, inter: int = HT_INTER_AUTO,
              gather_mode: int = HT_GATHER_AUTO, hbm_budget_bytes: int = 0, want_stats: bool = False, sync: bool = True,
-             order: int = HT_ORDER_AGG_FIRST, reuse_input_aggregate: bool = False):
+             order: int = HT_ORDER_AGG_FIRST, reuse_input_aggregate: bool = False, use_graph: bool = False):
     """One epoch; Ws (device tensors) are updated in place.  Returns (loss, stats or None)."""
     L = len(dims) - 1
     assert len(Ws) == L and labels.is_cuda and labels.dtype == torch.int32
@@ -425,7 +431,7 @@ def ht_epoch(ctx, g, dims: Sequence[int], Ws: List[torch.Tensor], lr: float, X: 
     dims_a = (C.c_int32 * (L + 1))(*dims)
     Wp = (C.c_void_p * L)(*[w.data_ptr() for w in Ws])
     model = ht_model(L, 0, dims_a, Wp, lr, 0)
-    plan = ht_plan_opts(res_h, res_a, res_g, inter, gather_mode, order, hbm_budget_bytes, int(reuse_input_aggregate), 0)
+    plan = ht_plan_opts(res_h, res_a, res_g, inter, gather_mode, order, hbm_budget_bytes, int(reuse_input_aggregate), int(use_graph))
     x = tensor_view(X, dims[0])
     loss = C.c_float(0.0)
     st = ht_stats() if want_stats else None

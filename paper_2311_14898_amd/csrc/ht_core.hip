@@ -48,6 +48,7 @@ int ht_scratch(ht_ctx* ctx, int slot, size_t bytes, void** out) {
     int rc = ht_dev_alloc(ctx, &ctx->scratch[slot], want);
     if (rc != HT_OK) return rc;
     ctx->scratch_bytes[slot] = want;
+    ++ctx->scratch_gen;
   }
   *out = ctx->scratch[slot];
   return HT_OK;
@@ -180,6 +181,8 @@ int ht_sync(ht_ctx* ctx) {
   for (int i = 0; i < 3; ++i) HT_HIP(ctx, hipStreamSynchronize(ctx->side[i]));
   return HT_OK;
 }
+
+int64_t ht_ctx_graph_launches(const ht_ctx* ctx) { return ctx ? ctx->graph_launches : -1; }
 
 int ht_ctx_set_hbm_budget(ht_ctx* ctx, int64_t bytes) {
   if (!ctx || bytes < 0) return HT_EINVAL;

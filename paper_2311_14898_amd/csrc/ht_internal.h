@@ -36,6 +36,8 @@ struct ht_ctx {
   size_t ev_next = 0;
   EpochWs* ws = nullptr;  // buffers of the last ht_epoch
   // device scratch that calls keep between invocations (grow-only)
+  int64_t graph_launches = 0; // epochs that ran as one HIP graph launch
+  uint64_t scratch_gen = 0;   // bumped whenever a scratch slot is (re)allocated: captured pointers into scratch are stale then
   void* scratch[HT_N_SCRATCH] = {};
   size_t scratch_bytes[HT_N_SCRATCH] = {};
   // pinned host scratch (D2H staging of gradient rows)
@@ -174,6 +176,7 @@ struct ChunkMeta {
 
 struct ht_graph {
   ht_ctx* ctx = nullptr;
+  uint64_t serial = 0;         // unique per ht_partition call in this process: tells graphs at one address apart
   int64_t V = 0, Ep = 0;
   int32_t n = 0;
   int32_t add_self_loops = 1;

@@ -31,7 +31,11 @@ struct EpochWs {
   std::vector<void*> host_ptrs;
   float* loss_dev = nullptr;
   const float* a0_of = nullptr;      // a[0] holds A_hat X for the X at this address (nullptr: not valid)
-  const ht_graph* a0_graph = nullptr;
+  uint64_t a0_graph = 0;             // ... and for the graph with this serial number
+  // HIP graph of one epoch's stream work (all tensors in HBM): what it was captured for, and the
+  // key of the last epoch that ran eagerly to the end (its scratch sizes are what the capture needs)
+  std::vector<uintptr_t> graph_key, warm_key;
+  hipGraphExec_t graph_exec = nullptr;
 };
 
 namespace {
@@ -978,6 +982,7 @@ void ht_epoch_ws_free(ht_ctx* ctx) {
   (void)hipStreamSynchronize(ctx->stream);
   for (size_t i = 0; i < ws->dev_ptrs.size(); ++i) ht_dev_free(ctx, ws->dev_ptrs[i], ws->dev_bytes_of[i]);
   for (void* p : ws->host_ptrs) (void)hipHostFree(p);
+  if (ws->graph_exec) (void)hipGraphExecDestroy(ws->graph_exec);
   delete ws;
   ctx->ws = nullptr;
 }
@@ -1156,7 +1161,7 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
                ws->res_g == res_g && ws->upd_mask == upd_mask && ws->no_ckpt == recompute;
   if (reuse)
     for (int l = 0; l <= L; ++l) reuse = reuse && ws->dims[l] == model->dims[l];
-  const bool reuse0 = reuse && want_reuse0 && ws->a0_of == X->ptr && ws->a0_graph == g && ws->a[0].ptr;
+  const bool reuse0 = reuse && want_reuse0 && ws->a0_of == X->ptr && ws->a0_graph == g->serial && ws->a[0].ptr;
   if (!reuse) {
     ht_epoch_ws_free(ctx);
     ws = new (std::nothrow) EpochWs();
@@ -1219,73 +1224,131 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
         for (ht_tensor* t : todo) std::memset(t->ptr, 0, (size_t)t->rows * t->ld * 4);
       });
   }
-  // ---- forward (Alg. 1)
-  for (int l = 0; l < L; ++l) {
-    ht_layer_desc d{};
-    d.d_in = model->dims[l]; d.d_out = model->dims[l + 1];
-    d.act = l < L - 1 ? HT_ACT_RELU : HT_ACT_NONE;
-    d.gather_mode = gather_mode;
-    R.layer = l;
-    const bool upd = (upd_mask >> l) & 1;
-    d.order = upd ? HT_ORDER_UPDATE_FIRST : HT_ORDER_AGG_FIRST;
-    int rc = upd                ? layer_fwd_update_first(R, &d, l == 0 ? X : &ws->h[l], model->W[l], &ws->h[l + 1])
-             : (l == 0 && reuse0) ? layer_fwd_from_ckpt(R, &d, &ws->a[0], model->W[0], &ws->h[1])
-                                  : layer_fwd_impl(R, &d, l == 0 ? X : &ws->h[l], model->W[l], &ws->h[l + 1],
-                                                   recompute ? nullptr : &ws->a[l]);
-    if (rc != HT_OK) {
-      ws->a0_of = nullptr;
-      return fail(rc);
-    }
-    if (l == 0) {   // a^0 = A_hat X is in a[0] from here on (the backward pass only reads it)
-      const bool kept = !upd && !recompute;
-      ws->a0_of = kept ? X->ptr : nullptr;
-      ws->a0_graph = kept ? g : nullptr;
-    }
-  }
-  // ---- downstream task and its gradient (Alg. 1)
-  {
-    R.tm.begin(&R.st->t_loss_ms);
-    int rc = ht_softmax_ce(ctx, ctx->stream, ws->h[L].ptr, ws->h[L].ld, labels, V, model->dims[L], ws->gh[L].ptr,
-                           ws->gh[L].ld, ws->loss_dev);
-    R.tm.end();
-    if (rc != HT_OK) return fail(rc);
-  }
-  // ---- backward (Alg. 1)
-  for (int l = L - 1; l >= 0; --l) {
-    ht_layer_desc d{};
-    d.d_in = model->dims[l]; d.d_out = model->dims[l + 1];
-    d.act = l < L - 1 ? HT_ACT_RELU : HT_ACT_NONE;
-    d.gather_mode = gather_mode;
-    d.ckpt_kind = recompute ? HT_CKPT_INPUT : HT_CKPT_AGG;
-    R.dhin_is_zero = false;
-    if (l > 0) {
-      if (ws->gh[l].loc == HT_LOC_HOST_PINNED) {
-        if (zeroer.th.joinable()) zeroer.th.join();     // cleared beside the forward pass (or stored exactly once)
-      } else {
-        int rc = zero_tensor(ctx, &ws->gh[l]);
-        if (rc != HT_OK) return fail(rc);
+  // ---- the epoch's stream work.  With every tensor in HBM it is kernels on one stream only, so it
+  // can be recorded once into a HIP graph and replayed (ht_plan_opts.use_graph): the first epoch of a
+  // key runs eagerly (it sizes the scratch memory, which a capture may not allocate), the second is
+  // captured, instantiated and launched, later ones are one graph launch.
+  auto enqueue = [&]() -> int {
+    // ---- forward (Alg. 1)
+    for (int l = 0; l < L; ++l) {
+      ht_layer_desc d{};
+      d.d_in = model->dims[l]; d.d_out = model->dims[l + 1];
+      d.act = l < L - 1 ? HT_ACT_RELU : HT_ACT_NONE;
+      d.gather_mode = gather_mode;
+      R.layer = l;
+      const bool upd = (upd_mask >> l) & 1;
+      d.order = upd ? HT_ORDER_UPDATE_FIRST : HT_ORDER_AGG_FIRST;
+      int rc = upd                ? layer_fwd_update_first(R, &d, l == 0 ? X : &ws->h[l], model->W[l], &ws->h[l + 1])
+               : (l == 0 && reuse0) ? layer_fwd_from_ckpt(R, &d, &ws->a[0], model->W[0], &ws->h[1])
+                                    : layer_fwd_impl(R, &d, l == 0 ? X : &ws->h[l], model->W[l], &ws->h[l + 1],
+                                                     recompute ? nullptr : &ws->a[l]);
+      if (rc != HT_OK) {
+        ws->a0_of = nullptr;
+        return rc;
       }
-      R.dhin_is_zero = true;
+      if (l == 0) {   // a^0 = A_hat X is in a[0] from here on (the backward pass only reads it)
+        const bool kept = !upd && !recompute;
+        ws->a0_of = kept ? X->ptr : nullptr;
+        ws->a0_graph = kept ? g->serial : 0;
+      }
     }
-    R.layer = l;
-    const bool mask_ok = inter == HT_INTER_MASK || (recompute && ws->h[l + 1].loc == HT_LOC_DEVICE);
-    const ht_tensor* mask_from = (mask_ok && l < L - 1) ? &ws->h[l + 1] : nullptr;
-    const ht_tensor* ckpt = recompute ? (l == 0 ? X : &ws->h[l]) : &ws->a[l];
-    const bool upd = (upd_mask >> l) & 1;
-    d.order = upd ? HT_ORDER_UPDATE_FIRST : HT_ORDER_AGG_FIRST;
-    int rc = upd ? layer_bwd_update_first(R, &d, l == 0 ? X : &ws->h[l], model->W[l], &ws->gh[l + 1],
-                                          l < L - 1 ? &ws->h[l + 1] : nullptr, l > 0 ? &ws->gh[l] : nullptr, ws->dW[l])
-                 : layer_bwd_impl(R, &d, ckpt, model->W[l], &ws->gh[l + 1], mask_from,
-                                  l > 0 ? &ws->gh[l] : nullptr, ws->dW[l]);
-    if (rc != HT_OK) return fail(rc);
+    // ---- downstream task and its gradient (Alg. 1)
+    {
+      R.tm.begin(&R.st->t_loss_ms);
+      int rc = ht_softmax_ce(ctx, ctx->stream, ws->h[L].ptr, ws->h[L].ld, labels, V, model->dims[L], ws->gh[L].ptr,
+                             ws->gh[L].ld, ws->loss_dev);
+      R.tm.end();
+      if (rc != HT_OK) return rc;
+    }
+    // ---- backward (Alg. 1)
+    for (int l = L - 1; l >= 0; --l) {
+      ht_layer_desc d{};
+      d.d_in = model->dims[l]; d.d_out = model->dims[l + 1];
+      d.act = l < L - 1 ? HT_ACT_RELU : HT_ACT_NONE;
+      d.gather_mode = gather_mode;
+      d.ckpt_kind = recompute ? HT_CKPT_INPUT : HT_CKPT_AGG;
+      R.dhin_is_zero = false;
+      if (l > 0) {
+        if (ws->gh[l].loc == HT_LOC_HOST_PINNED) {
+          if (zeroer.th.joinable()) zeroer.th.join();     // cleared beside the forward pass (or stored exactly once)
+        } else {
+          int rc = zero_tensor(ctx, &ws->gh[l]);
+          if (rc != HT_OK) return rc;
+        }
+        R.dhin_is_zero = true;
+      }
+      R.layer = l;
+      const bool mask_ok = inter == HT_INTER_MASK || (recompute && ws->h[l + 1].loc == HT_LOC_DEVICE);
+      const ht_tensor* mask_from = (mask_ok && l < L - 1) ? &ws->h[l + 1] : nullptr;
+      const ht_tensor* ckpt = recompute ? (l == 0 ? X : &ws->h[l]) : &ws->a[l];
+      const bool upd = (upd_mask >> l) & 1;
+      d.order = upd ? HT_ORDER_UPDATE_FIRST : HT_ORDER_AGG_FIRST;
+      int rc = upd ? layer_bwd_update_first(R, &d, l == 0 ? X : &ws->h[l], model->W[l], &ws->gh[l + 1],
+                                            l < L - 1 ? &ws->h[l + 1] : nullptr, l > 0 ? &ws->gh[l] : nullptr, ws->dW[l])
+                   : layer_bwd_impl(R, &d, ckpt, model->W[l], &ws->gh[l + 1], mask_from,
+                                    l > 0 ? &ws->gh[l] : nullptr, ws->dW[l]);
+      if (rc != HT_OK) return rc;
+    }
+    // ---- parameter update (Alg. 1)
+    R.tm.begin(&R.st->t_update_ms);
+    for (int l = 0; l < L; ++l) {
+      int rc = ht_sgd(ctx, ctx->stream, model->W[l], ws->dW[l], (int64_t)model->dims[l] * model->dims[l + 1], model->lr);
+      if (rc != HT_OK) return rc;
+    }
+    R.tm.end();
+    return HT_OK;
+  };
+  const bool all_hbm = X->loc == HT_LOC_DEVICE && res_h == HT_RES_HBM && res_g == HT_RES_HBM && (recompute || res_a == HT_RES_HBM);
+  std::vector<uintptr_t> key;
+  if (plan && plan->use_graph && all_hbm && !stats) {
+    key = {(uintptr_t)g->serial, (uintptr_t)ctx->scratch_gen, (uintptr_t)X->ptr, (uintptr_t)X->ld, (uintptr_t)labels, (uintptr_t)inter, (uintptr_t)upd_mask,
+           (uintptr_t)reuse0, (uintptr_t)gather_mode, (uintptr_t)L};
+    uint32_t lr_bits;
+    std::memcpy(&lr_bits, &model->lr, 4);
+    key.push_back(lr_bits);
+    for (int l = 0; l < L; ++l) key.push_back((uintptr_t)model->W[l]);
   }
-  // ---- parameter update (Alg. 1)
-  R.tm.begin(&R.st->t_update_ms);
-  for (int l = 0; l < L; ++l) {
-    int rc = ht_sgd(ctx, ctx->stream, model->W[l], ws->dW[l], (int64_t)model->dims[l] * model->dims[l + 1], model->lr);
-    if (rc != HT_OK) return fail(rc);
+  bool launched = false;
+  if (!key.empty() && ws->graph_exec && ws->graph_key == key) {
+    hipError_t e = hipGraphLaunch(ws->graph_exec, ctx->stream);
+    if (e != hipSuccess) return fail(ht_set_err(ctx, HT_EHIP, "hipGraphLaunch: %s", hipGetErrorString(e)));
+    launched = true;
+    ++ctx->graph_launches;
+  } else if (!key.empty() && ws->warm_key == key) {
+    if (ws->graph_exec) {
+      (void)hipGraphExecDestroy(ws->graph_exec);
+      ws->graph_exec = nullptr;
+      ws->graph_key.clear();
+    }
+    hipGraph_t graph = nullptr;
+    hipError_t e = hipStreamBeginCapture(ctx->stream, hipStreamCaptureModeThreadLocal);
+    if (e != hipSuccess) return fail(ht_set_err(ctx, HT_EHIP, "hipStreamBeginCapture: %s", hipGetErrorString(e)));
+    const int rc = enqueue();
+    e = hipStreamEndCapture(ctx->stream, &graph);
+    if (rc == HT_OK && e == hipSuccess && graph) {
+      e = hipGraphInstantiate(&ws->graph_exec, graph, nullptr, nullptr, 0);
+      if (e == hipSuccess) e = hipGraphLaunch(ws->graph_exec, ctx->stream);
+      if (e == hipSuccess) {
+        ws->graph_key = key;
+        launched = true;
+        ++ctx->graph_launches;
+      } else if (ws->graph_exec) {
+        (void)hipGraphExecDestroy(ws->graph_exec);
+        ws->graph_exec = nullptr;
+      }
+    }
+    if (graph) (void)hipGraphDestroy(graph);
+    if (!launched) {   // nothing has run: this epoch runs eagerly below, and the key is not tried again
+      (void)hipGetLastError();
+      ws->warm_key.clear();
+      ws->a0_of = reuse0 ? ws->a0_of : nullptr;
+    }
   }
-  R.tm.end();
+  if (!launched) {
+    const int rc = enqueue();
+    if (rc != HT_OK) return fail(rc);
+    ws->warm_key = key;
+  }
   {
     hipError_t e = hipMemcpyAsync(loss_out, ws->loss_dev, 4, hipMemcpyDeviceToHost, ctx->stream);
     if (e != hipSuccess) return fail(ht_set_err(ctx, HT_EHIP, "loss copy: %s", hipGetErrorString(e)));

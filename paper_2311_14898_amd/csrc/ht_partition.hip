@@ -8,6 +8,7 @@
 // Sec. 6 (same buffer position for duplicated vertices of adjacent chunks;
 // loaded rows take freed positions; topology rewritten to buffer positions).
 #include <algorithm>
+#include <atomic>
 #include <cstdlib>
 
 #include "ht_internal.h"
@@ -1130,7 +1131,9 @@ int ht_partition(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src, const in
     return ht_set_err(ctx, HT_EINVAL, "ht_partition: bad options");
   HT_HIP(ctx, hipSetDevice(ctx->device));
   auto t0 = std::chrono::steady_clock::now();
+  static std::atomic<uint64_t> next_serial{1};
   ht_graph* g = new (std::nothrow) ht_graph();
+  if (g) g->serial = next_serial.fetch_add(1);
   if (!g) return ht_set_err(ctx, HT_ENOMEM, "ht_partition: host allocation failed");
   int rc = partition_impl(ctx, V, E, src, dst, n_chunks, opts, g);
   if (rc != HT_OK) {

@@ -207,6 +207,41 @@ def test_input_aggregate_reused_across_epochs(ctx, cfg1):
             B.ht_graph_destroy(g)
 
 
+def test_epoch_replayed_from_a_hip_graph(ctx, cfg1):
+    """use_graph: the first epoch of a key runs eagerly, the second is captured and launched, later ones are
+    replays.  Every epoch must give the bits of an eager epoch, with other work on the context (also work that
+    reallocates the library's scratch memory) and synchronisations between the replays, and after a change of lr."""
+    w, src, dst, X, y, Ws, ref = cfg1
+    g = B.ht_partition(ctx, w.V, src.cuda(), dst.cuda(), w.n_chunks)
+    try:
+        Xd, yd = B.to_matrix(X), y.cuda()
+        for order, reuse in ((B.HT_ORDER_AGG_FIRST, False), (B.HT_ORDER_AUTO, True)):
+            lrs = [w.lr] * 6 + [0.5] * 4
+            eager, Wd = [], [x.clone().cuda() for x in Ws]
+            for lr in lrs:
+                loss, _ = B.ht_epoch(ctx, g, w.dims, Wd, lr, Xd, yd, order=order, reuse_input_aggregate=reuse)
+                eager.append((loss, [x.cpu().numpy().copy() for x in Wd]))
+            Wd = [x.clone().cuda() for x in Ws]
+            n_graph = B.ht_ctx_graph_launches(ctx)
+            side_in = B.to_matrix(inputs.features(w.V, 24, seed=9))
+            big_in = B.to_matrix(inputs.features(w.V, 200, seed=10))
+            for k, lr in enumerate(lrs):
+                loss, _ = B.ht_epoch(ctx, g, w.dims, Wd, lr, Xd, yd, order=order, reuse_input_aggregate=reuse, use_graph=True)
+                assert loss == eager[k][0], (k, loss, eager[k][0])
+                for a, b in zip(Wd, eager[k][1]):
+                    assert np.array_equal(a.cpu().numpy(), b), f"epoch {k}"
+                # other work between the epochs: a layer on the same context (it overwrites scratch memory), once
+                # with rows so wide that scratch slots grow and move (k == 3: in the middle of the replays)
+                d_in, h_in = (200, big_in) if k == 3 else (24, side_in)
+                Wl = torch.ones(d_in, 16, device="cuda")
+                B.ht_layer_fwd(ctx, g, d_in, 16, B.HT_ACT_RELU, h_in, Wl, B.alloc_matrix(w.V, 16), gather_mode=B.HT_GATHER_BUFFER)
+                torch.cuda.synchronize()
+            # eager, captured + launched, replays; after the scratch moved and after the new lr: eager, captured, replays
+            assert B.ht_ctx_graph_launches(ctx) - n_graph >= 5, B.ht_ctx_graph_launches(ctx) - n_graph
+    finally:
+        B.ht_graph_destroy(g)
+
+
 def test_planner_prices_recomputation_against_the_host_side_cache(ctx, cfg1):
     """HT_INTER_AUTO under a byte budget that a^l does not fit (Sec. 4.2's trade-off, priced for this GPU)."""
     w, src, dst, X, y, Ws, ref = cfg1
