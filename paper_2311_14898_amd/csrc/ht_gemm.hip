@@ -60,21 +60,32 @@ __global__ void __launch_bounds__(256) k_gemm_nn(const float* __restrict__ A, in
   constexpr int NA = BM * 4 / 256, NB = BK * BN / 4 / 256;
   static_assert(NA * 256 == BM * 4 && NB * 256 == BK * BN / 4, "tile loads must divide among 256 threads");
   float4 ra[NA], rb[NB];
+  // interior blocks (all BM rows exist) take their full K-steps without any bounds test
+  const bool interior = m0 + BM <= M;
   auto fetch = [&](int k0) {
+    if (interior && k0 + BK <= K) {
 #pragma unroll
-    for (int u = 0; u < NA; ++u) {
-      const int f = tid + u * 256;
-      const int row = f >> 2, kv = (f & 3) * 4;
-      const int64_t gm = m0 + row;
-      const int gk = k0 + kv;
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (gm < M && gk < K) {
-        v = ld4g(A + gm * lda + gk);
-        if (gk + 1 >= K) v.y = 0.f;
-        if (gk + 2 >= K) v.z = 0.f;
-        if (gk + 3 >= K) v.w = 0.f;
+      for (int u = 0; u < NA; ++u) {
+        const int f = tid + u * 256;
+        const int row = f >> 2, kv = (f & 3) * 4;
+        ra[u] = ld4g(A + (m0 + row) * lda + k0 + kv);
       }
-      ra[u] = v;
+    } else {
+#pragma unroll
+      for (int u = 0; u < NA; ++u) {
+        const int f = tid + u * 256;
+        const int row = f >> 2, kv = (f & 3) * 4;
+        const int64_t gm = m0 + row;
+        const int gk = k0 + kv;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (gm < M && gk < K) {
+          v = ld4g(A + gm * lda + gk);
+          if (gk + 1 >= K) v.y = 0.f;
+          if (gk + 2 >= K) v.z = 0.f;
+          if (gk + 3 >= K) v.w = 0.f;
+        }
+        ra[u] = v;
+      }
     }
 #pragma unroll
     for (int u = 0; u < NB; ++u) {
@@ -124,14 +135,24 @@ __global__ void __launch_bounds__(256) k_gemm_nn(const float* __restrict__ A, in
     for (int j = 0; j < TJ; ++j) {
       const int gc = n0 + wn * TJ * 32 + j * 32 + l32;
       if (gc >= N) continue;
+      float* cp = C + (m0 + wm * TI * 32 + i * 32 + half * 4) * ldc + gc;
+      if (interior && relu < 2) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int64_t gr = m0 + wm * TI * 32 + i * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
-        if (gr < M) {
+        for (int e = 0; e < 16; ++e) {
           float v = acc[i][j][e];
-          if (relu & 1) v = v > 0.f ? v : 0.f;
-          if (relu & 2) v += C[gr * ldc + gc];
-          C[gr * ldc + gc] = v;
+          if (relu) v = v > 0.f ? v : 0.f;
+          cp[((e >> 2) * 8 + (e & 3)) * ldc] = v;
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int64_t gr = m0 + wm * TI * 32 + i * 32 + (e >> 2) * 8 + half * 4 + (e & 3);
+          if (gr < M) {
+            float v = acc[i][j][e];
+            if (relu & 1) v = v > 0.f ? v : 0.f;
+            if (relu & 2) v += C[gr * ldc + gc];
+            C[gr * ldc + gc] = v;
+          }
         }
       }
     }
@@ -165,36 +186,57 @@ __global__ void __launch_bounds__(256) k_gemm_tn(const float* __restrict__ A, in
   constexpr int NA = BK * BM / 4 / 256, NB = BK * BN / 4 / 256;
   static_assert(NA * 256 == BK * BM / 4 && NB * 256 == BK * BN / 4, "tile loads must divide among 256 threads");
   float4 ra[NA], rb[NB];
+  // tiles that lie inside both operands are fetched without bounds tests
+  const bool full_a = kc0 + BM <= K, full_b = n0 + BN <= N;
   auto fetch = [&](int64_t mm0) {
+    const bool full_m = mm0 + BK <= me;
+    if (full_m && full_a) {
 #pragma unroll
-    for (int u = 0; u < NA; ++u) {
-      const int f = tid + u * 256;
-      const int mr = f / (BM / 4), cv = (f % (BM / 4)) * 4;
-      const int64_t gm = mm0 + mr;
-      const int gk = kc0 + cv;
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (gm < me && gk < K) {
-        v = ld4g(A + gm * lda + gk);
-        if (gk + 1 >= K) v.y = 0.f;
-        if (gk + 2 >= K) v.z = 0.f;
-        if (gk + 3 >= K) v.w = 0.f;
+      for (int u = 0; u < NA; ++u) {
+        const int f = tid + u * 256;
+        const int mr = f / (BM / 4), cv = (f % (BM / 4)) * 4;
+        ra[u] = ld4g(A + (mm0 + mr) * lda + kc0 + cv);
       }
-      ra[u] = v;
+    } else {
+#pragma unroll
+      for (int u = 0; u < NA; ++u) {
+        const int f = tid + u * 256;
+        const int mr = f / (BM / 4), cv = (f % (BM / 4)) * 4;
+        const int64_t gm = mm0 + mr;
+        const int gk = kc0 + cv;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (gm < me && gk < K) {
+          v = ld4g(A + gm * lda + gk);
+          if (gk + 1 >= K) v.y = 0.f;
+          if (gk + 2 >= K) v.z = 0.f;
+          if (gk + 3 >= K) v.w = 0.f;
+        }
+        ra[u] = v;
+      }
     }
+    if (full_m && full_b) {
 #pragma unroll
-    for (int u = 0; u < NB; ++u) {
-      const int f = tid + u * 256;
-      const int mr = f / (BN / 4), cv = (f % (BN / 4)) * 4;
-      const int64_t gm = mm0 + mr;
-      const int gn = n0 + cv;
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (gm < me && gn < N) {
-        v = ld4g(B + gm * ldb + gn);
-        if (gn + 1 >= N) v.y = 0.f;
-        if (gn + 2 >= N) v.z = 0.f;
-        if (gn + 3 >= N) v.w = 0.f;
+      for (int u = 0; u < NB; ++u) {
+        const int f = tid + u * 256;
+        const int mr = f / (BN / 4), cv = (f % (BN / 4)) * 4;
+        rb[u] = ld4g(B + (mm0 + mr) * ldb + n0 + cv);
       }
-      rb[u] = v;
+    } else {
+#pragma unroll
+      for (int u = 0; u < NB; ++u) {
+        const int f = tid + u * 256;
+        const int mr = f / (BN / 4), cv = (f % (BN / 4)) * 4;
+        const int64_t gm = mm0 + mr;
+        const int gn = n0 + cv;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (gm < me && gn < N) {
+          v = ld4g(B + gm * ldb + gn);
+          if (gn + 1 >= N) v.y = 0.f;
+          if (gn + 2 >= N) v.z = 0.f;
+          if (gn + 3 >= N) v.w = 0.f;
+        }
+        rb[u] = v;
+      }
     }
   };
   auto stash = [&]() {
