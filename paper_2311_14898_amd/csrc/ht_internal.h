@@ -121,14 +121,14 @@ static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b;
 
 // ---- primitives (ht_prims.hip) -------------------------------------------------------
 // Exclusive prefix sum of n values into out[0..n); out[n] = total when want_total.
-// Row pitch (in floats) of a library-allocated [rows x d] matrix: a multiple of 4 (16-byte
-// vectors); in HBM, rows start on 128-byte cache lines when that costs at most 3 % more memory,
-// so a feature slab never shares a line with the slab of another XCD.
 // Rates the epoch planner prices its choices with (measured on MI355X: host link beside compute,
 // rows gathered per second by the aggregation kernel, in bytes).
 constexpr double HT_LINK_BYTES_PER_S = 45e9;
 constexpr double HT_GATHER_BYTES_PER_S = 15e12;
 
+// Row pitch (in floats) of a library-allocated [rows x d] matrix: a multiple of 4 (16-byte
+// vectors); in HBM, rows start on 128-byte cache lines when that costs at most 3 % more memory,
+// so a feature slab never shares a line with the slab of another XCD.
 inline int64_t ht_row_pitch(int32_t d, bool device) {
   const int64_t p4 = ((int64_t)d + 3) & ~(int64_t)3, p32 = ((int64_t)d + 31) & ~(int64_t)31;
   return (device && p32 * 100 <= p4 * 103) ? p32 : p4;
