@@ -97,6 +97,8 @@ def main_gat(args):
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     w = inputs.WORKLOADS[args.workload].scaled(args.scale)
     src, dst = inputs.rmat_edges(w.V, w.E, w.graph_seed, device="cuda")
+    if args.permute_ids:
+        src, dst = inputs.permute_ids(src, dst, w.V)
     X = inputs.features(w.V, w.dims[0])
     y = inputs.labels(w.V, w.dims[-1], labelled_one_in=w.labelled_one_in)
     Ws = inputs.glorot_weights(w.dims)
@@ -212,6 +214,8 @@ def main():
                     help="stage order of a layer: aggregate then transform as Eq. 2 prints it (the timed default), or "
                          "transform first in the layers that get narrower (same function, fewer bytes aggregated)")
     ap.add_argument("--no-other-order", action="store_true", help="do not time the second stage order as well")
+    ap.add_argument("--permute-ids", action="store_true", help="relabel the vertices by a seeded random permutation "
+                    "(sensitivity row: R-MAT keeps its hubs at the low ids)")
     ap.add_argument("--hbm-budget-gb", type=float, default=0, help="byte budget the residency planner works with "
                     "(default: the free HBM)")
     ap.add_argument("--inter", choices=["auto", "hybrid", "recompute"], default="auto",
@@ -245,6 +249,8 @@ def main():
     host = w.residency in ("host", "host_all") and args.residency == "workload"
     t_gen = time.perf_counter()
     src, dst = inputs.rmat_edges(w.V, w.E, w.graph_seed, device="cuda")
+    if args.permute_ids:
+        src, dst = inputs.permute_ids(src, dst, w.V)
     X = inputs.features(w.V, w.dims[0])
     y = inputs.labels(w.V, w.dims[-1], labelled_one_in=w.labelled_one_in)
     Ws = inputs.glorot_weights(w.dims)
@@ -365,7 +371,7 @@ def main():
                       "scale": args.scale},
            "gteps": gteps, "hbm_gbps_dominant_kernel": achieved, "loss": loss,
            "partition_ms": info.partition_ms, "alpha": info.alpha, "v_ori": info.v_ori, "v_ru": info.v_ru,
-           "dedup_row_savings": 1.0 - info.v_ru / max(info.v_ori, 1), "v_load": info.v_load, "cache": args.cache, "reorder": args.reorder,
+           "dedup_row_savings": 1.0 - info.v_ru / max(info.v_ori, 1), "v_load": info.v_load, "cache": args.cache, "reorder": args.reorder, "permuted_ids": args.permute_ids,
            "cache_rows": info.cache_rows,
            "phase_ms_per_step": {k: tot[k] / args.steps for k in
                                  ("t_gather_ms", "t_spmm_fwd_ms", "t_spmm_bwd_ms", "t_gemm_ms", "t_loss_ms", "t_copy_ms",

@@ -126,6 +126,15 @@ def rmat_edges(V: int, E: int, seed: int = 1, device="cpu", batch: int = 1 << 24
     return torch.cat(srcs), torch.cat(dsts)
 
 
+def permute_ids(src: torch.Tensor, dst: torch.Tensor, V: int, seed: int = 7) -> Tuple[torch.Tensor, torch.Tensor]:
+    """The same graph with its vertices relabelled by a seeded random permutation (R-MAT puts the hubs at the
+    low ids; real datasets do not order their vertices that way).  Used for a sensitivity row only."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    perm = torch.randperm(V, generator=g).to(torch.int32).to(src.device)
+    return perm[src.long()], perm[dst.long()]
+
+
 def features(V: int, d: int, seed: int = 2) -> torch.Tensor:
     """N(0,1) fp32 features [V, d], generated on the CPU."""
     g = torch.Generator(device="cpu")
