@@ -101,9 +101,15 @@ __global__ void k_sgd(float* __restrict__ W, const float* __restrict__ dW, int64
   if (i < n) W[i] = W[i] - lr * dW[i];
 }
 
-__global__ void k_zero(uint32_t* __restrict__ p, int64_t n_words) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n_words) p[i] = 0u;
+// n16 16-byte words from p16 (16-byte aligned), then the words of the ragged ends; a bounded grid
+// that strides, so the launch also fits a HIP graph node at any size
+__global__ void k_zero(uint4* __restrict__ p16, int64_t n16, uint32_t* __restrict__ head, int n_head,
+                       uint32_t* __restrict__ tail, int n_tail) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (int64_t i = t; i < n16; i += stride) p16[i] = make_uint4(0u, 0u, 0u, 0u);
+  if (t < n_head) head[t] = 0u;
+  if (t < n_tail) tail[t] = 0u;
 }
 
 }  // namespace
@@ -166,8 +172,17 @@ int ht_sgd(ht_ctx* ctx, hipStream_t st, float* W, const float* dW, int64_t n, fl
 int ht_fill_zero(ht_ctx* ctx, hipStream_t st, void* p, size_t bytes) {
   if (bytes == 0) return HT_OK;
   if (bytes & 3) return ht_set_err(ctx, HT_EINVAL, "fill: size must be a multiple of 4");
+  if ((uintptr_t)p & 3) return ht_set_err(ctx, HT_EINVAL, "fill: pointer must be 4-byte aligned");
   const int64_t n = (int64_t)(bytes >> 2);
-  k_zero<<<(unsigned)((n + 255) / 256), 256, 0, st>>>((uint32_t*)p, n);
+  uint32_t* w = (uint32_t*)p;
+  int n_head = (int)((16 - ((uintptr_t)p & 15)) & 15) >> 2;   // words before the first 16-byte boundary
+  if (n_head > n) n_head = (int)n;
+  const int64_t n16 = (n - n_head) >> 2;
+  const int n_tail = (int)(n - n_head - 4 * n16);
+  int64_t blocks = (n16 + 255) / 256;
+  if (blocks > 16384) blocks = 16384;
+  if (blocks < 1) blocks = 1;
+  k_zero<<<(unsigned)blocks, 256, 0, st>>>((uint4*)(w + n_head), n16, w, n_head, w + n_head + 4 * n16, n_tail);
   HT_LAUNCH_CHECK(ctx);
   return HT_OK;
 }

@@ -34,11 +34,13 @@ struct EpochWs {
   uint64_t a0_graph = 0;             // ... and for the graph with this serial number
   // HIP graph of one epoch's stream work (all tensors in HBM): what it was captured for, and the
   // key of the last epoch that ran eagerly to the end (its scratch sizes are what the capture needs)
-  std::vector<uintptr_t> graph_key, warm_key;
+  std::vector<uintptr_t> graph_key, warm_key, bad_key;   // bad_key: a capture of this key failed, it stays eager
   hipGraphExec_t graph_exec = nullptr;
 };
 
 namespace {
+
+__global__ void k_noop() {}
 
 int check_tensor(ht_ctx* ctx, const ht_tensor* t, int64_t rows, int32_t cols, const char* name) {
   if (!t || !t->ptr) return ht_set_err(ctx, HT_EINVAL, "%s: null tensor", name);
@@ -1228,6 +1230,7 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
   // can be recorded once into a HIP graph and replayed (ht_plan_opts.use_graph): the first epoch of a
   // key runs eagerly (it sizes the scratch memory, which a capture may not allocate), the second is
   // captured, instantiated and launched, later ones are one graph launch.
+  bool in_capture = false;
   auto enqueue = [&]() -> int {
     // ---- forward (Alg. 1)
     for (int l = 0; l < L; ++l) {
@@ -1260,6 +1263,12 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
       R.tm.end();
       if (rc != HT_OK) return rc;
     }
+    if (in_capture)
+      if (const char* dbg = getenv("HT_GRAPH_DEBUG"))
+        if (atoi(dbg) == 3) {   // a launch the runtime rejects on the host, to exercise the fallback after a broken capture
+          k_noop<<<1, 4096, 0, ctx->stream>>>();
+          HT_LAUNCH_CHECK(ctx);
+        }
     // ---- backward (Alg. 1)
     for (int l = L - 1; l >= 0; --l) {
       ht_layer_desc d{};
@@ -1314,7 +1323,7 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
     if (e != hipSuccess) return fail(ht_set_err(ctx, HT_EHIP, "hipGraphLaunch: %s", hipGetErrorString(e)));
     launched = true;
     ++ctx->graph_launches;
-  } else if (!key.empty() && ws->warm_key == key) {
+  } else if (!key.empty() && ws->warm_key == key && ws->bad_key != key) {
     if (ws->graph_exec) {
       (void)hipGraphExecDestroy(ws->graph_exec);
       ws->graph_exec = nullptr;
@@ -1323,8 +1332,12 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
     hipGraph_t graph = nullptr;
     hipError_t e = hipStreamBeginCapture(ctx->stream, hipStreamCaptureModeThreadLocal);
     if (e != hipSuccess) return fail(ht_set_err(ctx, HT_EHIP, "hipStreamBeginCapture: %s", hipGetErrorString(e)));
-    const int rc = enqueue();
+    in_capture = true;
+    int rc = enqueue();
+    in_capture = false;
     e = hipStreamEndCapture(ctx->stream, &graph);
+    if (const char* dbg = getenv("HT_GRAPH_DEBUG"))
+      if (atoi(dbg) == 2 && rc == HT_OK) rc = ht_set_err(ctx, HT_ESTATE, "capture discarded on request");   // exercises the fallback
     if (rc == HT_OK && e == hipSuccess && graph) {
       e = hipGraphInstantiate(&ws->graph_exec, graph, nullptr, nullptr, 0);
       if (e == hipSuccess) e = hipGraphLaunch(ws->graph_exec, ctx->stream);
@@ -1339,8 +1352,10 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
     }
     if (graph) (void)hipGraphDestroy(graph);
     if (!launched) {   // nothing has run: this epoch runs eagerly below, and the key is not tried again
+      if (getenv("HT_GRAPH_DEBUG"))
+        fprintf(stderr, "ht_epoch: graph capture failed (enqueue rc %d: %s; hip: %s)\n", rc, ctx->err.c_str(), hipGetErrorString(e));
       (void)hipGetLastError();
-      ws->warm_key.clear();
+      ws->bad_key = key;
       ws->a0_of = reuse0 ? ws->a0_of : nullptr;
     }
   }

@@ -242,6 +242,30 @@ def test_epoch_replayed_from_a_hip_graph(ctx, cfg1):
         B.ht_graph_destroy(g)
 
 
+def test_epoch_falls_back_when_the_capture_breaks(ctx, cfg1, monkeypatch):
+    """HT_GRAPH_DEBUG=3 makes the library issue, while it captures, one launch that the runtime rejects on the host
+    (an impossible block size; nothing reaches the GPU): the capture is dropped, the epoch runs eagerly with the
+    same result, and that key is not captured again."""
+    w, src, dst, X, y, Ws, ref = cfg1
+    g = B.ht_partition(ctx, w.V, src.cuda(), dst.cuda(), w.n_chunks)
+    try:
+        Xd, yd = B.to_matrix(X), y.cuda()
+        runs = []
+        for broken in (False, True):
+            if broken:
+                monkeypatch.setenv("HT_GRAPH_DEBUG", "3")
+            Wd = [x.clone().cuda() for x in Ws]
+            n0 = B.ht_ctx_graph_launches(ctx)
+            losses = [B.ht_epoch(ctx, g, w.dims, Wd, 0.3, Xd, yd, use_graph=broken)[0] for _ in range(5)]
+            runs.append((losses, [x.cpu().numpy() for x in Wd]))
+            assert B.ht_ctx_graph_launches(ctx) == n0
+        assert runs[0][0] == runs[1][0]
+        for a, b in zip(runs[0][1], runs[1][1]):
+            assert np.array_equal(a, b)
+    finally:
+        B.ht_graph_destroy(g)
+
+
 def test_planner_prices_recomputation_against_the_host_side_cache(ctx, cfg1):
     """HT_INTER_AUTO under a byte budget that a^l does not fit (Sec. 4.2's trade-off, priced for this GPU)."""
     w, src, dst, X, y, Ws, ref = cfg1
