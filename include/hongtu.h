@@ -403,6 +403,11 @@ typedef struct {
 int ht_epoch(ht_ctx *ctx, const ht_graph *g, const ht_model *model, const ht_tensor *X,
              const int32_t *labels, const ht_plan_opts *plan, float *loss_out, ht_stats *stats);
 
+/* Zeros in every row of t (pad columns included), wherever it lives; for the
+ * gradient tensors that ht_layer_bwd / ht_gat_layer_bwd accumulate into.  The call
+ * synchronises. */
+int ht_tensor_zero(ht_ctx *ctx, ht_tensor *t);
+
 /* Views of the buffers the last ht_epoch on ctx left behind (valid until the
  * next ht_epoch with another shape, or ht_ctx_destroy):
  *   kind 0: h^l (l = 1..L)   1: a^l (l = 0..L-1)   2: grad h^l (l = 1..L)

@@ -108,7 +108,7 @@ class ht_plan_opts(C.Structure):
                 ("reuse_input_aggregate", C.c_int32), ("use_graph", C.c_int32)]
 
 
-EXPORTS = ["ht_ctx_create", "ht_ctx_destroy", "ht_sync", "ht_ctx_set_hbm_budget", "ht_ctx_graph_launches", "ht_strerror", "ht_last_error",
+EXPORTS = ["ht_ctx_create", "ht_ctx_destroy", "ht_sync", "ht_ctx_set_hbm_budget", "ht_ctx_graph_launches", "ht_tensor_zero", "ht_strerror", "ht_last_error",
            "ht_partition", "ht_graph_destroy", "ht_graph_info_get", "ht_graph_chunk_info", "ht_graph_export_chunk",
            "ht_graph_export_csc", "ht_graph_chunk_order", "ht_layer_fwd", "ht_layer_bwd", "ht_epoch", "ht_epoch_buffer", "ht_tensor_to_host", "ht_memory_model",
            "ht_chunk_rows_model", "ht_gat_layer_fwd", "ht_gat_layer_bwd", "ht_gat_epoch", "ht_gat_scores", "ht_comm_cost_model"]
@@ -160,6 +160,7 @@ def load():
     lib.ht_epoch.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(ht_model), C.POINTER(ht_tensor), C.c_void_p,
                              C.POINTER(ht_plan_opts), C.POINTER(C.c_float), C.POINTER(ht_stats)]
     lib.ht_epoch_buffer.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(ht_tensor)]
+    lib.ht_tensor_zero.argtypes = [C.c_void_p, C.POINTER(ht_tensor)]
     lib.ht_tensor_to_host.argtypes = [C.c_void_p, C.POINTER(ht_tensor), C.c_void_p]
     lib.ht_memory_model.argtypes = [C.c_int64, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_double),
                                     C.POINTER(C.c_double)]
@@ -440,6 +441,13 @@ def ht_epoch(ctx, g, dims: Sequence[int], Ws: List[torch.Tensor], lr: float, X: 
     _check(load().ht_epoch(ctx, g, C.byref(model), C.byref(x), C.c_void_p(labels.data_ptr()), C.byref(plan),
                            C.byref(loss), C.byref(st) if st is not None else None), ctx)
     return loss.value, st
+
+
+def ht_tensor_zero(ctx, t: torch.Tensor, cols: int):
+    """Zero a [rows x ld] tensor (HBM or pinned host) through the library."""
+    tv = tensor_view(t, cols)
+    torch.cuda.synchronize()
+    _check(load().ht_tensor_zero(ctx, C.byref(tv)), ctx)
 
 
 def ht_epoch_buffer(ctx, kind: int, layer: int) -> torch.Tensor:

@@ -1,6 +1,8 @@
 // Small HBM-bound kernels: ReLU derivative mask (Sec. 2.3), softmax
 // cross-entropy and its gradient (the downstream task of Alg. 1),
 // SGD step (Alg. 1), zero fill.
+#include <algorithm>
+
 #include "ht_internal.h"
 
 namespace {
@@ -49,26 +51,27 @@ __global__ void __launch_bounds__(256) k_softmax_ce(const float* __restrict__ lo
                                                     float* __restrict__ grad, int64_t ld_g,
                                                     float* __restrict__ loss_v) {
   const int lane = threadIdx.x & 63;
-  const int64_t v = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (v >= V) return;
-  const int32_t y = labels[v];
-  const float* x = logits + v * ld;
-  float* g = grad + v * ld_g;
-  if (y < 0) {
-    for (int c = lane; c < C; c += 64) g[c] = 0.f;
-    if (lane == 0) loss_v[v] = 0.f;
-    return;
+  // (a bounded grid that strides: a launch holds fewer than 2^32 threads, 64 V can be more)
+  for (int64_t v = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); v < V; v += (int64_t)gridDim.x * 4) {
+    const int32_t y = labels[v];
+    const float* x = logits + v * ld;
+    float* g = grad + v * ld_g;
+    if (y < 0) {
+      for (int c = lane; c < C; c += 64) g[c] = 0.f;
+      if (lane == 0) loss_v[v] = 0.f;
+      continue;
+    }
+    const float invT = 1.f / (float)(*Tp);
+    float m = -INFINITY;
+    for (int c = lane; c < C; c += 64) m = fmaxf(m, x[c]);
+    m = wave_max(m);
+    float z = 0.f;
+    for (int c = lane; c < C; c += 64) z += expf(x[c] - m);
+    z = wave_sum(z);
+    const float lse = m + logf(z);
+    for (int c = lane; c < C; c += 64) g[c] = (expf(x[c] - lse) - (c == y ? 1.f : 0.f)) * invT;
+    if (lane == 0) loss_v[v] = lse - x[y];
   }
-  const float invT = 1.f / (float)(*Tp);
-  float m = -INFINITY;
-  for (int c = lane; c < C; c += 64) m = fmaxf(m, x[c]);
-  m = wave_max(m);
-  float z = 0.f;
-  for (int c = lane; c < C; c += 64) z += expf(x[c] - m);
-  z = wave_sum(z);
-  const float lse = m + logf(z);
-  for (int c = lane; c < C; c += 64) g[c] = (expf(x[c] - lse) - (c == y ? 1.f : 0.f)) * invT;
-  if (lane == 0) loss_v[v] = lse - x[y];
 }
 
 // Fixed-order sum of n floats in fp64: 256-thread blocks of 4096 elements, then one block.
@@ -141,7 +144,7 @@ int ht_softmax_ce(ht_ctx* ctx, hipStream_t st, const float* logits, int64_t ld, 
   HT_TRY(ht_fill_zero(ctx, st, T, 16));
   k_count_labelled<<<(unsigned)((V + 255) / 256), 256, 0, st>>>(labels, V, T);
   HT_LAUNCH_CHECK(ctx);
-  k_softmax_ce<<<(unsigned)((V + 3) / 4), 256, 0, st>>>(logits, ld, labels, V, C, T, grad, ld_g, loss_v);
+  k_softmax_ce<<<(unsigned)std::min<int64_t>((V + 3) / 4, 1 << 22), 256, 0, st>>>(logits, ld, labels, V, C, T, grad, ld_g, loss_v);
   HT_LAUNCH_CHECK(ctx);
   k_sum_stage<<<(unsigned)nb1, 256, 0, st>>>(loss_v, nullptr, V, st1);
   HT_LAUNCH_CHECK(ctx);

@@ -62,19 +62,19 @@ __global__ void __launch_bounds__(256) k_gat_pq(const float* __restrict__ T, int
                                                 const float* __restrict__ a_src, int64_t V, float* __restrict__ p,
                                                 float* __restrict__ q) {
   const int lane = threadIdx.x & 63;
-  const int64_t v = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (v >= V) return;
-  float sp = 0.f, sq = 0.f;
-  for (int c = lane; c < d; c += 64) {
-    const float t = T[v * ld + c];
-    sp = fmaf(a_dst[c], t, sp);
-    sq = fmaf(a_src[c], t, sq);
-  }
-  sp = wave_sum(sp);
-  sq = wave_sum(sq);
-  if (lane == 0) {
-    p[v] = sp;
-    q[v] = sq;
+  for (int64_t v = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); v < V; v += (int64_t)gridDim.x * 4) {
+    float sp = 0.f, sq = 0.f;
+    for (int c = lane; c < d; c += 64) {
+      const float t = T[v * ld + c];
+      sp = fmaf(a_dst[c], t, sp);
+      sq = fmaf(a_src[c], t, sq);
+    }
+    sp = wave_sum(sp);
+    sq = wave_sum(sq);
+    if (lane == 0) {
+      p[v] = sp;
+      q[v] = sq;
+    }
   }
 }
 
@@ -422,11 +422,11 @@ __global__ void __launch_bounds__(256) k_gat_finish(float* __restrict__ dT, int6
                                                     const float* __restrict__ dp, const float* __restrict__ a_dst,
                                                     const float* __restrict__ a_src, int64_t V, float* __restrict__ pq4) {
   const int lane = threadIdx.x & 63;
-  const int64_t v = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (v >= V) return;
-  const float dpv = dp[v], dqv = dT[v * ld + sc_col];
-  for (int c = lane; c < d; c += 64) dT[v * ld + c] += dpv * a_dst[c] + dqv * a_src[c];
-  if (lane == 0) st4(pq4 + v * 4, make_float4(dpv, dqv, 0.f, 0.f));
+  for (int64_t v = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); v < V; v += (int64_t)gridDim.x * 4) {
+    const float dpv = dp[v], dqv = dT[v * ld + sc_col];
+    for (int c = lane; c < d; c += 64) dT[v * ld + c] += dpv * a_dst[c] + dqv * a_src[c];
+    if (lane == 0) st4(pq4 + v * 4, make_float4(dpv, dqv, 0.f, 0.f));
+  }
 }
 
 __global__ void k_gat_split(const float* __restrict__ da4, int d, float* __restrict__ da_dst, float* __restrict__ da_src) {
@@ -569,7 +569,7 @@ int prepare(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const ht_te
     st->gemm_flops += 2.0 * nr * desc->d_in * desc->d_out;
   }
   if (g->V > 0) {
-    k_gat_pq<<<(unsigned)((g->V + 3) / 4), 256, 0, s>>>(ws->T, ws->ld_t, desc->d_out, a_dst, a_src, g->V, ws->p, ws->q);
+    k_gat_pq<<<(unsigned)std::min<int64_t>((g->V + 3) / 4, 1 << 22), 256, 0, s>>>(ws->T, ws->ld_t, desc->d_out, a_dst, a_src, g->V, ws->p, ws->q);
     HT_LAUNCH_CHECK(ctx);
   }
   return HT_OK;
@@ -792,7 +792,7 @@ int gat_bwd_impl(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const 
     local->edges += 2 * c.nnz;
   }
   if (g->V > 0) {
-    k_gat_finish<<<(unsigned)((g->V + 3) / 4), 256, 0, st>>>(dT, ld_dt, d, sc_col, ws.dp, a_dst, a_src, g->V, ws.pq4);
+    k_gat_finish<<<(unsigned)std::min<int64_t>((g->V + 3) / 4, 1 << 22), 256, 0, st>>>(dT, ld_dt, d, sc_col, ws.dp, a_dst, a_src, g->V, ws.pq4);
     HT_LAUNCH_CHECK(ctx);
   }
   // da = T^T [dp dq 0 0]; dW = H^T dt; dH += dt W^T, in row blocks; host-resident H_in / dH_in blocks go

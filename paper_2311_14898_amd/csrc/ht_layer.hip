@@ -1375,6 +1375,16 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
   return finish(R, stats, t0, true);
 }
 
+int ht_tensor_zero(ht_ctx* ctx, ht_tensor* t) {
+  if (!ctx) return HT_EINVAL;
+  if (!t || !t->ptr || t->rows < 0 || t->ld < t->cols || (t->ld & 3))
+    return ht_set_err(ctx, HT_EINVAL, "ht_tensor_zero: bad tensor");
+  HT_HIP(ctx, hipSetDevice(ctx->device));
+  HT_TRY(zero_tensor(ctx, t));
+  HT_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  return HT_OK;
+}
+
 int ht_epoch_buffer(ht_ctx* ctx, int32_t kind, int32_t layer, ht_tensor* out) {
   if (!ctx || !out) return HT_EINVAL;
   EpochWs* ws = ctx->ws;

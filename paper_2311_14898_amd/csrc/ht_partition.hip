@@ -524,6 +524,9 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
   const int mode = opts ? opts->balance_mode : HT_BALANCE_EDGES;
   const int ptr_loc = opts ? opts->ptr_loc : HT_PTR_DEVICE;
   const int64_t Ep = E + (self_loops ? V : 0);
+  // the per-edge kernels take one thread per stored edge, and a launch holds fewer than 2^32 threads
+  if (Ep >= ((int64_t)1 << 32) - 4096)
+    return ht_set_err(ctx, HT_EINVAL, "ht_partition: %lld stored edges; fewer than 2^32 are supported", (long long)Ep);
   g->ctx = ctx;
   g->V = V;
   g->Ep = Ep;

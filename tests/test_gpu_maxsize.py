@@ -240,3 +240,48 @@ def test_cfg4_full_scale_partition_with_schedule_aware_buffer():
             if x is not None:
                 B.ht_graph_destroy(x)
         B.ht_ctx_destroy(ctx)
+
+
+def test_tensors_of_more_than_2_to_32_words():
+    """A launch holds fewer than 2^32 threads (a larger grid is not rejected by a plain launch, its excess is
+    dropped): whole-tensor kernels must stride.  The library's fill over a 20 GiB tensor, at an address that is not
+    16-byte aligned, with a ragged tail; and the per-vertex GAT kernels through a layer whose vertex count alone
+    would need 2^32 threads at one wave per vertex (70 M vertices, no edges but the self-loops)."""
+    if torch.cuda.mem_get_info()[0] < 120e9:
+        pytest.skip("needs a GPU with 120 GB of free memory")
+    ctx = B.ht_ctx_create(0)
+    try:
+        rows, ld = 21_000_003, 256                       # 5.4 G words
+        t = torch.ones((rows, ld), dtype=torch.float32, device="cuda")
+        B.ht_tensor_zero(ctx, t, ld)
+        for r0 in range(0, rows, 1 << 22):
+            assert not bool(t[r0:r0 + (1 << 22)].any()), f"rows from {r0} were not cleared"
+        flat = torch.ones(5_000_000_007, dtype=torch.float32, device="cuda")
+        view = flat[3:3 + 4_999_999_996].view(-1, 4)      # starts 12 bytes past a 16-byte boundary
+        B.ht_tensor_zero(ctx, view, 4)
+        assert float(flat[:3].sum()) == 3.0 and float(flat[3 + 4_999_999_996:].sum()) == 8.0
+        for r0 in range(0, view.shape[0], 1 << 28):
+            assert not bool(view[r0:r0 + (1 << 28)].any())
+        del t, flat, view
+        torch.cuda.empty_cache()
+        # GAT layer on 70 M isolated vertices: softmax over the self-loop alone, so h' = relu(H W) row by row
+        V, d_in, d_out = 70_000_000, 8, 4
+        ids = torch.arange(0, 16, dtype=torch.int32, device="cuda")
+        g = B.ht_partition(ctx, V, ids[:0], ids[:0], 64)
+        try:
+            H = torch.empty((V, d_in), dtype=torch.float32, device="cuda").uniform_(-1, 1, generator=torch.Generator("cuda").manual_seed(3))
+            W = inputs.glorot_weights([d_in, d_out])[0].cuda()
+            a = torch.full((d_out,), 0.3, device="cuda")
+            out = torch.empty((V, B.pad_ld(d_out, B.HT_LOC_DEVICE)), dtype=torch.float32, device="cuda")
+            B.ht_gat_layer_fwd(ctx, g, d_in, d_out, B.HT_ACT_RELU, H, W, a, a, out)
+            for r0 in (0, V // 2, V - 1_000_000):          # the last range lies beyond 2^32 threads' worth of vertices
+                ref = torch.relu(H[r0:r0 + 1_000_000].double() @ W.double())
+                got = out[r0:r0 + 1_000_000, :d_out].double()
+                assert float((got - ref).abs().max()) <= 1e-5 * float(ref.abs().max())
+            p, q = B.ht_gat_scores(ctx, g, d_in, d_out, H, W, a, a)
+            t_tail = (H[V - 1000:].double() @ W.double()).cpu().numpy()
+            assert np.abs(p[V - 1000:] - 0.3 * t_tail.sum(axis=1)).max() <= 1e-5
+        finally:
+            B.ht_graph_destroy(g)
+    finally:
+        B.ht_ctx_destroy(ctx)
