@@ -1,0 +1,107 @@
+"""ht_epoch under seeded random combinations of graph shape, widths, chunking, buffer policy, residency,
+intermediate-data mode, gather mode and stage order, each against the CPU oracle.  A combination the library
+documents as invalid must come back as an error code, never as a wrong result."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_2311_14898_amd import binding as B
+from paper_2311_14898_amd import inputs
+from tests.util import assert_close
+
+pytestmark = pytest.mark.gpu
+
+N_CASES = 40
+MARGIN = 5e-7
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = B.ht_ctx_create(0)
+    yield c
+    B.ht_ctx_destroy(c)
+
+
+def draw_case(seed):
+    rng = np.random.default_rng(1000 + seed)
+    V = int(rng.integers(200, 3000))
+    deg = float(rng.choice([1.5, 4, 12, 30]))
+    L = int(rng.integers(1, 5))
+    dims = [int(rng.choice([3, 8, 17, 32, 41, 64, 100, 130])) for _ in range(L + 1)]
+    dims[-1] = int(rng.choice([2, 5, 8, 41]))
+    n = int(rng.choice([1, 2, 3, 7, 16, 33]))
+    w = inputs.Workload(f"r{seed}", V, max(1, int(V * deg)), dims, n, labelled_one_in=int(rng.choice([1, 1, 3])),
+                        graph_seed=20 + seed, lr=0.05)
+    part = dict(cache_policy=int(rng.choice([B.HT_CACHE_ADJACENT, B.HT_CACHE_FARTHEST])),
+                cache_rows=int(rng.choice([0, 0, -1, V // 3, V])), reorder_chunks=bool(rng.integers(0, 2)))
+    host = bool(rng.integers(0, 2))
+    res = [B.HT_RES_HOST, B.HT_RES_HBM, B.HT_RES_AUTO]
+    plan = dict(res_h=int(rng.choice(res)) if host else B.HT_RES_AUTO, res_a=int(rng.choice(res)) if host else B.HT_RES_AUTO,
+                res_g=int(rng.choice(res)) if host else B.HT_RES_AUTO,
+                inter=int(rng.choice([B.HT_INTER_AUTO, B.HT_INTER_MASK, B.HT_INTER_HYBRID, B.HT_INTER_RECOMPUTE])),
+                gather_mode=int(rng.choice([B.HT_GATHER_AUTO, B.HT_GATHER_AUTO, B.HT_GATHER_DIRECT, B.HT_GATHER_BUFFER])),
+                order=int(rng.choice([B.HT_ORDER_AGG_FIRST, B.HT_ORDER_UPDATE_FIRST, B.HT_ORDER_AUTO])),
+                reuse_input_aggregate=bool(rng.integers(0, 2)), use_graph=bool(rng.integers(0, 2)))
+    x_loc = B.HT_LOC_HOST_PINNED if host and rng.integers(0, 2) else B.HT_LOC_DEVICE
+    return w, part, plan, x_loc
+
+
+@pytest.mark.parametrize("seed", range(N_CASES))
+def test_random_plan(ctx, seed):
+    w, part, plan, x_loc = draw_case(seed)
+    print(f"case {seed}: V={w.V} E={w.E} dims={w.dims} n={w.n_chunks} {part} {plan} x_loc={x_loc}", flush=True)
+    L = w.n_layers
+
+    def margin_of(ref):
+        """Smallest pre-activation relative to the largest: the ReLU decision is safe well above fp32 rounding.
+        Exact zeros do not count: they come from all-zero input rows and are zero on both sides."""
+        m = 1.0
+        for l in range(L - 1):
+            z = np.abs(ref["z"][l])
+            if (z > 0).any():
+                m = min(m, z[z > 0].min() / z.max())
+        return m
+
+    for attempt in range(24):      # a graph whose first epoch takes every ReLU decision clear of rounding
+        src, dst, X, y, Ws = inputs.make_inputs(w)
+        indptr, col = orc.csc_build(w.V, src.numpy(), dst.numpy())
+        if margin_of(orc.gcn_epoch(indptr, col, w.dims, X.numpy(), [x.numpy() for x in Ws], y.numpy(), lr=w.lr)) >= MARGIN:
+            break
+        w.graph_seed += 100
+    else:
+        pytest.skip("no graph seed with a safe ReLU margin")
+    if part["cache_rows"] > 0:       # a sized buffer holds at least the largest source set
+        g = B.ht_partition(ctx, w.V, src.cuda(), dst.cuda(), w.n_chunks, reorder_chunks=part["reorder_chunks"])
+        part["cache_rows"] = max(part["cache_rows"], int(B.ht_graph_info_get(g).max_nsrc))
+        B.ht_graph_destroy(g)
+    g = B.ht_partition(ctx, w.V, src.cuda(), dst.cuda(), w.n_chunks, **part)
+    try:
+        Xd = B.to_matrix(X, x_loc)
+        Wd = [x.clone().cuda() for x in Ws]
+        W_ref = [x.numpy() for x in Ws]
+        for epoch in range(3):        # the third epoch of a key is a graph replay, the second reuses a^0
+            ref = orc.gcn_epoch(indptr, col, w.dims, X.numpy(), W_ref, y.numpy(), lr=w.lr)
+            if margin_of(ref) < MARGIN:
+                assert epoch > 0
+                print(f"  stopped before epoch {epoch}: a pre-activation within rounding of zero", flush=True)
+                break       # fp32 and fp64 may take different ReLU decisions from here on
+            try:
+                loss, _ = B.ht_epoch(ctx, g, w.dims, Wd, w.lr, Xd, y.cuda(), **plan)
+            except B.HongtuError as e:
+                # documented refusals: reading rows in place needs them in HBM
+                host_rows = x_loc == B.HT_LOC_HOST_PINNED or (L > 1 and plan["res_h"] == B.HT_RES_HOST) \
+                    or (L > 1 and plan["res_g"] == B.HT_RES_HOST)
+                assert plan["gather_mode"] == B.HT_GATHER_DIRECT and host_rows, str(e)
+                assert e.code in (B.HT_EINVAL, B.HT_ESHAPE), str(e)
+                return
+            assert abs(loss - ref["loss"]) <= 1e-4 * abs(ref["loss"]), (epoch, loss, ref["loss"])
+            for l in range(L):
+                assert_close(B.ht_epoch_buffer(ctx, B.HT_BUF_H, l + 1).numpy(), ref["h"][l], f"epoch {epoch} h^{l + 1}")
+                assert_close(B.ht_epoch_buffer(ctx, B.HT_BUF_GH, l + 1).numpy(), ref["gh"][l], f"epoch {epoch} grad h^{l + 1}")
+                assert_close(B.ht_epoch_buffer(ctx, B.HT_BUF_DW, l).numpy(), ref["gW"][l], f"epoch {epoch} grad W^{l}")
+                assert_close(Wd[l].cpu().numpy(), ref["W_new"][l], f"epoch {epoch} W^{l}")
+            W_ref = ref["W_new"]      # the oracle trains on its own weights
+    finally:
+        B.ht_graph_destroy(g)
+        torch.cuda.synchronize()
