@@ -187,9 +187,12 @@ def _check(rc: int, ctx=None):
 
 
 def pad_ld(d: int, loc: int = HT_LOC_HOST_PINNED) -> int:
-    """Row pitch in floats: whole 16-byte vectors; in HBM whole 128-byte lines when that costs <= 3 %."""
-    p4, p32 = (d + 3) // 4 * 4, (d + 31) // 32 * 32
-    return p32 if (loc == HT_LOC_DEVICE and p32 * 100 <= p4 * 103) else p4
+    """Row pitch in floats: in HBM whole 16-byte vectors, whole 128-byte lines when that costs <= 3 %; in pinned
+    host memory whole 64-byte blocks (rows that cross the link in whole requests)."""
+    p4, p16, p32 = (d + 3) // 4 * 4, (d + 15) // 16 * 16, (d + 31) // 32 * 32
+    if loc != HT_LOC_DEVICE:
+        return p16
+    return p32 if p32 * 100 <= p4 * 103 else p4
 
 
 def alloc_matrix(rows: int, cols: int, loc: int = HT_LOC_DEVICE, zero: bool = True) -> torch.Tensor:

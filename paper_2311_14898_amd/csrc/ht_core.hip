@@ -127,6 +127,7 @@ int ht_ctx_create(ht_ctx** out, int device, void* hip_stream) {
   c->device = device;
   if (const char* v = getenv("HT_AGG_VARIANT")) c->agg_variant = atoi(v);
   if (const char* v = getenv("HT_LINK_BLOCKS")) c->link_blocks = atoi(v) > 0 ? atoi(v) : 64;
+  if (const char* v = getenv("HT_GATHER_BLOCKS")) c->gather_blocks = atoi(v) > 0 ? atoi(v) : 128;
   if (const char* v = getenv("HT_XCD_CONTIG")) c->xcd_contig = atoi(v);
   if (const char* v = getenv("HT_NO_LINK_FENCE")) c->no_link_fence = atoi(v);
   if (const char* v = getenv("HT_LINK_MEMCPY")) c->link_memcpy = atoi(v);

@@ -47,6 +47,8 @@ struct ht_ctx {
                           // (HT_XCD_CONTIG; measured slower at cfg2: 30.7 vs 26.0 ms per epoch)
   int no_link_fence = 0;  // 1: let aggregation kernels overlap link traffic (HT_NO_LINK_FENCE, for A/B runs)
   int link_blocks = 64;   // workgroups of a kernel that moves rows over the host link (HT_LINK_BLOCKS)
+  int gather_blocks = 128; // workgroups of the neighbour-row gather from host memory (HT_GATHER_BLOCKS): beside a D2H
+                           // copy the gather's read requests queue behind the write data, and more waves keep more in flight
   int link_memcpy = 0;    // 1: use hipMemcpyAsync for contiguous host<->device row ranges (HT_LINK_MEMCPY)
   int slabs_fwd = 0, slabs_bwd = 0;  // caps on feature slabs (HT_SLABS_FWD / HT_SLABS_BWD), 0 = by width
   int agg_unroll = 4;     // HT_AGG_UNROLL: row reads in flight per lane (4 or 8)
@@ -128,10 +130,14 @@ constexpr double HT_GATHER_BYTES_PER_S = 15e12;
 
 // Row pitch (in floats) of a library-allocated [rows x d] matrix: a multiple of 4 (16-byte
 // vectors); in HBM, rows start on 128-byte cache lines when that costs at most 3 % more memory,
-// so a feature slab never shares a line with the slab of another XCD.
+// so a feature slab never shares a line with the slab of another XCD; in pinned host memory rows
+// start on 64-byte boundaries: a row read over the link then splits into whole 64-byte requests
+// (rows at a 400-byte pitch were gathered at 22 GB/s beside a D2H copy that fell to 29 GB/s; at a
+// 448-byte pitch 26-34 GB/s beside 46-50 GB/s).
 inline int64_t ht_row_pitch(int32_t d, bool device) {
-  const int64_t p4 = ((int64_t)d + 3) & ~(int64_t)3, p32 = ((int64_t)d + 31) & ~(int64_t)31;
-  return (device && p32 * 100 <= p4 * 103) ? p32 : p4;
+  const int64_t p4 = ((int64_t)d + 3) & ~(int64_t)3, p16 = ((int64_t)d + 15) & ~(int64_t)15, p32 = ((int64_t)d + 31) & ~(int64_t)31;
+  if (!device) return p16;
+  return p32 * 100 <= p4 * 103 ? p32 : p4;
 }
 
 int ht_scan_i32(ht_ctx* ctx, const int32_t* in, int64_t* out, int64_t n, bool want_total);

@@ -170,7 +170,7 @@ int gather_chunk(Run& R, int j, const ht_tensor* H_in, const float* Hin, int d, 
   const ChunkMeta& c = g->chunks[j];
   const int id = R.tm.begin_on(&R.st->t_gather_ms, st);
   HT_TRY(ht_gather_rows(R.ctx, st, Hin, H_in->ld, g->load.p + c.load_off, nbuf, H_in->ld, g->load_slot.p + c.load_off,
-                        c.n_load, d, g->s.p, H_in->loc == HT_LOC_HOST_PINNED ? R.ctx->link_blocks : 0));
+                        c.n_load, d, g->s.p, H_in->loc == HT_LOC_HOST_PINNED ? R.ctx->gather_blocks : 0));
   R.tm.end_id(id);
   R.st->rows_loaded += c.n_load;
   R.st->rows_reused += c.n_reuse;

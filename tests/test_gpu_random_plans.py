@@ -44,12 +44,14 @@ def draw_case(seed):
                 order=int(rng.choice([B.HT_ORDER_AGG_FIRST, B.HT_ORDER_UPDATE_FIRST, B.HT_ORDER_AUTO])),
                 reuse_input_aggregate=bool(rng.integers(0, 2)), use_graph=bool(rng.integers(0, 2)))
     x_loc = B.HT_LOC_HOST_PINNED if host and rng.integers(0, 2) else B.HT_LOC_DEVICE
+    plan["x_tight"] = bool(rng.integers(0, 2))      # X at the smallest legal row pitch (16-byte vectors, not 64-byte blocks)
     return w, part, plan, x_loc
 
 
 @pytest.mark.parametrize("seed", range(N_CASES))
 def test_random_plan(ctx, seed):
     w, part, plan, x_loc = draw_case(seed)
+    x_tight = plan.pop("x_tight")
     print(f"case {seed}: V={w.V} E={w.E} dims={w.dims} n={w.n_chunks} {part} {plan} x_loc={x_loc}", flush=True)
     L = w.n_layers
 
@@ -77,7 +79,11 @@ def test_random_plan(ctx, seed):
         B.ht_graph_destroy(g)
     g = B.ht_partition(ctx, w.V, src.cuda(), dst.cuda(), w.n_chunks, **part)
     try:
-        Xd = B.to_matrix(X, x_loc)
+        if x_tight and x_loc == B.HT_LOC_HOST_PINNED:
+            Xd = torch.zeros(w.V, (w.dims[0] + 3) // 4 * 4, dtype=torch.float32, pin_memory=True)
+            Xd[:, :w.dims[0]].copy_(X)
+        else:
+            Xd = B.to_matrix(X, x_loc)
         Wd = [x.clone().cuda() for x in Ws]
         W_ref = [x.numpy() for x in Ws]
         for epoch in range(3):        # the third epoch of a key is a graph replay, the second reuses a^0
