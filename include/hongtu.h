@@ -27,6 +27,9 @@
  *   - Vertex tensors are fp32, row-major, [rows x cols] with a row pitch `ld`
  *     in floats; ld >= cols and ld % 4 == 0 (rows are read as 16-byte vectors).
  *     Columns cols..ld-1 are padding: never read as data, may be overwritten.
+ *     Advice, not a requirement: a pitch of whole 64-byte blocks (ld % 16 == 0)
+ *     for tensors in host memory, of whole 128-byte lines (ld % 32 == 0) in HBM;
+ *     the library's own tensors are laid out so.
  *   - `loc` says where a tensor lives: HT_LOC_DEVICE (HBM of the context's GPU)
  *     or HT_LOC_HOST_PINNED (page-locked host memory the GPU can address, e.g.
  *     hipHostMalloc or torch pin_memory).  Plain pageable memory is not accepted.

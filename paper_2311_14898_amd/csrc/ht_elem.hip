@@ -122,6 +122,8 @@ int ht_relu_mask(ht_ctx* ctx, hipStream_t st, const float* dh, int64_t ld_dh, co
   if (rows <= 0 || cols <= 0) return HT_OK;
   const int cols4 = (cols + 3) & ~3;
   const int64_t n = rows * (cols4 >> 2);
+  // one thread per 16-byte vector: a launch of 2^32 threads or more would silently run only a part
+  if (n >= ((int64_t)1 << 32) - 256) return ht_set_err(ctx, HT_ESHAPE, "ReLU mask: %lld rows x %d columns in one chunk is too large", (long long)rows, cols);
   k_relu_mask<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(dh, ld_dh, ref, ld_ref, dz, ld_dz, rows, cols4);
   HT_LAUNCH_CHECK(ctx);
   return HT_OK;
