@@ -71,6 +71,8 @@ def test_random_plan(ctx, seed):
         if margin_of(orc.gcn_epoch(indptr, col, w.dims, X.numpy(), [x.numpy() for x in Ws], y.numpy(), lr=w.lr)) >= MARGIN:
             break
         w.graph_seed += 100
+        if attempt % 6 == 5:          # fewer pre-activations: fewer of them close to zero
+            w.V, w.E = max(100, w.V // 2), max(1, w.E // 2)
     else:
         pytest.skip("no graph seed with a safe ReLU margin")
     if part["cache_rows"] > 0:       # a sized buffer holds at least the largest source set
