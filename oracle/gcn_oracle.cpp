@@ -15,7 +15,9 @@
 //   * Chunks, Sec. 4.1 / 4.3: a chunk is a set of destinations with all their
 //     in-edges; N_j is its in-neighbour set.
 //   * Dedup sets and volumes, Sec. 5.1 / 5.3: reuse set N_j ^ N_{j-1}, load set
-//     N_j \ N_{j-1}, V_ori and V_+ru (one GPU, so the inter-GPU term is void).
+//     N_j \ N_{j-1}, V_ori and V_+ru (one GPU, so the inter-GPU term is void);
+//     V_ori, V_+p2p, V_+ru for m partitions of n subgraphs and the partition
+//     reorganisation of Alg. 4 (a planning step: sets only, no second GPU).
 //   * Epoch, Alg. 1: forward over layers, loss, backward, parameter update.
 //   * GAT layer, Eq. 3: attention coefficients from a^l [W h_v || W h_u], LeakyReLU,
 //     neighbour-oriented softmax, weighted sum; its backward by the chain rule.
@@ -188,6 +190,108 @@ void orc_chunk_order(const int64_t* indptr, const int32_t* col, int n, const int
     order[j] = best;
     placed[best] = 1;
   }
+}
+
+// Communication volumes of Sec. 5.3 for m partitions of n subgraphs each, in rows per pass.
+// Subgraph k of partition i is the destination range [b[i*n+k], b[i*n+k+1]); layout[i*n+j] names the
+// subgraph of partition i that runs in batch j (the m subgraphs of a batch run at the same time, one
+// per GPU).  With N_ij the in-neighbour set of that subgraph and U_j the union of N_ij over i:
+//   out[0] = V_ori  = sum over i, j of |N_ij|          (every subgraph fetches its own neighbours)
+//   out[1] = V_+p2p = sum over j of |U_j|              (a batch fetches each vertex once)
+//   out[2] = V_+ru  = |U_0| + sum over j >= 1 of |U_j minus U_{j-1}|   (and keeps what the last batch had)
+void orc_volumes_mn(const int64_t* indptr, const int32_t* col, int m, int n, const int64_t* b, const int32_t* layout,
+                    int64_t* out) {
+  int64_t ori = 0, p2p = 0, ru = 0;
+  std::set<int32_t> prev;
+  for (int j = 0; j < n; ++j) {
+    std::set<int32_t> U;
+    for (int i = 0; i < m; ++i) {
+      const int c = i * n + layout[i * n + j];
+      std::set<int32_t> N(col + indptr[b[c]], col + indptr[b[c + 1]]);
+      ori += (int64_t)N.size();
+      U.insert(N.begin(), N.end());
+    }
+    p2p += (int64_t)U.size();
+    for (int32_t v : U)
+      if (j == 0 || !prev.count(v)) ++ru;
+    prev.swap(U);
+  }
+  out[0] = ori;
+  out[1] = p2p;
+  out[2] = ru;
+}
+
+// Partition reorganisation, Alg. 4, both phases, for m partitions of n subgraphs (same indexing as
+// orc_volumes_mn).  layout[i*n+j] = subgraph of partition i that ends up in batch j.
+//   Phase 1 (which subgraphs share a batch): the batches start as the subgraphs of partition 0 in
+//   their given order, U_j = N_0j.  Partitions 1 .. m-1 are taken in turn; for each, batch after
+//   batch (j = 0 .. n-1) receives the not yet assigned subgraph k of that partition with the largest
+//   |N_ik ^ U_j|, and U_j grows by N_ik.
+//   Phase 2 (in which order the batches run): batch 0 stays first; then, step by step, the unplaced
+//   batch whose union shares the most vertices with the union of the batch placed last comes next.
+//   Every partition's subgraphs follow their batch, partition 0 included (the listing's inner loop
+//   starts at 1, which would leave partition 0 out of step with its batch).
+// Ties go to the smallest index in both phases (the paper does not say).
+void orc_reorganize(const int64_t* indptr, const int32_t* col, int m, int n, const int64_t* b, int32_t* layout) {
+  auto nbrs = [&](int c) {
+    std::vector<int32_t> N(col + indptr[b[c]], col + indptr[b[c + 1]]);
+    std::sort(N.begin(), N.end());
+    N.erase(std::unique(N.begin(), N.end()), N.end());
+    return N;
+  };
+  auto common = [](const std::vector<int32_t>& x, const std::vector<int32_t>& y) {
+    std::vector<int32_t> t;
+    std::set_intersection(x.begin(), x.end(), y.begin(), y.end(), std::back_inserter(t));
+    return (int64_t)t.size();
+  };
+  // phase 1
+  std::vector<std::vector<int32_t>> Gt(m, std::vector<int32_t>(n));   // Gt[i][j]: subgraph of partition i in batch j
+  std::vector<std::vector<int32_t>> U(n);
+  for (int j = 0; j < n; ++j) {
+    Gt[0][j] = j;
+    U[j] = nbrs(j);
+  }
+  for (int i = 1; i < m; ++i) {
+    std::vector<char> taken(n, 0);
+    for (int j = 0; j < n; ++j) {
+      int best = -1;
+      int64_t best_ov = -1;
+      for (int k = 0; k < n; ++k) {
+        if (taken[k]) continue;
+        const int64_t ov = common(nbrs(i * n + k), U[j]);
+        if (ov > best_ov) {
+          best_ov = ov;
+          best = k;
+        }
+      }
+      Gt[i][j] = best;
+      taken[best] = 1;
+      const std::vector<int32_t> Nk = nbrs(i * n + best);
+      std::vector<int32_t> t;
+      std::set_union(U[j].begin(), U[j].end(), Nk.begin(), Nk.end(), std::back_inserter(t));
+      U[j].swap(t);
+    }
+  }
+  // phase 2
+  std::vector<int32_t> at(n, 0);   // at[j]: the phase-1 batch that runs at position j
+  std::vector<char> placed(n, 0);
+  if (n > 0) placed[0] = 1;
+  for (int j = 1; j < n; ++j) {
+    int best = -1;
+    int64_t best_ov = -1;
+    for (int k = 0; k < n; ++k) {
+      if (placed[k]) continue;
+      const int64_t ov = common(U[k], U[at[j - 1]]);
+      if (ov > best_ov) {
+        best_ov = ov;
+        best = k;
+      }
+    }
+    at[j] = best;
+    placed[best] = 1;
+  }
+  for (int i = 0; i < m; ++i)
+    for (int j = 0; j < n; ++j) layout[i * n + j] = Gt[i][at[j]];
 }
 
 // Row-buffer schedule: which neighbour rows are reused, loaded and released at

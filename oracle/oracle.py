@@ -100,6 +100,27 @@ def chunk_order(indptr: np.ndarray, col: np.ndarray, b: np.ndarray) -> np.ndarra
     return order
 
 
+def volumes_mn(indptr, col, b, m: int, n: int, layout=None) -> Tuple[int, int, int]:
+    """(V_ori, V_+p2p, V_+ru) of Sec. 5.3 for m partitions of n subgraphs; b has m*n+1 boundaries; layout[i*n+j] =
+    subgraph of partition i in batch j (default: subgraph j)."""
+    indptr, col, b = _i64(indptr), _i32(col), _i64(b)
+    assert len(b) == m * n + 1
+    lay = _i32(np.tile(np.arange(n), m) if layout is None else layout)
+    assert len(lay) == m * n
+    out = np.zeros(3, dtype=np.int64)
+    lib().orc_volumes_mn(_p(indptr), _p(col), C.c_int(m), C.c_int(n), _p(b), _p(lay), _p(out))
+    return int(out[0]), int(out[1]), int(out[2])
+
+
+def reorganize(indptr, col, b, m: int, n: int) -> np.ndarray:
+    """Partition reorganisation (Alg. 4, both phases): layout[i*n+j] = subgraph of partition i that ends up in batch j."""
+    indptr, col, b = _i64(indptr), _i32(col), _i64(b)
+    assert len(b) == m * n + 1
+    lay = np.zeros(m * n, dtype=np.int32)
+    lib().orc_reorganize(_p(indptr), _p(col), C.c_int(m), C.c_int(n), _p(b), _p(lay))
+    return lay
+
+
 def cache_schedule(indptr, col, b, order, rows: int, policy: int) -> List[Dict[str, np.ndarray]]:
     """Per schedule position the rows reused, loaded and released (after the chunk) by a buffer of `rows` rows.
     policy 0: adjacent reuse (Sec. 5.1); policy 1: release only for room, farthest next use first."""

@@ -341,6 +341,116 @@ def test_chunk_order_greedy_against_python_sets():
     assert orc.chunk_order(indptr, col, np.array([0, 11, 12, 13])).tolist() == [0, 2, 1]
 
 
+# ------------------------------------------------------------------ m partitions: volumes and Alg. 4
+
+def _graph_of_sets(sets, V):
+    """A graph in which subgraph c is one destination vertex (id V + c) whose in-neighbours are sets[c]; no self-loops.
+    Returns CSC and the boundaries that make every such destination a subgraph of its own."""
+    src = np.array([u for c, S in enumerate(sets) for u in sorted(S)], dtype=np.int32)
+    dst = np.array([V + c for c, S in enumerate(sets) for _ in S], dtype=np.int32)
+    indptr, col = orc.csc_build(V + len(sets), src, dst, add_self_loops=False)
+    b = np.array([0] + [V + c + 1 for c in range(len(sets))], dtype=np.int64)     # subgraph 0 also holds the source-only ids
+    return indptr, col, b
+
+
+def _py_volumes(sets, m, n, layout):
+    ori = sum(len(S) for S in sets)
+    U = [set().union(*[sets[i * n + layout[i * n + j]] for i in range(m)]) for j in range(n)]
+    p2p = sum(len(u) for u in U)
+    ru = len(U[0]) + sum(len(U[j] - U[j - 1]) for j in range(1, n))
+    return ori, p2p, ru
+
+
+def _py_reorganize(sets, m, n):
+    """Alg. 4 with Python sets; ties to the smallest index."""
+    Gt = [[0] * n for _ in range(m)]
+    U = []
+    for j in range(n):
+        Gt[0][j] = j
+        U.append(set(sets[j]))
+    for i in range(1, m):
+        K = list(range(n))
+        for j in range(n):
+            k = max(K, key=lambda a: (len(sets[i * n + a] & U[j]), -a))
+            Gt[i][j] = k
+            U[j] |= sets[i * n + k]
+            K.remove(k)
+    at = [0]
+    K = list(range(1, n))
+    while K:
+        k = max(K, key=lambda a: (len(U[a] & U[at[-1]]), -a))
+        at.append(k)
+        K.remove(k)
+    return [Gt[i][at[j]] for i in range(m) for j in range(n)]
+
+
+def test_volumes_mn_paper_example():
+    # Sec. 5.1: 19 transfers without deduplication, 11 once a batch fetches each vertex once, 8 with reuse
+    # between the two batches.  The text prints the two batch unions; the six subgraph sets below are one
+    # choice with those unions and 19 members in all (three partitions, two batches).
+    g, _ = _golden("dedup_transfer_counts.txt")
+    sets = [{0, 1, 2, 3}, {2, 3, 4},        # partition 0: batch 0, batch 1
+            {2, 3, 4, 7}, {4, 5, 6},        # partition 1
+            {0, 4, 7}, {3, 6}]              # partition 2
+    assert sorted(set().union(sets[0], sets[2], sets[4])) == g["union0"]
+    assert sorted(set().union(sets[1], sets[3], sets[5])) == g["union1"]
+    indptr, col, b = _graph_of_sets(sets, 8)
+    assert orc.volumes_mn(indptr, col, b, 3, 2) == (g["transfers_before"][0], g["transfers_after_union"][0],
+                                                    g["transfers_after_reuse"][0])
+
+
+def test_reorganize_against_python_sets():
+    rng = np.random.default_rng(5)
+    for m, n in ((1, 1), (1, 5), (2, 2), (2, 6), (3, 4), (4, 5)):
+        for trial in range(4):
+            V = 40
+            sets = [set(rng.choice(V, size=int(rng.integers(1, 15)), replace=False).tolist()) for _ in range(m * n)]
+            indptr, col, b = _graph_of_sets(sets, V)
+            lay = orc.reorganize(indptr, col, b, m, n)
+            assert lay.tolist() == _py_reorganize(sets, m, n)
+            for i in range(m):
+                assert sorted(lay[i * n:(i + 1) * n].tolist()) == list(range(n))      # a permutation per partition
+            ident = list(range(n)) * m
+            for layout in (ident, lay.tolist()):
+                vo, vp, vr = orc.volumes_mn(indptr, col, b, m, n, layout)
+                assert (vo, vp, vr) == _py_volumes(sets, m, n, layout)
+                assert vo >= vp >= vr >= len(set().union(*sets))
+            if m == 1:      # one partition: the batch order is the chunk order, and no inter-GPU term
+                assert lay.tolist() == orc.chunk_order(indptr, col, b).tolist()
+                vo, vp, vr = orc.volumes_mn(indptr, col, b, 1, n)
+                assert vo == vp and (vo, vr) == orc.volumes(indptr, col, b)
+
+
+def test_reorganize_recovers_a_planted_matching():
+    # every partition holds the same n disjoint neighbour sets in its own shuffled order: phase 1 must put equal
+    # sets into the same batch, after which a batch fetches |S_j| rows instead of m |S_j|
+    rng = np.random.default_rng(9)
+    m, n, per = 4, 6, 5
+    S = [set(range(j * per, (j + 1) * per)) for j in range(n)]
+    perms = [list(range(n))] + [rng.permutation(n).tolist() for _ in range(m - 1)]
+    sets = [S[perms[i][k]] for i in range(m) for k in range(n)]
+    indptr, col, b = _graph_of_sets(sets, n * per)
+    lay = orc.reorganize(indptr, col, b, m, n)
+    for i in range(m):
+        for j in range(n):
+            assert perms[i][lay[i * n + j]] == j       # batch j holds S_j of every partition (phase 2: all ties)
+    before = orc.volumes_mn(indptr, col, b, m, n)
+    after = orc.volumes_mn(indptr, col, b, m, n, lay)
+    assert after == (m * n * per, n * per, n * per) and before[0] == after[0] and before[1] > after[1]
+
+
+def test_reorganize_hand_made_case():
+    # two partitions, three subgraphs each.  Phase 1: batch 0 = {0,1,2} takes {1,2,3} (2 common) over {0,9} (1) and
+    # {7,8}; batch 1 = {4,5} takes {0,9} (tie at 0 common: smaller index) and batch 2 = {7,8,9} gets {7,8}.
+    # Phase 2: unions {0,1,2,3}, {0,4,5,9}, {7,8,9}: after batch 0 comes batch 1 (1 common against 0), then batch 2.
+    sets = [{0, 1, 2}, {4, 5}, {7, 8, 9},
+            {0, 9}, {7, 8}, {1, 2, 3}]
+    indptr, col, b = _graph_of_sets(sets, 10)
+    assert orc.reorganize(indptr, col, b, 2, 3).tolist() == [0, 1, 2, 2, 0, 1]
+    assert orc.volumes_mn(indptr, col, b, 2, 3) == (15, 14, 12)      # unions {0,1,2,9}, {4,5,7,8}, {1,2,3,7,8,9}: 4 + 4 + 4 loaded
+    assert orc.volumes_mn(indptr, col, b, 2, 3, [0, 1, 2, 2, 0, 1]) == (15, 11, 9)
+
+
 # ------------------------------------------------------------------ row-buffer schedules
 
 def _tiny_chunks(rng, V, n, per):
