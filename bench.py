@@ -188,6 +188,30 @@ def read_traffic(name):
     return None
 
 
+def plan_partitions(ctx, w, src, dst, m):
+    """Alg. 4 and the volumes of Sec. 5.3 for m partitions of the workload's chunk count each; a planning result
+    computed on this one GPU (Table 7's quantities on the stand-in graph).  Outside the timed region."""
+    from paper_2311_14898_amd import binding as B
+    n = w.n_chunks
+    gm = B.ht_partition(ctx, w.V, src, dst, m * n)
+    t0 = time.perf_counter()
+    layout, before, after = B.ht_graph_reorganize(ctx, gm, m)
+    ms = (time.perf_counter() - t0) * 1e3
+    B.ht_graph_destroy(gm)
+    row = 4 * max(w.dims[:-1])
+    t_hd, t_dd, t_ru = 57e9, 153e9, 5e12        # host link (measured here), one xGMI link (nominal), HBM row gather
+
+    def rep(v):
+        vo, vp, vr = v
+        return {"v_ori": vo, "v_p2p": vp, "v_ru": vr, "inter_gpu_dup_over_V": (vo - vp) / w.V, "intra_gpu_dup_over_V": (vp - vr) / w.V,
+                "reduction": (vo - vr) / max(vo, 1), "eq4_cost_s_per_pass_widest_layer": B.ht_comm_cost_model(vo, vp, vr, row, t_hd, t_dd, t_ru)}
+
+    moved = int(sum(int(layout[i * n + j]) != j for i in range(m) for j in range(n)))
+    return {"partitions": m, "chunks_per_partition": n, "initial": rep(before), "reorganized": rep(after),
+            "subgraphs_moved": moved, "reorganize_ms": ms,
+            "throughputs": {"T_hd": t_hd, "T_dd": t_dd, "T_ru": t_ru, "note": "T_dd is the nominal rate of one xGMI link, not measured: one GPU here"}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -220,6 +244,8 @@ def main():
                     "(default: the free HBM)")
     ap.add_argument("--inter", choices=["auto", "hybrid", "recompute"], default="auto",
                     help="intermediate data: the planner's choice, a^l cached (Fig. 5(c)), or recomputed (Fig. 5(b))")
+    ap.add_argument("--partitions", type=int, default=0, help="also plan the workload for this many GPUs (no second GPU "
+                    "is used): the chunks of m partitions reorganised by Alg. 4, communication volumes before and after")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a 1 GiB device copy kernel (known traffic) to scale rocprofv3 byte counters")
     args = ap.parse_args()
@@ -396,6 +422,8 @@ def main():
            "roofline": roofline}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, src.cpu().numpy(), dst.cpu().numpy(), X, y, Ws)
+    if args.partitions > 0:
+        out["reorganization"] = plan_partitions(ctx, w, src, dst, args.partitions)
     B.ht_graph_destroy(g)
     B.ht_ctx_destroy(ctx)
     print(json.dumps(out))

@@ -189,6 +189,29 @@ int ht_graph_export_csc(const ht_graph *g, int64_t *indptr /*V+1*/, int32_t *col
  * unless reorder_chunks was set. */
 int ht_graph_chunk_order(const ht_graph *g, int32_t *order /*n_chunks*/);
 
+/* Partition reorganisation for m GPUs (Alg. 4, both phases) and the communication
+ * volumes of Sec. 5.3, computed on one GPU as a planning step: sets of vertex
+ * ids only, no second GPU is touched.  g holds m*n chunks in vertex-id order
+ * (ht_partition with n_chunks = m*n, reorder_chunks = 0): chunk i*n + k is
+ * subgraph k of partition i, and batch j of the initial layout is subgraph j of
+ * every partition.
+ *   Phase 1: the batches start as partition 0's subgraphs, U_j = N_0j; the
+ *   partitions 1..m-1 in turn give batch j = 0..n-1 their not yet assigned
+ *   subgraph k with the largest |N_ik ^ U_j|, and U_j grows by N_ik.
+ *   Phase 2: batch 0 runs first, then always the unplaced batch whose union
+ *   shares the most vertices with the union of the batch placed last.
+ *   Ties go to the smallest index (the paper does not say).
+ * layout (host, m*n entries): layout[i*n + j] = subgraph of partition i that
+ * runs in batch j.  before / after (host, 3 entries each, may be NULL):
+ * {V_ori, V_+p2p, V_+ru} in rows per pass for the initial and the reorganised
+ * layout; with ht_comm_cost_model they give Eq. 4.  With m = 1 phase 1 is void,
+ * the layout is the chunk order that reorder_chunks = 1 applies, and V_+p2p =
+ * V_ori.  Temporary HBM: (m*n + n) * V / 8 bytes.  Synchronous.
+ * HT_EINVAL: m < 1 or not a divisor of the chunk count; HT_ESTATE: g was built
+ * with reorder_chunks = 1 or belongs to another context. */
+int ht_graph_reorganize(ht_ctx *ctx, const ht_graph *g, int32_t m, int32_t *layout, int64_t *before,
+                        int64_t *after);
+
 /* -------------------------------------------------------------------- layer */
 
 enum { HT_ACT_NONE = 0, HT_ACT_RELU = 1 };

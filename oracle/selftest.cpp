@@ -73,6 +73,18 @@ int main() {
             for (int j = 0; j < n; ++j) { loads += nl[j]; leaves += nv[j]; }
             need(loads == leaves, "every loaded row leaves");
           }
+        // the same chunks read as m partitions of n / m subgraphs: reorganisation and volumes
+        for (int m : {1, 2, 3})
+          if (n % m == 0) {
+            const int nn = n / m;
+            std::vector<int32_t> lay(n), ident(n);
+            for (int c = 0; c < n; ++c) ident[c] = c % nn;
+            orc_reorganize(indptr.data(), col.data(), m, nn, b.data(), lay.data());
+            int64_t v0[3], v1[3];
+            orc_volumes_mn(indptr.data(), col.data(), m, nn, b.data(), ident.data(), v0);
+            orc_volumes_mn(indptr.data(), col.data(), m, nn, b.data(), lay.data(), v1);
+            need(v0[0] == v1[0] && v0[0] == v_ori && v1[1] <= v1[0] && v1[2] <= v1[1], "volumes of m partitions");
+          }
         // one layer step chunk by chunk, both directions
         const int64_t d = 9;
         std::vector<double> h(V * d), a(V * d), ga(V * d), gh(V * d);

@@ -110,7 +110,7 @@ class ht_plan_opts(C.Structure):
 
 EXPORTS = ["ht_ctx_create", "ht_ctx_destroy", "ht_sync", "ht_ctx_set_hbm_budget", "ht_ctx_graph_launches", "ht_tensor_zero", "ht_strerror", "ht_last_error",
            "ht_partition", "ht_graph_destroy", "ht_graph_info_get", "ht_graph_chunk_info", "ht_graph_export_chunk",
-           "ht_graph_export_csc", "ht_graph_chunk_order", "ht_layer_fwd", "ht_layer_bwd", "ht_epoch", "ht_epoch_buffer", "ht_tensor_to_host", "ht_memory_model",
+           "ht_graph_export_csc", "ht_graph_chunk_order", "ht_graph_reorganize", "ht_layer_fwd", "ht_layer_bwd", "ht_epoch", "ht_epoch_buffer", "ht_tensor_to_host", "ht_memory_model",
            "ht_chunk_rows_model", "ht_gat_layer_fwd", "ht_gat_layer_bwd", "ht_gat_epoch", "ht_gat_scores", "ht_comm_cost_model"]
 
 _lib = None
@@ -152,6 +152,7 @@ def load():
     lib.ht_graph_export_chunk.argtypes = [C.c_void_p, C.c_int32, C.POINTER(ht_chunk_host)]
     lib.ht_graph_export_csc.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.ht_graph_chunk_order.argtypes = [C.c_void_p, C.c_void_p]
+    lib.ht_graph_reorganize.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.ht_layer_fwd.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(ht_layer_desc), C.POINTER(ht_tensor), C.c_void_p,
                                  C.POINTER(ht_tensor), C.POINTER(ht_tensor), C.POINTER(ht_stats)]
     lib.ht_layer_bwd.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(ht_layer_desc), C.POINTER(ht_tensor), C.c_void_p,
@@ -306,6 +307,15 @@ def ht_graph_chunk_order(g) -> np.ndarray:
     order = np.zeros(info.n_chunks, np.int32)
     _check(load().ht_graph_chunk_order(g, order.ctypes.data))
     return order
+
+
+def ht_graph_reorganize(ctx, g, m: int):
+    """(layout[m*n], (V_ori, V_+p2p, V_+ru) before, the same after) for the graph's chunks read as m partitions."""
+    info = ht_graph_info_get(g)
+    layout = np.zeros(info.n_chunks, np.int32)
+    before, after = np.zeros(3, np.int64), np.zeros(3, np.int64)
+    _check(load().ht_graph_reorganize(ctx, g, m, layout.ctypes.data, before.ctypes.data, after.ctypes.data), ctx)
+    return layout, tuple(int(x) for x in before), tuple(int(x) for x in after)
 
 
 # -------------------------------------------------------------------- layer

@@ -1228,4 +1228,110 @@ int ht_graph_chunk_order(const ht_graph* g, int32_t* order) {
   return HT_OK;
 }
 
+// Alg. 4 on neighbour bitmaps: one |V|-bit map per subgraph and one per batch union; every greedy
+// step is one launch that counts the common members of all candidates with the current union.
+int ht_graph_reorganize(ht_ctx* ctx, const ht_graph* g, int32_t m, int32_t* layout, int64_t* before, int64_t* after) {
+  if (!ctx) return HT_EINVAL;
+  if (!g || !layout) return ht_set_err(ctx, HT_EINVAL, "ht_graph_reorganize: null argument");
+  if (g->ctx != ctx) return ht_set_err(ctx, HT_ESTATE, "graph belongs to another context");
+  if (m < 1 || g->n % m != 0)
+    return ht_set_err(ctx, HT_EINVAL, "ht_graph_reorganize: %d chunks do not split into %d partitions", g->n, m);
+  for (int j = 0; j < g->n; ++j)
+    if (g->order[j] != j)
+      return ht_set_err(ctx, HT_ESTATE, "ht_graph_reorganize: the graph's chunks must be in vertex-id order (reorder_chunks = 0)");
+  const int n = g->n / m, mn = g->n;
+  const int64_t nw = ceil_div64(g->V, 64);
+  hipStream_t st = ctx->stream;
+  DevArr<uint64_t> bms, U;
+  HT_TRY(bms.alloc(ctx, (size_t)mn * nw));
+  HT_TRY(U.alloc(ctx, (size_t)n * nw));
+  HT_HIP(ctx, hipMemsetAsync(bms.p, 0, (size_t)mn * nw * 8, st));
+  for (int c = 0; c < mn; ++c) {
+    const ChunkMeta& ch = g->chunks[c];
+    if (ch.nnz > 0) {
+      k_mark<<<nblk(ch.nnz), TB, 0, st>>>(g->col.p + ch.e0, ch.nnz, (uint32_t*)(bms.p + (size_t)c * nw));
+      HT_LAUNCH_CHECK(ctx);
+    }
+  }
+  DevArr<unsigned long long> cnt;
+  HT_TRY(cnt.alloc(ctx, (size_t)2 * n));
+  std::vector<unsigned long long> hcnt((size_t)2 * n);
+  const unsigned gx = (unsigned)std::min<int64_t>(ceil_div64(nw, TB), 64);
+  // hcnt[k] = |cand_k ^ with| for the ncand bitmaps that start at cand
+  auto common = [&](const uint64_t* cand, int ncand, const uint64_t* with) -> int {
+    HT_HIP(ctx, hipMemsetAsync(cnt.p, 0, (size_t)ncand * 8, st));
+    k_overlap<<<dim3(gx, ncand), TB, 0, st>>>(cand, nw, with, cnt.p);
+    HT_LAUNCH_CHECK(ctx);
+    HT_HIP(ctx, hipMemcpyAsync(hcnt.data(), cnt.p, (size_t)ncand * 8, hipMemcpyDeviceToHost, st));
+    HT_HIP(ctx, hipStreamSynchronize(st));
+    return HT_OK;
+  };
+  // V_ori, V_+p2p, V_+ru (Sec. 5.3) of a layout; uses U for the batch unions
+  auto volumes = [&](const std::vector<int32_t>& lay, int64_t* out) -> int {
+    HT_HIP(ctx, hipMemsetAsync(U.p, 0, (size_t)n * nw * 8, st));
+    for (int j = 0; j < n; ++j)
+      for (int i = 0; i < m; ++i) {
+        k_bm_or<<<nblk(nw), TB, 0, st>>>(U.p + (size_t)j * nw, bms.p + (size_t)(i * n + lay[i * n + j]) * nw, nw);
+        HT_LAUNCH_CHECK(ctx);
+      }
+    HT_HIP(ctx, hipMemsetAsync(cnt.p, 0, (size_t)2 * n * 8, st));
+    for (int j = 0; j < n; ++j) {   // slot j: |U_j|; slot n + j: |U_j ^ U_{j-1}|
+      k_overlap<<<dim3(gx, 1), TB, 0, st>>>(U.p + (size_t)j * nw, nw, U.p + (size_t)j * nw, cnt.p + j);
+      HT_LAUNCH_CHECK(ctx);
+      if (j > 0) {
+        k_overlap<<<dim3(gx, 1), TB, 0, st>>>(U.p + (size_t)j * nw, nw, U.p + (size_t)(j - 1) * nw, cnt.p + n + j);
+        HT_LAUNCH_CHECK(ctx);
+      }
+    }
+    HT_HIP(ctx, hipMemcpyAsync(hcnt.data(), cnt.p, (size_t)2 * n * 8, hipMemcpyDeviceToHost, st));
+    HT_HIP(ctx, hipStreamSynchronize(st));
+    out[0] = g->v_ori;
+    out[1] = out[2] = 0;
+    for (int j = 0; j < n; ++j) {
+      out[1] += (int64_t)hcnt[j];
+      out[2] += (int64_t)hcnt[j] - (j > 0 ? (int64_t)hcnt[n + j] : 0);
+    }
+    return HT_OK;
+  };
+  std::vector<int32_t> lay((size_t)mn);
+  for (int c = 0; c < mn; ++c) lay[c] = c % n;
+  if (before) HT_TRY(volumes(lay, before));
+  // ---- phase 1: the batches start as partition 0's subgraphs; every other partition hands each batch, in
+  // batch order, its unassigned subgraph with the most neighbours in common with the batch's union so far
+  std::vector<int32_t> Gt((size_t)mn);
+  for (int j = 0; j < n; ++j) Gt[j] = j;
+  HT_HIP(ctx, hipMemcpyAsync(U.p, bms.p, (size_t)n * nw * 8, hipMemcpyDeviceToDevice, st));
+  for (int i = 1; i < m; ++i) {
+    std::vector<char> taken(n, 0);
+    for (int j = 0; j < n; ++j) {
+      HT_TRY(common(bms.p + (size_t)i * n * nw, n, U.p + (size_t)j * nw));
+      int best = -1;
+      for (int k = 0; k < n; ++k)
+        if (!taken[k] && (best < 0 || hcnt[k] > hcnt[best])) best = k;
+      Gt[(size_t)i * n + j] = best;
+      taken[best] = 1;
+      k_bm_or<<<nblk(nw), TB, 0, st>>>(U.p + (size_t)j * nw, bms.p + (size_t)(i * n + best) * nw, nw);
+      HT_LAUNCH_CHECK(ctx);
+    }
+  }
+  // ---- phase 2: batch 0 first, then always the unplaced batch whose union shares the most with the last one
+  std::vector<int32_t> at(n, 0);
+  std::vector<char> placed(n, 0);
+  if (n > 0) placed[0] = 1;
+  for (int j = 1; j < n; ++j) {
+    HT_TRY(common(U.p, n, U.p + (size_t)at[j - 1] * nw));
+    int best = -1;
+    for (int k = 0; k < n; ++k)
+      if (!placed[k] && (best < 0 || hcnt[k] > hcnt[best])) best = k;
+    at[j] = best;
+    placed[best] = 1;
+  }
+  for (int i = 0; i < m; ++i)
+    for (int j = 0; j < n; ++j) lay[(size_t)i * n + j] = Gt[(size_t)i * n + at[j]];
+  if (after) HT_TRY(volumes(lay, after));
+  for (int c = 0; c < mn; ++c) layout[c] = lay[c];
+  HT_HIP(ctx, hipStreamSynchronize(st));
+  return HT_OK;
+}
+
 }  // extern "C"

@@ -238,3 +238,61 @@ def test_bad_arguments(ctx):
         B.ht_partition(ctx, 10, src, dst, 2, cache_rows=1)   # buffer smaller than a chunk's neighbour set
     with pytest.raises(B.HongtuError):
         B.ht_partition(ctx, 10, src, dst, 2, cache_policy=2)
+
+
+# ------------------------------------------------------------------ m partitions: Alg. 4 and the volumes of Sec. 5.3
+
+def check_reorganize(ctx, V, src, dst, m, n, self_loops=True, mode=B.HT_BALANCE_EDGES):
+    g = B.ht_partition(ctx, V, src.cuda(), dst.cuda(), m * n, add_self_loops=self_loops, balance_mode=mode)
+    try:
+        layout, before, after = B.ht_graph_reorganize(ctx, g, m)
+        indptr, col = orc.csc_build(V, src.numpy(), dst.numpy(), self_loops)
+        b = orc.chunk_bounds(indptr, m * n, mode)
+        o_layout = orc.reorganize(indptr, col, b, m, n)
+        assert np.array_equal(layout, o_layout), f"m={m} n={n}: layout {layout} vs {o_layout}"
+        assert before == orc.volumes_mn(indptr, col, b, m, n)
+        assert after == orc.volumes_mn(indptr, col, b, m, n, o_layout)
+        return layout, before, after
+    finally:
+        B.ht_graph_destroy(g)
+
+
+def test_reorganize_against_the_oracle(ctx):
+    rng = np.random.default_rng(21)
+    for V, E, m, n in ((50, 300, 2, 3), (64, 1000, 4, 4), (3000, 40_000, 3, 7), (3000, 40_000, 1, 9), (129, 600, 8, 1)):
+        src = torch.from_numpy(rng.integers(0, V, E).astype(np.int32))
+        dst = torch.from_numpy(rng.integers(0, V, E).astype(np.int32))
+        keep = src != dst
+        check_reorganize(ctx, V, src[keep], dst[keep], m, n, self_loops=bool(rng.integers(0, 2)))
+    # the skewed generator at the smallest workload, four and eight partitions of four chunks
+    w = inputs.WORKLOADS["cfg1"]
+    src, dst = inputs.rmat_edges(w.V, w.E, w.graph_seed)
+    for m in (4, 8):
+        layout, before, after = check_reorganize(ctx, w.V, src, dst, m, 4)
+        assert before[0] == after[0] and after[0] >= after[1] >= after[2] >= w.V
+    # hubs and empty subgraphs: more chunks than edge targets can fill
+    src, dst = hub_graph(400, 3000, 900, 700, 3)
+    check_reorganize(ctx, 400, src, dst, 4, 8, mode=B.HT_BALANCE_VERTICES)
+    check_reorganize(ctx, 400, src, dst, 4, 8)
+
+
+def test_reorganize_one_partition_is_the_chunk_reordering(ctx):
+    w = inputs.WORKLOADS["cfg1"]
+    src, dst = inputs.rmat_edges(w.V, w.E, w.graph_seed)
+    g = B.ht_partition(ctx, w.V, src.cuda(), dst.cuda(), 12)
+    g2 = B.ht_partition(ctx, w.V, src.cuda(), dst.cuda(), 12, reorder_chunks=True)
+    try:
+        layout, before, after = B.ht_graph_reorganize(ctx, g, 1)
+        assert np.array_equal(layout, B.ht_graph_chunk_order(g2))
+        i1, i2 = B.ht_graph_info_get(g), B.ht_graph_info_get(g2)
+        assert before == (i1.v_ori, i1.v_ori, i1.v_ru) and after == (i2.v_ori, i2.v_ori, i2.v_ru)
+        assert not np.array_equal(layout, np.arange(12)), "the case needs a schedule that differs from the id order"
+        with pytest.raises(B.HongtuError):       # a graph whose chunks are already out of vertex-id order
+            B.ht_graph_reorganize(ctx, g2, 1)
+        with pytest.raises(B.HongtuError):       # 12 chunks do not split into 5 partitions
+            B.ht_graph_reorganize(ctx, g, 5)
+        with pytest.raises(B.HongtuError):
+            B.ht_graph_reorganize(ctx, g, 0)
+    finally:
+        B.ht_graph_destroy(g)
+        B.ht_graph_destroy(g2)
