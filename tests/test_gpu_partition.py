@@ -296,3 +296,27 @@ def test_reorganize_one_partition_is_the_chunk_reordering(ctx):
     finally:
         B.ht_graph_destroy(g)
         B.ht_graph_destroy(g2)
+
+
+def test_reorganize_finds_planted_locality(ctx):
+    """m partitions whose subgraphs draw their sources from n disjoint blocks, each partition in its own shuffled
+    order: phase 1 has to put the subgraphs of one block into one batch, which cuts the rows a batch fetches m-fold."""
+    rng = np.random.default_rng(3)
+    m, n, per, blk = 4, 6, 50, 200             # per destinations per subgraph, blk sources per block
+    V = m * n * per                             # destinations are all vertices; the first n * blk ids double as sources
+    assert n * blk <= V
+    perms = [np.arange(n)] + [rng.permutation(n) for _ in range(m - 1)]
+    src, dst = [], []
+    for i in range(m):
+        for k in range(n):
+            d0 = (i * n + k) * per
+            for v in range(d0, d0 + per):
+                us = rng.choice(blk, size=20, replace=False) + perms[i][k] * blk
+                src.extend(us.tolist())
+                dst.extend([v] * 20)
+    src, dst = torch.tensor(src, dtype=torch.int32), torch.tensor(dst, dtype=torch.int32)
+    keep = src != dst
+    layout, before, after = check_reorganize(ctx, V, src[keep], dst[keep], m, n, self_loops=False, mode=B.HT_BALANCE_VERTICES)
+    for i in range(m):
+        assert [int(perms[i][layout[i * n + j]]) for j in range(n)] == [int(perms[0][layout[j]]) for j in range(n)]
+    assert before[0] == after[0] and after[1] <= n * blk and before[1] > 2 * after[1]
