@@ -79,12 +79,17 @@ __global__ void k_bounds(const int64_t* __restrict__ indptr, int64_t V, const in
   b[j] = lo;
 }
 
+// Sets bit col[t] for every entry.  A repeated source follows its first copy (sources ascend inside a
+// destination) and is skipped; the bit is tested with a device-scope load first, which sees the bits other
+// XCDs have set (a plain load may be served from this XCD's own caches for a long time, and the hub
+// sources' words then take an atomic per entry).
 __global__ void k_mark(const int32_t* __restrict__ col, int64_t nnz, uint32_t* bm32) {
   int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= nnz) return;
   const uint32_t u = (uint32_t)col[t];
+  if (t > 0 && (uint32_t)col[t - 1] == u) return;
   const uint32_t bit = 1u << (u & 31);
-  if (!(bm32[u >> 5] & bit)) atomicOr(&bm32[u >> 5], bit);
+  if (!(__hip_atomic_load(&bm32[u >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bit)) atomicOr(&bm32[u >> 5], bit);
 }
 
 // totals[0] += popc(cur), totals[1] += popc(cur & prev), totals[2] += popc(cur & res)

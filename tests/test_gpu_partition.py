@@ -270,6 +270,9 @@ def test_reorganize_against_the_oracle(ctx):
     for m in (4, 8):
         layout, before, after = check_reorganize(ctx, w.V, src, dst, m, 4)
         assert before[0] == after[0] and after[0] >= after[1] >= after[2] >= w.V
+    # bitmaps of several thousand words (the counting kernel's grid-stride loop and its atomics across blocks)
+    src, dst = inputs.rmat_edges(300_000, 3_000_000, 5)
+    check_reorganize(ctx, 300_000, src, dst, 4, 8)
     # hubs and empty subgraphs: more chunks than edge targets can fill
     src, dst = hub_graph(400, 3000, 900, 700, 3)
     check_reorganize(ctx, 400, src, dst, 4, 8, mode=B.HT_BALANCE_VERTICES)
