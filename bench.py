@@ -237,7 +237,7 @@ def main():
     ap.add_argument("--order", choices=["paper", "auto"], default="paper",
                     help="stage order of a layer: aggregate then transform as Eq. 2 prints it (the timed default), or "
                          "transform first in the layers that get narrower (same function, fewer bytes aggregated)")
-    ap.add_argument("--no-other-order", action="store_true", help="do not time the second stage order as well")
+    ap.add_argument("--no-other-order", action="store_true", help="one pass only, every phase timed: no second pass for the phase breakdown, no other stage order, no reuse or graph runs")
     ap.add_argument("--permute-ids", action="store_true", help="relabel the vertices by a seeded random permutation "
                     "(sensitivity row: R-MAT keeps its hubs at the low ids)")
     ap.add_argument("--hbm-budget-gb", type=float, default=0, help="byte budget the residency planner works with "
@@ -316,9 +316,9 @@ def main():
         del a, b
     note("inputs resident")
 
-    def timed_epochs(order, reuse=False):
+    def timed_epochs(order, reuse=False, detail=B.HT_STATS_ALL, warmup=None):
         """W warm-up epochs, then K timed ones; returns (seconds, summed stats, last loss)."""
-        for _ in range(max(args.warmup, 1 if reuse else 0)):
+        for _ in range(max(args.warmup if warmup is None else warmup, 1 if reuse else 0)):
             B.ht_epoch(ctx, g, w.dims, Wd, w.lr, Xd, yd, order=order, reuse_input_aggregate=reuse, **plan)
             note("warm-up epoch done")
         torch.cuda.synchronize()
@@ -326,7 +326,7 @@ def main():
         t0 = time.perf_counter()
         for _ in range(args.steps):
             loss, st = B.ht_epoch(ctx, g, w.dims, Wd, w.lr, Xd, yd, want_stats=True, order=order,
-                                  reuse_input_aggregate=reuse, **plan)
+                                  reuse_input_aggregate=reuse, stats_detail=detail, **plan)
             d = st.as_dict()
             note(f"epoch done: {d['t_total_ms']:.1f} ms, loss {loss:.5f}")
             if tot is None:
@@ -338,8 +338,22 @@ def main():
         return time.perf_counter() - t0, tot, loss
 
     main_order = B.HT_ORDER_AUTO if args.order == "auto" else B.HT_ORDER_AGG_FIRST
-    elapsed, tot, loss = timed_epochs(main_order)
+    # The timed region carries event pairs around the forward aggregation kernels only (the roofline's kernel is
+    # one of them); the per-phase breakdown comes from a second pass of K epochs with every phase timed, whose
+    # events cost a few per cent of a cfg2 epoch.  With --no-other-order there is one pass, fully timed.
+    lean = not args.no_other_order
+    elapsed, tot, loss = timed_epochs(main_order, detail=B.HT_STATS_AGG_FWD if lean else B.HT_STATS_ALL)
     agg = {"t": tot["t_agg_fwd_layer_ms"][0], "n": tot["n_agg_fwd_layer"][0], "bytes": tot["agg_fwd_layer_alg_bytes"][0]}
+    phase_pass = None
+    if lean:
+        p_el, p_tot, _ = timed_epochs(main_order, warmup=0)
+        phase_pass = {"ms_per_step": 1e3 * p_el / args.steps,
+                      "note": "phase_ms_per_step, gemm_tflops and gemm_frac_of_fp32_mfma_peak come from this second pass of "
+                              "K epochs with every phase timed; value and roofline from the first, which times only the "
+                              "forward aggregation kernels"}
+        for k in p_tot:
+            if k.startswith("t_") and k not in ("t_agg_fwd_layer_ms", "t_total_ms"):
+                tot[k] = p_tot[k]
     other = None
     if not host and args.scale == 1.0 and not args.no_other_order:
         # the other stage order on the same graph and weights (which keep training: the loss differs)
@@ -414,7 +428,7 @@ def main():
            "bytes_h2d_nodedup_per_step": tot["bytes_h2d_nodedup"] / args.steps,
            "input_generation_s": t_gen,
            "paper_context": "HongTu-IM 2-layer GCN on reddit (same shape), 1xA100: 0.20 s/epoch (Table 4); other hardware, real dataset",
-           "order": args.order, "other_order": other, "input_aggregate_reuse": reuse_run, "hip_graph": graph_run,
+           "phase_pass": phase_pass, "order": args.order, "other_order": other, "input_aggregate_reuse": reuse_run, "hip_graph": graph_run,
            "plan": {"inter": ["auto", "mask", "hybrid", "recompute"][tot["plan_inter"] // args.steps],
                     "h": ["-", "hbm", "host"][tot["plan_res_h"] // args.steps],
                     "a": ["-", "hbm", "host"][tot["plan_res_a"] // args.steps],

@@ -420,7 +420,14 @@ typedef struct {
                    * epoch's kernels are captured into a HIP graph on the second call with the same
                    * graph, X, labels, parameter pointers, lr and plan, and replayed from then on
                    * (same kernels, same order: same bits).  Ignored otherwise. */
+  int32_t stats_detail; /* what a non-null ht_stats times with event pairs on the streams:
+                   * HT_STATS_ALL (0) every phase of every chunk; HT_STATS_AGG_FWD (1) only the
+                   * forward aggregation kernels (t_agg_fwd_layer_ms, t_spmm_fwd_ms), the other
+                   * t_* fields stay 0.  Counters (rows, bytes, edges, flops) are filled either way.
+                   * Events cost a few microseconds each: a few per cent of a cfg2-sized epoch. */
+  int32_t reserved;
 } ht_plan_opts;
+enum { HT_STATS_ALL = 0, HT_STATS_AGG_FWD = 1 };
 
 /* One training epoch (Alg. 1): forward over layers and chunks, softmax
  * cross-entropy averaged over labelled vertices (labels[v] >= 0; device int32

@@ -27,6 +27,7 @@ HT_GATHER_AUTO, HT_GATHER_DIRECT, HT_GATHER_BUFFER = 0, 1, 2
 HT_CKPT_AGG, HT_CKPT_INPUT = 0, 1
 HT_ORDER_AGG_FIRST, HT_ORDER_UPDATE_FIRST, HT_ORDER_AUTO = 0, 1, 2
 HT_RES_AUTO, HT_RES_HBM, HT_RES_HOST = 0, 1, 2
+HT_STATS_ALL, HT_STATS_AGG_FWD = 0, 1
 HT_INTER_AUTO, HT_INTER_MASK, HT_INTER_HYBRID, HT_INTER_RECOMPUTE = 0, 1, 2, 3
 HT_BUF_H, HT_BUF_A, HT_BUF_GH, HT_BUF_DW = 0, 1, 2, 3
 HT_MAX_LAYERS = 8
@@ -105,7 +106,8 @@ class ht_gat_model(C.Structure):
 class ht_plan_opts(C.Structure):
     _fields_ = [("res_h", C.c_int32), ("res_a", C.c_int32), ("res_g", C.c_int32), ("inter", C.c_int32),
                 ("gather_mode", C.c_int32), ("order", C.c_int32), ("hbm_budget_bytes", C.c_int64),
-                ("reuse_input_aggregate", C.c_int32), ("use_graph", C.c_int32)]
+                ("reuse_input_aggregate", C.c_int32), ("use_graph", C.c_int32), ("stats_detail", C.c_int32),
+                ("reserved", C.c_int32)]
 
 
 EXPORTS = ["ht_ctx_create", "ht_ctx_destroy", "ht_sync", "ht_ctx_set_hbm_budget", "ht_ctx_graph_launches", "ht_tensor_zero", "ht_strerror", "ht_last_error",
@@ -436,7 +438,8 @@ def ht_gat_epoch(ctx, g, dims: Sequence[int], Ws: List[torch.Tensor], a_dst: Lis
 def ht_epoch(ctx, g, dims: Sequence[int], Ws: List[torch.Tensor], lr: float, X: torch.Tensor, labels: torch.Tensor,
              res_h: int = HT_RES_AUTO, res_a: int = HT_RES_AUTO, res_g: int = HT_RES_AUTO, inter: int = HT_INTER_AUTO,
              gather_mode: int = HT_GATHER_AUTO, hbm_budget_bytes: int = 0, want_stats: bool = False, sync: bool = True,
-             order: int = HT_ORDER_AGG_FIRST, reuse_input_aggregate: bool = False, use_graph: bool = False):
+             order: int = HT_ORDER_AGG_FIRST, reuse_input_aggregate: bool = False, use_graph: bool = False,
+             stats_detail: int = 0):
     """One epoch; Ws (device tensors) are updated in place.  Returns (loss, stats or None)."""
     L = len(dims) - 1
     assert len(Ws) == L and labels.is_cuda and labels.dtype == torch.int32
@@ -445,7 +448,8 @@ def ht_epoch(ctx, g, dims: Sequence[int], Ws: List[torch.Tensor], lr: float, X: 
     dims_a = (C.c_int32 * (L + 1))(*dims)
     Wp = (C.c_void_p * L)(*[w.data_ptr() for w in Ws])
     model = ht_model(L, 0, dims_a, Wp, lr, 0)
-    plan = ht_plan_opts(res_h, res_a, res_g, inter, gather_mode, order, hbm_budget_bytes, int(reuse_input_aggregate), int(use_graph))
+    plan = ht_plan_opts(res_h, res_a, res_g, inter, gather_mode, order, hbm_budget_bytes, int(reuse_input_aggregate), int(use_graph),
+                        stats_detail, 0)
     x = tensor_view(X, dims[0])
     loss = C.c_float(0.0)
     st = ht_stats() if want_stats else None

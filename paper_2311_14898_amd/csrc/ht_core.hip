@@ -86,6 +86,7 @@ hipEvent_t ht_event(ht_ctx* ctx) {
 
 int Timer::begin_on(double* acc, hipStream_t s) {
   if (!on) return -1;
+  if (only_lo && (acc < only_lo || acc >= only_hi)) return -1;
   hipEvent_t a = ht_event(ctx), b = ht_event(ctx);
   if (!a || !b) {
     on = false;

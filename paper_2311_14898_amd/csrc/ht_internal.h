@@ -311,9 +311,11 @@ struct Timer {
     double* dst;
   };
   std::vector<Ent> ev;
+  const double *only_lo = nullptr, *only_hi = nullptr;   // when set: time only accumulators inside [only_lo, only_hi)
   Timer(ht_ctx* c, hipStream_t s, bool enabled) : ctx(c), st(s), on(enabled) {}
-  void begin(double* acc) { begin_on(acc, st); }
-  void end() { end_id((int)ev.size() - 1); }
+  int last = -1;   // id of the pair opened by the last begin() (-1: that phase is not timed)
+  void begin(double* acc) { last = begin_on(acc, st); }
+  void end() { end_id(last); last = -1; }
   int begin_on(double* acc, hipStream_t s);  // returns an id for end_id (-1 when timing is off)
   void end_id(int id);
   int resolve();  // after the streams are synchronised

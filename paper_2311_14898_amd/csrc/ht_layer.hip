@@ -1202,6 +1202,11 @@ int ht_epoch(ht_ctx* ctx, const ht_graph* g, const ht_model* model, const ht_ten
 
   ht_stats local{};
   Run R(ctx, g, &local, stats != nullptr);
+  if (plan && plan->stats_detail == HT_STATS_AGG_FWD) {
+    R.tm.only_lo = &local.t_agg_fwd_layer_ms[0];
+    R.tm.only_hi = &local.t_agg_fwd_layer_ms[0] + HT_MAX_LAYERS;
+  } else if (plan && plan->stats_detail != HT_STATS_ALL)
+    return ht_set_err(ctx, HT_EINVAL, "ht_epoch: unknown stats_detail %d", plan->stats_detail);
   auto fail = [&](int rc) {
     (void)hipStreamSynchronize(ctx->stream);
     ctx->ev_next = 0;

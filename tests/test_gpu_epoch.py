@@ -382,3 +382,20 @@ def test_two_epochs_reuse_workspace_and_loss_decreases(ctx, cfg1):
         assert l2 < l1 < l0
     finally:
         B.ht_graph_destroy(g)
+
+
+def test_stats_detail_times_only_the_forward_aggregation(ctx, cfg1):
+    w, src, dst, X, y, Ws, ref = cfg1
+    full = run_epoch(ctx, w, src, dst, X, y, Ws)
+    lean = run_epoch(ctx, w, src, dst, X, y, Ws, stats_detail=B.HT_STATS_AGG_FWD)
+    assert lean["loss"] == full["loss"]
+    for l in range(w.n_layers):
+        assert np.array_equal(lean["W_new"][l], full["W_new"][l])
+    a, b = full["stats"].as_dict(), lean["stats"].as_dict()
+    assert all(t > 0 for t in b["t_agg_fwd_layer_ms"][:w.n_layers]) and b["t_spmm_fwd_ms"] > 0
+    for k in ("t_gemm_ms", "t_spmm_bwd_ms", "t_loss_ms", "t_update_ms", "t_agg_fix_ms"):
+        assert a[k] > 0 and b[k] == 0, k
+    for k in ("edges", "gemm_flops", "n_spmm_fwd", "n_spmm_bwd", "spmm_fwd_alg_bytes", "rows_loaded", "bytes_h2d"):
+        assert a[k] == b[k], k
+    with pytest.raises(B.HongtuError):
+        run_epoch(ctx, w, src, dst, X, y, Ws, stats_detail=7)
