@@ -186,10 +186,13 @@ __global__ void __launch_bounds__(256) k_gat_dp(const float* __restrict__ dz, co
   if (lane == 0) dp_chunk[r] = s - S[r] * r_chunk[r];
 }
 
-// dz = dh * [h > 0] (or dh), pad columns zero, and S_v = dz_v . h_v; a wave per row of the chunk
+// dz = dh * [h > 0] (or dh), pad columns zero, S_v = dz_v . h_v, and d4[row] = (p_v, m_v, 1/Z_v, S_v) (p, m, zinv
+// point at the chunk's first destination); a wave per row of the chunk
 __global__ void __launch_bounds__(256) k_gat_dz(const float* __restrict__ dh, int64_t ld_dh, const float* __restrict__ h,
                                                 int64_t ld_h, int relu, int64_t rows, int d, float* __restrict__ dz,
-                                                int64_t ld_dz, float* __restrict__ S) {
+                                                int64_t ld_dz, float* __restrict__ S, const float* __restrict__ p,
+                                                const float* __restrict__ m, const float* __restrict__ zinv,
+                                                float* __restrict__ d4) {
   const int lane = threadIdx.x & 63;
   const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (r >= rows) return;
@@ -205,7 +208,11 @@ __global__ void __launch_bounds__(256) k_gat_dz(const float* __restrict__ dh, in
     dz[r * ld_dz + c] = g;
   }
   s = wave_sum(s);
-  if (lane == 0) S[r] = s;
+  if (lane == 0) {
+    S[r] = s;
+    // what the source pass needs of a destination, in one 16-byte read per entry instead of four 4-byte ones
+    st4(d4 + r * 4, make_float4(p[r], m[r], zinv[r], s));
+  }
 }
 
 struct GatPass {
@@ -222,6 +229,7 @@ struct GatPass {
   const float* p; const float* q;        // per vertex
   const float* m; const float* zinv;     // per vertex: the coefficients are recomputed from them
   const float* S;            // per row of the chunk
+  const float* d4;           // per row of the chunk: (p_v, m_v, 1/Z_v, S_v)
   int64_t dst0;              // first destination of the chunk
   float slope;
   // outputs
@@ -268,11 +276,11 @@ __global__ void __launch_bounds__(256) k_gat_src(GatPass a) {
     float my_c = 0.f, my_cf = 0.f, my_cs = 0.f;   // w_e, w_e f_e, w_e f_e S_v of the lane's entry
     if (lane < nh) {
       my_v = a.idx[e0 + base + lane];
-      const int64_t v = a.dst0 + my_v;
-      const float y = a.p[v] + qu;
-      my_c = coef(y, a.slope, a.m[v], a.zinv[v], a.mult ? a.mult[e0 + base + lane] : 1.f);
+      const float4 dv = ld4(a.d4 + (int64_t)my_v * 4);
+      const float y = dv.x + qu;
+      my_c = coef(y, a.slope, dv.y, dv.z, a.mult ? a.mult[e0 + base + lane] : 1.f);
       my_cf = my_c * (y > 0.f ? 1.f : a.slope);
-      my_cs = my_cf * a.S[my_v];
+      my_cs = my_cf * dv.w;
     }
     csum += wave_sum(my_cs);
     for (int32_t k = 0; k < nh; k += 4) {
@@ -355,11 +363,11 @@ __global__ void __launch_bounds__(256) k_gat_src_g(GatPass a) {
     float my_c = 0.f, my_cf = 0.f, my_cs = 0.f;
     if (lane < nh) {
       my_v = a.idx[e0 + base + lane];
-      const int64_t v = a.dst0 + my_v;
-      const float y = a.p[v] + qu;
-      my_c = coef(y, a.slope, a.m[v], a.zinv[v], a.mult ? a.mult[e0 + base + lane] : 1.f);
+      const float4 dv = ld4(a.d4 + (int64_t)my_v * 4);
+      const float y = dv.x + qu;
+      my_c = coef(y, a.slope, dv.y, dv.z, a.mult ? a.mult[e0 + base + lane] : 1.f);
       my_cf = my_c * (y > 0.f ? 1.f : a.slope);
-      my_cs = my_cf * a.S[my_v];
+      my_cs = my_cf * dv.w;
     }
     csum += wave_sum(my_cs);
     for (int32_t k = 0; k < nh; k += 4 * NG) {
@@ -438,7 +446,7 @@ __global__ void k_gat_split(const float* __restrict__ da4, int d, float* __restr
 }
 
 struct GatWs {
-  float *T, *p, *q, *m, *zinv, *S, *dp, *r, *pq4, *w, *wf;
+  float *T, *p, *q, *m, *zinv, *S, *dp, *r, *pq4, *d4, *w, *wf;
   int64_t ld_t;
 };
 
@@ -531,10 +539,11 @@ int prepare(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const ht_te
   ws->ld_t = ht_row_pitch(desc->d_out, true);
   HT_TRY(ht_scratch(ctx, HT_S_TFULL, (size_t)V * ws->ld_t * 4, (void**)&ws->T));
   float* vec = nullptr;
-  HT_TRY(ht_scratch(ctx, HT_S_GATV, (size_t)V * 12 * 4, (void**)&vec));
+  HT_TRY(ht_scratch(ctx, HT_S_GATV, (size_t)V * 16 * 4, (void**)&vec));
   ws->p = vec; ws->q = vec + V; ws->m = vec + 2 * V; ws->zinv = vec + 3 * V; ws->S = vec + 4 * V; ws->dp = vec + 5 * V;
   ws->r = vec + 6 * V;
   ws->pq4 = vec + 8 * V;      // 16-byte aligned whatever V is
+  ws->d4 = vec + 12 * V;      // per chunk, rows of the chunk
   const size_t ne = (size_t)std::max<int64_t>(g->max_nnz, 1);
   HT_TRY(ht_scratch(ctx, HT_S_GATE, ne * 4 * (backward ? 2 : 1), (void**)&ws->w));
   ws->wf = backward ? ws->w + ne : nullptr;
@@ -740,11 +749,12 @@ int gat_bwd_impl(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const 
     if (hout_host || dho_host) HT_TRY(lk.wait(st, ev_in[b]));
     k_gat_dz<<<(unsigned)((ndst + 3) / 4), 256, 0, st>>>(dho_host ? gbuf[b] : dH_out->ptr + c.dst0 * dH_out->ld, dH_out->ld,
                                                           hout_host ? hbuf[b] : H_out->ptr + c.dst0 * H_out->ld, H_out->ld,
-                                                          desc->act == HT_ACT_RELU, ndst, d, dz, ws.ld_t, ws.S);
+                                                          desc->act == HT_ACT_RELU, ndst, d, dz, ws.ld_t, ws.S, ws.p + c.dst0,
+                                                          ws.m + c.dst0, ws.zinv + c.dst0, ws.d4);
     HT_LAUNCH_CHECK(ctx);
     if (hout_host || dho_host) HT_TRY(lk.rec(st, &ev_free[b]));   // the staged rows have been consumed
     GatPass a{};
-    a.d = d; a.p = ws.p; a.q = ws.q; a.m = ws.m; a.zinv = ws.zinv; a.S = ws.S; a.dst0 = c.dst0; a.slope = desc->slope;
+    a.d = d; a.p = ws.p; a.q = ws.q; a.m = ws.m; a.zinv = ws.zinv; a.S = ws.S; a.d4 = ws.d4; a.dst0 = c.dst0; a.slope = desc->slope;
     // destination pass: Q_v = sum_e w_e f_e t_u through the aggregation kernel, then dp_v = dz_v . Q_v - S_v r_v
     tm->begin(&local->t_gat_dst_ms);
     {
