@@ -21,7 +21,7 @@ struct EpochWs;
 enum {
   HT_S_PACKW = 0, HT_S_TNPART, HT_S_LOSS, HT_S_ACHUNK, HT_S_OCHUNK, HT_S_ZCHUNK, HT_S_DZCHUNK, HT_S_DACHUNK,
   HT_S_NBUF, HT_S_SPART, HT_S_LEAVE, HT_S_MISC, HT_S_TFULL, HT_S_TFULL2, HT_S_GATV, HT_S_GATE, HT_S_GATWS, HT_S_GATP,
-  HT_S_LINK0, HT_S_LINK1, HT_S_LINK2, HT_N_SCRATCH
+  HT_S_LINK0, HT_S_LINK1, HT_S_LINK2, HT_S_SCAN, HT_S_RSORT, HT_N_SCRATCH
 };
 
 struct ht_ctx {

@@ -78,6 +78,25 @@ __global__ void __launch_bounds__(SCAN_THREADS) k_scan_apply(const Tin* in, int6
   if (want_total && blockIdx.x == gridDim.x - 1 && threadIdx.x == SCAN_THREADS - 1) out[n] = off;
 }
 
+// Block sums of every level live back to back in one scratch slot of the context (the level of n elements
+// needs ceil(n / SCAN_TILE) sums, the next one a tile-th of that, ...): no allocation, hence no
+// implicit device synchronisation, per call.  ws points at this level's sums.
+template <typename Tin>
+int scan_level(ht_ctx* ctx, const Tin* in, int64_t* out, int64_t n, bool want_total, int64_t* ws) {
+  const int64_t nb = ceil_div64(n, SCAN_TILE);
+  if (nb == 1) {
+    k_scan_apply<Tin><<<1, SCAN_THREADS, 0, ctx->stream>>>(in, n, nullptr, out, want_total ? 1 : 0);
+    HT_LAUNCH_CHECK(ctx);
+    return HT_OK;
+  }
+  k_scan_reduce<Tin><<<(unsigned)nb, SCAN_THREADS, 0, ctx->stream>>>(in, n, ws);
+  HT_LAUNCH_CHECK(ctx);
+  HT_TRY(scan_level<int64_t>(ctx, ws, ws, nb, false, ws + nb));
+  k_scan_apply<Tin><<<(unsigned)nb, SCAN_THREADS, 0, ctx->stream>>>(in, n, ws, out, want_total ? 1 : 0);
+  HT_LAUNCH_CHECK(ctx);
+  return HT_OK;
+}
+
 template <typename Tin>
 int scan_impl(ht_ctx* ctx, const Tin* in, int64_t* out, int64_t n, bool want_total) {
   if (n < 0) return ht_set_err(ctx, HT_EINVAL, "scan: negative length");
@@ -85,21 +104,11 @@ int scan_impl(ht_ctx* ctx, const Tin* in, int64_t* out, int64_t n, bool want_tot
     if (want_total) HT_HIP(ctx, hipMemsetAsync(out, 0, sizeof(int64_t), ctx->stream));
     return HT_OK;
   }
-  const int64_t nb = ceil_div64(n, SCAN_TILE);
-  if (nb == 1) {
-    k_scan_apply<Tin><<<1, SCAN_THREADS, 0, ctx->stream>>>(in, n, nullptr, out, want_total ? 1 : 0);
-    HT_LAUNCH_CHECK(ctx);
-    return HT_OK;
-  }
-  DevArr<int64_t> sums;
-  HT_TRY(sums.alloc(ctx, (size_t)nb));
-  k_scan_reduce<Tin><<<(unsigned)nb, SCAN_THREADS, 0, ctx->stream>>>(in, n, sums.p);
-  HT_LAUNCH_CHECK(ctx);
-  HT_TRY(scan_impl<int64_t>(ctx, sums.p, sums.p, nb, false));
-  k_scan_apply<Tin><<<(unsigned)nb, SCAN_THREADS, 0, ctx->stream>>>(in, n, sums.p, out, want_total ? 1 : 0);
-  HT_LAUNCH_CHECK(ctx);
-  // sums is freed on return; hipFree waits for the kernels that use it.
-  return HT_OK;
+  size_t sums = 0;
+  for (int64_t m = ceil_div64(n, SCAN_TILE); m > 1; m = ceil_div64(m, SCAN_TILE)) sums += (size_t)m;
+  int64_t* ws = nullptr;
+  if (sums > 0) HT_TRY(ht_scratch(ctx, HT_S_SCAN, sums * sizeof(int64_t), (void**)&ws));
+  return scan_level<Tin>(ctx, in, out, n, want_total, ws);
 }
 
 // ------------------------------------------------------------------ radix sort
@@ -219,10 +228,12 @@ int ht_radix_sort_u64(ht_ctx* ctx, uint64_t* keys, uint64_t* tmp, int64_t n, int
   *sorted = keys;
   if (n <= 1 || bit_hi <= bit_lo) return HT_OK;
   const int64_t nblocks = ceil_div64(n, RS_TILE);
-  DevArr<int32_t> table;
-  DevArr<int64_t> offs;
-  HT_TRY(table.alloc(ctx, (size_t)(RS_BINS * nblocks)));
-  HT_TRY(offs.alloc(ctx, (size_t)(RS_BINS * nblocks)));
+  // per-block digit counts and their offsets, in a scratch slot of the context (no allocation per call)
+  const size_t cells = (size_t)(RS_BINS * nblocks);
+  char* rs = nullptr;
+  HT_TRY(ht_scratch(ctx, HT_S_RSORT, cells * 12 + 16, (void**)&rs));
+  struct { int64_t* p; } offs{(int64_t*)rs};
+  struct { int32_t* p; } table{(int32_t*)(rs + cells * 8)};
   uint64_t* a = keys;
   uint64_t* b = tmp;
   for (int shift = bit_lo; shift < bit_hi; shift += 8) {
