@@ -448,6 +448,7 @@ int bits_for(int64_t n) {  // bits needed for values 0..n-1 (at least 1)
 struct ItemTmp {
   DevArr<int32_t> nseg, npart, isfix;
   DevArr<int64_t> it_base, part_base, fix_base;
+  DevArr<char> stage;   // items in row order, before they are permuted into dispatch order
   int alloc(ht_ctx* ctx, int64_t maxrows) {
     HT_TRY(nseg.alloc(ctx, maxrows));
     HT_TRY(npart.alloc(ctx, maxrows));
@@ -484,40 +485,41 @@ int build_items(ht_ctx* ctx, ItemTmp& t, const int64_t* ptr, int64_t ptr0, int64
   const size_t ni = (size_t)tot[0], nf = (size_t)tot[2];
   const size_t bytes = ni * 8 + ni * 4 * 3 + nf * 4 * 3;
   HT_TRY(out->blob.alloc(ctx, bytes));
-  char* p = out->blob.p;
-  out->e0 = (int64_t*)p; p += ni * 8;
-  out->row = (int32_t*)p; p += ni * 4;
-  out->len = (int32_t*)p; p += ni * 4;
-  out->part = (int32_t*)p; p += ni * 4;
-  out->fx_row = (int32_t*)p; p += nf * 4;
-  out->fx_part0 = (int32_t*)p; p += nf * 4;
-  out->fx_nseg = (int32_t*)p;
-  k_items_fill<<<nblk(nrows), TB, 0, st>>>(ptr, ptr0, nrows, seg, t.it_base.p, t.part_base.p, t.fix_base.p, out->row,
-                                          out->e0, out->len, out->part, out->fx_row, out->fx_part0, out->fx_nseg);
+  struct Lay { int64_t* e0; int32_t *row, *len, *part, *fx_row, *fx_part0, *fx_nseg; };
+  auto carve = [&](char* p) {
+    Lay l;
+    l.e0 = (int64_t*)p; p += ni * 8;
+    l.row = (int32_t*)p; p += ni * 4;
+    l.len = (int32_t*)p; p += ni * 4;
+    l.part = (int32_t*)p; p += ni * 4;
+    l.fx_row = (int32_t*)p; p += nf * 4;
+    l.fx_part0 = (int32_t*)p; p += nf * 4;
+    l.fx_nseg = (int32_t*)p;
+    return l;
+  };
+  const Lay fin = carve(out->blob.p);
+  out->e0 = fin.e0; out->row = fin.row; out->len = fin.len; out->part = fin.part;
+  out->fx_row = fin.fx_row; out->fx_part0 = fin.fx_part0; out->fx_nseg = fin.fx_nseg;
+  const bool sorted_items = order && ni > 1;
+  // Items are made in row order; when they are to be dispatched in the order of the first row they read, they
+  // are made in a staging block that outlives the chunk (no allocation per chunk) and permuted into place.
+  Lay made = fin;
+  if (sorted_items) {
+    if (t.stage.n < bytes) HT_TRY(t.stage.alloc(ctx, bytes + bytes / 4));
+    made = carve(t.stage.p);
+    made.fx_row = fin.fx_row; made.fx_part0 = fin.fx_part0; made.fx_nseg = fin.fx_nseg;   // cut-row lists keep row order
+  }
+  k_items_fill<<<nblk(nrows), TB, 0, st>>>(ptr, ptr0, nrows, seg, t.it_base.p, t.part_base.p, t.fix_base.p, made.row,
+                                          made.e0, made.len, made.part, made.fx_row, made.fx_part0, made.fx_nseg);
   HT_LAUNCH_CHECK(ctx);
-  if (order && ni > 1) {
-    k_item_keys<<<nblk((int64_t)ni), TB, 0, st>>>(out->e0, out->len, (int64_t)ni, idx, keysA);
+  if (sorted_items) {
+    k_item_keys<<<nblk((int64_t)ni), TB, 0, st>>>(made.e0, made.len, (int64_t)ni, idx, keysA);
     HT_LAUNCH_CHECK(ctx);
     uint64_t* sorted = nullptr;
     HT_TRY(ht_radix_sort_u64(ctx, keysA, keysB, (int64_t)ni, 32, 32 + bits_for(idx_range), &sorted));
-    DevArr<char> blob2;
-    HT_TRY(blob2.alloc(ctx, bytes));
-    char* q = blob2.p;
-    int64_t* e0_o = (int64_t*)q; q += ni * 8;
-    int32_t* row_o = (int32_t*)q; q += ni * 4;
-    int32_t* len_o = (int32_t*)q; q += ni * 4;
-    int32_t* part_o = (int32_t*)q; q += ni * 4;
-    k_item_permute<<<nblk((int64_t)ni), TB, 0, st>>>(sorted, (int64_t)ni, out->row, out->e0, out->len, out->part, row_o,
-                                                    e0_o, len_o, part_o);
+    k_item_permute<<<nblk((int64_t)ni), TB, 0, st>>>(sorted, (int64_t)ni, made.row, made.e0, made.len, made.part, fin.row,
+                                                    fin.e0, fin.len, fin.part);
     HT_LAUNCH_CHECK(ctx);
-    if (nf > 0)
-      HT_HIP(ctx, hipMemcpyAsync(q, out->fx_row, nf * 4 * 3, hipMemcpyDeviceToDevice, st));
-    out->fx_row = (int32_t*)q; q += nf * 4;
-    out->fx_part0 = (int32_t*)q; q += nf * 4;
-    out->fx_nseg = (int32_t*)q;
-    out->e0 = e0_o; out->row = row_o; out->len = len_o; out->part = part_o;
-    HT_HIP(ctx, hipStreamSynchronize(st));
-    out->blob = std::move(blob2);
   }
   return HT_OK;
 }
