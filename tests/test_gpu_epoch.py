@@ -399,3 +399,42 @@ def test_stats_detail_times_only_the_forward_aggregation(ctx, cfg1):
         assert a[k] == b[k], k
     with pytest.raises(B.HongtuError):
         run_epoch(ctx, w, src, dst, X, y, Ws, stats_detail=7)
+
+
+def test_hbm_budget_refusals_leave_the_context_usable(cfg1):
+    """ht_ctx_set_hbm_budget: a call that would allocate beyond the cap returns HT_ENOMEM at whatever allocation
+    crosses it (in the partition, in the epoch's workspace or in a scratch slot), frees what it had taken, and the
+    same context works once the cap is lifted."""
+    w, src, dst, X, y, Ws, ref = cfg1
+    ctx = B.ht_ctx_create(0)
+    try:
+        refused_part = refused_epoch = passed = 0
+        for budget in [1 << 10, 1 << 17, 1 << 20, 3 << 20, 5 << 20, 6 << 20, 7 << 20, 8 << 20, 10 << 20, 12 << 20,
+                       16 << 20, 24 << 20, 64 << 20]:
+            B.ht_ctx_set_hbm_budget(ctx, budget)
+            try:
+                g = B.ht_partition(ctx, w.V, src.cuda(), dst.cuda(), w.n_chunks)
+            except B.HongtuError as e:
+                assert e.code == B.HT_ENOMEM, str(e)
+                refused_part += 1
+                continue
+            try:
+                Wd = [x.clone().cuda() for x in Ws]
+                loss, _ = B.ht_epoch(ctx, g, w.dims, Wd, w.lr, B.to_matrix(X), y.cuda())
+                assert abs(loss - ref["loss"]) <= 1e-4 * abs(ref["loss"])
+                passed += 1
+            except B.HongtuError as e:
+                assert e.code == B.HT_ENOMEM, str(e)
+                refused_epoch += 1
+            finally:
+                B.ht_graph_destroy(g)
+        assert refused_part > 0 and passed > 0, (refused_part, refused_epoch, passed)
+        # had the refused calls kept their allocations, this cap (enough for one clean run) would now be too small
+        out = run_epoch(ctx, w, src, dst, X, y, Ws)
+        compare(out, ref, w.n_layers)
+        B.ht_ctx_set_hbm_budget(ctx, 0)
+        compare(run_epoch(ctx, w, src, dst, X, y, Ws), ref, w.n_layers)
+        with pytest.raises(B.HongtuError):
+            B.ht_ctx_set_hbm_budget(ctx, -1)
+    finally:
+        B.ht_ctx_destroy(ctx)
