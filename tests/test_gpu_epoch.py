@@ -438,3 +438,44 @@ def test_hbm_budget_refusals_leave_the_context_usable(cfg1):
             B.ht_ctx_set_hbm_budget(ctx, -1)
     finally:
         B.ht_ctx_destroy(ctx)
+
+
+def test_contexts_on_caller_streams(cfg1):
+    """A context may run on a stream the caller owns; two contexts on two streams, used in turn, do not disturb each
+    other (each has its own workspaces and scratch memory) and give the bits a lone context gives."""
+    w, src, dst, X, y, Ws, ref = cfg1
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()        # default priority
+    c1 = B.ht_ctx_create(0, hip_stream=s1.cuda_stream)
+    c2 = B.ht_ctx_create(0, hip_stream=s2.cuda_stream)
+    host = dict(x_loc=B.HT_LOC_HOST_PINNED, res_h=B.HT_RES_HOST, res_a=B.HT_RES_HOST, res_g=B.HT_RES_HOST)
+    try:
+        lone = run_epoch(c1, w, src, dst, X, y, Ws)
+        compare(lone, ref, w.n_layers)
+        g1 = B.ht_partition(c1, w.V, src.cuda(), dst.cuda(), w.n_chunks)
+        g2 = B.ht_partition(c2, w.V, src.cuda(), dst.cuda(), 7)
+        try:
+            W1 = [x.clone().cuda() for x in Ws]
+            W2 = [x.clone().cuda() for x in Ws]
+            X1, X2 = B.to_matrix(X), B.to_matrix(X, B.HT_LOC_HOST_PINNED)
+            yd = y.cuda()
+            torch.cuda.synchronize()
+            # enqueue on both without waiting in between (sync=False skips the binding's device-wide wait)
+            l1, _ = B.ht_epoch(c1, g1, w.dims, W1, w.lr, X1, yd, sync=False)
+            l2, _ = B.ht_epoch(c2, g2, w.dims, W2, w.lr, X2, yd, sync=False, res_h=B.HT_RES_HOST, res_a=B.HT_RES_HOST,
+                               res_g=B.HT_RES_HOST)
+            B.ht_sync(c1)
+            B.ht_sync(c2)
+            assert l1 == lone["loss"]
+            assert abs(l2 - ref["loss"]) <= 1e-4 * abs(ref["loss"])
+            for l in range(w.n_layers):
+                assert np.array_equal(W1[l].cpu().numpy(), lone["W_new"][l])
+                assert_close(W2[l].cpu().numpy(), ref["W_new"][l], f"W^{l} on the second stream")
+            with pytest.raises(B.HongtuError):      # a graph belongs to the context that made it
+                B.ht_epoch(c2, g1, w.dims, W2, w.lr, X1, yd)
+        finally:
+            B.ht_graph_destroy(g1)
+            B.ht_graph_destroy(g2)
+        compare(run_epoch(c2, w, src, dst, X, y, Ws, **host), ref, w.n_layers)
+    finally:
+        B.ht_ctx_destroy(c1)
+        B.ht_ctx_destroy(c2)
