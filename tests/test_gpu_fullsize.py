@@ -165,6 +165,27 @@ def test_float_outputs_sampled_rows(run):
                 assert (np.abs(gh_dev[l][u] - ref) <= 1e-4 * scale + slack).all(), (l, u)
 
 
+def test_forward_and_loss_against_an_independent_oracle_pass(run):
+    """The checks above feed each oracle step with the device's own input of that step.  This one shares nothing with
+    the device but the seeded inputs: the oracle builds its own CSC from the edge list and runs the whole forward
+    pass in fp64; the loss and sampled rows of every layer output must agree.  (Forward values do not depend on how a
+    pre-activation within rounding of zero is decided; the backward pass does, hence the step-wise checks above.)"""
+    w, ctx = run["w"], run["ctx"]
+    L = w.n_layers
+    indptr, col = orc.csc_build(w.V, run["src"], run["dst"])
+    h = run["X"]
+    rng = np.random.default_rng(5)
+    rows = np.unique(rng.integers(0, w.V, 4096))
+    for l in range(L):
+        a = orc.aggregate(indptr, col, h)
+        assert_close(B.ht_epoch_buffer(ctx, B.HT_BUF_A, l).numpy()[rows], a[rows], f"a^{l} rows, independent pass")
+        z = orc.matmul(a, run["Ws"][l])
+        h = np.maximum(z, 0.0) if l < L - 1 else z
+        assert_close(B.ht_epoch_buffer(ctx, B.HT_BUF_H, l + 1).numpy()[rows], h[rows], f"h^{l + 1} rows, independent pass")
+    loss_ref, _ = orc.softmax_ce(h, run["y"])
+    assert abs(run["loss"] - loss_ref) <= 1e-4 * abs(loss_ref), (run["loss"], loss_ref)
+
+
 def test_stats_and_traffic_counters(run):
     w, st = run["w"], run["stats"]
     Ep = w.E + w.V
