@@ -86,6 +86,22 @@ def test_cfg3_host_resident_epoch(data, cache_rows):
         z_ref = orc.matmul(a_dev[l][rows], Ws[l])
         assert_close(h_dev[l + 1][rows], np.maximum(z_ref, 0.0) if l < L - 1 else z_ref, f"h^{l + 1} rows")
     note("forward rows checked")
+    if full:
+        # the same forward pass by an oracle run that shares only the seeded inputs with the device (its own CSC,
+        # its own layer inputs); forward values do not depend on how a pre-activation within rounding of 0 is decided
+        indptr, col = orc.csc_build(V, src, dst)
+        h = X
+        rows_i = np.unique(np.random.default_rng(8).integers(0, V, 4096))
+        for l in range(L):
+            a = orc.aggregate(indptr, col, h)
+            assert_close(a_dev[l][rows_i], a[rows_i], f"a^{l} rows, independent pass")
+            z = orc.matmul(a, Ws[l])
+            h = np.maximum(z, 0.0) if l < L - 1 else z
+            assert_close(h_dev[l + 1][rows_i], h[rows_i], f"h^{l + 1} rows, independent pass")
+        loss_ind, _ = orc.softmax_ce(h, y)
+        assert abs(loss - loss_ind) <= 1e-4 * abs(loss_ind), (loss, loss_ind)
+        del indptr, col, a, z, h
+        note("independent forward pass checked")
     loss_ref, g_ref = orc.softmax_ce(h_dev[L], y)
     assert abs(loss - loss_ref) <= 1e-4 * abs(loss_ref)
     assert_close(gh_dev[L][rows], g_ref[rows], "grad h^L rows")
