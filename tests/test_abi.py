@@ -46,3 +46,48 @@ def test_comm_cost_model():
     assert B.ht_comm_cost_model(14, 14, 8, 400, 25e9, 0.0, 1500e9) == pytest.approx(8 * 400 / 25e9 + 6 * 400 / 1500e9)
     assert B.ht_comm_cost_model(14, 11, 12, 400, 25e9, 200e9, 1500e9) == -1.0      # v_ru > v_p2p
     assert B.ht_comm_cost_model(14, 11, 8, 400, 0.0, 200e9, 1500e9) == -1.0        # a needed throughput is missing
+
+
+C_CLIENT = r"""
+#include <stdio.h>
+#include <string.h>
+#include "hongtu.h"
+int main(void) {
+  /* a plain C99 caller: the header alone, no C++ and no torch */
+  int32_t dims[4] = {128, 256, 256, 172};
+  double vb = 0.0, ib = 0.0;
+  if (ht_memory_model(111000000LL, 3, dims, &vb, &ib) != HT_OK) return 1;
+  printf("%.0f %.0f\n", vb, ib);
+  printf("%.6f\n", ht_chunk_rows_model(1000, 10, 2.5));
+  printf("%.9e\n", ht_comm_cost_model(19, 11, 8, 400, 25e9, 200e9, 1500e9));
+  if (strlen(ht_strerror(HT_ENOMEM)) == 0 || strlen(ht_strerror(12345)) == 0) return 2;
+  /* argument errors come back as codes, nothing is dereferenced */
+  if (ht_ctx_set_hbm_budget(NULL, 1) != HT_EINVAL) return 3;
+  if (ht_graph_destroy(NULL) == 12345) return 4;
+  if (ht_ctx_graph_launches(NULL) != -1) return 5;
+  ht_plan_opts p;
+  memset(&p, 0, sizeof p);
+  p.stats_detail = HT_STATS_AGG_FWD;
+  printf("%d %d\n", (int)sizeof(ht_tensor), (int)sizeof p);
+  return 0;
+}
+"""
+
+
+def test_a_c99_program_links_against_the_library(tmp_path):
+    import ctypes as C
+    import subprocess
+    B.load()
+    libdir = os.path.join(ROOT, "paper_2311_14898_amd")
+    src = tmp_path / "client.c"
+    src.write_text(C_CLIENT)
+    exe = tmp_path / "client"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe),
+                    "-L", libdir, "-lhongtu", f"-Wl,-rpath,{libdir}", "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    vb, ib = B.ht_memory_model(111_000_000, [128, 256, 256, 172])
+    assert float(out[0]) == vb and float(out[1]) == ib
+    assert float(out[2]) == pytest.approx(350.0)
+    assert float(out[3]) == pytest.approx(8 * 400 / 25e9 + (19 - 11) * 400 / 200e9 + (11 - 8) * 400 / 1500e9, rel=1e-9)
+    # the binding's ctypes mirrors have the C compiler's sizes
+    assert int(out[4]) == C.sizeof(B.ht_tensor) and int(out[5]) == C.sizeof(B.ht_plan_opts)
