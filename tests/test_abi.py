@@ -91,3 +91,34 @@ def test_a_c99_program_links_against_the_library(tmp_path):
     assert float(out[3]) == pytest.approx(8 * 400 / 25e9 + (19 - 11) * 400 / 200e9 + (11 - 8) * 400 / 1500e9, rel=1e-9)
     # the binding's ctypes mirrors have the C compiler's sizes
     assert int(out[4]) == C.sizeof(B.ht_tensor) and int(out[5]) == C.sizeof(B.ht_plan_opts)
+
+
+def test_no_fallback_when_the_library_is_missing(monkeypatch, tmp_path):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "libhongtu.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        B.load()
+    with pytest.raises(RuntimeError):
+        B.ht_memory_model(10, [4, 4])
+
+
+def test_product_package_and_oracle_do_not_import_each_other():
+    pkg = os.path.join(ROOT, "paper_2311_14898_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle\b", text, flags=re.M), f
+                assert "gcn_oracle" not in text and "orc_" not in text, f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".cpp", ".c", ".h")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "binding" not in text and "hongtu.h" not in text and "libhongtu" not in text, f
+
+
+def test_without_a_gpu_a_context_is_refused():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(B.HongtuError):
+        B.ht_ctx_create(0)
