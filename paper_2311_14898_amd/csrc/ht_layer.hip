@@ -11,6 +11,7 @@
 //            while their vertex stays buffered and leave to the gradient home
 //            (CPU-side add when that home is host memory).
 #include <algorithm>
+#include <atomic>
 #include <cstring>
 #include <condition_variable>
 #include <mutex>
@@ -508,7 +509,8 @@ class AccWorker {
   std::condition_variable cv_;
   std::vector<AccTask> q_;
   int64_t done_ = 0;
-  bool stop_ = false, failed_ = false;
+  bool stop_ = false;
+  std::atomic<bool> failed_{false};   // read by the enqueueing thread without the lock
   double ms_ = 0.0;
 };
 
