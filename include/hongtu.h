@@ -345,14 +345,6 @@ int ht_gat_layer_bwd(ht_ctx *ctx, const ht_graph *g, const ht_gat_desc *desc, co
                      const ht_tensor *dH_out, ht_tensor *dH_in, float *dW, float *da_dst, float *da_src,
                      ht_stats *stats);
 
-/* The two per-vertex halves of the attention scores, p_v = a_dst . t_v and
- * q_u = a_src . t_u, exactly as the layer kernels compute them (same kernels,
- * fp32), copied to the host arrays p_host, q_host [V].  The score of edge
- * (u -> v) is the fp32 sum p_v + q_u; a checker uses this to take LeakyReLU's
- * slope decision for scores within rounding of 0 in the kernels' precision. */
-int ht_gat_scores(ht_ctx *ctx, const ht_graph *g, const ht_gat_desc *desc, const ht_tensor *H_in,
-                  const float *W, const float *a_dst, const float *a_src, float *p_host, float *q_host);
-
 /* where a class of vertex tensors lives (also used by ht_plan_opts below) */
 enum { HT_RES_AUTO = 0, HT_RES_HBM = 1, HT_RES_HOST = 2 };
 typedef struct {

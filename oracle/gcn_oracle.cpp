@@ -494,11 +494,10 @@ double orc_softmax_ce(int64_t V, int64_t C, const double* logits, const int32_t*
 //   gh[l] [V x dims[l+1]]  gradient of the loss w.r.t. h^{l+1}
 //   ga[l] [V x dims[l]]    gradient w.r.t. a^l
 //   gW    concatenated like W;  W_new = W - lr * gW;  *loss.
-// ReLU'(z) = [z > relu_thresh]; the method's value is relu_thresh = 0.  The
-// forward ReLU is always max(z, 0).
+// ReLU'(z) = [z > 0] (Sec. 2.3: 1 for positive inputs and 0 otherwise).
 int orc_gcn_epoch(int64_t V, const int64_t* indptr, const int32_t* col, int L,
                   const int32_t* dims, const float* X, const float* W, const int32_t* labels,
-                  double lr, double relu_thresh, double** a_out, double** z_out, double** h_out,
+                  double lr, double** a_out, double** z_out, double** h_out,
                   double** gh_out, double** ga_out, double* gW_out, double* W_new,
                   double* loss_out) {
   std::vector<double> s(V);
@@ -528,7 +527,7 @@ int orc_gcn_epoch(int64_t V, const int64_t* indptr, const int32_t* col, int L,
     if (gh_out && gh_out[l]) std::memcpy(gh_out[l], gh.data(), sizeof(double) * V * dn);
     std::vector<double> gz(V * dn);
     for (int64_t i = 0; i < V * dn; ++i)
-      gz[i] = (l < L - 1) ? (z[l][i] > relu_thresh ? gh[i] : 0.0) : gh[i];
+      gz[i] = (l < L - 1) ? (z[l][i] > 0.0 ? gh[i] : 0.0) : gh[i];
     std::vector<double> gW(di * dn);
     orc_matmul_tn(V, di, dn, a[l].data(), gz.data(), gW.data());
     std::vector<double> ga(V * di);
@@ -666,13 +665,12 @@ void orc_gat_fwd(int64_t V, const int64_t* indptr, const int32_t* col, int64_t d
 //   LeakyReLU: dy_e = dx_e * (1 if y_e > 0 else slope)
 //   dp_v += dy_e ; dq_u += dy_e ;  dt_v += dp_v a_dst ; dt_u += dq_u a_src
 //   da_dst = sum_v dp_v t_v ; da_src = sum_u dq_u t_u ; dW = H^T dt ; dH = dt W^T
-// dec_p / dec_q (nullable, [V] fp32): see the LeakyReLU step below.
 // Two sweeps so that every loop runs over independent rows: destinations first
 // (d alpha, dy_e, dp_v), then sources over their out-edges in edge order
 // (dt_u, dq_u); the out-edge lists come from a counting sort of the edge ids.
 void orc_gat_bwd(int64_t V, const int64_t* indptr, const int32_t* col, int64_t d_in, int64_t d_out, const double* H,
                  const double* W, const double* a_dst, const double* a_src, double slope, int relu, const double* T,
-                 const double* alpha, const double* Z, const double* dOut, const float* dec_p, const float* dec_q,
+                 const double* alpha, const double* Z, const double* dOut,
                  double* dH, double* dW, double* da_dst, double* da_src) {
   const int64_t E = indptr[V];
   std::vector<double> p(V), q(V), dp(V, 0.0), dq(V, 0.0), dT((size_t)V * d_out, 0.0), dy((size_t)E);
@@ -701,10 +699,7 @@ void orc_gat_bwd(int64_t V, const int64_t* indptr, const int32_t* col, int64_t d
     for (int64_t e = e0; e < e1; ++e) {
       const double dx = alpha[e] * (dy[e] - S);
       const double y = p[v] + q[col[e]];
-      // which slope: the sign of y; or, when a checker supplies fp32 halves of the score, the sign of
-      // their fp32 sum (an fp32 implementation's decision for scores within rounding of 0)
-      const bool pos = dec_p ? (float)(dec_p[v] + dec_q[col[e]]) > 0.f : y > 0.0;
-      dy[e] = dx * (pos ? 1.0 : slope);
+      dy[e] = dx * (y > 0.0 ? 1.0 : slope);
       acc += dy[e];
     }
     dp[v] = acc;

@@ -207,7 +207,7 @@ def softmax_ce(logits, labels) -> Tuple[float, np.ndarray]:
 
 
 def gcn_epoch(indptr, col, dims: Sequence[int], X, Ws: Sequence[np.ndarray], labels, lr: float = 0.01,
-              relu_thresh: float = 0.0, want: Sequence[str] = ("a", "z", "h", "gh", "ga")) -> Dict[str, object]:
+              want: Sequence[str] = ("a", "z", "h", "gh", "ga")) -> Dict[str, object]:
     """One epoch on the whole graph.  Returns loss, gW (list), W_new (list) and the
     per-layer arrays named in `want` (lists indexed by layer l)."""
     L = len(dims) - 1
@@ -230,7 +230,7 @@ def gcn_epoch(indptr, col, dims: Sequence[int], X, Ws: Sequence[np.ndarray], lab
     Wn = np.zeros(Wcat.shape[0], dtype=np.float64)
     loss = C.c_double(0.0)
     rc = lib().orc_gcn_epoch(C.c_int64(V), _p(indptr), _p(col), C.c_int(L), _p(dims_a), _p(X), _p(Wcat),
-                             _p(labels), C.c_double(lr), C.c_double(relu_thresh), ptr_arrays["a"],
+                             _p(labels), C.c_double(lr), ptr_arrays["a"],
                              ptr_arrays["z"], ptr_arrays["h"], ptr_arrays["gh"], ptr_arrays["ga"], _p(gW),
                              _p(Wn), C.byref(loss))
     assert rc == 0
@@ -284,22 +284,15 @@ def gat_layer_fwd(indptr, col, H, W, a_dst, a_src, slope: float = 0.2, relu: boo
 
 
 def gat_layer_bwd(indptr, col, H, W, a_dst, a_src, fwd: Dict[str, np.ndarray], dh, slope: float = 0.2,
-                  relu: bool = True, want_dH: bool = True, decide_pq=None) -> Dict[str, np.ndarray]:
-    """Gradients of the layer above given dh = grad h; `fwd` is gat_layer_fwd's result.
-    decide_pq = (p32, q32), fp32 [V] each: take every edge's LeakyReLU slope from the sign of the fp32
-    sum p32[v] + q32[u] instead of the fp64 score (ties within fp32 rounding of 0)."""
+                  relu: bool = True, want_dH: bool = True) -> Dict[str, np.ndarray]:
+    """Gradients of the layer above given dh = grad h; `fwd` is gat_layer_fwd's result."""
     H, W, a_dst, a_src, dh = _f64(H), _f64(W), _f64(a_dst), _f64(a_src), _f64(dh)
     V, d_in = H.shape
     d_out = W.shape[1]
     indptr, col = _i64(indptr), _i32(col)
     out = {"dH": np.zeros((V, d_in)) if want_dH else None, "dW": np.zeros((d_in, d_out)), "da_dst": np.zeros(d_out),
            "da_src": np.zeros(d_out)}
-    dp32 = dq32 = None
-    if decide_pq is not None:
-        dp32 = np.ascontiguousarray(decide_pq[0], dtype=np.float32)
-        dq32 = np.ascontiguousarray(decide_pq[1], dtype=np.float32)
-        assert dp32.shape == (V,) and dq32.shape == (V,)
     lib().orc_gat_bwd(C.c_int64(V), _p(indptr), _p(col), C.c_int64(d_in), C.c_int64(d_out), _p(H), _p(W), _p(a_dst),
                       _p(a_src), C.c_double(slope), C.c_int(int(relu)), _p(fwd["t"]), _p(fwd["alpha"]), _p(fwd["z"]),
-                      _p(dh), _p(dp32), _p(dq32), _p(out["dH"]), _p(out["dW"]), _p(out["da_dst"]), _p(out["da_src"]))
+                      _p(dh), _p(out["dH"]), _p(out["dW"]), _p(out["da_dst"]), _p(out["da_src"]))
     return out

@@ -114,12 +114,12 @@ int main() {
     }
     std::vector<double> gW(W.size()), Wn(W.size());
     double loss = 0.0;
-    need(orc_gcn_epoch(V, indptr.data(), col.data(), L, dims, X.data(), W.data(), labels.data(), 0.01, 0.0, ap.data(),
+    need(orc_gcn_epoch(V, indptr.data(), col.data(), L, dims, X.data(), W.data(), labels.data(), 0.01, ap.data(),
                        zp.data(), hp.data(), ghp.data(), gap.data(), gW.data(), Wn.data(), &loss) == 0,
          "gcn epoch");
     need(std::isfinite(loss) && finite_all(gW) && finite_all(Wn), "gcn epoch is finite");
     // and without the optional outputs
-    need(orc_gcn_epoch(V, indptr.data(), col.data(), L, dims, X.data(), W.data(), labels.data(), 0.01, 0.0, nullptr,
+    need(orc_gcn_epoch(V, indptr.data(), col.data(), L, dims, X.data(), W.data(), labels.data(), 0.01, nullptr,
                        nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr) == 0,
          "gcn epoch without outputs");
 
@@ -136,7 +136,7 @@ int main() {
       orc_gat_fwd(V, indptr.data(), col.data(), di, dn, H.data(), Wg.data(), ad.data(), as.data(), 0.2, relu, T.data(),
                   alpha.data(), Z.data(), out.data());
       orc_gat_bwd(V, indptr.data(), col.data(), di, dn, H.data(), Wg.data(), ad.data(), as.data(), 0.2, relu, T.data(),
-                  alpha.data(), Z.data(), dOut.data(), nullptr, nullptr, dH.data(), dW.data(), dad.data(), das.data());
+                  alpha.data(), Z.data(), dOut.data(), dH.data(), dW.data(), dad.data(), das.data());
       need(finite_all(out) && finite_all(dH) && finite_all(dW) && finite_all(dad) && finite_all(das), "GAT layer is finite");
     }
   }

@@ -113,7 +113,7 @@ class ht_plan_opts(C.Structure):
 EXPORTS = ["ht_ctx_create", "ht_ctx_destroy", "ht_sync", "ht_ctx_set_hbm_budget", "ht_ctx_graph_launches", "ht_tensor_zero", "ht_strerror", "ht_last_error",
            "ht_partition", "ht_graph_destroy", "ht_graph_info_get", "ht_graph_chunk_info", "ht_graph_export_chunk",
            "ht_graph_export_csc", "ht_graph_chunk_order", "ht_graph_reorganize", "ht_layer_fwd", "ht_layer_bwd", "ht_epoch", "ht_epoch_buffer", "ht_tensor_to_host", "ht_memory_model",
-           "ht_chunk_rows_model", "ht_gat_layer_fwd", "ht_gat_layer_bwd", "ht_gat_epoch", "ht_gat_scores", "ht_comm_cost_model"]
+           "ht_chunk_rows_model", "ht_gat_layer_fwd", "ht_gat_layer_bwd", "ht_gat_epoch", "ht_comm_cost_model"]
 
 _lib = None
 
@@ -172,8 +172,6 @@ def load():
     lib.ht_gat_layer_bwd.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(ht_gat_desc), C.POINTER(ht_tensor), C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.POINTER(ht_tensor), C.POINTER(ht_tensor),
                                      C.POINTER(ht_tensor), C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(ht_stats)]
-    lib.ht_gat_scores.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(ht_gat_desc), C.POINTER(ht_tensor), C.c_void_p,
-                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.ht_gat_epoch.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(ht_gat_model), C.POINTER(ht_tensor), C.c_void_p,
                                  C.POINTER(C.c_float), C.POINTER(ht_stats)]
     _lib = lib
@@ -394,20 +392,6 @@ def ht_gat_layer_bwd(ctx, g, d_in: int, d_out: int, act: int, H_in: torch.Tensor
 
 def ht_comm_cost_model(v_ori: int, v_p2p: int, v_ru: int, bytes_per_row: int, t_hd: float, t_dd: float, t_ru: float) -> float:
     return float(load().ht_comm_cost_model(v_ori, v_p2p, v_ru, bytes_per_row, t_hd, t_dd, t_ru))
-
-
-def ht_gat_scores(ctx, g, d_in: int, d_out: int, H_in: torch.Tensor, W: torch.Tensor, a_dst: torch.Tensor,
-                  a_src: torch.Tensor, slope: float = 0.2):
-    """(p, q): the per-vertex halves of the attention scores as the kernels compute them, numpy fp32 [V]."""
-    import numpy as np
-    desc = ht_gat_desc(d_in, d_out, HT_ACT_NONE, slope)
-    hin = tensor_view(H_in, d_in)
-    V = H_in.shape[0]
-    p, q = np.empty(V, np.float32), np.empty(V, np.float32)
-    torch.cuda.synchronize()
-    _check(load().ht_gat_scores(ctx, g, C.byref(desc), C.byref(hin), C.c_void_p(W.data_ptr()), _vec(a_dst, d_out),
-                                _vec(a_src, d_out), p.ctypes.data_as(C.c_void_p), q.ctypes.data_as(C.c_void_p)), ctx)
-    return p, q
 
 
 def ht_gat_epoch(ctx, g, dims: Sequence[int], Ws: List[torch.Tensor], a_dst: List[torch.Tensor], a_src: List[torch.Tensor],

@@ -924,29 +924,6 @@ int ht_gat_layer_bwd(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, co
   return HT_OK;
 }
 
-int ht_gat_scores(ht_ctx* ctx, const ht_graph* g, const ht_gat_desc* desc, const ht_tensor* H_in, const float* W,
-                  const float* a_dst, const float* a_src, float* p_host, float* q_host) {
-  if (!ctx) return HT_EINVAL;
-  if (!g || !desc || !H_in || !W || !a_dst || !a_src || !p_host || !q_host)
-    return ht_set_err(ctx, HT_EINVAL, "ht_gat_scores: null argument");
-  if (g->ctx != ctx) return ht_set_err(ctx, HT_ESTATE, "graph belongs to another context");
-  HT_TRY(check_desc(ctx, desc));
-  HT_TRY(check(ctx, g, desc, H_in, desc->d_in, "H_in"));
-  HT_HIP(ctx, hipSetDevice(ctx->device));
-  ht_stats local{};
-  Timer tm(ctx, ctx->stream, false);
-  GatWs ws{};
-  Link lk(ctx, &local, &tm);
-  if (on_host(H_in)) HT_TRY(lk.fork());
-  HT_TRY(prepare(ctx, g, desc, H_in, W, a_dst, a_src, false, &ws, &local, &tm, &lk));
-  HT_HIP(ctx, hipStreamSynchronize(ctx->stream));
-  if (g->V > 0) {
-    HT_HIP(ctx, hipMemcpy(p_host, ws.p, (size_t)g->V * 4, hipMemcpyDeviceToHost));
-    HT_HIP(ctx, hipMemcpy(q_host, ws.q, (size_t)g->V * 4, hipMemcpyDeviceToHost));
-  }
-  return HT_OK;
-}
-
 // Alg. 1 with GAT layers: forward over the layers (only the layer outputs are kept), softmax
 // cross-entropy on the labelled vertices, backward layer by layer with every layer's
 // intermediates recomputed from its input, SGD step on W^l and a^l.  With res_h = HT_RES_HOST

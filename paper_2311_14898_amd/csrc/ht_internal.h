@@ -57,7 +57,7 @@ struct ht_ctx {
   int agg_phases = 1;     // HT_AGG_PHASES: slabs are spread over this many consecutive launches
   int64_t link_block_rows = (int64_t)1 << 20;   // HT_LINK_BLOCK_ROWS: rows per staged block of a host-resident tensor (GAT path)
   int agg_variant = 0;  // 0: feature slabs per XCD; 1: full-width rows per wave (HT_AGG_VARIANT, for A/B runs)
-  int n_threads = 0;  // host threads for CPU-side accumulation (0 = decide on first use)
+  int n_threads = 0;  // host threads for CPU-side accumulation (0 = chosen on first use)
 };
 
 int ht_set_err(ht_ctx* ctx, int code, const char* fmt, ...);

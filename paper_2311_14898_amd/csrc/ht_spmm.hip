@@ -291,6 +291,18 @@ __global__ void __launch_bounds__(256) k_copy16(const float4* __restrict__ src, 
 
 int lanes_for(int nvec) { return nvec <= 8 ? 8 : nvec <= 16 ? 16 : nvec <= 32 ? 32 : 64; }
 
+// Grid of a row kernel: one lane group per row, at most `cap` blocks (k_rows strides over the rest).  A launch of
+// 2^32 threads or more is not rejected, its excess is silently dropped, so the grid is bounded whatever n_rows is.
+constexpr int64_t HT_ROW_GRID_MAX = 1 << 20;
+constexpr int64_t row_blocks(int64_t n_rows, int rows_per_block, int64_t cap) {
+  const int64_t want = (n_rows + rows_per_block - 1) / rows_per_block;
+  const int64_t lim = (cap > 0 && cap < HT_ROW_GRID_MAX) ? cap : HT_ROW_GRID_MAX;
+  return want < lim ? want : lim;
+}
+static_assert(row_blocks(1ll << 26, 4, 0) * 256 < (1ll << 32), "a row launch must stay below 2^32 threads");
+static_assert(row_blocks(111'000'000ll, 4, 0) == HT_ROW_GRID_MAX && row_blocks(int64_t(1) << 40, 1, 0) == HT_ROW_GRID_MAX, "");
+static_assert(row_blocks(1000, 4, 64) == 64 && row_blocks(100, 4, 64) == 25 && row_blocks(5, 4, 0) == 2, "");
+
 }  // namespace
 
 int ht_spmm_launch(ht_ctx* ctx, hipStream_t st, const SpmmArgs& a0) {
@@ -375,8 +387,7 @@ int ht_gather_rows(ht_ctx* ctx, hipStream_t st, const float* src, int64_t src_ld
   const int d4 = (d + 3) & ~3;
   const int lpr = lanes_for(d4 / 4);
   const int rpb = 256 / lpr;
-  int64_t blocks = (n_rows + rpb - 1) / rpb;
-  if (max_blocks > 0 && blocks > max_blocks) blocks = max_blocks;
+  const int64_t blocks = row_blocks(n_rows, rpb, max_blocks);
   k_rows<0><<<(unsigned)blocks, 256, 0, st>>>(src, src_ld, src_idx, dst, dst_ld, dst_idx, n_rows, d4, lpr, scale);
   HT_LAUNCH_CHECK(ctx);
   return HT_OK;
@@ -388,7 +399,7 @@ int ht_add_rows(ht_ctx* ctx, hipStream_t st, const float* src, int64_t src_ld, c
   const int d4 = (d + 3) & ~3;
   const int lpr = lanes_for(d4 / 4);
   const int rpb = 256 / lpr;
-  k_rows<1><<<(unsigned)((n_rows + rpb - 1) / rpb), 256, 0, st>>>(src, src_ld, src_idx, dst, dst_ld, dst_idx, n_rows,
+  k_rows<1><<<(unsigned)row_blocks(n_rows, rpb, 0), 256, 0, st>>>(src, src_ld, src_idx, dst, dst_ld, dst_idx, n_rows,
                                                                 d4, lpr, nullptr);
   HT_LAUNCH_CHECK(ctx);
   return HT_OK;

@@ -169,7 +169,7 @@ def test_forward_and_loss_against_an_independent_oracle_pass(run):
     """The checks above feed each oracle step with the device's own input of that step.  This one shares nothing with
     the device but the seeded inputs: the oracle builds its own CSC from the edge list and runs the whole forward
     pass in fp64; the loss and sampled rows of every layer output must agree.  (Forward values do not depend on how a
-    pre-activation within rounding of zero is decided; the backward pass does, hence the step-wise checks above.)"""
+    pre-activation within rounding of zero is resolved; the backward pass does, hence the step-wise checks above.)"""
     w, ctx = run["w"], run["ctx"]
     L = w.n_layers
     indptr, col = orc.csc_build(w.V, run["src"], run["dst"])

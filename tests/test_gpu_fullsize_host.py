@@ -88,7 +88,7 @@ def test_cfg3_host_resident_epoch(data, cache_rows):
     note("forward rows checked")
     if full:
         # the same forward pass by an oracle run that shares only the seeded inputs with the device (its own CSC,
-        # its own layer inputs); forward values do not depend on how a pre-activation within rounding of 0 is decided
+        # its own layer inputs); forward values do not depend on how a pre-activation within rounding of 0 is resolved
         indptr, col = orc.csc_build(V, src, dst)
         h = X
         rows_i = np.unique(np.random.default_rng(8).integers(0, V, 4096))

@@ -278,9 +278,6 @@ def test_tensors_of_more_than_2_to_32_words():
                 ref = torch.relu(H[r0:r0 + 1_000_000].double() @ W.double())
                 got = out[r0:r0 + 1_000_000, :d_out].double()
                 assert float((got - ref).abs().max()) <= 1e-5 * float(ref.abs().max())
-            p, q = B.ht_gat_scores(ctx, g, d_in, d_out, H, W, a, a)
-            t_tail = (H[V - 1000:].double() @ W.double()).cpu().numpy()
-            assert np.abs(p[V - 1000:] - 0.3 * t_tail.sum(axis=1)).max() <= 1e-5
         finally:
             B.ht_graph_destroy(g)
     finally:

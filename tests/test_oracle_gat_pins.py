@@ -116,20 +116,3 @@ def test_softmax_invariances():
     # huge scores do not overflow
     big = orc.gat_layer_fwd(indptr, col, 1e3 * H, W, a_dst, a_src, relu=False)
     assert np.isfinite(big["z"]).all()
-
-
-def test_decision_override_only_moves_ties():
-    indptr, col, H, W, a_dst, a_src, _ = case(seed=8)
-    rng = np.random.default_rng(2)
-    dh = rng.standard_normal((H.shape[0], W.shape[1]))
-    f = orc.gat_layer_fwd(indptr, col, H, W, a_dst, a_src)
-    base = orc.gat_layer_bwd(indptr, col, H, W, a_dst, a_src, f, dh)
-    p, q = f["t"] @ a_dst, f["t"] @ a_src
-    same = orc.gat_layer_bwd(indptr, col, H, W, a_dst, a_src, f, dh, decide_pq=(p, q))       # fp32 halves, no tie here
-    dst_of = np.repeat(np.arange(len(indptr) - 1), np.diff(indptr))
-    assert np.abs(p[dst_of] + q[col]).min() > 1e-4
-    for k in ("dH", "dW", "da_dst", "da_src"):
-        np.testing.assert_array_equal(base[k], same[k])
-    # all-negative decisions = slope everywhere = the gradient of the layer with a linear score scaled by slope
-    neg = orc.gat_layer_bwd(indptr, col, H, W, a_dst, a_src, f, dh, decide_pq=(-np.ones_like(p), np.zeros_like(q)))
-    assert not np.allclose(neg["da_dst"], base["da_dst"])

@@ -21,10 +21,47 @@ def rel_errors(x, ref):
     return (dmax / rmax if rmax > 0 else dmax), (dfro / rfro if rfro > 0 else dfro)
 
 
-def assert_close(x, ref, name="", tol=TOL):
+def row_errors(x, ref):
+    """Per-row check for 2-D tensors: every row v must satisfy
+    ||x_v - ref_v||_2 <= TOL * max(||ref_v||_2, 1e-3 * median_v ||ref_v||_2)
+    (the floor keeps rows that are zero, or nearly so, from demanding exact zeros' worth of precision; the median is
+    taken over the rows that are not exactly zero).  Returns (worst ratio error/allowance-per-TOL, its row)."""
+    x = np.asarray(x, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if ref.ndim != 2 or ref.shape[0] == 0:
+        return 0.0, -1
+    rn = np.sqrt((ref * ref).sum(axis=1))
+    en = np.sqrt(((x - ref) ** 2).sum(axis=1))
+    nz = rn[rn > 0]
+    floor = 1e-3 * (np.median(nz) if nz.size else 0.0)
+    allow = np.maximum(rn, floor)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        ratio = np.where(allow > 0, en / allow, np.where(en > 0, np.inf, 0.0))
+    v = int(np.argmax(ratio))
+    return float(ratio[v]), v
+
+
+def assert_close(x, ref, name="", tol=TOL, rows=True):
     emax, efro = rel_errors(x, ref)
     assert emax <= tol and efro <= tol, f"{name}: max-norm rel err {emax:.3e}, Frobenius rel err {efro:.3e} > {tol}"
+    if rows:
+        erow, v = row_errors(x, ref)
+        assert erow <= tol, (f"{name}: row {v} is off by {erow:.3e} of its own norm (allowed {tol}); "
+                             f"||ref_v|| = {np.linalg.norm(np.asarray(ref, dtype=np.float64)[v]):.3e}")
     return emax, efro
+
+
+def assert_in_interval(x, base, lo_slack, hi_slack, name="", tol=TOL):
+    """x must lie in [base + lo_slack, base + hi_slack] (lo_slack <= 0 <= hi_slack, element-wise: what the
+    undecidable decisions can move) widened by the per-tensor tolerances of assert_close: the part of x - base
+    outside the slack is held to the max-norm and Frobenius bounds, and row by row to the per-row bound."""
+    x = np.asarray(x, dtype=np.float64)
+    base = np.asarray(base, dtype=np.float64)
+    assert x.shape == base.shape and np.isfinite(x).all()
+    assert (np.asarray(lo_slack) <= 0).all() and (np.asarray(hi_slack) >= 0).all()
+    err = x - base
+    excess = np.maximum(err - hi_slack, 0.0) + np.minimum(err - lo_slack, 0.0)   # distance to the interval, signed
+    return assert_close(base + excess, base, name, tol)
 
 
 def relu_margin(z, rel=1e-6):
