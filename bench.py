@@ -188,6 +188,20 @@ def read_traffic(name):
     return None
 
 
+def epoch_plan(B, w, residency="workload", hbm_budget_gb=0.0, inter="auto"):
+    """(X in pinned host memory?, keyword arguments of ht_epoch) for a workload.  residency "workload": as the
+    workload says ("host": h^l and grad h^l in pinned host memory; "host_all": the checkpoints a^l too); "auto":
+    wherever the planner's byte budget puts them; "h-host": h^l in pinned host memory, the rest by the planner."""
+    host = w.residency in ("host", "host_all") and residency == "workload"
+    res = B.HT_RES_HOST if host else B.HT_RES_AUTO
+    plan = dict(res_h=res, res_g=res, res_a=B.HT_RES_HOST if (host and w.residency == "host_all") else B.HT_RES_AUTO)
+    if residency == "h-host":
+        plan = dict(res_h=B.HT_RES_HOST, res_g=B.HT_RES_AUTO, res_a=B.HT_RES_AUTO)
+    plan["hbm_budget_bytes"] = int(hbm_budget_gb * 1e9)
+    plan["inter"] = {"auto": B.HT_INTER_AUTO, "hybrid": B.HT_INTER_HYBRID, "recompute": B.HT_INTER_RECOMPUTE}[inter]
+    return host, plan
+
+
 def plan_partitions(ctx, w, src, dst, m):
     """Alg. 4 and the volumes of Sec. 5.3 for m partitions of the workload's chunk count each; a planning result
     computed on this one GPU (Table 7's quantities on the stand-in graph).  Outside the timed region."""
@@ -272,7 +286,7 @@ def main():
     w = inputs.WORKLOADS[args.workload].scaled(args.scale)
     if args.chunks > 0:
         w.n_chunks = args.chunks
-    host = w.residency in ("host", "host_all") and args.residency == "workload"
+    host = epoch_plan(B, w, args.residency)[0]
     t_gen = time.perf_counter()
     src, dst = inputs.rmat_edges(w.V, w.E, w.graph_seed, device="cuda")
     if args.permute_ids:
@@ -299,13 +313,7 @@ def main():
     Xd = B.to_matrix(X, B.HT_LOC_HOST_PINNED if host else B.HT_LOC_DEVICE)
     yd = y.cuda()
     Wd = [x.clone().cuda() for x in Ws]
-    res = B.HT_RES_HOST if host else B.HT_RES_AUTO
-    # "host": vertex data (h^l, grad h^l) in pinned host memory; "host_all": the checkpoints a^l too
-    plan = dict(res_h=res, res_g=res, res_a=B.HT_RES_HOST if (host and w.residency == "host_all") else B.HT_RES_AUTO)
-    if args.residency == "h-host":
-        plan = dict(res_h=B.HT_RES_HOST, res_g=B.HT_RES_AUTO, res_a=B.HT_RES_AUTO)
-    plan["hbm_budget_bytes"] = int(args.hbm_budget_gb * 1e9)
-    plan["inter"] = {"auto": B.HT_INTER_AUTO, "hybrid": B.HT_INTER_HYBRID, "recompute": B.HT_INTER_RECOMPUTE}[args.inter]
+    plan = epoch_plan(B, w, args.residency, args.hbm_budget_gb, args.inter)[1]
 
     if args.calib_copy:
         a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()

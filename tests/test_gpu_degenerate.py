@@ -7,7 +7,7 @@ import torch
 
 from oracle import oracle as orc
 from paper_2311_14898_amd import binding as B
-from tests.util import assert_close
+from tests.util import assert_close, assert_close_grad
 
 pytestmark = pytest.mark.gpu
 DEV = B.HT_LOC_DEVICE
@@ -57,7 +57,7 @@ def test_gcn_layer_and_epoch(ctx, case):
                 for l in range(2):
                     # rows without in-edges are exactly zero; ReLU ties at 0 do not matter for zero rows
                     assert_close(B.ht_epoch_buffer(ctx, B.HT_BUF_H, l + 1).numpy(), ref["h"][l], f"h^{l + 1}")
-                    assert_close(Wd[l].cpu().numpy(), ref["W_new"][l], f"W^{l}")
+                    assert_close_grad(Wd[l].cpu().numpy(), ref["W_new"][l], f"W^{l}")
     finally:
         B.ht_graph_destroy(g)
 
@@ -85,10 +85,10 @@ def test_gat_layer(ctx, case):
         dad, das = torch.empty(d_out, device="cuda"), torch.empty(d_out, device="cuda")
         dH_in = B.alloc_matrix(V, d_in, DEV)
         B.ht_gat_layer_bwd(ctx, g, d_in, d_out, B.HT_ACT_NONE, Hd, Wd, ad, as_, H_out, _mat(dh), dW, dad, das, dH_in=dH_in)
-        assert_close(dW.cpu().numpy(), b["dW"], "dW")
+        assert_close_grad(dW.cpu().numpy(), b["dW"], "dW")
         # the two halves of a^l as one vector: on a graph whose scores all have one sign the destination
         # half's gradient is exactly 0 (the softmax does not see p_v), and a relative error needs a scale
-        assert_close(np.concatenate([dad.cpu().numpy(), das.cpu().numpy()]), np.concatenate([b["da_dst"], b["da_src"]]), "da")
-        assert_close(dH_in.cpu().numpy()[:, :d_in], b["dH"], "dH_in")
+        assert_close_grad(np.concatenate([dad.cpu().numpy(), das.cpu().numpy()]), np.concatenate([b["da_dst"], b["da_src"]]), "da")
+        assert_close_grad(dH_in.cpu().numpy()[:, :d_in], b["dH"], "dH_in")
     finally:
         B.ht_graph_destroy(g)

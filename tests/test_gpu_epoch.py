@@ -6,7 +6,7 @@ import torch
 from oracle import oracle as orc
 from paper_2311_14898_amd import binding as B
 from paper_2311_14898_amd import inputs
-from tests.util import assert_close
+from tests.util import assert_close, assert_close_grad
 
 pytestmark = pytest.mark.gpu
 
@@ -50,9 +50,9 @@ def compare(out, ref, L):
         if out["a"][l] is not None:
             assert_close(out["a"][l], ref["a"][l], f"a^{l}")
         assert_close(out["h"][l], ref["h"][l], f"h^{l + 1}")
-        assert_close(out["gh"][l], ref["gh"][l], f"grad h^{l + 1}")
-        assert_close(out["gW"][l], ref["gW"][l], f"grad W^{l}")
-        assert_close(out["W_new"][l], ref["W_new"][l], f"W^{l} after the step")
+        assert_close_grad(out["gh"][l], ref["gh"][l], f"grad h^{l + 1}")
+        assert_close_grad(out["gW"][l], ref["gW"][l], f"grad W^{l}")
+        assert_close_grad(out["W_new"][l], ref["W_new"][l], f"W^{l} after the step")
 
 
 @pytest.fixture(scope="module")
@@ -202,7 +202,7 @@ def test_input_aggregate_reused_across_epochs(ctx, cfg1):
                 indptr, col = orc.csc_build(w.V, src.numpy(), dst.numpy())
                 W2 = orc.gcn_epoch(indptr, col, w.dims, X.numpy(), ref["W_new"], y.numpy(), lr=w.lr)["W_new"]
                 for l in range(L):
-                    assert_close(Wd[l].cpu().numpy(), W2[l], f"W^{l} after two epochs")
+                    assert_close_grad(Wd[l].cpu().numpy(), W2[l], f"W^{l} after two epochs")
         finally:
             B.ht_graph_destroy(g)
 
@@ -469,7 +469,7 @@ def test_contexts_on_caller_streams(cfg1):
             assert abs(l2 - ref["loss"]) <= 1e-4 * abs(ref["loss"])
             for l in range(w.n_layers):
                 assert np.array_equal(W1[l].cpu().numpy(), lone["W_new"][l])
-                assert_close(W2[l].cpu().numpy(), ref["W_new"][l], f"W^{l} on the second stream")
+                assert_close_grad(W2[l].cpu().numpy(), ref["W_new"][l], f"W^{l} on the second stream")
             with pytest.raises(B.HongtuError):      # a graph belongs to the context that made it
                 B.ht_epoch(c2, g1, w.dims, W2, w.lr, X1, yd)
         finally:

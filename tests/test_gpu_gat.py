@@ -6,7 +6,7 @@ import torch
 from oracle import oracle as orc
 from paper_2311_14898_amd import binding as B
 from paper_2311_14898_amd import inputs
-from tests.util import assert_close, hub_graph
+from tests.util import assert_close, assert_close_grad, hub_graph
 
 pytestmark = pytest.mark.gpu
 DEV = B.HT_LOC_DEVICE
@@ -79,12 +79,12 @@ def _run(ctx, case, d_in, d_out, relu, seed, want_dhin=True, slope=0.2, host=())
             dH_in[:, :d_in] = torch.from_numpy(base)
     B.ht_gat_layer_bwd(ctx, case.g, d_in, d_out, act, Hd, Wd, ad, as_, mat(f["h"], "H_out"), mat(dh, "dH_out"), dW, dad, das,
                        dH_in=dH_in, slope=slope)
-    assert_close(dW.cpu().numpy(), b["dW"], "dW")
-    assert_close(dad.cpu().numpy(), b["da_dst"], "da_dst")
-    assert_close(das.cpu().numpy(), b["da_src"], "da_src")
+    assert_close_grad(dW.cpu().numpy(), b["dW"], "dW")
+    assert_close_grad(dad.cpu().numpy(), b["da_dst"], "da_dst")
+    assert_close_grad(das.cpu().numpy(), b["da_src"], "da_src")
     if want_dhin:
         got = dH_in.cpu().numpy()[:, :d_in].astype(np.float64)
-        assert_close(got - (base if host else 0.0), b["dH"], "dH_in")
+        assert_close_grad(got - (base if host else 0.0), b["dH"], "dH_in")
     return H_out, dW
 
 
@@ -192,9 +192,9 @@ def test_gat_epoch(ctx, cases):
     loss, st = B.ht_gat_epoch(ctx, c.g, dims, Wd, add, asd, lr, _mat(X), torch.from_numpy(y).cuda(), want_stats=True)
     assert abs(loss - loss_ref) <= 1e-4 * abs(loss_ref)
     for l, b in ((0, b0), (1, b1)):
-        assert_close(Wd[l].cpu().numpy(), Ws[l].astype(np.float64) - lr * b["dW"], f"W^{l} after the step")
-        assert_close(add[l].cpu().numpy(), ad[l].astype(np.float64) - lr * b["da_dst"], f"a_dst^{l} after the step")
-        assert_close(asd[l].cpu().numpy(), as_[l].astype(np.float64) - lr * b["da_src"], f"a_src^{l} after the step")
+        assert_close_grad(Wd[l].cpu().numpy(), Ws[l].astype(np.float64) - lr * b["dW"], f"W^{l} after the step")
+        assert_close_grad(add[l].cpu().numpy(), ad[l].astype(np.float64) - lr * b["da_dst"], f"a_dst^{l} after the step")
+        assert_close_grad(asd[l].cpu().numpy(), as_[l].astype(np.float64) - lr * b["da_src"], f"a_src^{l} after the step")
         assert np.abs(lr * b["dW"]).max() > 0.05 * np.abs(Ws[l]).max()      # the step is visible at the tolerance
     assert st.edges == len(c.col) * (2 + 4)     # 2 forward aggregations, 2 x 2 backward passes
     # small steps from the same start: the loss goes down
@@ -212,8 +212,8 @@ def test_gat_epoch(ctx, cases):
                                 res_h=B.HT_RES_HOST)
     assert abs(loss_h - loss_ref) <= 1e-4 * abs(loss_ref)
     for l, b in ((0, b0), (1, b1)):
-        assert_close(Wd[l].cpu().numpy(), Ws[l].astype(np.float64) - lr * b["dW"], f"W^{l} after the step (host)")
-        assert_close(add[l].cpu().numpy(), ad[l].astype(np.float64) - lr * b["da_dst"], f"a_dst^{l} after the step (host)")
+        assert_close_grad(Wd[l].cpu().numpy(), Ws[l].astype(np.float64) - lr * b["dW"], f"W^{l} after the step (host)")
+        assert_close_grad(add[l].cpu().numpy(), ad[l].astype(np.float64) - lr * b["da_dst"], f"a_dst^{l} after the step (host)")
     # link traffic, all in contiguous row ranges: X three times (t forward, t again and dW backward); h^1 out once and in
     # four times (t and dW of layer 1, forward and backward; as H_out of layer 0's backward); grad h^1 out and in once
     ld0, ld1 = B.pad_ld(dims[0], B.HT_LOC_HOST_PINNED), B.pad_ld(dims[1], B.HT_LOC_HOST_PINNED)

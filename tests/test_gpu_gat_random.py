@@ -7,7 +7,7 @@ import torch
 from oracle import oracle as orc
 from paper_2311_14898_amd import binding as B
 from paper_2311_14898_amd import inputs
-from tests.util import assert_close
+from tests.util import assert_close, assert_close_grad
 
 pytestmark = pytest.mark.gpu
 N_CASES = 20
@@ -94,9 +94,9 @@ def test_random_gat_epoch(ctx, seed):
                                  res_h=B.HT_RES_HOST if c["host_h"] else B.HT_RES_AUTO)
         assert abs(loss - loss_ref) <= 1e-4 * abs(loss_ref), (loss, loss_ref)
         for l in range(L):
-            assert_close(Wd[l].cpu().numpy(), Ws[l].astype(np.float64) - lr * b[l]["dW"], f"W^{l} after the step")
-            assert_close(add[l].cpu().numpy(), ad[l].astype(np.float64) - lr * b[l]["da_dst"], f"a_dst^{l} after the step")
-            assert_close(asd[l].cpu().numpy(), as_[l].astype(np.float64) - lr * b[l]["da_src"], f"a_src^{l} after the step")
+            assert_close_grad(Wd[l].cpu().numpy(), Ws[l].astype(np.float64) - lr * b[l]["dW"], f"W^{l} after the step")
+            assert_close_grad(add[l].cpu().numpy(), ad[l].astype(np.float64) - lr * b[l]["da_dst"], f"a_dst^{l} after the step")
+            assert_close_grad(asd[l].cpu().numpy(), as_[l].astype(np.float64) - lr * b[l]["da_src"], f"a_src^{l} after the step")
     finally:
         B.ht_graph_destroy(g)
         torch.cuda.synchronize()

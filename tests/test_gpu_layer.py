@@ -6,7 +6,7 @@ import torch
 from oracle import oracle as orc
 from paper_2311_14898_amd import binding as B
 from paper_2311_14898_amd import inputs
-from tests.util import assert_close, hub_graph, relu_margin
+from tests.util import assert_close, assert_close_grad, hub_graph, relu_margin
 
 pytestmark = pytest.mark.gpu
 DEV, HOST = B.HT_LOC_DEVICE, B.HT_LOC_HOST_PINNED
@@ -193,9 +193,9 @@ def _bwd(ctx, case, d_in, d_out, relu, loc, gather, mask_from_h, ckpt_input=Fals
                    dH_in=dH_in, H_out=H_out, ckpt_kind=B.HT_CKPT_INPUT if ckpt_input else B.HT_CKPT_AGG,
                    gather_mode=gather, order=order)
     B.ht_sync(ctx)
-    assert_close(dW.cpu().numpy(), dW_ref, "dW")
+    assert_close_grad(dW.cpu().numpy(), dW_ref, "dW")
     if want_dhin:
-        assert_close(dH_in.cpu().numpy()[:, :d_in], dhin_ref, "dH_in")
+        assert_close_grad(dH_in.cpu().numpy()[:, :d_in], dhin_ref, "dH_in")
 
 
 @pytest.mark.parametrize("d_in,d_out", [(8, 8), (64, 32), (100, 41), (256, 256), (602, 130)])

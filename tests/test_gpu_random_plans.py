@@ -8,7 +8,7 @@ import torch
 from oracle import oracle as orc
 from paper_2311_14898_amd import binding as B
 from paper_2311_14898_amd import inputs
-from tests.util import assert_close
+from tests.util import assert_close, assert_close_grad
 
 pytestmark = pytest.mark.gpu
 
@@ -106,9 +106,9 @@ def test_random_plan(ctx, seed):
             assert abs(loss - ref["loss"]) <= 1e-4 * abs(ref["loss"]), (epoch, loss, ref["loss"])
             for l in range(L):
                 assert_close(B.ht_epoch_buffer(ctx, B.HT_BUF_H, l + 1).numpy(), ref["h"][l], f"epoch {epoch} h^{l + 1}")
-                assert_close(B.ht_epoch_buffer(ctx, B.HT_BUF_GH, l + 1).numpy(), ref["gh"][l], f"epoch {epoch} grad h^{l + 1}")
-                assert_close(B.ht_epoch_buffer(ctx, B.HT_BUF_DW, l).numpy(), ref["gW"][l], f"epoch {epoch} grad W^{l}")
-                assert_close(Wd[l].cpu().numpy(), ref["W_new"][l], f"epoch {epoch} W^{l}")
+                assert_close_grad(B.ht_epoch_buffer(ctx, B.HT_BUF_GH, l + 1).numpy(), ref["gh"][l], f"epoch {epoch} grad h^{l + 1}")
+                assert_close_grad(B.ht_epoch_buffer(ctx, B.HT_BUF_DW, l).numpy(), ref["gW"][l], f"epoch {epoch} grad W^{l}")
+                assert_close_grad(Wd[l].cpu().numpy(), ref["W_new"][l], f"epoch {epoch} W^{l}")
             W_ref = ref["W_new"]      # the oracle trains on its own weights
     finally:
         B.ht_graph_destroy(g)

@@ -1,0 +1,152 @@
+"""Whole epochs of the two billion-edge workloads at the scale this box holds, in the configuration bench.py runs
+them (`bench.epoch_plan`): config 4 at scale 0.07 (7.77 M vertices, 112 M edges, 128-256-256-172, 64 chunks, labels on
+1 % of the vertices, h^l, a^l and grad h^l all in pinned host memory: Sec. 4.2's hybrid with the checkpoints on the
+CPU side) and config 5 at scale 0.35 (22.96 M vertices, 1.26 B edges, 256-256-256-64, 128 chunks, h^l in pinned host
+memory).  Neither is the full configuration: the box's pinned-memory cap sets the scale.
+
+The oracle cannot hold these tensors in fp64, so every layer step is recomputed by it on samples, from that step's
+actual inputs read back from where they live: >= 1000 destination rows of a^l and h^{l+1} (the sampled rows' in-edges
+form a small graph of their own), sampled columns of every weight gradient over all vertices, >= 200 sources of
+every grad h^l, the loss and its gradient from the full logits; and the link-traffic counters against the
+partition's row counts (Sec. 5.1, 5.3: V_ori and the rows actually loaded).  ReLU's derivative is read from the
+device's own h^{l+1}, so pre-activations within rounding of 0 need no special care here.
+"""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import bench
+from oracle import oracle as orc
+from paper_2311_14898_amd import binding as B
+from paper_2311_14898_amd import inputs
+from tests.util import assert_close, assert_close_grad
+
+pytestmark = pytest.mark.gpu
+N_ROWS, N_SOURCES, BLOCK = 1000, 200, 1 << 21
+
+
+def _select(keys: torch.Tensor, other: torch.Tensor, wanted: np.ndarray, V: int):
+    """(keys[e], other[e]) for the edges whose key is in `wanted`, on the CPU; the edge list stays on the GPU."""
+    lut = torch.zeros(V, dtype=torch.bool, device=keys.device)
+    lut[torch.as_tensor(wanted, device=keys.device)] = True
+    ks, os_ = [], []
+    for e0 in range(0, keys.numel(), 1 << 27):
+        k = keys[e0:e0 + (1 << 27)]
+        m = lut[k.long()]
+        ks.append(k[m].cpu())
+        os_.append(other[e0:e0 + (1 << 27)][m].cpu())
+    return torch.cat(ks).numpy(), torch.cat(os_).numpy()
+
+
+def _scaled_epoch(name, scale, residency):
+    t_start = time.perf_counter()
+    note = lambda msg: print(f"[{time.perf_counter() - t_start:6.1f}s] {name} @ {scale}: {msg}", flush=True)
+    w = inputs.WORKLOADS[name].scaled(scale)
+    V, dims, L = w.V, w.dims, w.n_layers
+    src, dst = inputs.rmat_edges(V, w.E, w.graph_seed, device="cuda")
+    X = inputs.features(V, dims[0])
+    y = inputs.labels(V, dims[-1], labelled_one_in=w.labelled_one_in)
+    Ws_t = inputs.glorot_weights(dims)
+    Ws = [x.numpy() for x in Ws_t]
+    note("inputs generated")
+    # degrees and the samples, from the edge list alone
+    deg_in = torch.bincount(dst.long(), minlength=V)
+    deg_out = torch.bincount(src.long(), minlength=V)
+    s = 1.0 / np.sqrt(deg_in.cpu().numpy().astype(np.float64) + 1.0)
+    rng = np.random.default_rng(11)
+    hubs_in = torch.topk(deg_in, 3).indices.cpu().numpy()
+    rows = np.unique(np.concatenate([rng.integers(0, V, N_ROWS + 50), hubs_in, [0, V - 1]]))
+    assert len(rows) >= N_ROWS
+    modest = torch.where(deg_out <= 200_000, deg_out, torch.zeros_like(deg_out))
+    us = np.unique(np.concatenate([rng.integers(0, V, N_SOURCES + 20), torch.topk(modest, 2).indices.cpu().numpy()]))
+    assert len(us) >= N_SOURCES
+    del deg_in, deg_out, modest
+    in_dst, in_src = _select(dst, src, rows, V)                     # in-edges of the sampled rows
+    out_src, out_dst = _select(src, dst, us, V)                     # out-edges of the sampled sources
+    # the sampled rows with all their in-neighbours as a graph of its own (local ids in `nodes` order)
+    nodes = np.unique(np.concatenate([in_src.astype(np.int64), rows]))
+    loc = lambda ids: np.searchsorted(nodes, ids).astype(np.int32)
+    sub_indptr, sub_col = orc.csc_build(len(nodes), loc(in_src), loc(in_dst), add_self_loops=True)
+    rows_l = loc(rows)
+    order = np.argsort(out_src, kind="stable")
+    out_src, out_dst = out_src[order], out_dst[order]
+    first = np.searchsorted(out_src, us)
+    last = np.searchsorted(out_src, us, side="right")
+    out_nbrs = [np.concatenate([out_dst[a:b].astype(np.int64), [u]]) for u, a, b in zip(us, first, last)]
+    vs_all = np.unique(np.concatenate(out_nbrs))
+    note(f"samples: {len(rows)} rows with {len(in_src)} in-edges ({len(nodes)} vertices), {len(us)} sources with {len(out_src)} out-edges")
+
+    host, plan = bench.epoch_plan(B, w, residency)
+    ctx = B.ht_ctx_create(0)
+    g = B.ht_partition(ctx, V, src, dst, w.n_chunks)
+    try:
+        del src, dst
+        torch.cuda.empty_cache()
+        info = B.ht_graph_info_get(g)
+        Wd = [x.clone().cuda() for x in Ws_t]
+        Xd = B.to_matrix(X, B.HT_LOC_HOST_PINNED if host else B.HT_LOC_DEVICE)
+        loss, st = B.ht_epoch(ctx, g, dims, Wd, w.lr, Xd, y.cuda(), want_stats=True, **plan)
+        note(f"epoch done in {st.t_total_ms:.0f} ms; plan inter={st.plan_inter} h={st.plan_res_h} a={st.plan_res_a} grad={st.plan_res_g}")
+        assert st.plan_res_h == B.HT_RES_HOST
+        # Sec. 5.1 / 5.3: per forward pass the buffer loads v_load rows of the v_ori the chunks reference
+        assert st.rows_loaded == info.v_load * L and st.rows_loaded + st.rows_reused == info.v_ori * L
+        assert info.v_load == info.v_ru and V <= info.v_ru < info.v_ori          # adjacent reuse: the paper's V_+ru
+        assert st.bytes_h2d_nodedup == 4 * sum(dims[:L]) * info.v_ori
+        assert st.bytes_h2d >= 4 * sum(dims[1:L]) * info.v_load and st.bytes_h2d < st.bytes_h2d_nodedup
+        assert st.edges == info.E_stored * (2 * L - 1)
+
+        buf = lambda kind, l, r: B.ht_epoch_buffer_rows(ctx, kind, l, r).numpy()
+        h_rows = lambda l, r: X[torch.as_tensor(r)].numpy() if l == 0 else buf(B.HT_BUF_H, l, r)
+        # forward, layer by layer, on the sampled rows from the device's own layer input
+        for l in range(L):
+            a_ref = orc.aggregate(sub_indptr, sub_col, h_rows(l, nodes), s=s[nodes])[rows_l]
+            a_dev = buf(B.HT_BUF_A, l, rows)
+            assert_close(a_dev, a_ref, f"a^{l} rows")
+            z_ref = orc.matmul(a_dev, Ws[l])
+            assert_close(h_rows(l + 1, rows), np.maximum(z_ref, 0.0) if l < L - 1 else z_ref, f"h^{l + 1} rows")
+        note("forward rows checked")
+        logits = B.ht_epoch_buffer(ctx, B.HT_BUF_H, L).numpy()
+        loss_ref, g_ref = orc.softmax_ce(logits, y.numpy())
+        assert abs(loss - loss_ref) <= 1e-4 * abs(loss_ref), (loss, loss_ref)
+        assert_close_grad(buf(B.HT_BUF_GH, L, rows), g_ref[rows], "grad h^L rows")
+        del logits, g_ref
+        note("loss checked")
+        W_new = [x.cpu().numpy() for x in Wd]
+        for l in range(L - 1, -1, -1):
+            def dz_rows(r):
+                gh = buf(B.HT_BUF_GH, l + 1, r).astype(np.float64)
+                return np.where(buf(B.HT_BUF_H, l + 1, r) > 0.0, gh, 0.0) if l < L - 1 else gh
+            # sampled columns of grad W^l = (a^l)^T dz over all vertices, block by block (numpy's fp64 product: the
+            # oracle's transposed product walks a tall operand column by column)
+            cols = np.unique(rng.integers(0, dims[l + 1], 6))
+            gW_ref = np.zeros((dims[l], len(cols)))
+            for r0 in range(0, V, BLOCK):
+                r = np.arange(r0, min(r0 + BLOCK, V))
+                gW_ref += buf(B.HT_BUF_A, l, r).T.astype(np.float64) @ np.ascontiguousarray(dz_rows(r)[:, cols])
+            gW_dev = B.ht_epoch_buffer(ctx, B.HT_BUF_DW, l).numpy()
+            assert (np.abs(gW_dev[:, cols] - gW_ref) <= 1e-4 * np.abs(gW_dev).max()).all(), f"grad W^{l} columns"
+            assert_close_grad(W_new[l], Ws[l].astype(np.float64) - w.lr * gW_dev.astype(np.float64), f"W^{l} step")
+            if l > 0:
+                # grad h^l[u] = s_u sum over u's out-edges (and its self-loop) of s_v (dz_v W^T)
+                da = orc.matmul_nt(dz_rows(vs_all), Ws[l])
+                ref = np.stack([s[u] * (s[vs][:, None] * da[np.searchsorted(vs_all, vs)]).sum(axis=0) for u, vs in zip(us, out_nbrs)])
+                assert_close_grad(buf(B.HT_BUF_GH, l, us), ref, f"grad h^{l} sources")
+            note(f"backward of layer {l} checked")
+        return st, info
+    finally:
+        B.ht_graph_destroy(g)
+        B.ht_ctx_destroy(ctx)
+
+
+def test_cfg4_at_scale_0p07_epoch_with_checkpoints_on_the_host():
+    st, info = _scaled_epoch("cfg4", 0.07, "workload")
+    assert st.plan_res_a == B.HT_RES_HOST and st.plan_res_g == B.HT_RES_HOST and st.bytes_d2h > 0
+
+
+def test_cfg5_at_scale_0p35_epoch_with_layer_outputs_on_the_host():
+    if torch.cuda.mem_get_info()[0] < 250e9:
+        pytest.skip("needs a GPU with 250 GB of free memory")
+    st, info = _scaled_epoch("cfg5", 0.35, "h-host")
+    print(f"rows loaded per pass {info.v_load} of {info.v_ori} referenced: dedup saves {1 - info.v_ru / info.v_ori:.3f}", flush=True)

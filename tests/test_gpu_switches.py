@@ -8,7 +8,7 @@ import torch
 from oracle import oracle as orc
 from paper_2311_14898_amd import binding as B
 from paper_2311_14898_amd import inputs
-from tests.util import assert_close
+from tests.util import assert_close, assert_close_grad
 
 pytestmark = pytest.mark.gpu
 
@@ -62,8 +62,8 @@ def test_switch(case, env, monkeypatch):
                 assert abs(loss - ref["loss"]) <= 1e-4 * abs(ref["loss"])
                 for l in range(w.n_layers):
                     assert_close(B.ht_epoch_buffer(ctx, B.HT_BUF_H, l + 1).numpy(), ref["h"][l], f"{env} host={host} h^{l + 1}")
-                    assert_close(B.ht_epoch_buffer(ctx, B.HT_BUF_GH, l + 1).numpy(), ref["gh"][l], f"{env} host={host} grad h^{l + 1}")
-                    assert_close(Wd[l].cpu().numpy(), ref["W_new"][l], f"{env} host={host} W^{l}")
+                    assert_close_grad(B.ht_epoch_buffer(ctx, B.HT_BUF_GH, l + 1).numpy(), ref["gh"][l], f"{env} host={host} grad h^{l + 1}")
+                    assert_close_grad(Wd[l].cpu().numpy(), ref["W_new"][l], f"{env} host={host} W^{l}")
             finally:
                 B.ht_graph_destroy(g)
     finally:

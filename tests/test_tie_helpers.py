@@ -64,3 +64,49 @@ def test_interval_and_row_checks_catch_what_they_should():
         pass
     else:
         raise AssertionError("a value outside the interval passed")
+
+
+def test_relu_tie_slack_contains_every_flip():
+    # A huge rounding factor makes many pre-activations "ties".  Flipping ReLU's derivative on any subset of them, in
+    # a numpy restatement of the backward pass built on the oracle's forward values, must keep every weight gradient
+    # inside the helper's interval; and flipping all of them at once must leave the interval's interior somewhere.
+    from tests.util import relu_tie_slack
+    rng = np.random.default_rng(0)
+    V, E, dims = 300, 3000, [12, 10, 9, 5]
+    src, dst = rng.integers(0, V, E).astype(np.int32), rng.integers(0, V, E).astype(np.int32)
+    indptr, col = orc.csc_build(V, src, dst)
+    X = rng.standard_normal((V, dims[0])).astype(np.float32)
+    Ws = [(rng.standard_normal((dims[l], dims[l + 1])) / 3).astype(np.float32) for l in range(3)]
+    y = rng.integers(0, 5, V).astype(np.int32)
+    ref = orc.gcn_epoch(indptr, col, dims, X, Ws, y, want=("a", "z", "gh"))
+    sl = relu_tie_slack(ref, indptr, col, Ws, dims, factor=3e5)
+    assert all(len(sl[l][2][0]) > 20 for l in range(2)) and len(sl[2][2][0]) == 0
+
+    def backward(masks):
+        gh = ref["gh"][2]
+        gW = [None] * 3
+        for l in (2, 1, 0):
+            dz = gh if l == 2 else gh * masks[l]
+            gW[l] = ref["a"][l].T @ dz
+            if l > 0:
+                gh = orc.aggregate_T(indptr, col, dz @ Ws[l].astype(np.float64).T)
+        return gW
+
+    base_masks = [ref["z"][l] > 0 for l in range(2)]
+    base = backward(base_masks)
+    for l in range(3):
+        np.testing.assert_allclose(base[l], ref["gW"][l], rtol=1e-9, atol=1e-12)
+    moved = False
+    for trial in range(6):
+        masks = [m.copy() for m in base_masks]
+        for l in range(2):
+            tv, tc = sl[l][2]
+            pick = np.ones(len(tv), bool) if trial == 0 else rng.random(len(tv)) < 0.5
+            masks[l][tv[pick], tc[pick]] ^= True
+        got = backward(masks)
+        for l in range(3):
+            lo, hi, _ = sl[l]
+            err = got[l] - ref["gW"][l]
+            assert (err >= lo - 1e-12).all() and (err <= hi + 1e-12).all(), (trial, l)
+            moved |= bool((np.abs(err) > 1e-9).any())
+    assert moved
