@@ -48,7 +48,9 @@ def cpu_baseline(w, src_cpu, dst_cpu, X, y, Ws):
         t = time.perf_counter() - t0
         return {"value": t, "unit": "s/epoch", "cores": cores, "kind": "oracle",
                 "sample": f"one whole epoch of the fp64 oracle (forward, loss, backward, update) on the same graph and "
-                          f"inputs, {t:.1f} s; CSC construction not timed", "oracle_loss": ref["loss"]}
+                          f"inputs, {t:.1f} s; CSC construction not timed", "oracle_loss": ref["loss"],
+                "oracle_loss_is": "the loss of epoch 1 (initial weights); compare with parity.device_loss_epoch1, not with "
+                                  "loss_after_steps"}, ref
     deg = np.bincount(dst_cpu, minlength=V).astype(np.int64) + 1          # stored in-degree with the self-loop
     full_indptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int64)
     s = orc.norm(full_indptr)
@@ -74,7 +76,7 @@ def cpu_baseline(w, src_cpu, dst_cpu, X, y, Ws):
     return {"value": t * ef / sample_flops, "unit": "s/epoch (extrapolated)", "cores": cores, "kind": "oracle",
             "sample": f"layer-0 forward step (fp64 aggregate + transform + ReLU) of the first {n_sample_chunks} chunks' "
                       f"{v1 - v0} destination rows, {sample_edges} of {Ep} stored edges, took {t:.2f} s; scaled to the "
-                      f"epoch by flop count ({ef / sample_flops:.1f}x)", "sample_seconds": t}
+                      f"epoch by flop count ({ef / sample_flops:.1f}x)", "sample_seconds": t}, None
 
 
 def gat_epoch_flops(w):
@@ -202,6 +204,81 @@ def epoch_plan(B, w, residency="workload", hbm_budget_gb=0.0, inter="auto"):
     return host, plan
 
 
+PCIE_NOMINAL_GBS = 64.0        # PCIe 5.0 x16, one direction
+LINK_MEASURED_GBS = 57.0       # copy-kernel microbenchmark on this machine's host link, one direction alone
+
+
+def offload_config(name, scale, residency, cache, steps, warmup, cpu_s_per_flop, note):
+    """One host-offloaded workload, timed like the headline one but for a few epochs: epoch time, the host link as
+    its roofline, host-GPU bytes with and without dedup (Sec. 5.1, 5.3).  Everything it allocates is released."""
+    import torch
+    from paper_2311_14898_amd import binding as B
+    from paper_2311_14898_amd import inputs
+    w = inputs.WORKLOADS[name].scaled(scale)
+    src, dst = inputs.rmat_edges(w.V, w.E, w.graph_seed, device="cuda")
+    X = inputs.features(w.V, w.dims[0])
+    y = inputs.labels(w.V, w.dims[-1], labelled_one_in=w.labelled_one_in)
+    Ws = inputs.glorot_weights(w.dims)
+    host, plan = epoch_plan(B, w, residency)
+    ctx = B.ht_ctx_create(0)
+    g = None
+    try:
+        g = B.ht_partition(ctx, w.V, src, dst, w.n_chunks,
+                           cache_policy=B.HT_CACHE_FARTHEST if cache == "farthest" else B.HT_CACHE_ADJACENT)
+        del src, dst
+        torch.cuda.empty_cache()
+        info = B.ht_graph_info_get(g)
+        Xd = B.to_matrix(X, B.HT_LOC_HOST_PINNED if host else B.HT_LOC_DEVICE)
+        yd, Wd = y.cuda(), [x.clone().cuda() for x in Ws]
+        note(f"{name} @ {scale} ({cache}): partitioned, inputs resident")
+        for _ in range(warmup):
+            B.ht_epoch(ctx, g, w.dims, Wd, w.lr, Xd, yd, **plan)
+        torch.cuda.synchronize()
+        tot = None
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            loss, st = B.ht_epoch(ctx, g, w.dims, Wd, w.lr, Xd, yd, want_stats=True, stats_detail=B.HT_STATS_AGG_FWD, **plan)
+            d = st.as_dict()
+            tot = d if tot is None else {k: ([a + b for a, b in zip(tot[k], v)] if isinstance(v, list) else tot[k] + v) for k, v in d.items()}
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t0
+        note(f"{name} @ {scale} ({cache}): {1e3 * el / steps:.0f} ms per epoch")
+        h2d, d2h = tot["bytes_h2d"] / steps, tot["bytes_d2h"] / steps
+        busier = max(h2d, d2h) / (el / steps) / 1e9
+        L = w.n_layers
+        return {"config": {"workload": f"{w.name}: {L}-layer GCN, R-MAT V={w.V} E={w.E} (+{w.V} self-loops), dims "
+                                       f"{'-'.join(map(str, w.dims))}, {w.n_chunks} chunks, residency {residency}",
+                           "scale": scale, "full_configuration": scale == 1.0},
+                "steps": steps, "warmup": warmup, "ms_per_step": 1e3 * el / steps, "loss_after_steps": loss,
+                "gteps": tot["edges"] / el / 1e9, "partition_ms": info.partition_ms,
+                "buffer": {"policy": "adjacent-chunk reuse (Sec. 5.1)" if cache == "adjacent" else
+                           "schedule-aware: rows leave after their last use, or for room with the farthest next use first",
+                           "rows": info.cache_rows},
+                "alpha": info.alpha, "v_ori": info.v_ori, "v_ru": info.v_ru, "v_load": info.v_load,
+                "dedup_row_savings": 1.0 - info.v_ru / max(info.v_ori, 1),
+                "rows_loaded_savings": 1.0 - info.v_load / max(info.v_ori, 1),
+                "bytes_h2d_per_step": h2d, "bytes_d2h_per_step": d2h,
+                "bytes_h2d_nodedup_per_step": tot["bytes_h2d_nodedup"] / steps,
+                "neighbour_rows_h2d_bytes_per_step": 4.0 * sum(w.dims[l] for l in range(L) if l > 0 or host) * info.v_load,
+                "plan": {"inter": ["auto", "mask", "hybrid", "recompute"][tot["plan_inter"] // steps],
+                         "h": ["-", "hbm", "host"][tot["plan_res_h"] // steps], "a": ["-", "hbm", "host"][tot["plan_res_a"] // steps],
+                         "grad_h": ["-", "hbm", "host"][tot["plan_res_g"] // steps]},
+                "roofline": {"bound": "host link", "achieved": busier, "peak": PCIE_NOMINAL_GBS, "unit": "GB/s",
+                             "frac": busier / PCIE_NOMINAL_GBS, "measured_peak": LINK_MEASURED_GBS,
+                             "frac_of_measured_peak": busier / LINK_MEASURED_GBS,
+                             "h2d_gbps_over_epoch": h2d / (el / steps) / 1e9, "d2h_gbps_over_epoch": d2h / (el / steps) / 1e9,
+                             "note": "bytes of the busier direction over the whole epoch (compute included) against PCIe 5.0 x16 "
+                                     "one way; measured_peak is a copy kernel alone on this box"},
+                "cpu_baseline": None if cpu_s_per_flop is None else
+                {"value": cpu_s_per_flop * epoch_flops(w), "unit": "s/epoch (extrapolated)", "kind": "oracle",
+                 "sample": "not run at this size: the headline workload's whole oracle epoch, timed in this run, scaled by flop count"}}
+    finally:
+        if g is not None:
+            B.ht_graph_destroy(g)
+        B.ht_ctx_destroy(ctx)
+        torch.cuda.empty_cache()
+
+
 def plan_partitions(ctx, w, src, dst, m):
     """Alg. 4 and the volumes of Sec. 5.3 for m partitions of the workload's chunk count each; a planning result
     computed on this one GPU (Table 7's quantities on the stand-in graph).  Outside the timed region."""
@@ -260,6 +337,8 @@ def main():
                     help="intermediate data: the planner's choice, a^l cached (Fig. 5(c)), or recomputed (Fig. 5(b))")
     ap.add_argument("--partitions", type=int, default=0, help="also plan the workload for this many GPUs (no second GPU "
                     "is used): the chunks of m partitions reorganised by Alg. 4, communication volumes before and after")
+    ap.add_argument("--no-offload-configs", action="store_true",
+                    help="skip the host-offloaded workloads that the default run times after the headline one")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a 1 GiB device copy kernel (known traffic) to scale rocprofv3 byte counters")
     args = ap.parse_args()
@@ -323,6 +402,14 @@ def main():
         torch.cuda.synchronize()
         del a, b
     note("inputs resident")
+
+    # Epoch 1 from the seeded weights, untimed, kept for the parity object: the oracle epoch of the CPU-baseline leg
+    # starts from the same weights.
+    Wp = [x.clone().cuda() for x in Ws]
+    loss_epoch1, _ = B.ht_epoch(ctx, g, w.dims, Wp, w.lr, Xd, yd, order=B.HT_ORDER_AUTO if args.order == "auto" else B.HT_ORDER_AGG_FIRST, **plan)
+    W_epoch1 = [x.cpu().numpy() for x in Wp]
+    gW_epoch1 = [B.ht_epoch_buffer(ctx, B.HT_BUF_DW, l).numpy() for l in range(w.n_layers)]
+    del Wp
 
     def timed_epochs(order, reuse=False, detail=B.HT_STATS_ALL, warmup=None):
         """W warm-up epochs, then K timed ones; returns (seconds, summed stats, last loss)."""
@@ -406,6 +493,11 @@ def main():
     traffic = read_traffic(f"agg_fwd_{args.workload}_traffic.txt") if args.scale == 1.0 else None
     roofline = {"bound": "hbm", "kernel": "forward aggregation, layer 0 (k_spmm_slab)", "achieved": achieved,
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                "traffic_source": None if traffic is None else f"profiles/agg_fwd_{args.workload}_traffic.txt (two rocprofv3 --pmc runs of this "
+                                  "command, committed; not measured in this run)",
+                "sustained_frac": None if traffic is None or avg_ms <= 0 else traffic / (avg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "sustained_note": "traffic / launch time / peak: the bytes that crossed the L2 boundary, re-reads included; frac "
+                                  "counts only the algorithmic bytes",
                 "avg_launch_ms": avg_ms, "launches": agg["n"], "algorithmic_bytes_per_launch": bytes_per_launch,
                 "gathered_GBs_cacheless": 4.0 * w.dims[0] * Ep / max(agg["t"] / args.steps * 1e-3, 1e-12) / 1e9}
 
@@ -417,7 +509,8 @@ def main():
                                   f"{'-'.join(map(str, w.dims))}, {w.n_chunks} chunks, vertex data in "
                                   f"{'pinned host memory' if host else 'HBM'}" + (f" (residency: {args.residency})" if args.residency != "workload" else ""),
                       "scale": args.scale},
-           "gteps": gteps, "hbm_gbps_dominant_kernel": achieved, "loss": loss,
+           "gteps": gteps, "hbm_gbps_dominant_kernel": achieved, "loss_after_steps": loss,
+           "loss_after_steps_is": f"the loss of the last timed epoch: epoch {args.warmup + args.steps} of training from the seeded weights",
            "partition_ms": info.partition_ms, "alpha": info.alpha, "v_ori": info.v_ori, "v_ru": info.v_ru,
            "dedup_row_savings": 1.0 - info.v_ru / max(info.v_ori, 1), "v_load": info.v_load, "cache": args.cache, "reorder": args.reorder, "permuted_ids": args.permute_ids,
            "cache_rows": info.cache_rows,
@@ -442,12 +535,37 @@ def main():
                     "a": ["-", "hbm", "host"][tot["plan_res_a"] // args.steps],
                     "grad_h": ["-", "hbm", "host"][tot["plan_res_g"] // args.steps]},
            "roofline": roofline}
+    cpu_s_per_flop = None
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, src.cpu().numpy(), dst.cpu().numpy(), X, y, Ws)
+        import numpy as np
+        out["cpu_baseline"], ref = cpu_baseline(w, src.cpu().numpy(), dst.cpu().numpy(), X, y, Ws)
+        if ref is not None:
+            cpu_s_per_flop = out["cpu_baseline"]["value"] / epoch_flops(w)
+            out["parity"] = {"epoch": 1, "device_loss_epoch1": loss_epoch1, "oracle_loss_epoch1": ref["loss"],
+                             "loss_rel": abs(loss_epoch1 - ref["loss"]) / abs(ref["loss"]),
+                             "w_new_max_rel": max(float(np.abs(W_epoch1[l] - ref["W_new"][l]).max() / np.abs(ref["W_new"][l]).max())
+                                                  for l in range(L)),
+                             "gw_max_rel": max(float(np.abs(gW_epoch1[l] - ref["gW"][l]).max() / np.abs(ref["gW"][l]).max()) for l in range(L)),
+                             "tolerance": 1e-4,
+                             "note": "the device's first epoch from the seeded weights against the fp64 oracle's epoch on the same "
+                                     "inputs: loss, updated weights and weight gradients (max-norm error over each matrix / its largest entry)"}
     if args.partitions > 0:
         out["reorganization"] = plan_partitions(ctx, w, src, dst, args.partitions)
     B.ht_graph_destroy(g)
     B.ht_ctx_destroy(ctx)
+    default_run = args.workload == "cfg2" and args.scale == 1.0 and args.residency == "workload" and args.cache == "adjacent" \
+        and args.chunks == 0 and not args.permute_ids and not args.no_other_order
+    if default_run and not args.no_offload_configs:
+        # the offload path (Alg. 2, Alg. 3; Sec. 5.1): the host-resident workloads, a few epochs each
+        del Xd, yd, Wd, src, dst, X, y
+        torch.cuda.empty_cache()
+        out["configs"] = []
+        for name, scale, residency, cache in (("cfg3", 1.0, "workload", "adjacent"), ("cfg3", 1.0, "workload", "farthest"),
+                                              ("cfg5", 0.35, "h-host", "adjacent")):
+            try:
+                out["configs"].append(offload_config(name, scale, residency, cache, 3, 1, cpu_s_per_flop, note))
+            except Exception as e:                       # the headline line must still be printed
+                out["configs"].append({"config": {"workload": name, "scale": scale}, "error": f"{type(e).__name__}: {e}"})
     print(json.dumps(out))
 
 

@@ -467,18 +467,20 @@ class _DeviceArray:
 
 
 def ht_epoch_buffer_rows(ctx, kind: int, layer: int, rows) -> torch.Tensor:
-    """The data columns of the given rows of an internal epoch buffer, as a CPU tensor [len(rows) x cols]; the rows
+    """The data columns of the given rows (an index array or a slice) of an internal epoch buffer, as a CPU tensor; the rows
     are indexed where the buffer lives (HBM or pinned host memory), so a multi-gigabyte buffer is never copied whole."""
     t = ht_tensor()
     _check(load().ht_epoch_buffer(ctx, kind, layer, C.byref(t)), ctx)
     ht_sync(ctx)
-    idx = torch.as_tensor(np.asarray(rows, dtype=np.int64))
-    assert idx.numel() == 0 or (int(idx.min()) >= 0 and int(idx.max()) < t.rows)
     if t.loc == HT_LOC_DEVICE:
         whole = torch.as_tensor(_DeviceArray(t), device="cuda")
-        return whole[idx.cuda(), : t.cols].cpu()
-    whole = torch.from_numpy(np.ctypeslib.as_array(C.cast(C.c_void_p(t.ptr), C.POINTER(C.c_float)), shape=(int(t.rows), int(t.ld))))
-    return whole[idx, : t.cols].clone()
+    else:
+        whole = torch.from_numpy(np.ctypeslib.as_array(C.cast(C.c_void_p(t.ptr), C.POINTER(C.c_float)), shape=(int(t.rows), int(t.ld))))
+    if isinstance(rows, slice):                      # a contiguous row range
+        return whole[rows, : t.cols].cpu().clone()
+    idx = torch.as_tensor(np.asarray(rows, dtype=np.int64))
+    assert idx.numel() == 0 or (int(idx.min()) >= 0 and int(idx.max()) < t.rows)
+    return whole[idx.to(whole.device), : t.cols].cpu().clone()
 
 
 def ht_tensor_to_host(ctx, t: ht_tensor) -> torch.Tensor:

@@ -90,11 +90,13 @@ def _scaled_epoch(name, scale, residency):
         loss, st = B.ht_epoch(ctx, g, dims, Wd, w.lr, Xd, y.cuda(), want_stats=True, **plan)
         note(f"epoch done in {st.t_total_ms:.0f} ms; plan inter={st.plan_inter} h={st.plan_res_h} a={st.plan_res_a} grad={st.plan_res_g}")
         assert st.plan_res_h == B.HT_RES_HOST
-        # Sec. 5.1 / 5.3: per forward pass the buffer loads v_load rows of the v_ori the chunks reference
-        assert st.rows_loaded == info.v_load * L and st.rows_loaded + st.rows_reused == info.v_ori * L
+        # Sec. 5.1 / 5.3: per forward pass over a host-resident layer input the buffer loads v_load rows of the v_ori
+        # the chunks reference (a layer input that lives in HBM is read in place: X here when only h^l is on the host)
+        in_dims = [dims[l] for l in range(L) if l > 0 or host]
+        assert st.rows_loaded == info.v_load * len(in_dims) and st.rows_loaded + st.rows_reused == info.v_ori * len(in_dims)
         assert info.v_load == info.v_ru and V <= info.v_ru < info.v_ori          # adjacent reuse: the paper's V_+ru
-        assert st.bytes_h2d_nodedup == 4 * sum(dims[:L]) * info.v_ori
-        assert st.bytes_h2d >= 4 * sum(dims[1:L]) * info.v_load and st.bytes_h2d < st.bytes_h2d_nodedup
+        assert st.bytes_h2d_nodedup == 4 * sum(in_dims) * info.v_ori
+        assert st.bytes_h2d >= 4 * sum(in_dims) * info.v_load and st.bytes_h2d < st.bytes_h2d_nodedup
         assert st.edges == info.E_stored * (2 * L - 1)
 
         buf = lambda kind, l, r: B.ht_epoch_buffer_rows(ctx, kind, l, r).numpy()
@@ -123,7 +125,7 @@ def _scaled_epoch(name, scale, residency):
             cols = np.unique(rng.integers(0, dims[l + 1], 6))
             gW_ref = np.zeros((dims[l], len(cols)))
             for r0 in range(0, V, BLOCK):
-                r = np.arange(r0, min(r0 + BLOCK, V))
+                r = slice(r0, min(r0 + BLOCK, V))
                 gW_ref += buf(B.HT_BUF_A, l, r).T.astype(np.float64) @ np.ascontiguousarray(dz_rows(r)[:, cols])
             gW_dev = B.ht_epoch_buffer(ctx, B.HT_BUF_DW, l).numpy()
             assert (np.abs(gW_dev[:, cols] - gW_ref) <= 1e-4 * np.abs(gW_dev).max()).all(), f"grad W^{l} columns"
