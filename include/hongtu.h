@@ -292,6 +292,26 @@ typedef struct {
 int ht_layer_fwd(ht_ctx *ctx, const ht_graph *g, const ht_layer_desc *desc, const ht_tensor *H_in,
                  const float *W, ht_tensor *H_out, ht_tensor *A_ckpt, ht_stats *stats);
 
+/* ht_layer_fwd for callers that cannot allocate device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * result as ht_layer_fwd (the same kernels in the same order), restricted to
+ * the all-in-HBM path: H_in, H_out and A_ckpt (required) in device memory,
+ * aggregate-first order, rows read in place (no neighbour buffer), no stats.
+ * Its two scratch buffers (the tile-padded copy of W and the partial sums of
+ * destination rows cut into several work items) live in an array that is part
+ * of the library's code object: HT_STATIC_SCRATCH_BYTES (16 MiB) on every GPU
+ * the library runs on, held until the process ends; its address is taken at
+ * ht_ctx_create.  The call allocates nothing and frees nothing.  A layer that
+ * needs more scratch than the array holds is refused with HT_ENOMEM before
+ * anything is launched (ht_last_error says how much it needs); ht_layer_fwd
+ * handles those.  All contexts on one GPU share the array and it keeps the last
+ * call's contents (every word that is read is written first by the same call):
+ * calls that overlap in time on one GPU, from any stream or context, race.
+ * Asynchronous on the context's stream like ht_layer_fwd. */
+#define HT_STATIC_SCRATCH_BYTES (16u << 20)
+int ht_layer_fwd_static(ht_ctx *ctx, const ht_graph *g, const ht_layer_desc *desc, const ht_tensor *H_in,
+                        const float *W, ht_tensor *H_out, ht_tensor *A_ckpt);
+
 /* Backward of one layer over all chunks:
  *   z = a W (recomputed) ; dz = dH_out * [z > 0] (no mask when act = none)
  *   dW = a^T dz (overwritten) ; da = dz W^T ; dH_in[N_j] += s_u * sum s_v da[v]

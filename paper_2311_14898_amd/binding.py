@@ -112,7 +112,7 @@ class ht_plan_opts(C.Structure):
 
 EXPORTS = ["ht_ctx_create", "ht_ctx_destroy", "ht_sync", "ht_ctx_set_hbm_budget", "ht_ctx_graph_launches", "ht_tensor_zero", "ht_strerror", "ht_last_error",
            "ht_partition", "ht_graph_destroy", "ht_graph_info_get", "ht_graph_chunk_info", "ht_graph_export_chunk",
-           "ht_graph_export_csc", "ht_graph_chunk_order", "ht_graph_reorganize", "ht_layer_fwd", "ht_layer_bwd", "ht_epoch", "ht_epoch_buffer", "ht_tensor_to_host", "ht_memory_model",
+           "ht_graph_export_csc", "ht_graph_chunk_order", "ht_graph_reorganize", "ht_layer_fwd", "ht_layer_fwd_static", "ht_layer_bwd", "ht_epoch", "ht_epoch_buffer", "ht_tensor_to_host", "ht_memory_model",
            "ht_chunk_rows_model", "ht_gat_layer_fwd", "ht_gat_layer_bwd", "ht_gat_epoch", "ht_comm_cost_model"]
 
 _lib = None
@@ -157,6 +157,8 @@ def load():
     lib.ht_graph_reorganize.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.ht_layer_fwd.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(ht_layer_desc), C.POINTER(ht_tensor), C.c_void_p,
                                  C.POINTER(ht_tensor), C.POINTER(ht_tensor), C.POINTER(ht_stats)]
+    lib.ht_layer_fwd_static.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(ht_layer_desc), C.POINTER(ht_tensor), C.c_void_p,
+                                        C.POINTER(ht_tensor), C.POINTER(ht_tensor)]
     lib.ht_layer_bwd.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(ht_layer_desc), C.POINTER(ht_tensor), C.c_void_p,
                                  C.POINTER(ht_tensor), C.POINTER(ht_tensor), C.POINTER(ht_tensor), C.c_void_p,
                                  C.POINTER(ht_stats)]
@@ -333,6 +335,16 @@ def ht_layer_fwd(ctx, g, d_in: int, d_out: int, act: int, H_in: torch.Tensor, W:
                                C.byref(ack) if ack is not None else None, C.byref(st) if st is not None else None),
            ctx)
     return st
+
+
+def ht_layer_fwd_static(ctx, g, d_in: int, d_out: int, act: int, H_in: torch.Tensor, W: torch.Tensor, H_out: torch.Tensor,
+                        A_ckpt: torch.Tensor):
+    """ht_layer_fwd without any device allocation (all tensors in HBM, scratch in the library's static array)."""
+    assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous() and tuple(W.shape) == (d_in, d_out)
+    desc = ht_layer_desc(d_in, d_out, act, HT_GATHER_AUTO, 0, HT_ORDER_AGG_FIRST)
+    hin, hout, ack = tensor_view(H_in, d_in), tensor_view(H_out, d_out), tensor_view(A_ckpt, d_in)
+    _check(load().ht_layer_fwd_static(ctx, g, C.byref(desc), C.byref(hin), C.c_void_p(W.data_ptr()), C.byref(hout),
+                                      C.byref(ack)), ctx)
 
 
 def ht_layer_bwd(ctx, g, d_in: int, d_out: int, act: int, ckpt: torch.Tensor, W: torch.Tensor, dH_out: torch.Tensor,

@@ -4,6 +4,46 @@
 
 #include "ht_internal.h"
 
+#include <mutex>
+
+// Scratch memory of the allocation-free entry point (ht_layer_fwd_static): part of the code object, so every GPU the
+// library runs on holds HT_STATIC_SCRATCH_BYTES of it from load to exit, and no call has to allocate.  In host code
+// this name is only a handle for hipGetSymbolAddress; kernels get the device address taken below.  (No
+// __attribute__((used)) here: it pins the device symbol to local binding, and the runtime, which finds the variable
+// by name in the code object, aborts when it cannot; referenced from host code alone the compiler exports it.)
+static __device__ __align__(256) unsigned char scratch[HT_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int HT_MAX_DEVICES = 64;
+std::mutex g_static_mu;
+unsigned char* g_static_ptr[HT_MAX_DEVICES] = {};
+
+// Address of `scratch` on the current device (each GPU has its own copy at its own address); taken once per device.
+int static_scratch_address(int device, unsigned char** out) {
+  *out = nullptr;
+  if (device < 0 || device >= HT_MAX_DEVICES) return HT_EINVAL;
+  std::lock_guard<std::mutex> lk(g_static_mu);
+  if (!g_static_ptr[device]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return HT_EHIP;
+    }
+    g_static_ptr[device] = (unsigned char*)p;
+  }
+  *out = g_static_ptr[device];
+  return HT_OK;
+}
+}  // namespace
+
+void ht_static_begin(ht_ctx* ctx) {
+  ctx->static_mode = true;
+  ctx->static_used = 0;
+  for (int i = 0; i < HT_N_SCRATCH; ++i) ctx->static_off[i] = ctx->static_len[i] = 0;
+}
+
+void ht_static_end(ht_ctx* ctx) { ctx->static_mode = false; }
+
 int ht_set_err(ht_ctx* ctx, int code, const char* fmt, ...) {
   char buf[512];
   va_list ap;
@@ -17,6 +57,7 @@ int ht_set_err(ht_ctx* ctx, int code, const char* fmt, ...) {
 int ht_dev_alloc(ht_ctx* ctx, void** out, size_t bytes) {
   *out = nullptr;
   if (bytes == 0) return HT_OK;
+  if (ctx->static_mode) return ht_set_err(ctx, HT_ESTATE, "a device allocation of %zu bytes was asked for inside the allocation-free entry point", bytes);
   if (ctx->hbm_budget > 0 && ctx->hbm_used + (int64_t)bytes > ctx->hbm_budget)
     return ht_set_err(ctx, HT_ENOMEM, "HBM budget exceeded: %lld in use + %zu requested > %lld",
                       (long long)ctx->hbm_used, bytes, (long long)ctx->hbm_budget);
@@ -37,6 +78,26 @@ void ht_dev_free(ht_ctx* ctx, void* p, size_t bytes) {
 }
 
 int ht_scratch(ht_ctx* ctx, int slot, size_t bytes, void** out) {
+  if (ctx->static_mode) {
+    // a piece of the static array per slot: cut at the slot's first request of this call, kept for its later ones
+    *out = nullptr;
+    if (!ctx->static_base) return ht_set_err(ctx, HT_ESTATE, "the static scratch array has no address on this device");
+    if (ctx->static_len[slot] < bytes) {
+      if (ctx->static_len[slot] != 0)
+        return ht_set_err(ctx, HT_ESTATE, "scratch slot %d grew from %zu to %zu bytes inside one allocation-free call", slot,
+                          ctx->static_len[slot], bytes);
+      const size_t off = (ctx->static_used + 255) & ~(size_t)255;
+      if (bytes > HT_STATIC_SCRATCH_BYTES || off > HT_STATIC_SCRATCH_BYTES - bytes)
+        return ht_set_err(ctx, HT_ENOMEM, "the allocation-free entry point needs %zu more bytes of scratch memory (slot %d) after "
+                          "%zu in use; its static array holds %zu: use the allocating entry point for this size", bytes, slot,
+                          ctx->static_used, HT_STATIC_SCRATCH_BYTES);
+      ctx->static_off[slot] = off;
+      ctx->static_len[slot] = bytes;
+      ctx->static_used = off + bytes;
+    }
+    *out = ctx->static_base + ctx->static_off[slot];
+    return HT_OK;
+  }
   if (ctx->scratch_bytes[slot] < bytes) {
     if (ctx->scratch[slot]) {
       HT_HIP(ctx, hipStreamSynchronize(ctx->stream));
@@ -126,6 +187,10 @@ int ht_ctx_create(ht_ctx** out, int device, void* hip_stream) {
   ht_ctx* c = new (std::nothrow) ht_ctx();
   if (!c) return HT_ENOMEM;
   c->device = device;
+  if (static_scratch_address(device, &c->static_base) != HT_OK) {
+    delete c;
+    return HT_EHIP;
+  }
   if (const char* v = getenv("HT_AGG_VARIANT")) c->agg_variant = atoi(v);
   if (const char* v = getenv("HT_LINK_BLOCKS")) c->link_blocks = atoi(v) > 0 ? atoi(v) : 64;
   if (const char* v = getenv("HT_GATHER_BLOCKS")) c->gather_blocks = atoi(v) > 0 ? atoi(v) : 128;

@@ -40,6 +40,13 @@ struct ht_ctx {
   uint64_t scratch_gen = 0;   // bumped whenever a scratch slot is (re)allocated: captured pointers into scratch are stale then
   void* scratch[HT_N_SCRATCH] = {};
   size_t scratch_bytes[HT_N_SCRATCH] = {};
+  // The device's statically allocated scratch array (ht_core.hip), its address taken once at ht_ctx_create.
+  // While static_mode is set (inside ht_layer_fwd_static) ht_scratch hands out pieces of it and nothing allocates.
+  unsigned char* static_base = nullptr;
+  bool static_mode = false;
+  size_t static_used = 0;
+  size_t static_off[HT_N_SCRATCH] = {};
+  size_t static_len[HT_N_SCRATCH] = {};
   // pinned host scratch (D2H staging of gradient rows)
   void* hscratch[3] = {nullptr, nullptr, nullptr};
   size_t hscratch_bytes[3] = {0, 0, 0};
@@ -77,6 +84,11 @@ int ht_set_err(ht_ctx* ctx, int code, const char* fmt, ...);
   } while (0)
 
 #define HT_LAUNCH_CHECK(ctx) HT_HIP(ctx, hipGetLastError())
+
+// HT_STATIC_SCRATCH_BYTES (hongtu.h): bytes of the statically allocated device scratch array that the
+// allocation-free entry point works in.
+void ht_static_begin(ht_ctx* ctx);   // ht_scratch serves from the static array until ht_static_end
+void ht_static_end(ht_ctx* ctx);
 
 // Device allocation with budget accounting.
 int ht_dev_alloc(ht_ctx* ctx, void** out, size_t bytes);

@@ -1053,6 +1053,37 @@ int ht_layer_fwd(ht_ctx* ctx, const ht_graph* g, const ht_layer_desc* desc, cons
   return finish(R, stats, t0, false);
 }
 
+// ht_layer_fwd for callers that cannot allocate: the same kernels in the same order, with the two scratch buffers of
+// the all-in-HBM path (the packed copy of W, the partial sums of cut rows) taken from the device's static array.
+int ht_layer_fwd_static(ht_ctx* ctx, const ht_graph* g, const ht_layer_desc* desc, const ht_tensor* H_in, const float* W,
+                        ht_tensor* H_out, ht_tensor* A_ckpt) {
+  if (!ctx) return HT_EINVAL;
+  if (!g || !desc || !H_in || !H_out || !A_ckpt || !W) return ht_set_err(ctx, HT_EINVAL, "ht_layer_fwd_static: null argument");
+  if (g->ctx != ctx) return ht_set_err(ctx, HT_ESTATE, "graph belongs to another context");
+  if (desc->d_in <= 0 || desc->d_out <= 0) return ht_set_err(ctx, HT_ESHAPE, "layer widths must be positive");
+  if (desc->order != HT_ORDER_AGG_FIRST) return ht_set_err(ctx, HT_EINVAL, "ht_layer_fwd_static: aggregate-first order only");
+  if (desc->gather_mode == HT_GATHER_BUFFER)
+    return ht_set_err(ctx, HT_EINVAL, "ht_layer_fwd_static: the neighbour buffer is not available here (rows are read in place)");
+  if (H_in->loc != HT_LOC_DEVICE || H_out->loc != HT_LOC_DEVICE || A_ckpt->loc != HT_LOC_DEVICE)
+    return ht_set_err(ctx, HT_ESHAPE, "ht_layer_fwd_static: H_in, H_out and A_ckpt must be in HBM");
+  // sizes are checked against the static array before anything is launched
+  const size_t need_w = (((size_t)desc->d_in + 15) & ~(size_t)15) * (((size_t)desc->d_out + 127) & ~(size_t)127) * 4;
+  const size_t need_p = (size_t)g->max_fpart * (size_t)A_ckpt->ld * 4;
+  if (need_w + need_p + 512 > HT_STATIC_SCRATCH_BYTES)
+    return ht_set_err(ctx, HT_ENOMEM, "ht_layer_fwd_static: this layer needs %zu bytes of scratch memory (packed W %zu, partial sums "
+                      "of %lld cut rows' items %zu); the static array holds %zu: use ht_layer_fwd", need_w + need_p, need_w,
+                      (long long)g->max_fpart, need_p, HT_STATIC_SCRATCH_BYTES);
+  HT_HIP(ctx, hipSetDevice(ctx->device));
+  ht_stats local{};
+  Run R(ctx, g, &local, false);
+  ht_static_begin(ctx);
+  int rc = layer_fwd_impl(R, desc, H_in, W, H_out, A_ckpt);
+  ht_static_end(ctx);
+  ctx->ev_next = 0;
+  if (rc != HT_OK) (void)hipStreamSynchronize(ctx->stream);
+  return rc;
+}
+
 int ht_layer_bwd(ht_ctx* ctx, const ht_graph* g, const ht_layer_desc* desc, const ht_tensor* ckpt, const float* W,
                  const ht_tensor* dH_out, const ht_tensor* H_out, ht_tensor* dH_in, float* dW, ht_stats* stats) {
   if (!ctx) return HT_EINVAL;
