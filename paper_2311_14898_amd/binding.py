@@ -478,7 +478,7 @@ class _DeviceArray:
                                          "version": 3, "strides": None}
 
 
-def ht_epoch_buffer_rows(ctx, kind: int, layer: int, rows) -> torch.Tensor:
+def ht_epoch_buffer_rows(ctx, kind: int, layer: int, rows, cols=None) -> torch.Tensor:
     """The data columns of the given rows (an index array or a slice) of an internal epoch buffer, as a CPU tensor; the rows
     are indexed where the buffer lives (HBM or pinned host memory), so a multi-gigabyte buffer is never copied whole."""
     t = ht_tensor()
@@ -488,11 +488,18 @@ def ht_epoch_buffer_rows(ctx, kind: int, layer: int, rows) -> torch.Tensor:
         whole = torch.as_tensor(_DeviceArray(t), device="cuda")
     else:
         whole = torch.from_numpy(np.ctypeslib.as_array(C.cast(C.c_void_p(t.ptr), C.POINTER(C.c_float)), shape=(int(t.rows), int(t.ld))))
+    if cols is not None:                             # a subset of the data columns, picked where the buffer lives
+        cidx = torch.as_tensor(np.asarray(cols, dtype=np.int64))
+        assert cidx.numel() == 0 or (int(cidx.min()) >= 0 and int(cidx.max()) < t.cols)
+        cidx = cidx.to(whole.device)
     if isinstance(rows, slice):                      # a contiguous row range
-        return whole[rows, : t.cols].cpu().clone()
-    idx = torch.as_tensor(np.asarray(rows, dtype=np.int64))
-    assert idx.numel() == 0 or (int(idx.min()) >= 0 and int(idx.max()) < t.rows)
-    return whole[idx.to(whole.device), : t.cols].cpu().clone()
+        part = whole[rows]
+    else:
+        idx = torch.as_tensor(np.asarray(rows, dtype=np.int64))
+        assert idx.numel() == 0 or (int(idx.min()) >= 0 and int(idx.max()) < t.rows)
+        part = whole[idx.to(whole.device)]
+    part = part[:, : t.cols] if cols is None else part[:, cidx]
+    return part.cpu().clone()
 
 
 def ht_tensor_to_host(ctx, t: ht_tensor) -> torch.Tensor:

@@ -117,16 +117,16 @@ def _scaled_epoch(name, scale, residency):
         note("loss checked")
         W_new = [x.cpu().numpy() for x in Wd]
         for l in range(L - 1, -1, -1):
-            def dz_rows(r):
-                gh = buf(B.HT_BUF_GH, l + 1, r).astype(np.float64)
-                return np.where(buf(B.HT_BUF_H, l + 1, r) > 0.0, gh, 0.0) if l < L - 1 else gh
+            def dz_rows(r, cols=None):
+                gh = B.ht_epoch_buffer_rows(ctx, B.HT_BUF_GH, l + 1, r, cols).numpy().astype(np.float64)
+                return np.where(B.ht_epoch_buffer_rows(ctx, B.HT_BUF_H, l + 1, r, cols).numpy() > 0.0, gh, 0.0) if l < L - 1 else gh
             # sampled columns of grad W^l = (a^l)^T dz over all vertices, block by block (numpy's fp64 product: the
             # oracle's transposed product walks a tall operand column by column)
             cols = np.unique(rng.integers(0, dims[l + 1], 6))
             gW_ref = np.zeros((dims[l], len(cols)))
             for r0 in range(0, V, BLOCK):
                 r = slice(r0, min(r0 + BLOCK, V))
-                gW_ref += buf(B.HT_BUF_A, l, r).T.astype(np.float64) @ np.ascontiguousarray(dz_rows(r)[:, cols])
+                gW_ref += buf(B.HT_BUF_A, l, r).T.astype(np.float64) @ dz_rows(r, cols)
             gW_dev = B.ht_epoch_buffer(ctx, B.HT_BUF_DW, l).numpy()
             assert (np.abs(gW_dev[:, cols] - gW_ref) <= 1e-4 * np.abs(gW_dev).max()).all(), f"grad W^{l} columns"
             assert_close_grad(W_new[l], Ws[l].astype(np.float64) - w.lr * gW_dev.astype(np.float64), f"W^{l} step")
