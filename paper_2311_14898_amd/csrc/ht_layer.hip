@@ -104,6 +104,9 @@ void cpu_accumulate(ht_ctx* ctx, float* grad, int64_t ld, const int32_t* ids, co
   for (auto& t : th) t.join();
 }
 
+// Destination rows from which the dense work of neighbouring chunks is no longer merged into one launch.
+constexpr int64_t HT_DENSE_MERGE_ROWS = 32768;
+
 struct Run {
   ht_ctx* ctx;
   const ht_graph* g;
@@ -304,6 +307,23 @@ int layer_fwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* H_in, con
   }
   hipEvent_t ev_out[2] = {nullptr, nullptr};   // D2H of the staging pair b has finished
   hipEvent_t ev_agg_prev = nullptr;            // the previous chunk's aggregation has read the buffer
+  // With a^l and h^{l+1} both in HBM the update stage of neighbouring chunks runs as one GEMM over their joint row
+  // range (chunks are balanced by edges, and a hub chunk of a thousand rows cannot fill the matrix cores); each output
+  // row is the same sum whatever range it is computed in.
+  const bool merge_dense = a_dev && h_dev;
+  int64_t pend0 = -1, pend1 = -1;
+  auto flush_dense = [&]() -> int {
+    if (pend0 < 0) return HT_OK;
+    const int64_t nr = pend1 - pend0;
+    R.tm.begin(&R.st->t_gemm_ms);
+    HT_TRY(ht_gemm_nn(ctx, P.s_c, A_ckpt->ptr + pend0 * a_ld, a_ld, W, H_out->ptr + pend0 * H_out->ld, H_out->ld, nr, di, dn,
+                      desc->act == HT_ACT_RELU));
+    R.tm.end();
+    R.st->n_gemm += 1;
+    R.st->gemm_flops += 2.0 * nr * di * dn;
+    pend0 = pend1 = -1;
+    return HT_OK;
+  };
   int q = 0;
   for (int j = 0; j < g->n; ++j) {
     const ChunkMeta& c = g->chunks[j];
@@ -330,6 +350,13 @@ int layer_fwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* H_in, con
     HT_TRY(spmm_chunk(R, j, buffer, buffer ? nbuf : Hin, H_in->ld, di, a_dst, a_ld));
     HT_TRY(P.agg_end());
     if (side_in) HT_TRY(P.rec(P.s_c, &ev_agg_prev));
+    if (merge_dense) {
+      if (pend0 >= 0 && c.dst0 != pend1) HT_TRY(flush_dense());   // not adjacent in vertex order (reorganised schedule)
+      if (pend0 < 0) pend0 = c.dst0;
+      pend1 = c.dst1;
+      if (pend1 - pend0 >= HT_DENSE_MERGE_ROWS) HT_TRY(flush_dense());
+      continue;
+    }
     float* h_dst = h_dev ? H_out->ptr + c.dst0 * H_out->ld : h_stage[b];
     R.tm.begin(&R.st->t_gemm_ms);
     HT_TRY(ht_gemm_nn(ctx, P.s_c, a_dst, a_ld, W, h_dst, H_out->ld, ndst, di, dn, desc->act == HT_ACT_RELU));
@@ -351,6 +378,7 @@ int layer_fwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* H_in, con
       HT_TRY(P.rec(P.s_out, &ev_out[b]));
     }
   }
+  HT_TRY(flush_dense());
   // later work on the compute stream sees every row at its home
   HT_TRY(P.wait(P.s_c, ev_out[0]));
   HT_TRY(P.wait(P.s_c, ev_out[1]));
@@ -554,9 +582,27 @@ int layer_bwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* ckpt, con
   float* z_stage[2] = {nullptr, nullptr};
   float *dz_chunk = nullptr, *da_chunk = nullptr, *gbuf = nullptr;
   const int64_t a_ld = agg_ckpt ? ckpt->ld : ld_i;
+  // The dense work (mask, grad W, grad a) of neighbouring chunks runs as one launch over their joint row range when
+  // everything it touches is in HBM and no buffer is updated in place between chunks: chunks are balanced by edges, and a
+  // hub chunk of a thousand rows cannot fill the matrix cores.  The grouping depends on the graph and on where the
+  // tensors live only, so every intermediate-data mode sums grad W in the same order.  Each group is a run of chunks
+  // adjacent in schedule and in vertex order, closed once it holds HT_DENSE_MERGE_ROWS rows; elsewhere one chunk each.
+  const bool merge_ok = !in_host && !agg_buffer && !(dH_in && gbuffer);
+  std::vector<std::pair<int, int>> groups;
+  int64_t gmax = mx;
+  for (int j = 0; j < g->n;) {
+    int k = j;
+    if (merge_ok && g->chunks[j].dst1 > g->chunks[j].dst0)
+      while (k + 1 < g->n && g->chunks[k + 1].dst1 > g->chunks[k + 1].dst0 && g->chunks[k + 1].dst0 == g->chunks[k].dst1 &&
+             g->chunks[k].dst1 - g->chunks[j].dst0 < HT_DENSE_MERGE_ROWS)
+        ++k;
+    groups.emplace_back(j, k);
+    gmax = std::max(gmax, g->chunks[k].dst1 - g->chunks[j].dst0);
+    j = k + 1;
+  }
   if (!agg_ckpt || a_host) {
-    HT_TRY(ht_scratch(ctx, HT_S_ACHUNK, (size_t)mx * a_ld * 4 * 2, (void**)&a_stage[0]));
-    a_stage[1] = a_stage[0] + mx * a_ld;
+    HT_TRY(ht_scratch(ctx, HT_S_ACHUNK, (size_t)gmax * a_ld * 4 * 2, (void**)&a_stage[0]));
+    a_stage[1] = a_stage[0] + gmax * a_ld;
   }
   if (dh_host) {
     HT_TRY(ht_scratch(ctx, HT_S_OCHUNK, (size_t)mx * dH_out->ld * 4 * 2, (void**)&dh_stage[0]));
@@ -565,13 +611,13 @@ int layer_bwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* ckpt, con
   if (relu) {
     const int64_t zl = H_out ? H_out->ld : ld_o;
     if (!H_out || ho_host) {
-      HT_TRY(ht_scratch(ctx, HT_S_ZCHUNK, (size_t)mx * zl * 4 * 2, (void**)&z_stage[0]));
-      z_stage[1] = z_stage[0] + mx * zl;
+      HT_TRY(ht_scratch(ctx, HT_S_ZCHUNK, (size_t)gmax * zl * 4 * 2, (void**)&z_stage[0]));
+      z_stage[1] = z_stage[0] + gmax * zl;
     }
-    HT_TRY(ht_scratch(ctx, HT_S_DZCHUNK, (size_t)mx * ld_o * 4, (void**)&dz_chunk));
+    HT_TRY(ht_scratch(ctx, HT_S_DZCHUNK, (size_t)gmax * ld_o * 4, (void**)&dz_chunk));
   }
   if (dH_in) {
-    HT_TRY(ht_scratch(ctx, HT_S_DACHUNK, (size_t)mx * ld_i * 4, (void**)&da_chunk));
+    HT_TRY(ht_scratch(ctx, HT_S_DACHUNK, (size_t)gmax * ld_i * 4, (void**)&da_chunk));
     if (gbuffer) HT_TRY(ht_scratch(ctx, HT_S_MISC, (size_t)g->cache_rows * ld_i * 4, (void**)&gbuf));
   }
   // CPU-side accumulation (Alg. 3): host copy of the leave lists, device and pinned staging pairs
@@ -663,9 +709,10 @@ int layer_bwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* ckpt, con
     }
     return HT_OK;
   };
-  for (int j = 0; j < g->n; ++j) {
-    const ChunkMeta& c = g->chunks[j];
-    const int64_t ndst = c.dst1 - c.dst0;
+  for (const auto& grp : groups) {
+    const int j0 = grp.first, j1 = grp.second;
+    const ChunkMeta& c = g->chunks[j0];                       // the group's first chunk: its rows start the range
+    const int64_t ndst = g->chunks[j1].dst1 - c.dst0;         // destination rows of the whole group
     if (ndst == 0) {   // no destinations: no edges, no neighbours; the schedule may still release rows here
       HT_TRY(leave_rows(c));
       continue;
@@ -713,11 +760,14 @@ int layer_bwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* ckpt, con
       HT_TRY(P.wait(P.s_c, ev_in));
     }
     // ---- compute
-    if (!agg_ckpt) {   // pure recomputation: aggregate again from h^l
-      if (agg_buffer) HT_TRY(gather_chunk(R, j, ckpt, Hin, di, nbuf, st));
-      HT_TRY(P.agg_begin());
-      HT_TRY(spmm_chunk(R, j, agg_buffer, agg_buffer ? nbuf : Hin, ckpt->ld, di, a_stage[b], a_ld));
-      HT_TRY(P.agg_end());
+    if (!agg_ckpt) {   // pure recomputation: aggregate again from h^l, chunk by chunk into the group's rows
+      for (int j = j0; j <= j1; ++j) {
+        const ChunkMeta& cj = g->chunks[j];
+        if (agg_buffer) HT_TRY(gather_chunk(R, j, ckpt, Hin, di, nbuf, st));
+        HT_TRY(P.agg_begin());
+        HT_TRY(spmm_chunk(R, j, agg_buffer, agg_buffer ? nbuf : Hin, ckpt->ld, di, a_stage[b] + (cj.dst0 - c.dst0) * a_ld, a_ld));
+        HT_TRY(P.agg_end());
+      }
       a_rows = a_stage[b];
     }
     const float* dz_rows = dh_rows;
@@ -750,44 +800,47 @@ int layer_bwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* ckpt, con
       R.st->gemm_flops += 2.0 * ndst * di * dn;
     }
     if (in_host) HT_TRY(P.rec(P.s_c, &ev_cdone[b]));   // the staged inputs have been consumed
-    if (dH_in) {
-      float* partial = nullptr;
-      const int64_t out_ld = gbuffer ? ld_i : dH_in->ld;
-      if (c.bwd.n_part > 0) HT_TRY(ht_scratch(ctx, HT_S_SPART, (size_t)g->max_bpart * out_ld * 4, (void**)&partial));
-      SpmmArgs a{};
-      a.it_row = c.bwd.row; a.it_e0 = c.bwd.e0; a.it_len = c.bwd.len; a.it_part = c.bwd.part; a.n_items = c.bwd.n_items;
-      a.n_edges = c.nnz;
-      a.fx_row = c.bwd.fx_row; a.fx_part0 = c.bwd.fx_part0; a.fx_nseg = c.bwd.fx_nseg; a.n_fix = c.bwd.n_fix;
-      if (g->merged) {
-        a.idx = g->usdst.p + c.ue0;
-        a.w_edge = g->uw_bwd.p + c.ue0;
-        a.n_edges = c.nu;
-      } else {
-        a.idx = g->sdst.p + c.e0;
-        a.ew = g->s.p + c.dst0;
+    for (int j = j0; j <= j1; ++j) {
+      const ChunkMeta& cj = g->chunks[j];
+      if (dH_in) {
+        float* partial = nullptr;
+        const int64_t out_ld = gbuffer ? ld_i : dH_in->ld;
+        if (cj.bwd.n_part > 0) HT_TRY(ht_scratch(ctx, HT_S_SPART, (size_t)g->max_bpart * out_ld * 4, (void**)&partial));
+        SpmmArgs a{};
+        a.it_row = cj.bwd.row; a.it_e0 = cj.bwd.e0; a.it_len = cj.bwd.len; a.it_part = cj.bwd.part; a.n_items = cj.bwd.n_items;
+        a.n_edges = cj.nnz;
+        a.fx_row = cj.bwd.fx_row; a.fx_part0 = cj.bwd.fx_part0; a.fx_nseg = cj.bwd.fx_nseg; a.n_fix = cj.bwd.n_fix;
+        if (g->merged) {
+          a.idx = g->usdst.p + cj.ue0;
+          a.w_edge = g->uw_bwd.p + cj.ue0;
+          a.n_edges = cj.nu;
+        } else {
+          a.idx = g->sdst.p + cj.e0;
+          a.ew = g->s.p + cj.dst0;
+        }
+        a.src = da_chunk + (cj.dst0 - c.dst0) * ld_i;      // the chunk's rows inside the group's grad a
+        a.src_ld = ld_i;
+        a.d = di;
+        a.out = gbuffer ? gbuf : dH_in->ptr;
+        a.out_ld = out_ld;
+        a.out_idx = gbuffer ? g->gslot.p + cj.nbr_off : g->nbr.p + cj.nbr_off;
+        a.post = g->s.p;
+        a.post_idx = g->nbr.p + cj.nbr_off;
+        a.accumulate = 1;
+        a.partial = partial;
+        a.max_slabs = ctx->slabs_bwd;
+        HT_TRY(P.wait(P.s_c, ev_stored));   // positions freed by the last store are written from here on
+        HT_TRY(P.agg_begin());
+        R.tm.begin(&R.st->t_spmm_bwd_ms);
+        HT_TRY(ht_spmm_launch(ctx, st, a));
+        R.tm.end();
+        HT_TRY(P.agg_end());
+        R.st->n_spmm_bwd += 1;
+        R.st->edges += cj.nnz;
+        R.st->spmm_bwd_alg_bytes += spmm_alg_bytes(cj, di);
       }
-      a.src = da_chunk;
-      a.src_ld = ld_i;
-      a.d = di;
-      a.out = gbuffer ? gbuf : dH_in->ptr;
-      a.out_ld = out_ld;
-      a.out_idx = gbuffer ? g->gslot.p + c.nbr_off : g->nbr.p + c.nbr_off;
-      a.post = g->s.p;
-      a.post_idx = g->nbr.p + c.nbr_off;
-      a.accumulate = 1;
-      a.partial = partial;
-      a.max_slabs = ctx->slabs_bwd;
-      HT_TRY(P.wait(P.s_c, ev_stored));   // positions freed by the last store are written from here on
-      HT_TRY(P.agg_begin());
-      R.tm.begin(&R.st->t_spmm_bwd_ms);
-      HT_TRY(ht_spmm_launch(ctx, st, a));
-      R.tm.end();
-      HT_TRY(P.agg_end());
-      R.st->n_spmm_bwd += 1;
-      R.st->edges += c.nnz;
-      R.st->spmm_bwd_alg_bytes += spmm_alg_bytes(c, di);
+      HT_TRY(leave_rows(cj));
     }
-    HT_TRY(leave_rows(c));
   }
   if (first) HT_TRY(ht_fill_zero(ctx, st, dW, (size_t)di * dn * 4));
   if (store_home) {   // dH_in is complete for later work on the stream
