@@ -44,8 +44,9 @@ def cpu_baseline(w, src_cpu, dst_cpu, X, y, Ws):
     if epoch_flops(w) < 1.5e12:
         indptr, col = orc.csc_build(V, src_cpu, dst_cpu, add_self_loops=True)
         t0 = time.perf_counter()
-        ref = orc.gcn_epoch(indptr, col, dims, X.numpy(), [x.numpy() for x in Ws], y.numpy(), lr=w.lr, want=())
+        ref = orc.gcn_epoch(indptr, col, dims, X.numpy(), [x.numpy() for x in Ws], y.numpy(), lr=w.lr, want=("a", "z", "gh"))
         t = time.perf_counter() - t0
+        ref["indptr"], ref["col"] = indptr, col
         return {"value": t, "unit": "s/epoch", "cores": cores, "kind": "oracle",
                 "sample": f"one whole epoch of the fp64 oracle (forward, loss, backward, update) on the same graph and "
                           f"inputs, {t:.1f} s; CSC construction not timed", "oracle_loss": ref["loss"],
@@ -202,6 +203,29 @@ def epoch_plan(B, w, residency="workload", hbm_budget_gb=0.0, inter="auto"):
     plan["hbm_budget_bytes"] = int(hbm_budget_gb * 1e9)
     plan["inter"] = {"auto": B.HT_INTER_AUTO, "hybrid": B.HT_INTER_HYBRID, "recompute": B.HT_INTER_RECOMPUTE}[inter]
     return host, plan
+
+
+def gw_parity(ref, gW_dev, w, Ws):
+    """Weight gradients of the device's first epoch against the oracle's.  A pre-activation within fp32 rounding of 0 gets
+    ReLU' = 0 or 1 with equal right, and one such element at a hub vertex moves an entry of grad W (a sum of |V| terms of
+    random sign) by up to a per cent: the oracle's own values say which elements those are and how far each can move the
+    gradient (oracle/ties.py), and the device must lie within that interval to the tolerance."""
+    import numpy as np
+    from oracle.ties import relu_tie_slack
+    slack = relu_tie_slack(ref, ref["indptr"], ref["col"], [x.numpy() for x in Ws], w.dims)
+    raw = outside = width = 0.0
+    n_ties = 0
+    for l in range(w.n_layers):
+        lo, hi, ties = slack[l]
+        m = float(np.abs(ref["gW"][l]).max())
+        err = gW_dev[l].astype(np.float64) - ref["gW"][l]
+        out = np.maximum(err - hi, 0.0) + np.minimum(err - lo, 0.0)
+        raw, outside, width = max(raw, float(np.abs(err).max()) / m), max(outside, float(np.abs(out).max()) / m), max(width, float(max(hi.max(), -lo.min())) / m)
+        n_ties += len(ties[0])
+    return {"max_rel_outside_tie_interval": outside, "max_rel_raw": raw, "undecidable_pre_activations": n_ties,
+            "tie_interval_max_rel_width": width,
+            "note": "max_rel_outside_tie_interval is the figure the 1e-4 tolerance applies to; max_rel_raw compares with the oracle's "
+                    "own fp64 decisions on the undecidable elements"}
 
 
 PCIE_NOMINAL_GBS = 64.0        # PCIe 5.0 x16, one direction
@@ -545,10 +569,11 @@ def main():
                              "loss_rel": abs(loss_epoch1 - ref["loss"]) / abs(ref["loss"]),
                              "w_new_max_rel": max(float(np.abs(W_epoch1[l] - ref["W_new"][l]).max() / np.abs(ref["W_new"][l]).max())
                                                   for l in range(L)),
-                             "gw_max_rel": max(float(np.abs(gW_epoch1[l] - ref["gW"][l]).max() / np.abs(ref["gW"][l]).max()) for l in range(L)),
+                             "gw": gw_parity(ref, gW_epoch1, w, Ws),
                              "tolerance": 1e-4,
                              "note": "the device's first epoch from the seeded weights against the fp64 oracle's epoch on the same "
-                                     "inputs: loss, updated weights and weight gradients (max-norm error over each matrix / its largest entry)"}
+                                     "inputs: loss and updated weights (max-norm error over each matrix / its largest entry); gw: the weight gradients, "
+                                     "where a ReLU derivative that fp32 cannot decide moves whole entries (see its note)"}
     if args.partitions > 0:
         out["reorganization"] = plan_partitions(ctx, w, src, dst, args.partitions)
     B.ht_graph_destroy(g)
