@@ -505,6 +505,23 @@ def main():
         n0 = B.ht_ctx_graph_launches(ctx)
         graph_run = {"eager_no_stats_ms_per_step": plain(False), "graph_ms_per_step": plain(True),
                      "graph_launches": B.ht_ctx_graph_launches(ctx) - n0}
+    gather_hbm = None
+    if not host and not args.no_other_order:
+        # The row gather with an HBM source (Alg. 2 when the layer input lives in HBM; the epochs above read it in place
+        # instead): layer 0 through the in-place neighbour buffer, three passes, the gather kernels' own HIP-event time.
+        Ho, Ao = B.alloc_matrix(w.V, w.dims[1], zero=False), B.alloc_matrix(w.V, w.dims[0], zero=False)
+        gt, gr = 0.0, 0
+        for _ in range(3):
+            gst = B.ht_layer_fwd(ctx, g, w.dims[0], w.dims[1], B.HT_ACT_RELU, Xd, Wd[0], Ho, A_ckpt=Ao,
+                                 gather_mode=B.HT_GATHER_BUFFER, want_stats=True)
+            gt, gr = gt + gst.t_gather_ms, gr + gst.rows_loaded
+        del Ho, Ao
+        gbytes = gr * (2.0 * 4.0 * w.dims[0] + 4.0)
+        gather_hbm = {"kernel": "k_rows<0>, HBM source, layer 0 (d = %d)" % w.dims[0], "rows_per_pass": gr // 3,
+                      "algorithmic_bytes_per_pass": gbytes / 3, "ms_per_pass": gt / 3,
+                      "achieved": gbytes / max(gt * 1e-3, 1e-12) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                      "frac": gbytes / max(gt * 1e-3, 1e-12) / 1e9 / HBM_PEAK_GBS,
+                      "note": "read + write of every loaded row and its index; not part of value (HBM-resident inputs are read in place)"}
     ms_per_step = 1e3 * elapsed / args.steps
     Ep = info.E_stored
     L = w.n_layers
@@ -553,7 +570,7 @@ def main():
            "bytes_h2d_nodedup_per_step": tot["bytes_h2d_nodedup"] / args.steps,
            "input_generation_s": t_gen,
            "paper_context": "HongTu-IM 2-layer GCN on reddit (same shape), 1xA100: 0.20 s/epoch (Table 4); other hardware, real dataset",
-           "phase_pass": phase_pass, "order": args.order, "other_order": other, "input_aggregate_reuse": reuse_run, "hip_graph": graph_run,
+           "phase_pass": phase_pass, "order": args.order, "other_order": other, "input_aggregate_reuse": reuse_run, "hip_graph": graph_run, "gather_hbm": gather_hbm,
            "plan": {"inter": ["auto", "mask", "hybrid", "recompute"][tot["plan_inter"] // args.steps],
                     "h": ["-", "hbm", "host"][tot["plan_res_h"] // args.steps],
                     "a": ["-", "hbm", "host"][tot["plan_res_a"] // args.steps],
