@@ -603,7 +603,7 @@ def main():
         torch.cuda.empty_cache()
         out["configs"] = []
         for name, scale, residency, cache in (("cfg3", 1.0, "workload", "adjacent"), ("cfg3", 1.0, "workload", "farthest"),
-                                              ("cfg5", 0.35, "h-host", "adjacent")):
+                                              ("cfg4", 0.07, "workload", "adjacent"), ("cfg5", 0.35, "h-host", "adjacent")):
             try:
                 out["configs"].append(offload_config(name, scale, residency, cache, 3, 1, cpu_s_per_flop, note))
             except Exception as e:                       # the headline line must still be printed
