@@ -83,7 +83,7 @@ __global__ void k_bounds(const int64_t* __restrict__ indptr, int64_t V, const in
 // destination) and is skipped.  The bit is tested twice before the atomic: with a plain load, which the CU's own
 // cache serves (its view can only lag behind: a bit seen set is set, and most entries stop here), then with a
 // device-scope load, which sees the bits other XCDs have set (a stale plain view alone would send the hub sources'
-// words to an atomic per entry).  cfg2: 346 -> about 200 us per chunk.
+// words to an atomic per entry).  cfg2: 346 -> 258 us per launch.
 #ifndef HT_MARK_PLAIN_FIRST
 #define HT_MARK_PLAIN_FIRST 1
 #endif
