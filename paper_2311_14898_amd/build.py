@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhongtu.so")
 OBJ = os.path.join(HERE, "_build")
 SOURCES = ["ht_core.hip", "ht_prims.hip", "ht_partition.hip", "ht_spmm.hip", "ht_gemm.hip", "ht_elem.hip",
-           "ht_layer.hip", "ht_gat.hip"]
+           "ht_layer.hip", "ht_gat.hip", "ht_fused.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

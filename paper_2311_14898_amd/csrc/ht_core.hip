@@ -202,6 +202,7 @@ int ht_ctx_create(ht_ctx** out, int device, void* hip_stream) {
   if (const char* v = getenv("HT_AGG_UNROLL")) c->agg_unroll = atoi(v) == 8 ? 8 : 4;
   if (const char* v = getenv("HT_AGG_UNIFORM")) c->agg_uniform = atoi(v);
   if (const char* v = getenv("HT_SLAB_ALIGN")) c->slab_align = atoi(v);
+  if (const char* v = getenv("HT_FUSE_UPDATE")) c->fuse_update = atoi(v);
   if (const char* v = getenv("HT_AGG_PHASES")) c->agg_phases = atoi(v) > 1 ? atoi(v) : 1;
   if (const char* v = getenv("HT_LINK_BLOCK_ROWS")) c->link_block_rows = atoll(v) > 0 ? atoll(v) : c->link_block_rows;
   if (hip_stream) {

@@ -317,6 +317,17 @@ int gemm_nn_packed(ht_ctx* ctx, hipStream_t st, const float* A, int64_t lda, con
 }  // namespace
 
 // scratch slots: 0 = packed W, 1 = TN partial tiles
+// Bp = the zero-padded, tile-aligned copy of W [K x N] that the NN kernels read ([round_up(K, 16) x round_up(N, 128)], in
+// the context's scratch); *Np its row pitch.
+int ht_pack_w(ht_ctx* ctx, hipStream_t st, const float* W, int32_t K, int32_t N, float** Bp, int* Np) {
+  const int Kp = round_up(K, BK), Npp = round_up(N, 128);
+  HT_TRY(ht_scratch(ctx, HT_S_PACKW, (size_t)Kp * Npp * 4, (void**)Bp));
+  k_pack_b<<<(unsigned)(((int64_t)Kp * Npp + 255) / 256), 256, 0, st>>>(W, K, N, 0, *Bp, Kp, Npp);
+  HT_LAUNCH_CHECK(ctx);
+  *Np = Npp;
+  return HT_OK;
+}
+
 int ht_gemm_nn(ht_ctx* ctx, hipStream_t st, const float* A, int64_t lda, const float* B, float* C, int64_t ldc,
                int64_t M, int32_t K, int32_t N, int relu) {
   if (lda & 3) return ht_set_err(ctx, HT_ESHAPE, "gemm: row pitch must be a multiple of 4");

@@ -64,6 +64,7 @@ struct ht_ctx {
   int agg_phases = 1;     // HT_AGG_PHASES: slabs are spread over this many consecutive launches
   int64_t link_block_rows = (int64_t)1 << 20;   // HT_LINK_BLOCK_ROWS: rows per staged block of a host-resident tensor (GAT path)
   int agg_variant = 0;  // 0: feature slabs per XCD; 1: full-width rows per wave (HT_AGG_VARIANT, for A/B runs)
+  int fuse_update = 0;  // HT_FUSE_UPDATE=1: layers that keep no aggregate run aggregate + transform as one kernel (A/B)
   int n_threads = 0;  // host threads for CPU-side accumulation (0 = chosen on first use)
 };
 
@@ -302,6 +303,10 @@ int ht_gemm_nt(ht_ctx* ctx, hipStream_t st, const float* A, int64_t lda, const f
 // C[K x N] (+)= A[M x K]^T B[M x N]; fixed-order reduction over M slices.
 int ht_gemm_tn(ht_ctx* ctx, hipStream_t st, const float* A, int64_t lda, const float* B, int64_t ldb, float* C,
                int64_t M, int32_t K, int32_t N, int accumulate);
+
+// Aggregate + transform of one chunk in one kernel, the aggregate kept in LDS (ht_fused.hip)
+int ht_agg_update_fused(ht_ctx* ctx, hipStream_t st, const ht_graph* g, const ChunkMeta& c, const float* H_in, int64_t in_ld,
+                        int32_t d_in, const float* W, int32_t d_out, int relu, float* H_out, int64_t out_ld);
 
 // Elementwise / loss (ht_elem.hip)
 // dz = dh * [ref > 0]

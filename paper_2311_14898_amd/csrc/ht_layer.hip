@@ -287,7 +287,9 @@ int layer_fwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* H_in, con
   float* a_stage[2] = {nullptr, nullptr};
   float* h_stage[2] = {nullptr, nullptr};
   float* nbuf = nullptr;
-  if (!a_dev) {
+  // A/B variant: no aggregate is kept and everything is in HBM: aggregate and transform in one kernel (ht_fused.hip)
+  const bool fused = ctx->fuse_update && !A_ckpt && h_dev && !buffer && H_in->loc == HT_LOC_DEVICE && di <= 1024;
+  if (!a_dev && !fused) {
     HT_TRY(ht_scratch(ctx, HT_S_ACHUNK, (size_t)mx * a_ld * 4 * 2, (void**)&a_stage[0]));
     a_stage[1] = a_stage[0] + mx * a_ld;
   }
@@ -343,6 +345,20 @@ int layer_fwd_impl(Run& R, const ht_layer_desc* desc, const ht_tensor* H_in, con
       } else {
         HT_TRY(gather_chunk(R, j, H_in, Hin, di, nbuf, P.s_c));
       }
+    }
+    if (fused) {
+      const int li = R.layer < HT_MAX_LAYERS ? R.layer : HT_MAX_LAYERS - 1;
+      R.tm.begin(&R.st->t_agg_fwd_layer_ms[li]);
+      HT_TRY(ht_agg_update_fused(ctx, P.s_c, g, c, Hin, H_in->ld, di, W, dn, desc->act == HT_ACT_RELU, H_out->ptr, H_out->ld));
+      R.tm.end();
+      R.st->n_spmm_fwd += 1;
+      R.st->n_agg_fwd_layer[li] += 1;
+      R.st->edges += c.nnz;
+      R.st->spmm_fwd_alg_bytes += spmm_alg_bytes(c, di);
+      R.st->agg_fwd_layer_alg_bytes[li] += spmm_alg_bytes(c, di);
+      R.st->n_gemm += 1;
+      R.st->gemm_flops += 2.0 * ndst * di * dn;
+      continue;
     }
     if (staged) HT_TRY(P.wait(P.s_c, ev_out[b]));
     float* a_dst = a_dev ? A_ckpt->ptr + c.dst0 * a_ld : a_stage[b];
