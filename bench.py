@@ -137,7 +137,10 @@ def main_gat(args):
            "config": {"workload": f"{w.name}: {L}-layer GAT (one head), R-MAT V={w.V} E={w.E} (+{w.V} self-loops), dims "
                                   f"{'-'.join(map(str, w.dims))}, {w.n_chunks} chunks, vertex data in "
                                   f"{'pinned host memory (t = HW of a layer in HBM)' if host else 'HBM'}", "scale": args.scale},
-           "loss": loss, "gteps": tot["edges"] / elapsed / 1e9,
+           "loss_after_steps": loss,
+           "loss_after_steps_is": f"the loss of the last timed epoch: epoch {args.warmup + args.steps} of training from the seeded "
+                                  "parameters (cpu_baseline.oracle_loss is epoch 1's)",
+           "gteps": tot["edges"] / elapsed / 1e9,
            "bytes_h2d_per_step": tot["bytes_h2d"] / K, "bytes_d2h_per_step": tot["bytes_d2h"] / K,
            "phase_ms_per_step": {"softmax": tot["t_gat_softmax_ms"] / K, "aggregate_fwd": tot["t_spmm_fwd_ms"] / K,
                                  "destination_pass": tot["t_gat_dst_ms"] / K, "source_pass": src_ms,
