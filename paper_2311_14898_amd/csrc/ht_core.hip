@@ -235,7 +235,7 @@ int ht_ctx_destroy(ht_ctx* ctx) {
   ht_epoch_ws_free(ctx);
   for (int i = 0; i < HT_N_SCRATCH; ++i)
     if (ctx->scratch[i]) ht_dev_free(ctx, ctx->scratch[i], ctx->scratch_bytes[i]);
-  for (int i = 0; i < 3; ++i)
+  for (int i = 0; i < 4; ++i)
     if (ctx->hscratch[i]) (void)hipHostFree(ctx->hscratch[i]);
   for (hipEvent_t e : ctx->ev_pool) (void)hipEventDestroy(e);
   if (ctx->own_stream) (void)hipStreamDestroy(ctx->stream);

@@ -47,9 +47,9 @@ struct ht_ctx {
   size_t static_used = 0;
   size_t static_off[HT_N_SCRATCH] = {};
   size_t static_len[HT_N_SCRATCH] = {};
-  // pinned host scratch (D2H staging of gradient rows)
-  void* hscratch[3] = {nullptr, nullptr, nullptr};
-  size_t hscratch_bytes[3] = {0, 0, 0};
+  // pinned host scratch (slots 0-2: D2H staging of gradient rows; HT_HS_READBACK: small counts read back by ht_partition)
+  void* hscratch[4] = {nullptr, nullptr, nullptr, nullptr};
+  size_t hscratch_bytes[4] = {0, 0, 0, 0};
   int xcd_contig = 0;     // 1: XCDs take contiguous parts of the item list instead of interleaving it
                           // (HT_XCD_CONTIG; measured slower at cfg2: 30.7 vs 26.0 ms per epoch)
   int no_link_fence = 0;  // 1: let aggregation kernels overlap link traffic (HT_NO_LINK_FENCE, for A/B runs)
@@ -97,6 +97,7 @@ void ht_dev_free(ht_ctx* ctx, void* p, size_t bytes);
 // Grow-only scratch slot (kept on the context).
 int ht_scratch(ht_ctx* ctx, int slot, size_t bytes, void** out);
 // Grow-only pinned host scratch.
+constexpr int HT_HS_READBACK = 3;
 int ht_host_scratch(ht_ctx* ctx, int slot, size_t bytes, void** out);
 
 template <typename T>
@@ -104,14 +105,15 @@ struct DevArr {
   T* p = nullptr;
   size_t n = 0;
   ht_ctx* ctx = nullptr;
+  bool owned = true;   // false: a view into a block that another DevArr owns
   DevArr() = default;
   DevArr(const DevArr&) = delete;
   DevArr& operator=(const DevArr&) = delete;
-  DevArr(DevArr&& o) noexcept : p(o.p), n(o.n), ctx(o.ctx) { o.p = nullptr; o.n = 0; }
+  DevArr(DevArr&& o) noexcept : p(o.p), n(o.n), ctx(o.ctx), owned(o.owned) { o.p = nullptr; o.n = 0; }
   DevArr& operator=(DevArr&& o) noexcept {
     if (this != &o) {
       release();
-      p = o.p; n = o.n; ctx = o.ctx;
+      p = o.p; n = o.n; ctx = o.ctx; owned = o.owned;
       o.p = nullptr; o.n = 0;
     }
     return *this;
@@ -121,15 +123,38 @@ struct DevArr {
     release();
     ctx = c;
     n = count;
+    owned = true;
     if (count == 0) return HT_OK;
     return ht_dev_alloc(c, (void**)&p, count * sizeof(T));
   }
   void release() {
-    if (p) ht_dev_free(ctx, p, n * sizeof(T));
+    if (p && owned) ht_dev_free(ctx, p, n * sizeof(T));
     p = nullptr;
     n = 0;
   }
   size_t bytes() const { return n * sizeof(T); }
+};
+
+// Arrays of one lifetime carved out of one device allocation: an allocation and its release cost tens of
+// microseconds each whatever their size, and ht_partition makes dozens.  add() every array first, then
+// alloc(), then take() them in the same order; every array starts on a 256-byte boundary.
+struct DevBlock {
+  DevArr<char> mem;
+  size_t planned = 0, taken = 0;
+  static size_t pad(size_t b) { return (b + 255) & ~(size_t)255; }
+  template <typename T>
+  void add(size_t count) { planned += pad(count * sizeof(T)); }
+  int alloc(ht_ctx* c) { taken = 0; return mem.alloc(c, planned > 0 ? planned : 1); }
+  template <typename T>
+  void take(DevArr<T>& a, size_t count) {
+    a.release();
+    a.ctx = mem.ctx;
+    a.owned = false;
+    a.n = count;
+    a.p = (T*)(mem.p + taken);
+    taken += pad(count * sizeof(T));
+  }
+  void release() { mem.release(); planned = taken = 0; }
 };
 
 static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -232,6 +257,7 @@ struct ht_graph {
   DevArr<int32_t> usdst;       // [n_unique] local destination of each distinct pair, by-source order
   DevArr<float> uw_bwd;        // [n_unique] multiplicity * s[destination]
   DevArr<float> umult_bwd;     // [n_unique] multiplicity, by-source order
+  DevBlock blk_pairs, blk_chunks;   // the allocations behind the distinct-pair arrays and the per-chunk arenas
   int64_t v_ori = 0, v_ru = 0, v_load = 0;  // v_load: rows actually loaded per pass with this buffer
   int64_t max_nsrc = 0, max_ndst = 0, max_nnz = 0, max_fpart = 0, max_bpart = 0;
   int64_t cache_rows = 0;

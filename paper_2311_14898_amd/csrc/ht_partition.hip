@@ -269,6 +269,17 @@ __global__ void k_remap(const int32_t* __restrict__ col, int64_t nnz, const uint
 }
 
 // key = (local source << 32) | local destination, one thread per edge
+__global__ void k_set_i64(int64_t* p, int64_t v) { *p = v; }
+
+// a[at[i]] and b[at[i]] (b may be null) for a handful of positions
+__global__ void k_gather_offsets(const int64_t* __restrict__ a, const int64_t* __restrict__ b, const int64_t* __restrict__ at,
+                                 int64_t n, int64_t* __restrict__ out_a, int64_t* __restrict__ out_b) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  out_a[i] = a[at[i]];
+  out_b[i] = b ? b[at[i]] : 0;
+}
+
 __global__ void k_csr_keys(const int64_t* __restrict__ indptr, int64_t dst0, int64_t dst1, int64_t e0, int64_t nnz,
                            const int32_t* __restrict__ col_local, uint64_t* __restrict__ keys) {
   int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -451,16 +462,21 @@ int bits_for(int64_t n) {  // bits needed for values 0..n-1 (at least 1)
 }
 
 struct ItemTmp {
+  DevBlock blk;
   DevArr<int32_t> nseg, npart, isfix;
   DevArr<int64_t> it_base, part_base, fix_base;
   DevArr<char> stage;   // items in row order, before they are permuted into dispatch order
+  int64_t* totals = nullptr;   // pinned host memory for the three counts of a build_items call (set by the caller)
   int alloc(ht_ctx* ctx, int64_t maxrows) {
-    HT_TRY(nseg.alloc(ctx, maxrows));
-    HT_TRY(npart.alloc(ctx, maxrows));
-    HT_TRY(isfix.alloc(ctx, maxrows));
-    HT_TRY(it_base.alloc(ctx, maxrows + 1));
-    HT_TRY(part_base.alloc(ctx, maxrows + 1));
-    HT_TRY(fix_base.alloc(ctx, maxrows + 1));
+    for (int k = 0; k < 3; ++k) blk.add<int32_t>(maxrows);
+    for (int k = 0; k < 3; ++k) blk.add<int64_t>(maxrows + 1);
+    HT_TRY(blk.alloc(ctx));
+    blk.take(nseg, maxrows);
+    blk.take(npart, maxrows);
+    blk.take(isfix, maxrows);
+    blk.take(it_base, maxrows + 1);
+    blk.take(part_base, maxrows + 1);
+    blk.take(fix_base, maxrows + 1);
     return HT_OK;
   }
 };
@@ -478,7 +494,7 @@ int build_items(ht_ctx* ctx, ItemTmp& t, const int64_t* ptr, int64_t ptr0, int64
   HT_TRY(ht_scan_i32(ctx, t.nseg.p, t.it_base.p, nrows, true));
   HT_TRY(ht_scan_i32(ctx, t.npart.p, t.part_base.p, nrows, true));
   HT_TRY(ht_scan_i32(ctx, t.isfix.p, t.fix_base.p, nrows, true));
-  int64_t tot[3];
+  int64_t* tot = t.totals;   // pinned: the three copies are queued without a stall each
   HT_HIP(ctx, hipMemcpyAsync(&tot[0], t.it_base.p + nrows, 8, hipMemcpyDeviceToHost, st));
   HT_HIP(ctx, hipMemcpyAsync(&tot[1], t.part_base.p + nrows, 8, hipMemcpyDeviceToHost, st));
   HT_HIP(ctx, hipMemcpyAsync(&tot[2], t.fix_base.p + nrows, 8, hipMemcpyDeviceToHost, st));
@@ -544,6 +560,14 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
   g->Ep = Ep;
   g->n = n;
   g->add_self_loops = self_loops;
+  // pinned host memory for the small counts read back from the device: 8 words for the work-item counts,
+  // then three lists of n + 1 boundary values
+  int64_t* hpin = nullptr;
+  {
+    void* hp = nullptr;
+    HT_TRY(ht_host_scratch(ctx, HT_HS_READBACK, (size_t)(8 + 3 * ((size_t)n + 1)) * 8, &hp));
+    hpin = (int64_t*)hp;
+  }
 
   // ---- edge list on the device
   DevArr<int32_t> src_copy, dst_copy;
@@ -616,17 +640,24 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
       g->merged = true;
       g->n_unique = nU;
       HT_TRY(upos.alloc(ctx, (size_t)nU + 1));
-      HT_TRY(g->uindptr.alloc(ctx, (size_t)V + 1));
-      HT_TRY(g->ucol.alloc(ctx, (size_t)nU));
-      HT_TRY(g->ucol_slot.alloc(ctx, (size_t)nU));
-      HT_TRY(g->uw_fwd.alloc(ctx, (size_t)nU));
-      HT_TRY(g->umult.alloc(ctx, (size_t)nU));
-      HT_TRY(g->usdst.alloc(ctx, (size_t)nU));
-      HT_TRY(g->uw_bwd.alloc(ctx, (size_t)nU));
-      HT_TRY(g->umult_bwd.alloc(ctx, (size_t)nU));
+      {
+        DevBlock& b = g->blk_pairs;
+        b.add<int64_t>((size_t)V + 1);
+        for (int k = 0; k < 7; ++k) b.add<int32_t>((size_t)nU);
+        HT_TRY(b.alloc(ctx));
+        b.take(g->uindptr, (size_t)V + 1);
+        b.take(g->ucol, (size_t)nU);
+        b.take(g->ucol_slot, (size_t)nU);
+        b.take(g->uw_fwd, (size_t)nU);
+        b.take(g->umult, (size_t)nU);
+        b.take(g->usdst, (size_t)nU);
+        b.take(g->uw_bwd, (size_t)nU);
+        b.take(g->umult_bwd, (size_t)nU);
+      }
       k_flag_positions<<<nblk(Ep), TB, 0, st>>>(dflag.p, drank.p, Ep, upos.p);
       HT_LAUNCH_CHECK(ctx);
-      HT_HIP(ctx, hipMemcpyAsync(upos.p + nU, &Ep, 8, hipMemcpyHostToDevice, st));
+      k_set_i64<<<1, 1, 0, st>>>(upos.p + nU, Ep);
+      HT_LAUNCH_CHECK(ctx);
       k_merge_fwd<<<nblk(nU), TB, 0, st>>>(upos.p, nU, g->col.p, g->s.p, g->ucol.p, g->uw_fwd.p, g->umult.p);
       HT_LAUNCH_CHECK(ctx);
       k_uindptr<<<nblk(V + 1), TB, 0, st>>>(g->indptr.p, drank.p, V, Ep, nU, g->uindptr.p);
@@ -654,15 +685,22 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
     HT_HIP(ctx, hipMemcpyAsync(&g->bounds[1], db.p, (n - 1) * 8, hipMemcpyDeviceToHost, st));
     HT_HIP(ctx, hipStreamSynchronize(st));
   }
-  std::vector<int64_t> eoff(n + 1);
-  for (int j = 0; j <= n; ++j)  // n is small: one 8-byte copy per boundary
-    HT_HIP(ctx, hipMemcpyAsync(&eoff[j], g->indptr.p + g->bounds[j], 8, hipMemcpyDeviceToHost, st));
-  HT_HIP(ctx, hipStreamSynchronize(st));
-  std::vector<int64_t> ueoff(n + 1, 0);
-  if (g->merged) {
-    for (int j = 0; j <= n; ++j)
-      HT_HIP(ctx, hipMemcpyAsync(&ueoff[j], g->uindptr.p + g->bounds[j], 8, hipMemcpyDeviceToHost, st));
+  // edge offsets of the chunk boundaries, in both edge spaces: one gather, one copy back
+  std::vector<int64_t> eoff(n + 1), ueoff(n + 1, 0);
+  {
+    const size_t nb1 = (size_t)n + 1;
+    DevArr<int64_t> dq;
+    HT_TRY(dq.alloc(ctx, 3 * nb1));
+    int64_t* hb = hpin + 8;
+    std::copy(g->bounds.begin(), g->bounds.end(), hb);
+    HT_HIP(ctx, hipMemcpyAsync(dq.p, hb, nb1 * 8, hipMemcpyHostToDevice, st));
+    k_gather_offsets<<<nblk((int64_t)nb1), TB, 0, st>>>(g->indptr.p, g->merged ? g->uindptr.p : nullptr, dq.p, (int64_t)nb1,
+                                                       dq.p + nb1, dq.p + 2 * nb1);
+    HT_LAUNCH_CHECK(ctx);
+    HT_HIP(ctx, hipMemcpyAsync(hb + nb1, dq.p + nb1, 2 * nb1 * 8, hipMemcpyDeviceToHost, st));
     HT_HIP(ctx, hipStreamSynchronize(st));
+    std::copy(hb + nb1, hb + 2 * nb1, eoff.begin());
+    if (g->merged) std::copy(hb + 2 * nb1, hb + 3 * nb1, ueoff.begin());
   }
   g->chunks.clear();
   g->chunks.resize(n);
@@ -688,17 +726,29 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
   // comes next (ties: smallest id).  All n neighbour bitmaps are kept for the n-1 greedy steps.
   g->order.resize(n);
   for (int j = 0; j < n; ++j) g->order[j] = j;
-  if (opts && opts->reorder_chunks && n > 2) {
-    DevArr<uint64_t> bms;
-    HT_TRY(bms.alloc(ctx, (size_t)n * nw));
-    HT_HIP(ctx, hipMemsetAsync(bms.p, 0, (size_t)n * nw * 8, st));
-    for (int j = 0; j < n; ++j) {
-      const ChunkMeta& c = g->chunks[j];
-      if (c.nnz > 0) {
-        k_mark<<<nblk(c.nnz), TB, 0, st>>>(g->col.p + c.e0, c.nnz, (uint32_t*)(bms.p + (size_t)j * nw));
-        HT_LAUNCH_CHECK(ctx);
+  // The chunks' neighbour bitmaps (bit u of row j: u is in N_j) are needed by the reorganisation, the counting
+  // pass, the buffer simulation and the list pass.  When all n of them fit a modest share of the free memory
+  // they are marked once and kept, row = original chunk id; otherwise each use marks its own again.
+  DevArr<uint64_t> allbm;
+  {
+    const size_t need = (size_t)n * (size_t)nw * 8;
+    size_t free_b = 0, total_b = 0;
+    HT_HIP(ctx, hipMemGetInfo(&free_b, &total_b));
+    const bool want_reorder = opts && opts->reorder_chunks && n > 2;
+    if (want_reorder || (need <= ((size_t)2 << 30) && need <= free_b / 16)) {
+      HT_TRY(allbm.alloc(ctx, (size_t)n * nw));
+      HT_HIP(ctx, hipMemsetAsync(allbm.p, 0, need, st));
+      for (int j = 0; j < n; ++j) {
+        const ChunkMeta& c = g->chunks[j];
+        if (c.nnz > 0) {
+          k_mark<<<nblk(c.nnz), TB, 0, st>>>(g->col.p + c.e0, c.nnz, (uint32_t*)(allbm.p + (size_t)j * nw));
+          HT_LAUNCH_CHECK(ctx);
+        }
       }
     }
+  }
+  if (opts && opts->reorder_chunks && n > 2) {
+    uint64_t* bms = allbm.p;
     DevArr<unsigned long long> ov;
     HT_TRY(ov.alloc(ctx, n));
     std::vector<unsigned long long> hov(n);
@@ -707,7 +757,7 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
     const unsigned gx = (unsigned)std::min<int64_t>(ceil_div64(nw, TB), 64);
     for (int j = 1; j < n; ++j) {
       HT_HIP(ctx, hipMemsetAsync(ov.p, 0, (size_t)n * 8, st));
-      k_overlap<<<dim3(gx, n), TB, 0, st>>>(bms.p, nw, bms.p + (size_t)g->order[j - 1] * nw, ov.p);
+      k_overlap<<<dim3(gx, n), TB, 0, st>>>(bms, nw, bms + (size_t)g->order[j - 1] * nw, ov.p);
       HT_LAUNCH_CHECK(ctx);
       HT_HIP(ctx, hipMemcpyAsync(hov.data(), ov.p, (size_t)n * 8, hipMemcpyDeviceToHost, st));
       HT_HIP(ctx, hipStreamSynchronize(st));
@@ -721,32 +771,46 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
     for (int j = 0; j < n; ++j) sorted_chunks[j] = std::move(g->chunks[g->order[j]]);
     g->chunks = std::move(sorted_chunks);
   }
+  // bitmap of the chunk at schedule position j: the kept one, or marked afresh into `scratch`
+  auto chunk_bm = [&](int j, uint64_t* scratch, uint64_t** out) -> int {
+    if (allbm.p) {
+      *out = allbm.p + (size_t)g->order[j] * nw;
+      return HT_OK;
+    }
+    const ChunkMeta& c = g->chunks[j];
+    HT_HIP(ctx, hipMemsetAsync(scratch, 0, nw * 8, st));
+    if (c.nnz > 0) {
+      k_mark<<<nblk(c.nnz), TB, 0, st>>>(g->col.p + c.e0, c.nnz, (uint32_t*)scratch);
+      HT_LAUNCH_CHECK(ctx);
+    }
+    *out = scratch;
+    return HT_OK;
+  };
 
   // ---- pass 1: |N_j|, |N_j ^ N_{j-1}| and |N_j ^ (N_0 u ... u N_{j-1})| for every chunk, in schedule order
+  DevBlock tmp1;
   DevArr<uint64_t> bmA, bmB, bmT, bmR;
-  HT_TRY(bmA.alloc(ctx, nw));
-  HT_TRY(bmB.alloc(ctx, nw));
-  HT_TRY(bmT.alloc(ctx, nw));
-  HT_TRY(bmR.alloc(ctx, nw));
   DevArr<unsigned long long> totals;
-  HT_TRY(totals.alloc(ctx, (size_t)3 * n));
+  for (int k = 0; k < 4; ++k) tmp1.add<uint64_t>(nw);
+  tmp1.add<unsigned long long>((size_t)3 * n);
+  HT_TRY(tmp1.alloc(ctx));
+  tmp1.take(bmA, nw);
+  tmp1.take(bmB, nw);
+  tmp1.take(bmT, nw);
+  tmp1.take(bmR, nw);
+  tmp1.take(totals, (size_t)3 * n);
   HT_HIP(ctx, hipMemsetAsync(totals.p, 0, (size_t)3 * n * 8, st));
-  uint64_t* cur = bmA.p;
-  uint64_t* prev = bmB.p;   // the previous chunk's set
+  uint64_t* cur = nullptr;
+  uint64_t* prev = bmB.p;   // the previous chunk's set (none before the first chunk)
   HT_HIP(ctx, hipMemsetAsync(prev, 0, nw * 8, st));
   HT_HIP(ctx, hipMemsetAsync(bmR.p, 0, nw * 8, st));
   for (int j = 0; j < n; ++j) {
-    const ChunkMeta& c = g->chunks[j];
-    HT_HIP(ctx, hipMemsetAsync(cur, 0, nw * 8, st));
-    if (c.nnz > 0) {
-      k_mark<<<nblk(c.nnz), TB, 0, st>>>(g->col.p + c.e0, c.nnz, (uint32_t*)cur);
-      HT_LAUNCH_CHECK(ctx);
-    }
+    HT_TRY(chunk_bm(j, (j & 1) ? bmB.p : bmA.p, &cur));
     k_popc3<<<nblk(nw), TB, 0, st>>>(cur, prev, bmR.p, nw, totals.p + 3 * j);
     HT_LAUNCH_CHECK(ctx);
     k_bm_or<<<nblk(nw), TB, 0, st>>>(bmR.p, cur, nw);
     HT_LAUNCH_CHECK(ctx);
-    std::swap(cur, prev);
+    prev = cur;
   }
   std::vector<unsigned long long> htot(3 * n);
   HT_HIP(ctx, hipMemcpyAsync(htot.data(), totals.p, (size_t)3 * n * 8, hipMemcpyDeviceToHost, st));
@@ -806,15 +870,12 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
       HT_HIP(ctx, hipStreamSynchronize(st));
     }
     // N_j lists and next uses, last chunk first
+    uint64_t* bmj = nullptr;   // N_j as a bitmap
     for (int j = n - 1; j >= 0; --j) {
       const ChunkMeta& c = g->chunks[j];
-      HT_HIP(ctx, hipMemsetAsync(bmA.p, 0, nw * 8, st));
-      if (c.nnz > 0) {
-        k_mark<<<nblk(c.nnz), TB, 0, st>>>(g->col.p + c.e0, c.nnz, (uint32_t*)bmA.p);
-        HT_LAUNCH_CHECK(ctx);
-      }
-      HT_TRY(ht_bitmap_prefix(ctx, bmA.p, nw, cnt1.p, pref1.p));
-      HT_TRY(ht_bitmap_expand(ctx, bmA.p, nw, pref1.p, g->nbr.p + c.nbr_off));
+      HT_TRY(chunk_bm(j, bmA.p, &bmj));
+      HT_TRY(ht_bitmap_prefix(ctx, bmj, nw, cnt1.p, pref1.p));
+      HT_TRY(ht_bitmap_expand(ctx, bmj, nw, pref1.p, g->nbr.p + c.nbr_off));
       if (c.nsrc > 0) {
         k_next_use<<<nblk(c.nsrc), TB, 0, st>>>(g->nbr.p + c.nbr_off, c.nsrc, last.p, j, nxt.p + c.nbr_off);
         HT_LAUNCH_CHECK(ctx);
@@ -825,13 +886,9 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
     std::vector<unsigned int> hh((size_t)n + 1);
     for (int j = 0; j < n; ++j) {
       const ChunkMeta& c = g->chunks[j];
-      HT_HIP(ctx, hipMemsetAsync(bmA.p, 0, nw * 8, st));
-      if (c.nnz > 0) {
-        k_mark<<<nblk(c.nnz), TB, 0, st>>>(g->col.p + c.e0, c.nnz, (uint32_t*)bmA.p);
-        HT_LAUNCH_CHECK(ctx);
-      }
+      HT_TRY(chunk_bm(j, bmA.p, &bmj));
       HT_HIP(ctx, hipMemsetAsync(tot2.p, 0, 16, st));
-      k_popc_union<<<nblk(nw), TB, 0, st>>>(bmR.p, bmA.p, nw, tot2.p);
+      k_popc_union<<<nblk(nw), TB, 0, st>>>(bmR.p, bmj, nw, tot2.p);
       HT_LAUNCH_CHECK(ctx);
       unsigned long long t2[2];
       HT_HIP(ctx, hipMemcpyAsync(t2, tot2.p, 16, hipMemcpyDeviceToHost, st));
@@ -840,7 +897,7 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
       const int64_t over = (int64_t)t2[0] - C;
       if (over > 0) {
         uint64_t* E = Ebm.p + (size_t)j * nw;
-        k_bm_op<<<nblk(nw), TB, 0, st>>>(bmR.p, bmA.p, nw, 1, bmT.p);   // candidates: resident, not needed now
+        k_bm_op<<<nblk(nw), TB, 0, st>>>(bmR.p, bmj, nw, 1, bmT.p);   // candidates: resident, not needed now
         HT_LAUNCH_CHECK(ctx);
         HT_HIP(ctx, hipMemsetAsync(hist.p, 0, ((size_t)n + 1) * 4, st));
         k_hist_nu<<<(unsigned)std::min<int64_t>(nblk(nw), 2048), TB, 0, st>>>(bmT.p, nw, nu.p, n + 1, hist.p);
@@ -866,7 +923,7 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
         HT_LAUNCH_CHECK(ctx);
         n_leave[j - 1] = over;     // j > 0 here: nothing is resident before the first chunk
       }
-      k_bm_or<<<nblk(nw), TB, 0, st>>>(bmR.p, bmA.p, nw);
+      k_bm_or<<<nblk(nw), TB, 0, st>>>(bmR.p, bmj, nw);
       HT_LAUNCH_CHECK(ctx);
       if (c.nsrc > 0) {
         k_set_nu<<<nblk(c.nsrc), TB, 0, st>>>(g->nbr.p + c.nbr_off, c.nsrc, nxt.p + c.nbr_off, nu.p);
@@ -922,54 +979,67 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
 
   // ---- arenas
   const size_t vr = (size_t)std::max<int64_t>(g->v_load, 1);
-  HT_TRY(g->slot.alloc(ctx, vo));
-  HT_TRY(g->gslot.alloc(ctx, vo));
-  HT_TRY(g->sptr.alloc(ctx, vo + n));
-  HT_TRY(g->reuse.alloc(ctx, (size_t)std::max<int64_t>(g->v_ori - g->v_load, 1)));
-  HT_TRY(g->load.alloc(ctx, vr));
-  HT_TRY(g->load_slot.alloc(ctx, vr));
-  HT_TRY(g->leave.alloc(ctx, vr));
-  HT_TRY(g->leave_slot.alloc(ctx, vr));
   const size_t ep = (size_t)std::max<int64_t>(Ep, 1);
-  HT_TRY(g->col_local.alloc(ctx, ep));
-  HT_TRY(g->col_slot.alloc(ctx, ep));
-  HT_TRY(g->sdst.alloc(ctx, ep));
+  const size_t n_reused = (size_t)std::max<int64_t>(g->v_ori - g->v_load, 1);
+  {
+    DevBlock& b = g->blk_chunks;
+    b.add<int32_t>(vo); b.add<int32_t>(vo); b.add<int64_t>(vo + n); b.add<int32_t>(n_reused);
+    for (int k = 0; k < 4; ++k) b.add<int32_t>(vr);
+    for (int k = 0; k < 3; ++k) b.add<int32_t>(ep);
+    if (g->merged) b.add<int64_t>(vo + n);
+    HT_TRY(b.alloc(ctx));
+    b.take(g->slot, vo);
+    b.take(g->gslot, vo);
+    b.take(g->sptr, vo + n);
+    b.take(g->reuse, n_reused);
+    b.take(g->load, vr);
+    b.take(g->load_slot, vr);
+    b.take(g->leave, vr);
+    b.take(g->leave_slot, vr);
+    b.take(g->col_local, ep);
+    b.take(g->col_slot, ep);
+    b.take(g->sdst, ep);
+    if (g->merged) b.take(g->usptr, vo + n);
+  }
 
   // ---- pass 2 temporaries
   const int64_t nwC = ceil_div64(C, 64);
   const int64_t nwmax = std::max(nw, nwC);
-  DevArr<int32_t> cnt_tmp, vslot, freelist;
-  DevArr<int64_t> pref;
+  DevBlock tmp2;
+  DevArr<int32_t> cnt_tmp, vslot, freelist, mflag;
+  DevArr<int64_t> pref, mrank, mpos;
   DevArr<uint64_t> freebm;
-  HT_TRY(cnt_tmp.alloc(ctx, nwmax));
-  HT_TRY(pref.alloc(ctx, nwmax + 1));
-  HT_TRY(vslot.alloc(ctx, (size_t)V));
-  HT_TRY(freelist.alloc(ctx, (size_t)C));
-  HT_TRY(freebm.alloc(ctx, nwC));
+  const size_t mnnz = (size_t)std::max<int64_t>(g->max_nnz, 1);
+  tmp2.add<int32_t>(nwmax); tmp2.add<int64_t>(nwmax + 1); tmp2.add<int32_t>((size_t)V); tmp2.add<int32_t>((size_t)C);
+  tmp2.add<uint64_t>(nwC);
+  if (g->merged) { tmp2.add<int32_t>(mnnz); tmp2.add<int64_t>(mnnz + 1); tmp2.add<int64_t>(mnnz + 1); }
+  HT_TRY(tmp2.alloc(ctx));
+  tmp2.take(cnt_tmp, nwmax);
+  tmp2.take(pref, nwmax + 1);
+  tmp2.take(vslot, (size_t)V);
+  tmp2.take(freelist, (size_t)C);
+  tmp2.take(freebm, nwC);
+  if (g->merged) {
+    tmp2.take(mflag, mnnz);
+    tmp2.take(mrank, mnnz + 1);
+    tmp2.take(mpos, mnnz + 1);
+  }
   HT_HIP(ctx, hipMemsetAsync(vslot.p, 0xFF, (size_t)V * 4, st));
-  {
-    std::vector<uint64_t> fb(nwC, ~0ull);
-    if (C % 64) fb[nwC - 1] = (~0ull) >> (64 - (C % 64));
-    HT_HIP(ctx, hipMemcpyAsync(freebm.p, fb.data(), nwC * 8, hipMemcpyHostToDevice, st));
-    HT_HIP(ctx, hipStreamSynchronize(st));
+  // every position free: all ones, the last word cut to C bits (its value travels from pinned memory)
+  HT_HIP(ctx, hipMemsetAsync(freebm.p, 0xFF, nwC * 8, st));
+  if (C % 64) {
+    hpin[4] = (int64_t)((~0ull) >> (64 - (C % 64)));
+    HT_HIP(ctx, hipMemcpyAsync(freebm.p + (nwC - 1), &hpin[4], 8, hipMemcpyHostToDevice, st));
   }
   ItemTmp itmp;
   HT_TRY(itmp.alloc(ctx, std::max<int64_t>(std::max(g->max_ndst, g->max_nsrc), 1)));
-  DevArr<int32_t> mflag;
-  DevArr<int64_t> mrank, mpos;
-  if (g->merged) {
-    HT_TRY(g->usptr.alloc(ctx, vo + n));
-    HT_TRY(mflag.alloc(ctx, (size_t)std::max<int64_t>(g->max_nnz, 1)));
-    HT_TRY(mrank.alloc(ctx, (size_t)std::max<int64_t>(g->max_nnz, 1) + 1));
-    HT_TRY(mpos.alloc(ctx, (size_t)std::max<int64_t>(g->max_nnz, 1) + 1));
-  }
-
+  itmp.totals = hpin;
   const char* ord_env = getenv("HT_ITEM_ORDER");
   const bool order_items = !(ord_env && atoi(ord_env) == 0);
   int seg_fwd = HT_SEG, seg_bwd = HT_SEG / 2;   // measured best at cfg2; the variables are for experiments
   if (const char* v = getenv("HT_SEG_FWD")) seg_fwd = std::max(64, atoi(v));
   if (const char* v = getenv("HT_SEG_BWD")) seg_bwd = std::max(64, atoi(v));
-  cur = bmA.p;
+  // prev: the previous chunk's set (adjacent reuse), or the resident rows, kept up to date in bmB (schedule-aware)
   prev = bmB.p;
   HT_HIP(ctx, hipMemsetAsync(prev, 0, nw * 8, st));
   for (int j = 0; j < n; ++j) {
@@ -979,11 +1049,7 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
     int32_t* gslot_j = g->gslot.p + c.nbr_off;
     int64_t* sptr_j = g->sptr.p + c.sptr_off;
     // unique sorted sources and local indices
-    HT_HIP(ctx, hipMemsetAsync(cur, 0, nw * 8, st));
-    if (c.nnz > 0) {
-      k_mark<<<nblk(c.nnz), TB, 0, st>>>(g->col.p + c.e0, c.nnz, (uint32_t*)cur);
-      HT_LAUNCH_CHECK(ctx);
-    }
+    HT_TRY(chunk_bm(j, (far_first || !(j & 1)) ? bmA.p : bmB.p, &cur));
     HT_TRY(ht_bitmap_prefix(ctx, cur, nw, cnt_tmp.p, pref.p));
     HT_TRY(ht_bitmap_expand(ctx, cur, nw, pref.p, nbr_j));
     if (c.nnz > 0) {
@@ -1067,13 +1133,13 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
         HT_TRY(ht_scan_i32(ctx, mflag.p, mrank.p, c.nnz, false));
         k_flag_positions<<<nblk(c.nnz), TB, 0, st>>>(mflag.p, mrank.p, c.nnz, mpos.p);
         HT_LAUNCH_CHECK(ctx);
-        HT_HIP(ctx, hipMemcpyAsync(mpos.p + c.nu, &c.nnz, 8, hipMemcpyHostToDevice, st));
+        k_set_i64<<<1, 1, 0, st>>>(mpos.p + c.nu, c.nnz);
+        HT_LAUNCH_CHECK(ctx);
         k_merge_bwd<<<nblk(c.nu), TB, 0, st>>>(mpos.p, c.nu, csr_sorted, g->s.p + c.dst0, g->usdst.p + c.ue0,
                                                g->uw_bwd.p + c.ue0, g->umult_bwd.p + c.ue0, other);
         HT_LAUNCH_CHECK(ctx);
         k_boundaries<<<nblk(c.nu), TB, 0, st>>>(other, c.nu, 32, c.nsrc, usptr_j);
         HT_LAUNCH_CHECK(ctx);
-        HT_HIP(ctx, hipStreamSynchronize(st));   // c.nnz was read by the async copy above
       }
       HT_TRY(build_items(ctx, itmp, g->uindptr.p + c.dst0, c.ue0, c.dst1 - c.dst0, g->ucol.p + c.ue0, V, keysA.p, keysB.p,
                          order_items, seg_fwd, &c.fwd));
@@ -1088,7 +1154,7 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
       k_bm_or<<<nblk(nw), TB, 0, st>>>(prev, cur, nw);
       HT_LAUNCH_CHECK(ctx);
     } else {
-      std::swap(cur, prev);
+      prev = cur;
     }
   }
   // what is still buffered leaves at the end of a pass

@@ -53,11 +53,21 @@ __global__ void __launch_bounds__(SCAN_THREADS) k_scan_reduce(const Tin* __restr
 }
 
 // block_offsets may be null (single block).  out may alias in when Tin is int64.
-template <typename Tin>
+// RAW_SUMS: block_offsets holds the blocks' own sums, not their prefix; a block adds up the sums
+// before it by itself (a few thousand values at most), which saves the launch that scans them.
+template <typename Tin, bool RAW_SUMS>
 __global__ void __launch_bounds__(SCAN_THREADS) k_scan_apply(const Tin* in, int64_t n,
                                                             const int64_t* __restrict__ block_offsets,
                                                             int64_t* out, int want_total) {
   const int64_t base = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_ITEMS;
+  int64_t before = 0;
+  if (RAW_SUMS) {
+    int64_t part = 0;
+    for (int64_t i = threadIdx.x; i < (int64_t)blockIdx.x; i += SCAN_THREADS) part += block_offsets[i];
+    block_excl_scan_i64(part, &before);
+  } else if (block_offsets) {
+    before = block_offsets[blockIdx.x];
+  }
   int64_t v[SCAN_ITEMS];
   int64_t s = 0;
 #pragma unroll
@@ -67,8 +77,7 @@ __global__ void __launch_bounds__(SCAN_THREADS) k_scan_apply(const Tin* in, int6
     s += v[i];
   }
   int64_t tot;
-  int64_t off = block_excl_scan_i64(s, &tot);
-  off += block_offsets ? block_offsets[blockIdx.x] : 0;
+  int64_t off = block_excl_scan_i64(s, &tot) + before;
 #pragma unroll
   for (int i = 0; i < SCAN_ITEMS; ++i) {
     int64_t idx = base + i;
@@ -78,21 +87,59 @@ __global__ void __launch_bounds__(SCAN_THREADS) k_scan_apply(const Tin* in, int6
   if (want_total && blockIdx.x == gridDim.x - 1 && threadIdx.x == SCAN_THREADS - 1) out[n] = off;
 }
 
+// One block walks the whole input tile by tile with a running carry: one launch for short inputs
+// (bitmap word counts, per-row item counts of a chunk).  out may alias in when Tin is int64.
+template <typename Tin>
+__global__ void __launch_bounds__(SCAN_THREADS) k_scan_one_block(const Tin* in, int64_t n, int64_t* out,
+                                                                int want_total) {
+  int64_t carry = 0;
+  for (int64_t t0 = 0; t0 < n; t0 += SCAN_TILE) {
+    const int64_t base = t0 + (int64_t)threadIdx.x * SCAN_ITEMS;
+    int64_t v[SCAN_ITEMS];
+    int64_t s = 0;
+#pragma unroll
+    for (int i = 0; i < SCAN_ITEMS; ++i) {
+      int64_t idx = base + i;
+      v[i] = idx < n ? (int64_t)in[idx] : 0;
+      s += v[i];
+    }
+    int64_t tot;
+    int64_t off = block_excl_scan_i64(s, &tot) + carry;
+#pragma unroll
+    for (int i = 0; i < SCAN_ITEMS; ++i) {
+      int64_t idx = base + i;
+      if (idx < n) out[idx] = off;
+      off += v[i];
+    }
+    carry += tot;
+  }
+  if (want_total && threadIdx.x == 0) out[n] = carry;
+}
+
+constexpr int64_t SCAN_ONE_BLOCK_MAX = 16 * SCAN_TILE;   // up to here one block is faster than two launches
+constexpr int64_t SCAN_RAW_SUMS_MAX = 4096;              // blocks whose sums each block adds up by itself
+
 // Block sums of every level live back to back in one scratch slot of the context (the level of n elements
 // needs ceil(n / SCAN_TILE) sums, the next one a tile-th of that, ...): no allocation, hence no
 // implicit device synchronisation, per call.  ws points at this level's sums.
 template <typename Tin>
 int scan_level(ht_ctx* ctx, const Tin* in, int64_t* out, int64_t n, bool want_total, int64_t* ws) {
   const int64_t nb = ceil_div64(n, SCAN_TILE);
-  if (nb == 1) {
-    k_scan_apply<Tin><<<1, SCAN_THREADS, 0, ctx->stream>>>(in, n, nullptr, out, want_total ? 1 : 0);
+  const int wt = want_total ? 1 : 0;
+  if (n <= SCAN_ONE_BLOCK_MAX) {
+    k_scan_one_block<Tin><<<1, SCAN_THREADS, 0, ctx->stream>>>(in, n, out, wt);
     HT_LAUNCH_CHECK(ctx);
     return HT_OK;
   }
   k_scan_reduce<Tin><<<(unsigned)nb, SCAN_THREADS, 0, ctx->stream>>>(in, n, ws);
   HT_LAUNCH_CHECK(ctx);
+  if (nb <= SCAN_RAW_SUMS_MAX) {
+    k_scan_apply<Tin, true><<<(unsigned)nb, SCAN_THREADS, 0, ctx->stream>>>(in, n, ws, out, wt);
+    HT_LAUNCH_CHECK(ctx);
+    return HT_OK;
+  }
   HT_TRY(scan_level<int64_t>(ctx, ws, ws, nb, false, ws + nb));
-  k_scan_apply<Tin><<<(unsigned)nb, SCAN_THREADS, 0, ctx->stream>>>(in, n, ws, out, want_total ? 1 : 0);
+  k_scan_apply<Tin, false><<<(unsigned)nb, SCAN_THREADS, 0, ctx->stream>>>(in, n, ws, out, wt);
   HT_LAUNCH_CHECK(ctx);
   return HT_OK;
 }
