@@ -258,6 +258,7 @@ struct ht_graph {
   DevArr<float> uw_bwd;        // [n_unique] multiplicity * s[destination]
   DevArr<float> umult_bwd;     // [n_unique] multiplicity, by-source order
   DevBlock blk_pairs, blk_chunks;   // the allocations behind the distinct-pair arrays and the per-chunk arenas
+  DevArr<char> items_mem;           // the allocation behind the chunks' work-item lists
   int64_t v_ori = 0, v_ru = 0, v_load = 0;  // v_load: rows actually loaded per pass with this buffer
   int64_t max_nsrc = 0, max_ndst = 0, max_nnz = 0, max_fpart = 0, max_bpart = 0;
   int64_t cache_rows = 0;

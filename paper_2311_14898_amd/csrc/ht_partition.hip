@@ -79,45 +79,90 @@ __global__ void k_bounds(const int64_t* __restrict__ indptr, int64_t V, const in
   b[j] = lo;
 }
 
-// Sets bit col[t] for every entry.  A repeated source follows its first copy (sources ascend inside a
-// destination) and is skipped.  The bit is tested twice before the atomic: with a plain load, which the CU's own
-// cache serves (its view can only lag behind: a bit seen set is set, and most entries stop here), then with a
-// device-scope load, which sees the bits other XCDs have set (a stale plain view alone would send the hub sources'
-// words to an atomic per entry).  cfg2: 346 -> 258 us per launch.
-#ifndef HT_MARK_PLAIN_FIRST
-#define HT_MARK_PLAIN_FIRST 1
-#endif
-__global__ void k_mark(const int32_t* __restrict__ col, int64_t nnz, uint32_t* bm32) {
+// The set of sources of a chunk, N_j, as a bitmap.  Marking bits directly needs an atomic OR per entry, and the
+// XCDs' L2s only agree on a word through device-scope accesses, which travel to the memory side: with a plain
+// test first, then a device-scope test, then the atomic, a 14 M-entry chunk took 258 us (346 without the plain
+// test) and a 9.8 M-entry chunk of a 23 M-vertex graph 467 us.  So entries mark a byte per vertex with plain
+// stores instead (every writer stores the same 1, the caches merge bytes on write-back, nothing has to be
+// coherent before the kernel ends), and a second kernel packs 64 bytes into a word and clears them for the next
+// chunk.  A repeated source follows its first copy (sources ascend inside a destination) and is skipped; a byte
+// seen set (a cached view can only lag behind) is not stored again.
+__global__ void k_mark_bytes(const int32_t* __restrict__ col, int64_t nnz, uint8_t* seen) {
   int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= nnz) return;
   const uint32_t u = (uint32_t)col[t];
   if (t > 0 && (uint32_t)col[t - 1] == u) return;
-  const uint32_t bit = 1u << (u & 31);
-  if (HT_MARK_PLAIN_FIRST && (bm32[u >> 5] & bit)) return;   // a cached view can only lag behind: a set bit is set
-  if (!(__hip_atomic_load(&bm32[u >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bit)) atomicOr(&bm32[u >> 5], bit);
+  if (!seen[u]) seen[u] = 1;
+}
+// bm[w] = bit b set iff seen[64 w + b]; the bytes (0 or 1 each) are cleared.  Eight bytes become eight bits by
+// one multiplication: byte k sits at bit 8k and the factor's term 2^(56 - 7k) moves it to bit 56 + k; no two
+// (byte, term) pairs meet in one bit, so nothing carries.
+__global__ void k_pack_seen(uint8_t* seen, uint64_t* __restrict__ bm, int64_t nw) {
+  int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (w >= nw) return;
+  ulonglong2* p = reinterpret_cast<ulonglong2*>(seen + w * 64);
+  uint64_t bits = 0;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const ulonglong2 v = p[q];
+    bits |= ((v.x * 0x0102040810204080ull) >> 56) << (16 * q);
+    bits |= ((v.y * 0x0102040810204080ull) >> 56) << (16 * q + 8);
+    if (v.x | v.y) p[q] = make_ulonglong2(0ull, 0ull);
+  }
+  bm[w] = bits;
 }
 
-// totals[0] += popc(cur), totals[1] += popc(cur & prev), totals[2] += popc(cur & res)
-__global__ void k_popc3(const uint64_t* __restrict__ cur, const uint64_t* __restrict__ prev,
-                        const uint64_t* __restrict__ res, int64_t nw, unsigned long long* __restrict__ totals) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  unsigned long long a = 0, b = 0, c = 0;
-  if (i < nw) {
-    a = __popcll(cur[i]);
-    b = __popcll(cur[i] & prev[i]);
-    c = __popcll(cur[i] & res[i]);
+// bm = the distinct values of col[0..nnz) as a bitmap of nw words; seen: nw * 64 zero bytes, zero again afterwards
+int mark_sources(ht_ctx* ctx, hipStream_t st, const int32_t* col, int64_t nnz, uint8_t* seen, int64_t nw, uint64_t* bm) {
+  if (nnz > 0) {
+    k_mark_bytes<<<nblk(nnz), TB, 0, st>>>(col, nnz, seen);
+    HT_LAUNCH_CHECK(ctx);
   }
+  k_pack_seen<<<nblk(nw), TB, 0, st>>>(seen, bm, nw);   // writes every word of bm
+  HT_LAUNCH_CHECK(ctx);
+  return HT_OK;
+}
+
+// Sum of up to three per-thread counts over the grid into totals[0..2]: waves by shuffles, the block's four waves
+// through LDS, one atomic add per block and total (with one add per wave the adds of a 23 M-bit bitmap, all to the
+// same three words, took 180 us).  Launch with a bounded grid; the callers stride.
+__device__ __forceinline__ void block_add3(unsigned long long a, unsigned long long b, unsigned long long c,
+                                           unsigned long long* __restrict__ totals, int ntot) {
+  __shared__ unsigned long long part[4][3];
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
     a += __shfl_down(a, o, 64);
     b += __shfl_down(b, o, 64);
     c += __shfl_down(c, o, 64);
   }
+  const int wave = threadIdx.x >> 6;
   if ((threadIdx.x & 63) == 0) {
-    if (a) atomicAdd(&totals[0], a);
-    if (b) atomicAdd(&totals[1], b);
-    if (c) atomicAdd(&totals[2], c);
+    part[wave][0] = a;
+    part[wave][1] = b;
+    part[wave][2] = c;
   }
+  __syncthreads();
+  if ((int)threadIdx.x < ntot) {
+    unsigned long long t = 0;
+    for (int w = 0; w < (int)(blockDim.x >> 6); ++w) t += part[w][threadIdx.x];
+    if (t) atomicAdd(&totals[threadIdx.x], t);
+  }
+}
+constexpr int POPC_GRID = 256;
+inline unsigned popc_grid(int64_t nw) { return (unsigned)std::max<int64_t>(1, std::min<int64_t>(nblk(nw), POPC_GRID)); }
+
+// totals[0] += popc(cur), totals[1] += popc(cur & prev), totals[2] += popc(cur & res)
+__global__ void __launch_bounds__(256) k_popc3(const uint64_t* __restrict__ cur, const uint64_t* __restrict__ prev,
+                                               const uint64_t* __restrict__ res, int64_t nw,
+                                               unsigned long long* __restrict__ totals) {
+  unsigned long long a = 0, b = 0, c = 0;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nw; i += (int64_t)gridDim.x * blockDim.x) {
+    const uint64_t w = cur[i];
+    a += __popcll(w);
+    b += __popcll(w & prev[i]);
+    c += __popcll(w & res[i]);
+  }
+  block_add3(a, b, c, totals, 3);
 }
 
 // ---- row-buffer schedule with a known future (release for room, farthest next use first)
@@ -136,23 +181,14 @@ __global__ void k_set_nu(const int32_t* __restrict__ nbr, int64_t n, const int32
   if (i < n) nu[nbr[i]] = nxt[i];
 }
 // totals[0] += |R u cur|, totals[1] += |R ^ cur|
-__global__ void k_popc_union(const uint64_t* __restrict__ R, const uint64_t* __restrict__ cur, int64_t nw,
-                             unsigned long long* __restrict__ totals) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+__global__ void __launch_bounds__(256) k_popc_union(const uint64_t* __restrict__ R, const uint64_t* __restrict__ cur,
+                                                    int64_t nw, unsigned long long* __restrict__ totals) {
   unsigned long long a = 0, b = 0;
-  if (i < nw) {
-    a = __popcll(R[i] | cur[i]);
-    b = __popcll(R[i] & cur[i]);
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nw; i += (int64_t)gridDim.x * blockDim.x) {
+    a += __popcll(R[i] | cur[i]);
+    b += __popcll(R[i] & cur[i]);
   }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    a += __shfl_down(a, o, 64);
-    b += __shfl_down(b, o, 64);
-  }
-  if ((threadIdx.x & 63) == 0) {
-    if (a) atomicAdd(&totals[0], a);
-    if (b) atomicAdd(&totals[1], b);
-  }
+  block_add3(a, b, 0, totals, 2);
 }
 // hist[nu[u]] += 1 for every u in the candidate set (integer counts: order does not matter).
 // nbins <= HIST_LDS_BINS: counted per block in LDS first, so the few global bins see one add per block.
@@ -467,6 +503,10 @@ struct ItemTmp {
   DevArr<int64_t> it_base, part_base, fix_base;
   DevArr<char> stage;   // items in row order, before they are permuted into dispatch order
   int64_t* totals = nullptr;   // pinned host memory for the three counts of a build_items call (set by the caller)
+  // the graph's block for all work-item lists (set by the caller): a list takes the next bytes of it, or an
+  // allocation of its own when the block is full
+  char* arena = nullptr;
+  size_t arena_cap = 0, arena_off = 0;
   int alloc(ht_ctx* ctx, int64_t maxrows) {
     for (int k = 0; k < 3; ++k) blk.add<int32_t>(maxrows);
     for (int k = 0; k < 3; ++k) blk.add<int64_t>(maxrows + 1);
@@ -505,7 +545,16 @@ int build_items(ht_ctx* ctx, ItemTmp& t, const int64_t* ptr, int64_t ptr0, int64
   // one allocation: e0 (8 B) first, then the 4-byte arrays
   const size_t ni = (size_t)tot[0], nf = (size_t)tot[2];
   const size_t bytes = ni * 8 + ni * 4 * 3 + nf * 4 * 3;
-  HT_TRY(out->blob.alloc(ctx, bytes));
+  if (t.arena && t.arena_off + DevBlock::pad(bytes) <= t.arena_cap) {
+    out->blob.release();
+    out->blob.ctx = ctx;
+    out->blob.owned = false;
+    out->blob.p = t.arena + t.arena_off;
+    out->blob.n = bytes;
+    t.arena_off += DevBlock::pad(bytes);
+  } else {
+    HT_TRY(out->blob.alloc(ctx, bytes));
+  }
   struct Lay { int64_t* e0; int32_t *row, *len, *part, *fx_row, *fx_part0, *fx_nseg; };
   auto carve = [&](char* p) {
     Lay l;
@@ -621,13 +670,14 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
   // ---- duplicate edges: count the distinct (destination, source) pairs; merge when it pays
   const char* mg_env = getenv("HT_MERGE_DUPS");
   const bool merge_allowed = !(mg_env && atoi(mg_env) == 0);
-  DevArr<int32_t> dflag;
-  DevArr<int64_t> drank, upos;
+  // flags and their ranks live in the two key buffers, which are idle between the sort above and the per-chunk
+  // sorts below (releasing 12 bytes per edge of separate arrays took 49 ms on a 1.3 G-edge graph)
+  struct { int32_t* p; } dflag{(int32_t*)keysA.p};
+  struct { int64_t* p; } drank{(int64_t*)keysB.p};
+  DevArr<int64_t> upos;
   int64_t nU = Ep;
   g->merged = false;
   if (merge_allowed && Ep > 0) {
-    HT_TRY(dflag.alloc(ctx, (size_t)Ep));
-    HT_TRY(drank.alloc(ctx, (size_t)Ep + 1));
     k_dup_flags_u32<<<nblk(Ep), TB, 0, st>>>(g->col.p, Ep, dflag.p);
     HT_LAUNCH_CHECK(ctx);
     k_row_start_flags<<<nblk(V), TB, 0, st>>>(g->indptr.p, V, Ep, dflag.p);
@@ -664,8 +714,6 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
       HT_LAUNCH_CHECK(ctx);
       HT_HIP(ctx, hipStreamSynchronize(st));
     }
-    dflag.release();
-    drank.release();
   }
 
   // ---- chunk boundaries
@@ -729,6 +777,12 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
   // The chunks' neighbour bitmaps (bit u of row j: u is in N_j) are needed by the reorganisation, the counting
   // pass, the buffer simulation and the list pass.  When all n of them fit a modest share of the free memory
   // they are marked once and kept, row = original chunk id; otherwise each use marks its own again.
+  DevArr<uint8_t> seen;   // one byte per vertex, zero between two uses
+  HT_TRY(seen.alloc(ctx, (size_t)nw * 64));
+  HT_HIP(ctx, hipMemsetAsync(seen.p, 0, (size_t)nw * 64, st));
+  auto mark_chunk = [&](const ChunkMeta& c, uint64_t* bm) -> int {
+    return mark_sources(ctx, st, g->col.p + c.e0, c.nnz, seen.p, nw, bm);
+  };
   DevArr<uint64_t> allbm;
   {
     const size_t need = (size_t)n * (size_t)nw * 8;
@@ -737,14 +791,7 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
     const bool want_reorder = opts && opts->reorder_chunks && n > 2;
     if (want_reorder || (need <= ((size_t)2 << 30) && need <= free_b / 16)) {
       HT_TRY(allbm.alloc(ctx, (size_t)n * nw));
-      HT_HIP(ctx, hipMemsetAsync(allbm.p, 0, need, st));
-      for (int j = 0; j < n; ++j) {
-        const ChunkMeta& c = g->chunks[j];
-        if (c.nnz > 0) {
-          k_mark<<<nblk(c.nnz), TB, 0, st>>>(g->col.p + c.e0, c.nnz, (uint32_t*)(allbm.p + (size_t)j * nw));
-          HT_LAUNCH_CHECK(ctx);
-        }
-      }
+      for (int j = 0; j < n; ++j) HT_TRY(mark_chunk(g->chunks[j], allbm.p + (size_t)j * nw));
     }
   }
   if (opts && opts->reorder_chunks && n > 2) {
@@ -777,12 +824,7 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
       *out = allbm.p + (size_t)g->order[j] * nw;
       return HT_OK;
     }
-    const ChunkMeta& c = g->chunks[j];
-    HT_HIP(ctx, hipMemsetAsync(scratch, 0, nw * 8, st));
-    if (c.nnz > 0) {
-      k_mark<<<nblk(c.nnz), TB, 0, st>>>(g->col.p + c.e0, c.nnz, (uint32_t*)scratch);
-      HT_LAUNCH_CHECK(ctx);
-    }
+    HT_TRY(mark_chunk(g->chunks[j], scratch));
     *out = scratch;
     return HT_OK;
   };
@@ -806,7 +848,7 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
   HT_HIP(ctx, hipMemsetAsync(bmR.p, 0, nw * 8, st));
   for (int j = 0; j < n; ++j) {
     HT_TRY(chunk_bm(j, (j & 1) ? bmB.p : bmA.p, &cur));
-    k_popc3<<<nblk(nw), TB, 0, st>>>(cur, prev, bmR.p, nw, totals.p + 3 * j);
+    k_popc3<<<popc_grid(nw), TB, 0, st>>>(cur, prev, bmR.p, nw, totals.p + 3 * j);
     HT_LAUNCH_CHECK(ctx);
     k_bm_or<<<nblk(nw), TB, 0, st>>>(bmR.p, cur, nw);
     HT_LAUNCH_CHECK(ctx);
@@ -888,7 +930,7 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
       const ChunkMeta& c = g->chunks[j];
       HT_TRY(chunk_bm(j, bmA.p, &bmj));
       HT_HIP(ctx, hipMemsetAsync(tot2.p, 0, 16, st));
-      k_popc_union<<<nblk(nw), TB, 0, st>>>(bmR.p, bmj, nw, tot2.p);
+      k_popc_union<<<popc_grid(nw), TB, 0, st>>>(bmR.p, bmj, nw, tot2.p);
       HT_LAUNCH_CHECK(ctx);
       unsigned long long t2[2];
       HT_HIP(ctx, hipMemcpyAsync(t2, tot2.p, 16, hipMemcpyDeviceToHost, st));
@@ -946,7 +988,7 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
     }
     if (n > 0) {
       HT_HIP(ctx, hipMemsetAsync(tot2.p, 0, 16, st));
-      k_popc_union<<<nblk(nw), TB, 0, st>>>(bmR.p, bmR.p, nw, tot2.p);
+      k_popc_union<<<popc_grid(nw), TB, 0, st>>>(bmR.p, bmR.p, nw, tot2.p);
       HT_LAUNCH_CHECK(ctx);
       unsigned long long t2[2];
       HT_HIP(ctx, hipMemcpyAsync(t2, tot2.p, 16, hipMemcpyDeviceToHost, st));
@@ -1039,6 +1081,22 @@ int partition_impl(ht_ctx* ctx, int64_t V, int64_t E, const int32_t* src_in, con
   int seg_fwd = HT_SEG, seg_bwd = HT_SEG / 2;   // measured best at cfg2; the variables are for experiments
   if (const char* v = getenv("HT_SEG_FWD")) seg_fwd = std::max(64, atoi(v));
   if (const char* v = getenv("HT_SEG_BWD")) seg_bwd = std::max(64, atoi(v));
+  // One block for the work-item lists of all chunks and both directions.  A row of len entries makes
+  // ceil(len / seg) items and is a cut row when that is more than one, so rows + entries / seg bounds the items
+  // and entries / seg the cut rows; the lists take 20 bytes per item and 12 per cut row.
+  {
+    size_t cap = 0;
+    for (int j = 0; j < n; ++j) {
+      const ChunkMeta& c = g->chunks[j];
+      const size_t ent = (size_t)(g->merged ? c.nu : c.nnz);
+      const size_t rows[2] = {(size_t)(c.dst1 - c.dst0), (size_t)c.nsrc};
+      const size_t seg[2] = {(size_t)seg_fwd, (size_t)seg_bwd};
+      for (int d = 0; d < 2; ++d) cap += DevBlock::pad(20 * (rows[d] + ent / seg[d] + 1) + 12 * (ent / seg[d] + 1));
+    }
+    HT_TRY(g->items_mem.alloc(ctx, cap));
+    itmp.arena = g->items_mem.p;
+    itmp.arena_cap = cap;
+  }
   // prev: the previous chunk's set (adjacent reuse), or the resident rows, kept up to date in bmB (schedule-aware)
   prev = bmB.p;
   HT_HIP(ctx, hipMemsetAsync(prev, 0, nw * 8, st));
@@ -1323,13 +1381,12 @@ int ht_graph_reorganize(ht_ctx* ctx, const ht_graph* g, int32_t m, int32_t* layo
   DevArr<uint64_t> bms, U;
   HT_TRY(bms.alloc(ctx, (size_t)mn * nw));
   HT_TRY(U.alloc(ctx, (size_t)n * nw));
-  HT_HIP(ctx, hipMemsetAsync(bms.p, 0, (size_t)mn * nw * 8, st));
+  DevArr<uint8_t> seen;
+  HT_TRY(seen.alloc(ctx, (size_t)nw * 64));
+  HT_HIP(ctx, hipMemsetAsync(seen.p, 0, (size_t)nw * 64, st));
   for (int c = 0; c < mn; ++c) {
     const ChunkMeta& ch = g->chunks[c];
-    if (ch.nnz > 0) {
-      k_mark<<<nblk(ch.nnz), TB, 0, st>>>(g->col.p + ch.e0, ch.nnz, (uint32_t*)(bms.p + (size_t)c * nw));
-      HT_LAUNCH_CHECK(ctx);
-    }
+    HT_TRY(mark_sources(ctx, st, g->col.p + ch.e0, ch.nnz, seen.p, nw, bms.p + (size_t)c * nw));
   }
   DevArr<unsigned long long> cnt;
   HT_TRY(cnt.alloc(ctx, (size_t)2 * n));

@@ -184,12 +184,18 @@ __global__ void __launch_bounds__(RS_THREADS) k_rs_hist(const uint64_t* __restri
 // Stable scatter.  Key order inside a block is (wave, round, lane) = index
 // order.  A lane's rank among equal digits: earlier waves' counts, earlier
 // rounds of its own wave, lower lanes of its own round (ballot match).
+// The block first puts its keys into digit order in LDS and then writes them out in that order, so that
+// consecutive lanes store consecutive keys of one digit's run (a lane storing its own key straight to its
+// final place touches a 128-byte line of the output from up to 16 different store instructions).
 __global__ void __launch_bounds__(RS_THREADS) k_rs_scatter(const uint64_t* __restrict__ in,
                                                           uint64_t* __restrict__ out, int64_t n, int shift,
                                                           uint32_t mask, const int64_t* __restrict__ offs,
                                                           int64_t nblocks) {
   __shared__ uint32_t cnt[RS_WAVES][RS_BINS];
-  __shared__ int64_t goff[RS_BINS];
+  __shared__ int64_t goff[RS_BINS];     // where the block's run of a digit starts in the output, minus lstart
+  __shared__ uint32_t lstart[RS_BINS];  // where it starts in the block's tile
+  __shared__ uint32_t wtot[RS_WAVES];
+  __shared__ uint64_t tile[RS_TILE];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   for (int i = threadIdx.x; i < RS_WAVES * RS_BINS; i += RS_THREADS) (&cnt[0][0])[i] = 0;
   __syncthreads();
@@ -228,7 +234,22 @@ __global__ void __launch_bounds__(RS_THREADS) k_rs_scatter(const uint64_t* __res
       cnt[w][dgt] = run;
       run += c;
     }
-    goff[dgt] = offs[(int64_t)dgt * nblocks + blockIdx.x];
+    // exclusive prefix of the digit totals over the block's 256 digits
+    uint32_t inc = run;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t y = __shfl_up(inc, o, 64);
+      if (lane >= o) inc += y;
+    }
+    if (lane == 63) wtot[wave] = inc;
+    __syncthreads();
+    uint32_t off = 0;
+#pragma unroll
+    for (int w = 0; w < RS_WAVES; ++w)
+      if (w < wave) off += wtot[w];
+    const uint32_t ls = off + inc - run;
+    lstart[dgt] = ls;
+    goff[dgt] = offs[(int64_t)dgt * nblocks + blockIdx.x] - (int64_t)ls;
   }
   __syncthreads();
 #pragma unroll
@@ -236,8 +257,17 @@ __global__ void __launch_bounds__(RS_THREADS) k_rs_scatter(const uint64_t* __res
     const int64_t idx = base + r * 64 + lane;
     if (idx < n) {
       const uint32_t dg = (uint32_t)(key[r] >> shift) & mask;
-      out[goff[dg] + cnt[wave][dg] + rank[r]] = key[r];
+      tile[lstart[dg] + cnt[wave][dg] + rank[r]] = key[r];
     }
+  }
+  __syncthreads();
+  const int64_t left = n - (int64_t)blockIdx.x * RS_TILE;
+  const int here = left < RS_TILE ? (int)left : RS_TILE;
+#pragma unroll 4
+  for (int i = threadIdx.x; i < here; i += RS_THREADS) {
+    const uint64_t k = tile[i];
+    const uint32_t dg = (uint32_t)(k >> shift) & mask;
+    out[goff[dg] + i] = k;
   }
 }
 
