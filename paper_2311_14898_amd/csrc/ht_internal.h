@@ -56,7 +56,7 @@ struct ht_ctx {
   int link_blocks = 64;   // workgroups of a kernel that moves rows over the host link (HT_LINK_BLOCKS)
   int gather_blocks = 128; // workgroups of the neighbour-row gather from host memory (HT_GATHER_BLOCKS): beside a D2H
                            // copy the gather's read requests queue behind the write data, and more waves keep more in flight
-  int link_memcpy = 0;    // 1: use hipMemcpyAsync for contiguous host<->device row ranges (HT_LINK_MEMCPY)
+  int link_memcpy = 0;    // hipMemcpyAsync for contiguous host<->device row ranges: 1 both ways, 2 to the host only, 3 from the host only (HT_LINK_MEMCPY)
   int slabs_fwd = 0, slabs_bwd = 0;  // caps on feature slabs (HT_SLABS_FWD / HT_SLABS_BWD), 0 = by width
   int agg_unroll = 4;     // HT_AGG_UNROLL: row reads in flight per lane (4 or 8)
   int agg_uniform = 1;    // HT_AGG_UNIFORM=0: no wave-uniform fast path for one-edge-per-step shapes

@@ -242,7 +242,8 @@ int copy_rows(Run& R, hipStream_t st, void* dst, const void* src, size_t bytes, 
   if (bytes == 0) return HT_OK;
   ht_ctx* ctx = R.ctx;
   const int id = R.tm.begin_on(&R.st->t_copy_ms, st);
-  if (ctx->link_memcpy) {
+  const int lm = ctx->link_memcpy;   // 1: both directions, 2: device to host only, 3: host to device only
+  if (lm == 1 || (lm == 2 && kind == hipMemcpyDeviceToHost) || (lm == 3 && kind == hipMemcpyHostToDevice)) {
     HT_HIP(ctx, hipMemcpyAsync(dst, src, bytes, kind, st));
   } else {
     void* d = dst;

@@ -27,6 +27,8 @@ SETTINGS = [
     {"HT_SEG_FWD": "64", "HT_SEG_BWD": "256"},
     {"HT_LINK_MEMCPY": "1"},
     {"HT_LINK_MEMCPY": "1", "HT_NO_LINK_FENCE": "1"},
+    {"HT_LINK_MEMCPY": "2"},
+    {"HT_LINK_MEMCPY": "3"},
     {"HT_NO_LINK_FENCE": "1"},
     {"HT_LINK_BLOCKS": "16", "HT_GATHER_BLOCKS": "512"},
 ]
